@@ -1,0 +1,191 @@
+"""CPU oracle for the LoRDBA adapter forward branch (Def. 1, Eq. (lordba),
+Eq. (adapter-mode-fwd), Eq. (lordba-fwd) of the paper).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke()`` and
+by the ``cpu_baseline`` leg of ``bench.py``.  The product package never imports
+this module, and this module never imports the product package.
+
+The arithmetic lives in ``lordba_oracle.c`` (plain fp64 loops); this file only
+compiles it with gcc, marshals numpy arrays through ctypes, and provides the
+row-wise error metric the parity tests use.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lordba_oracle.c")
+_LIB = os.path.join(_HERE, "liblordba_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no GPU toolchain involved)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared",
+             "-Wall", "-Wextra", _SRC, "-o", tmp, "-lm", "-lpthread"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        lib.lordba_oracle_f16_to_f64.restype = ctypes.c_double
+        lib.lordba_oracle_f16_to_f64.argtypes = [ctypes.c_uint16]
+        lib.lordba_oracle_f16_array_to_f64.restype = None
+        lib.lordba_oracle_f16_array_to_f64.argtypes = [vp, vp, i64]
+        lib.lordba_oracle_pack.restype = ci
+        lib.lordba_oracle_pack.argtypes = [vp, i64, i64, vp]
+        lib.lordba_oracle_unpack.restype = None
+        lib.lordba_oracle_unpack.argtypes = [vp, i64, i64, vp]
+        lib.lordba_oracle_sign_f64.restype = ci
+        lib.lordba_oracle_sign_f64.argtypes = [vp, i64, vp]
+        lib.lordba_oracle_forward.restype = ci
+        lib.lordba_oracle_forward.argtypes = [vp] * 8 + [i64] * 4 + [ci]
+        lib.lordba_oracle_forward_packed.restype = ci
+        lib.lordba_oracle_forward_packed.argtypes = [vp] * 8 + [i64] * 4 + [ci]
+        _lib = lib
+    return _lib
+
+
+def _as(a, dtype, shape=None):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.dtype(dtype):
+        raise TypeError("expected dtype %s, got %s" % (np.dtype(dtype), a.dtype))
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise ValueError("expected shape %s, got %s" % (tuple(shape), tuple(a.shape)))
+    return a
+
+
+def _f16_bits(a, shape=None):
+    """fp16 array -> its uint16 bit patterns (a view, no value conversion)."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    return _as(a, np.uint16, shape)
+
+
+def _ptr(a):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def f16_to_f64(bits) -> np.ndarray:
+    """Decode fp16 bit patterns (uint16 or float16 array) with the oracle's own decoder."""
+    b = _f16_bits(bits)
+    out = np.empty(b.shape, dtype=np.float64)
+    _load().lordba_oracle_f16_array_to_f64(_ptr(b), _ptr(out), b.size)
+    return out
+
+
+def packed_words(rows: int, cols: int) -> int:
+    return (rows * cols + 31) // 32
+
+
+def pack(signs) -> np.ndarray:
+    """int8 +-1 matrix [rows, cols] -> canonical packed uint32 words (bit = 1 means -1)."""
+    s = _as(signs, np.int8)
+    if s.ndim != 2:
+        raise ValueError("signs must be 2-D")
+    rows, cols = s.shape
+    words = np.empty(packed_words(rows, cols), dtype=np.uint32)
+    st = _load().lordba_oracle_pack(_ptr(s), rows, cols, _ptr(words))
+    if st != 0:
+        raise ValueError("sign entries must be +1 or -1 (status %d)" % st)
+    return words
+
+
+def unpack(words, rows: int, cols: int) -> np.ndarray:
+    w = _as(words, np.uint32, (packed_words(rows, cols),))
+    out = np.empty((rows, cols), dtype=np.int8)
+    _load().lordba_oracle_unpack(_ptr(w), rows, cols, _ptr(out))
+    return out
+
+
+def sign(u) -> np.ndarray:
+    """Entry-wise sign with sign(0) = +1 (Sec. 2, Notation)."""
+    u = _as(np.asarray(u, dtype=np.float64), np.float64)
+    out = np.empty(u.shape, dtype=np.int8)
+    st = _load().lordba_oracle_sign_f64(_ptr(u), u.size, _ptr(out))
+    if st != 0:
+        raise ValueError("NaN has no sign (status %d)" % st)
+    return out
+
+
+def forward(x, signsA, signsB, s_in, s_rank, s_out, y_base, nthreads: int = 1) -> np.ndarray:
+    """fp64 Y = Y_base + X diag(s_in) S_A^T diag(s_rank) S_B^T diag(s_out).
+
+    x[T,d_in], y_base[T,d_out], s_*: float16 (or their uint16 bit patterns);
+    signsA[r,d_in], signsB[d_out,r]: int8 +-1.  Returns float64 [T,d_out].
+    """
+    sA = _as(signsA, np.int8)
+    sB = _as(signsB, np.int8)
+    r, d_in = sA.shape
+    d_out = sB.shape[0]
+    if sB.shape != (d_out, r):
+        raise ValueError("signsB must be [d_out, r]")
+    xb = _f16_bits(x)
+    T = xb.shape[0]
+    xb = _f16_bits(xb, (T, d_in))
+    yb = _f16_bits(y_base, (T, d_out))
+    si = _f16_bits(s_in, (d_in,))
+    sr = _f16_bits(s_rank, (r,))
+    so = _f16_bits(s_out, (d_out,))
+    y = np.empty((T, d_out), dtype=np.float64)
+    st = _load().lordba_oracle_forward(_ptr(xb), _ptr(sA), _ptr(sB), _ptr(si), _ptr(sr), _ptr(so),
+                                       _ptr(yb), _ptr(y), T, d_in, d_out, r, int(nthreads))
+    if st != 0:
+        raise ValueError("oracle forward failed with status %d" % st)
+    return y
+
+
+def forward_packed(x, packedA, packedB, s_in, s_rank, s_out, y_base, r: int, nthreads: int = 1) -> np.ndarray:
+    """Same map with canonical packed carriers, unpacked by the oracle's own unpacker."""
+    xb = _f16_bits(x)
+    T, d_in = xb.shape
+    yb = _f16_bits(y_base)
+    d_out = yb.shape[1]
+    pA = _as(packedA, np.uint32, (packed_words(r, d_in),))
+    pB = _as(packedB, np.uint32, (packed_words(d_out, r),))
+    si = _f16_bits(s_in, (d_in,))
+    sr = _f16_bits(s_rank, (r,))
+    so = _f16_bits(s_out, (d_out,))
+    yb = _f16_bits(yb, (T, d_out))
+    y = np.empty((T, d_out), dtype=np.float64)
+    st = _load().lordba_oracle_forward_packed(_ptr(xb), _ptr(pA), _ptr(pB), _ptr(si), _ptr(sr), _ptr(so),
+                                              _ptr(yb), _ptr(y), T, d_in, d_out, r, int(nthreads))
+    if st != 0:
+        raise ValueError("oracle forward failed with status %d" % st)
+    return y
+
+
+def row_rel_l2(y_test, y_ref) -> np.ndarray:
+    """Per token row: ||y_test - y_ref||_2 / ||y_ref||_2 in fp64.
+
+    A row whose reference norm is 0 scores 0 if y_test is exactly 0 there, else inf.
+    """
+    a = np.asarray(y_test, dtype=np.float64)
+    b = np.asarray(y_ref, dtype=np.float64)
+    num = np.sqrt(((a - b) ** 2).sum(axis=1))
+    den = np.sqrt((b ** 2).sum(axis=1))
+    out = np.empty_like(num)
+    nz = den > 0
+    out[nz] = num[nz] / den[nz]
+    out[~nz] = np.where(num[~nz] == 0, 0.0, np.inf)
+    return out
+
+
+def available_cores() -> int:
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:  # pragma: no cover
+        return os.cpu_count() or 1

@@ -1,0 +1,226 @@
+/*
+ * LoRDBA adapter forward branch: CPU oracle.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, fp64 definition that
+ * the GPU library is checked against.  Nothing in the product path may call it;
+ * it shares no code, header, table or helper with the HIP library, and it has
+ * its own fp16 decoder and its own bit packer.
+ *
+ * What it computes (paper notation; BASELINE name in brackets):
+ *   host projection N x M  [d_in x d_out], carrier rank R [r], T token rows,
+ *   B1 in {+-1}^{N x R}  [sign(A) = B1^T, stored as S_A[r, d_in]],
+ *   B2 in {+-1}^{R x M}  [sign(B) = B2^T, stored as S_B[d_out, r]],
+ *   alpha in R^N [s_in], beta in R^R [s_rank], gamma in R^M [s_out].
+ *   Def. 1 / Eq. (lordba), canonical l = 1 envelope:
+ *       DeltaW = diag(alpha) B1 diag(beta) B2 diag(gamma)
+ *   Eq. (adapter-mode-fwd): Y = Y_base + X DeltaW
+ *   evaluated in the order of Eq. (lordba-fwd):
+ *       ((((X D_alpha) B1) D_beta) B2) D_gamma
+ *
+ * Every fp16 input is taken at its exact real value; all arithmetic is IEEE
+ * binary64, plain left-to-right loops, no blocking, no fusion, no reordering.
+ *
+ * Parity pins (tests/test_oracle_*.py, none of them calls back into this file
+ * for the expected value): exact rational brute force of the dense DeltaW on
+ * tiny shapes, numpy fp64 GEMM special case, closed forms (all-ones, rank-1,
+ * unit-vector rows), invariants (zero scales, sign gauge, linearity), the
+ * plus-set/minus-set form of Eq. (sign-accum), the 65536-entry fp16 table
+ * against numpy, and hand-written packed words.  No function here is
+ * "parity unpinned".
+ */
+#include <math.h>
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---------------------------------------------------------------- fp16 ---- */
+
+/* IEEE 754 binary16 bit pattern -> exact binary64 value.
+ * 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits. */
+double lordba_oracle_f16_to_f64(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int f = h & 0x3ff;
+    double v;
+    if (e == 0) {
+        v = ldexp((double)f, -24);              /* zero and subnormals: f * 2^-24 */
+    } else if (e == 31) {
+        v = (f == 0) ? INFINITY : NAN;
+    } else {
+        v = ldexp((double)(1024 + f), e - 25);  /* (1 + f/1024) * 2^(e-15) */
+    }
+    return sign ? -v : v;
+}
+
+void lordba_oracle_f16_array_to_f64(const uint16_t *h, double *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = lordba_oracle_f16_to_f64(h[i]);
+}
+
+/* ------------------------------------------------------------- packing ---- */
+
+/* Canonical packed carrier format (the paper only says "bit-packed", Sec. 3.3;
+ * storage R(N+M) bits, Eq. (lordba-bits)).  Reading taken here: a [rows, cols]
+ * sign matrix is the row-major bit stream n = row*cols + col; bit n lives in bit
+ * (n mod 32) of 32-bit word (n div 32); bit = 1 means -1, bit = 0 means +1 (the
+ * IEEE sign-bit convention); pad bits of the last word are 0.
+ * Returns 0, or 3 if an entry is not +-1. */
+int lordba_oracle_pack(const int8_t *signs, int64_t rows, int64_t cols, uint32_t *words)
+{
+    int64_t nbits = rows * cols;
+    int64_t nwords = (nbits + 31) / 32;
+    for (int64_t w = 0; w < nwords; ++w) words[w] = 0u;
+    for (int64_t row = 0; row < rows; ++row) {
+        for (int64_t col = 0; col < cols; ++col) {
+            int8_t s = signs[row * cols + col];
+            if (s != 1 && s != -1) return 3;
+            int64_t n = row * cols + col;
+            if (s == -1) words[n / 32] |= (uint32_t)1 << (n % 32);
+        }
+    }
+    return 0;
+}
+
+void lordba_oracle_unpack(const uint32_t *words, int64_t rows, int64_t cols, int8_t *signs)
+{
+    for (int64_t row = 0; row < rows; ++row) {
+        for (int64_t col = 0; col < cols; ++col) {
+            int64_t n = row * cols + col;
+            int bit = (int)((words[n / 32] >> (n % 32)) & 1u);
+            signs[n] = bit ? -1 : 1;
+        }
+    }
+}
+
+/* Binarisation of a real latent carrier: sign(u) with sign(0) = +1 (Sec. 2,
+ * Notation).  Compared by value, so -0.0 also maps to +1.  Returns 3 on NaN. */
+int lordba_oracle_sign_f64(const double *u, int64_t n, int8_t *signs)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        if (u[i] != u[i]) return 3;
+        signs[i] = (u[i] >= 0.0) ? 1 : -1;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------- forward ---- */
+
+/* One token row, staged exactly as Eq. (lordba-fwd):
+ *   w = x D_alpha;  t = w B1;  u = t D_beta;  v = u B2;  delta = v D_gamma;
+ *   y = y_base + delta                                  (Eq. adapter-mode-fwd)
+ * sA is S_A[r, d_in] = B1^T, sB is S_B[d_out, r] = B2^T, both int8 +-1. */
+static void forward_row(const uint16_t *x_row, const int8_t *sA, const int8_t *sB,
+                        const double *alpha, const double *beta, const double *gamma,
+                        const uint16_t *ybase_row, double *y_row,
+                        int64_t d_in, int64_t d_out, int64_t r,
+                        double *w, double *u)
+{
+    for (int64_t i = 0; i < d_in; ++i)
+        w[i] = lordba_oracle_f16_to_f64(x_row[i]) * alpha[i];
+    for (int64_t k = 0; k < r; ++k) {
+        double t = 0.0;
+        for (int64_t i = 0; i < d_in; ++i)
+            t += w[i] * (double)sA[k * d_in + i];          /* (w B1)_k, B1[i,k] = S_A[k,i] */
+        u[k] = t * beta[k];
+    }
+    for (int64_t j = 0; j < d_out; ++j) {
+        double v = 0.0;
+        for (int64_t k = 0; k < r; ++k)
+            v += u[k] * (double)sB[j * r + k];             /* (u B2)_j, B2[k,j] = S_B[j,k] */
+        y_row[j] = lordba_oracle_f16_to_f64(ybase_row[j]) + v * gamma[j];
+    }
+}
+
+typedef struct {
+    const uint16_t *x; const int8_t *sA; const int8_t *sB;
+    const double *alpha, *beta, *gamma;
+    const uint16_t *y_base; double *y;
+    int64_t t0, t1, d_in, d_out, r;
+    int status;
+} row_job;
+
+static void *row_worker(void *arg)
+{
+    row_job *jb = (row_job *)arg;
+    double *w = (double *)malloc(sizeof(double) * (size_t)(jb->d_in > 0 ? jb->d_in : 1));
+    double *u = (double *)malloc(sizeof(double) * (size_t)(jb->r > 0 ? jb->r : 1));
+    if (!w || !u) { jb->status = 9; free(w); free(u); return NULL; }
+    for (int64_t t = jb->t0; t < jb->t1; ++t)
+        forward_row(jb->x + t * jb->d_in, jb->sA, jb->sB, jb->alpha, jb->beta, jb->gamma,
+                    jb->y_base + t * jb->d_out, jb->y + t * jb->d_out,
+                    jb->d_in, jb->d_out, jb->r, w, u);
+    free(w); free(u);
+    jb->status = 0;
+    return NULL;
+}
+
+/* x[T,d_in], y_base[T,d_out]: fp16 bit patterns, row-major.  signsA[r,d_in],
+ * signsB[d_out,r]: int8 +-1.  s_in[d_in], s_rank[r], s_out[d_out]: fp16 bit
+ * patterns.  y[T,d_out]: fp64 out.  Token rows are independent, so nthreads > 1
+ * only splits the row range; each row is computed by the same plain loops.
+ * Returns 0, 2 on a bad dimension, 3 on a sign that is not +-1, 9 on malloc failure. */
+int lordba_oracle_forward(const uint16_t *x, const int8_t *signsA, const int8_t *signsB,
+                          const uint16_t *s_in, const uint16_t *s_rank, const uint16_t *s_out,
+                          const uint16_t *y_base, double *y,
+                          int64_t T, int64_t d_in, int64_t d_out, int64_t r, int nthreads)
+{
+    if (T < 0 || d_in < 1 || d_out < 1 || r < 1) return 2;
+    for (int64_t n = 0; n < r * d_in; ++n) if (signsA[n] != 1 && signsA[n] != -1) return 3;
+    for (int64_t n = 0; n < d_out * r; ++n) if (signsB[n] != 1 && signsB[n] != -1) return 3;
+    if (T == 0) return 0;
+
+    double *alpha = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *beta = (double *)malloc(sizeof(double) * (size_t)r);
+    double *gamma = (double *)malloc(sizeof(double) * (size_t)d_out);
+    if (!alpha || !beta || !gamma) { free(alpha); free(beta); free(gamma); return 9; }
+    lordba_oracle_f16_array_to_f64(s_in, alpha, d_in);
+    lordba_oracle_f16_array_to_f64(s_rank, beta, r);
+    lordba_oracle_f16_array_to_f64(s_out, gamma, d_out);
+
+    if (nthreads < 1) nthreads = 1;
+    if ((int64_t)nthreads > T) nthreads = (int)T;
+    row_job *jobs = (row_job *)calloc((size_t)nthreads, sizeof(row_job));
+    pthread_t *tids = (pthread_t *)calloc((size_t)nthreads, sizeof(pthread_t));
+    int status = 0;
+    if (!jobs || !tids) { status = 9; goto done; }
+    for (int i = 0; i < nthreads; ++i) {
+        row_job *jb = &jobs[i];
+        jb->x = x; jb->sA = signsA; jb->sB = signsB;
+        jb->alpha = alpha; jb->beta = beta; jb->gamma = gamma;
+        jb->y_base = y_base; jb->y = y;
+        jb->t0 = T * i / nthreads; jb->t1 = T * (i + 1) / nthreads;
+        jb->d_in = d_in; jb->d_out = d_out; jb->r = r; jb->status = 0;
+    }
+    if (nthreads == 1) {
+        row_worker(&jobs[0]);
+    } else {
+        for (int i = 0; i < nthreads; ++i)
+            if (pthread_create(&tids[i], NULL, row_worker, &jobs[i]) != 0) { jobs[i].status = 9; tids[i] = 0; row_worker(&jobs[i]); }
+        for (int i = 0; i < nthreads; ++i)
+            if (tids[i]) pthread_join(tids[i], NULL);
+    }
+    for (int i = 0; i < nthreads; ++i) if (jobs[i].status) status = jobs[i].status;
+done:
+    free(jobs); free(tids); free(alpha); free(beta); free(gamma);
+    return status;
+}
+
+/* Same map, but the carriers arrive in the canonical packed format and are
+ * unpacked with this file's own unpacker first. */
+int lordba_oracle_forward_packed(const uint16_t *x, const uint32_t *packedA, const uint32_t *packedB,
+                                 const uint16_t *s_in, const uint16_t *s_rank, const uint16_t *s_out,
+                                 const uint16_t *y_base, double *y,
+                                 int64_t T, int64_t d_in, int64_t d_out, int64_t r, int nthreads)
+{
+    if (T < 0 || d_in < 1 || d_out < 1 || r < 1) return 2;
+    int8_t *sA = (int8_t *)malloc((size_t)(r * d_in));
+    int8_t *sB = (int8_t *)malloc((size_t)(d_out * r));
+    if (!sA || !sB) { free(sA); free(sB); return 9; }
+    lordba_oracle_unpack(packedA, r, d_in, sA);
+    lordba_oracle_unpack(packedB, d_out, r, sB);
+    int st = lordba_oracle_forward(x, sA, sB, s_in, s_rank, s_out, y_base, y, T, d_in, d_out, r, nthreads);
+    free(sA); free(sB);
+    return st;
+}

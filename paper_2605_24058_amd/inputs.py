@@ -1,0 +1,99 @@
+"""Seeded synthetic inputs for the LoRDBA adapter forward branch.
+
+This module holds no arithmetic of the method: it only draws the tensors that
+both the GPU library and the CPU oracle are fed with.  The recipe follows the
+benchmark configurations: activations x and y_base ~ N(0,1) rounded to fp16,
+carrier signs i.i.d. +-1 with probability 1/2, and the three channel scale
+vectors lognormal(mu=-3, sigma=0.5) rounded to fp16.  Everything is a pure
+function of (seed, shape); nothing is read from disk.
+
+The shapes stand in for LLaMA-2-7B / LLaMA-2-13B projection shapes; no model
+weights, trained adapters or datasets are involved.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Iterator, List, Tuple
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Shape:
+    name: str
+    T: int
+    d_in: int
+    d_out: int
+    r: int
+
+    def activation_bytes(self) -> int:
+        return 2 * self.T * (self.d_in + 2 * self.d_out)
+
+    def adapter_bytes(self) -> int:
+        bits = self.r * (self.d_in + self.d_out)
+        return (bits + 7) // 8 + 2 * (self.d_in + self.r + self.d_out)
+
+    def algorithmic_bytes(self) -> int:
+        """x + y_base + y_out + packed carriers + three fp16 scale vectors."""
+        return self.activation_bytes() + self.adapter_bytes()
+
+    def sign_macs(self) -> int:
+        return self.T * self.r * (self.d_in + self.d_out)
+
+
+# The five benchmark configurations (index = position in the configuration list).
+C1 = Shape("c1_512x512_r4_T64", 64, 512, 512, 4)
+C2 = Shape("c2_llama7b_attn_4096x4096_r16_T2048", 2048, 4096, 4096, 16)
+C3_UP = Shape("c3_llama7b_mlp_up_4096x11008_r16_T4096", 4096, 4096, 11008, 16)
+C3_DOWN = Shape("c3_llama7b_mlp_down_11008x4096_r16_T4096", 4096, 11008, 4096, 16)
+C4: List[Shape] = [Shape("c4_4096x4096_r%d_T%d" % (r, T), T, 4096, 4096, r)
+                   for r in (8, 16, 32, 64) for T in (1, 8, 64)]
+C5_Q = Shape("c5_llama13b_qkvo_5120x5120_r16_T8192", 8192, 5120, 5120, 16)
+C5_UP = Shape("c5_llama13b_gateup_5120x13824_r16_T8192", 8192, 5120, 13824, 16)
+C5_DOWN = Shape("c5_llama13b_down_13824x5120_r16_T8192", 8192, 13824, 5120, 16)
+C5_LAYERS = 40
+C5_PROJECTIONS: Tuple[Tuple[str, Shape], ...] = (
+    ("q", C5_Q), ("k", C5_Q), ("v", C5_Q), ("o", C5_Q),
+    ("gate", C5_UP), ("up", C5_UP), ("down", C5_DOWN))
+
+
+def _rng(seed: int, *stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(np.random.SeedSequence([int(seed), *map(int, stream)])))
+
+
+def make_adapter(seed: int, d_in: int, d_out: int, r: int) -> Dict[str, np.ndarray]:
+    """Carrier signs (int8 +-1) and fp16 scales of one adapter."""
+    g = _rng(seed, 1)
+    signsA = (g.integers(0, 2, size=(r, d_in), dtype=np.int8) * 2 - 1).astype(np.int8)
+    signsB = (g.integers(0, 2, size=(d_out, r), dtype=np.int8) * 2 - 1).astype(np.int8)
+
+    def lognormal(n):
+        return np.exp(-3.0 + 0.5 * g.standard_normal(n)).astype(np.float16)
+
+    return {"signsA": signsA, "signsB": signsB,
+            "s_in": lognormal(d_in), "s_rank": lognormal(r), "s_out": lognormal(d_out)}
+
+
+def make_activations(seed: int, T: int, d_in: int, d_out: int) -> Dict[str, np.ndarray]:
+    g = _rng(seed, 2)
+    x = g.standard_normal((T, d_in), dtype=np.float32).astype(np.float16)
+    y_base = g.standard_normal((T, d_out), dtype=np.float32).astype(np.float16)
+    return {"x": x, "y_base": y_base}
+
+
+def make_inputs(seed: int, T: int, d_in: int, d_out: int, r: int) -> Dict[str, np.ndarray]:
+    """All tensors of one lordba_forward call, from one seed."""
+    out = make_adapter(seed, d_in, d_out, r)
+    out.update(make_activations(seed, T, d_in, d_out))
+    return out
+
+
+def make_inputs_for(shape: Shape, seed: int) -> Dict[str, np.ndarray]:
+    return make_inputs(seed, shape.T, shape.d_in, shape.d_out, shape.r)
+
+
+def c5_adapter_seeds(seed: int) -> Iterator[Tuple[int, str, Shape, int]]:
+    """(layer, projection name, shape, derived seed) for the 40 x 7 adapter set."""
+    for layer in range(C5_LAYERS):
+        for p, (name, shape) in enumerate(C5_PROJECTIONS):
+            yield layer, name, shape, int(np.random.SeedSequence([int(seed), layer, p]).generate_state(1)[0])
