@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Throughput of the LoRDBA adapter forward branch on one MI355X.
+
+A step is one lordba_forward call (the whole hot path: bit-unpack, s_in scaling + sign(A) reduction,
+s_rank scaling, sign(B) expansion, s_out epilogue added to y_base) on one batch of seeded synthetic
+inputs that are already resident in HBM.  The default workload is the LLaMA-2-7B attention-projection
+shape d_in = d_out = 4096, r = 16, T = 2048.  Steps cycle through enough distinct (x, y_base, y_out)
+buffer sets that the 256 MB Infinity Cache cannot hold them, so the reported GB/s is HBM traffic.
+
+Prints one JSON line: metric/value (tokens/s), ms_per_step, a `roofline` object for the kernel
+(algorithmic bytes per launch / average launch duration from HIP events on the launch stream, against
+the 8 TB/s HBM peak), and a `cpu_baseline` object (the fp64 CPU oracle timed on the host cores).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+CACHE_BYTES = 256 << 20        # Infinity Cache
+
+WORKLOADS = {}
+
+
+def _workloads():
+    from paper_2605_24058_amd import inputs
+    if not WORKLOADS:
+        for sh in [inputs.C1, inputs.C2, inputs.C3_UP, inputs.C3_DOWN, inputs.C5_Q, inputs.C5_UP, inputs.C5_DOWN] + inputs.C4:
+            WORKLOADS[sh.name] = sh
+        WORKLOADS.update({"c1": inputs.C1, "c2": inputs.C2, "c3_up": inputs.C3_UP, "c3_down": inputs.C3_DOWN,
+                          "c5_q": inputs.C5_Q, "c5_up": inputs.C5_UP, "c5_down": inputs.C5_DOWN})
+    return WORKLOADS
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2400)
+    ap.add_argument("--warmup", type=int, default=240)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to cycle through (0 = enough to defeat the cache)")
+    ap.add_argument("--algo", type=int, default=0, help="kernel selector passed to lordba_forward_algo (0 = library default)")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (token rows shard with no exchange; see DESIGN.md). "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2605_24058_amd import binding, inputs
+
+    sh = _workloads()[args.workload]
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    binding.load_library()      # raises if the HIP library is missing: there is no fallback path
+
+    # ---- inputs: one adapter, `sets` activation sets, all resident in HBM before timing ------------------------
+    per_set = sh.activation_bytes()
+    sets = args.sets if args.sets > 0 else max(2, -(-2 * CACHE_BYTES // per_set) + 1)
+    sets = min(sets, max(1, int(200e9 // per_set)))
+    host0 = inputs.make_inputs_for(sh, args.seed)
+    pA, pB = binding.lordba_pack_signs(host0["signsA"], host0["signsB"])
+    dev = {k: torch.from_numpy(host0[k]).cuda() for k in ("s_in", "s_rank", "s_out")}
+    dev["packedA"] = torch.from_numpy(pA.view(np.int32)).cuda()
+    dev["packedB"] = torch.from_numpy(pB.view(np.int32)).cuda()
+    xs, ybs, youts = [], [], []
+    for s in range(sets):
+        act = host0 if s == 0 else inputs.make_activations(args.seed + 1000 * s, sh.T, sh.d_in, sh.d_out)
+        xs.append(torch.from_numpy(act["x"]).cuda())
+        ybs.append(torch.from_numpy(act["y_base"]).cuda())
+        youts.append(torch.empty_like(ybs[-1]))
+    torch.cuda.synchronize()
+
+    def step(i):
+        s = i % sets
+        binding.lordba_forward(xs[s], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                               ybs[s], y_out=youts[s], algo=args.algo, check=False)
+
+    K, W = args.steps, args.warmup
+    use_graph = not args.no_graph
+    for i in range(max(W, sets)):
+        step(i)
+    torch.cuda.synchronize()
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if use_graph:
+        # The K launches of the timed region are captured once and replayed: same kernels, same buffers, no host
+        # launch cost between them.  Only kernel launches are captured (no memset nodes).
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(K):
+                step(i)
+        g.replay()               # untimed replay: graph upload
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(K):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    wall_s = t1 - t0
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_s * 1e3 / K
+    kern_us = ev_ms * 1e3 / K                  # average launch-to-launch duration on the stream, from HIP events
+    alg_bytes = sh.algorithmic_bytes()
+    achieved = alg_bytes / (kern_us * 1e-6) / 1e9
+
+    out = {
+        "metric": "adapter-branch tokens/s and achieved HBM GB/s at d=4096, r=16, T=2048",
+        "value": sh.T * K / wall_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 in/out, f32 accumulate", "data": "synthetic",
+        "config": {"workload": sh.name, "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
+                   "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "algo": args.algo,
+                   "seed": args.seed},
+        "achieved_hbm_gbs": achieved, "hbm_peak_gbs": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_us": kern_us, "algorithmic_bytes": alg_bytes},
+    }
+
+    # ---- CPU baseline: the fp64 oracle as it stands, on the host cores, same workload (bounded sample) ---------
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = oracle.available_cores()
+        budget_macs = 4e9                        # keeps the leg to a few seconds at ~1e9 fp64 MAC/s/core
+        rows = sh.T if sh.sign_macs() <= budget_macs else max(16, int(sh.T * budget_macs / sh.sign_macs()))
+        idx = np.arange(rows) if rows == sh.T else np.linspace(0, sh.T - 1, rows).astype(np.int64)
+        xh, ybh = host0["x"][idx], host0["y_base"][idx]
+        run = lambda nt: oracle.forward(xh, host0["signsA"], host0["signsB"], host0["s_in"], host0["s_rank"],
+                                        host0["s_out"], ybh, nthreads=nt)
+        c0 = time.perf_counter(); want = run(cores); c1 = time.perf_counter()
+        s_rows = max(1, rows // 8)
+        c2 = time.perf_counter()
+        oracle.forward(xh[:s_rows], host0["signsA"], host0["signsB"], host0["s_in"], host0["s_rank"], host0["s_out"],
+                       ybh[:s_rows], nthreads=1)
+        c3 = time.perf_counter()
+        got = youts[0].cpu().numpy()[idx].astype(np.float64)
+        err = float(oracle.row_rel_l2(got, want).max())
+        out["cpu_baseline"] = {"value": rows / (c1 - c0), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                               "sample": "%d of %d token rows of the same workload, all %d host threads" % (rows, sh.T, cores),
+                               "single_thread_tokens_per_s": s_rows / (c3 - c2),
+                               "gbs_equiv": rows / sh.T * alg_bytes / (c1 - c0) / 1e9}
+        out["parity_max_row_rel_l2"] = err
+        out["parity_ok"] = bool(err <= 1e-3)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

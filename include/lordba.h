@@ -1,0 +1,120 @@
+/*
+ * lordba.h - C ABI of the MI355X (gfx950) LoRDBA adapter-forward library.
+ *
+ * The library evaluates the unmerged LoRDBA side branch of one adapted projection and adds it to
+ * the base projection's output (paper: Def. 1 and Eq. (lordba) with one scale envelope, l = 1;
+ * Eq. (adapter-mode-fwd); evaluation order of Eq. (lordba-fwd), Sec. 3.3):
+ *
+ *     y_out[t, j] = y_base[t, j]
+ *                 + s_out[j] * sum_k S_B[j, k] * s_rank[k] * sum_i S_A[k, i] * s_in[i] * x[t, i]
+ *
+ * Notation bridge (paper, row-vector convention X DeltaW  ->  this header):
+ *     N, M, R, T            ->  d_in, d_out, r, T
+ *     B1 in {+-1}^{N x R}   ->  S_A = B1^T, logical shape [r, d_in]
+ *     B2 in {+-1}^{R x M}   ->  S_B = B2^T, logical shape [d_out, r]
+ *     alpha, beta, gamma    ->  s_in[d_in], s_rank[r], s_out[d_out]   (fp16, any finite real value)
+ *     W0^T x (base output)  ->  y_base (an input; the base GEMM is not part of this library)
+ *
+ * Canonical packed carrier format (the paper says only "bit-packed", Sec. 3.3; storage is
+ * R(N+M) bits, Eq. (lordba-bits)).  A [rows, cols] sign matrix is the row-major bit stream
+ * n = row * cols + col; bit n is bit (n mod 32) of the little-endian uint32 word (n div 32);
+ * bit = 1 encodes -1 and bit = 0 encodes +1 (the IEEE sign-bit convention, so applying a
+ * carrier entry is an XOR into a sign bit); pad bits in the last word are 0.  packedA holds
+ * S_A as [r, d_in], packedB holds S_B as [d_out, r].
+ *
+ * All functions return a lordba_status; none throws, aborts or prints.
+ */
+#ifndef LORDBA_H
+#define LORDBA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int lordba_status;
+enum {
+    LORDBA_OK = 0,
+    LORDBA_ERR_NULL = 1,      /* a required pointer is NULL                                   */
+    LORDBA_ERR_DIM = 2,       /* T < 0, d_in < 1, d_out < 1, r < 1, r > LORDBA_MAX_RANK, or a
+                                 size that does not fit 32-bit indexing of one row             */
+    LORDBA_ERR_VALUE = 3,     /* a sign entry that is not +-1 (int8 variant) or is NaN (f32)  */
+    LORDBA_ERR_ALIAS = 4,     /* y_out overlaps an input other than being exactly y_base      */
+    LORDBA_ERR_ALIGN = 5,     /* a pointer is not aligned to its element size                 */
+    LORDBA_ERR_NO_DEVICE = 6, /* no usable HIP device / not a gfx950 device                   */
+    LORDBA_ERR_LAUNCH = 7,    /* the HIP runtime rejected the launch                          */
+    LORDBA_ERR_ALGO = 8       /* lordba_forward_algo: the requested kernel cannot run this shape */
+};
+
+#define LORDBA_MAX_RANK 64
+
+/* Number of uint32 words of a packed [rows, cols] sign matrix: ceil(rows * cols / 32).
+ * Returns 0 if rows or cols is negative. */
+size_t lordba_packed_words(int64_t rows, int64_t cols);
+
+/* HOST function (all pointers are host memory; no device work).  Packs both carriers of one
+ * adapter into the canonical format above (Sec. 3.3: the packed {B1, B2} is stored once per adapter).
+ *   signsA : int8[r * d_in],  values in {-1, +1}, row-major [r, d_in]      (S_A)
+ *   signsB : int8[d_out * r], values in {-1, +1}, row-major [d_out, r]     (S_B)
+ *   packedA: uint32[lordba_packed_words(r, d_in)]   out, caller-owned
+ *   packedB: uint32[lordba_packed_words(d_out, r)]  out, caller-owned
+ * Any other entry value -> LORDBA_ERR_VALUE (outputs are then unspecified).  1 <= r <= 64. */
+lordba_status lordba_pack_signs(const int8_t* signsA, const int8_t* signsB,
+                                uint32_t* packedA, uint32_t* packedB,
+                                int64_t d_in, int64_t d_out, int64_t r);
+
+/* HOST function.  Same, from real-valued latent carriers, binarised with sign(0) = +1
+ * (Sec. 2, Notation; B = sign(H) of Sec. 3.2).  Compared by value: -0.0 -> +1.  NaN -> LORDBA_ERR_VALUE. */
+lordba_status lordba_pack_signs_f32(const float* latentA, const float* latentB,
+                                    uint32_t* packedA, uint32_t* packedB,
+                                    int64_t d_in, int64_t d_out, int64_t r);
+
+/* HOST function.  Inverse of the packing: int8 +-1 matrices from canonical words. */
+lordba_status lordba_unpack_signs(const uint32_t* packedA, const uint32_t* packedB,
+                                  int8_t* signsA, int8_t* signsB,
+                                  int64_t d_in, int64_t d_out, int64_t r);
+
+/* DEVICE function: the adapter forward branch (Eq. (lordba-fwd) added to the base output,
+ * Eq. (adapter-mode-fwd)).  Every pointer is DEVICE memory on the current HIP device, row-major
+ * and contiguous; the caller owns all of it.  The call only enqueues work on `stream`
+ * (a hipStream_t passed as void*; NULL = the default stream): it never synchronises, allocates
+ * or frees, and uses no workspace.
+ *   x      : fp16 [T, d_in]        s_in  : fp16 [d_in]
+ *   packedA: uint32, S_A packed    s_rank: fp16 [r]
+ *   packedB: uint32, S_B packed    s_out : fp16 [d_out]
+ *   y_base : fp16 [T, d_out]       y_out : fp16 [T, d_out]  (out)
+ * y_out may be the very same pointer as y_base (in-place update); any other overlap of y_out with
+ * an input -> LORDBA_ERR_ALIAS.  T == 0 -> LORDBA_OK and no work (x, y_base, y_out may then be NULL).
+ * 1 <= r <= 64.
+ * Arithmetic: fp16 inputs at their exact values, products s_in*x exact, fp32 accumulation, one
+ * round-to-nearest-even to fp16 at the end; every token row is within 1e-3 relative L2 of the
+ * exact result.  Shapes with d_in % 32 == 0, d_out % 8 == 0 and 16-byte aligned pointers take the
+ * matrix-core kernel; anything else takes a slower general kernel with the same results.
+ * Non-finite inputs propagate by IEEE rules; nothing is clamped. */
+lordba_status lordba_forward(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                             const void* s_in, const void* s_rank, const void* s_out,
+                             const void* y_base, void* y_out,
+                             int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream);
+
+/* Same as lordba_forward with the kernel chosen by the caller (benchmarks and tests):
+ *   LORDBA_ALGO_AUTO      what lordba_forward does
+ *   LORDBA_ALGO_GENERAL   vector-ALU kernel, one workgroup per token row, any shape
+ *   LORDBA_ALGO_MFMA_T8   matrix-core kernel, 8 token rows per workgroup
+ *   LORDBA_ALGO_MFMA_T16  matrix-core kernel, 16 token rows per workgroup
+ * A kernel that cannot run the shape -> LORDBA_ERR_ALGO. */
+enum { LORDBA_ALGO_AUTO = 0, LORDBA_ALGO_GENERAL = 1, LORDBA_ALGO_MFMA_T8 = 2, LORDBA_ALGO_MFMA_T16 = 3 };
+lordba_status lordba_forward_algo(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                  const void* s_in, const void* s_rank, const void* s_out,
+                                  const void* y_base, void* y_out,
+                                  int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream,
+                                  int algo);
+
+/* Static, never-NULL description of a status code. */
+const char* lordba_status_string(lordba_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORDBA_H */

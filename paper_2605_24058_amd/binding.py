@@ -1,0 +1,179 @@
+"""ctypes binding of liblordba.so (argument marshalling only; every step of the path runs in the
+library's HIP kernels).  Names and argument order follow include/lordba.h.
+
+torch is used for device memory and streams only: tensors are passed as raw device pointers and
+the current torch stream is passed as the hipStream_t.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import sys
+from typing import Optional, Tuple
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_PKG)
+_CSRC = os.path.join(_PKG, "csrc")
+_LIB_PATH = os.path.join(_PKG, "liblordba.so")
+_SOURCES = ("lordba_forward.hip", "lordba_pack.cpp")
+_lib = None
+
+ALGO_AUTO, ALGO_GENERAL, ALGO_MFMA_T8, ALGO_MFMA_T16 = 0, 1, 2, 3
+
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-Wall", "-Wno-unused-command-line-argument"]
+
+
+class LordbaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: status %d (%s)" % (where, status, lordba_status_string(status)))
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = _LIB_PATH + ".tmp.%d" % os.getpid()
+    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(_ROOT, "include")] + \
+          [os.path.join(_CSRC, s) for s in _SOURCES] + ["-o", tmp]
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in proc.stdout.splitlines() if "not a recognized feature for this target" not in l)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    if verbose and out.strip():
+        print(out, file=sys.stderr)
+    os.replace(tmp, _LIB_PATH)
+    return _LIB_PATH
+
+
+def load_library():
+    """Load liblordba.so; there is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("liblordba.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                           "(or paper_2605_24058_amd.build_library()) first; there is no CPU fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.lordba_packed_words.restype = ctypes.c_size_t
+    lib.lordba_packed_words.argtypes = [i64, i64]
+    for name in ("lordba_pack_signs", "lordba_pack_signs_f32", "lordba_unpack_signs"):
+        f = getattr(lib, name)
+        f.restype = ci
+        f.argtypes = [vp, vp, vp, vp, i64, i64, i64]
+    lib.lordba_forward.restype = ci
+    lib.lordba_forward.argtypes = [vp] * 8 + [i64] * 4 + [vp]
+    lib.lordba_forward_algo.restype = ci
+    lib.lordba_forward_algo.argtypes = [vp] * 8 + [i64] * 4 + [vp, ci]
+    lib.lordba_status_string.restype = ctypes.c_char_p
+    lib.lordba_status_string.argtypes = [ci]
+    _lib = lib
+    return lib
+
+
+def lordba_status_string(status: int) -> str:
+    return load_library().lordba_status_string(int(status)).decode()
+
+
+def lordba_packed_words(rows: int, cols: int) -> int:
+    return int(load_library().lordba_packed_words(rows, cols))
+
+
+def _np_ptr(a: np.ndarray):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def lordba_pack_signs(signsA, signsB) -> Tuple[np.ndarray, np.ndarray]:
+    """Host packing.  signsA [r, d_in], signsB [d_out, r]: int8 +-1, or float32 latents (sign(0) = +1).
+    Returns (packedA, packedB) as uint32 numpy arrays in the canonical format."""
+    lib = load_library()
+    A = np.ascontiguousarray(signsA)
+    B = np.ascontiguousarray(signsB)
+    if A.ndim != 2 or B.ndim != 2 or B.shape[1] != A.shape[0]:
+        raise ValueError("need signsA [r, d_in] and signsB [d_out, r]")
+    if A.dtype != B.dtype or A.dtype not in (np.dtype(np.int8), np.dtype(np.float32)):
+        raise TypeError("carriers must both be int8 (+-1) or both float32 (latents)")
+    r, d_in = A.shape
+    d_out = B.shape[0]
+    pA = np.empty(max(lordba_packed_words(r, d_in), 1), dtype=np.uint32)[:lordba_packed_words(r, d_in)]
+    pB = np.empty(max(lordba_packed_words(d_out, r), 1), dtype=np.uint32)[:lordba_packed_words(d_out, r)]
+    fn = lib.lordba_pack_signs if A.dtype == np.int8 else lib.lordba_pack_signs_f32
+    st = fn(_np_ptr(A), _np_ptr(B), _np_ptr(pA), _np_ptr(pB), d_in, d_out, r)
+    if st != 0:
+        raise LordbaError(st, fn.__name__)
+    return pA, pB
+
+
+def lordba_unpack_signs(packedA, packedB, d_in: int, d_out: int, r: int) -> Tuple[np.ndarray, np.ndarray]:
+    lib = load_library()
+    pA = np.ascontiguousarray(packedA, dtype=np.uint32)
+    pB = np.ascontiguousarray(packedB, dtype=np.uint32)
+    if pA.size != lordba_packed_words(r, d_in) or pB.size != lordba_packed_words(d_out, r):
+        raise ValueError("packed buffers have the wrong length")
+    A = np.empty((r, d_in), dtype=np.int8)
+    B = np.empty((d_out, r), dtype=np.int8)
+    st = lib.lordba_unpack_signs(_np_ptr(pA), _np_ptr(pB), _np_ptr(A), _np_ptr(B), d_in, d_out, r)
+    if st != 0:
+        raise LordbaError(st, "lordba_unpack_signs")
+    return A, B
+
+
+def lordba_forward(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out=None, stream=None,
+                   algo: int = ALGO_AUTO, check: bool = True):
+    """y_out = y_base + adapter branch, on the GPU.  All arguments are torch CUDA tensors:
+    x [T, d_in] f16, packedA / packedB int32 (the uint32 words, reinterpreted), s_in [d_in], s_rank [r],
+    s_out [d_out], y_base [T, d_out] f16.  y_out defaults to a new tensor; pass y_base itself for in-place.
+    Enqueues on `stream` (default: torch's current stream) and returns y_out without synchronising."""
+    import torch
+
+    lib = load_library()
+    if check:
+        for name, t_ in (("x", x), ("s_in", s_in), ("s_rank", s_rank), ("s_out", s_out), ("y_base", y_base)):
+            if t_.dtype != torch.float16 or not t_.is_cuda or not t_.is_contiguous():
+                raise TypeError("%s must be a contiguous float16 CUDA tensor" % name)
+        for name, t_ in (("packedA", packedA), ("packedB", packedB)):
+            if t_.dtype != torch.int32 or not t_.is_cuda or not t_.is_contiguous():
+                raise TypeError("%s must be a contiguous int32 CUDA tensor holding the packed words" % name)
+        if x.dim() != 2 or y_base.dim() != 2 or x.shape[0] != y_base.shape[0]:
+            raise ValueError("x must be [T, d_in] and y_base [T, d_out]")
+    T, d_in = x.shape
+    d_out = y_base.shape[1]
+    r = s_rank.numel()
+    if check:
+        if s_in.numel() != d_in or s_out.numel() != d_out:
+            raise ValueError("scale vector lengths do not match x / y_base")
+        if packedA.numel() != (r * d_in + 31) // 32 or packedB.numel() != (d_out * r + 31) // 32:
+            raise ValueError("packed carrier lengths do not match the shape")
+    if y_out is None:
+        y_out = torch.empty_like(y_base)
+    elif check and (y_out.dtype != torch.float16 or not y_out.is_cuda or not y_out.is_contiguous()
+                    or y_out.shape != y_base.shape):
+        raise TypeError("y_out must be a contiguous float16 CUDA tensor shaped like y_base")
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    st = lib.lordba_forward_algo(x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(),
+                                 s_rank.data_ptr(), s_out.data_ptr(), y_base.data_ptr(), y_out.data_ptr(),
+                                 T, d_in, d_out, r, ctypes.c_void_p(stream), int(algo))
+    if st != 0:
+        raise LordbaError(st, "lordba_forward")
+    return y_out
+
+
+def to_device(inputs: dict, device="cuda:0") -> dict:
+    """Pack the carriers with the library and move one call's tensors to the GPU (plumbing for tests and bench)."""
+    import torch
+
+    pA, pB = lordba_pack_signs(inputs["signsA"], inputs["signsB"])
+    dev = {k: torch.from_numpy(inputs[k]).to(device) for k in ("x", "y_base", "s_in", "s_rank", "s_out")}
+    dev["packedA"] = torch.from_numpy(pA.view(np.int32)).to(device)
+    dev["packedB"] = torch.from_numpy(pB.view(np.int32)).to(device)
+    return dev

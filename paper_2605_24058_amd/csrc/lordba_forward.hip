@@ -1,0 +1,574 @@
+// LoRDBA adapter forward branch for MI355X (gfx950, wave64, MFMA):
+//
+//   y_out[t,j] = y_base[t,j] + s_out[j] * sum_k S_B[j,k] * s_rank[k] * sum_i S_A[k,i] * s_in[i] * x[t,i]
+//
+// (Def. 1 / Eq. (lordba) with l = 1, Eq. (adapter-mode-fwd), evaluation order of Eq. (lordba-fwd).)
+//
+// Token rows are independent, so one workgroup owns a tile of token rows from the first load of x to
+// the last store of y_out and no workgroup ever waits for another: there is no split over d_in across
+// workgroups, no partial-sum workspace and no second launch.
+//
+// Matrix-core kernel (lordba_fwd_mfma_kernel), per workgroup of NW waves and TMV token rows:
+//   stage 0  the 256-entry table "8 carrier bits -> 8 fp16 sign masks" and s_in go to LDS.
+//   stage 1  t[tok, k] = sum_i x[tok,i] * (+-s_in[i]).  The 128-column chunks of d_in are dealt round-robin
+//            to the waves.  A wave reads its chunk of x with row-contiguous 16-byte loads, transposes it
+//            through a wave-private LDS tile into the MFMA operand layout, builds the other operand
+//            (+-s_in as fp16: s_in XOR sign mask, so the product with x is exact in fp32) from one dword of
+//            carrier bits per lane, and issues v_mfma_f32_16x16x32_f16.  Partial tiles of the waves are
+//            summed in LDS in a fixed order (deterministic).
+//   stage 2  u = s_rank * t in fp32; each token row of u is scaled by a power of two so that its largest
+//            entry is in [2^13, 2^14) and split into fp16 hi + fp16 lo (22 significant bits, no overflow or
+//            underflow whatever the magnitude of the scales); hi and lo fill the K = 32 slots of one MFMA
+//            per 16 ranks.
+//   stage 3  v[tok, j] = sum_k u[tok,k] * (+-1), 8 MFMAs per 128 output columns, arranged so that each lane
+//            ends up with 8 consecutive output columns of its token rows: y_base is read and y_out written
+//            with row-contiguous 16-byte accesses, y_out = fp16_rne(y_base + s_out * v * 2^-scale).
+//
+// General kernel (lordba_fwd_general_kernel): plain vector-ALU code, one workgroup per token row, any
+// shape and alignment; also the fallback when the LDS need of the matrix-core kernel exceeds the CU.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <mutex>
+
+#include "lordba.h"
+
+namespace {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+constexpr int kXRow = 136;  // halves per row of the x transpose tile: 128 columns + 8 pad -> conflict-free b128 reads
+constexpr int kURow = 40;   // halves per row of the u tile: 32 slots + 8 pad
+constexpr int kLutBytes = 256 * 16;
+
+__device__ __forceinline__ u4 load16(const void* p) { return *reinterpret_cast<const u4*>(p); }
+__device__ __forceinline__ void store16(void* p, u4 v) { *reinterpret_cast<u4*>(p) = v; }
+__device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
+__device__ __forceinline__ u4 as_u4(h8 v) { return __builtin_bit_cast(u4, v); }
+__device__ __forceinline__ float flip(float v, uint32_t bit) { return __uint_as_float(__float_as_uint(v) ^ (bit << 31)); }
+
+// Row of the MFMA token operand -> token row of the tile.  With 16 token rows it is the identity.  With 8, MFMA
+// rows 4q+0 and 4q+1 carry token rows 2q and 2q+1 and rows 4q+2, 4q+3 repeat them (their results are ignored), so
+// that in the accumulator layout (lane = column, registers = rows 4q..4q+3) every lane owns two live token rows.
+template <int TMV>
+__device__ __forceinline__ int tile_row_of_mfma_row(int m) { return TMV == 16 ? m : ((m >> 2) * 2 + (m & 1)); }
+
+struct FwdArgs {
+    const _Float16* x;
+    const uint32_t* pA;
+    const uint32_t* pB;
+    const _Float16* s_in;
+    const _Float16* s_rank;
+    const _Float16* s_out;
+    const _Float16* y_base;
+    _Float16* y_out;
+    int T, d_in, d_out, r;
+};
+
+// 8 carrier bits starting at bit `bit0` of a packed stream of `nwords` words (bits past the end read as 0).
+__device__ __forceinline__ uint32_t fetch8(const uint32_t* __restrict__ words, int64_t bit0, int64_t nwords) {
+    const int64_t w = bit0 >> 5;
+    const uint32_t lo = w < nwords ? words[w] : 0u;
+    const uint32_t hi = (w + 1) < nwords ? words[w + 1] : 0u;
+    return static_cast<uint32_t>(((static_cast<uint64_t>(hi) << 32) | lo) >> (bit0 & 31)) & 0xffu;
+}
+
+template <int RB, int TMV, int NW, bool XLDS>
+__global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
+    constexpr int NI = TMV / 4;  // 16-byte row accesses per lane per 128-column block of a tile
+    constexpr int D1 = XLDS ? (TMV == 8 ? 8 : 4) : 4;  // x chunks in flight per wave
+    constexpr int D2 = TMV == 8 ? 4 : 2;               // y_base column blocks in flight per wave
+    constexpr int XPW = XLDS ? NI : 4;                 // x registers (16 B) per chunk
+    constexpr int ABW = XLDS ? 1 : 4;                  // carrier dwords per lane per chunk and rank block
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, q = lane >> 4;
+    const int T = a.T, d_in = a.d_in, d_out = a.d_out, r = a.r;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
+
+    u4* lut = reinterpret_cast<u4*>(smem);
+    _Float16* sin_s = reinterpret_cast<_Float16*>(smem + kLutBytes);
+    const int sin_bytes = ((d_in * 2 + 15) >> 4) << 4;
+    unsigned char* p = smem + kLutBytes + sin_bytes;
+    _Float16* xs = reinterpret_cast<_Float16*>(p) + (XLDS ? wave * TMV * kXRow : 0);
+    p += XLDS ? NW * TMV * kXRow * 2 : 0;
+    float* red = reinterpret_cast<float*>(p);
+    p += NW * RB * 1024;
+    _Float16* us = reinterpret_cast<_Float16*>(p) + wave * RB * 16 * kURow;
+
+    // ---------------------------------------------------------------- stage 1: x chunk pipeline ----
+    const int nchunks = (d_in + 127) >> 7;
+    const int my_n = wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0;
+    const int words_per_row = d_in >> 5;  // d_in % 32 == 0 on this path
+
+    u4 xbuf[D1][XPW];
+    uint32_t abits[D1][RB][ABW];
+
+    auto issue_x = [&](int slot, int n) {
+        const int c = wave + NW * n;
+        if (XLDS) {
+#pragma unroll
+            for (int m = 0; m < NI; ++m) {
+                int64_t tok = t0 + m * 4 + q;
+                tok = tok < T ? tok : T - 1;
+                int col = c * 128 + li * 8;
+                col = col < d_in ? col : d_in - 8;
+                xbuf[slot][m] = load16(a.x + tok * d_in + col);
+            }
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                int rk = rb * 16 + li;
+                rk = rk < r ? rk : r - 1;
+                const int w = c * 4 + q;
+                abits[slot][rb][0] = w < words_per_row ? a.pA[static_cast<int64_t>(rk) * words_per_row + w] : 0u;
+            }
+        } else {
+            int64_t tok = t0 + tile_row_of_mfma_row<TMV>(li);
+            tok = tok < T ? tok : T - 1;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                int col = c * 128 + s * 32 + q * 8;
+                col = col < d_in ? col : d_in - 8;
+                xbuf[slot][s] = load16(a.x + tok * d_in + col);
+            }
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                int rk = rb * 16 + li;
+                rk = rk < r ? rk : r - 1;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int w = c * 4 + s;
+                    abits[slot][rb][s] = w < words_per_row ? a.pA[static_cast<int64_t>(rk) * words_per_row + w] : 0u;
+                }
+            }
+        }
+    };
+
+#pragma unroll
+    for (int slot = 0; slot < D1; ++slot)
+        if (slot < my_n) issue_x(slot, slot);
+
+    // ---------------------------------------------------------------- stage 0: LDS tables ----------
+    for (int e = tid; e < 256; e += NW * 64) {
+        u4 m;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            m[i] = (((e >> (2 * i)) & 1u) << 15) | (((e >> (2 * i + 1)) & 1u) << 31);
+        lut[e] = m;
+    }
+    for (int c8 = tid * 8; c8 < d_in; c8 += NW * 64 * 8) store16(sin_s + c8, load16(a.s_in + c8));
+    __syncthreads();
+
+    bool rank_ok[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) rank_ok[rb] = rb * 16 + li < r;
+
+    f4 acc[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
+
+    auto consume_x = [&](int slot, int n) {
+        const int c = wave + NW * n;
+        if (XLDS) {
+#pragma unroll
+            for (int m = 0; m < NI; ++m) store16(xs + (m * 4 + q) * kXRow + li * 8, xbuf[slot][m]);
+            __builtin_amdgcn_wave_barrier();
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            h8 xf;
+            int col0;
+            if (XLDS) {
+                col0 = c * 128 + q * 32 + s * 8;
+                xf = as_h8(load16(xs + tile_row_of_mfma_row<TMV>(li) * kXRow + q * 32 + s * 8));
+            } else {
+                col0 = c * 128 + s * 32 + q * 8;
+                xf = as_h8(xbuf[slot][s]);
+            }
+            const bool col_ok = col0 < d_in;
+            const u4 sv = load16(sin_s + (col_ok ? col0 : 0));
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                const uint32_t byte = XLDS ? (abits[slot][rb][0] >> (s * 8)) & 0xffu
+                                           : (abits[slot][rb][s] >> (q * 8)) & 0xffu;
+                u4 wv = sv ^ lut[byte];
+                if (!(col_ok && rank_ok[rb])) wv = u4{0u, 0u, 0u, 0u};
+                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf, as_h8(wv), acc[rb], 0, 0, 0);
+            }
+        }
+        if (XLDS) __builtin_amdgcn_wave_barrier();
+    };
+
+    for (int n0 = 0; n0 < my_n; n0 += D1) {
+#pragma unroll
+        for (int slot = 0; slot < D1; ++slot) {
+            const int n = n0 + slot;
+            if (n < my_n) {
+                consume_x(slot, n);
+                if (n + D1 < my_n) issue_x(slot, n + D1);
+            }
+        }
+    }
+
+    // ---------------------------------------------------------------- stage 3 prefetch -------------
+    const int nblk = (d_out + 127) >> 7;
+    const int my_b = wave < nblk ? (nblk - wave + NW - 1) / NW : 0;
+    u4 ybuf[D2][NI];
+    u4 sobuf[D2];
+
+    auto issue_y = [&](int slot, int n) {
+        const int b = wave + NW * n;
+        int j0 = b * 128 + li * 8;
+        j0 = j0 < d_out ? j0 : d_out - 8;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            int64_t tok = t0 + (TMV == 16 ? q * 4 + i : q * 2 + i);
+            tok = tok < T ? tok : T - 1;
+            ybuf[slot][i] = load16(a.y_base + tok * d_out + j0);
+        }
+        sobuf[slot] = load16(a.s_out + j0);
+    };
+#pragma unroll
+    for (int slot = 0; slot < D2; ++slot)
+        if (slot < my_b) issue_y(slot, slot);
+
+    // ---------------------------------------------------------------- stage 2: reduce, scale, split -
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+        *reinterpret_cast<f4*>(red + ((wave * RB + rb) * 64 + lane) * 4) = acc[rb];
+    __syncthreads();
+
+    float inv[4];
+    {
+        f4 u[RB];
+        float amax[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            f4 tsum = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < NW; ++w) tsum += *reinterpret_cast<const f4*>(red + ((w * RB + rb) * 64 + lane) * 4);
+            const int rk = rb * 16 + li;
+            const float sr = rk < r ? static_cast<float>(a.s_rank[rk]) : 0.f;
+            u[rb] = tsum * sr;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) amax[i] = fmaxf(amax[i], fabsf(u[rb][i]));
+        }
+        float mul[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int sh = 1; sh < 16; sh <<= 1) amax[i] = fmaxf(amax[i], __shfl_xor(amax[i], sh, 64));
+            int e = static_cast<int>((__float_as_uint(amax[i]) >> 23) & 0xffu);
+            e = e < 14 ? 14 : (e > 254 ? 254 : e);
+            mul[i] = __uint_as_float(static_cast<uint32_t>(267 - e) << 23);  // 2^(13 - (e - 127))
+            inv[i] = __uint_as_float(static_cast<uint32_t>(e - 13) << 23);   // its reciprocal
+        }
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float up = u[rb][i] * mul[i];
+                const _Float16 hi = static_cast<_Float16>(up);
+                const _Float16 lo = static_cast<_Float16>(up - static_cast<float>(hi));
+                us[(rb * 16 + q * 4 + i) * kURow + li] = hi;
+                us[(rb * 16 + q * 4 + i) * kURow + 16 + li] = lo;
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    h8 ufrag[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) ufrag[rb] = as_h8(load16(us + (rb * 16 + li) * kURow + q * 8));
+
+    // ---------------------------------------------------------------- stage 3: expand + epilogue ----
+    const int64_t nwordsB = (static_cast<int64_t>(d_out) * r + 31) >> 5;
+    const uint32_t one2 = 0x3C003C00u;  // two fp16 1.0
+    const int rbytes = r >> 3;
+
+    auto consume_y = [&](int slot, int n) {
+        const int b = wave + NW * n;
+        const int j0 = b * 128 + li * 8;
+        const bool j_ok = j0 < d_out;
+        const int jc = j_ok ? j0 : d_out - 8;
+
+        u4 bw = u4{0u, 0u, 0u, 0u};
+        if (r == 16) bw = load16(a.pB + (jc >> 1));  // 8 rows of 16 bits = 4 words
+        f4 v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            v[e] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                uint32_t byte;
+                if (r == 16) {
+                    byte = (bw[e >> 1] >> ((e & 1) * 16 + (q & 1) * 8)) & 0xffu;
+                } else if ((r & 7) == 0) {
+                    const int bi = rb * 2 + (q & 1);
+                    byte = bi < rbytes ? reinterpret_cast<const uint8_t*>(a.pB)[static_cast<int64_t>(jc + e) * rbytes + bi] : 0u;
+                } else {
+                    byte = fetch8(a.pB, static_cast<int64_t>(jc + e) * r + rb * 16 + (q & 1) * 8, nwordsB);
+                }
+                u4 sg = lut[byte];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sg[i] ^= one2;
+                v[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb], as_h8(sg), v[e], 0, 0, 0);
+            }
+        }
+        const h8 so = as_h8(sobuf[slot]);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int64_t tok = t0 + (TMV == 16 ? q * 4 + i : q * 2 + i);
+            const h8 yb = as_h8(ybuf[slot][i]);
+            h8 out;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float dv = v[e][i] * inv[i];
+                out[e] = static_cast<_Float16>(static_cast<float>(yb[e]) + static_cast<float>(so[e]) * dv);
+            }
+            if (j_ok && tok < T) store16(a.y_out + tok * d_out + j0, as_u4(out));
+        }
+    };
+
+    for (int n0 = 0; n0 < my_b; n0 += D2) {
+#pragma unroll
+        for (int slot = 0; slot < D2; ++slot) {
+            const int n = n0 + slot;
+            if (n < my_b) {
+                consume_y(slot, n);
+                if (n + D2 < my_b) issue_y(slot, n + D2);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------ general kernel ----
+template <int RP>
+__global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a, int vec_x) {
+    __shared__ float red[4][RP];
+    __shared__ float u_s[RP];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int d_in = a.d_in, d_out = a.d_out, r = a.r;
+    const int64_t t = blockIdx.x;
+    const _Float16* xr = a.x + t * d_in;
+
+    float acc[RP];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) acc[k] = 0.f;
+
+    if (vec_x) {  // d_in % 8 == 0, x and s_in 16-byte aligned: 8 columns per lane per step, one carrier byte per rank
+        const uint8_t* bytesA = reinterpret_cast<const uint8_t*>(a.pA);
+        for (int i0 = tid * 8; i0 < d_in; i0 += 256 * 8) {
+            const h8 xv = as_h8(load16(xr + i0));
+            const h8 sv = as_h8(load16(a.s_in + i0));
+            float w[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) w[e] = static_cast<float>(xv[e]) * static_cast<float>(sv[e]);
+#pragma unroll
+            for (int k = 0; k < RP; ++k) {
+                if (k < r) {
+                    const uint32_t byte = bytesA[(static_cast<int64_t>(k) * d_in + i0) >> 3];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[k] += flip(w[e], (byte >> e) & 1u);
+                }
+            }
+        }
+    } else {
+        for (int i = tid; i < d_in; i += 256) {
+            const float w = static_cast<float>(xr[i]) * static_cast<float>(a.s_in[i]);
+#pragma unroll
+            for (int k = 0; k < RP; ++k) {
+                if (k < r) {
+                    const int64_t n = static_cast<int64_t>(k) * d_in + i;
+                    acc[k] += flip(w, (a.pA[n >> 5] >> (n & 31)) & 1u);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < RP; ++k) {
+        float v = acc[k];
+#pragma unroll
+        for (int sh = 32; sh >= 1; sh >>= 1) v += __shfl_xor(v, sh, 64);
+        if (lane == 0) red[wave][k] = v;
+    }
+    __syncthreads();
+    if (tid < RP) {
+        const float tk = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+        u_s[tid] = tid < r ? static_cast<float>(a.s_rank[tid]) * tk : 0.f;
+    }
+    __syncthreads();
+    const _Float16* ybr = a.y_base + t * d_out;
+    _Float16* yor = a.y_out + t * d_out;
+    for (int j = tid; j < d_out; j += 256) {
+        float v = 0.f;
+        const int64_t n0 = static_cast<int64_t>(j) * r;
+        for (int k = 0; k < r; ++k) {
+            const int64_t n = n0 + k;
+            v += flip(u_s[k], (a.pB[n >> 5] >> (n & 31)) & 1u);
+        }
+        yor[j] = static_cast<_Float16>(static_cast<float>(ybr[j]) + static_cast<float>(a.s_out[j]) * v);
+    }
+}
+
+// ------------------------------------------------------------------------------------------ host side ----
+
+constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
+
+template <int RB, int TMV, int NW, bool XLDS>
+size_t mfma_lds_bytes(int d_in) {
+    size_t b = kLutBytes + ((static_cast<size_t>(d_in) * 2 + 15) / 16) * 16;
+    if (XLDS) b += static_cast<size_t>(NW) * TMV * kXRow * 2;
+    b += static_cast<size_t>(NW) * RB * 1024;
+    b += static_cast<size_t>(NW) * RB * 16 * kURow * 2;
+    return b;
+}
+
+template <int RB, int TMV, int NW, bool XLDS>
+lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
+    const size_t lds = mfma_lds_bytes<RB, TMV, NW, XLDS>(a.d_in);
+    if (lds > kMaxLds) return LORDBA_ERR_ALGO;
+    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, XLDS>;
+    if (lds > 64 * 1024) {
+        // Opt in to more than 64 KiB of dynamic LDS once per device and kernel; raising the limit is idempotent.
+        static std::mutex mu;
+        static size_t granted[64] = {0};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LORDBA_ERR_NO_DEVICE;
+        std::lock_guard<std::mutex> g(mu);
+        if (granted[dev] < lds) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    static_cast<int>(kMaxLds)) != hipSuccess) {
+                (void)hipGetLastError();
+                return LORDBA_ERR_LAUNCH;
+            }
+            granted[dev] = kMaxLds;
+        }
+    }
+    const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(a.T) + TMV - 1) / TMV);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, stream, a);
+    return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
+}
+
+template <int TMV, bool XLDS>
+lordba_status launch_mfma_rb(const FwdArgs& a, hipStream_t stream) {
+    switch ((a.r + 15) / 16) {
+        case 1: return launch_mfma<1, TMV, 4, XLDS>(a, stream);
+        case 2: return launch_mfma<2, TMV, 4, XLDS>(a, stream);
+        case 3: return launch_mfma<3, TMV, 4, XLDS>(a, stream);
+        case 4: return launch_mfma<4, TMV, 4, XLDS>(a, stream);
+        default: return LORDBA_ERR_DIM;
+    }
+}
+
+lordba_status launch_general(const FwdArgs& a, hipStream_t stream, bool vec_x) {
+    const dim3 grid(static_cast<unsigned>(a.T)), block(256);
+    if (a.r <= 8) hipLaunchKernelGGL(lordba_fwd_general_kernel<8>, grid, block, 0, stream, a, vec_x ? 1 : 0);
+    else if (a.r <= 16) hipLaunchKernelGGL(lordba_fwd_general_kernel<16>, grid, block, 0, stream, a, vec_x ? 1 : 0);
+    else if (a.r <= 32) hipLaunchKernelGGL(lordba_fwd_general_kernel<32>, grid, block, 0, stream, a, vec_x ? 1 : 0);
+    else hipLaunchKernelGGL(lordba_fwd_general_kernel<64>, grid, block, 0, stream, a, vec_x ? 1 : 0);
+    return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
+}
+
+bool overlaps(const void* p, size_t pn, const void* q, size_t qn) {
+    const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(q);
+    return pn != 0 && qn != 0 && a < b + qn && b < a + pn;
+}
+bool aligned(const void* p, size_t n) { return (reinterpret_cast<uintptr_t>(p) & (n - 1)) == 0; }
+
+// The kernels are built for gfx950 only; say so instead of failing inside the launch on another device.
+lordba_status check_device() {
+    static std::mutex mu;
+    static int state[64] = {0};  // 0 unknown, 1 ok, 2 not usable
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LORDBA_ERR_NO_DEVICE; }
+    if (dev < 0 || dev >= 64) return LORDBA_ERR_NO_DEVICE;
+    std::lock_guard<std::mutex> g(mu);
+    if (state[dev] == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); state[dev] = 2; }
+        else {
+            const char* n = prop.gcnArchName;
+            bool ok = false;
+            for (; n[0] && n[1] && n[2] && n[3] && n[4] && n[5]; ++n)
+                if (n[0] == 'g' && n[1] == 'f' && n[2] == 'x' && n[3] == '9' && n[4] == '5' && n[5] == '0') { ok = true; break; }
+            state[dev] = ok ? 1 : 2;
+        }
+    }
+    return state[dev] == 1 ? LORDBA_OK : LORDBA_ERR_NO_DEVICE;
+}
+
+}  // namespace
+
+extern "C" lordba_status lordba_forward_algo(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                             const void* s_in, const void* s_rank, const void* s_out,
+                                             const void* y_base, void* y_out,
+                                             int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream,
+                                             int algo) {
+    if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || r > LORDBA_MAX_RANK) return LORDBA_ERR_DIM;
+    if (T > INT32_MAX - 64 || d_in > (1 << 24) || d_out > (1 << 24)) return LORDBA_ERR_DIM;
+    if (algo < 0 || algo > 5) return LORDBA_ERR_ALGO;
+    // With no token rows the activation pointers may legitimately be NULL (empty allocations).
+    if (T == 0) return (packedA && packedB && s_in && s_rank && s_out) ? LORDBA_OK : LORDBA_ERR_NULL;
+    if (!x || !packedA || !packedB || !s_in || !s_rank || !s_out || !y_base || !y_out) return LORDBA_ERR_NULL;
+    if (!aligned(x, 2) || !aligned(s_in, 2) || !aligned(s_rank, 2) || !aligned(s_out, 2) || !aligned(y_base, 2) ||
+        !aligned(y_out, 2) || !aligned(packedA, 4) || !aligned(packedB, 4))
+        return LORDBA_ERR_ALIGN;
+    const size_t ny = static_cast<size_t>(T) * d_out * 2, nx = static_cast<size_t>(T) * d_in * 2;
+    const size_t nA = lordba_packed_words(r, d_in) * 4, nB = lordba_packed_words(d_out, r) * 4;
+    if (overlaps(y_out, ny, x, nx) || overlaps(y_out, ny, packedA, nA) || overlaps(y_out, ny, packedB, nB) ||
+        overlaps(y_out, ny, s_in, d_in * 2) || overlaps(y_out, ny, s_rank, r * 2) || overlaps(y_out, ny, s_out, d_out * 2))
+        return LORDBA_ERR_ALIAS;
+    if (y_out != y_base && overlaps(y_out, ny, y_base, ny)) return LORDBA_ERR_ALIAS;
+    const lordba_status dev = check_device();
+    if (dev != LORDBA_OK) return dev;
+
+    FwdArgs a;
+    a.x = static_cast<const _Float16*>(x);
+    a.pA = packedA;
+    a.pB = packedB;
+    a.s_in = static_cast<const _Float16*>(s_in);
+    a.s_rank = static_cast<const _Float16*>(s_rank);
+    a.s_out = static_cast<const _Float16*>(s_out);
+    a.y_base = static_cast<const _Float16*>(y_base);
+    a.y_out = static_cast<_Float16*>(y_out);
+    a.T = static_cast<int>(T);
+    a.d_in = static_cast<int>(d_in);
+    a.d_out = static_cast<int>(d_out);
+    a.r = static_cast<int>(r);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    const bool al16 = aligned(x, 16) && aligned(s_in, 16) && aligned(s_out, 16) && aligned(y_base, 16) &&
+                      aligned(y_out, 16) && aligned(packedB, 16);
+    const bool mfma_ok = al16 && (d_in % 32 == 0) && (d_out % 8 == 0);
+    const bool vec_x = aligned(x, 16) && aligned(s_in, 16) && (d_in % 8 == 0);
+
+    if (algo == LORDBA_ALGO_GENERAL) return launch_general(a, st, vec_x);
+    if (algo == LORDBA_ALGO_AUTO) {
+        if (mfma_ok) {
+            // 16-row tiles halve the per-row cost of building sign operands; take them once they still give every
+            // CU two workgroups, otherwise 8-row tiles keep all 256 CUs busy.
+            const lordba_status s = (T >= 16 * 512) ? launch_mfma_rb<16, true>(a, st) : launch_mfma_rb<8, true>(a, st);
+            if (s != LORDBA_ERR_ALGO) return s;
+        }
+        return launch_general(a, st, vec_x);
+    }
+    if (!mfma_ok) return LORDBA_ERR_ALGO;
+    switch (algo) {
+        case LORDBA_ALGO_MFMA_T8: return launch_mfma_rb<8, true>(a, st);
+        case LORDBA_ALGO_MFMA_T16: return launch_mfma_rb<16, true>(a, st);
+        case 4: return (d_in % 128 == 0) ? launch_mfma_rb<8, false>(a, st) : LORDBA_ERR_ALGO;   // direct operand loads, 8 rows
+        case 5: return (d_in % 128 == 0) ? launch_mfma_rb<16, false>(a, st) : LORDBA_ERR_ALGO;  // direct operand loads, 16 rows
+        default: return LORDBA_ERR_ALGO;
+    }
+}
+
+extern "C" lordba_status lordba_forward(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                        const void* s_in, const void* s_rank, const void* s_out,
+                                        const void* y_base, void* y_out,
+                                        int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream) {
+    return lordba_forward_algo(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream,
+                               LORDBA_ALGO_AUTO);
+}

@@ -1,0 +1,284 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Bar: per token row, ||y_gpu - y||_2 / ||y||_2 <= 1e-3 (fp16 in/out, fp32
+accumulation), both as configured and with y_base = 0 (the branch alone, so that an error in the
+branch cannot hide behind a much larger y_base).  Carrier packing is compared bit for bit in the
+CPU suite."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_24058_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-3
+NTHREADS = min(16, oracle.available_cores())
+A_AUTO, A_GEN, A_T8, A_T16, A_D8, A_D16 = 0, 1, 2, 3, 4, 5
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load_library()
+    return torch
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def gpu_forward(torch, d, algo=A_AUTO, inplace=False, guard=True):
+    """Runs the library on cuda:0.  y_out sits inside a larger NaN-filled buffer so that unwritten
+    elements and writes outside [T, d_out] are both visible."""
+    dev = binding.to_device(d)
+    T, d_out = d["y_base"].shape
+    n = T * d_out
+    pad = 4096
+    if inplace:
+        y = binding.lordba_forward(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                                   dev["y_base"], y_out=dev["y_base"], algo=algo)
+        torch.cuda.synchronize()
+        return y.cpu().numpy()
+    big = torch.full((n + 2 * pad,), float("nan"), dtype=torch.float16, device="cuda:0")
+    y_out = big[pad:pad + n].view(T, d_out)
+    binding.lordba_forward(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                           dev["y_base"], y_out=y_out, algo=algo)
+    torch.cuda.synchronize()
+    host = big.cpu().numpy()
+    if guard:
+        assert np.isnan(host[:pad]).all() and np.isnan(host[pad + n:]).all(), "write outside y_out"
+    out = host[pad:pad + n].reshape(T, d_out)
+    assert np.array_equal(dev["x"].cpu().numpy(), d["x"]) and np.array_equal(dev["y_base"].cpu().numpy(), d["y_base"])
+    return out
+
+
+def oracle_forward(d, rows=None):
+    x, yb = (d["x"], d["y_base"]) if rows is None else (d["x"][rows], d["y_base"][rows])
+    return oracle.forward(x, d["signsA"], d["signsB"], d["s_in"], d["s_rank"], d["s_out"], yb, nthreads=NTHREADS)
+
+
+def check(torch, d, algo, label, rows=None):
+    """Parity as configured and delta-only.  `rows` restricts the oracle to a row sample."""
+    worst = 0.0
+    for tag, dd in (("full", d), ("delta", dict(d, y_base=np.zeros_like(d["y_base"])))):
+        say("  case %s algo=%d %s" % (label, algo, tag))
+        got = gpu_forward(torch, dd, algo)
+        assert not np.isnan(got).any(), "unwritten or NaN output (%s, %s)" % (label, tag)
+        want = oracle_forward(dd, rows)
+        g = got if rows is None else got[rows]
+        err = oracle.row_rel_l2(g.astype(np.float64), want)
+        assert err.max() <= TOL, "%s %s algo %d: max row rel-L2 %.3e at row %d" % (label, tag, algo, err.max(), err.argmax())
+        worst = max(worst, err.max())
+        if tag == "full":
+            # informative: how many outputs equal the correctly rounded oracle value
+            exact = np.mean(g == want.astype(np.float16))
+            assert exact > 0.97, "%s: only %.4f of outputs equal fp16(oracle)" % (label, exact)
+    return worst
+
+
+def mfma_algos(sh):
+    al = []
+    if sh.d_in % 32 == 0 and sh.d_out % 8 == 0:
+        al += [A_T8, A_T16]
+        if sh.d_in % 128 == 0:
+            al += [A_D8, A_D16]
+    return al
+
+
+# ------------------------------------------------------------------ small, several tiles, ragged ---
+
+SMALL = [
+    inputs.C1,
+    inputs.Shape("ragged_T37_160x136_r16", 37, 160, 136, 16),      # tail token tile, tail column chunk and block
+    inputs.Shape("ragged_T19_96x200_r4", 19, 96, 200, 4),
+    inputs.Shape("T1_128x128_r16", 1, 128, 128, 16),
+    inputs.Shape("T17_1024x1152_r16", 17, 1024, 1152, 16),
+    inputs.Shape("T33_640x384_r8", 33, 640, 384, 8),
+    inputs.Shape("T21_256x512_r1", 21, 256, 512, 1),
+    inputs.Shape("T9_512x256_r12", 9, 512, 256, 12),
+    inputs.Shape("T40_384x640_r17", 40, 384, 640, 17),
+    inputs.Shape("T25_256x256_r24", 25, 256, 256, 24),
+    inputs.Shape("T16_512x512_r32", 16, 512, 512, 32),
+    inputs.Shape("T23_256x384_r33", 23, 256, 384, 33),
+    inputs.Shape("T8_384x256_r48", 8, 384, 256, 48),
+    inputs.Shape("T31_512x640_r64", 31, 512, 640, 64),
+    inputs.Shape("T12_2048x2048_r7", 12, 2048, 2048, 7),
+]
+
+
+@pytest.mark.parametrize("sh", SMALL, ids=lambda s: s.name)
+def test_small_shapes_all_kernels(torch_cuda, sh):
+    d = inputs.make_inputs_for(sh, 100 + sh.T)
+    for algo in [A_AUTO, A_GEN] + mfma_algos(sh):
+        check(torch_cuda, d, algo, sh.name)
+
+
+GENERAL_ONLY = [
+    inputs.Shape("odd_T5_33x17_r3", 5, 33, 17, 3),         # nothing aligned: general kernel, scalar path
+    inputs.Shape("odd_T7_100x60_r5", 7, 100, 60, 5),
+    inputs.Shape("odd_T3_1x1_r1", 3, 1, 1, 1),
+    inputs.Shape("odd_T4_40x36_r9", 4, 40, 36, 9),          # d_in % 8 == 0 but not % 32: vector x path of the general kernel
+]
+
+
+@pytest.mark.parametrize("sh", GENERAL_ONLY, ids=lambda s: s.name)
+def test_unaligned_shapes_take_the_general_kernel(torch_cuda, sh):
+    d = inputs.make_inputs_for(sh, 7)
+    check(torch_cuda, d, A_AUTO, sh.name)
+    check(torch_cuda, d, A_GEN, sh.name)
+    dev = binding.to_device(d)
+    with pytest.raises(binding.LordbaError) as e:
+        binding.lordba_forward(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                               dev["y_base"], algo=A_T8)
+    assert e.value.status == 8
+
+
+# ---------------------------------------------------------------------------- benchmark shapes ---
+
+def test_headline_config_all_rows(torch_cuda):
+    d = inputs.make_inputs_for(inputs.C2, 2)
+    for algo in [A_AUTO, A_T8, A_T16, A_D8, A_D16, A_GEN]:
+        check(torch_cuda, d, algo, inputs.C2.name)
+
+
+@pytest.mark.parametrize("sh", [inputs.C3_UP, inputs.C3_DOWN], ids=lambda s: s.name)
+def test_mlp_shapes_all_rows(torch_cuda, sh):
+    d = inputs.make_inputs_for(sh, 3)
+    for algo in [A_AUTO, A_T8]:
+        check(torch_cuda, d, algo, sh.name)
+
+
+@pytest.mark.parametrize("sh", inputs.C4, ids=lambda s: s.name)
+def test_small_batch_sweep(torch_cuda, sh):
+    d = inputs.make_inputs_for(sh, 4)
+    for algo in [A_AUTO, A_T16, A_GEN]:
+        check(torch_cuda, d, algo, sh.name)
+
+
+@pytest.mark.parametrize("sh", [inputs.C5_Q, inputs.C5_UP, inputs.C5_DOWN], ids=lambda s: s.name)
+def test_llama13b_shapes_sampled_rows(torch_cuda, sh):
+    # full-size launch; the oracle checks every 61st token row plus the first and last tiles
+    seed = next(s for _, _, shp, s in inputs.c5_adapter_seeds(5) if shp is sh)
+    d = inputs.make_inputs_for(sh, seed)
+    rows = np.unique(np.concatenate([np.arange(0, sh.T, 61), np.arange(16), np.arange(sh.T - 16, sh.T)]))
+    got = gpu_forward(torch_cuda, d, A_AUTO)
+    assert not np.isnan(got).any()
+    err = oracle.row_rel_l2(got[rows].astype(np.float64), oracle_forward(d, rows))
+    assert err.max() <= TOL
+    # properties that hold for every row: the branch is small next to y_base and has the predicted variance
+    delta = got.astype(np.float64) - d["y_base"].astype(np.float64)
+    f = lambda a: a.astype(np.float64)
+    pred = np.mean(f(d["s_out"]) ** 2) * np.sum(f(d["s_rank"]) ** 2) * np.sum(f(d["s_in"]) ** 2)
+    assert abs(np.mean(delta ** 2) / pred - 1.0) < 0.1
+
+
+# ----------------------------------------------------------------------------------- edge cases ---
+
+def test_T_zero_is_a_no_op(torch_cuda):
+    torch = torch_cuda
+    d = inputs.make_inputs(1, 0, 64, 64, 8)
+    dev = binding.to_device(d)
+    y = binding.lordba_forward(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                               dev["y_base"])
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == (0, 64)
+
+
+@pytest.mark.parametrize("which", ["s_in", "s_rank", "s_out"])
+def test_zero_scales_return_y_base_bit_for_bit(torch_cuda, which):
+    d = inputs.make_inputs(21, 19, 256, 384, 16)
+    d[which][:] = np.float16(0)
+    for algo in (A_AUTO, A_GEN, A_T16):
+        assert np.array_equal(gpu_forward(torch_cuda, d, algo), d["y_base"])
+
+
+def test_negative_and_mixed_sign_scales(torch_cuda):
+    d = inputs.make_inputs(22, 24, 512, 384, 16)
+    g = np.random.default_rng(0)
+    for k in ("s_in", "s_rank", "s_out"):
+        d[k] = (d[k].astype(np.float32) * g.choice([-1.0, 1.0], size=d[k].shape)).astype(np.float16)
+    d["s_rank"][3] = np.float16(0)
+    for algo in (A_AUTO, A_GEN, A_T8, A_T16):
+        check(torch_cuda, d, algo, "mixed_sign_scales")
+
+
+@pytest.mark.parametrize("scale", [2.0 ** -10, 2.0 ** 8])
+def test_rank_scale_magnitude_does_not_matter(torch_cuda, scale):
+    # the fp16 hi/lo split of u is done per token row after a power-of-two normalisation, so very small or
+    # very large s_rank must not cost accuracy (checked on the branch alone)
+    d = inputs.make_inputs(23, 20, 512, 256, 16)
+    d["s_rank"] = (d["s_rank"].astype(np.float32) * scale).astype(np.float16)
+    d["y_base"][:] = np.float16(0)
+    for algo in (A_T8, A_T16, A_GEN):
+        got = gpu_forward(torch_cuda, d, algo)
+        err = oracle.row_rel_l2(got.astype(np.float64), oracle_forward(d))
+        assert err.max() <= TOL
+
+
+def test_subnormal_input_scales(torch_cuda):
+    # s_in entirely in the fp16 subnormal range: products with x must survive (no flush to zero of operands)
+    d = inputs.make_inputs(24, 16, 256, 256, 16)
+    d["s_in"] = (d["s_in"].astype(np.float32) * 2.0 ** -12).astype(np.float16)
+    assert (np.abs(d["s_in"].astype(np.float32)) < 2.0 ** -14).all() and (d["s_in"] != 0).all()
+    d["s_out"] = (d["s_out"].astype(np.float32) * 2.0 ** 9).astype(np.float16)
+    d["s_rank"] = (d["s_rank"].astype(np.float32) * 2.0 ** 4).astype(np.float16)
+    d["y_base"][:] = np.float16(0)
+    for algo in (A_T8, A_GEN):
+        got = gpu_forward(torch_cuda, d, algo)
+        err = oracle.row_rel_l2(got.astype(np.float64), oracle_forward(d))
+        assert err.max() <= TOL, "algo %d err %.3e" % (algo, err.max())
+
+
+def test_in_place_update(torch_cuda):
+    d = inputs.make_inputs(25, 45, 512, 640, 16)
+    for algo in (A_AUTO, A_GEN, A_T16):
+        a = gpu_forward(torch_cuda, d, algo)
+        b = gpu_forward(torch_cuda, d, algo, inplace=True)
+        assert np.array_equal(a, b)
+
+
+def test_sign_gauge_and_determinism_bit_for_bit(torch_cuda):
+    d = inputs.make_inputs(26, 37, 512, 384, 16)
+    for algo in (A_T8, A_T16, A_GEN):
+        a = gpu_forward(torch_cuda, d, algo)
+        assert np.array_equal(a, gpu_forward(torch_cuda, d, algo))
+        e = dict(d, signsA=d["signsA"].copy(), signsB=d["signsB"].copy())
+        for k in (0, 5, 15):
+            e["signsA"][k, :] *= -1
+            e["signsB"][:, k] *= -1
+        assert np.array_equal(a, gpu_forward(torch_cuda, e, algo))
+
+
+def test_all_plus_carriers_closed_form(torch_cuda):
+    # all signs +1, all scales 1, integer x: y = y_base + r * sum_i x[t, i] is exact in fp32, so the only
+    # rounding is the final one to fp16 and the result must equal the correctly rounded closed form
+    T, d_in, d_out, r = 18, 256, 128, 16
+    d = inputs.make_inputs(27, T, d_in, d_out, r)
+    d["signsA"][:] = 1
+    d["signsB"][:] = 1
+    for k in ("s_in", "s_rank", "s_out"):
+        d[k][:] = np.float16(1)
+    g = np.random.default_rng(1)
+    d["x"] = g.integers(-2, 3, size=(T, d_in)).astype(np.float16)
+    d["y_base"] = g.integers(-4, 5, size=(T, d_out)).astype(np.float16)
+    want = d["y_base"].astype(np.float64) + r * d["x"].astype(np.float64).sum(axis=1, keepdims=True)
+    for algo in (A_AUTO, A_GEN, A_T8, A_T16):
+        assert np.array_equal(gpu_forward(torch_cuda, d, algo), want.astype(np.float16))
+
+
+def test_stream_argument_is_honoured(torch_cuda):
+    torch = torch_cuda
+    d = inputs.make_inputs(28, 64, 512, 512, 16)
+    dev = binding.to_device(d)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        y = binding.lordba_forward(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                                   dev["y_base"])
+    s.synchronize()
+    err = oracle.row_rel_l2(y.cpu().numpy().astype(np.float64), oracle_forward(d))
+    assert err.max() <= TOL
