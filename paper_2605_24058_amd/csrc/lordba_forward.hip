@@ -45,6 +45,10 @@ constexpr int kLutBytes = 256 * 16;
 
 __device__ __forceinline__ u4 load16(const void* p) { return *reinterpret_cast<const u4*>(p); }
 __device__ __forceinline__ void store16(void* p, u4 v) { *reinterpret_cast<u4*>(p) = v; }
+// Streaming accesses for x, y_base and y_out: each byte is touched once, so it should not displace the adapter
+// (carrier bits, scales) from the caches.
+__device__ __forceinline__ u4 load16_stream(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const u4*>(p)); }
+__device__ __forceinline__ void store16_stream(void* p, u4 v) { __builtin_nontemporal_store(v, reinterpret_cast<u4*>(p)); }
 __device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
 __device__ __forceinline__ u4 as_u4(h8 v) { return __builtin_bit_cast(u4, v); }
 __device__ __forceinline__ float flip(float v, uint32_t bit) { return __uint_as_float(__float_as_uint(v) ^ (bit << 31)); }
@@ -67,182 +71,211 @@ struct FwdArgs {
     int T, d_in, d_out, r;
 };
 
-// 8 carrier bits starting at bit `bit0` of a packed stream of `nwords` words (bits past the end read as 0).
+// 8 carrier bits starting at bit `bit0` of a packed stream of `nwords` words.  Both words are always read from a
+// clamped, valid index (no branch, no access past the end); bits past the end of the stream are not meaningful and
+// the callers only use them for padded ranks, whose other operand is zero.
 __device__ __forceinline__ uint32_t fetch8(const uint32_t* __restrict__ words, int64_t bit0, int64_t nwords) {
-    const int64_t w = bit0 >> 5;
-    const uint32_t lo = w < nwords ? words[w] : 0u;
-    const uint32_t hi = (w + 1) < nwords ? words[w + 1] : 0u;
+    int64_t w = bit0 >> 5;
+    w = w < nwords ? w : nwords - 1;
+    const int64_t w1 = (w + 1) < nwords ? w + 1 : nwords - 1;
+    const uint32_t lo = words[w], hi = words[w1];
     return static_cast<uint32_t>(((static_cast<uint64_t>(hi) << 32) | lo) >> (bit0 & 31)) & 0xffu;
 }
 
-template <int RB, int TMV, int NW, bool XLDS>
+constexpr int kUBytes = 16 * kURow * 2;  // one rank block of the u tile
+
+// LDS bytes of the matrix-core kernel (host and device use the same formula).
+__host__ __device__ constexpr int mfma_sin_cols(int d_in) { return ((d_in + 127) >> 7) << 7; }
+__host__ __device__ constexpr size_t mfma_lds_bytes(int RB, int TMV, int NW, int d_in) {
+    return 2 * kLutBytes + static_cast<size_t>(mfma_sin_cols(d_in)) * 2 + static_cast<size_t>(NW) * TMV * kXRow * 2 +
+           static_cast<size_t>(NW) * RB * 1024 + static_cast<size_t>(RB) * kUBytes + 64;
+}
+
+// RB   rank blocks of 16 (r <= 16 * RB)
+// TMV  token rows per workgroup (8 or 16)
+// NW   waves per workgroup
+// D1   128-column chunks of x a wave keeps in flight
+// OS   "one shot": every wave's chunks fit in D1, so stage 1 is straight-line code and the first y_base blocks are
+//      requested right behind x; otherwise stage 1 loops over groups of D1 chunks and y_base is requested after it
+// R16  r is a multiple of 16: the carrier bits of a lane's 8 output columns are RB aligned 16-byte loads
+template <int RB, int TMV, int NW, int D1, bool OS, bool R16>
 __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     constexpr int NI = TMV / 4;  // 16-byte row accesses per lane per 128-column block of a tile
-    constexpr int D1 = XLDS ? (TMV == 8 ? 8 : 4) : 4;  // x chunks in flight per wave
-    constexpr int D2 = TMV == 8 ? 4 : 2;               // y_base column blocks in flight per wave
-    constexpr int XPW = XLDS ? NI : 4;                 // x registers (16 B) per chunk
-    constexpr int ABW = XLDS ? 1 : 4;                  // carrier dwords per lane per chunk and rank block
+    constexpr int D2 = 2;        // y_base column blocks in flight per wave
 
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, q = lane >> 4;
     const int T = a.T, d_in = a.d_in, d_out = a.d_out, r = a.r;
     const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
+    const int nchunks = (d_in + 127) >> 7;
+    const int sin_cols = nchunks << 7;
 
-    u4* lut = reinterpret_cast<u4*>(smem);
-    _Float16* sin_s = reinterpret_cast<_Float16*>(smem + kLutBytes);
-    const int sin_bytes = ((d_in * 2 + 15) >> 4) << 4;
-    unsigned char* p = smem + kLutBytes + sin_bytes;
-    _Float16* xs = reinterpret_cast<_Float16*>(p) + (XLDS ? wave * TMV * kXRow : 0);
-    p += XLDS ? NW * TMV * kXRow * 2 : 0;
+    u4* lutm = reinterpret_cast<u4*>(smem);              // 8 bits -> 8 fp16 sign masks (0x8000 where the bit is set)
+    u4* lutp = reinterpret_cast<u4*>(smem + kLutBytes);  // 8 bits -> 8 fp16 values +-1.0
+    _Float16* sin_s = reinterpret_cast<_Float16*>(smem + 2 * kLutBytes);  // s_in, zero-filled up to a whole chunk
+    unsigned char* p = smem + 2 * kLutBytes + sin_cols * 2;
+    _Float16* xs = reinterpret_cast<_Float16*>(p) + wave * TMV * kXRow;
+    p += NW * TMV * kXRow * 2;
     float* red = reinterpret_cast<float*>(p);
     p += NW * RB * 1024;
-    _Float16* us = reinterpret_cast<_Float16*>(p) + wave * RB * 16 * kURow;
+    _Float16* us = reinterpret_cast<_Float16*>(p);
+    p += RB * kUBytes;
+    float* invs = reinterpret_cast<float*>(p);
 
-    // ---------------------------------------------------------------- stage 1: x chunk pipeline ----
-    const int nchunks = (d_in + 127) >> 7;
+    // Loads are returned in issue order, so they are issued in the order their data is needed: s_rank and the first
+    // slice of s_in, then x, then (one-shot) y_base.
+    float sr[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int rk = rb * 16 + li;
+        const _Float16 h = a.s_rank[rk < r ? rk : r - 1];
+        sr[rb] = rk < r ? static_cast<float>(h) : 0.f;
+    }
+    u4 sin0;
+    {
+        const int c8 = tid * 8;
+        sin0 = load16(a.s_in + (c8 < d_in ? c8 : 0));
+        if (c8 >= d_in) sin0 = u4{0u, 0u, 0u, 0u};
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the issue order: the compiler must not sink these loads below x / y_base
+
+    // ---------------------------------------------------------------- stage 1 loads -----------------
+    // Chunk c = 128 columns of d_in; wave w owns chunks w, w + NW, ...  Loads: lane (row q + 4m, 16-byte column group
+    // li) -> 256 contiguous bytes per row and quarter-wave.  Carrier bits: lane (rank li, dword q of the chunk) holds
+    // the 32 bits of its rank for columns 32q..32q+31 of the chunk; byte s of that dword belongs to MFMA step s.
     const int my_n = wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0;
     const int words_per_row = d_in >> 5;  // d_in % 32 == 0 on this path
-
-    u4 xbuf[D1][XPW];
-    uint32_t abits[D1][RB][ABW];
+    u4 xbuf[D1][NI];
+    uint32_t abits[D1][RB];
 
     auto issue_x = [&](int slot, int n) {
-        const int c = wave + NW * n;
-        if (XLDS) {
+        int c = wave + NW * n;
+        c = c < nchunks ? c : nchunks - 1;  // past the end: re-read a valid chunk, the result is not used
 #pragma unroll
-            for (int m = 0; m < NI; ++m) {
-                int64_t tok = t0 + m * 4 + q;
-                tok = tok < T ? tok : T - 1;
-                int col = c * 128 + li * 8;
-                col = col < d_in ? col : d_in - 8;
-                xbuf[slot][m] = load16(a.x + tok * d_in + col);
-            }
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                int rk = rb * 16 + li;
-                rk = rk < r ? rk : r - 1;
-                const int w = c * 4 + q;
-                abits[slot][rb][0] = w < words_per_row ? a.pA[static_cast<int64_t>(rk) * words_per_row + w] : 0u;
-            }
-        } else {
-            int64_t tok = t0 + tile_row_of_mfma_row<TMV>(li);
+        for (int m = 0; m < NI; ++m) {
+            int64_t tok = t0 + m * 4 + q;
             tok = tok < T ? tok : T - 1;
+            int col = c * 128 + li * 8;
+            col = col < d_in ? col : d_in - 8;
+            xbuf[slot][m] = load16_stream(a.x + tok * d_in + col);
+        }
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                int col = c * 128 + s * 32 + q * 8;
-                col = col < d_in ? col : d_in - 8;
-                xbuf[slot][s] = load16(a.x + tok * d_in + col);
-            }
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                int rk = rb * 16 + li;
-                rk = rk < r ? rk : r - 1;
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const int w = c * 4 + s;
-                    abits[slot][rb][s] = w < words_per_row ? a.pA[static_cast<int64_t>(rk) * words_per_row + w] : 0u;
-                }
-            }
+        for (int rb = 0; rb < RB; ++rb) {
+            int rk = rb * 16 + li;
+            rk = rk < r ? rk : r - 1;
+            int w = c * 4 + q;
+            w = w < words_per_row ? w : words_per_row - 1;  // columns past d_in meet s_in = 0
+            abits[slot][rb] = a.pA[static_cast<int64_t>(rk) * words_per_row + w];
         }
     };
+#pragma unroll
+    for (int slot = 0; slot < D1; ++slot) issue_x(slot, slot);
+    __builtin_amdgcn_sched_barrier(0);
 
-#pragma unroll
-    for (int slot = 0; slot < D1; ++slot)
-        if (slot < my_n) issue_x(slot, slot);
-
-    // ---------------------------------------------------------------- stage 0: LDS tables ----------
-    for (int e = tid; e < 256; e += NW * 64) {
-        u4 m;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            m[i] = (((e >> (2 * i)) & 1u) << 15) | (((e >> (2 * i + 1)) & 1u) << 31);
-        lut[e] = m;
-    }
-    for (int c8 = tid * 8; c8 < d_in; c8 += NW * 64 * 8) store16(sin_s + c8, load16(a.s_in + c8));
-    __syncthreads();
-
-    bool rank_ok[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) rank_ok[rb] = rb * 16 + li < r;
-
-    f4 acc[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
-
-    auto consume_x = [&](int slot, int n) {
-        const int c = wave + NW * n;
-        if (XLDS) {
-#pragma unroll
-            for (int m = 0; m < NI; ++m) store16(xs + (m * 4 + q) * kXRow + li * 8, xbuf[slot][m]);
-            __builtin_amdgcn_wave_barrier();
-        }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            h8 xf;
-            int col0;
-            if (XLDS) {
-                col0 = c * 128 + q * 32 + s * 8;
-                xf = as_h8(load16(xs + tile_row_of_mfma_row<TMV>(li) * kXRow + q * 32 + s * 8));
-            } else {
-                col0 = c * 128 + s * 32 + q * 8;
-                xf = as_h8(xbuf[slot][s]);
-            }
-            const bool col_ok = col0 < d_in;
-            const u4 sv = load16(sin_s + (col_ok ? col0 : 0));
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                const uint32_t byte = XLDS ? (abits[slot][rb][0] >> (s * 8)) & 0xffu
-                                           : (abits[slot][rb][s] >> (q * 8)) & 0xffu;
-                u4 wv = sv ^ lut[byte];
-                if (!(col_ok && rank_ok[rb])) wv = u4{0u, 0u, 0u, 0u};
-                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf, as_h8(wv), acc[rb], 0, 0, 0);
-            }
-        }
-        if (XLDS) __builtin_amdgcn_wave_barrier();
-    };
-
-    for (int n0 = 0; n0 < my_n; n0 += D1) {
-#pragma unroll
-        for (int slot = 0; slot < D1; ++slot) {
-            const int n = n0 + slot;
-            if (n < my_n) {
-                consume_x(slot, n);
-                if (n + D1 < my_n) issue_x(slot, n + D1);
-            }
-        }
-    }
-
-    // ---------------------------------------------------------------- stage 3 prefetch -------------
+    // ---------------------------------------------------------------- stage 3 loads -----------------
+    // Block b = 128 output columns; wave w owns blocks w, w + NW, ...; lane (li, q) owns columns 8 li .. 8 li + 7 of
+    // the block for its token rows.
     const int nblk = (d_out + 127) >> 7;
     const int my_b = wave < nblk ? (nblk - wave + NW - 1) / NW : 0;
+    const int64_t nwordsB = (static_cast<int64_t>(d_out) * r + 31) >> 5;
     u4 ybuf[D2][NI];
     u4 sobuf[D2];
+    u4 bbuf[D2][R16 ? RB : 1];
 
     auto issue_y = [&](int slot, int n) {
-        const int b = wave + NW * n;
+        int b = wave + NW * n;
+        b = b < nblk ? b : nblk - 1;
         int j0 = b * 128 + li * 8;
         j0 = j0 < d_out ? j0 : d_out - 8;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             int64_t tok = t0 + (TMV == 16 ? q * 4 + i : q * 2 + i);
             tok = tok < T ? tok : T - 1;
-            ybuf[slot][i] = load16(a.y_base + tok * d_out + j0);
+            ybuf[slot][i] = load16_stream(a.y_base + tok * d_out + j0);
         }
         sobuf[slot] = load16(a.s_out + j0);
-    };
+        if (R16) {  // 8 rows of r bits = RB * 16 contiguous, 16-byte aligned bytes
 #pragma unroll
-    for (int slot = 0; slot < D2; ++slot)
-        if (slot < my_b) issue_y(slot, slot);
+            for (int rb = 0; rb < RB; ++rb) bbuf[slot][rb] = load16(a.pB + (static_cast<int64_t>(j0) * r >> 5) + rb * 4);
+        }
+    };
+    if (OS) {
+#pragma unroll
+        for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---------------------------------------------------------------- stage 0: LDS tables ----------
+    for (int e = tid; e < 256; e += NW * 64) {
+        u4 m, pm;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            m[i] = (((e >> (2 * i)) & 1u) << 15) | (((e >> (2 * i + 1)) & 1u) << 31);
+            pm[i] = m[i] ^ 0x3C003C00u;
+        }
+        lutm[e] = m;
+        lutp[e] = pm;
+    }
+    if (tid * 8 < sin_cols) store16(sin_s + tid * 8, sin0);
+    for (int c8 = (tid + NW * 64) * 8; c8 < sin_cols; c8 += NW * 64 * 8) {
+        u4 v = load16(a.s_in + (c8 < d_in ? c8 : 0));
+        if (c8 >= d_in) v = u4{0u, 0u, 0u, 0u};
+        store16(sin_s + c8, v);
+    }
+    __syncthreads();
+
+    // ---------------------------------------------------------------- stage 1: sign(A) reduction ---
+    f4 acc[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
+
+    auto consume_x = [&](int slot, int n) {
+        const int c = wave + NW * n;
+#pragma unroll
+        for (int m = 0; m < NI; ++m) store16(xs + (m * 4 + q) * kXRow + li * 8, xbuf[slot][m]);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const h8 xf = as_h8(load16(xs + tile_row_of_mfma_row<TMV>(li) * kXRow + q * 32 + s * 8));
+            const u4 sv = load16(sin_s + c * 128 + q * 32 + s * 8);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                const uint32_t off = s == 0 ? (abits[slot][rb] << 4) & 0xff0u : (abits[slot][rb] >> (s * 8 - 4)) & 0xff0u;
+                const u4 mask = *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutm) + off);
+                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf, as_h8(sv ^ mask), acc[rb], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    if (OS) {
+#pragma unroll
+        for (int slot = 0; slot < D1; ++slot)
+            if (slot < my_n) consume_x(slot, slot);
+    } else {
+        const int ngroups = (my_n + D1 - 1) / D1;
+        for (int g = 0; g + 1 < ngroups; ++g) {
+#pragma unroll
+            for (int slot = 0; slot < D1; ++slot) {
+                consume_x(slot, g * D1 + slot);
+                issue_x(slot, (g + 1) * D1 + slot);
+            }
+        }
+#pragma unroll
+        for (int slot = 0; slot < D1; ++slot)
+            if ((ngroups - 1) * D1 + slot < my_n) consume_x(slot, (ngroups - 1) * D1 + slot);
+#pragma unroll
+        for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
+    }
 
     // ---------------------------------------------------------------- stage 2: reduce, scale, split -
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
         *reinterpret_cast<f4*>(red + ((wave * RB + rb) * 64 + lane) * 4) = acc[rb];
     __syncthreads();
-
-    float inv[4];
-    {
+    if (wave == 0) {
+        // Accumulator layout: lane (li, q) holds rank li of the block for MFMA rows 4q .. 4q+3.
         f4 u[RB];
         float amax[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -250,27 +283,21 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
             f4 tsum = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int w = 0; w < NW; ++w) tsum += *reinterpret_cast<const f4*>(red + ((w * RB + rb) * 64 + lane) * 4);
-            const int rk = rb * 16 + li;
-            const float sr = rk < r ? static_cast<float>(a.s_rank[rk]) : 0.f;
-            u[rb] = tsum * sr;
+            u[rb] = tsum * sr[rb];
 #pragma unroll
             for (int i = 0; i < 4; ++i) amax[i] = fmaxf(amax[i], fabsf(u[rb][i]));
         }
-        float mul[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
 #pragma unroll
             for (int sh = 1; sh < 16; sh <<= 1) amax[i] = fmaxf(amax[i], __shfl_xor(amax[i], sh, 64));
             int e = static_cast<int>((__float_as_uint(amax[i]) >> 23) & 0xffu);
             e = e < 14 ? 14 : (e > 254 ? 254 : e);
-            mul[i] = __uint_as_float(static_cast<uint32_t>(267 - e) << 23);  // 2^(13 - (e - 127))
-            inv[i] = __uint_as_float(static_cast<uint32_t>(e - 13) << 23);   // its reciprocal
-        }
+            const float mul = __uint_as_float(static_cast<uint32_t>(267 - e) << 23);  // 2^(13 - (e - 127))
+            if (li == 0) invs[q * 4 + i] = __uint_as_float(static_cast<uint32_t>(e - 13) << 23);  // its reciprocal
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float up = u[rb][i] * mul[i];
+            for (int rb = 0; rb < RB; ++rb) {
+                const float up = u[rb][i] * mul;
                 const _Float16 hi = static_cast<_Float16>(up);
                 const _Float16 lo = static_cast<_Float16>(up - static_cast<float>(hi));
                 us[(rb * 16 + q * 4 + i) * kURow + li] = hi;
@@ -278,42 +305,38 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
             }
         }
     }
-    __builtin_amdgcn_wave_barrier();
+    __syncthreads();
     h8 ufrag[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) ufrag[rb] = as_h8(load16(us + (rb * 16 + li) * kURow + q * 8));
+    float inv[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) inv[i] = invs[q * 4 + i];
 
     // ---------------------------------------------------------------- stage 3: expand + epilogue ----
-    const int64_t nwordsB = (static_cast<int64_t>(d_out) * r + 31) >> 5;
-    const uint32_t one2 = 0x3C003C00u;  // two fp16 1.0
-    const int rbytes = r >> 3;
-
+    // MFMA e of a block produces column 8 li + e of the block for lane group li, so after the 8 MFMAs a lane holds 8
+    // consecutive columns of its token rows.  K slots of one MFMA: hi(u) of ranks 0..15, then lo(u) of ranks 0..15;
+    // lane group q supplies ranks 8 (q & 1) .. 8 (q & 1) + 7 for both halves.
     auto consume_y = [&](int slot, int n) {
         const int b = wave + NW * n;
         const int j0 = b * 128 + li * 8;
         const bool j_ok = j0 < d_out;
         const int jc = j_ok ? j0 : d_out - 8;
-
-        u4 bw = u4{0u, 0u, 0u, 0u};
-        if (r == 16) bw = load16(a.pB + (jc >> 1));  // 8 rows of 16 bits = 4 words
         f4 v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             v[e] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                uint32_t byte;
-                if (r == 16) {
-                    byte = (bw[e >> 1] >> ((e & 1) * 16 + (q & 1) * 8)) & 0xffu;
-                } else if ((r & 7) == 0) {
-                    const int bi = rb * 2 + (q & 1);
-                    byte = bi < rbytes ? reinterpret_cast<const uint8_t*>(a.pB)[static_cast<int64_t>(jc + e) * rbytes + bi] : 0u;
+                uint32_t off;
+                if (R16) {
+                    const int hw = e * RB + rb;  // half-word index inside the lane's RB * 8 half-words
+                    const uint32_t word = bbuf[slot][hw >> 3][(hw >> 1) & 3];
+                    off = ((word >> ((hw & 1) * 16)) >> ((q & 1) * 8) << 4) & 0xff0u;
                 } else {
-                    byte = fetch8(a.pB, static_cast<int64_t>(jc + e) * r + rb * 16 + (q & 1) * 8, nwordsB);
+                    off = fetch8(a.pB, static_cast<int64_t>(jc + e) * r + rb * 16 + (q & 1) * 8, nwordsB) << 4;
                 }
-                u4 sg = lut[byte];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sg[i] ^= one2;
+                const u4 sg = *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutp) + off);
                 v[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb], as_h8(sg), v[e], 0, 0, 0);
             }
         }
@@ -328,7 +351,7 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
                 const float dv = v[e][i] * inv[i];
                 out[e] = static_cast<_Float16>(static_cast<float>(yb[e]) + static_cast<float>(so[e]) * dv);
             }
-            if (j_ok && tok < T) store16(a.y_out + tok * d_out + j0, as_u4(out));
+            if (j_ok && tok < T) store16_stream(a.y_out + tok * d_out + j0, as_u4(out));
         }
     };
 
@@ -336,10 +359,8 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
         for (int slot = 0; slot < D2; ++slot) {
             const int n = n0 + slot;
-            if (n < my_b) {
-                consume_y(slot, n);
-                if (n + D2 < my_b) issue_y(slot, n + D2);
-            }
+            if (n < my_b) consume_y(slot, n);
+            if (n + D2 < my_b) issue_y(slot, n + D2);
         }
     }
 }
@@ -417,34 +438,25 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a, int 
 
 constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
 
-template <int RB, int TMV, int NW, bool XLDS>
-size_t mfma_lds_bytes(int d_in) {
-    size_t b = kLutBytes + ((static_cast<size_t>(d_in) * 2 + 15) / 16) * 16;
-    if (XLDS) b += static_cast<size_t>(NW) * TMV * kXRow * 2;
-    b += static_cast<size_t>(NW) * RB * 1024;
-    b += static_cast<size_t>(NW) * RB * 16 * kURow * 2;
-    return b;
-}
-
-template <int RB, int TMV, int NW, bool XLDS>
+template <int RB, int TMV, int NW, int D1, bool OS, bool R16>
 lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
-    const size_t lds = mfma_lds_bytes<RB, TMV, NW, XLDS>(a.d_in);
+    const size_t lds = mfma_lds_bytes(RB, TMV, NW, a.d_in);
     if (lds > kMaxLds) return LORDBA_ERR_ALGO;
-    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, XLDS>;
+    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, R16>;
     if (lds > 64 * 1024) {
         // Opt in to more than 64 KiB of dynamic LDS once per device and kernel; raising the limit is idempotent.
         static std::mutex mu;
-        static size_t granted[64] = {0};
+        static bool granted[64] = {false};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LORDBA_ERR_NO_DEVICE;
         std::lock_guard<std::mutex> g(mu);
-        if (granted[dev] < lds) {
+        if (!granted[dev]) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     static_cast<int>(kMaxLds)) != hipSuccess) {
                 (void)hipGetLastError();
                 return LORDBA_ERR_LAUNCH;
             }
-            granted[dev] = kMaxLds;
+            granted[dev] = true;
         }
     }
     const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(a.T) + TMV - 1) / TMV);
@@ -452,13 +464,27 @@ lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
 }
 
-template <int TMV, bool XLDS>
+// Picks the x pipeline: one-shot when every wave's chunks fit the deepest pipeline that the register budget of the
+// workgroup size allows, otherwise the looped variant.
+template <int RB, int TMV, int NW, bool R16>
+lordba_status launch_mfma_depth(const FwdArgs& a, hipStream_t stream) {
+    constexpr bool kDeep = TMV == 8 && NW <= 8 && RB == 1;  // 8 chunks in flight only where the registers allow it
+    const int nchunks = (a.d_in + 127) / 128;
+    const int per_wave = (nchunks + NW - 1) / NW;
+    if (per_wave <= 2) return launch_mfma<RB, TMV, NW, 2, true, R16>(a, stream);
+    if (per_wave <= 4) return launch_mfma<RB, TMV, NW, 4, true, R16>(a, stream);
+    if (kDeep && per_wave <= 8) return launch_mfma<RB, TMV, NW, (kDeep ? 8 : 4), true, R16>(a, stream);
+    return launch_mfma<RB, TMV, NW, (TMV == 8 ? 4 : 2), false, R16>(a, stream);
+}
+
+template <int TMV, int NW>
 lordba_status launch_mfma_rb(const FwdArgs& a, hipStream_t stream) {
+    const bool r16 = a.r % 16 == 0;
     switch ((a.r + 15) / 16) {
-        case 1: return launch_mfma<1, TMV, 4, XLDS>(a, stream);
-        case 2: return launch_mfma<2, TMV, 4, XLDS>(a, stream);
-        case 3: return launch_mfma<3, TMV, 4, XLDS>(a, stream);
-        case 4: return launch_mfma<4, TMV, 4, XLDS>(a, stream);
+        case 1: return r16 ? launch_mfma_depth<1, TMV, NW, true>(a, stream) : launch_mfma_depth<1, TMV, NW, false>(a, stream);
+        case 2: return r16 ? launch_mfma_depth<2, TMV, NW, true>(a, stream) : launch_mfma_depth<2, TMV, NW, false>(a, stream);
+        case 3: return r16 ? launch_mfma_depth<3, TMV, NW, true>(a, stream) : launch_mfma_depth<3, TMV, NW, false>(a, stream);
+        case 4: return r16 ? launch_mfma_depth<4, TMV, NW, true>(a, stream) : launch_mfma_depth<4, TMV, NW, false>(a, stream);
         default: return LORDBA_ERR_DIM;
     }
 }
@@ -509,7 +535,7 @@ extern "C" lordba_status lordba_forward_algo(const void* x, const uint32_t* pack
                                              int algo) {
     if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || r > LORDBA_MAX_RANK) return LORDBA_ERR_DIM;
     if (T > INT32_MAX - 64 || d_in > (1 << 24) || d_out > (1 << 24)) return LORDBA_ERR_DIM;
-    if (algo < 0 || algo > 5) return LORDBA_ERR_ALGO;
+    if (algo < 0 || algo > 7) return LORDBA_ERR_ALGO;
     // With no token rows the activation pointers may legitimately be NULL (empty allocations).
     if (T == 0) return (packedA && packedB && s_in && s_rank && s_out) ? LORDBA_OK : LORDBA_ERR_NULL;
     if (!x || !packedA || !packedB || !s_in || !s_rank || !s_out || !y_base || !y_out) return LORDBA_ERR_NULL;
@@ -550,17 +576,20 @@ extern "C" lordba_status lordba_forward_algo(const void* x, const uint32_t* pack
         if (mfma_ok) {
             // 16-row tiles halve the per-row cost of building sign operands; take them once they still give every
             // CU two workgroups, otherwise 8-row tiles keep all 256 CUs busy.
-            const lordba_status s = (T >= 16 * 512) ? launch_mfma_rb<16, true>(a, st) : launch_mfma_rb<8, true>(a, st);
+            const lordba_status s = (T >= 16 * 512) ? launch_mfma_rb<16, 8>(a, st) : launch_mfma_rb<8, 8>(a, st);
             if (s != LORDBA_ERR_ALGO) return s;
         }
         return launch_general(a, st, vec_x);
     }
     if (!mfma_ok) return LORDBA_ERR_ALGO;
     switch (algo) {
-        case LORDBA_ALGO_MFMA_T8: return launch_mfma_rb<8, true>(a, st);
-        case LORDBA_ALGO_MFMA_T16: return launch_mfma_rb<16, true>(a, st);
-        case 4: return (d_in % 128 == 0) ? launch_mfma_rb<8, false>(a, st) : LORDBA_ERR_ALGO;   // direct operand loads, 8 rows
-        case 5: return (d_in % 128 == 0) ? launch_mfma_rb<16, false>(a, st) : LORDBA_ERR_ALGO;  // direct operand loads, 16 rows
+        case LORDBA_ALGO_MFMA_T8: return launch_mfma_rb<8, 8>(a, st);
+        case LORDBA_ALGO_MFMA_T16: return launch_mfma_rb<16, 8>(a, st);
+        // tuning variants: waves per workgroup
+        case 4: return launch_mfma_rb<8, 4>(a, st);
+        case 5: return launch_mfma_rb<16, 4>(a, st);
+        case 6: return launch_mfma_rb<8, 16>(a, st);
+        case 7: return launch_mfma_rb<16, 16>(a, st);
         default: return LORDBA_ERR_ALGO;
     }
 }

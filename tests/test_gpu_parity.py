@@ -15,7 +15,8 @@ pytestmark = pytest.mark.gpu
 
 TOL = 1e-3
 NTHREADS = min(16, oracle.available_cores())
-A_AUTO, A_GEN, A_T8, A_T16, A_D8, A_D16 = 0, 1, 2, 3, 4, 5
+A_AUTO, A_GEN, A_T8, A_T16 = 0, 1, 2, 3
+A_VARIANTS = (4, 5, 6, 7)        # same kernel, other workgroup sizes (4 or 16 waves)
 
 
 @pytest.fixture(scope="module")
@@ -83,9 +84,7 @@ def check(torch, d, algo, label, rows=None):
 def mfma_algos(sh):
     al = []
     if sh.d_in % 32 == 0 and sh.d_out % 8 == 0:
-        al += [A_T8, A_T16]
-        if sh.d_in % 128 == 0:
-            al += [A_D8, A_D16]
+        al += [A_T8, A_T16] + list(A_VARIANTS)
     return al
 
 
@@ -114,7 +113,11 @@ SMALL = [
 def test_small_shapes_all_kernels(torch_cuda, sh):
     d = inputs.make_inputs_for(sh, 100 + sh.T)
     for algo in [A_AUTO, A_GEN] + mfma_algos(sh):
-        check(torch_cuda, d, algo, sh.name)
+        try:
+            check(torch_cuda, d, algo, sh.name)
+        except binding.LordbaError as e:
+            # a tuning variant may decline a shape (its LDS need exceeds the CU); the named kernels may not
+            assert e.status == 8 and algo in A_VARIANTS, (algo, e.status)
 
 
 GENERAL_ONLY = [
@@ -128,6 +131,9 @@ GENERAL_ONLY = [
 @pytest.mark.parametrize("sh", GENERAL_ONLY, ids=lambda s: s.name)
 def test_unaligned_shapes_take_the_general_kernel(torch_cuda, sh):
     d = inputs.make_inputs_for(sh, 7)
+    # with so few input channels the branch alone (~1e-4) would land in the fp16 subnormal range, where the
+    # output format itself cannot hold 1e-3 relative accuracy: lift it into the normal range
+    d["s_out"] = (d["s_out"].astype(np.float32) * 2.0 ** 8).astype(np.float16)
     check(torch_cuda, d, A_AUTO, sh.name)
     check(torch_cuda, d, A_GEN, sh.name)
     dev = binding.to_device(d)
@@ -141,7 +147,7 @@ def test_unaligned_shapes_take_the_general_kernel(torch_cuda, sh):
 
 def test_headline_config_all_rows(torch_cuda):
     d = inputs.make_inputs_for(inputs.C2, 2)
-    for algo in [A_AUTO, A_T8, A_T16, A_D8, A_D16, A_GEN]:
+    for algo in [A_AUTO, A_T8, A_T16, A_GEN] + list(A_VARIANTS):
         check(torch_cuda, d, algo, inputs.C2.name)
 
 
@@ -212,6 +218,7 @@ def test_rank_scale_magnitude_does_not_matter(torch_cuda, scale):
     # very large s_rank must not cost accuracy (checked on the branch alone)
     d = inputs.make_inputs(23, 20, 512, 256, 16)
     d["s_rank"] = (d["s_rank"].astype(np.float32) * scale).astype(np.float16)
+    d["s_out"] = (d["s_out"].astype(np.float32) / scale).astype(np.float16)   # keeps y_out in the fp16 normal range
     d["y_base"][:] = np.float16(0)
     for algo in (A_T8, A_T16, A_GEN):
         got = gpu_forward(torch_cuda, d, algo)
