@@ -51,6 +51,17 @@ __device__ __forceinline__ u4 load16_stream(const void* p) { return __builtin_no
 __device__ __forceinline__ void store16_stream(void* p, u4 v) { __builtin_nontemporal_store(v, reinterpret_cast<u4*>(p)); }
 __device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
 __device__ __forceinline__ u4 as_u4(h8 v) { return __builtin_bit_cast(u4, v); }
+// Value of the lane N places further along its row of 16 lanes (rotation inside the row, a DPP move: no LDS traffic).
+template <int N>
+__device__ __forceinline__ float row_rotate(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row_max16(float v) {
+    v = fmaxf(v, row_rotate<8>(v));
+    v = fmaxf(v, row_rotate<4>(v));
+    v = fmaxf(v, row_rotate<2>(v));
+    return fmaxf(v, row_rotate<1>(v));
+}
 __device__ __forceinline__ float flip(float v, uint32_t bit) { return __uint_as_float(__float_as_uint(v) ^ (bit << 31)); }
 
 // Row of the MFMA token operand -> token row of the tile.  With 16 token rows it is the identity.  With 8, MFMA
@@ -95,8 +106,8 @@ __host__ __device__ constexpr size_t mfma_lds_bytes(int RB, int TMV, int NW, int
 // TMV  token rows per workgroup (8 or 16)
 // NW   waves per workgroup
 // D1   128-column chunks of x a wave keeps in flight
-// OS   "one shot": every wave's chunks fit in D1, so stage 1 is straight-line code and the first y_base blocks are
-//      requested right behind x; otherwise stage 1 loops over groups of D1 chunks and y_base is requested after it
+// OS   "one shot": every wave's chunks fit in D1, so stage 1 is straight-line code; otherwise stage 1 loops over
+//      groups of D1 chunks
 // R16  r is a multiple of 16: the carrier bits of a lane's 8 output columns are RB aligned 16-byte loads
 template <int RB, int TMV, int NW, int D1, bool OS, bool R16>
 __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
@@ -200,10 +211,10 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
             for (int rb = 0; rb < RB; ++rb) bbuf[slot][rb] = load16(a.pB + (static_cast<int64_t>(j0) * r >> 5) + rb * 4);
         }
     };
-    if (OS) {
-#pragma unroll
-        for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
-    }
+    // y_base is requested only after a wave has consumed its x.  The CU's vector memory pipeline accepts a bounded
+    // number of outstanding requests and returns data in request order across all waves, so an earlier request for
+    // y_base would only sit in front of other waves' x and hold stage 1 up; issued here it refills the pipeline
+    // exactly as x drains from it.
     __builtin_amdgcn_sched_barrier(0);
 
     // ---------------------------------------------------------------- stage 0: LDS tables ----------
@@ -253,6 +264,8 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
         for (int slot = 0; slot < D1; ++slot)
             if (slot < my_n) consume_x(slot, slot);
+#pragma unroll
+        for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
     } else {
         const int ngroups = (my_n + D1 - 1) / D1;
         for (int g = 0; g + 1 < ngroups; ++g) {
@@ -280,18 +293,24 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
         float amax[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            f4 tsum = f4{0.f, 0.f, 0.f, 0.f};
+            // All NW partial tiles are requested before the first add (fixed summation order: deterministic).
+            f4 part[NW];
 #pragma unroll
-            for (int w = 0; w < NW; ++w) tsum += *reinterpret_cast<const f4*>(red + ((w * RB + rb) * 64 + lane) * 4);
-            u[rb] = tsum * sr[rb];
+            for (int w = 0; w < NW; ++w) part[w] = *reinterpret_cast<const f4*>(red + ((w * RB + rb) * 64 + lane) * 4);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int st = 1; st < NW; st <<= 1) {
+#pragma unroll
+                for (int w = 0; w + st < NW; w += 2 * st) part[w] += part[w + st];
+            }
+            u[rb] = part[0] * sr[rb];
 #pragma unroll
             for (int i = 0; i < 4; ++i) amax[i] = fmaxf(amax[i], fabsf(u[rb][i]));
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-#pragma unroll
-            for (int sh = 1; sh < 16; sh <<= 1) amax[i] = fmaxf(amax[i], __shfl_xor(amax[i], sh, 64));
-            int e = static_cast<int>((__float_as_uint(amax[i]) >> 23) & 0xffu);
+            const float rowmax = row_max16(amax[i]);  // over the 16 ranks of the block; amax already spans the blocks
+            int e = static_cast<int>((__float_as_uint(rowmax) >> 23) & 0xffu);
             e = e < 14 ? 14 : (e > 254 ? 254 : e);
             const float mul = __uint_as_float(static_cast<uint32_t>(267 - e) << 23);  // 2^(13 - (e - 127))
             if (li == 0) invs[q * 4 + i] = __uint_as_float(static_cast<uint32_t>(e - 13) << 23);  // its reciprocal
@@ -575,8 +594,8 @@ extern "C" lordba_status lordba_forward_algo(const void* x, const uint32_t* pack
     if (algo == LORDBA_ALGO_AUTO) {
         if (mfma_ok) {
             // 16-row tiles halve the per-row cost of building sign operands; take them once they still give every
-            // CU two workgroups, otherwise 8-row tiles keep all 256 CUs busy.
-            const lordba_status s = (T >= 16 * 512) ? launch_mfma_rb<16, 8>(a, st) : launch_mfma_rb<8, 8>(a, st);
+            // CU two workgroups, otherwise 8-row tiles of 16 waves keep all 256 CUs busy.
+            const lordba_status s = (T >= 16 * 512) ? launch_mfma_rb<16, 8>(a, st) : launch_mfma_rb<8, 16>(a, st);
             if (s != LORDBA_ERR_ALGO) return s;
         }
         return launch_general(a, st, vec_x);
