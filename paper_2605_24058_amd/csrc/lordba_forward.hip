@@ -9,20 +9,22 @@
 // workgroups, no partial-sum workspace and no second launch.
 //
 // Matrix-core kernel (lordba_fwd_mfma_kernel), per workgroup of NW waves and TMV token rows:
-//   stage 0  the 256-entry table "8 carrier bits -> 8 fp16 sign masks" and s_in go to LDS.
 //   stage 1  t[tok, k] = sum_i x[tok,i] * (+-s_in[i]).  The 128-column chunks of d_in are dealt round-robin
 //            to the waves.  A wave reads its chunk of x with row-contiguous 16-byte loads, transposes it
 //            through a wave-private LDS tile into the MFMA operand layout, builds the other operand
-//            (+-s_in as fp16: s_in XOR sign mask, so the product with x is exact in fp32) from one dword of
-//            carrier bits per lane, and issues v_mfma_f32_16x16x32_f16.  Partial tiles of the waves are
-//            summed in LDS in a fixed order (deterministic).
+//            (+-s_in as fp16: s_in with its sign bit XORed with the carrier bit, so the product with x is
+//            exact in fp32) with a few vector-ALU bit operations from one dword of carrier bits per lane, and
+//            issues v_mfma_f32_16x16x32_f16.  No workgroup barrier is involved: a wave starts as soon as its
+//            own data is there.  The partial tiles of the waves are summed through LDS in a fixed order.
 //   stage 2  u = s_rank * t in fp32; each token row of u is scaled by a power of two so that its largest
 //            entry is in [2^13, 2^14) and split into fp16 hi + fp16 lo (22 significant bits, no overflow or
 //            underflow whatever the magnitude of the scales); hi and lo fill the K = 32 slots of one MFMA
 //            per 16 ranks.
 //   stage 3  v[tok, j] = sum_k u[tok,k] * (+-1), 8 MFMAs per 128 output columns, arranged so that each lane
 //            ends up with 8 consecutive output columns of its token rows: y_base is read and y_out written
-//            with row-contiguous 16-byte accesses, y_out = fp16_rne(y_base + s_out * v * 2^-scale).
+//            with row-contiguous 16-byte accesses, y_out = fp16_rne(y_base + s_out * v * 2^-scale).  The +-1
+//            operands come from a 256-entry LDS table (8 carrier bits -> 8 fp16); those of a wave's first
+//            block are built with the vector ALU while the wave waits for the others to finish stage 1.
 //
 // General kernel (lordba_fwd_general_kernel): plain vector-ALU code, one workgroup per token row, any
 // shape and alignment; also the fallback when the LDS need of the matrix-core kernel exceeds the CU.
@@ -96,23 +98,65 @@ __device__ __forceinline__ uint32_t fetch8(const uint32_t* __restrict__ words, i
 constexpr int kUBytes = 16 * kURow * 2;  // one rank block of the u tile
 
 // LDS bytes of the matrix-core kernel (host and device use the same formula).
-__host__ __device__ constexpr int mfma_sin_cols(int d_in) { return ((d_in + 127) >> 7) << 7; }
-__host__ __device__ constexpr size_t mfma_lds_bytes(int RB, int TMV, int NW, int d_in) {
-    return 2 * kLutBytes + static_cast<size_t>(mfma_sin_cols(d_in)) * 2 + static_cast<size_t>(NW) * TMV * kXRow * 2 +
+__host__ __device__ constexpr size_t mfma_lds_bytes(int RB, int TMV, int NW, int D1) {
+    return kLutBytes + static_cast<size_t>(NW) * D1 * 256 + static_cast<size_t>(NW) * TMV * kXRow * 2 +
            static_cast<size_t>(NW) * RB * 1024 + static_cast<size_t>(RB) * kUBytes + 64;
+}
+
+typedef uint16_t us2 __attribute__((ext_vector_type(2)));
+
+// Sign masks of one operand dword from a word whose two 16-bit halves both hold the 8 carrier bits of the lane in
+// their low byte: bit 2i goes to the sign of the low fp16, bit 2i+1 to the sign of the high fp16.  The packed 16-bit
+// shift drops everything above the wanted bit; the bits below it are removed by the caller's mask.
+template <int I>
+__device__ __forceinline__ uint32_t spread_pair(uint32_t both) {
+    const us2 sh = {static_cast<uint16_t>(15 - 2 * I), static_cast<uint16_t>(14 - 2 * I)};
+    return __builtin_bit_cast(uint32_t, static_cast<us2>(__builtin_bit_cast(us2, both) << sh));
+}
+// 8 carrier bits -> 8 fp16 values +-1.0 (bit set = -1.0), with vector ALU only.
+__device__ __forceinline__ u4 pm_one_from_bits(uint32_t both) {
+    u4 f;
+    f[0] = (spread_pair<0>(both) & 0x80008000u) | 0x3C003C00u;
+    f[1] = (spread_pair<1>(both) & 0x80008000u) | 0x3C003C00u;
+    f[2] = (spread_pair<2>(both) & 0x80008000u) | 0x3C003C00u;
+    f[3] = (spread_pair<3>(both) & 0x80008000u) | 0x3C003C00u;
+    return f;
+}
+// 8 fp16 values with the sign of element e flipped where carrier bit e is set.
+__device__ __forceinline__ u4 flip_by_bits(u4 v, uint32_t both) {
+    v[0] ^= spread_pair<0>(both) & 0x80008000u;
+    v[1] ^= spread_pair<1>(both) & 0x80008000u;
+    v[2] ^= spread_pair<2>(both) & 0x80008000u;
+    v[3] ^= spread_pair<3>(both) & 0x80008000u;
+    return v;
+}
+
+// y = fp16(v * s + b) for two neighbouring outputs: s and b are fp16 pairs, v0/v1 fp32.  Written so that the compiler
+// selects the mixed-precision FMA (v_fma_mixlo/mixhi_f16: fp16 operands read directly, fp32 arithmetic, one rounding to
+// fp16).  Deliberately not inline assembly: the compiler reuses dead accumulator registers of an MFMA that is still in
+// flight, and it inserts the wait states such a write needs only for instructions it can see.
+__device__ __forceinline__ uint32_t scale_add_pair(float v0, float v1, uint32_t s_pair, uint32_t b_pair) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    const h2 s = __builtin_bit_cast(h2, s_pair), b = __builtin_bit_cast(h2, b_pair);
+    h2 o;
+    o[0] = static_cast<_Float16>(__builtin_fmaf(v0, static_cast<float>(s[0]), static_cast<float>(b[0])));
+    o[1] = static_cast<_Float16>(__builtin_fmaf(v1, static_cast<float>(s[1]), static_cast<float>(b[1])));
+    return __builtin_bit_cast(uint32_t, o);
 }
 
 // RB   rank blocks of 16 (r <= 16 * RB)
 // TMV  token rows per workgroup (8 or 16)
-// NW   waves per workgroup
+// NW   waves per workgroup (>= 4)
 // D1   128-column chunks of x a wave keeps in flight
 // OS   "one shot": every wave's chunks fit in D1, so stage 1 is straight-line code; otherwise stage 1 loops over
 //      groups of D1 chunks
 // R16  r is a multiple of 16: the carrier bits of a lane's 8 output columns are RB aligned 16-byte loads
 template <int RB, int TMV, int NW, int D1, bool OS, bool R16>
 __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
-    constexpr int NI = TMV / 4;  // 16-byte row accesses per lane per 128-column block of a tile
-    constexpr int D2 = 2;        // y_base column blocks in flight per wave
+    static_assert(NW >= 4, "stage 2 is spread over the first four waves");
+    constexpr int NI = TMV / 4;           // 16-byte row accesses per lane per 128-column block of a tile
+    constexpr int D2 = 2;                 // y_base column blocks in flight per wave
+    constexpr bool PRE = R16 && RB == 1;  // sign operands of the first block are built before u is known
 
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -120,13 +164,12 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     const int T = a.T, d_in = a.d_in, d_out = a.d_out, r = a.r;
     const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
     const int nchunks = (d_in + 127) >> 7;
-    const int sin_cols = nchunks << 7;
 
-    u4* lutm = reinterpret_cast<u4*>(smem);              // 8 bits -> 8 fp16 sign masks (0x8000 where the bit is set)
-    u4* lutp = reinterpret_cast<u4*>(smem + kLutBytes);  // 8 bits -> 8 fp16 values +-1.0
-    _Float16* sin_s = reinterpret_cast<_Float16*>(smem + 2 * kLutBytes);  // s_in, zero-filled up to a whole chunk
-    unsigned char* p = smem + 2 * kLutBytes + sin_cols * 2;
-    _Float16* xs = reinterpret_cast<_Float16*>(p) + wave * TMV * kXRow;
+    u4* lutp = reinterpret_cast<u4*>(smem);  // 8 bits -> 8 fp16 values +-1.0
+    unsigned char* p = smem + kLutBytes;
+    _Float16* sinw = reinterpret_cast<_Float16*>(p) + wave * D1 * 128;  // wave-private s_in slices, one per chunk slot
+    p += NW * D1 * 256;
+    _Float16* xs = reinterpret_cast<_Float16*>(p) + wave * TMV * kXRow;  // wave-private x transpose tile
     p += NW * TMV * kXRow * 2;
     float* red = reinterpret_cast<float*>(p);
     p += NW * RB * 1024;
@@ -134,8 +177,9 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     p += RB * kUBytes;
     float* invs = reinterpret_cast<float*>(p);
 
-    // Loads are returned in issue order, so they are issued in the order their data is needed: s_rank and the first
-    // slice of s_in, then x, then (one-shot) y_base.
+    // The CU's vector memory pipeline takes a bounded number of outstanding requests and returns data in request
+    // order, so loads are issued in the order their data is needed: s_rank, then per chunk s_in and x, and y_base only
+    // after the wave has consumed its x (an earlier request would sit in front of other waves' x).
     float sr[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -143,26 +187,26 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
         const _Float16 h = a.s_rank[rk < r ? rk : r - 1];
         sr[rb] = rk < r ? static_cast<float>(h) : 0.f;
     }
-    u4 sin0;
-    {
-        const int c8 = tid * 8;
-        sin0 = load16(a.s_in + (c8 < d_in ? c8 : 0));
-        if (c8 >= d_in) sin0 = u4{0u, 0u, 0u, 0u};
-    }
-    __builtin_amdgcn_sched_barrier(0);  // keep the issue order: the compiler must not sink these loads below x / y_base
 
     // ---------------------------------------------------------------- stage 1 loads -----------------
-    // Chunk c = 128 columns of d_in; wave w owns chunks w, w + NW, ...  Loads: lane (row q + 4m, 16-byte column group
-    // li) -> 256 contiguous bytes per row and quarter-wave.  Carrier bits: lane (rank li, dword q of the chunk) holds
-    // the 32 bits of its rank for columns 32q..32q+31 of the chunk; byte s of that dword belongs to MFMA step s.
+    // Chunk c = 128 columns of d_in; wave w owns chunks w, w + NW, ...  x: lane (row q + 4m, 16-byte column group li)
+    // -> 256 contiguous bytes per row and quarter-wave.  s_in: the chunk's 256 bytes, one dword per lane.  Carrier
+    // bits: lane (rank li, dword q of the chunk) holds the 32 bits of its rank for columns 32q..32q+31 of the chunk;
+    // byte s of that dword belongs to MFMA step s.
     const int my_n = wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0;
     const int words_per_row = d_in >> 5;  // d_in % 32 == 0 on this path
     u4 xbuf[D1][NI];
+    uint32_t sinbuf[D1];
     uint32_t abits[D1][RB];
 
     auto issue_x = [&](int slot, int n) {
         int c = wave + NW * n;
         c = c < nchunks ? c : nchunks - 1;  // past the end: re-read a valid chunk, the result is not used
+        {
+            const int pair = c * 64 + lane;  // fp16 pair index; d_in is even, so a pair is inside or outside as a whole
+            const uint32_t v = reinterpret_cast<const uint32_t*>(a.s_in)[pair * 2 < d_in ? pair : 0];
+            sinbuf[slot] = pair * 2 < d_in ? v : 0u;  // columns past d_in get scale 0
+        }
 #pragma unroll
         for (int m = 0; m < NI; ++m) {
             int64_t tok = t0 + m * 4 + q;
@@ -182,9 +226,9 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     };
 #pragma unroll
     for (int slot = 0; slot < D1; ++slot) issue_x(slot, slot);
-    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_sched_barrier(0);  // keep the issue order: nothing below may be hoisted above these requests
 
-    // ---------------------------------------------------------------- stage 3 loads -----------------
+    // ---------------------------------------------------------------- stage 3 loads (issued later) ---
     // Block b = 128 output columns; wave w owns blocks w, w + NW, ...; lane (li, q) owns columns 8 li .. 8 li + 7 of
     // the block for its token rows.
     const int nblk = (d_out + 127) >> 7;
@@ -199,62 +243,48 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
         b = b < nblk ? b : nblk - 1;
         int j0 = b * 128 + li * 8;
         j0 = j0 < d_out ? j0 : d_out - 8;
+        if (R16) {  // 8 rows of r bits = RB * 16 contiguous, 16-byte aligned bytes
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) bbuf[slot][rb] = load16(a.pB + (static_cast<int64_t>(j0) * r >> 5) + rb * 4);
+        }
+        sobuf[slot] = load16(a.s_out + j0);
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             int64_t tok = t0 + (TMV == 16 ? q * 4 + i : q * 2 + i);
             tok = tok < T ? tok : T - 1;
             ybuf[slot][i] = load16_stream(a.y_base + tok * d_out + j0);
         }
-        sobuf[slot] = load16(a.s_out + j0);
-        if (R16) {  // 8 rows of r bits = RB * 16 contiguous, 16-byte aligned bytes
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) bbuf[slot][rb] = load16(a.pB + (static_cast<int64_t>(j0) * r >> 5) + rb * 4);
-        }
     };
-    // y_base is requested only after a wave has consumed its x.  The CU's vector memory pipeline accepts a bounded
-    // number of outstanding requests and returns data in request order across all waves, so an earlier request for
-    // y_base would only sit in front of other waves' x and hold stage 1 up; issued here it refills the pipeline
-    // exactly as x drains from it.
-    __builtin_amdgcn_sched_barrier(0);
 
-    // ---------------------------------------------------------------- stage 0: LDS tables ----------
-    for (int e = tid; e < 256; e += NW * 64) {
-        u4 m, pm;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            m[i] = (((e >> (2 * i)) & 1u) << 15) | (((e >> (2 * i + 1)) & 1u) << 31);
-            pm[i] = m[i] ^ 0x3C003C00u;
-        }
-        lutm[e] = m;
-        lutp[e] = pm;
-    }
-    if (tid * 8 < sin_cols) store16(sin_s + tid * 8, sin0);
-    for (int c8 = (tid + NW * 64) * 8; c8 < sin_cols; c8 += NW * 64 * 8) {
-        u4 v = load16(a.s_in + (c8 < d_in ? c8 : 0));
-        if (c8 >= d_in) v = u4{0u, 0u, 0u, 0u};
-        store16(sin_s + c8, v);
-    }
-    __syncthreads();
+    // ---------------------------------------------------------------- stage 0: +-1 table -------------
+    // Only used after the barriers of stage 2, which also make it visible.
+    for (int e = tid; e < 256; e += NW * 64) lutp[e] = pm_one_from_bits(static_cast<uint32_t>(e) * 0x10001u);
 
     // ---------------------------------------------------------------- stage 1: sign(A) reduction ---
+    // Every wave works on wave-private LDS as soon as its own data has arrived.  The barrier waits for no data: it only
+    // keeps the fast waves from requesting y_base before the slow ones (held back by the bounded request queue) have
+    // requested their x.
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
     f4 acc[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
 
-    auto consume_x = [&](int slot, int n) {
-        const int c = wave + NW * n;
+    auto consume_x = [&](int slot) {
+        _Float16* sw = sinw + slot * 128;
+        reinterpret_cast<uint32_t*>(sw)[lane] = sinbuf[slot];
 #pragma unroll
         for (int m = 0; m < NI; ++m) store16(xs + (m * 4 + q) * kXRow + li * 8, xbuf[slot][m]);
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const h8 xf = as_h8(load16(xs + tile_row_of_mfma_row<TMV>(li) * kXRow + q * 32 + s * 8));
-            const u4 sv = load16(sin_s + c * 128 + q * 32 + s * 8);
+            const u4 sv = load16(sw + q * 32 + s * 8);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                const uint32_t off = s == 0 ? (abits[slot][rb] << 4) & 0xff0u : (abits[slot][rb] >> (s * 8 - 4)) & 0xff0u;
-                const u4 mask = *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutm) + off);
-                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf, as_h8(sv ^ mask), acc[rb], 0, 0, 0);
+                // byte s of the lane's carrier dword into the low byte of both halves (the other bytes are shifted out)
+                const uint32_t both = __builtin_amdgcn_perm(abits[slot][rb], abits[slot][rb], 0x00010001u * s);
+                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf, as_h8(flip_by_bits(sv, both)), acc[rb], 0, 0, 0);
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -263,65 +293,73 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     if (OS) {
 #pragma unroll
         for (int slot = 0; slot < D1; ++slot)
-            if (slot < my_n) consume_x(slot, slot);
-#pragma unroll
-        for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
+            if (slot < my_n) consume_x(slot);
     } else {
         const int ngroups = (my_n + D1 - 1) / D1;
         for (int g = 0; g + 1 < ngroups; ++g) {
 #pragma unroll
             for (int slot = 0; slot < D1; ++slot) {
-                consume_x(slot, g * D1 + slot);
+                consume_x(slot);
                 issue_x(slot, (g + 1) * D1 + slot);
             }
         }
 #pragma unroll
         for (int slot = 0; slot < D1; ++slot)
-            if ((ngroups - 1) * D1 + slot < my_n) consume_x(slot, (ngroups - 1) * D1 + slot);
-#pragma unroll
-        for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
+            if ((ngroups - 1) * D1 + slot < my_n) consume_x(slot);
     }
+#pragma unroll
+    for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
 
     // ---------------------------------------------------------------- stage 2: reduce, scale, split -
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
         *reinterpret_cast<f4*>(red + ((wave * RB + rb) * 64 + lane) * 4) = acc[rb];
+
+    // While the slower waves finish stage 1, build the sign operands of the first block (they do not depend on u).
+    // K slots of one stage-3 MFMA: hi(u) of ranks 0..15, then lo(u) of ranks 0..15; lane group q supplies ranks
+    // 8 (q & 1) .. 8 (q & 1) + 7 for both halves, i.e. byte (q & 1) of the 16-bit row of its column.
+    const uint32_t sel_even = 0x00010001u * static_cast<uint32_t>(q & 1);        // row in the low half-word of a dword
+    const uint32_t sel_odd = 0x00010001u * static_cast<uint32_t>(2 + (q & 1));   // row in the high half-word
+    u4 pre[PRE ? 8 : 1];
+    if (PRE) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t word = bbuf[0][0][e >> 1];
+            pre[e] = pm_one_from_bits(__builtin_amdgcn_perm(word, word, (e & 1) ? sel_odd : sel_even));
+        }
+    }
     __syncthreads();
-    if (wave == 0) {
-        // Accumulator layout: lane (li, q) holds rank li of the block for MFMA rows 4q .. 4q+3.
-        f4 u[RB];
-        float amax[4] = {0.f, 0.f, 0.f, 0.f};
+
+    if (wave < 4) {
+        // Accumulator layout: lane (li, q) holds rank li of the block for MFMA rows 4q .. 4q+3; wave i takes row 4q+i.
+        const int i = wave;
+        float u[RB];
+        float amax = 0.f;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            // All NW partial tiles are requested before the first add (fixed summation order: deterministic).
-            f4 part[NW];
+            float part[NW];  // all partial sums are requested before the first add; fixed order: deterministic
 #pragma unroll
-            for (int w = 0; w < NW; ++w) part[w] = *reinterpret_cast<const f4*>(red + ((w * RB + rb) * 64 + lane) * 4);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int w = 0; w < NW; ++w) part[w] = red[((w * RB + rb) * 64 + lane) * 4 + i];
 #pragma unroll
             for (int st = 1; st < NW; st <<= 1) {
 #pragma unroll
                 for (int w = 0; w + st < NW; w += 2 * st) part[w] += part[w + st];
             }
             u[rb] = part[0] * sr[rb];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) amax[i] = fmaxf(amax[i], fabsf(u[rb][i]));
+            amax = fmaxf(amax, fabsf(u[rb]));
         }
+        const float rowmax = row_max16(amax);  // over the 16 ranks of a block; amax already spans the blocks
+        int e = static_cast<int>((__float_as_uint(rowmax) >> 23) & 0xffu);
+        e = e < 14 ? 14 : (e > 254 ? 254 : e);
+        const float mul = __uint_as_float(static_cast<uint32_t>(267 - e) << 23);  // 2^(13 - (e - 127))
+        if (li == 0) invs[q * 4 + i] = __uint_as_float(static_cast<uint32_t>(e - 13) << 23);  // its reciprocal
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float rowmax = row_max16(amax[i]);  // over the 16 ranks of the block; amax already spans the blocks
-            int e = static_cast<int>((__float_as_uint(rowmax) >> 23) & 0xffu);
-            e = e < 14 ? 14 : (e > 254 ? 254 : e);
-            const float mul = __uint_as_float(static_cast<uint32_t>(267 - e) << 23);  // 2^(13 - (e - 127))
-            if (li == 0) invs[q * 4 + i] = __uint_as_float(static_cast<uint32_t>(e - 13) << 23);  // its reciprocal
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                const float up = u[rb][i] * mul;
-                const _Float16 hi = static_cast<_Float16>(up);
-                const _Float16 lo = static_cast<_Float16>(up - static_cast<float>(hi));
-                us[(rb * 16 + q * 4 + i) * kURow + li] = hi;
-                us[(rb * 16 + q * 4 + i) * kURow + 16 + li] = lo;
-            }
+        for (int rb = 0; rb < RB; ++rb) {
+            const float up = u[rb] * mul;
+            const _Float16 hi = static_cast<_Float16>(up);
+            const _Float16 lo = static_cast<_Float16>(up - static_cast<float>(hi));
+            us[(rb * 16 + q * 4 + i) * kURow + li] = hi;
+            us[(rb * 16 + q * 4 + i) * kURow + 16 + li] = lo;
         }
     }
     __syncthreads();
@@ -334,51 +372,61 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 
     // ---------------------------------------------------------------- stage 3: expand + epilogue ----
     // MFMA e of a block produces column 8 li + e of the block for lane group li, so after the 8 MFMAs a lane holds 8
-    // consecutive columns of its token rows.  K slots of one MFMA: hi(u) of ranks 0..15, then lo(u) of ranks 0..15;
-    // lane group q supplies ranks 8 (q & 1) .. 8 (q & 1) + 7 for both halves.
-    auto consume_y = [&](int slot, int n) {
+    // consecutive columns of its token rows.
+    auto consume_y = [&](int slot, int n, bool use_pre) {
         const int b = wave + NW * n;
         const int j0 = b * 128 + li * 8;
         const bool j_ok = j0 < d_out;
         const int jc = j_ok ? j0 : d_out - 8;
+        // Table offsets of all 8 * RB sign operands first (for a general r these are global loads: one wait for all).
+        uint32_t off[8][RB];
+        if (!(PRE && use_pre)) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    if (R16) {
+                        const int hw = e * RB + rb;  // half-word index inside the lane's RB * 8 half-words
+                        const uint32_t word = bbuf[slot][hw >> 3][(hw >> 1) & 3] >> ((q & 1) * 8);
+                        off[e][rb] = (hw & 1) ? (word >> 12) & 0xff0u : (word << 4) & 0xff0u;
+                    } else {
+                        off[e][rb] = fetch8(a.pB, static_cast<int64_t>(jc + e) * r + rb * 16 + (q & 1) * 8, nwordsB) << 4;
+                    }
+                }
+            }
+        }
         f4 v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             v[e] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                uint32_t off;
-                if (R16) {
-                    const int hw = e * RB + rb;  // half-word index inside the lane's RB * 8 half-words
-                    const uint32_t word = bbuf[slot][hw >> 3][(hw >> 1) & 3];
-                    off = ((word >> ((hw & 1) * 16)) >> ((q & 1) * 8) << 4) & 0xff0u;
-                } else {
-                    off = fetch8(a.pB, static_cast<int64_t>(jc + e) * r + rb * 16 + (q & 1) * 8, nwordsB) << 4;
-                }
-                const u4 sg = *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutp) + off);
+                const u4 sg = (PRE && use_pre) ? pre[e]
+                                               : *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutp) + off[e][rb]);
                 v[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb], as_h8(sg), v[e], 0, 0, 0);
             }
         }
-        const h8 so = as_h8(sobuf[slot]);
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int64_t tok = t0 + (TMV == 16 ? q * 4 + i : q * 2 + i);
-            const h8 yb = as_h8(ybuf[slot][i]);
-            h8 out;
+            u4 out;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float dv = v[e][i] * inv[i];
-                out[e] = static_cast<_Float16>(static_cast<float>(yb[e]) + static_cast<float>(so[e]) * dv);
-            }
-            if (j_ok && tok < T) store16_stream(a.y_out + tok * d_out + j0, as_u4(out));
+            for (int d = 0; d < 4; ++d)
+                out[d] = scale_add_pair(v[2 * d][i] * inv[i], v[2 * d + 1][i] * inv[i], sobuf[slot][d], ybuf[slot][i][d]);
+            if (j_ok && tok < T) store16_stream(a.y_out + tok * d_out + j0, out);
         }
     };
 
+    if (my_b > 0) {
+        consume_y(0, 0, true);
+        if (D2 < my_b) issue_y(0, D2);
+    }
     for (int n0 = 0; n0 < my_b; n0 += D2) {
 #pragma unroll
         for (int slot = 0; slot < D2; ++slot) {
             const int n = n0 + slot;
-            if (n < my_b) consume_y(slot, n);
+            if (n == 0) continue;
+            if (n < my_b) consume_y(slot, n, false);
             if (n + D2 < my_b) issue_y(slot, n + D2);
         }
     }
@@ -459,7 +507,7 @@ constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
 
 template <int RB, int TMV, int NW, int D1, bool OS, bool R16>
 lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
-    const size_t lds = mfma_lds_bytes(RB, TMV, NW, a.d_in);
+    const size_t lds = mfma_lds_bytes(RB, TMV, NW, D1);
     if (lds > kMaxLds) return LORDBA_ERR_ALGO;
     auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, R16>;
     if (lds > 64 * 1024) {
