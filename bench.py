@@ -22,6 +22,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+# HBM bytes per launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size
+# (profiles/lordba_fwd_mfma_c2_hbm_traffic.txt); bench.py cannot read hardware counters itself.
+MEASURED_TRAFFIC_BYTES = {"c2_llama7b_attn_4096x4096_r16_T2048": 49495 * 1024}
 CACHE_BYTES = 256 << 20        # Infinity Cache
 
 WORKLOADS = {}
@@ -48,6 +51,10 @@ def main():
     ap.add_argument("--algo", type=int, default=0, help="kernel selector passed to lordba_forward_algo (0 = library default)")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the streaming reference kernel")
+    ap.add_argument("--mode", choices=["forward", "stream", "copy"], default="forward",
+                    help="forward: the adapter kernel (default).  stream / copy: run ONLY the streaming reference kernel "
+                         "(read x, read y_base, write y_out) or a plain copy of x's bytes, for scaling profiler counters")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -82,46 +89,64 @@ def main():
         youts.append(torch.empty_like(ybs[-1]))
     torch.cuda.synchronize()
 
-    def step(i):
+    ref = binding.load_bench_library() if (args.mode != "forward" or not args.no_ceiling) else None
+    cur = lambda: torch.cuda.current_stream().cuda_stream
+
+    def forward_step(i):
         s = i % sets
         binding.lordba_forward(xs[s], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
                                ybs[s], y_out=youts[s], algo=args.algo, check=False)
 
+    def stream_step(i):      # same buffers, same byte split, no arithmetic: the practical HBM ceiling
+        s = i % sets
+        rc = ref.lordba_bench_stream(xs[s].data_ptr(), ybs[s].data_ptr(), youts[s].data_ptr(),
+                                     xs[s].numel() * 2, ybs[s].numel() * 2, cur())
+        assert rc == 0, rc
+
+    def copy_step(i):        # plain copy of known size (x's bytes into y_out's buffer if it fits, else into x of the next set)
+        s = i % sets
+        n = min(xs[s].numel(), youts[s].numel()) * 2
+        rc = ref.lordba_bench_copy(xs[s].data_ptr(), youts[s].data_ptr(), n - n % 16, cur())
+        assert rc == 0, rc
+
+    step = {"forward": forward_step, "stream": stream_step, "copy": copy_step}[args.mode]
+
+    def timed(fn, K, W, graph):
+        """Average microseconds per step from HIP events on the launch stream, and the wall-clock seconds."""
+        for i in range(max(W, sets)):
+            fn(i)
+        torch.cuda.synchronize()
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if graph:
+            # The K launches of the timed region are captured once and replayed: same kernels, same buffers, no host
+            # launch cost between them.  Only kernel launches are captured (no memset nodes).
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(K):
+                    fn(i)
+            g.replay()               # untimed replay: graph upload
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            a0.record()
+            g.replay()
+            a1.record()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+        else:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            a0.record()
+            for i in range(K):
+                fn(i)
+            a1.record()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+        return a0.elapsed_time(a1) * 1e3 / K, t1 - t0
+
     K, W = args.steps, args.warmup
     use_graph = not args.no_graph
-    for i in range(max(W, sets)):
-        step(i)
-    torch.cuda.synchronize()
-
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    if use_graph:
-        # The K launches of the timed region are captured once and replayed: same kernels, same buffers, no host
-        # launch cost between them.  Only kernel launches are captured (no memset nodes).
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            for i in range(K):
-                step(i)
-        g.replay()               # untimed replay: graph upload
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        e0.record()
-        g.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    else:
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        e0.record()
-        for i in range(K):
-            step(i)
-        e1.record()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    wall_s = t1 - t0
-    ev_ms = e0.elapsed_time(e1)
+    kern_us, wall_s = timed(step, K, W, use_graph)   # kern_us: average launch-to-launch duration on the stream
     ms_per_step = wall_s * 1e3 / K
-    kern_us = ev_ms * 1e3 / K                  # average launch-to-launch duration on the stream, from HIP events
     alg_bytes = sh.algorithmic_bytes()
     achieved = alg_bytes / (kern_us * 1e-6) / 1e9
 
@@ -129,18 +154,27 @@ def main():
         "metric": "adapter-branch tokens/s and achieved HBM GB/s at d=4096, r=16, T=2048",
         "value": sh.T * K / wall_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 in/out, f32 accumulate", "data": "synthetic",
+        "dtype": "f32", "io_dtype": "f16", "data": "synthetic",
         "config": {"workload": sh.name, "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
                    "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "algo": args.algo,
-                   "seed": args.seed},
+                   "seed": args.seed, "mode": args.mode},
         "achieved_hbm_gbs": achieved, "hbm_peak_gbs": HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(sh.name) if args.mode == "forward" and args.algo == 0 else None,
                      "kernel_us": kern_us, "algorithmic_bytes": alg_bytes},
     }
 
+    if args.mode == "forward" and not args.no_ceiling:
+        c_us, _ = timed(stream_step, max(200, K // 4), 20, use_graph)
+        forward_step(0)          # y_out of set 0 was overwritten by the reference kernel: restore it for the parity check
+        torch.cuda.synchronize()
+        out["stream_ceiling"] = {"what": "nontemporal read x + read y_base + write y_out, no arithmetic, same buffers",
+                                 "kernel_us": c_us, "gbs": sh.activation_bytes() / (c_us * 1e-6) / 1e9,
+                                 "forward_vs_ceiling": c_us / kern_us}
+
     # ---- CPU baseline: the fp64 oracle as it stands, on the host cores, same workload (bounded sample) ---------
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.mode == "forward":
         import oracle
         cores = oracle.available_cores()
         budget_macs = 4e9                        # keeps the leg to a few seconds at ~1e9 fp64 MAC/s/core

@@ -103,6 +103,7 @@ lordba_status lordba_forward(const void* x, const uint32_t* packedA, const uint3
  *   LORDBA_ALGO_GENERAL   vector-ALU kernel, one workgroup per token row, any shape
  *   LORDBA_ALGO_MFMA_T8   matrix-core kernel, 8 token rows per workgroup
  *   LORDBA_ALGO_MFMA_T16  matrix-core kernel, 16 token rows per workgroup
+ * Values 4..7 select the same matrix-core kernel with fewer waves per workgroup (tuning only).
  * A kernel that cannot run the shape -> LORDBA_ERR_ALGO. */
 enum { LORDBA_ALGO_AUTO = 0, LORDBA_ALGO_GENERAL = 1, LORDBA_ALGO_MFMA_T8 = 2, LORDBA_ALGO_MFMA_T16 = 3 };
 lordba_status lordba_forward_algo(const void* x, const uint32_t* packedA, const uint32_t* packedB,

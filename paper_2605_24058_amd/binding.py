@@ -52,6 +52,39 @@ def build_library(verbose: bool = False) -> str:
     return _LIB_PATH
 
 
+_BENCH_LIB_PATH = os.path.join(_PKG, "libmembench.so")
+_bench_lib = None
+
+
+def build_bench_library(verbose: bool = False) -> str:
+    """Compile the streaming reference kernels that bench.py times next to the adapter kernel."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = _BENCH_LIB_PATH + ".tmp.%d" % os.getpid()
+    cmd = [hipcc] + HIPCC_FLAGS + [os.path.join(_CSRC, "membench.hip"), "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + proc.stdout)
+    os.replace(tmp, _BENCH_LIB_PATH)
+    return _BENCH_LIB_PATH
+
+
+def load_bench_library():
+    global _bench_lib
+    if _bench_lib is None:
+        if not os.path.exists(_BENCH_LIB_PATH):
+            raise RuntimeError("libmembench.so is not built: run __graft_entry__.build() first")
+        lib = ctypes.CDLL(_BENCH_LIB_PATH)
+        i64, vp = ctypes.c_int64, ctypes.c_void_p
+        lib.lordba_bench_stream.restype = ctypes.c_int
+        lib.lordba_bench_stream.argtypes = [vp, vp, vp, i64, i64, vp]
+        lib.lordba_bench_copy.restype = ctypes.c_int
+        lib.lordba_bench_copy.argtypes = [vp, vp, i64, vp]
+        _bench_lib = lib
+    return _bench_lib
+
+
 def load_library():
     """Load liblordba.so; there is no fallback: a missing library is an error."""
     global _lib

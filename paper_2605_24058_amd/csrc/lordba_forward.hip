@@ -52,7 +52,6 @@ __device__ __forceinline__ void store16(void* p, u4 v) { *reinterpret_cast<u4*>(
 __device__ __forceinline__ u4 load16_stream(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const u4*>(p)); }
 __device__ __forceinline__ void store16_stream(void* p, u4 v) { __builtin_nontemporal_store(v, reinterpret_cast<u4*>(p)); }
 __device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
-__device__ __forceinline__ u4 as_u4(h8 v) { return __builtin_bit_cast(u4, v); }
 // Value of the lane N places further along its row of 16 lanes (rotation inside the row, a DPP move: no LDS traffic).
 template <int N>
 __device__ __forceinline__ float row_rotate(float v) {
@@ -547,6 +546,14 @@ lordba_status launch_mfma_depth(const FwdArgs& a, hipStream_t stream) {
 template <int TMV, int NW>
 lordba_status launch_mfma_rb(const FwdArgs& a, hipStream_t stream) {
     const bool r16 = a.r % 16 == 0;
+    constexpr int kMaxRb = NW == 16 ? (TMV == 8 ? 2 : 1) : 4;  // 16 waves: 128 registers per lane
+    if ((a.r + 15) / 16 > kMaxRb) return LORDBA_ERR_ALGO;
+    if constexpr (NW == 16) {
+        if (a.r <= 16) return r16 ? launch_mfma_depth<1, TMV, NW, true>(a, stream) : launch_mfma_depth<1, TMV, NW, false>(a, stream);
+        if constexpr (TMV == 8)
+            return r16 ? launch_mfma_depth<2, TMV, NW, true>(a, stream) : launch_mfma_depth<2, TMV, NW, false>(a, stream);
+        return LORDBA_ERR_ALGO;
+    }
     switch ((a.r + 15) / 16) {
         case 1: return r16 ? launch_mfma_depth<1, TMV, NW, true>(a, stream) : launch_mfma_depth<1, TMV, NW, false>(a, stream);
         case 2: return r16 ? launch_mfma_depth<2, TMV, NW, true>(a, stream) : launch_mfma_depth<2, TMV, NW, false>(a, stream);
@@ -639,26 +646,26 @@ extern "C" lordba_status lordba_forward_algo(const void* x, const uint32_t* pack
     const bool vec_x = aligned(x, 16) && aligned(s_in, 16) && (d_in % 8 == 0);
 
     if (algo == LORDBA_ALGO_GENERAL) return launch_general(a, st, vec_x);
-    if (algo == LORDBA_ALGO_AUTO) {
-        if (mfma_ok) {
-            // 16-row tiles halve the per-row cost of building sign operands; take them once they still give every
-            // CU two workgroups, otherwise 8-row tiles of 16 waves keep all 256 CUs busy.
-            const lordba_status s = (T >= 16 * 512) ? launch_mfma_rb<16, 8>(a, st) : launch_mfma_rb<8, 16>(a, st);
-            if (s != LORDBA_ERR_ALGO) return s;
-        }
-        return launch_general(a, st, vec_x);
+    if (algo != LORDBA_ALGO_AUTO && !mfma_ok) return LORDBA_ERR_ALGO;
+    if (algo == LORDBA_ALGO_AUTO && !mfma_ok) return launch_general(a, st, vec_x);
+
+    // Tile and workgroup shape.  16-row tiles halve the per-row cost of building sign operands and are taken once
+    // T / 16 tiles still fill the 256 CUs; below that, 8-row tiles keep every CU busy.  16 waves per workgroup hide
+    // the most latency but leave 128 registers per lane, which is enough up to r = 32 (8 rows) or r = 16 (16 rows).
+    const int rb = static_cast<int>((r + 15) / 16);
+    const bool tall = algo == LORDBA_ALGO_AUTO ? T >= 4096 : (algo == LORDBA_ALGO_MFMA_T16 || algo == 5 || algo == 7);
+    lordba_status s;
+    if (algo == 4 || algo == 5) {          // tuning variants: 4 waves
+        s = tall ? launch_mfma_rb<16, 4>(a, st) : launch_mfma_rb<8, 4>(a, st);
+    } else if (algo == 6 || algo == 7) {   // tuning variants: 8 waves
+        s = tall ? launch_mfma_rb<16, 8>(a, st) : launch_mfma_rb<8, 8>(a, st);
+    } else if (tall) {
+        s = rb == 1 ? launch_mfma_rb<16, 16>(a, st) : launch_mfma_rb<16, 8>(a, st);
+    } else {
+        s = rb <= 2 ? launch_mfma_rb<8, 16>(a, st) : launch_mfma_rb<8, 8>(a, st);
     }
-    if (!mfma_ok) return LORDBA_ERR_ALGO;
-    switch (algo) {
-        case LORDBA_ALGO_MFMA_T8: return launch_mfma_rb<8, 8>(a, st);
-        case LORDBA_ALGO_MFMA_T16: return launch_mfma_rb<16, 8>(a, st);
-        // tuning variants: waves per workgroup
-        case 4: return launch_mfma_rb<8, 4>(a, st);
-        case 5: return launch_mfma_rb<16, 4>(a, st);
-        case 6: return launch_mfma_rb<8, 16>(a, st);
-        case 7: return launch_mfma_rb<16, 16>(a, st);
-        default: return LORDBA_ERR_ALGO;
-    }
+    if (s == LORDBA_ERR_ALGO && algo == LORDBA_ALGO_AUTO) return launch_general(a, st, vec_x);
+    return s;
 }
 
 extern "C" lordba_status lordba_forward(const void* x, const uint32_t* packedA, const uint32_t* packedB,

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-3
 NTHREADS = min(16, oracle.available_cores())
 A_AUTO, A_GEN, A_T8, A_T16 = 0, 1, 2, 3
-A_VARIANTS = (4, 5, 6, 7)        # same kernel, other workgroup sizes (4 or 16 waves)
+A_VARIANTS = (4, 5, 6, 7)        # same kernel, other workgroup sizes (4 or 8 waves)
 
 
 @pytest.fixture(scope="module")
