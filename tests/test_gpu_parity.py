@@ -289,3 +289,31 @@ def test_stream_argument_is_honoured(torch_cuda):
     s.synchronize()
     err = oracle.row_rel_l2(y.cpu().numpy().astype(np.float64), oracle_forward(d))
     assert err.max() <= TOL
+
+
+def test_hip_graph_replays_match_eager(torch_cuda):
+    # bench.py replays a captured graph of launches; check several replays, with eager work and synchronisations in
+    # between, against the eager result (only kernel nodes are captured: the library records no memset)
+    torch = torch_cuda
+    d = inputs.make_inputs(29, 100, 1024, 768, 16)
+    dev = binding.to_device(d)
+    args = (dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"], dev["y_base"])
+    eager = binding.lordba_forward(*args).clone()
+    torch.cuda.synchronize()
+    y_a, y_b = torch.empty_like(eager), torch.empty_like(eager)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        binding.lordba_forward(*args, y_out=y_a)
+        binding.lordba_forward(*args, y_out=y_b)
+    for rep in range(4):
+        y_a.fill_(float("nan"))
+        y_b.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_a, eager) and torch.equal(y_b, eager), rep
+        again = binding.lordba_forward(*args)          # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(again, eager)
+    err = oracle.row_rel_l2(eager.cpu().numpy().astype(np.float64), oracle_forward(d))
+    assert err.max() <= TOL
