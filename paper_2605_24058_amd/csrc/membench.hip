@@ -8,8 +8,8 @@ namespace {
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
 // c[i] = a[i] ^ b[i] over 16-byte units; a and b may have different lengths (c has b's length).  Streaming hints as in
-// the adapter kernel.  The surplus of a (if any) is read and folded into a value that is stored only if it is
-// impossible, so the reads cannot be dropped.
+// the adapter kernel.  The surplus of a (if any) is read and folded into a value that is stored only if it equals a
+// run-time argument (in practice never), so the compiler cannot drop the reads.
 __global__ __launch_bounds__(256) void stream_xor_kernel(const u4* __restrict__ a, const u4* __restrict__ b, u4* __restrict__ c,
                                                         int64_t na, int64_t nb, uint32_t never) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
@@ -19,9 +19,11 @@ __global__ __launch_bounds__(256) void stream_xor_kernel(const u4* __restrict__ 
         if (i < na) v ^= __builtin_nontemporal_load(a + i);
         __builtin_nontemporal_store(v, c + i);
     }
-    u4 acc = {0u, 0u, 0u, 0u};
-    for (int64_t i = nb + i0; i < na; i += stride) acc ^= __builtin_nontemporal_load(a + i);
-    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == never && never == 0xdeadbeefu && i0 == -1) c[0] = acc;
+    if (na > nb) {
+        u4 acc = {1u, 2u, 3u, 4u};
+        for (int64_t i = nb + i0; i < na; i += stride) acc ^= __builtin_nontemporal_load(a + i);
+        if ((acc[0] + acc[1] + acc[2] + acc[3]) == never) c[i0 % nb] = acc;
+    }
 }
 
 __global__ __launch_bounds__(256) void copy_kernel(const u4* __restrict__ src, u4* __restrict__ dst, int64_t n) {
@@ -34,7 +36,7 @@ __global__ __launch_bounds__(256) void copy_kernel(const u4* __restrict__ src, u
 extern "C" int lordba_bench_stream(const void* a, const void* b, void* c, int64_t a_bytes, int64_t b_bytes, void* stream) {
     if (!a || !b || !c || a_bytes < 0 || b_bytes < 16 || (a_bytes & 15) || (b_bytes & 15)) return -1;
     hipLaunchKernelGGL(stream_xor_kernel, dim3(2048), dim3(256), 0, static_cast<hipStream_t>(stream), static_cast<const u4*>(a),
-                       static_cast<const u4*>(b), static_cast<u4*>(c), a_bytes / 16, b_bytes / 16, 0u);
+                       static_cast<const u4*>(b), static_cast<u4*>(c), a_bytes / 16, b_bytes / 16, 0x9e3779b9u);
     return static_cast<int>(hipGetLastError());
 }
 
