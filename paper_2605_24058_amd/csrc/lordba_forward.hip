@@ -149,13 +149,16 @@ __device__ __forceinline__ uint32_t scale_add_pair(float v0, float v1, uint32_t 
 // D1   128-column chunks of x a wave keeps in flight
 // OS   "one shot": every wave's chunks fit in D1, so stage 1 is straight-line code; otherwise stage 1 loops over
 //      groups of D1 chunks
-// R16  r is a multiple of 16: the carrier bits of a lane's 8 output columns are RB aligned 16-byte loads
-template <int RB, int TMV, int NW, int D1, bool OS, bool R16>
+// BM   how a lane fetches the sign(B) bits of its 8 output columns: 1 = r is a multiple of 16 (RB aligned 16-byte
+//      loads), 2 = r is 8 (one aligned 8-byte load, one byte per column), 0 = any r (two dwords per operand)
+template <int RB, int TMV, int NW, int D1, bool OS, int BM>
 __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     static_assert(NW >= 4, "stage 2 is spread over the first four waves");
     constexpr int NI = TMV / 4;           // 16-byte row accesses per lane per 128-column block of a tile
     constexpr int D2 = 2;                 // y_base column blocks in flight per wave
-    constexpr bool PRE = R16 && RB == 1;  // sign operands of the first block are built before u is known
+    constexpr bool R16 = BM == 1, R8 = BM == 2;
+    static_assert(!R8 || RB == 1, "r = 8 is one rank block");
+    constexpr bool PRE = (R16 || R8) && RB == 1;  // sign operands of the first block are built before u is known
 
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -246,6 +249,10 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) bbuf[slot][rb] = load16(a.pB + (static_cast<int64_t>(j0) * r >> 5) + rb * 4);
         }
+        if (R8) {  // 8 rows of 8 bits: one aligned 8-byte load, byte e is column e
+            const uint2 w = *reinterpret_cast<const uint2*>(a.pB + (j0 >> 2));
+            bbuf[slot][0] = u4{w.x, w.y, 0u, 0u};
+        }
         sobuf[slot] = load16(a.s_out + j0);
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -323,8 +330,13 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     if (PRE) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const uint32_t word = bbuf[0][0][e >> 1];
-            pre[e] = pm_one_from_bits(__builtin_amdgcn_perm(word, word, (e & 1) ? sel_odd : sel_even));
+            if (R8) {  // ranks 8..15 (odd q) are padding and meet u = 0: any sign will do there
+                const uint32_t word = bbuf[0][0][e >> 2];
+                pre[e] = pm_one_from_bits(__builtin_amdgcn_perm(word, word, 0x00010001u * static_cast<uint32_t>(e & 3)));
+            } else {
+                const uint32_t word = bbuf[0][0][e >> 1];
+                pre[e] = pm_one_from_bits(__builtin_amdgcn_perm(word, word, (e & 1) ? sel_odd : sel_even));
+            }
         }
     }
     __syncthreads();
@@ -388,6 +400,8 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
                         const int hw = e * RB + rb;  // half-word index inside the lane's RB * 8 half-words
                         const uint32_t word = bbuf[slot][hw >> 3][(hw >> 1) & 3] >> ((q & 1) * 8);
                         off[e][rb] = (hw & 1) ? (word >> 12) & 0xff0u : (word << 4) & 0xff0u;
+                    } else if (R8) {
+                        off[e][rb] = ((bbuf[slot][0][e >> 2] >> ((e & 3) * 8)) << 4) & 0xff0u;
                     } else {
                         off[e][rb] = fetch8(a.pB, static_cast<int64_t>(jc + e) * r + rb * 16 + (q & 1) * 8, nwordsB) << 4;
                     }
@@ -504,11 +518,11 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a, int 
 
 constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
 
-template <int RB, int TMV, int NW, int D1, bool OS, bool R16>
+template <int RB, int TMV, int NW, int D1, bool OS, int BM>
 lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
     const size_t lds = mfma_lds_bytes(RB, TMV, NW, D1);
     if (lds > kMaxLds) return LORDBA_ERR_ALGO;
-    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, R16>;
+    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, BM>;
     if (lds > 64 * 1024) {
         // Opt in to more than 64 KiB of dynamic LDS once per device and kernel; raising the limit is idempotent.
         static std::mutex mu;
@@ -532,35 +546,33 @@ lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
 
 // Picks the x pipeline: one-shot when every wave's chunks fit the deepest pipeline that the register budget of the
 // workgroup size allows, otherwise the looped variant.
-template <int RB, int TMV, int NW, bool R16>
+template <int RB, int TMV, int NW, int BM>
 lordba_status launch_mfma_depth(const FwdArgs& a, hipStream_t stream) {
     constexpr bool kDeep = TMV == 8 && NW <= 8 && RB == 1;  // 8 chunks in flight only where the registers allow it
     const int nchunks = (a.d_in + 127) / 128;
     const int per_wave = (nchunks + NW - 1) / NW;
-    if (per_wave <= 2) return launch_mfma<RB, TMV, NW, 2, true, R16>(a, stream);
-    if (per_wave <= 4) return launch_mfma<RB, TMV, NW, 4, true, R16>(a, stream);
-    if (kDeep && per_wave <= 8) return launch_mfma<RB, TMV, NW, (kDeep ? 8 : 4), true, R16>(a, stream);
-    return launch_mfma<RB, TMV, NW, (TMV == 8 ? 4 : 2), false, R16>(a, stream);
+    if (per_wave <= 2) return launch_mfma<RB, TMV, NW, 2, true, BM>(a, stream);
+    if (per_wave <= 4) return launch_mfma<RB, TMV, NW, 4, true, BM>(a, stream);
+    if (kDeep && per_wave <= 8) return launch_mfma<RB, TMV, NW, (kDeep ? 8 : 4), true, BM>(a, stream);
+    return launch_mfma<RB, TMV, NW, (TMV == 8 ? 4 : 2), false, BM>(a, stream);
 }
 
 template <int TMV, int NW>
 lordba_status launch_mfma_rb(const FwdArgs& a, hipStream_t stream) {
-    const bool r16 = a.r % 16 == 0;
     constexpr int kMaxRb = NW == 16 ? (TMV == 8 ? 2 : 1) : 4;  // 16 waves: 128 registers per lane
-    if ((a.r + 15) / 16 > kMaxRb) return LORDBA_ERR_ALGO;
-    if constexpr (NW == 16) {
-        if (a.r <= 16) return r16 ? launch_mfma_depth<1, TMV, NW, true>(a, stream) : launch_mfma_depth<1, TMV, NW, false>(a, stream);
-        if constexpr (TMV == 8)
-            return r16 ? launch_mfma_depth<2, TMV, NW, true>(a, stream) : launch_mfma_depth<2, TMV, NW, false>(a, stream);
-        return LORDBA_ERR_ALGO;
+    const int rb = (a.r + 15) / 16;
+    if (rb > kMaxRb) return LORDBA_ERR_ALGO;
+    if (a.r == 8) return launch_mfma_depth<1, TMV, NW, 2>(a, stream);
+    const bool r16 = a.r % 16 == 0;
+    if (rb == 1) return r16 ? launch_mfma_depth<1, TMV, NW, 1>(a, stream) : launch_mfma_depth<1, TMV, NW, 0>(a, stream);
+    if constexpr (kMaxRb >= 2) {
+        if (rb == 2) return r16 ? launch_mfma_depth<2, TMV, NW, 1>(a, stream) : launch_mfma_depth<2, TMV, NW, 0>(a, stream);
     }
-    switch ((a.r + 15) / 16) {
-        case 1: return r16 ? launch_mfma_depth<1, TMV, NW, true>(a, stream) : launch_mfma_depth<1, TMV, NW, false>(a, stream);
-        case 2: return r16 ? launch_mfma_depth<2, TMV, NW, true>(a, stream) : launch_mfma_depth<2, TMV, NW, false>(a, stream);
-        case 3: return r16 ? launch_mfma_depth<3, TMV, NW, true>(a, stream) : launch_mfma_depth<3, TMV, NW, false>(a, stream);
-        case 4: return r16 ? launch_mfma_depth<4, TMV, NW, true>(a, stream) : launch_mfma_depth<4, TMV, NW, false>(a, stream);
-        default: return LORDBA_ERR_DIM;
+    if constexpr (kMaxRb >= 4) {
+        if (rb == 3) return r16 ? launch_mfma_depth<3, TMV, NW, 1>(a, stream) : launch_mfma_depth<3, TMV, NW, 0>(a, stream);
+        if (rb == 4) return r16 ? launch_mfma_depth<4, TMV, NW, 1>(a, stream) : launch_mfma_depth<4, TMV, NW, 0>(a, stream);
     }
+    return LORDBA_ERR_DIM;
 }
 
 lordba_status launch_general(const FwdArgs& a, hipStream_t stream, bool vec_x) {

@@ -97,6 +97,7 @@ SMALL = [
     inputs.Shape("T1_128x128_r16", 1, 128, 128, 16),
     inputs.Shape("T17_1024x1152_r16", 17, 1024, 1152, 16),
     inputs.Shape("T33_640x384_r8", 33, 640, 384, 8),
+    inputs.Shape("ragged_T13_288x200_r8", 13, 288, 200, 8),         # r = 8 byte-per-column path with a tail block
     inputs.Shape("T21_256x512_r1", 21, 256, 512, 1),
     inputs.Shape("T9_512x256_r12", 9, 512, 256, 12),
     inputs.Shape("T40_384x640_r17", 40, 384, 640, 17),
