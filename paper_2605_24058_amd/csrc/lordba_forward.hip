@@ -51,6 +51,10 @@ __device__ __forceinline__ void store16(void* p, u4 v) { *reinterpret_cast<u4*>(
 // (carrier bits, scales) from the caches.
 __device__ __forceinline__ u4 load16_stream(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const u4*>(p)); }
 __device__ __forceinline__ void store16_stream(void* p, u4 v) { __builtin_nontemporal_store(v, reinterpret_cast<u4*>(p)); }
+// Address = uniform base (kept in scalar registers) + unsigned 32-bit byte offset per lane: one add-free addressing
+// mode, no 64-bit vector arithmetic.
+__device__ __forceinline__ const void* at(const void* base, uint32_t byte_off) { return static_cast<const char*>(base) + byte_off; }
+__device__ __forceinline__ void* at(void* base, uint32_t byte_off) { return static_cast<char*>(base) + byte_off; }
 __device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
 // Value of the lane N places further along its row of 16 lanes (rotation inside the row, a DPP move: no LDS traffic).
 template <int N>
@@ -182,13 +186,11 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     // The CU's vector memory pipeline takes a bounded number of outstanding requests and returns data in request
     // order, so loads are issued in the order their data is needed: s_rank, then per chunk s_in and x, and y_base only
     // after the wave has consumed its x (an earlier request would sit in front of other waves' x).
-    float sr[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int rk = rb * 16 + li;
-        const _Float16 h = a.s_rank[rk < r ? rk : r - 1];
-        sr[rb] = rk < r ? static_cast<float>(h) : 0.f;
-    }
+    // A tile never spans more than 16 rows of at most 2^24 columns, so offsets inside it fit 32 bits.
+    const int last = static_cast<int>(T - 1 - t0 < TMV - 1 ? T - 1 - t0 : TMV - 1);  // last live row of the tile
+    const _Float16* xt = a.x + t0 * d_in;
+    const _Float16* ybt = a.y_base + t0 * d_out;
+    _Float16* yot = a.y_out + t0 * d_out;
 
     // ---------------------------------------------------------------- stage 1 loads -----------------
     // Chunk c = 128 columns of d_in; wave w owns chunks w, w + NW, ...  x: lane (row q + 4m, 16-byte column group li)
@@ -206,16 +208,16 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
         c = c < nchunks ? c : nchunks - 1;  // past the end: re-read a valid chunk, the result is not used
         {
             const int pair = c * 64 + lane;  // fp16 pair index; d_in is even, so a pair is inside or outside as a whole
-            const uint32_t v = reinterpret_cast<const uint32_t*>(a.s_in)[pair * 2 < d_in ? pair : 0];
+            const uint32_t v = *static_cast<const uint32_t*>(at(a.s_in, static_cast<uint32_t>(pair * 2 < d_in ? pair : 0) * 4u));
             sinbuf[slot] = pair * 2 < d_in ? v : 0u;  // columns past d_in get scale 0
         }
 #pragma unroll
         for (int m = 0; m < NI; ++m) {
-            int64_t tok = t0 + m * 4 + q;
-            tok = tok < T ? tok : T - 1;
+            int row = m * 4 + q;
+            row = row < last ? row : last;
             int col = c * 128 + li * 8;
             col = col < d_in ? col : d_in - 8;
-            xbuf[slot][m] = load16_stream(a.x + tok * d_in + col);
+            xbuf[slot][m] = load16_stream(at(xt, static_cast<uint32_t>(row * d_in + col) * 2u));
         }
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
@@ -223,12 +225,20 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
             rk = rk < r ? rk : r - 1;
             int w = c * 4 + q;
             w = w < words_per_row ? w : words_per_row - 1;  // columns past d_in meet s_in = 0
-            abits[slot][rb] = a.pA[static_cast<int64_t>(rk) * words_per_row + w];
+            abits[slot][rb] = *static_cast<const uint32_t*>(at(a.pA, static_cast<uint32_t>(rk * words_per_row + w) * 4u));
         }
     };
 #pragma unroll
     for (int slot = 0; slot < D1; ++slot) issue_x(slot, slot);
     __builtin_amdgcn_sched_barrier(0);  // keep the issue order: nothing below may be hoisted above these requests
+    float sr[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int rk = rb * 16 + li;
+        const _Float16 h = *static_cast<const _Float16*>(at(a.s_rank, static_cast<uint32_t>(rk < r ? rk : r - 1) * 2u));
+        sr[rb] = rk < r ? static_cast<float>(h) : 0.f;
+    }
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---------------------------------------------------------------- stage 3 loads (issued later) ---
     // Block b = 128 output columns; wave w owns blocks w, w + NW, ...; lane (li, q) owns columns 8 li .. 8 li + 7 of
@@ -247,18 +257,18 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
         j0 = j0 < d_out ? j0 : d_out - 8;
         if (R16) {  // 8 rows of r bits = RB * 16 contiguous, 16-byte aligned bytes
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) bbuf[slot][rb] = load16(a.pB + (static_cast<int64_t>(j0) * r >> 5) + rb * 4);
+            for (int rb = 0; rb < RB; ++rb) bbuf[slot][rb] = load16(at(a.pB, static_cast<uint32_t>(j0 * (r >> 3) + rb * 16)));
         }
         if (R8) {  // 8 rows of 8 bits: one aligned 8-byte load, byte e is column e
-            const uint2 w = *reinterpret_cast<const uint2*>(a.pB + (j0 >> 2));
+            const uint2 w = *static_cast<const uint2*>(at(a.pB, static_cast<uint32_t>(j0)));
             bbuf[slot][0] = u4{w.x, w.y, 0u, 0u};
         }
-        sobuf[slot] = load16(a.s_out + j0);
+        sobuf[slot] = load16(at(a.s_out, static_cast<uint32_t>(j0) * 2u));
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            int64_t tok = t0 + (TMV == 16 ? q * 4 + i : q * 2 + i);
-            tok = tok < T ? tok : T - 1;
-            ybuf[slot][i] = load16_stream(a.y_base + tok * d_out + j0);
+            int row = TMV == 16 ? q * 4 + i : q * 2 + i;
+            row = row < last ? row : last;
+            ybuf[slot][i] = load16_stream(at(ybt, static_cast<uint32_t>(row * d_out + j0) * 2u));
         }
     };
 
@@ -421,12 +431,12 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
         }
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int64_t tok = t0 + (TMV == 16 ? q * 4 + i : q * 2 + i);
+            const int row = TMV == 16 ? q * 4 + i : q * 2 + i;
             u4 out;
 #pragma unroll
             for (int d = 0; d < 4; ++d)
                 out[d] = scale_add_pair(v[2 * d][i] * inv[i], v[2 * d + 1][i] * inv[i], sobuf[slot][d], ybuf[slot][i][d]);
-            if (j_ok && tok < T) store16_stream(a.y_out + tok * d_out + j0, out);
+            if (j_ok && row <= last) store16_stream(at(yot, static_cast<uint32_t>(row * d_out + j0) * 2u), out);
         }
     };
 
