@@ -10,6 +10,12 @@ buffer sets that the 256 MB Infinity Cache cannot hold them, so the reported GB/
 Prints one JSON line: metric/value (tokens/s), ms_per_step, a `roofline` object for the kernel
 (algorithmic bytes per launch / average launch duration from HIP events on the launch stream, against
 the 8 TB/s HBM peak), and a `cpu_baseline` object (the fp64 CPU oracle timed on the host cores).
+
+Two further workloads report what the single-shape line cannot:
+  --workload c5_model   one step = the 280 adapter calls of a 40-layer LLaMA-2-13B pass at T = 8192
+                        (280 distinct adapters resident, three rotating activation sets); value = model-level tokens/s
+  --workload c4_sweep   the decode-size shapes r in {8,16,32,64} x T in {1,8,64}: microseconds per call beside the
+                        launch-to-launch floor of an empty kernel on the same stream
 """
 import argparse
 import json
@@ -40,18 +46,185 @@ def _workloads():
     return WORKLOADS
 
 
+def timed(fn, K, W, graph, reps=1):
+    """Runs fn(0..K-1) as the timed region `reps` times.  Returns (microseconds per step of each repetition from HIP
+    events on the launch stream, wall-clock seconds of the first repetition)."""
+    import torch
+    for i in range(W):
+        fn(i)
+    torch.cuda.synchronize()
+    us, wall = [], None
+    if graph:
+        # The K launches of the timed region are captured once and replayed: same kernels, same buffers, no host
+        # launch cost between them.  Only kernel launches are captured (no memset nodes).
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(K):
+                fn(i)
+        g.replay()               # untimed replay: graph upload
+        run = g.replay
+    else:
+        def run():
+            for i in range(K):
+                fn(i)
+    for _ in range(reps):
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        a0.record()
+        run()
+        a1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        us.append(a0.elapsed_time(a1) * 1e3 / K)
+        wall = wall if wall is not None else t1 - t0
+    return us, wall
+
+
+def _median(v):
+    v = sorted(v)
+    return v[len(v) // 2] if len(v) % 2 else 0.5 * (v[len(v) // 2 - 1] + v[len(v) // 2])
+
+
+def bench_c4_sweep(args):
+    """Decode-size calls: a roofline fraction says nothing at <= 1.7 MB per call, so the line reports microseconds per
+    call beside the launch-to-launch floor of the stream (an empty kernel in the same graph-replay harness)."""
+    import numpy as np
+    import torch
+    from paper_2605_24058_amd import binding, inputs
+    ref = binding.load_bench_library()
+    cur = lambda: torch.cuda.current_stream().cuda_stream
+    K, W = args.steps, args.warmup
+    use_graph = not args.no_graph
+
+    def empty_step(i):
+        assert ref.lordba_bench_empty(cur()) == 0
+
+    torch.manual_seed(args.seed)
+    floor_us, _ = timed(empty_step, K, W, use_graph, reps=5)
+    rows, total_wall, total_tok = [], 0.0, 0
+    for sh in inputs.C4:
+        sets = 16                                   # distinct activation sets: inputs come from HBM / far cache, not L2
+        host = inputs.make_inputs_for(sh, args.seed)
+        dev = binding.to_device(host)
+        xs = [dev["x"]] + [torch.randn_like(dev["x"]) for _ in range(sets - 1)]
+        ybs = [dev["y_base"]] + [torch.randn_like(dev["y_base"]) for _ in range(sets - 1)]
+        youts = [torch.empty_like(y) for y in ybs]
+
+        def step(i):
+            s = i % sets
+            binding.lordba_forward(xs[s], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                                   ybs[s], y_out=youts[s], algo=args.algo, check=False)
+
+        us, wall = timed(step, K, W, use_graph, reps=5)
+        total_wall += wall
+        total_tok += sh.T * K
+        rows.append({"r": sh.r, "T": sh.T, "us_per_call": _median(us), "tokens_per_s": sh.T / (_median(us) * 1e-6),
+                     "algorithmic_bytes": sh.algorithmic_bytes()})
+    out = {"metric": "adapter-branch microseconds per call at d=4096, r in {8,16,32,64}, T in {1,8,64}",
+           "value": total_tok / total_wall, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": total_wall * 1e3 / (K * len(rows)), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "io_dtype": "f16", "data": "synthetic",
+           "config": {"workload": "c4_sweep", "d_in": 4096, "d_out": 4096, "launch": "hip_graph" if use_graph else "eager",
+                      "algo": args.algo, "seed": args.seed, "repetitions": 5, "statistic": "median"},
+           "launch_floor_us": _median(floor_us), "calls": rows}
+    print(json.dumps(out))
+
+
+def bench_c5_model(args):
+    """All 280 adapter calls of one LLaMA-2-13B pass (40 layers x q, k, v, o, gate, up, down) at T = 8192."""
+    import numpy as np
+    import torch
+    from paper_2605_24058_amd import binding, inputs
+    K, W = args.steps, args.warmup
+    use_graph = not args.no_graph
+    T = inputs.C5_Q.T
+    nsets = 3
+    # ---- 280 adapters, all resident ------------------------------------------------------------------------------
+    adapters = []
+    for layer, name, sh, seed in inputs.c5_adapter_seeds(args.seed):
+        h = inputs.make_adapter(seed, sh.d_in, sh.d_out, sh.r)
+        pA, pB = binding.lordba_pack_signs(h["signsA"], h["signsB"])
+        d = {k: torch.from_numpy(h[k]).cuda() for k in ("s_in", "s_rank", "s_out")}
+        d["packedA"] = torch.from_numpy(pA.view(np.int32)).cuda()
+        d["packedB"] = torch.from_numpy(pB.view(np.int32)).cuda()
+        adapters.append((layer, name, sh, h, d))
+    # ---- three rotating activation sets, each with buffers of both widths -----------------------------------------
+    widths = sorted({sh.d_in for *_, sh, _, _ in adapters} | {sh.d_out for *_, sh, _, _ in adapters})
+    host_sets, dev_sets = [], []
+    for s in range(nsets):
+        hs, ds = {}, {}
+        for w in widths:
+            act = inputs.make_activations(args.seed + 7919 * (s + 1) + w, T, w, w)
+            hs[w] = act
+            ds[w] = {"x": torch.from_numpy(act["x"]).cuda(), "y_base": torch.from_numpy(act["y_base"]).cuda()}
+            ds[w]["y_out"] = torch.empty_like(ds[w]["y_base"])
+        host_sets.append(hs)
+        dev_sets.append(ds)
+    torch.cuda.synchronize()
+    ncalls = len(adapters)
+
+    def call(c):
+        layer, name, sh, h, d = adapters[c]
+        s = c % nsets
+        return binding.lordba_forward(dev_sets[s][sh.d_in]["x"], d["packedA"], d["packedB"], d["s_in"], d["s_rank"], d["s_out"],
+                                      dev_sets[s][sh.d_out]["y_base"], y_out=dev_sets[s][sh.d_out]["y_out"],
+                                      algo=args.algo, check=False)
+
+    def model_pass(i):
+        for c in range(ncalls):
+            call(c)
+
+    us, wall = timed(model_pass, K, W, use_graph, reps=1)
+    pass_us = us[0]
+    alg_bytes = sum(sh.algorithmic_bytes() for *_, sh, _, _ in adapters)
+    achieved = alg_bytes / (pass_us * 1e-6) / 1e9
+    out = {"metric": "model-level adapter-branch tokens/s over the 280 adapter calls of LLaMA-2-13B at T=8192",
+           "value": T * K / wall, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": wall * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "io_dtype": "f16", "data": "synthetic",
+           "config": {"workload": "c5_model", "T": T, "r": 16, "layers": inputs.C5_LAYERS, "calls_per_step": ncalls,
+                      "activation_sets": nsets, "launch": "hip_graph" if use_graph else "eager", "algo": args.algo,
+                      "seed": args.seed},
+           "achieved_hbm_gbs": achieved, "hbm_peak_gbs": HBM_PEAK_GBS,
+           "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel_us": pass_us / ncalls,
+                        "algorithmic_bytes": alg_bytes, "note": "all 280 launches of a pass taken together"}}
+    if not args.no_cpu_baseline:
+        # The oracle on every 64th token row of all 280 projections; the same rows are the parity check.
+        import oracle
+        cores = oracle.available_cores()
+        idx = np.arange(0, T, 64)
+        didx = torch.from_numpy(idx).cuda()
+        worst, cpu_s = 0.0, 0.0
+        for c in range(ncalls):
+            layer, name, sh, h, d = adapters[c]
+            s = c % nsets
+            xh, ybh = host_sets[s][sh.d_in]["x"][idx], host_sets[s][sh.d_out]["y_base"][idx]
+            c0 = time.perf_counter()
+            want = oracle.forward(xh, h["signsA"], h["signsB"], h["s_in"], h["s_rank"], h["s_out"], ybh, nthreads=cores)
+            cpu_s += time.perf_counter() - c0
+            got = call(c)[didx]
+            worst = max(worst, float(oracle.row_rel_l2(got.cpu().numpy().astype(np.float64), want).max()))
+        out["cpu_baseline"] = {"value": len(idx) / cpu_s, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                               "sample": "every 64th token row (%d of %d) through all %d projections" % (len(idx), T, ncalls)}
+        out["parity_max_row_rel_l2"] = worst
+        out["parity_ok"] = bool(worst <= 1e-3)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2400)
-    ap.add_argument("--warmup", type=int, default=240)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to cycle through (0 = enough to defeat the cache)")
     ap.add_argument("--algo", type=int, default=0, help="kernel selector passed to lordba_forward_algo (0 = library default)")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-ceiling", action="store_true", help="skip the streaming reference kernel")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the streaming reference kernel and the extra repetitions")
     ap.add_argument("--mode", choices=["forward", "stream", "copy"], default="forward",
                     help="forward: the adapter kernel (default).  stream / copy: run ONLY the streaming reference kernel "
                          "(read x, read y_base, write y_out) or a plain copy of x's bytes, for scaling profiler counters")
@@ -67,10 +240,19 @@ def main():
 
     from paper_2605_24058_amd import binding, inputs
 
-    sh = _workloads()[args.workload]
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     binding.load_library()      # raises if the HIP library is missing: there is no fallback path
+
+    if args.workload == "c5_model":
+        args.steps = 10 if args.steps is None else args.steps
+        args.warmup = 1 if args.warmup is None else args.warmup
+        return bench_c5_model(args)
+    args.steps = 2400 if args.steps is None else args.steps
+    args.warmup = 240 if args.warmup is None else args.warmup
+    if args.workload == "c4_sweep":
+        return bench_c4_sweep(args)
+    sh = _workloads()[args.workload]
 
     # ---- inputs: one adapter, `sets` activation sets, all resident in HBM before timing ------------------------
     per_set = sh.activation_bytes()
@@ -97,6 +279,10 @@ def main():
         binding.lordba_forward(xs[s], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
                                ybs[s], y_out=youts[s], algo=args.algo, check=False)
 
+    def hot_step(i):         # one buffer set only: the streams stay in the Infinity Cache
+        binding.lordba_forward(xs[0], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                               ybs[0], y_out=youts[0], algo=args.algo, check=False)
+
     def stream_step(i):      # same buffers, same byte split, no arithmetic: the practical HBM ceiling
         s = i % sets
         rc = ref.lordba_bench_stream(xs[s].data_ptr(), ybs[s].data_ptr(), youts[s].data_ptr(),
@@ -111,41 +297,12 @@ def main():
 
     step = {"forward": forward_step, "stream": stream_step, "copy": copy_step}[args.mode]
 
-    def timed(fn, K, W, graph):
-        """Average microseconds per step from HIP events on the launch stream, and the wall-clock seconds."""
-        for i in range(max(W, sets)):
-            fn(i)
-        torch.cuda.synchronize()
-        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        if graph:
-            # The K launches of the timed region are captured once and replayed: same kernels, same buffers, no host
-            # launch cost between them.  Only kernel launches are captured (no memset nodes).
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                for i in range(K):
-                    fn(i)
-            g.replay()               # untimed replay: graph upload
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            a0.record()
-            g.replay()
-            a1.record()
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-        else:
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            a0.record()
-            for i in range(K):
-                fn(i)
-            a1.record()
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-        return a0.elapsed_time(a1) * 1e3 / K, t1 - t0
-
     K, W = args.steps, args.warmup
     use_graph = not args.no_graph
-    kern_us, wall_s = timed(step, K, W, use_graph)   # kern_us: average launch-to-launch duration on the stream
+    full = args.mode == "forward" and not args.no_ceiling
+    # The first repetition is the timed region (value, ms_per_step, roofline); the others only show the spread.
+    reps_us, wall_s = timed(step, K, max(W, sets), use_graph, reps=5 if full else 1)
+    kern_us = reps_us[0]     # average launch-to-launch duration on the stream over the timed region
     ms_per_step = wall_s * 1e3 / K
     alg_bytes = sh.algorithmic_bytes()
     achieved = alg_bytes / (kern_us * 1e-6) / 1e9
@@ -165,13 +322,20 @@ def main():
                      "kernel_us": kern_us, "algorithmic_bytes": alg_bytes},
     }
 
-    if args.mode == "forward" and not args.no_ceiling:
-        c_us, _ = timed(stream_step, max(200, K // 4), 20, use_graph)
+    if full:
+        out["roofline"]["kernel_us_repetitions"] = reps_us
+        out["roofline"]["kernel_us_median"] = _median(reps_us)
+        c_us, _ = timed(stream_step, max(200, K // 4), 20, use_graph, reps=3)
+        c_us = _median(c_us)
+        h_us, _ = timed(hot_step, max(200, K // 4), 20, use_graph, reps=3)
+        h_us = _median(h_us)
         forward_step(0)          # y_out of set 0 was overwritten by the reference kernel: restore it for the parity check
         torch.cuda.synchronize()
         out["stream_ceiling"] = {"what": "nontemporal read x + read y_base + write y_out, no arithmetic, same buffers",
                                  "kernel_us": c_us, "gbs": sh.activation_bytes() / (c_us * 1e-6) / 1e9,
                                  "forward_vs_ceiling": c_us / kern_us}
+        out["cache_resident"] = {"what": "same call on ONE buffer set (streams served by the 256 MB Infinity Cache): not HBM",
+                                 "kernel_us": h_us, "gbs": alg_bytes / (h_us * 1e-6) / 1e9}
 
     # ---- CPU baseline: the fp64 oracle as it stands, on the host cores, same workload (bounded sample) ---------
     if not args.no_cpu_baseline and args.mode == "forward":

@@ -81,6 +81,8 @@ def load_bench_library():
         lib.lordba_bench_stream.argtypes = [vp, vp, vp, i64, i64, vp]
         lib.lordba_bench_copy.restype = ctypes.c_int
         lib.lordba_bench_copy.argtypes = [vp, vp, i64, vp]
+        lib.lordba_bench_empty.restype = ctypes.c_int
+        lib.lordba_bench_empty.argtypes = [vp]
         _bench_lib = lib
     return _bench_lib
 

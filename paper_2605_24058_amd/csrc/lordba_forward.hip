@@ -41,6 +41,9 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
+#ifndef LORDBA_VALU_SIGNS
+#define LORDBA_VALU_SIGNS 0
+#endif
 constexpr int kXRow = 136;  // halves per row of the x transpose tile: 128 columns + 8 pad -> conflict-free b128 reads
 constexpr int kURow = 40;   // halves per row of the u tile: 32 slots + 8 pad
 constexpr int kLutBytes = 256 * 16;
@@ -118,11 +121,12 @@ __device__ __forceinline__ uint32_t spread_pair(uint32_t both) {
 }
 // 8 carrier bits -> 8 fp16 values +-1.0 (bit set = -1.0), with vector ALU only.
 __device__ __forceinline__ u4 pm_one_from_bits(uint32_t both) {
+    // (shifted & sign bits) | 1.0 in one three-input bit operation (truth table 0xEA = (a & b) | c)
     u4 f;
-    f[0] = (spread_pair<0>(both) & 0x80008000u) | 0x3C003C00u;
-    f[1] = (spread_pair<1>(both) & 0x80008000u) | 0x3C003C00u;
-    f[2] = (spread_pair<2>(both) & 0x80008000u) | 0x3C003C00u;
-    f[3] = (spread_pair<3>(both) & 0x80008000u) | 0x3C003C00u;
+    f[0] = __builtin_amdgcn_bitop3_b32(spread_pair<0>(both), 0x80008000u, 0x3C003C00u, 0xEA);
+    f[1] = __builtin_amdgcn_bitop3_b32(spread_pair<1>(both), 0x80008000u, 0x3C003C00u, 0xEA);
+    f[2] = __builtin_amdgcn_bitop3_b32(spread_pair<2>(both), 0x80008000u, 0x3C003C00u, 0xEA);
+    f[3] = __builtin_amdgcn_bitop3_b32(spread_pair<3>(both), 0x80008000u, 0x3C003C00u, 0xEA);
     return f;
 }
 // 8 fp16 values with the sign of element e flipped where carrier bit e is set.
@@ -155,7 +159,8 @@ __device__ __forceinline__ uint32_t scale_add_pair(float v0, float v1, uint32_t 
 //      groups of D1 chunks
 // BM   how a lane fetches the sign(B) bits of its 8 output columns: 1 = r is a multiple of 16 (RB aligned 16-byte
 //      loads), 2 = r is 8 (one aligned 8-byte load, one byte per column), 0 = any r (two dwords per operand)
-template <int RB, int TMV, int NW, int D1, bool OS, int BM>
+// LP   the waves that do not run stage 2 build their first block's sign operands during stage 2 instead of before it
+template <int RB, int TMV, int NW, int D1, bool OS, int BM, bool LP>
 __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     static_assert(NW >= 4, "stage 2 is spread over the first four waves");
     constexpr int NI = TMV / 4;           // 16-byte row accesses per lane per 128-column block of a tile
@@ -163,6 +168,7 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     constexpr bool R16 = BM == 1, R8 = BM == 2;
     static_assert(!R8 || RB == 1, "r = 8 is one rank block");
     constexpr bool PRE = (R16 || R8) && RB == 1;  // sign operands of the first block are built before u is known
+    constexpr bool kValuSigns = (R16 || R8) && LORDBA_VALU_SIGNS;  // stage 3 builds every sign operand with the vector ALU
 
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -337,7 +343,7 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     const uint32_t sel_even = 0x00010001u * static_cast<uint32_t>(q & 1);        // row in the low half-word of a dword
     const uint32_t sel_odd = 0x00010001u * static_cast<uint32_t>(2 + (q & 1));   // row in the high half-word
     u4 pre[PRE ? 8 : 1];
-    if (PRE) {
+    auto build_pre = [&]() {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             if (R8) {  // ranks 8..15 (odd q) are padding and meet u = 0: any sign will do there
@@ -348,7 +354,11 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
                 pre[e] = pm_one_from_bits(__builtin_amdgcn_perm(word, word, (e & 1) ? sel_odd : sel_even));
             }
         }
-    }
+    };
+    // The waves that run stage 2 build theirs while they wait for the slower waves to finish stage 1.  The others idle
+    // during stage 2 anyway: with LP they build theirs there, which takes the work off the slowest wave's way to the
+    // first barrier; without LP (a few workgroups, latency-bound) everything is built as early as possible.
+    if (PRE && (!LP || wave < 4)) build_pre();
     __syncthreads();
 
     if (wave < 4) {
@@ -382,6 +392,8 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
             us[(rb * 16 + q * 4 + i) * kURow + li] = hi;
             us[(rb * 16 + q * 4 + i) * kURow + 16 + li] = lo;
         }
+    } else if (PRE && LP) {
+        build_pre();
     }
     __syncthreads();
     h8 ufrag[RB];
@@ -401,7 +413,7 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
         const int jc = j_ok ? j0 : d_out - 8;
         // Table offsets of all 8 * RB sign operands first (for a general r these are global loads: one wait for all).
         uint32_t off[8][RB];
-        if (!(PRE && use_pre)) {
+        if (!(PRE && use_pre) && !kValuSigns) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
 #pragma unroll
@@ -424,8 +436,21 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
             v[e] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                const u4 sg = (PRE && use_pre) ? pre[e]
-                                               : *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutp) + off[e][rb]);
+                u4 sg;
+                if (PRE && use_pre) {
+                    sg = pre[e];
+                } else if (kValuSigns) {
+                    if (R8) {
+                        const uint32_t word = bbuf[slot][0][e >> 2];
+                        sg = pm_one_from_bits(__builtin_amdgcn_perm(word, word, 0x00010001u * static_cast<uint32_t>(e & 3)));
+                    } else {
+                        const int hw = e * RB + rb;
+                        const uint32_t word = bbuf[slot][hw >> 3][(hw >> 1) & 3];
+                        sg = pm_one_from_bits(__builtin_amdgcn_perm(word, word, (hw & 1) ? sel_odd : sel_even));
+                    }
+                } else {
+                    sg = *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutp) + off[e][rb]);
+                }
                 v[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb], as_h8(sg), v[e], 0, 0, 0);
             }
         }
@@ -528,11 +553,11 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a, int 
 
 constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
 
-template <int RB, int TMV, int NW, int D1, bool OS, int BM>
-lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
+template <int RB, int TMV, int NW, int D1, bool OS, int BM, bool LP>
+lordba_status launch_mfma_lp(const FwdArgs& a, hipStream_t stream) {
     const size_t lds = mfma_lds_bytes(RB, TMV, NW, D1);
     if (lds > kMaxLds) return LORDBA_ERR_ALGO;
-    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, BM>;
+    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, BM, LP>;
     if (lds > 64 * 1024) {
         // Opt in to more than 64 KiB of dynamic LDS once per device and kernel; raising the limit is idempotent.
         static std::mutex mu;
@@ -552,6 +577,16 @@ lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
     const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(a.T) + TMV - 1) / TMV);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, stream, a);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
+}
+
+// LP only exists where sign operands are built ahead (one rank block, byte-aligned carrier rows); it pays once the grid
+// covers the chip, where the slowest wave at the first barrier sets the pace of the workgroup.
+template <int RB, int TMV, int NW, int D1, bool OS, int BM>
+lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
+    if constexpr (RB == 1 && BM != 0) {
+        if ((static_cast<int64_t>(a.T) + TMV - 1) / TMV >= 128) return launch_mfma_lp<RB, TMV, NW, D1, OS, BM, true>(a, stream);
+    }
+    return launch_mfma_lp<RB, TMV, NW, D1, OS, BM, false>(a, stream);
 }
 
 // Picks the x pipeline: one-shot when every wave's chunks fit the deepest pipeline that the register budget of the
