@@ -1,5 +1,5 @@
-"""CPU oracle for the LoRDBA adapter forward branch (Def. 1, Eq. (lordba),
-Eq. (adapter-mode-fwd), Eq. (lordba-fwd) of the paper).
+"""CPU oracle for the LoRDBA adapter forward branch (Def. 1, Eq. (lordba) with one or
+several scale envelopes, Eq. (adapter-mode-fwd), Eq. (lordba-fwd) of the paper).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke()`` and
 by the ``cpu_baseline`` leg of ``bench.py``.  The product package never imports
@@ -54,6 +54,8 @@ def _load():
         lib.lordba_oracle_forward.argtypes = [vp] * 8 + [i64] * 4 + [ci]
         lib.lordba_oracle_forward_packed.restype = ci
         lib.lordba_oracle_forward_packed.argtypes = [vp] * 8 + [i64] * 4 + [ci]
+        lib.lordba_oracle_forward_multi.restype = ci
+        lib.lordba_oracle_forward_multi.argtypes = [vp] * 8 + [i64] * 5 + [ci]
         _lib = lib
     return _lib
 
@@ -145,6 +147,36 @@ def forward(x, signsA, signsB, s_in, s_rank, s_out, y_base, nthreads: int = 1) -
                                        _ptr(yb), _ptr(y), T, d_in, d_out, r, int(nthreads))
     if st != 0:
         raise ValueError("oracle forward failed with status %d" % st)
+    return y
+
+
+def forward_multi(x, signsA, signsB, s_in, s_rank, s_out, y_base, nthreads: int = 1) -> np.ndarray:
+    """fp64 Y = Y_base + X sum_e diag(s_in[e]) S_A^T diag(s_rank[e]) S_B^T diag(s_out[e])  (Eq. (lordba), l >= 1).
+
+    s_in[ell,d_in], s_rank[ell,r], s_out[ell,d_out]: float16; the rest as in forward().
+    """
+    sA = _as(signsA, np.int8)
+    sB = _as(signsB, np.int8)
+    r, d_in = sA.shape
+    d_out = sB.shape[0]
+    if sB.shape != (d_out, r):
+        raise ValueError("signsB must be [d_out, r]")
+    si = _f16_bits(s_in)
+    if si.ndim != 2:
+        raise ValueError("s_in must be [ell, d_in]")
+    ell = si.shape[0]
+    si = _f16_bits(si, (ell, d_in))
+    sr = _f16_bits(s_rank, (ell, r))
+    so = _f16_bits(s_out, (ell, d_out))
+    xb = _f16_bits(x)
+    T = xb.shape[0]
+    xb = _f16_bits(xb, (T, d_in))
+    yb = _f16_bits(y_base, (T, d_out))
+    y = np.empty((T, d_out), dtype=np.float64)
+    st = _load().lordba_oracle_forward_multi(_ptr(xb), _ptr(sA), _ptr(sB), _ptr(si), _ptr(sr), _ptr(so),
+                                             _ptr(yb), _ptr(y), T, d_in, d_out, r, ell, int(nthreads))
+    if st != 0:
+        raise ValueError("oracle forward_multi failed with status %d" % st)
     return y
 
 

@@ -25,8 +25,12 @@
  * tiny shapes, numpy fp64 GEMM special case, closed forms (all-ones, rank-1,
  * unit-vector rows), invariants (zero scales, sign gauge, linearity), the
  * plus-set/minus-set form of Eq. (sign-accum), the 65536-entry fp16 table
- * against numpy, and hand-written packed words.  No function here is
- * "parity unpinned".
+ * against numpy, and hand-written packed words.  The multi-envelope forward
+ * (Eq. (lordba) with l >= 1) is pinned by the dense DeltaW built term by term
+ * in exact rationals and in numpy, by its reduction to the one-envelope
+ * function, by the zero-beta envelope that must change nothing (Sec. 3.2,
+ * initialisation of additional envelopes), and by additivity over envelopes.
+ * No function here is "parity unpinned".
  */
 #include <math.h>
 #include <pthread.h>
@@ -223,4 +227,109 @@ int lordba_oracle_forward_packed(const uint16_t *x, const uint32_t *packedA, con
     int st = lordba_oracle_forward(x, sA, sB, s_in, s_rank, s_out, y_base, y, T, d_in, d_out, r, nthreads);
     free(sA); free(sB);
     return st;
+}
+
+/* ------------------------------------------------- multi-envelope forward ---- */
+
+/* Def. 1 / Eq. (lordba) with envelope rank l >= 1: the carriers B1, B2 are shared and
+ *   DeltaW = sum_{e=1..l} diag(alpha_e) B1 diag(beta_e) B2 diag(gamma_e),
+ *   Y = Y_base + X DeltaW                                 (Eq. adapter-mode-fwd).
+ * One token row: each envelope is staged as in Eq. (lordba-fwd) and added to the
+ * row in envelope order, y = ((y_base + delta_1) + delta_2) + ...
+ * alpha is [l, d_in], beta [l, r], gamma [l, d_out], row-major. */
+static void forward_row_multi(const uint16_t *x_row, const int8_t *sA, const int8_t *sB,
+                              const double *alpha, const double *beta, const double *gamma,
+                              const uint16_t *ybase_row, double *y_row,
+                              int64_t d_in, int64_t d_out, int64_t r, int64_t ell,
+                              double *w, double *u)
+{
+    for (int64_t j = 0; j < d_out; ++j)
+        y_row[j] = lordba_oracle_f16_to_f64(ybase_row[j]);
+    for (int64_t e = 0; e < ell; ++e) {
+        const double *al = alpha + e * d_in, *be = beta + e * r, *ga = gamma + e * d_out;
+        for (int64_t i = 0; i < d_in; ++i)
+            w[i] = lordba_oracle_f16_to_f64(x_row[i]) * al[i];
+        for (int64_t k = 0; k < r; ++k) {
+            double t = 0.0;
+            for (int64_t i = 0; i < d_in; ++i)
+                t += w[i] * (double)sA[k * d_in + i];
+            u[k] = t * be[k];
+        }
+        for (int64_t j = 0; j < d_out; ++j) {
+            double v = 0.0;
+            for (int64_t k = 0; k < r; ++k)
+                v += u[k] * (double)sB[j * r + k];
+            y_row[j] += v * ga[j];
+        }
+    }
+}
+
+typedef struct {
+    row_job base;
+    int64_t ell;
+} row_job_multi;
+
+static void *row_worker_multi(void *arg)
+{
+    row_job_multi *jm = (row_job_multi *)arg;
+    row_job *jb = &jm->base;
+    double *w = (double *)malloc(sizeof(double) * (size_t)(jb->d_in > 0 ? jb->d_in : 1));
+    double *u = (double *)malloc(sizeof(double) * (size_t)(jb->r > 0 ? jb->r : 1));
+    if (!w || !u) { jb->status = 9; free(w); free(u); return NULL; }
+    for (int64_t t = jb->t0; t < jb->t1; ++t)
+        forward_row_multi(jb->x + t * jb->d_in, jb->sA, jb->sB, jb->alpha, jb->beta, jb->gamma,
+                          jb->y_base + t * jb->d_out, jb->y + t * jb->d_out,
+                          jb->d_in, jb->d_out, jb->r, jm->ell, w, u);
+    free(w); free(u);
+    jb->status = 0;
+    return NULL;
+}
+
+/* As lordba_oracle_forward, with s_in[ell, d_in], s_rank[ell, r], s_out[ell, d_out] (fp16 bit
+ * patterns, row-major) and ell >= 1 envelopes over the same carriers. */
+int lordba_oracle_forward_multi(const uint16_t *x, const int8_t *signsA, const int8_t *signsB,
+                                const uint16_t *s_in, const uint16_t *s_rank, const uint16_t *s_out,
+                                const uint16_t *y_base, double *y,
+                                int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, int nthreads)
+{
+    if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || ell < 1) return 2;
+    for (int64_t n = 0; n < r * d_in; ++n) if (signsA[n] != 1 && signsA[n] != -1) return 3;
+    for (int64_t n = 0; n < d_out * r; ++n) if (signsB[n] != 1 && signsB[n] != -1) return 3;
+    if (T == 0) return 0;
+
+    double *alpha = (double *)malloc(sizeof(double) * (size_t)(ell * d_in));
+    double *beta = (double *)malloc(sizeof(double) * (size_t)(ell * r));
+    double *gamma = (double *)malloc(sizeof(double) * (size_t)(ell * d_out));
+    if (!alpha || !beta || !gamma) { free(alpha); free(beta); free(gamma); return 9; }
+    lordba_oracle_f16_array_to_f64(s_in, alpha, ell * d_in);
+    lordba_oracle_f16_array_to_f64(s_rank, beta, ell * r);
+    lordba_oracle_f16_array_to_f64(s_out, gamma, ell * d_out);
+
+    if (nthreads < 1) nthreads = 1;
+    if ((int64_t)nthreads > T) nthreads = (int)T;
+    row_job_multi *jobs = (row_job_multi *)calloc((size_t)nthreads, sizeof(row_job_multi));
+    pthread_t *tids = (pthread_t *)calloc((size_t)nthreads, sizeof(pthread_t));
+    int status = 0;
+    if (!jobs || !tids) { status = 9; goto done; }
+    for (int i = 0; i < nthreads; ++i) {
+        row_job *jb = &jobs[i].base;
+        jb->x = x; jb->sA = signsA; jb->sB = signsB;
+        jb->alpha = alpha; jb->beta = beta; jb->gamma = gamma;
+        jb->y_base = y_base; jb->y = y;
+        jb->t0 = T * i / nthreads; jb->t1 = T * (i + 1) / nthreads;
+        jb->d_in = d_in; jb->d_out = d_out; jb->r = r; jb->status = 0;
+        jobs[i].ell = ell;
+    }
+    if (nthreads == 1) {
+        row_worker_multi(&jobs[0]);
+    } else {
+        for (int i = 0; i < nthreads; ++i)
+            if (pthread_create(&tids[i], NULL, row_worker_multi, &jobs[i]) != 0) { tids[i] = 0; row_worker_multi(&jobs[i]); }
+        for (int i = 0; i < nthreads; ++i)
+            if (tids[i]) pthread_join(tids[i], NULL);
+    }
+    for (int i = 0; i < nthreads; ++i) if (jobs[i].base.status) status = jobs[i].base.status;
+done:
+    free(jobs); free(tids); free(alpha); free(beta); free(gamma);
+    return status;
 }

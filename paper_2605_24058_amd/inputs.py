@@ -37,6 +37,14 @@ class Shape:
         """x + y_base + y_out + packed carriers + three fp16 scale vectors."""
         return self.activation_bytes() + self.adapter_bytes()
 
+    def adapter_bytes_multi(self, ell: int) -> int:
+        """Packed carriers (shared by all envelopes) + ell triples of fp16 scale vectors."""
+        bits = self.r * (self.d_in + self.d_out)
+        return (bits + 7) // 8 + 2 * ell * (self.d_in + self.r + self.d_out)
+
+    def algorithmic_bytes_multi(self, ell: int) -> int:
+        return self.activation_bytes() + self.adapter_bytes_multi(ell)
+
     def sign_macs(self) -> int:
         return self.T * self.r * (self.d_in + self.d_out)
 
@@ -72,6 +80,30 @@ def make_adapter(seed: int, d_in: int, d_out: int, r: int) -> Dict[str, np.ndarr
 
     return {"signsA": signsA, "signsB": signsB,
             "s_in": lognormal(d_in), "s_rank": lognormal(r), "s_out": lognormal(d_out)}
+
+
+def make_envelopes(seed: int, d_in: int, d_out: int, r: int, ell: int) -> Dict[str, np.ndarray]:
+    """Scale vectors of ell envelopes over the carriers of make_adapter(seed, ...): s_in [ell, d_in], s_rank [ell, r],
+    s_out [ell, d_out].  Envelope 0 is the adapter's own triple; each further envelope draws the same lognormal
+    magnitudes from its own stream and gives every rank-scale entry a random sign (envelopes are real-valued and
+    may cancel one another)."""
+    base = make_adapter(seed, d_in, d_out, r)
+    s_in, s_rank, s_out = [base["s_in"]], [base["s_rank"]], [base["s_out"]]
+    for e in range(1, ell):
+        g = _rng(seed, 3, e)
+        ln = lambda n: np.exp(-3.0 + 0.5 * g.standard_normal(n))
+        flip = g.integers(0, 2, size=r) * 2 - 1
+        s_in.append(ln(d_in).astype(np.float16))
+        s_rank.append((ln(r) * flip).astype(np.float16))
+        s_out.append(ln(d_out).astype(np.float16))
+    return {"s_in": np.stack(s_in), "s_rank": np.stack(s_rank), "s_out": np.stack(s_out)}
+
+
+def make_inputs_multi(seed: int, T: int, d_in: int, d_out: int, r: int, ell: int) -> Dict[str, np.ndarray]:
+    """All tensors of one multi-envelope call: carriers and activations as make_inputs, scales as make_envelopes."""
+    out = make_inputs(seed, T, d_in, d_out, r)
+    out.update(make_envelopes(seed, d_in, d_out, r, ell))
+    return out
 
 
 def make_activations(seed: int, T: int, d_in: int, d_out: int) -> Dict[str, np.ndarray]:
