@@ -49,6 +49,7 @@ enum {
 };
 
 #define LORDBA_MAX_RANK 64
+#define LORDBA_MAX_ENVELOPES 4
 
 /* Number of uint32 words of a packed [rows, cols] sign matrix: ceil(rows * cols / 32).
  * Returns 0 if rows or cols is negative. */
@@ -111,6 +112,29 @@ lordba_status lordba_forward_algo(const void* x, const uint32_t* packedA, const 
                                   const void* y_base, void* y_out,
                                   int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream,
                                   int algo);
+
+/* DEVICE function: the forward branch of an adapter with `ell` scale envelopes over the same carriers
+ * (Def. 1 / Eq. (lordba) with envelope rank l = ell; Sec. 3.3: the packed carriers are stored once and
+ * shared by all envelopes):
+ *   y_out[t, j] = y_base[t, j] + sum_{e < ell} s_out[e, j] * sum_k S_B[j, k] * s_rank[e, k] * sum_i S_A[k, i] * s_in[e, i] * x[t, i]
+ * Arguments as lordba_forward, except
+ *   s_in  : fp16 [ell, d_in]     s_rank: fp16 [ell, r]     s_out : fp16 [ell, d_out]     (row-major, contiguous)
+ *   1 <= ell <= LORDBA_MAX_ENVELOPES; anything else -> LORDBA_ERR_DIM.  ell == 1 is lordba_forward.
+ * x and y_base are read once and y_out written once whatever ell is; the envelopes are accumulated in
+ * fp32 in their order and the sum is rounded once to fp16.  Same error bound, aliasing rules, stream
+ * semantics (enqueue only, no allocation, no workspace) and error codes as lordba_forward. */
+lordba_status lordba_forward_multi(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                   const void* s_in, const void* s_rank, const void* s_out,
+                                   const void* y_base, void* y_out,
+                                   int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream);
+
+/* Same with the kernel chosen by the caller: LORDBA_ALGO_AUTO, _GENERAL, _MFMA_T8 or _MFMA_T16 (for ell >= 2 the
+ * matrix-core kernel always runs 8 waves per workgroup; the tuning values 4..7 exist for ell == 1 only). */
+lordba_status lordba_forward_multi_algo(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                        const void* s_in, const void* s_rank, const void* s_out,
+                                        const void* y_base, void* y_out,
+                                        int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell,
+                                        void* stream, int algo);
 
 /* Static, never-NULL description of a status code. */
 const char* lordba_status_string(lordba_status status);

@@ -18,7 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
 _LIB_PATH = os.path.join(_PKG, "liblordba.so")
-_SOURCES = ("lordba_forward.hip", "lordba_pack.cpp")
+_SOURCES = ("lordba_forward.hip", "lordba_forward_multi.hip", "lordba_pack.cpp")
 _lib = None
 
 ALGO_AUTO, ALGO_GENERAL, ALGO_MFMA_T8, ALGO_MFMA_T16 = 0, 1, 2, 3
@@ -35,20 +35,37 @@ class LordbaError(RuntimeError):
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU)."""
+    """Compile the HIP library for gfx950 with hipcc (cross-compiles without a GPU).  The translation units are
+    compiled side by side (the kernel templates take most of the time), then linked."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = _LIB_PATH + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(_ROOT, "include")] + \
-          [os.path.join(_CSRC, s) for s in _SOURCES] + ["-o", tmp]
-    if verbose:
-        print(" ".join(cmd), file=sys.stderr)
-    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in proc.stdout.splitlines() if "not a recognized feature for this target" not in l)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out, file=sys.stderr)
-    os.replace(tmp, _LIB_PATH)
+    tag = ".tmp.%d" % os.getpid()
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    objs, procs = [], []
+    for src in _SOURCES:
+        obj = os.path.join(_PKG, src + tag + ".o")
+        cmd = [hipcc] + flags + ["-I", os.path.join(_ROOT, "include"), "-c", os.path.join(_CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), file=sys.stderr)
+        objs.append(obj)
+        procs.append(subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True))
+    outs = [p.communicate()[0] for p in procs]
+    tmp = _LIB_PATH + tag
+    try:
+        for p, out in zip(procs, outs):
+            out = "\n".join(l for l in out.splitlines() if "not a recognized feature for this target" not in l)
+            if p.returncode != 0:
+                raise RuntimeError("hipcc failed:\n" + out)
+            if verbose and out.strip():
+                print(out, file=sys.stderr)
+        link = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp],
+                              stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if link.returncode != 0:
+            raise RuntimeError("link failed:\n" + link.stdout)
+        os.replace(tmp, _LIB_PATH)
+    finally:
+        for f in objs + [tmp]:
+            if os.path.exists(f):
+                os.remove(f)
     return _LIB_PATH
 
 
@@ -107,6 +124,10 @@ def load_library():
     lib.lordba_forward.argtypes = [vp] * 8 + [i64] * 4 + [vp]
     lib.lordba_forward_algo.restype = ci
     lib.lordba_forward_algo.argtypes = [vp] * 8 + [i64] * 4 + [vp, ci]
+    for name, extra in (("lordba_forward_multi", [vp]), ("lordba_forward_multi_algo", [vp, ci])):
+        f = getattr(lib, name)      # AttributeError if the library was built from older sources: rebuild it
+        f.restype = ci
+        f.argtypes = [vp] * 8 + [i64] * 5 + extra
     lib.lordba_status_string.restype = ctypes.c_char_p
     lib.lordba_status_string.argtypes = [ci]
     _lib = lib
@@ -200,6 +221,49 @@ def lordba_forward(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out=None,
                                  T, d_in, d_out, r, ctypes.c_void_p(stream), int(algo))
     if st != 0:
         raise LordbaError(st, "lordba_forward")
+    return y_out
+
+
+def lordba_forward_multi(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out=None, stream=None,
+                         algo: int = ALGO_AUTO, check: bool = True):
+    """y_out = y_base + the branch of an adapter with ell scale envelopes over the same carriers, on the GPU.
+    As lordba_forward, with s_in [ell, d_in], s_rank [ell, r], s_out [ell, d_out] (float16, contiguous)."""
+    import torch
+
+    lib = load_library()
+    if check:
+        for name, t_ in (("x", x), ("s_in", s_in), ("s_rank", s_rank), ("s_out", s_out), ("y_base", y_base)):
+            if t_.dtype != torch.float16 or not t_.is_cuda or not t_.is_contiguous():
+                raise TypeError("%s must be a contiguous float16 CUDA tensor" % name)
+        for name, t_ in (("packedA", packedA), ("packedB", packedB)):
+            if t_.dtype != torch.int32 or not t_.is_cuda or not t_.is_contiguous():
+                raise TypeError("%s must be a contiguous int32 CUDA tensor holding the packed words" % name)
+        if x.dim() != 2 or y_base.dim() != 2 or x.shape[0] != y_base.shape[0]:
+            raise ValueError("x must be [T, d_in] and y_base [T, d_out]")
+        if s_in.dim() != 2 or s_rank.dim() != 2 or s_out.dim() != 2:
+            raise ValueError("s_in, s_rank, s_out must be [ell, d_in], [ell, r], [ell, d_out]")
+    T, d_in = x.shape
+    d_out = y_base.shape[1]
+    ell, r = s_rank.shape
+    if check:
+        if tuple(s_in.shape) != (ell, d_in) or tuple(s_out.shape) != (ell, d_out):
+            raise ValueError("scale array shapes do not match x / y_base / ell")
+        if packedA.numel() != (r * d_in + 31) // 32 or packedB.numel() != (d_out * r + 31) // 32:
+            raise ValueError("packed carrier lengths do not match the shape")
+    if y_out is None:
+        y_out = torch.empty_like(y_base)
+    elif check and (y_out.dtype != torch.float16 or not y_out.is_cuda or not y_out.is_contiguous()
+                    or y_out.shape != y_base.shape):
+        raise TypeError("y_out must be a contiguous float16 CUDA tensor shaped like y_base")
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    st = lib.lordba_forward_multi_algo(x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(),
+                                       s_rank.data_ptr(), s_out.data_ptr(), y_base.data_ptr(), y_out.data_ptr(),
+                                       T, d_in, d_out, r, ell, ctypes.c_void_p(stream), int(algo))
+    if st != 0:
+        raise LordbaError(st, "lordba_forward_multi")
     return y_out
 
 

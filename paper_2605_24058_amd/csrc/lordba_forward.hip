@@ -1,734 +1,18 @@
-// LoRDBA adapter forward branch for MI355X (gfx950, wave64, MFMA):
-//
-//   y_out[t,j] = y_base[t,j] + s_out[j] * sum_k S_B[j,k] * s_rank[k] * sum_i S_A[k,i] * s_in[i] * x[t,i]
-//
-// (Def. 1 / Eq. (lordba) with l = 1, Eq. (adapter-mode-fwd), evaluation order of Eq. (lordba-fwd).)
-//
-// Token rows are independent, so one workgroup owns a tile of token rows from the first load of x to
-// the last store of y_out and no workgroup ever waits for another: there is no split over d_in across
-// workgroups, no partial-sum workspace and no second launch.
-//
-// Matrix-core kernel (lordba_fwd_mfma_kernel), per workgroup of NW waves and TMV token rows:
-//   stage 1  t[tok, k] = sum_i x[tok,i] * (+-s_in[i]).  The 128-column chunks of d_in are dealt round-robin
-//            to the waves.  A wave reads its chunk of x with row-contiguous 16-byte loads, transposes it
-//            through a wave-private LDS tile into the MFMA operand layout, builds the other operand
-//            (+-s_in as fp16: s_in with its sign bit XORed with the carrier bit, so the product with x is
-//            exact in fp32) with a few vector-ALU bit operations from one dword of carrier bits per lane, and
-//            issues v_mfma_f32_16x16x32_f16.  No workgroup barrier is involved: a wave starts as soon as its
-//            own data is there.  The partial tiles of the waves are summed through LDS in a fixed order.
-//   stage 2  u = s_rank * t in fp32; each token row of u is scaled by a power of two so that its largest
-//            entry is in [2^13, 2^14) and split into fp16 hi + fp16 lo (22 significant bits, no overflow or
-//            underflow whatever the magnitude of the scales); hi and lo fill the K = 32 slots of one MFMA
-//            per 16 ranks.
-//   stage 3  v[tok, j] = sum_k u[tok,k] * (+-1), 8 MFMAs per 128 output columns, arranged so that each lane
-//            ends up with 8 consecutive output columns of its token rows: y_base is read and y_out written
-//            with row-contiguous 16-byte accesses, y_out = fp16_rne(y_base + s_out * v * 2^-scale).  The +-1
-//            operands come from a 256-entry LDS table (8 carrier bits -> 8 fp16); those of a wave's first
-//            block are built with the vector ALU while the wave waits for the others to finish stage 1.
-//
-// General kernel (lordba_fwd_general_kernel): plain vector-ALU code, one workgroup per token row, any
-// shape and alignment; also the fallback when the LDS need of the matrix-core kernel exceeds the CU.
-#include <hip/hip_runtime.h>
-#include <stdint.h>
-
-#include <mutex>
-
-#include "lordba.h"
-
-namespace {
-
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-
-#ifndef LORDBA_VALU_SIGNS
-#define LORDBA_VALU_SIGNS 0
-#endif
-constexpr int kXRow = 136;  // halves per row of the x transpose tile: 128 columns + 8 pad -> conflict-free b128 reads
-constexpr int kURow = 40;   // halves per row of the u tile: 32 slots + 8 pad
-constexpr int kLutBytes = 256 * 16;
-
-__device__ __forceinline__ u4 load16(const void* p) { return *reinterpret_cast<const u4*>(p); }
-__device__ __forceinline__ void store16(void* p, u4 v) { *reinterpret_cast<u4*>(p) = v; }
-// Streaming accesses for x, y_base and y_out: each byte is touched once, so it should not displace the adapter
-// (carrier bits, scales) from the caches.
-__device__ __forceinline__ u4 load16_stream(const void* p) { return __builtin_nontemporal_load(reinterpret_cast<const u4*>(p)); }
-__device__ __forceinline__ void store16_stream(void* p, u4 v) { __builtin_nontemporal_store(v, reinterpret_cast<u4*>(p)); }
-// Address = uniform base (kept in scalar registers) + unsigned 32-bit byte offset per lane: one add-free addressing
-// mode, no 64-bit vector arithmetic.
-__device__ __forceinline__ const void* at(const void* base, uint32_t byte_off) { return static_cast<const char*>(base) + byte_off; }
-__device__ __forceinline__ void* at(void* base, uint32_t byte_off) { return static_cast<char*>(base) + byte_off; }
-__device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
-// Value of the lane N places further along its row of 16 lanes (rotation inside the row, a DPP move: no LDS traffic).
-template <int N>
-__device__ __forceinline__ float row_rotate(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
-}
-__device__ __forceinline__ float row_max16(float v) {
-    v = fmaxf(v, row_rotate<8>(v));
-    v = fmaxf(v, row_rotate<4>(v));
-    v = fmaxf(v, row_rotate<2>(v));
-    return fmaxf(v, row_rotate<1>(v));
-}
-__device__ __forceinline__ float flip(float v, uint32_t bit) { return __uint_as_float(__float_as_uint(v) ^ (bit << 31)); }
-
-// Row of the MFMA token operand -> token row of the tile.  With 16 token rows it is the identity.  With 8, MFMA
-// rows 4q+0 and 4q+1 carry token rows 2q and 2q+1 and rows 4q+2, 4q+3 repeat them (their results are ignored), so
-// that in the accumulator layout (lane = column, registers = rows 4q..4q+3) every lane owns two live token rows.
-template <int TMV>
-__device__ __forceinline__ int tile_row_of_mfma_row(int m) { return TMV == 16 ? m : ((m >> 2) * 2 + (m & 1)); }
-
-struct FwdArgs {
-    const _Float16* x;
-    const uint32_t* pA;
-    const uint32_t* pB;
-    const _Float16* s_in;
-    const _Float16* s_rank;
-    const _Float16* s_out;
-    const _Float16* y_base;
-    _Float16* y_out;
-    int T, d_in, d_out, r;
-};
-
-// 8 carrier bits starting at bit `bit0` of a packed stream of `nwords` words.  Both words are always read from a
-// clamped, valid index (no branch, no access past the end); bits past the end of the stream are not meaningful and
-// the callers only use them for padded ranks, whose other operand is zero.
-__device__ __forceinline__ uint32_t fetch8(const uint32_t* __restrict__ words, int64_t bit0, int64_t nwords) {
-    int64_t w = bit0 >> 5;
-    w = w < nwords ? w : nwords - 1;
-    const int64_t w1 = (w + 1) < nwords ? w + 1 : nwords - 1;
-    const uint32_t lo = words[w], hi = words[w1];
-    return static_cast<uint32_t>(((static_cast<uint64_t>(hi) << 32) | lo) >> (bit0 & 31)) & 0xffu;
-}
-
-constexpr int kUBytes = 16 * kURow * 2;  // one rank block of the u tile
-
-// LDS bytes of the matrix-core kernel (host and device use the same formula).
-__host__ __device__ constexpr size_t mfma_lds_bytes(int RB, int TMV, int NW, int D1) {
-    return kLutBytes + static_cast<size_t>(NW) * D1 * 256 + static_cast<size_t>(NW) * TMV * kXRow * 2 +
-           static_cast<size_t>(NW) * RB * 1024 + static_cast<size_t>(RB) * kUBytes + 64;
-}
-
-typedef uint16_t us2 __attribute__((ext_vector_type(2)));
-
-// Sign masks of one operand dword from a word whose two 16-bit halves both hold the 8 carrier bits of the lane in
-// their low byte: bit 2i goes to the sign of the low fp16, bit 2i+1 to the sign of the high fp16.  The packed 16-bit
-// shift drops everything above the wanted bit; the bits below it are removed by the caller's mask.
-template <int I>
-__device__ __forceinline__ uint32_t spread_pair(uint32_t both) {
-    const us2 sh = {static_cast<uint16_t>(15 - 2 * I), static_cast<uint16_t>(14 - 2 * I)};
-    return __builtin_bit_cast(uint32_t, static_cast<us2>(__builtin_bit_cast(us2, both) << sh));
-}
-// 8 carrier bits -> 8 fp16 values +-1.0 (bit set = -1.0), with vector ALU only.
-__device__ __forceinline__ u4 pm_one_from_bits(uint32_t both) {
-    // (shifted & sign bits) | 1.0 in one three-input bit operation (truth table 0xEA = (a & b) | c)
-    u4 f;
-    f[0] = __builtin_amdgcn_bitop3_b32(spread_pair<0>(both), 0x80008000u, 0x3C003C00u, 0xEA);
-    f[1] = __builtin_amdgcn_bitop3_b32(spread_pair<1>(both), 0x80008000u, 0x3C003C00u, 0xEA);
-    f[2] = __builtin_amdgcn_bitop3_b32(spread_pair<2>(both), 0x80008000u, 0x3C003C00u, 0xEA);
-    f[3] = __builtin_amdgcn_bitop3_b32(spread_pair<3>(both), 0x80008000u, 0x3C003C00u, 0xEA);
-    return f;
-}
-// 8 fp16 values with the sign of element e flipped where carrier bit e is set.
-__device__ __forceinline__ u4 flip_by_bits(u4 v, uint32_t both) {
-    v[0] ^= spread_pair<0>(both) & 0x80008000u;
-    v[1] ^= spread_pair<1>(both) & 0x80008000u;
-    v[2] ^= spread_pair<2>(both) & 0x80008000u;
-    v[3] ^= spread_pair<3>(both) & 0x80008000u;
-    return v;
-}
-
-// y = fp16(v * s + b) for two neighbouring outputs: s and b are fp16 pairs, v0/v1 fp32.  Written so that the compiler
-// selects the mixed-precision FMA (v_fma_mixlo/mixhi_f16: fp16 operands read directly, fp32 arithmetic, one rounding to
-// fp16).  Deliberately not inline assembly: the compiler reuses dead accumulator registers of an MFMA that is still in
-// flight, and it inserts the wait states such a write needs only for instructions it can see.
-__device__ __forceinline__ uint32_t scale_add_pair(float v0, float v1, uint32_t s_pair, uint32_t b_pair) {
-    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-    const h2 s = __builtin_bit_cast(h2, s_pair), b = __builtin_bit_cast(h2, b_pair);
-    h2 o;
-    o[0] = static_cast<_Float16>(__builtin_fmaf(v0, static_cast<float>(s[0]), static_cast<float>(b[0])));
-    o[1] = static_cast<_Float16>(__builtin_fmaf(v1, static_cast<float>(s[1]), static_cast<float>(b[1])));
-    return __builtin_bit_cast(uint32_t, o);
-}
-
-// RB   rank blocks of 16 (r <= 16 * RB)
-// TMV  token rows per workgroup (8 or 16)
-// NW   waves per workgroup (>= 4)
-// D1   128-column chunks of x a wave keeps in flight
-// OS   "one shot": every wave's chunks fit in D1, so stage 1 is straight-line code; otherwise stage 1 loops over
-//      groups of D1 chunks
-// BM   how a lane fetches the sign(B) bits of its 8 output columns: 1 = r is a multiple of 16 (RB aligned 16-byte
-//      loads), 2 = r is 8 (one aligned 8-byte load, one byte per column), 0 = any r (two dwords per operand)
-// LP   the waves that do not run stage 2 build their first block's sign operands during stage 2 instead of before it
-template <int RB, int TMV, int NW, int D1, bool OS, int BM, bool LP>
-__global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
-    static_assert(NW >= 4, "stage 2 is spread over the first four waves");
-    constexpr int NI = TMV / 4;           // 16-byte row accesses per lane per 128-column block of a tile
-    constexpr int D2 = 2;                 // y_base column blocks in flight per wave
-    constexpr bool R16 = BM == 1, R8 = BM == 2;
-    static_assert(!R8 || RB == 1, "r = 8 is one rank block");
-    constexpr bool PRE = (R16 || R8) && RB == 1;  // sign operands of the first block are built before u is known
-    constexpr bool kValuSigns = (R16 || R8) && LORDBA_VALU_SIGNS;  // stage 3 builds every sign operand with the vector ALU
-
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 15, q = lane >> 4;
-    const int T = a.T, d_in = a.d_in, d_out = a.d_out, r = a.r;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
-    const int nchunks = (d_in + 127) >> 7;
-
-    u4* lutp = reinterpret_cast<u4*>(smem);  // 8 bits -> 8 fp16 values +-1.0
-    unsigned char* p = smem + kLutBytes;
-    _Float16* sinw = reinterpret_cast<_Float16*>(p) + wave * D1 * 128;  // wave-private s_in slices, one per chunk slot
-    p += NW * D1 * 256;
-    _Float16* xs = reinterpret_cast<_Float16*>(p) + wave * TMV * kXRow;  // wave-private x transpose tile
-    p += NW * TMV * kXRow * 2;
-    float* red = reinterpret_cast<float*>(p);
-    p += NW * RB * 1024;
-    _Float16* us = reinterpret_cast<_Float16*>(p);
-    p += RB * kUBytes;
-    float* invs = reinterpret_cast<float*>(p);
-
-    // The CU's vector memory pipeline takes a bounded number of outstanding requests and returns data in request
-    // order, so loads are issued in the order their data is needed: s_rank, then per chunk s_in and x, and y_base only
-    // after the wave has consumed its x (an earlier request would sit in front of other waves' x).
-    // A tile never spans more than 16 rows of at most 2^24 columns, so offsets inside it fit 32 bits.
-    const int last = static_cast<int>(T - 1 - t0 < TMV - 1 ? T - 1 - t0 : TMV - 1);  // last live row of the tile
-    const _Float16* xt = a.x + t0 * d_in;
-    const _Float16* ybt = a.y_base + t0 * d_out;
-    _Float16* yot = a.y_out + t0 * d_out;
-
-    // ---------------------------------------------------------------- stage 1 loads -----------------
-    // Chunk c = 128 columns of d_in; wave w owns chunks w, w + NW, ...  x: lane (row q + 4m, 16-byte column group li)
-    // -> 256 contiguous bytes per row and quarter-wave.  s_in: the chunk's 256 bytes, one dword per lane.  Carrier
-    // bits: lane (rank li, dword q of the chunk) holds the 32 bits of its rank for columns 32q..32q+31 of the chunk;
-    // byte s of that dword belongs to MFMA step s.
-    const int my_n = wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0;
-    const int words_per_row = d_in >> 5;  // d_in % 32 == 0 on this path
-    u4 xbuf[D1][NI];
-    uint32_t sinbuf[D1];
-    uint32_t abits[D1][RB];
-
-    auto issue_x = [&](int slot, int n) {
-        int c = wave + NW * n;
-        c = c < nchunks ? c : nchunks - 1;  // past the end: re-read a valid chunk, the result is not used
-        {
-            const int pair = c * 64 + lane;  // fp16 pair index; d_in is even, so a pair is inside or outside as a whole
-            const uint32_t v = *static_cast<const uint32_t*>(at(a.s_in, static_cast<uint32_t>(pair * 2 < d_in ? pair : 0) * 4u));
-            sinbuf[slot] = pair * 2 < d_in ? v : 0u;  // columns past d_in get scale 0
-        }
-#pragma unroll
-        for (int m = 0; m < NI; ++m) {
-            int row = m * 4 + q;
-            row = row < last ? row : last;
-            int col = c * 128 + li * 8;
-            col = col < d_in ? col : d_in - 8;
-            xbuf[slot][m] = load16_stream(at(xt, static_cast<uint32_t>(row * d_in + col) * 2u));
-        }
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            int rk = rb * 16 + li;
-            rk = rk < r ? rk : r - 1;
-            int w = c * 4 + q;
-            w = w < words_per_row ? w : words_per_row - 1;  // columns past d_in meet s_in = 0
-            abits[slot][rb] = *static_cast<const uint32_t*>(at(a.pA, static_cast<uint32_t>(rk * words_per_row + w) * 4u));
-        }
-    };
-#pragma unroll
-    for (int slot = 0; slot < D1; ++slot) issue_x(slot, slot);
-    __builtin_amdgcn_sched_barrier(0);  // keep the issue order: nothing below may be hoisted above these requests
-    float sr[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int rk = rb * 16 + li;
-        const _Float16 h = *static_cast<const _Float16*>(at(a.s_rank, static_cast<uint32_t>(rk < r ? rk : r - 1) * 2u));
-        sr[rb] = rk < r ? static_cast<float>(h) : 0.f;
-    }
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---------------------------------------------------------------- stage 3 loads (issued later) ---
-    // Block b = 128 output columns; wave w owns blocks w, w + NW, ...; lane (li, q) owns columns 8 li .. 8 li + 7 of
-    // the block for its token rows.
-    const int nblk = (d_out + 127) >> 7;
-    const int my_b = wave < nblk ? (nblk - wave + NW - 1) / NW : 0;
-    const int64_t nwordsB = (static_cast<int64_t>(d_out) * r + 31) >> 5;
-    u4 ybuf[D2][NI];
-    u4 sobuf[D2];
-    u4 bbuf[D2][R16 ? RB : 1];
-
-    auto issue_y = [&](int slot, int n) {
-        int b = wave + NW * n;
-        b = b < nblk ? b : nblk - 1;
-        int j0 = b * 128 + li * 8;
-        j0 = j0 < d_out ? j0 : d_out - 8;
-        if (R16) {  // 8 rows of r bits = RB * 16 contiguous, 16-byte aligned bytes
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) bbuf[slot][rb] = load16(at(a.pB, static_cast<uint32_t>(j0 * (r >> 3) + rb * 16)));
-        }
-        if (R8) {  // 8 rows of 8 bits: one aligned 8-byte load, byte e is column e
-            const uint2 w = *static_cast<const uint2*>(at(a.pB, static_cast<uint32_t>(j0)));
-            bbuf[slot][0] = u4{w.x, w.y, 0u, 0u};
-        }
-        sobuf[slot] = load16(at(a.s_out, static_cast<uint32_t>(j0) * 2u));
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            int row = TMV == 16 ? q * 4 + i : q * 2 + i;
-            row = row < last ? row : last;
-            ybuf[slot][i] = load16_stream(at(ybt, static_cast<uint32_t>(row * d_out + j0) * 2u));
-        }
-    };
-
-    // ---------------------------------------------------------------- stage 0: +-1 table -------------
-    // Only used after the barriers of stage 2, which also make it visible.
-    for (int e = tid; e < 256; e += NW * 64) lutp[e] = pm_one_from_bits(static_cast<uint32_t>(e) * 0x10001u);
-
-    // ---------------------------------------------------------------- stage 1: sign(A) reduction ---
-    // Every wave works on wave-private LDS as soon as its own data has arrived.  The barrier waits for no data: it only
-    // keeps the fast waves from requesting y_base before the slow ones (held back by the bounded request queue) have
-    // requested their x.
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    f4 acc[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
-
-    auto consume_x = [&](int slot) {
-        _Float16* sw = sinw + slot * 128;
-        reinterpret_cast<uint32_t*>(sw)[lane] = sinbuf[slot];
-#pragma unroll
-        for (int m = 0; m < NI; ++m) store16(xs + (m * 4 + q) * kXRow + li * 8, xbuf[slot][m]);
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const h8 xf = as_h8(load16(xs + tile_row_of_mfma_row<TMV>(li) * kXRow + q * 32 + s * 8));
-            const u4 sv = load16(sw + q * 32 + s * 8);
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                // byte s of the lane's carrier dword into the low byte of both halves (the other bytes are shifted out)
-                const uint32_t both = __builtin_amdgcn_perm(abits[slot][rb], abits[slot][rb], 0x00010001u * s);
-                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf, as_h8(flip_by_bits(sv, both)), acc[rb], 0, 0, 0);
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-    };
-
-    if (OS) {
-#pragma unroll
-        for (int slot = 0; slot < D1; ++slot)
-            if (slot < my_n) consume_x(slot);
-    } else {
-        const int ngroups = (my_n + D1 - 1) / D1;
-        for (int g = 0; g + 1 < ngroups; ++g) {
-#pragma unroll
-            for (int slot = 0; slot < D1; ++slot) {
-                consume_x(slot);
-                issue_x(slot, (g + 1) * D1 + slot);
-            }
-        }
-#pragma unroll
-        for (int slot = 0; slot < D1; ++slot)
-            if ((ngroups - 1) * D1 + slot < my_n) consume_x(slot);
-    }
-#pragma unroll
-    for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
-
-    // ---------------------------------------------------------------- stage 2: reduce, scale, split -
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-        *reinterpret_cast<f4*>(red + ((wave * RB + rb) * 64 + lane) * 4) = acc[rb];
-
-    // While the slower waves finish stage 1, build the sign operands of the first block (they do not depend on u).
-    // K slots of one stage-3 MFMA: hi(u) of ranks 0..15, then lo(u) of ranks 0..15; lane group q supplies ranks
-    // 8 (q & 1) .. 8 (q & 1) + 7 for both halves, i.e. byte (q & 1) of the 16-bit row of its column.
-    const uint32_t sel_even = 0x00010001u * static_cast<uint32_t>(q & 1);        // row in the low half-word of a dword
-    const uint32_t sel_odd = 0x00010001u * static_cast<uint32_t>(2 + (q & 1));   // row in the high half-word
-    u4 pre[PRE ? 8 : 1];
-    auto build_pre = [&]() {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            if (R8) {  // ranks 8..15 (odd q) are padding and meet u = 0: any sign will do there
-                const uint32_t word = bbuf[0][0][e >> 2];
-                pre[e] = pm_one_from_bits(__builtin_amdgcn_perm(word, word, 0x00010001u * static_cast<uint32_t>(e & 3)));
-            } else {
-                const uint32_t word = bbuf[0][0][e >> 1];
-                pre[e] = pm_one_from_bits(__builtin_amdgcn_perm(word, word, (e & 1) ? sel_odd : sel_even));
-            }
-        }
-    };
-    // The waves that run stage 2 build theirs while they wait for the slower waves to finish stage 1.  The others idle
-    // during stage 2 anyway: with LP they build theirs there, which takes the work off the slowest wave's way to the
-    // first barrier; without LP (a few workgroups, latency-bound) everything is built as early as possible.
-    if (PRE && (!LP || wave < 4)) build_pre();
-    __syncthreads();
-
-    if (wave < 4) {
-        // Accumulator layout: lane (li, q) holds rank li of the block for MFMA rows 4q .. 4q+3; wave i takes row 4q+i.
-        const int i = wave;
-        float u[RB];
-        float amax = 0.f;
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            float part[NW];  // all partial sums are requested before the first add; fixed order: deterministic
-#pragma unroll
-            for (int w = 0; w < NW; ++w) part[w] = red[((w * RB + rb) * 64 + lane) * 4 + i];
-#pragma unroll
-            for (int st = 1; st < NW; st <<= 1) {
-#pragma unroll
-                for (int w = 0; w + st < NW; w += 2 * st) part[w] += part[w + st];
-            }
-            u[rb] = part[0] * sr[rb];
-            amax = fmaxf(amax, fabsf(u[rb]));
-        }
-        const float rowmax = row_max16(amax);  // over the 16 ranks of a block; amax already spans the blocks
-        int e = static_cast<int>((__float_as_uint(rowmax) >> 23) & 0xffu);
-        e = e < 14 ? 14 : (e > 254 ? 254 : e);
-        const float mul = __uint_as_float(static_cast<uint32_t>(267 - e) << 23);  // 2^(13 - (e - 127))
-        if (li == 0) invs[q * 4 + i] = __uint_as_float(static_cast<uint32_t>(e - 13) << 23);  // its reciprocal
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            const float up = u[rb] * mul;
-            const _Float16 hi = static_cast<_Float16>(up);
-            const _Float16 lo = static_cast<_Float16>(up - static_cast<float>(hi));
-            us[(rb * 16 + q * 4 + i) * kURow + li] = hi;
-            us[(rb * 16 + q * 4 + i) * kURow + 16 + li] = lo;
-        }
-    } else if (PRE && LP) {
-        build_pre();
-    }
-    __syncthreads();
-    h8 ufrag[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) ufrag[rb] = as_h8(load16(us + (rb * 16 + li) * kURow + q * 8));
-    float inv[NI];
-#pragma unroll
-    for (int i = 0; i < NI; ++i) inv[i] = invs[q * 4 + i];
-
-    // ---------------------------------------------------------------- stage 3: expand + epilogue ----
-    // MFMA e of a block produces column 8 li + e of the block for lane group li, so after the 8 MFMAs a lane holds 8
-    // consecutive columns of its token rows.
-    auto consume_y = [&](int slot, int n, bool use_pre) {
-        const int b = wave + NW * n;
-        const int j0 = b * 128 + li * 8;
-        const bool j_ok = j0 < d_out;
-        const int jc = j_ok ? j0 : d_out - 8;
-        // Table offsets of all 8 * RB sign operands first (for a general r these are global loads: one wait for all).
-        uint32_t off[8][RB];
-        if (!(PRE && use_pre) && !kValuSigns) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb) {
-                    if (R16) {
-                        const int hw = e * RB + rb;  // half-word index inside the lane's RB * 8 half-words
-                        const uint32_t word = bbuf[slot][hw >> 3][(hw >> 1) & 3] >> ((q & 1) * 8);
-                        off[e][rb] = (hw & 1) ? (word >> 12) & 0xff0u : (word << 4) & 0xff0u;
-                    } else if (R8) {
-                        off[e][rb] = ((bbuf[slot][0][e >> 2] >> ((e & 3) * 8)) << 4) & 0xff0u;
-                    } else {
-                        off[e][rb] = fetch8(a.pB, static_cast<int64_t>(jc + e) * r + rb * 16 + (q & 1) * 8, nwordsB) << 4;
-                    }
-                }
-            }
-        }
-        f4 v[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            v[e] = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                u4 sg;
-                if (PRE && use_pre) {
-                    sg = pre[e];
-                } else if (kValuSigns) {
-                    if (R8) {
-                        const uint32_t word = bbuf[slot][0][e >> 2];
-                        sg = pm_one_from_bits(__builtin_amdgcn_perm(word, word, 0x00010001u * static_cast<uint32_t>(e & 3)));
-                    } else {
-                        const int hw = e * RB + rb;
-                        const uint32_t word = bbuf[slot][hw >> 3][(hw >> 1) & 3];
-                        sg = pm_one_from_bits(__builtin_amdgcn_perm(word, word, (hw & 1) ? sel_odd : sel_even));
-                    }
-                } else {
-                    sg = *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutp) + off[e][rb]);
-                }
-                v[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb], as_h8(sg), v[e], 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int row = TMV == 16 ? q * 4 + i : q * 2 + i;
-            u4 out;
-#pragma unroll
-            for (int d = 0; d < 4; ++d)
-                out[d] = scale_add_pair(v[2 * d][i] * inv[i], v[2 * d + 1][i] * inv[i], sobuf[slot][d], ybuf[slot][i][d]);
-            if (j_ok && row <= last) store16_stream(at(yot, static_cast<uint32_t>(row * d_out + j0) * 2u), out);
-        }
-    };
-
-    if (my_b > 0) {
-        consume_y(0, 0, true);
-        if (D2 < my_b) issue_y(0, D2);
-    }
-    for (int n0 = 0; n0 < my_b; n0 += D2) {
-#pragma unroll
-        for (int slot = 0; slot < D2; ++slot) {
-            const int n = n0 + slot;
-            if (n == 0) continue;
-            if (n < my_b) consume_y(slot, n, false);
-            if (n + D2 < my_b) issue_y(slot, n + D2);
-        }
-    }
-}
-
-// ------------------------------------------------------------------------------------ general kernel ----
-template <int RP>
-__global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a, int vec_x) {
-    __shared__ float red[4][RP];
-    __shared__ float u_s[RP];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int d_in = a.d_in, d_out = a.d_out, r = a.r;
-    const int64_t t = blockIdx.x;
-    const _Float16* xr = a.x + t * d_in;
-
-    float acc[RP];
-#pragma unroll
-    for (int k = 0; k < RP; ++k) acc[k] = 0.f;
-
-    if (vec_x) {  // d_in % 8 == 0, x and s_in 16-byte aligned: 8 columns per lane per step, one carrier byte per rank
-        const uint8_t* bytesA = reinterpret_cast<const uint8_t*>(a.pA);
-        for (int i0 = tid * 8; i0 < d_in; i0 += 256 * 8) {
-            const h8 xv = as_h8(load16(xr + i0));
-            const h8 sv = as_h8(load16(a.s_in + i0));
-            float w[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) w[e] = static_cast<float>(xv[e]) * static_cast<float>(sv[e]);
-#pragma unroll
-            for (int k = 0; k < RP; ++k) {
-                if (k < r) {
-                    const uint32_t byte = bytesA[(static_cast<int64_t>(k) * d_in + i0) >> 3];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[k] += flip(w[e], (byte >> e) & 1u);
-                }
-            }
-        }
-    } else {
-        for (int i = tid; i < d_in; i += 256) {
-            const float w = static_cast<float>(xr[i]) * static_cast<float>(a.s_in[i]);
-#pragma unroll
-            for (int k = 0; k < RP; ++k) {
-                if (k < r) {
-                    const int64_t n = static_cast<int64_t>(k) * d_in + i;
-                    acc[k] += flip(w, (a.pA[n >> 5] >> (n & 31)) & 1u);
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < RP; ++k) {
-        float v = acc[k];
-#pragma unroll
-        for (int sh = 32; sh >= 1; sh >>= 1) v += __shfl_xor(v, sh, 64);
-        if (lane == 0) red[wave][k] = v;
-    }
-    __syncthreads();
-    if (tid < RP) {
-        const float tk = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
-        u_s[tid] = tid < r ? static_cast<float>(a.s_rank[tid]) * tk : 0.f;
-    }
-    __syncthreads();
-    const _Float16* ybr = a.y_base + t * d_out;
-    _Float16* yor = a.y_out + t * d_out;
-    for (int j = tid; j < d_out; j += 256) {
-        float v = 0.f;
-        const int64_t n0 = static_cast<int64_t>(j) * r;
-        for (int k = 0; k < r; ++k) {
-            const int64_t n = n0 + k;
-            v += flip(u_s[k], (a.pB[n >> 5] >> (n & 31)) & 1u);
-        }
-        yor[j] = static_cast<_Float16>(static_cast<float>(ybr[j]) + static_cast<float>(a.s_out[j]) * v);
-    }
-}
-
-// ------------------------------------------------------------------------------------------ host side ----
-
-constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
-
-template <int RB, int TMV, int NW, int D1, bool OS, int BM, bool LP>
-lordba_status launch_mfma_lp(const FwdArgs& a, hipStream_t stream) {
-    const size_t lds = mfma_lds_bytes(RB, TMV, NW, D1);
-    if (lds > kMaxLds) return LORDBA_ERR_ALGO;
-    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, BM, LP>;
-    if (lds > 64 * 1024) {
-        // Opt in to more than 64 KiB of dynamic LDS once per device and kernel; raising the limit is idempotent.
-        static std::mutex mu;
-        static bool granted[64] = {false};
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LORDBA_ERR_NO_DEVICE;
-        std::lock_guard<std::mutex> g(mu);
-        if (!granted[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    static_cast<int>(kMaxLds)) != hipSuccess) {
-                (void)hipGetLastError();
-                return LORDBA_ERR_LAUNCH;
-            }
-            granted[dev] = true;
-        }
-    }
-    const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(a.T) + TMV - 1) / TMV);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, stream, a);
-    return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
-}
-
-// LP only exists where sign operands are built ahead (one rank block, byte-aligned carrier rows); it pays once the grid
-// covers the chip, where the slowest wave at the first barrier sets the pace of the workgroup.
-template <int RB, int TMV, int NW, int D1, bool OS, int BM>
-lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
-    if constexpr (RB == 1 && BM != 0) {
-        if ((static_cast<int64_t>(a.T) + TMV - 1) / TMV >= 128) return launch_mfma_lp<RB, TMV, NW, D1, OS, BM, true>(a, stream);
-    }
-    return launch_mfma_lp<RB, TMV, NW, D1, OS, BM, false>(a, stream);
-}
-
-// Picks the x pipeline: one-shot when every wave's chunks fit the deepest pipeline that the register budget of the
-// workgroup size allows, otherwise the looped variant.
-template <int RB, int TMV, int NW, int BM>
-lordba_status launch_mfma_depth(const FwdArgs& a, hipStream_t stream) {
-    constexpr bool kDeep = TMV == 8 && NW <= 8 && RB == 1;  // 8 chunks in flight only where the registers allow it
-    const int nchunks = (a.d_in + 127) / 128;
-    const int per_wave = (nchunks + NW - 1) / NW;
-    if (per_wave <= 2) return launch_mfma<RB, TMV, NW, 2, true, BM>(a, stream);
-    if (per_wave <= 4) return launch_mfma<RB, TMV, NW, 4, true, BM>(a, stream);
-    if (kDeep && per_wave <= 8) return launch_mfma<RB, TMV, NW, (kDeep ? 8 : 4), true, BM>(a, stream);
-    return launch_mfma<RB, TMV, NW, (TMV == 8 ? 4 : 2), false, BM>(a, stream);
-}
-
-template <int TMV, int NW>
-lordba_status launch_mfma_rb(const FwdArgs& a, hipStream_t stream) {
-    constexpr int kMaxRb = NW == 16 ? (TMV == 8 ? 2 : 1) : 4;  // 16 waves: 128 registers per lane
-    const int rb = (a.r + 15) / 16;
-    if (rb > kMaxRb) return LORDBA_ERR_ALGO;
-    if (a.r == 8) return launch_mfma_depth<1, TMV, NW, 2>(a, stream);
-    const bool r16 = a.r % 16 == 0;
-    if (rb == 1) return r16 ? launch_mfma_depth<1, TMV, NW, 1>(a, stream) : launch_mfma_depth<1, TMV, NW, 0>(a, stream);
-    if constexpr (kMaxRb >= 2) {
-        if (rb == 2) return r16 ? launch_mfma_depth<2, TMV, NW, 1>(a, stream) : launch_mfma_depth<2, TMV, NW, 0>(a, stream);
-    }
-    if constexpr (kMaxRb >= 4) {
-        if (rb == 3) return r16 ? launch_mfma_depth<3, TMV, NW, 1>(a, stream) : launch_mfma_depth<3, TMV, NW, 0>(a, stream);
-        if (rb == 4) return r16 ? launch_mfma_depth<4, TMV, NW, 1>(a, stream) : launch_mfma_depth<4, TMV, NW, 0>(a, stream);
-    }
-    return LORDBA_ERR_DIM;
-}
-
-lordba_status launch_general(const FwdArgs& a, hipStream_t stream, bool vec_x) {
-    const dim3 grid(static_cast<unsigned>(a.T)), block(256);
-    if (a.r <= 8) hipLaunchKernelGGL(lordba_fwd_general_kernel<8>, grid, block, 0, stream, a, vec_x ? 1 : 0);
-    else if (a.r <= 16) hipLaunchKernelGGL(lordba_fwd_general_kernel<16>, grid, block, 0, stream, a, vec_x ? 1 : 0);
-    else if (a.r <= 32) hipLaunchKernelGGL(lordba_fwd_general_kernel<32>, grid, block, 0, stream, a, vec_x ? 1 : 0);
-    else hipLaunchKernelGGL(lordba_fwd_general_kernel<64>, grid, block, 0, stream, a, vec_x ? 1 : 0);
-    return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
-}
-
-bool overlaps(const void* p, size_t pn, const void* q, size_t qn) {
-    const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(q);
-    return pn != 0 && qn != 0 && a < b + qn && b < a + pn;
-}
-bool aligned(const void* p, size_t n) { return (reinterpret_cast<uintptr_t>(p) & (n - 1)) == 0; }
-
-// The kernels are built for gfx950 only; say so instead of failing inside the launch on another device.
-lordba_status check_device() {
-    static std::mutex mu;
-    static int state[64] = {0};  // 0 unknown, 1 ok, 2 not usable
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LORDBA_ERR_NO_DEVICE; }
-    if (dev < 0 || dev >= 64) return LORDBA_ERR_NO_DEVICE;
-    std::lock_guard<std::mutex> g(mu);
-    if (state[dev] == 0) {
-        hipDeviceProp_t prop;
-        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); state[dev] = 2; }
-        else {
-            const char* n = prop.gcnArchName;
-            bool ok = false;
-            for (; n[0] && n[1] && n[2] && n[3] && n[4] && n[5]; ++n)
-                if (n[0] == 'g' && n[1] == 'f' && n[2] == 'x' && n[3] == '9' && n[4] == '5' && n[5] == '0') { ok = true; break; }
-            state[dev] = ok ? 1 : 2;
-        }
-    }
-    return state[dev] == 1 ? LORDBA_OK : LORDBA_ERR_NO_DEVICE;
-}
-
-}  // namespace
+// C entry points of the one-envelope adapter forward branch (the kernels and the dispatch live in lordba_fwd_impl.h).
+#include "lordba_fwd_impl.h"
 
 extern "C" lordba_status lordba_forward_algo(const void* x, const uint32_t* packedA, const uint32_t* packedB,
                                              const void* s_in, const void* s_rank, const void* s_out,
                                              const void* y_base, void* y_out,
                                              int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream,
                                              int algo) {
-    if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || r > LORDBA_MAX_RANK) return LORDBA_ERR_DIM;
-    if (T > INT32_MAX - 64 || d_in > (1 << 24) || d_out > (1 << 24)) return LORDBA_ERR_DIM;
-    if (algo < 0 || algo > 7) return LORDBA_ERR_ALGO;
-    // With no token rows the activation pointers may legitimately be NULL (empty allocations).
-    if (T == 0) return (packedA && packedB && s_in && s_rank && s_out) ? LORDBA_OK : LORDBA_ERR_NULL;
-    if (!x || !packedA || !packedB || !s_in || !s_rank || !s_out || !y_base || !y_out) return LORDBA_ERR_NULL;
-    if (!aligned(x, 2) || !aligned(s_in, 2) || !aligned(s_rank, 2) || !aligned(s_out, 2) || !aligned(y_base, 2) ||
-        !aligned(y_out, 2) || !aligned(packedA, 4) || !aligned(packedB, 4))
-        return LORDBA_ERR_ALIGN;
-    const size_t ny = static_cast<size_t>(T) * d_out * 2, nx = static_cast<size_t>(T) * d_in * 2;
-    const size_t nA = lordba_packed_words(r, d_in) * 4, nB = lordba_packed_words(d_out, r) * 4;
-    if (overlaps(y_out, ny, x, nx) || overlaps(y_out, ny, packedA, nA) || overlaps(y_out, ny, packedB, nB) ||
-        overlaps(y_out, ny, s_in, d_in * 2) || overlaps(y_out, ny, s_rank, r * 2) || overlaps(y_out, ny, s_out, d_out * 2))
-        return LORDBA_ERR_ALIAS;
-    if (y_out != y_base && overlaps(y_out, ny, y_base, ny)) return LORDBA_ERR_ALIAS;
-    const lordba_status dev = check_device();
-    if (dev != LORDBA_OK) return dev;
-
-    FwdArgs a;
-    a.x = static_cast<const _Float16*>(x);
-    a.pA = packedA;
-    a.pB = packedB;
-    a.s_in = static_cast<const _Float16*>(s_in);
-    a.s_rank = static_cast<const _Float16*>(s_rank);
-    a.s_out = static_cast<const _Float16*>(s_out);
-    a.y_base = static_cast<const _Float16*>(y_base);
-    a.y_out = static_cast<_Float16*>(y_out);
-    a.T = static_cast<int>(T);
-    a.d_in = static_cast<int>(d_in);
-    a.d_out = static_cast<int>(d_out);
-    a.r = static_cast<int>(r);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-
-    const bool al16 = aligned(x, 16) && aligned(s_in, 16) && aligned(s_out, 16) && aligned(y_base, 16) &&
-                      aligned(y_out, 16) && aligned(packedB, 16);
-    const bool mfma_ok = al16 && (d_in % 32 == 0) && (d_out % 8 == 0);
-    const bool vec_x = aligned(x, 16) && aligned(s_in, 16) && (d_in % 8 == 0);
-
-    if (algo == LORDBA_ALGO_GENERAL) return launch_general(a, st, vec_x);
-    if (algo != LORDBA_ALGO_AUTO && !mfma_ok) return LORDBA_ERR_ALGO;
-    if (algo == LORDBA_ALGO_AUTO && !mfma_ok) return launch_general(a, st, vec_x);
-
-    // Tile and workgroup shape.  16-row tiles halve the per-row cost of building sign operands and are taken once
-    // T / 16 tiles still fill the 256 CUs; below that, 8-row tiles keep every CU busy.  16 waves per workgroup hide
-    // the most latency but leave 128 registers per lane, which is enough up to r = 32 (8 rows) or r = 16 (16 rows).
-    const int rb = static_cast<int>((r + 15) / 16);
-    const bool tall = algo == LORDBA_ALGO_AUTO ? T >= 4096 : (algo == LORDBA_ALGO_MFMA_T16 || algo == 5 || algo == 7);
-    lordba_status s;
-    if (algo == 4 || algo == 5) {          // tuning variants: 4 waves
-        s = tall ? launch_mfma_rb<16, 4>(a, st) : launch_mfma_rb<8, 4>(a, st);
-    } else if (algo == 6 || algo == 7) {   // tuning variants: 8 waves
-        s = tall ? launch_mfma_rb<16, 8>(a, st) : launch_mfma_rb<8, 8>(a, st);
-    } else if (tall) {
-        s = rb == 1 ? launch_mfma_rb<16, 16>(a, st) : launch_mfma_rb<16, 8>(a, st);
-    } else {
-        s = rb <= 2 ? launch_mfma_rb<8, 16>(a, st) : launch_mfma_rb<8, 8>(a, st);
-    }
-    if (s == LORDBA_ERR_ALGO && algo == LORDBA_ALGO_AUTO) return launch_general(a, st, vec_x);
-    return s;
+    return forward_impl<1>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo);
 }
 
 extern "C" lordba_status lordba_forward(const void* x, const uint32_t* packedA, const uint32_t* packedB,
                                         const void* s_in, const void* s_rank, const void* s_out,
                                         const void* y_base, void* y_out,
                                         int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream) {
-    return lordba_forward_algo(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream,
-                               LORDBA_ALGO_AUTO);
+    return forward_impl<1>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream,
+                           LORDBA_ALGO_AUTO);
 }

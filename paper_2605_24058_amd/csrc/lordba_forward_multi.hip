@@ -1,0 +1,26 @@
+// C entry points of the multi-envelope adapter forward branch (Eq. (lordba) with envelope rank l >= 2; the kernels and
+// the dispatch live in lordba_fwd_impl.h and are instantiated here for 2, 3 and 4 envelopes).
+#include "lordba_fwd_impl.h"
+
+extern "C" lordba_status lordba_forward_multi_algo(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                                   const void* s_in, const void* s_rank, const void* s_out,
+                                                   const void* y_base, void* y_out,
+                                                   int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell,
+                                                   void* stream, int algo) {
+    switch (ell) {
+        case 1: return lordba_forward_algo(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo);
+        case 2: return forward_impl<2>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo);
+        case 3: return forward_impl<3>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo);
+        case 4: return forward_impl<4>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo);
+        default: return LORDBA_ERR_DIM;
+    }
+}
+
+extern "C" lordba_status lordba_forward_multi(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                              const void* s_in, const void* s_rank, const void* s_out,
+                                              const void* y_base, void* y_out,
+                                              int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell,
+                                              void* stream) {
+    return lordba_forward_multi_algo(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, ell, stream,
+                                     LORDBA_ALGO_AUTO);
+}

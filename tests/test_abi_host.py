@@ -117,6 +117,28 @@ def test_forward_validation_needs_no_device(lib):
     assert lib.lordba_forward_algo(x, pA, pB, si, sr, so, yb, yo, T, d_in, d_out, r, None, 99) == 8
 
 
+def test_forward_multi_validation_needs_no_device(lib):
+    base = 0x10000000
+    x, pA, pB, si, sr, so, yb, yo = (base + i * 0x1000000 for i in range(8))
+    T, d_in, d_out, r = 4, 64, 64, 8
+    f = lambda *a: lib.lordba_forward_multi(*a, None)
+    for ell in (1, 2, 3, 4):
+        ok_args = [x, pA, pB, si, sr, so, yb, yo, T, d_in, d_out, r, ell]
+        for i in range(8):
+            a = list(ok_args); a[i] = None
+            assert f(*a) == 1
+        assert f(x, pA, pB, si, sr, so, yb, yo, 0, d_in, d_out, r, ell) == 0
+        assert f(x, pA, pB, si, sr, so, yb, x, T, d_in, d_out, r, ell) == 4
+        assert f(x + 1, pA, pB, si, sr, so, yb, yo, T, d_in, d_out, r, ell) == 5
+        assert f(x, pA, pB, si, sr, so, yb, yo, T, d_in, d_out, 65, ell) == 2
+    for ell in (0, -1, 5, 1 << 40):
+        assert f(x, pA, pB, si, sr, so, yb, yo, T, d_in, d_out, r, ell) == 2
+    # y_out overlapping the SECOND row of a scale array is only an overlap when there are two envelopes
+    second_row = so + d_out * 2
+    assert f(x, pA, pB, si, sr, so, yb, second_row, 1, d_in, d_out, r, 2) == 4
+    assert lib.lordba_forward_multi_algo(x, pA, pB, si, sr, so, yb, yo, T, d_in, d_out, r, 2, None, 4) == 8
+
+
 def test_forward_without_gpu_reports_no_device(lib):
     import torch
     if torch.cuda.is_available():
