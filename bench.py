@@ -220,6 +220,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--ell", type=int, default=1, help="scale envelopes over the same carriers (1 = lordba_forward; "
+                    "2..4 = lordba_forward_multi); single-shape workloads only")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to cycle through (0 = enough to defeat the cache)")
     ap.add_argument("--algo", type=int, default=0, help="kernel selector passed to lordba_forward_algo (0 = library default)")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
@@ -258,7 +260,10 @@ def main():
     per_set = sh.activation_bytes()
     sets = args.sets if args.sets > 0 else max(2, -(-2 * CACHE_BYTES // per_set) + 1)
     sets = min(sets, max(1, int(200e9 // per_set)))
+    ell = args.ell
     host0 = inputs.make_inputs_for(sh, args.seed)
+    if ell > 1:
+        host0.update(inputs.make_envelopes(args.seed, sh.d_in, sh.d_out, sh.r, ell))
     pA, pB = binding.lordba_pack_signs(host0["signsA"], host0["signsB"])
     dev = {k: torch.from_numpy(host0[k]).cuda() for k in ("s_in", "s_rank", "s_out")}
     dev["packedA"] = torch.from_numpy(pA.view(np.int32)).cuda()
@@ -274,14 +279,16 @@ def main():
     ref = binding.load_bench_library() if (args.mode != "forward" or not args.no_ceiling) else None
     cur = lambda: torch.cuda.current_stream().cuda_stream
 
+    fwd = binding.lordba_forward if ell == 1 else binding.lordba_forward_multi
+
     def forward_step(i):
         s = i % sets
-        binding.lordba_forward(xs[s], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
-                               ybs[s], y_out=youts[s], algo=args.algo, check=False)
+        fwd(xs[s], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+            ybs[s], y_out=youts[s], algo=args.algo, check=False)
 
     def hot_step(i):         # one buffer set only: the streams stay in the Infinity Cache
-        binding.lordba_forward(xs[0], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
-                               ybs[0], y_out=youts[0], algo=args.algo, check=False)
+        fwd(xs[0], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+            ybs[0], y_out=youts[0], algo=args.algo, check=False)
 
     def stream_step(i):      # same buffers, same byte split, no arithmetic: the practical HBM ceiling
         s = i % sets
@@ -304,21 +311,22 @@ def main():
     reps_us, wall_s = timed(step, K, max(W, sets), use_graph, reps=5 if full else 1)
     kern_us = reps_us[0]     # average launch-to-launch duration on the stream over the timed region
     ms_per_step = wall_s * 1e3 / K
-    alg_bytes = sh.algorithmic_bytes()
+    alg_bytes = sh.algorithmic_bytes_multi(ell)
     achieved = alg_bytes / (kern_us * 1e-6) / 1e9
 
     out = {
-        "metric": "adapter-branch tokens/s and achieved HBM GB/s at d=4096, r=16, T=2048",
+        "metric": "adapter-branch tokens/s and achieved HBM GB/s at d=4096, r=16, T=2048" if ell == 1 else
+                  "multi-envelope adapter-branch tokens/s and achieved HBM GB/s",
         "value": sh.T * K / wall_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "io_dtype": "f16", "data": "synthetic",
         "config": {"workload": sh.name, "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
-                   "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "algo": args.algo,
+                   "ell": ell, "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "algo": args.algo,
                    "seed": args.seed, "mode": args.mode},
         "achieved_hbm_gbs": achieved, "hbm_peak_gbs": HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(sh.name) if args.mode == "forward" and args.algo == 0 else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(sh.name) if args.mode == "forward" and args.algo == 0 and ell == 1 else None,
                      "kernel_us": kern_us, "algorithmic_bytes": alg_bytes},
     }
 
@@ -342,16 +350,18 @@ def main():
         import oracle
         cores = oracle.available_cores()
         budget_macs = 4e9                        # keeps the leg to a few seconds at ~1e9 fp64 MAC/s/core
-        rows = sh.T if sh.sign_macs() <= budget_macs else max(16, int(sh.T * budget_macs / sh.sign_macs()))
+        macs = sh.sign_macs() * ell
+        rows = sh.T if macs <= budget_macs else max(16, int(sh.T * budget_macs / macs))
         idx = np.arange(rows) if rows == sh.T else np.linspace(0, sh.T - 1, rows).astype(np.int64)
         xh, ybh = host0["x"][idx], host0["y_base"][idx]
-        run = lambda nt: oracle.forward(xh, host0["signsA"], host0["signsB"], host0["s_in"], host0["s_rank"],
-                                        host0["s_out"], ybh, nthreads=nt)
+        ofwd = oracle.forward if ell == 1 else oracle.forward_multi
+        run = lambda nt: ofwd(xh, host0["signsA"], host0["signsB"], host0["s_in"], host0["s_rank"],
+                              host0["s_out"], ybh, nthreads=nt)
         c0 = time.perf_counter(); want = run(cores); c1 = time.perf_counter()
         s_rows = max(1, rows // 8)
         c2 = time.perf_counter()
-        oracle.forward(xh[:s_rows], host0["signsA"], host0["signsB"], host0["s_in"], host0["s_rank"], host0["s_out"],
-                       ybh[:s_rows], nthreads=1)
+        ofwd(xh[:s_rows], host0["signsA"], host0["signsB"], host0["s_in"], host0["s_rank"], host0["s_out"],
+             ybh[:s_rows], nthreads=1)
         c3 = time.perf_counter()
         got = youts[0].cpu().numpy()[idx].astype(np.float64)
         err = float(oracle.row_rel_l2(got, want).max())

@@ -410,12 +410,23 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
         build_pre();
     }
     __syncthreads();
-    h8 ufrag[RB][L];
+    // With 8 token rows, MFMA rows 4a+2 and 4a+3 only repeat rows 4a and 4a+1: in stage 3 they carry the SECOND envelope of
+    // a pair instead, so that two envelopes cost the matrix-core work and the accumulator registers of one.
+    constexpr int VS = TMV == 8 ? (L + 1) / 2 : L;  // accumulator sets per output column
+    h8 ufrag[RB][VS];
     float inv[NI][L];
 #pragma unroll
-    for (int en = 0; en < L; ++en) {
+    for (int vs = 0; vs < VS; ++vs) {
+        int en = vs;
+        if (TMV == 8 && L > 1) {
+            en = 2 * vs + ((li >> 1) & 1);
+            en = en < L ? en : L - 1;  // odd L: the spare rows repeat the last envelope and are ignored
+        }
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) ufrag[rb][en] = as_h8(load16(us + ((rb * L + en) * 16 + li) * kURow + q * 8));
+        for (int rb = 0; rb < RB; ++rb) ufrag[rb][vs] = as_h8(load16(us + ((rb * L + en) * 16 + li) * kURow + q * 8));
+    }
+#pragma unroll
+    for (int en = 0; en < L; ++en) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) inv[i][en] = invs[en * 16 + q * 4 + i];
     }
@@ -447,11 +458,11 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
                 }
             }
         }
-        f4 v[L][8];
+        f4 v[VS][8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
 #pragma unroll
-            for (int en = 0; en < L; ++en) v[en][e] = f4{0.f, 0.f, 0.f, 0.f};
+            for (int vs = 0; vs < VS; ++vs) v[vs][e] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 // Built ahead for the first block; otherwise from the table (measured faster than building them here
@@ -459,8 +470,8 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
                 const u4 sg = (PRE && use_pre) ? pre[e]
                                                : *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutp) + off[e][rb]);
 #pragma unroll
-                for (int en = 0; en < L; ++en)
-                    v[en][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb][en], as_h8(sg), v[en][e], 0, 0, 0);
+                for (int vs = 0; vs < VS; ++vs)
+                    v[vs][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb][vs], as_h8(sg), v[vs][e], 0, 0, 0);
             }
         }
 #pragma unroll
@@ -474,8 +485,10 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
                 for (int en = 0; en < L; ++en) {  // envelopes are added in their order, in fp32; one rounding at the end
                     const h2 so = as_h2(sobuf[slot][en][d]);
-                    o0 = __builtin_fmaf(v[en][2 * d][i] * inv[i][en], static_cast<float>(so[0]), o0);
-                    o1 = __builtin_fmaf(v[en][2 * d + 1][i] * inv[i][en], static_cast<float>(so[1]), o1);
+                    const int vs = TMV == 8 ? en >> 1 : en;           // accumulator set of this envelope
+                    const int vi = TMV == 8 ? i + 2 * (en & 1) : i;   // and its register inside the set
+                    o0 = __builtin_fmaf(v[vs][2 * d][vi] * inv[i][en], static_cast<float>(so[0]), o0);
+                    o1 = __builtin_fmaf(v[vs][2 * d + 1][vi] * inv[i][en], static_cast<float>(so[1]), o1);
                 }
                 h2 o;
                 o[0] = static_cast<_Float16>(o0);
@@ -634,7 +647,7 @@ template <int TMV, int NW, int L>
 lordba_status launch_mfma_rb(const FwdArgs& a, hipStream_t stream) {
     // Rank blocks a variant holds in registers without spilling.  16 waves: 128 registers per lane.  Several envelopes
     // keep L accumulator sets per block: 16-row tiles then only fit two envelopes of at most two rank blocks.
-    constexpr int kMaxRb = NW == 16 ? (TMV == 8 ? 2 : 1)
+    constexpr int kMaxRb = NW == 16 ? (L == 1 ? (TMV == 8 ? 2 : 1) : (L == 2 && TMV == 8 ? 1 : 0))
                            : L == 1 ? 4
                            : TMV == 16 ? (L == 2 ? 2 : 0)
                            : (L == 4 ? 3 : 4);
@@ -765,8 +778,14 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
             s = rb <= 2 ? launch_mfma_rb<8, 16, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
         }
     } else {
-        s = tall ? launch_mfma_rb<16, 8, L>(a, st) : launch_mfma_rb<8, 8, L>(a, st);
-        if (s == LORDBA_ERR_ALGO && tall && algo == LORDBA_ALGO_AUTO) s = launch_mfma_rb<8, 8, L>(a, st);
+        if (tall) {
+            s = launch_mfma_rb<16, 8, L>(a, st);
+            if (s == LORDBA_ERR_ALGO && algo == LORDBA_ALGO_AUTO) s = launch_mfma_rb<8, 8, L>(a, st);
+        } else {
+            s = LORDBA_ERR_ALGO;
+            if constexpr (L == 2) s = launch_mfma_rb<8, 16, L>(a, st);  // a pair of envelopes fits the registers of 16 waves
+            if (s == LORDBA_ERR_ALGO) s = launch_mfma_rb<8, 8, L>(a, st);
+        }
     }
     if (s == LORDBA_ERR_ALGO && algo == LORDBA_ALGO_AUTO) return launch_general(a, st, vec_x);
     return s;
