@@ -42,6 +42,7 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
+constexpr unsigned kSplitBlocks = 4;  // output blocks per workgroup when a tile's blocks are split (one per SIMD)
 constexpr int kXRow = 136;  // halves per row of the x transpose tile: 128 columns + 8 pad -> conflict-free b128 reads
 constexpr int kURow = 40;   // halves per row of the u tile: 32 slots + 8 pad
 constexpr int kLutBytes = 256 * 16;
@@ -87,6 +88,7 @@ struct FwdArgs {
     _Float16* y_out;
     int T, d_in, d_out, r;
     int ell;  // envelopes: s_in, s_rank, s_out are [ell, d_in], [ell, r], [ell, d_out]
+    int blocks_per_wg;  // matrix-core kernel: 128-column output blocks per workgroup (the grid's y extent covers d_out)
 };
 
 // 8 carrier bits starting at bit `bit0` of a packed stream of `nwords` words.  Both words are always read from a
@@ -152,12 +154,16 @@ __device__ __forceinline__ h2 as_h2(uint32_t v) { return __builtin_bit_cast(h2, 
 //      groups of D1 chunks
 // BM   how a lane fetches the sign(B) bits of its 8 output columns: 1 = r is a multiple of 16 (RB aligned 16-byte
 //      loads), 2 = r is 8 (one aligned 8-byte load, one byte per column), 0 = any r (two dwords per operand)
-// LP   the waves that do not run stage 2 build their first block's sign operands during stage 2 instead of before it
+// GM   grid mode.  1 (grids that fill the chip): the waves that do not run stage 2 build their first block's sign
+//      operands during stage 2 instead of before it.  2 (a handful of tiles): gridDim.y workgroups share a token tile
+//      and split its output blocks; the x extent of the grid is padded to a multiple of 8 and padding workgroups exit.
+//      0: neither.
 // L    scale envelopes over the same carriers (Eq. (lordba)): s_in, s_rank, s_out hold L rows; everything that depends
 //      on a scale is done L times, everything that depends only on x or on the carrier bits once
-template <int RB, int TMV, int NW, int D1, bool OS, int BM, bool LP, int L>
+template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L>
 __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     static_assert(NW >= 4, "stage 2 is spread over the first four waves");
+    constexpr bool LP = GM == 1, SPLIT = GM == 2;
     constexpr int NI = TMV / 4;           // 16-byte row accesses per lane per 128-column block of a tile
     constexpr int D2 = 2;                 // y_base column blocks in flight per wave
     constexpr bool R16 = BM == 1, R8 = BM == 2;
@@ -169,6 +175,7 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     const int li = lane & 15, q = lane >> 4;
     const int T = a.T, d_in = a.d_in, d_out = a.d_out, r = a.r;
     const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
+    if (SPLIT && t0 >= T) return;  // padding workgroup (the whole workgroup leaves, before any barrier)
     const int nchunks = (d_in + 127) >> 7;
 
     u4* lutp = reinterpret_cast<u4*>(smem);  // 8 bits -> 8 fp16 values +-1.0
@@ -248,7 +255,12 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     // ---------------------------------------------------------------- stage 3 loads (issued later) ---
     // Block b = 128 output columns; wave w owns blocks w, w + NW, ...; lane (li, q) owns columns 8 li .. 8 li + 7 of
     // the block for its token rows.
-    const int nblk = (d_out + 127) >> 7;
+    // gridDim.y workgroups may share a token tile (small T: most of the chip would idle otherwise): each repeats stages 1
+    // and 2, which costs no extra HBM traffic worth naming at such T, and takes its own contiguous range of blocks.
+    const int nblk_all = (d_out + 127) >> 7;
+    const int per_wg = SPLIT ? a.blocks_per_wg : nblk_all;
+    const int b_first = SPLIT ? static_cast<int>(blockIdx.y) * per_wg : 0;
+    const int nblk = nblk_all - b_first < per_wg ? (nblk_all - b_first > 0 ? nblk_all - b_first : 0) : per_wg;
     const int my_b = wave < nblk ? (nblk - wave + NW - 1) / NW : 0;
     const int64_t nwordsB = (static_cast<int64_t>(d_out) * r + 31) >> 5;
     u4 ybuf[D2][NI];
@@ -256,8 +268,8 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     u4 bbuf[D2][R16 ? RB : 1];
 
     auto issue_y = [&](int slot, int n) {
-        int b = wave + NW * n;
-        b = b < nblk ? b : nblk - 1;
+        int b = b_first + wave + NW * n;
+        b = b < nblk_all ? b : nblk_all - 1;  // past the end: re-read a valid block, the result is not used
         int j0 = b * 128 + li * 8;
         j0 = j0 < d_out ? j0 : d_out - 8;
         if (R16) {  // 8 rows of r bits = RB * 16 contiguous, 16-byte aligned bytes
@@ -435,7 +447,7 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     // MFMA e of a block produces column 8 li + e of the block for lane group li, so after the 8 MFMAs a lane holds 8
     // consecutive columns of its token rows.
     auto consume_y = [&](int slot, int n, bool use_pre) {
-        const int b = wave + NW * n;
+        const int b = b_first + wave + NW * n;
         const int j0 = b * 128 + li * 8;
         const bool j_ok = j0 < d_out;
         const int jc = j_ok ? j0 : d_out - 8;
@@ -594,11 +606,11 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a, int 
 
 constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
 
-template <int RB, int TMV, int NW, int D1, bool OS, int BM, bool LP, int L>
-lordba_status launch_mfma_lp(const FwdArgs& a, hipStream_t stream) {
+template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L>
+lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
     const size_t lds = mfma_lds_bytes(RB, TMV, NW, D1, L);
     if (lds > kMaxLds) return LORDBA_ERR_ALGO;
-    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, BM, LP, L>;
+    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, BM, GM, L>;
     if (lds > 64 * 1024) {
         // Opt in to more than 64 KiB of dynamic LDS once per device and kernel; raising the limit is idempotent.
         static std::mutex mu;
@@ -615,19 +627,41 @@ lordba_status launch_mfma_lp(const FwdArgs& a, hipStream_t stream) {
             granted[dev] = true;
         }
     }
-    const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(a.T) + TMV - 1) / TMV);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, stream, a);
+    const unsigned tiles = static_cast<unsigned>((static_cast<int64_t>(a.T) + TMV - 1) / TMV);
+    FwdArgs b = a;
+    dim3 grid(tiles);
+    if constexpr (GM == 2) {
+        // A handful of tiles leaves most CUs idle and each workgroup with a long serial stage 3: the output blocks of a
+        // tile are split over several workgroups (each repeats the cheap stages 1 and 2; nothing is exchanged).
+        const unsigned nblk = static_cast<unsigned>((a.d_out + 127) / 128);
+        unsigned split = (nblk + kSplitBlocks - 1) / kSplitBlocks;
+        const unsigned cap = 256 / tiles;
+        split = split < cap ? split : cap;
+        split = split < 1 ? 1 : split;
+        b.blocks_per_wg = static_cast<int>((nblk + split - 1) / split);
+        split = (nblk + b.blocks_per_wg - 1) / b.blocks_per_wg;  // no workgroup without a block
+        // Workgroups are dealt to the 8 XCDs round-robin in launch order (x fastest).  With an x extent that is a
+        // multiple of 8, the workgroups that share a tile (same x) land on one XCD and read x, s_in and the carriers
+        // through one L2 instead of fetching them into eight; the padding workgroups exit at once.
+        grid = dim3((tiles + 7u) & ~7u, split);
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, stream, b);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
 }
 
-// LP only exists where sign operands are built ahead (one rank block, byte-aligned carrier rows); it pays once the grid
-// covers the chip, where the slowest wave at the first barrier sets the pace of the workgroup.
+// Grid mode 1 only exists where sign operands are built ahead (one rank block, byte-aligned carrier rows); it pays once
+// the grid covers the chip, where the slowest wave at the first barrier sets the pace of the workgroup.  Grid mode 2
+// is for 8-row tiles when there are at most 32 of them.
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int L>
 lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
+    const int64_t tiles = (static_cast<int64_t>(a.T) + TMV - 1) / TMV;
     if constexpr (RB == 1 && BM != 0 && L == 1) {
-        if ((static_cast<int64_t>(a.T) + TMV - 1) / TMV >= 128) return launch_mfma_lp<RB, TMV, NW, D1, OS, BM, true, L>(a, stream);
+        if (tiles >= 128) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 1, L>(a, stream);
     }
-    return launch_mfma_lp<RB, TMV, NW, D1, OS, BM, false, L>(a, stream);
+    if constexpr (TMV == 8 && NW >= 8) {
+        if (tiles <= 32 && a.d_out > static_cast<int>(kSplitBlocks) * 128) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 2, L>(a, stream);
+    }
+    return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 0, L>(a, stream);
 }
 
 // Picks the x pipeline: one-shot when every wave's chunks fit the deepest pipeline that the register budget of the
@@ -748,6 +782,7 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
     a.d_out = static_cast<int>(d_out);
     a.r = static_cast<int>(r);
     a.ell = L;
+    a.blocks_per_wg = 0;  // set per launch in grid mode 2
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     // Rows of the scale arrays start at multiples of d_in / d_out elements: the conditions below also align them.
