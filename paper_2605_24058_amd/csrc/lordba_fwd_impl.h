@@ -157,13 +157,13 @@ __device__ __forceinline__ h2 as_h2(uint32_t v) { return __builtin_bit_cast(h2, 
 // GM   grid mode.  1 (grids that fill the chip): the waves that do not run stage 2 build their first block's sign
 //      operands during stage 2 instead of before it.  2 (a handful of tiles): gridDim.y workgroups share a token tile
 //      and split its output blocks; the x extent of the grid is padded to a multiple of 8 and padding workgroups exit.
-//      0: neither.
+//      3 (fewer token rows than a tile): as 2, and rows past T are not requested at all.  0: none of these.
 // L    scale envelopes over the same carriers (Eq. (lordba)): s_in, s_rank, s_out hold L rows; everything that depends
 //      on a scale is done L times, everything that depends only on x or on the carrier bits once
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L>
 __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     static_assert(NW >= 4, "stage 2 is spread over the first four waves");
-    constexpr bool LP = GM == 1, SPLIT = GM == 2;
+    constexpr bool LP = GM == 1, SPLIT = GM >= 2, MASK = GM == 3;
     constexpr int NI = TMV / 4;           // 16-byte row accesses per lane per 128-column block of a tile
     constexpr int D2 = 2;                 // y_base column blocks in flight per wave
     constexpr bool R16 = BM == 1, R8 = BM == 2;
@@ -223,10 +223,17 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
         for (int m = 0; m < NI; ++m) {
             int row = m * 4 + q;
+            const bool live = row <= last;
             row = row < last ? row : last;
             int col = c * 128 + li * 8;
             col = col < d_in ? col : d_in - 8;
-            xbuf[slot][m] = load16_stream(at(xt, static_cast<uint32_t>(row * d_in + col) * 2u));
+            if (MASK) {
+                // fewer than 8 token rows: rows past T are not requested at all (a tile with one live row moves an eighth)
+                xbuf[slot][m] = u4{0u, 0u, 0u, 0u};
+                if (live) xbuf[slot][m] = load16_stream(at(xt, static_cast<uint32_t>(row * d_in + col) * 2u));
+            } else {
+                xbuf[slot][m] = load16_stream(at(xt, static_cast<uint32_t>(row * d_in + col) * 2u));
+            }
         }
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
@@ -285,8 +292,14 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             int row = TMV == 16 ? q * 4 + i : q * 2 + i;
+            const bool live = row <= last;
             row = row < last ? row : last;
-            ybuf[slot][i] = load16_stream(at(ybt, static_cast<uint32_t>(row * d_out + j0) * 2u));
+            if (MASK) {
+                ybuf[slot][i] = u4{0u, 0u, 0u, 0u};
+                if (live) ybuf[slot][i] = load16_stream(at(ybt, static_cast<uint32_t>(row * d_out + j0) * 2u));
+            } else {
+                ybuf[slot][i] = load16_stream(at(ybt, static_cast<uint32_t>(row * d_out + j0) * 2u));
+            }
         }
     };
 
@@ -630,7 +643,7 @@ lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
     const unsigned tiles = static_cast<unsigned>((static_cast<int64_t>(a.T) + TMV - 1) / TMV);
     FwdArgs b = a;
     dim3 grid(tiles);
-    if constexpr (GM == 2) {
+    if constexpr (GM >= 2) {
         // A handful of tiles leaves most CUs idle and each workgroup with a long serial stage 3: the output blocks of a
         // tile are split over several workgroups (each repeats the cheap stages 1 and 2; nothing is exchanged).
         const unsigned nblk = static_cast<unsigned>((a.d_out + 127) / 128);
@@ -651,7 +664,7 @@ lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
 
 // Grid mode 1 only exists where sign operands are built ahead (one rank block, byte-aligned carrier rows); it pays once
 // the grid covers the chip, where the slowest wave at the first barrier sets the pace of the workgroup.  Grid mode 2
-// is for 8-row tiles when there are at most 32 of them.
+// is for 8-row tiles when there are at most 32 of them, grid mode 3 for a single partial tile (decode).
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int L>
 lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
     const int64_t tiles = (static_cast<int64_t>(a.T) + TMV - 1) / TMV;
@@ -659,6 +672,7 @@ lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
         if (tiles >= 128) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 1, L>(a, stream);
     }
     if constexpr (TMV == 8 && NW >= 8) {
+        if (a.T < TMV) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 3, L>(a, stream);
         if (tiles <= 32 && a.d_out > static_cast<int>(kSplitBlocks) * 128) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 2, L>(a, stream);
     }
     return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 0, L>(a, stream);
