@@ -54,6 +54,8 @@ def _load():
         lib.lordba_oracle_forward.argtypes = [vp] * 8 + [i64] * 4 + [ci]
         lib.lordba_oracle_forward_packed.restype = ci
         lib.lordba_oracle_forward_packed.argtypes = [vp] * 8 + [i64] * 4 + [ci]
+        lib.lordba_oracle_forward_batched.restype = ci
+        lib.lordba_oracle_forward_batched.argtypes = [vp] * 9 + [i64] * 5
         lib.lordba_oracle_forward_multi.restype = ci
         lib.lordba_oracle_forward_multi.argtypes = [vp] * 8 + [i64] * 5 + [ci]
         _lib = lib
@@ -177,6 +179,35 @@ def forward_multi(x, signsA, signsB, s_in, s_rank, s_out, y_base, nthreads: int 
                                              _ptr(yb), _ptr(y), T, d_in, d_out, r, ell, int(nthreads))
     if st != 0:
         raise ValueError("oracle forward_multi failed with status %d" % st)
+    return y
+
+
+def forward_batched(x, signsA, signsB, s_in, s_rank, s_out, adapter_of_row, y_base) -> np.ndarray:
+    """fp64 Y[t] = Y_base[t] + X[t] DeltaW(adapter adapter_of_row[t]); rows with an id outside [0, n) pass through.
+
+    signsA[n,r,d_in], signsB[n,d_out,r]: int8 +-1; s_in[n,d_in], s_rank[n,r], s_out[n,d_out]: float16;
+    adapter_of_row[T]: int32."""
+    sA = _as(signsA, np.int8)
+    sB = _as(signsB, np.int8)
+    if sA.ndim != 3 or sB.ndim != 3:
+        raise ValueError("pools must be [n, r, d_in] and [n, d_out, r]")
+    n, r, d_in = sA.shape
+    d_out = sB.shape[1]
+    if sB.shape != (n, d_out, r):
+        raise ValueError("signsB must be [n, d_out, r]")
+    si = _f16_bits(s_in, (n, d_in))
+    sr = _f16_bits(s_rank, (n, r))
+    so = _f16_bits(s_out, (n, d_out))
+    xb = _f16_bits(x)
+    T = xb.shape[0]
+    xb = _f16_bits(xb, (T, d_in))
+    yb = _f16_bits(y_base, (T, d_out))
+    ids = _as(adapter_of_row, np.int32, (T,))
+    y = np.empty((T, d_out), dtype=np.float64)
+    st = _load().lordba_oracle_forward_batched(_ptr(xb), _ptr(sA), _ptr(sB), _ptr(si), _ptr(sr), _ptr(so), _ptr(ids),
+                                               _ptr(yb), _ptr(y), T, d_in, d_out, r, n)
+    if st != 0:
+        raise ValueError("oracle forward_batched failed with status %d" % st)
     return y
 
 

@@ -30,6 +30,9 @@
  * in exact rationals and in numpy, by its reduction to the one-envelope
  * function, by the zero-beta envelope that must change nothing (Sec. 3.2,
  * initialisation of additional envelopes), and by additivity over envelopes.
+ * The batched forward (one adapter of a pool per token row) is pinned by running
+ * the pinned one-adapter function on every group of rows separately, by the
+ * pass-through rows, and by its invariance under any permutation of the rows.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -331,5 +334,45 @@ int lordba_oracle_forward_multi(const uint16_t *x, const int8_t *signsA, const i
     for (int i = 0; i < nthreads; ++i) if (jobs[i].base.status) status = jobs[i].base.status;
 done:
     free(jobs); free(tids); free(alpha); free(beta); free(gamma);
+    return status;
+}
+
+/* ------------------------------------------------ multi-adapter batch ---- */
+
+/* Several adapters of the same shape served in one batch (Sec. 3.3, hot-swappable adapters served concurrently):
+ * token row t uses adapter id[t] of a pool,
+ *   y[t] = y_base[t] + x[t] DeltaW(theta_{id[t]})            (Eq. adapter-mode-fwd, row by row)
+ * and a row whose id is not in [0, n_adapters) has no adapter: y[t] = y_base[t].
+ * Pools are contiguous arrays over the adapter index: signsA[n, r, d_in], signsB[n, d_out, r], s_in[n, d_in],
+ * s_rank[n, r], s_out[n, d_out].  Plain loop over rows; each row is the one-adapter row function. */
+int lordba_oracle_forward_batched(const uint16_t *x, const int8_t *signsA, const int8_t *signsB,
+                                  const uint16_t *s_in, const uint16_t *s_rank, const uint16_t *s_out,
+                                  const int32_t *id, const uint16_t *y_base, double *y,
+                                  int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t n_adapters)
+{
+    if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || n_adapters < 0) return 2;
+    for (int64_t n = 0; n < n_adapters * r * d_in; ++n) if (signsA[n] != 1 && signsA[n] != -1) return 3;
+    for (int64_t n = 0; n < n_adapters * d_out * r; ++n) if (signsB[n] != 1 && signsB[n] != -1) return 3;
+    double *alpha = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *beta = (double *)malloc(sizeof(double) * (size_t)r);
+    double *gamma = (double *)malloc(sizeof(double) * (size_t)d_out);
+    double *w = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *u = (double *)malloc(sizeof(double) * (size_t)r);
+    int status = 0;
+    if (!alpha || !beta || !gamma || !w || !u) { status = 9; goto done; }
+    for (int64_t t = 0; t < T; ++t) {
+        const int64_t a = id[t];
+        if (a < 0 || a >= n_adapters) {
+            for (int64_t j = 0; j < d_out; ++j) y[t * d_out + j] = lordba_oracle_f16_to_f64(y_base[t * d_out + j]);
+            continue;
+        }
+        lordba_oracle_f16_array_to_f64(s_in + a * d_in, alpha, d_in);
+        lordba_oracle_f16_array_to_f64(s_rank + a * r, beta, r);
+        lordba_oracle_f16_array_to_f64(s_out + a * d_out, gamma, d_out);
+        forward_row(x + t * d_in, signsA + a * r * d_in, signsB + a * d_out * r, alpha, beta, gamma,
+                    y_base + t * d_out, y + t * d_out, d_in, d_out, r, w, u);
+    }
+done:
+    free(alpha); free(beta); free(gamma); free(w); free(u);
     return status;
 }

@@ -106,6 +106,33 @@ def make_inputs_multi(seed: int, T: int, d_in: int, d_out: int, r: int, ell: int
     return out
 
 
+def make_adapter_pool(seed: int, d_in: int, d_out: int, r: int, n: int) -> Dict[str, np.ndarray]:
+    """n independent adapters of one shape, stacked over a leading adapter index (adapter a = make_adapter(seed', ...)
+    with a seed derived from (seed, a))."""
+    ads = [make_adapter(int(np.random.SeedSequence([int(seed), 4, a]).generate_state(1)[0]), d_in, d_out, r) for a in range(n)]
+    return {k: np.stack([ad[k] for ad in ads]) for k in ("signsA", "signsB", "s_in", "s_rank", "s_out")}
+
+
+def make_adapter_ids(seed: int, T: int, n: int, pattern: str) -> np.ndarray:
+    """int32[T] adapter index per token row.
+    "segments": rows sorted by adapter, n contiguous segments of random lengths (prefill of n requests);
+    "decode":   every row draws its adapter independently (one token per request, unsorted);
+    "mixed":    as "segments", with about one row in eight marked -1 (a request without an adapter)."""
+    g = _rng(seed, 5)
+    if pattern == "decode":
+        return g.integers(0, n, size=T, dtype=np.int64).astype(np.int32)
+    cuts = np.sort(g.integers(0, T + 1, size=max(n - 1, 0)))
+    bounds = np.concatenate([[0], cuts, [T]]).astype(np.int64)
+    ids = np.empty(T, dtype=np.int32)
+    for a in range(n):
+        ids[bounds[a]:bounds[a + 1]] = a
+    if pattern == "mixed":
+        ids[g.random(T) < 0.125] = -1
+    elif pattern != "segments":
+        raise ValueError(pattern)
+    return ids
+
+
 def make_activations(seed: int, T: int, d_in: int, d_out: int) -> Dict[str, np.ndarray]:
     g = _rng(seed, 2)
     x = g.standard_normal((T, d_in), dtype=np.float32).astype(np.float16)
