@@ -136,6 +136,30 @@ lordba_status lordba_forward_multi_algo(const void* x, const uint32_t* packedA, 
                                         int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell,
                                         void* stream, int algo);
 
+/* DEVICE function: one batch served by several adapters of the same shape (Sec. 3.3: adapters are hot-swappable and
+ * served concurrently over one frozen base; Eq. (adapter-mode-fwd) holds row by row).  Token row t goes through adapter
+ * adapter_of_row[t] of a pool; a row whose index is outside [0, n_adapters) has no adapter and y_out[t] = y_base[t].
+ *   packedA_pool : uint32 [n_adapters, lordba_packed_words(r, d_in)]    each adapter's S_A in the canonical format
+ *   packedB_pool : uint32 [n_adapters, lordba_packed_words(d_out, r)]   each adapter's S_B
+ *   s_in_pool    : fp16 [n_adapters, d_in]    s_rank_pool: fp16 [n_adapters, r]    s_out_pool: fp16 [n_adapters, d_out]
+ *   adapter_of_row: int32 [T], device memory, any order (rows sorted by adapter are processed fastest: the kernel
+ *                  works on runs of equal index inside 8-row tiles)
+ * All other arguments, the arithmetic, the error bound, aliasing rules (y_out may be y_base), stream semantics (enqueue
+ * only, no allocation, no workspace) and error codes as lordba_forward; 1 <= n_adapters <= 2^20.  The index array is
+ * read on the device only: it is not validated by the host, out-of-range entries are defined as "no adapter". */
+lordba_status lordba_forward_batched(const void* x, const uint32_t* packedA_pool, const uint32_t* packedB_pool,
+                                     const void* s_in_pool, const void* s_rank_pool, const void* s_out_pool,
+                                     const int32_t* adapter_of_row, const void* y_base, void* y_out,
+                                     int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t n_adapters,
+                                     void* stream);
+
+/* Same with the kernel chosen by the caller: LORDBA_ALGO_AUTO, LORDBA_ALGO_GENERAL or LORDBA_ALGO_MFMA_T8. */
+lordba_status lordba_forward_batched_algo(const void* x, const uint32_t* packedA_pool, const uint32_t* packedB_pool,
+                                          const void* s_in_pool, const void* s_rank_pool, const void* s_out_pool,
+                                          const int32_t* adapter_of_row, const void* y_base, void* y_out,
+                                          int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t n_adapters,
+                                          void* stream, int algo);
+
 /* Static, never-NULL description of a status code. */
 const char* lordba_status_string(lordba_status status);
 

@@ -128,6 +128,10 @@ def load_library():
         f = getattr(lib, name)      # AttributeError if the library was built from older sources: rebuild it
         f.restype = ci
         f.argtypes = [vp] * 8 + [i64] * 5 + extra
+    for name, extra in (("lordba_forward_batched", [vp]), ("lordba_forward_batched_algo", [vp, ci])):
+        f = getattr(lib, name)
+        f.restype = ci
+        f.argtypes = [vp] * 9 + [i64] * 5 + extra
     lib.lordba_status_string.restype = ctypes.c_char_p
     lib.lordba_status_string.argtypes = [ci]
     _lib = lib
@@ -264,6 +268,59 @@ def lordba_forward_multi(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out
                                        T, d_in, d_out, r, ell, ctypes.c_void_p(stream), int(algo))
     if st != 0:
         raise LordbaError(st, "lordba_forward_multi")
+    return y_out
+
+
+def lordba_pack_pool(signsA_pool, signsB_pool) -> Tuple[np.ndarray, np.ndarray]:
+    """Packs every adapter of a pool (signsA_pool [n, r, d_in], signsB_pool [n, d_out, r]) with lordba_pack_signs and
+    stacks the results: uint32 [n, words_A], [n, words_B]."""
+    packed = [lordba_pack_signs(a, b) for a, b in zip(signsA_pool, signsB_pool)]
+    return np.stack([p[0] for p in packed]), np.stack([p[1] for p in packed])
+
+
+def lordba_forward_batched(x, packedA_pool, packedB_pool, s_in_pool, s_rank_pool, s_out_pool, adapter_of_row, y_base,
+                           y_out=None, stream=None, algo: int = ALGO_AUTO, check: bool = True):
+    """y_out[t] = y_base[t] + the branch of adapter adapter_of_row[t] of a pool, on the GPU.  Pools are torch CUDA tensors
+    stacked over the adapter index: packedA_pool / packedB_pool int32 [n, words], s_*_pool float16 [n, .];
+    adapter_of_row int32 [T] (an index outside [0, n) = no adapter)."""
+    import torch
+
+    lib = load_library()
+    if check:
+        for name, t_ in (("x", x), ("s_in_pool", s_in_pool), ("s_rank_pool", s_rank_pool), ("s_out_pool", s_out_pool),
+                         ("y_base", y_base)):
+            if t_.dtype != torch.float16 or not t_.is_cuda or not t_.is_contiguous():
+                raise TypeError("%s must be a contiguous float16 CUDA tensor" % name)
+        for name, t_ in (("packedA_pool", packedA_pool), ("packedB_pool", packedB_pool), ("adapter_of_row", adapter_of_row)):
+            if t_.dtype != torch.int32 or not t_.is_cuda or not t_.is_contiguous():
+                raise TypeError("%s must be a contiguous int32 CUDA tensor" % name)
+        if x.dim() != 2 or y_base.dim() != 2 or x.shape[0] != y_base.shape[0] or adapter_of_row.numel() != x.shape[0]:
+            raise ValueError("x must be [T, d_in], y_base [T, d_out], adapter_of_row [T]")
+        if s_rank_pool.dim() != 2 or packedA_pool.dim() != 2 or packedB_pool.dim() != 2:
+            raise ValueError("pools must be stacked over the adapter index")
+    T, d_in = x.shape
+    d_out = y_base.shape[1]
+    n, r = s_rank_pool.shape
+    if check:
+        if tuple(s_in_pool.shape) != (n, d_in) or tuple(s_out_pool.shape) != (n, d_out):
+            raise ValueError("scale pool shapes do not match")
+        if tuple(packedA_pool.shape) != (n, (r * d_in + 31) // 32) or tuple(packedB_pool.shape) != (n, (d_out * r + 31) // 32):
+            raise ValueError("packed pool shapes do not match")
+    if y_out is None:
+        y_out = torch.empty_like(y_base)
+    elif check and (y_out.dtype != torch.float16 or not y_out.is_cuda or not y_out.is_contiguous()
+                    or y_out.shape != y_base.shape):
+        raise TypeError("y_out must be a contiguous float16 CUDA tensor shaped like y_base")
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    st = lib.lordba_forward_batched_algo(x.data_ptr(), packedA_pool.data_ptr(), packedB_pool.data_ptr(), s_in_pool.data_ptr(),
+                                         s_rank_pool.data_ptr(), s_out_pool.data_ptr(), adapter_of_row.data_ptr(),
+                                         y_base.data_ptr(), y_out.data_ptr(), T, d_in, d_out, r, n,
+                                         ctypes.c_void_p(stream), int(algo))
+    if st != 0:
+        raise LordbaError(st, "lordba_forward_batched")
     return y_out
 
 

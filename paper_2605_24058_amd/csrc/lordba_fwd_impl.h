@@ -89,7 +89,22 @@ struct FwdArgs {
     int T, d_in, d_out, r;
     int ell;  // envelopes: s_in, s_rank, s_out are [ell, d_in], [ell, r], [ell, d_out]
     int blocks_per_wg;  // matrix-core kernel: 128-column output blocks per workgroup (the grid's y extent covers d_out)
+    // Multi-adapter batch (ids != nullptr): pA, pB, s_in, s_rank, s_out are pools of n_adapters adapters laid out one
+    // after the other, and token row t uses adapter ids[t]; an id outside [0, n_adapters) means "no adapter".
+    const int32_t* ids;
+    int n_adapters;
 };
+
+// The arguments of one adapter of a pool.
+__device__ __forceinline__ FwdArgs select_adapter(const FwdArgs& a, int id) {
+    FwdArgs b = a;
+    b.pA += static_cast<int64_t>(id) * ((static_cast<int64_t>(a.r) * a.d_in + 31) >> 5);
+    b.pB += static_cast<int64_t>(id) * ((static_cast<int64_t>(a.d_out) * a.r + 31) >> 5);
+    b.s_in += static_cast<int64_t>(id) * a.d_in;
+    b.s_rank += static_cast<int64_t>(id) * a.r;
+    b.s_out += static_cast<int64_t>(id) * a.d_out;
+    return b;
+}
 
 // 8 carrier bits starting at bit `bit0` of a packed stream of `nwords` words.  Both words are always read from a
 // clamped, valid index (no branch, no access past the end); bits past the end of the stream are not meaningful and
@@ -157,25 +172,27 @@ __device__ __forceinline__ h2 as_h2(uint32_t v) { return __builtin_bit_cast(h2, 
 // GM   grid mode.  1 (grids that fill the chip): the waves that do not run stage 2 build their first block's sign
 //      operands during stage 2 instead of before it.  2 (a handful of tiles): gridDim.y workgroups share a token tile
 //      and split its output blocks; the x extent of the grid is padded to a multiple of 8 and padding workgroups exit.
-//      3 (fewer token rows than a tile): as 2, and rows past T are not requested at all.  0: none of these.
+//      3 (fewer token rows than a tile): as 2, and rows past T are not requested at all.  4: multi-adapter batch, the
+//      tile is processed once per run of rows that use the same adapter.  0: none of these.
 // L    scale envelopes over the same carriers (Eq. (lordba)): s_in, s_rank, s_out hold L rows; everything that depends
 //      on a scale is done L times, everything that depends only on x or on the carrier bits once
+//
+// fwd_tile: rows first..last (inclusive, relative to token row t0) of one tile through one adapter, by the whole
+// workgroup.  Rows of the tile outside that range are neither requested as such (loads are clamped into the range) nor
+// stored.  The function may be called several times in a row by a workgroup (its barriers order the reuse of LDS).
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L>
-__global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
+__device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, const int64_t t0, const int first, const int last) {
     static_assert(NW >= 4, "stage 2 is spread over the first four waves");
-    constexpr bool LP = GM == 1, SPLIT = GM >= 2, MASK = GM == 3;
+    constexpr bool LP = GM == 1, SPLIT = GM == 2 || GM == 3, MASK = GM == 3;
     constexpr int NI = TMV / 4;           // 16-byte row accesses per lane per 128-column block of a tile
     constexpr int D2 = 2;                 // y_base column blocks in flight per wave
     constexpr bool R16 = BM == 1, R8 = BM == 2;
     static_assert(!R8 || RB == 1, "r = 8 is one rank block");
     constexpr bool PRE = (R16 || R8) && RB == 1;  // sign operands of the first block are built before u is known
 
-    extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, q = lane >> 4;
-    const int T = a.T, d_in = a.d_in, d_out = a.d_out, r = a.r;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
-    if (SPLIT && t0 >= T) return;  // padding workgroup (the whole workgroup leaves, before any barrier)
+    const int d_in = a.d_in, d_out = a.d_out, r = a.r;
     const int nchunks = (d_in + 127) >> 7;
 
     u4* lutp = reinterpret_cast<u4*>(smem);  // 8 bits -> 8 fp16 values +-1.0
@@ -194,7 +211,6 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     // order, so loads are issued in the order their data is needed: s_rank, then per chunk s_in and x, and y_base only
     // after the wave has consumed its x (an earlier request would sit in front of other waves' x).
     // A tile never spans more than 16 rows of at most 2^24 columns, so offsets inside it fit 32 bits.
-    const int last = static_cast<int>(T - 1 - t0 < TMV - 1 ? T - 1 - t0 : TMV - 1);  // last live row of the tile
     const _Float16* xt = a.x + t0 * d_in;
     const _Float16* ybt = a.y_base + t0 * d_out;
     _Float16* yot = a.y_out + t0 * d_out;
@@ -223,8 +239,9 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
         for (int m = 0; m < NI; ++m) {
             int row = m * 4 + q;
-            const bool live = row <= last;
+            const bool live = row >= first && row <= last;
             row = row < last ? row : last;
+            row = row > first ? row : first;
             int col = c * 128 + li * 8;
             col = col < d_in ? col : d_in - 8;
             if (MASK) {
@@ -292,8 +309,9 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             int row = TMV == 16 ? q * 4 + i : q * 2 + i;
-            const bool live = row <= last;
+            const bool live = row >= first && row <= last;
             row = row < last ? row : last;
+            row = row > first ? row : first;
             if (MASK) {
                 ybuf[slot][i] = u4{0u, 0u, 0u, 0u};
                 if (live) ybuf[slot][i] = load16_stream(at(ybt, static_cast<uint32_t>(row * d_out + j0) * 2u));
@@ -520,7 +538,7 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
                 o[1] = static_cast<_Float16>(o1);
                 out[d] = __builtin_bit_cast(uint32_t, o);
             }
-            if (j_ok && row <= last) store16_stream(at(yot, static_cast<uint32_t>(row * d_out + j0) * 2u), out);
+            if (j_ok && row >= first && row <= last) store16_stream(at(yot, static_cast<uint32_t>(row * d_out + j0) * 2u), out);
         }
     };
 
@@ -539,14 +557,61 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     }
 }
 
+template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L>
+__global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
+    if ((GM == 2 || GM == 3) && t0 >= a.T) return;  // padding workgroup (the whole workgroup leaves, before any barrier)
+    const int last = static_cast<int>(a.T - 1 - t0 < TMV - 1 ? a.T - 1 - t0 : TMV - 1);  // last live row of the tile
+    if constexpr (GM != 4) {
+        fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L>(a, smem, t0, 0, last);
+    } else {
+        // Multi-adapter batch: the rows of a tile are taken in runs of equal adapter index, one pass per run.  Sorted
+        // batches have one run per tile except where two requests meet; a decode batch has one run per row.
+        static_assert(TMV == 8, "runs are found among 8 rows");
+        const int lane = threadIdx.x & 63;
+        int my_id = -1;
+        if ((lane & 7) <= last) my_id = a.ids[t0 + (lane & 7)];
+        if (my_id >= a.n_adapters) my_id = -1;
+        int first = 0;
+        while (first <= last) {
+            const int id = __builtin_amdgcn_readlane(my_id, first);
+            int end = first;
+            while (end < last && __builtin_amdgcn_readlane(my_id, end + 1) == id) ++end;
+            if (id >= 0) {
+                const FwdArgs b = select_adapter(a, id);
+                fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L>(b, smem, t0, first, end);
+            } else if (a.y_out != a.y_base) {  // no adapter: the rows pass through
+                for (int row = first; row <= end; ++row) {
+                    const _Float16* src = a.y_base + (t0 + row) * a.d_out;
+                    _Float16* dst = a.y_out + (t0 + row) * a.d_out;
+                    for (int c = static_cast<int>(threadIdx.x) * 8; c < a.d_out; c += NW * 64 * 8)
+                        store16_stream(dst + c, load16_stream(src + c));
+                }
+            }
+            first = end + 1;
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------ general kernel ----
 template <int RP>
-__global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a, int vec_x) {
+__global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a0, int vec_x) {
     __shared__ float red[4][RP];
     __shared__ float u_s[LORDBA_MAX_ENVELOPES][RP];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int d_in = a.d_in, d_out = a.d_out, r = a.r, ell = a.ell;
     const int64_t t = blockIdx.x;
+    FwdArgs a = a0;
+    if (a0.ids != nullptr) {  // multi-adapter batch: this row's adapter, or none
+        const int id = a0.ids[t];
+        if (id < 0 || id >= a0.n_adapters) {
+            if (a0.y_out != a0.y_base)
+                for (int j = tid; j < a0.d_out; j += 256) a0.y_out[t * a0.d_out + j] = a0.y_base[t * a0.d_out + j];
+            return;
+        }
+        a = select_adapter(a0, id);
+    }
+    const int d_in = a.d_in, d_out = a.d_out, r = a.r, ell = a.ell;
     const _Float16* xr = a.x + t * d_in;
 
     for (int en = 0; en < ell; ++en) {  // u of every envelope (Eq. (lordba): the carriers are shared, the scales are not)
@@ -643,7 +708,7 @@ lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
     const unsigned tiles = static_cast<unsigned>((static_cast<int64_t>(a.T) + TMV - 1) / TMV);
     FwdArgs b = a;
     dim3 grid(tiles);
-    if constexpr (GM >= 2) {
+    if constexpr (GM == 2 || GM == 3) {
         // A handful of tiles leaves most CUs idle and each workgroup with a long serial stage 3: the output blocks of a
         // tile are split over several workgroups (each repeats the cheap stages 1 and 2; nothing is exchanged).
         const unsigned nblk = static_cast<unsigned>((a.d_out + 127) / 128);
@@ -668,6 +733,10 @@ lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int L>
 lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
     const int64_t tiles = (static_cast<int64_t>(a.T) + TMV - 1) / TMV;
+    if (a.ids != nullptr) {
+        if constexpr (TMV == 8 && L == 1 && NW >= 8) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 4, L>(a, stream);
+        return LORDBA_ERR_ALGO;
+    }
     if constexpr (RB == 1 && BM != 0 && L == 1) {
         if (tiles >= 128) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 1, L>(a, stream);
     }
@@ -762,21 +831,26 @@ template <int L>
 lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_t* packedB,
                            const void* s_in, const void* s_rank, const void* s_out,
                            const void* y_base, void* y_out,
-                           int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream, int algo) {
+                           int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream, int algo,
+                           const int32_t* ids = nullptr, int64_t n_adapters = 1, bool batched = false) {
     if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || r > LORDBA_MAX_RANK) return LORDBA_ERR_DIM;
+    if (batched && (n_adapters < 1 || n_adapters > (1 << 20))) return LORDBA_ERR_DIM;
     if (T > INT32_MAX - 64 || d_in > (1 << 24) || d_out > (1 << 24)) return LORDBA_ERR_DIM;
     if (algo < 0 || algo > (L == 1 ? 7 : 3)) return LORDBA_ERR_ALGO;
     // With no token rows the activation pointers may legitimately be NULL (empty allocations).
     if (T == 0) return (packedA && packedB && s_in && s_rank && s_out) ? LORDBA_OK : LORDBA_ERR_NULL;
     if (!x || !packedA || !packedB || !s_in || !s_rank || !s_out || !y_base || !y_out) return LORDBA_ERR_NULL;
+    if (batched && !ids) return LORDBA_ERR_NULL;
+    if (batched && !aligned(ids, 4)) return LORDBA_ERR_ALIGN;
     if (!aligned(x, 2) || !aligned(s_in, 2) || !aligned(s_rank, 2) || !aligned(s_out, 2) || !aligned(y_base, 2) ||
         !aligned(y_out, 2) || !aligned(packedA, 4) || !aligned(packedB, 4))
         return LORDBA_ERR_ALIGN;
     const size_t ny = static_cast<size_t>(T) * d_out * 2, nx = static_cast<size_t>(T) * d_in * 2;
-    const size_t nA = lordba_packed_words(r, d_in) * 4, nB = lordba_packed_words(d_out, r) * 4;
+    const size_t np = static_cast<size_t>(batched ? n_adapters : 1);  // adapters behind the pool pointers
+    const size_t nA = lordba_packed_words(r, d_in) * 4 * np, nB = lordba_packed_words(d_out, r) * 4 * np;
     if (overlaps(y_out, ny, x, nx) || overlaps(y_out, ny, packedA, nA) || overlaps(y_out, ny, packedB, nB) ||
-        overlaps(y_out, ny, s_in, L * d_in * 2) || overlaps(y_out, ny, s_rank, L * r * 2) ||
-        overlaps(y_out, ny, s_out, L * d_out * 2))
+        overlaps(y_out, ny, s_in, np * L * d_in * 2) || overlaps(y_out, ny, s_rank, np * L * r * 2) ||
+        overlaps(y_out, ny, s_out, np * L * d_out * 2) || (batched && overlaps(y_out, ny, ids, static_cast<size_t>(T) * 4)))
         return LORDBA_ERR_ALIAS;
     if (y_out != y_base && overlaps(y_out, ny, y_base, ny)) return LORDBA_ERR_ALIAS;
     const lordba_status dev = check_device();
@@ -797,12 +871,17 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
     a.r = static_cast<int>(r);
     a.ell = L;
     a.blocks_per_wg = 0;  // set per launch in grid mode 2
+    a.ids = batched ? ids : nullptr;
+    a.n_adapters = static_cast<int>(n_adapters);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     // Rows of the scale arrays start at multiples of d_in / d_out elements: the conditions below also align them.
     const bool al16 = aligned(x, 16) && aligned(s_in, 16) && aligned(s_out, 16) && aligned(y_base, 16) &&
                       aligned(y_out, 16) && aligned(packedB, 16);
-    const bool mfma_ok = al16 && (d_in % 32 == 0) && (d_out % 8 == 0);
+    // In a pool every adapter starts a whole number of words / elements after the previous one: the fast path needs the
+    // packed sign(B) of each adapter 16-byte aligned, i.e. d_out * r a multiple of 128.
+    const bool pool_ok = !batched || (d_out * r) % 128 == 0;
+    const bool mfma_ok = al16 && (d_in % 32 == 0) && (d_out % 8 == 0) && pool_ok;
     const bool vec_x = aligned(x, 16) && aligned(s_in, 16) && (d_in % 8 == 0);
 
     if (algo == LORDBA_ALGO_GENERAL) return launch_general(a, st, vec_x);
@@ -814,7 +893,9 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
     // the most latency but leave 128 registers per lane, which is enough up to r = 32 (8 rows) or r = 16 (16 rows)
     // with one envelope; several envelopes keep L accumulator sets and run on 8 waves.
     const int rb = static_cast<int>((r + 15) / 16);
-    const bool tall = algo == LORDBA_ALGO_AUTO ? T >= 4096 : (algo == LORDBA_ALGO_MFMA_T16 || algo == 5 || algo == 7);
+    const bool tall = batched ? false
+                              : algo == LORDBA_ALGO_AUTO ? T >= 4096 : (algo == LORDBA_ALGO_MFMA_T16 || algo == 5 || algo == 7);
+    if (batched && algo != LORDBA_ALGO_AUTO && algo != LORDBA_ALGO_MFMA_T8) return LORDBA_ERR_ALGO;
     lordba_status s;
     if constexpr (L == 1) {
         if (algo == 4 || algo == 5) {          // tuning variants: 4 waves
