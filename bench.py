@@ -222,6 +222,11 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--ell", type=int, default=1, help="scale envelopes over the same carriers (1 = lordba_forward; "
                     "2..4 = lordba_forward_multi); single-shape workloads only")
+    ap.add_argument("--adapters", type=int, default=0, help="serve the batch with a pool of this many adapters through "
+                    "lordba_forward_batched (0 = one adapter, lordba_forward); single-shape workloads, --ell 1 only")
+    ap.add_argument("--id-pattern", choices=["segments", "decode", "mixed"], default="segments",
+                    help="adapter index per token row: sorted segments (prefill of several requests), independent draws "
+                         "(decode, one token per request) or segments with rows that have no adapter")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to cycle through (0 = enough to defeat the cache)")
     ap.add_argument("--algo", type=int, default=0, help="kernel selector passed to lordba_forward_algo (0 = library default)")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
@@ -261,11 +266,20 @@ def main():
     sets = args.sets if args.sets > 0 else max(2, -(-2 * CACHE_BYTES // per_set) + 1)
     sets = min(sets, max(1, int(200e9 // per_set)))
     ell = args.ell
+    nad = args.adapters
+    assert not (nad and ell > 1), "--adapters goes with one envelope"
     host0 = inputs.make_inputs_for(sh, args.seed)
     if ell > 1:
         host0.update(inputs.make_envelopes(args.seed, sh.d_in, sh.d_out, sh.r, ell))
-    pA, pB = binding.lordba_pack_signs(host0["signsA"], host0["signsB"])
+    if nad:
+        host0.update(inputs.make_adapter_pool(args.seed, sh.d_in, sh.d_out, sh.r, nad))
+        host0["ids"] = inputs.make_adapter_ids(args.seed, sh.T, nad, args.id_pattern)
+        pA, pB = binding.lordba_pack_pool(host0["signsA"], host0["signsB"])
+    else:
+        pA, pB = binding.lordba_pack_signs(host0["signsA"], host0["signsB"])
     dev = {k: torch.from_numpy(host0[k]).cuda() for k in ("s_in", "s_rank", "s_out")}
+    if nad:
+        dev["ids"] = torch.from_numpy(host0["ids"]).cuda()
     dev["packedA"] = torch.from_numpy(pA.view(np.int32)).cuda()
     dev["packedB"] = torch.from_numpy(pB.view(np.int32)).cuda()
     xs, ybs, youts = [], [], []
@@ -279,7 +293,11 @@ def main():
     ref = binding.load_bench_library() if (args.mode != "forward" or not args.no_ceiling) else None
     cur = lambda: torch.cuda.current_stream().cuda_stream
 
-    fwd = binding.lordba_forward if ell == 1 else binding.lordba_forward_multi
+    if nad:
+        def fwd(x, pa, pb, si, sr, so, yb, **kw):
+            return binding.lordba_forward_batched(x, pa, pb, si, sr, so, dev["ids"], yb, **kw)
+    else:
+        fwd = binding.lordba_forward if ell == 1 else binding.lordba_forward_multi
 
     def forward_step(i):
         s = i % sets
@@ -312,21 +330,25 @@ def main():
     kern_us = reps_us[0]     # average launch-to-launch duration on the stream over the timed region
     ms_per_step = wall_s * 1e3 / K
     alg_bytes = sh.algorithmic_bytes_multi(ell)
+    if nad:                  # every adapter that some row uses is read once, plus the index array
+        used = len(set(int(a) for a in host0["ids"] if 0 <= a < nad))
+        alg_bytes = sh.activation_bytes() + used * sh.adapter_bytes() + 4 * sh.T
     achieved = alg_bytes / (kern_us * 1e-6) / 1e9
 
     out = {
-        "metric": "adapter-branch tokens/s and achieved HBM GB/s at d=4096, r=16, T=2048" if ell == 1 else
+        "metric": "multi-adapter batch: adapter-branch tokens/s and achieved HBM GB/s" if nad else
+                  "adapter-branch tokens/s and achieved HBM GB/s at d=4096, r=16, T=2048" if ell == 1 else
                   "multi-envelope adapter-branch tokens/s and achieved HBM GB/s",
         "value": sh.T * K / wall_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "io_dtype": "f16", "data": "synthetic",
         "config": {"workload": sh.name, "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
-                   "ell": ell, "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "algo": args.algo,
+                   "ell": ell, "adapters": nad, "id_pattern": args.id_pattern if nad else None, "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "algo": args.algo,
                    "seed": args.seed, "mode": args.mode},
         "achieved_hbm_gbs": achieved, "hbm_peak_gbs": HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(sh.name) if args.mode == "forward" and args.algo == 0 and ell == 1 else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(sh.name) if args.mode == "forward" and args.algo == 0 and ell == 1 and not nad else None,
                      "kernel_us": kern_us, "algorithmic_bytes": alg_bytes},
     }
 
@@ -350,11 +372,16 @@ def main():
         import oracle
         cores = oracle.available_cores()
         budget_macs = 4e9                        # keeps the leg to a few seconds at ~1e9 fp64 MAC/s/core
-        macs = sh.sign_macs() * ell
+        macs = sh.sign_macs() * ell * (8 if nad else 1)      # the batched oracle runs on one thread
         rows = sh.T if macs <= budget_macs else max(16, int(sh.T * budget_macs / macs))
         idx = np.arange(rows) if rows == sh.T else np.linspace(0, sh.T - 1, rows).astype(np.int64)
         xh, ybh = host0["x"][idx], host0["y_base"][idx]
         ofwd = oracle.forward if ell == 1 else oracle.forward_multi
+        if nad:              # the batched oracle is single-threaded: the thread count is ignored
+            ids_h = host0["ids"][idx]
+            ofwd = lambda x, sa, sb, si, sr, so, yb, nthreads=1: oracle.forward_batched(
+                x, sa, sb, si, sr, so, ids_h[:x.shape[0]], yb)
+            cores = 1
         run = lambda nt: ofwd(xh, host0["signsA"], host0["signsB"], host0["s_in"], host0["s_rank"],
                               host0["s_out"], ybh, nthreads=nt)
         c0 = time.perf_counter(); want = run(cores); c1 = time.perf_counter()

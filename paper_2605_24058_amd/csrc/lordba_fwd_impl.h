@@ -172,8 +172,8 @@ __device__ __forceinline__ h2 as_h2(uint32_t v) { return __builtin_bit_cast(h2, 
 // GM   grid mode.  1 (grids that fill the chip): the waves that do not run stage 2 build their first block's sign
 //      operands during stage 2 instead of before it.  2 (a handful of tiles): gridDim.y workgroups share a token tile
 //      and split its output blocks; the x extent of the grid is padded to a multiple of 8 and padding workgroups exit.
-//      3 (fewer token rows than a tile): as 2, and rows past T are not requested at all.  4: multi-adapter batch, the
-//      tile is processed once per run of rows that use the same adapter.  0: none of these.
+//      3 (fewer token rows than a tile): as 2, and rows past T are not requested at all.  4: multi-adapter batch,
+//      workgroup (tile, k) processes the k-th run of rows of its tile that use the same adapter.  0: none of these.
 // L    scale envelopes over the same carriers (Eq. (lordba)): s_in, s_rank, s_out hold L rows; everything that depends
 //      on a scale is done L times, everything that depends only on x or on the carrier bits once
 //
@@ -566,18 +566,26 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     if constexpr (GM != 4) {
         fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L>(a, smem, t0, 0, last);
     } else {
-        // Multi-adapter batch: the rows of a tile are taken in runs of equal adapter index, one pass per run.  Sorted
-        // batches have one run per tile except where two requests meet; a decode batch has one run per row.
+        // Multi-adapter batch: the rows of a tile are taken in runs of equal adapter index.  A tile of a sorted batch
+        // has one run (two where requests meet), a decode batch has one per row.
+        // Workgroup (tile, k) handles the k-th run of its tile and leaves if there is none, so the runs of a tile proceed
+        // in parallel.  A workgroup that only finds out that it has nothing to do still holds a CU slot for most of a
+        // microsecond: on grids that fill the chip the host picks 8-wave workgroups, two of which fit a CU, so that
+        // these pass through the second slot while the first works.  (One workgroup per tile looping over its runs
+        // was tried: inlined into a loop, and also behind a real call, the tile code compiles to twice the time.)
         static_assert(TMV == 8, "runs are found among 8 rows");
         const int lane = threadIdx.x & 63;
         int my_id = -1;
         if ((lane & 7) <= last) my_id = a.ids[t0 + (lane & 7)];
         if (my_id >= a.n_adapters) my_id = -1;
-        int first = 0;
-        while (first <= last) {
+        auto run_end = [&](int first) {  // last row of the run that starts at `first` (scalar walk, same in every wave)
             const int id = __builtin_amdgcn_readlane(my_id, first);
             int end = first;
             while (end < last && __builtin_amdgcn_readlane(my_id, end + 1) == id) ++end;
+            return end;
+        };
+        auto one_run = [&](int first, int end) {
+            const int id = __builtin_amdgcn_readlane(my_id, first);
             if (id >= 0) {
                 const FwdArgs b = select_adapter(a, id);
                 fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L>(b, smem, t0, first, end);
@@ -589,8 +597,12 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
                         store16_stream(dst + c, load16_stream(src + c));
                 }
             }
-            first = end + 1;
-        }
+        };
+        const int want = static_cast<int>(blockIdx.y);
+        int first = 0;
+        for (int run = 0; run < want && first <= last; ++run) first = run_end(first) + 1;
+        if (first > last) return;  // no such run: the whole workgroup leaves, before any barrier
+        one_run(first, run_end(first));
     }
 }
 
@@ -723,6 +735,7 @@ lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
         // through one L2 instead of fetching them into eight; the padding workgroups exit at once.
         grid = dim3((tiles + 7u) & ~7u, split);
     }
+    if constexpr (GM == 4) grid = dim3(tiles, TMV);  // one workgroup per possible run of a tile (see the kernel)
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, stream, b);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
 }
@@ -734,7 +747,9 @@ template <int RB, int TMV, int NW, int D1, bool OS, int BM, int L>
 lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
     const int64_t tiles = (static_cast<int64_t>(a.T) + TMV - 1) / TMV;
     if (a.ids != nullptr) {
-        if constexpr (TMV == 8 && L == 1 && NW >= 8) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 4, L>(a, stream);
+        if constexpr (TMV == 8 && L == 1 && NW >= 8) {
+            return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 4, L>(a, stream);
+        }
         return LORDBA_ERR_ALGO;
     }
     if constexpr (RB == 1 && BM != 0 && L == 1) {
@@ -904,6 +919,8 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
             s = tall ? launch_mfma_rb<16, 8, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
         } else if (tall) {
             s = rb == 1 ? launch_mfma_rb<16, 16, 1>(a, st) : launch_mfma_rb<16, 8, 1>(a, st);
+        } else if (batched && (T + 7) / 8 > 32) {
+            s = launch_mfma_rb<8, 8, 1>(a, st);  // two workgroups per CU: see the batch mode of the kernel
         } else {
             s = rb <= 2 ? launch_mfma_rb<8, 16, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
         }
