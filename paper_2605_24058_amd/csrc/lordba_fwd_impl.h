@@ -607,14 +607,15 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------ general kernel ----
-template <int RP>
+// PLAIN: one envelope, no adapter pool (known at compile time: the envelope loop and the index lookup disappear).
+template <int RP, bool PLAIN>
 __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a0, int vec_x) {
     __shared__ float red[4][RP];
     __shared__ float u_s[LORDBA_MAX_ENVELOPES][RP];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t t = blockIdx.x;
     FwdArgs a = a0;
-    if (a0.ids != nullptr) {  // multi-adapter batch: this row's adapter, or none
+    if (!PLAIN && a0.ids != nullptr) {  // multi-adapter batch: this row's adapter, or none
         const int id = a0.ids[t];
         if (id < 0 || id >= a0.n_adapters) {
             if (a0.y_out != a0.y_base)
@@ -623,7 +624,7 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a0, int
         }
         a = select_adapter(a0, id);
     }
-    const int d_in = a.d_in, d_out = a.d_out, r = a.r, ell = a.ell;
+    const int d_in = a.d_in, d_out = a.d_out, r = a.r, ell = PLAIN ? 1 : a.ell;
     const _Float16* xr = a.x + t * d_in;
 
     for (int en = 0; en < ell; ++en) {  // u of every envelope (Eq. (lordba): the carriers are shared, the scales are not)
@@ -640,10 +641,14 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a0, int
                 float w[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) w[e] = static_cast<float>(xv[e]) * static_cast<float>(sv[e]);
+                // one carrier byte per rank, a row of sign(A) apart: a running per-lane pointer instead of RP row bases
+                const uint8_t* pk = bytesA + (i0 >> 3);
+                const int row_bytes = d_in >> 3;
 #pragma unroll
                 for (int k = 0; k < RP; ++k) {
                     if (k < r) {
-                        const uint32_t byte = bytesA[(static_cast<int64_t>(k) * d_in + i0) >> 3];
+                        const uint32_t byte = *pk;
+                        pk += row_bytes;
 #pragma unroll
                         for (int e = 0; e < 8; ++e) acc[k] += flip(w[e], (byte >> e) & 1u);
                     }
@@ -804,12 +809,18 @@ lordba_status launch_mfma_rb(const FwdArgs& a, hipStream_t stream) {
     return LORDBA_ERR_DIM;
 }
 
-lordba_status launch_general(const FwdArgs& a, hipStream_t stream, bool vec_x) {
+template <bool PLAIN>
+void launch_general_rp(const FwdArgs& a, hipStream_t stream, bool vec_x) {
     const dim3 grid(static_cast<unsigned>(a.T)), block(256);
-    if (a.r <= 8) hipLaunchKernelGGL(lordba_fwd_general_kernel<8>, grid, block, 0, stream, a, vec_x ? 1 : 0);
-    else if (a.r <= 16) hipLaunchKernelGGL(lordba_fwd_general_kernel<16>, grid, block, 0, stream, a, vec_x ? 1 : 0);
-    else if (a.r <= 32) hipLaunchKernelGGL(lordba_fwd_general_kernel<32>, grid, block, 0, stream, a, vec_x ? 1 : 0);
-    else hipLaunchKernelGGL(lordba_fwd_general_kernel<64>, grid, block, 0, stream, a, vec_x ? 1 : 0);
+    if (a.r <= 8) hipLaunchKernelGGL((lordba_fwd_general_kernel<8, PLAIN>), grid, block, 0, stream, a, vec_x ? 1 : 0);
+    else if (a.r <= 16) hipLaunchKernelGGL((lordba_fwd_general_kernel<16, PLAIN>), grid, block, 0, stream, a, vec_x ? 1 : 0);
+    else if (a.r <= 32) hipLaunchKernelGGL((lordba_fwd_general_kernel<32, PLAIN>), grid, block, 0, stream, a, vec_x ? 1 : 0);
+    else hipLaunchKernelGGL((lordba_fwd_general_kernel<64, PLAIN>), grid, block, 0, stream, a, vec_x ? 1 : 0);
+}
+
+lordba_status launch_general(const FwdArgs& a, hipStream_t stream, bool vec_x) {
+    if (a.ell == 1 && a.ids == nullptr) launch_general_rp<true>(a, stream, vec_x);
+    else launch_general_rp<false>(a, stream, vec_x);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
 }
 
