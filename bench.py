@@ -218,7 +218,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c2",
+                    help="c1, c2 (default), c3_up, c3_down, c5_q, c5_up, c5_down or a full shape name; c5_model (the 280 adapter "
+                         "calls of a LLaMA-2-13B pass); c4_sweep (decode sizes, microseconds per call)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--ell", type=int, default=1, help="scale envelopes over the same carriers (1 = lordba_forward; "
                     "2..4 = lordba_forward_multi); single-shape workloads only")

@@ -162,3 +162,30 @@ def test_bad_arguments(torch_cuda):
     assert lib.lordba_forward_batched(*args, 2, None) == 0
     torch.cuda.synchronize()
     del dpA, dpB, y_out
+
+
+def test_hip_graph_replays_match_eager(torch_cuda):
+    # several replays of a captured batched launch (both grid modes), with eager work in between
+    torch = torch_cuda
+    for T in (40, 520):                   # a few tiles (a workgroup per run) and many tiles (8-wave workgroups)
+        d = make(11, T, 512, 384, 16, 5, "mixed")
+        pA, pB = binding.lordba_pack_pool(d["signsA"], d["signsB"])
+        f = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        args = (f(d["x"]), f(pA.view(np.int32)), f(pB.view(np.int32)), f(d["s_in"]), f(d["s_rank"]), f(d["s_out"]),
+                f(d["ids"]), f(d["y_base"]))
+        eager = binding.lordba_forward_batched(*args).clone()
+        torch.cuda.synchronize()
+        y_g = torch.empty_like(eager)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            binding.lordba_forward_batched(*args, y_out=y_g)
+        for rep in range(3):
+            y_g.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_g, eager), (T, rep)
+            again = binding.lordba_forward_batched(*args)
+            torch.cuda.synchronize()
+            assert torch.equal(again, eager)
+        assert oracle.row_rel_l2(eager.cpu().numpy().astype(np.float64), want_of(d)).max() <= TOL

@@ -210,3 +210,27 @@ def test_empty_batch(torch_cuda):
                                      dev["y_base"])
     torch.cuda.synchronize()
     assert tuple(y.shape) == (0, 64)
+
+
+def test_hip_graph_replays_match_eager(torch_cuda):
+    # several replays of a captured multi-envelope launch, with eager work in between, against the eager result
+    torch = torch_cuda
+    d = inputs.make_inputs_multi(12, 70, 1024, 768, 16, 2)
+    dev = to_device(torch, d)
+    args = (dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"], dev["y_base"])
+    eager = binding.lordba_forward_multi(*args).clone()
+    torch.cuda.synchronize()
+    y_g = torch.empty_like(eager)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        binding.lordba_forward_multi(*args, y_out=y_g)
+    for rep in range(3):
+        y_g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_g, eager), rep
+        again = binding.lordba_forward_multi(*args)
+        torch.cuda.synchronize()
+        assert torch.equal(again, eager)
+    assert oracle.row_rel_l2(eager.cpu().numpy().astype(np.float64), oracle_multi(d)).max() <= TOL
