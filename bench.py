@@ -30,7 +30,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size
 # (profiles/lordba_fwd_mfma_c2_hbm_traffic.txt); bench.py cannot read hardware counters itself.
-MEASURED_TRAFFIC_BYTES = {"c2_llama7b_attn_4096x4096_r16_T2048": 49492 * 1024}
+MEASURED_TRAFFIC_BYTES = {"c2_llama7b_attn_4096x4096_r16_T2048": 49487 * 1024}
 CACHE_BYTES = 256 << 20        # Infinity Cache
 
 WORKLOADS = {}
