@@ -1,5 +1,6 @@
-"""CPU oracle for the LoRDBA adapter forward branch (Def. 1, Eq. (lordba) with one or
-several scale envelopes, Eq. (adapter-mode-fwd), Eq. (lordba-fwd) of the paper).
+"""CPU oracle for the LoRDBA adapter branch: forward (Def. 1, Eq. (lordba) with one or
+several scale envelopes, Eq. (adapter-mode-fwd), Eq. (lordba-fwd) of the paper) and the
+backward pass of training with the smooth-sign straight-through factor (Eq. (smoothsign)).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke()`` and
 by the ``cpu_baseline`` leg of ``bench.py``.  The product package never imports
@@ -58,6 +59,10 @@ def _load():
         lib.lordba_oracle_forward_batched.argtypes = [vp] * 9 + [i64] * 5
         lib.lordba_oracle_forward_multi.restype = ci
         lib.lordba_oracle_forward_multi.argtypes = [vp] * 8 + [i64] * 5 + [ci]
+        lib.lordba_oracle_smooth_sign_grad.restype = ctypes.c_double
+        lib.lordba_oracle_smooth_sign_grad.argtypes = [ctypes.c_double, ctypes.c_double]
+        lib.lordba_oracle_backward.restype = ci
+        lib.lordba_oracle_backward.argtypes = [vp] * 9 + [ctypes.c_double] + [vp] * 7 + [i64] * 4
         _lib = lib
     return _lib
 
@@ -229,6 +234,55 @@ def forward_packed(x, packedA, packedB, s_in, s_rank, s_out, y_base, r: int, nth
     if st != 0:
         raise ValueError("oracle forward failed with status %d" % st)
     return y
+
+
+def smooth_sign_grad(u: float, kappa: float) -> float:
+    """kappa (1 - tanh^2(kappa u)), the backward-pass stand-in for d sign(u)/du (Eq. (smoothsign))."""
+    return float(_load().lordba_oracle_smooth_sign_grad(float(u), float(kappa)))
+
+
+def backward(x, g, signsA, signsB, s_in, s_rank, s_out, latA, latB, kappa: float, dx_base=None) -> dict:
+    """fp64 gradients of a loss with dL/dY = g through Y = Y_base + X diag(s_in) S_A^T diag(s_rank) S_B^T diag(s_out),
+    the carriers' gradients passed through the smooth-sign factor of Eq. (smoothsign) at the latents.
+
+    x[T,d_in], g[T,d_out], dx_base[T,d_in] (optional): float16; signsA[r,d_in], signsB[d_out,r]: int8 +-1;
+    s_*: float16; latA[r,d_in], latB[d_out,r]: float32.  Returns a dict of float64 arrays
+    dx[T,d_in], d_s_in[d_in], d_s_rank[r], d_s_out[d_out], d_latA[r,d_in], d_latB[d_out,r]."""
+    sA = _as(signsA, np.int8)
+    sB = _as(signsB, np.int8)
+    r, d_in = sA.shape
+    d_out = sB.shape[0]
+    if sB.shape != (d_out, r):
+        raise ValueError("signsB must be [d_out, r]")
+    xb = _f16_bits(x)
+    T = xb.shape[0]
+    xb = _f16_bits(xb, (T, d_in))
+    gb = _f16_bits(g, (T, d_out))
+    si = _f16_bits(s_in, (d_in,))
+    sr = _f16_bits(s_rank, (r,))
+    so = _f16_bits(s_out, (d_out,))
+    lA = _as(latA, np.float32, (r, d_in))
+    lB = _as(latB, np.float32, (d_out, r))
+    db = None if dx_base is None else _f16_bits(dx_base, (T, d_in))
+    out = {"dx": np.empty((T, d_in)), "d_s_in": np.empty(d_in), "d_s_rank": np.empty(r), "d_s_out": np.empty(d_out),
+           "d_latA": np.empty((r, d_in)), "d_latB": np.empty((d_out, r))}
+    st = _load().lordba_oracle_backward(
+        _ptr(xb), _ptr(gb), _ptr(sA), _ptr(sB), _ptr(si), _ptr(sr), _ptr(so), _ptr(lA), _ptr(lB), float(kappa),
+        None if db is None else _ptr(db), _ptr(out["dx"]), _ptr(out["d_s_in"]), _ptr(out["d_s_rank"]),
+        _ptr(out["d_s_out"]), _ptr(out["d_latA"]), _ptr(out["d_latB"]), T, d_in, d_out, r)
+    if st != 0:
+        raise ValueError("oracle backward failed with status %d" % st)
+    return out
+
+
+def rel_l2(a_test, a_ref) -> float:
+    """||a_test - a_ref||_2 / ||a_ref||_2 over a whole array (0 if both are exactly 0, inf if only the reference is)."""
+    a = np.asarray(a_test, dtype=np.float64).ravel()
+    b = np.asarray(a_ref, dtype=np.float64).ravel()
+    num, den = np.sqrt(((a - b) ** 2).sum()), np.sqrt((b ** 2).sum())
+    if den > 0:
+        return float(num / den)
+    return 0.0 if num == 0 else float("inf")
 
 
 def row_rel_l2(y_test, y_ref) -> np.ndarray:

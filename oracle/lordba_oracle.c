@@ -1,5 +1,5 @@
 /*
- * LoRDBA adapter forward branch: CPU oracle.
+ * LoRDBA adapter branch (forward, and the backward pass of training): CPU oracle.
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, fp64 definition that
  * the GPU library is checked against.  Nothing in the product path may call it;
@@ -33,6 +33,12 @@
  * The batched forward (one adapter of a pool per token row) is pinned by running
  * the pinned one-adapter function on every group of rows separately, by the
  * pass-through rows, and by its invariance under any permutation of the rows.
+ * The backward pass (Sec. 3.2; Eq. (smoothsign); Alg. QAT-LoRDBA) is pinned by
+ * torch autograd in fp64 over Eq. (lordba-fwd) with a sign function whose
+ * derivative is the smooth-sign factor, by exact unit-step differences of the
+ * loss on a dense numpy DeltaW, by the contraction of X^T G in exact rationals,
+ * by the adjoint identity with the pinned forward, by Euler's relation for the
+ * three scale vectors, and by closed forms of the smooth-sign factor.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -374,5 +380,118 @@ int lordba_oracle_forward_batched(const uint16_t *x, const int8_t *signsA, const
     }
 done:
     free(alpha); free(beta); free(gamma); free(w); free(u);
+    return status;
+}
+
+/* ------------------------------------------------- backward of the branch ---- */
+
+/* Smooth-sign straight-through factor, Eq. (smoothsign): on the backward pass the derivative of sign(u)
+ * is replaced by d/du tanh(kappa u) = kappa (1 - tanh^2(kappa u)).  Written as kappa / cosh^2(kappa u),
+ * the same function without the cancellation of 1 - tanh^2 at large |kappa u|. */
+double lordba_oracle_smooth_sign_grad(double u, double kappa)
+{
+    double c = cosh(kappa * u);
+    return kappa / (c * c);
+}
+
+/* Gradients of a scalar loss through the branch (training of Sec. 3.2, "Forward and backward pass";
+ * Alg. QAT-LoRDBA), for given G = dL/dY:
+ *   forward, Eq. (lordba-fwd):  w = x D_alpha;  t = w B1;  u = t D_beta;  v = u B2;  y = y_base + v D_gamma
+ *   with B1 = sign(U1), B2 = sign(U2) (here S_A = B1^T, S_B = B2^T, and the latents in the same layouts:
+ *   latA[r, d_in] = U1^T, latB[d_out, r] = U2^T).
+ * Reverse mode, one token row after the other, every product written out:
+ *   d_gamma_j += g_j v_j            dv_j = g_j gamma_j
+ *   dB2[k,j]  += u_k dv_j           du_k = sum_j dv_j B2[k,j]
+ *   d_beta_k  += du_k t_k           dt_k = du_k beta_k
+ *   dB1[i,k]  += w_i dt_k           dw_i = sum_k dt_k B1[i,k]
+ *   d_alpha_i += dw_i x_i           dx_i = dx_base_i + dw_i alpha_i
+ * and at the end the carriers' gradients pass through the smooth-sign factor of Eq. (smoothsign):
+ *   d_latA[k,i] = dB1[i,k] * kappa (1 - tanh^2(kappa latA[k,i])),   d_latB[j,k] likewise from dB2[k,j].
+ * The carriers used are the given signs (the caller keeps them equal to sign(latent)); the scales are
+ * the fp16 values the forward pass used, at their exact values.
+ * x[T,d_in], g[T,d_out], dx_base[T,d_in] (may be NULL = 0): fp16 bit patterns.  latA, latB: binary32.
+ * Outputs (fp64): dx[T,d_in], d_s_in[d_in], d_s_rank[r], d_s_out[d_out], d_latA[r,d_in], d_latB[d_out,r].
+ * Returns 0, 2 on a bad dimension, 3 on a sign that is not +-1, 9 on malloc failure. */
+int lordba_oracle_backward(const uint16_t *x, const uint16_t *g, const int8_t *signsA, const int8_t *signsB,
+                           const uint16_t *s_in, const uint16_t *s_rank, const uint16_t *s_out,
+                           const float *latA, const float *latB, double kappa,
+                           const uint16_t *dx_base, double *dx,
+                           double *d_s_in, double *d_s_rank, double *d_s_out, double *d_latA, double *d_latB,
+                           int64_t T, int64_t d_in, int64_t d_out, int64_t r)
+{
+    if (T < 0 || d_in < 1 || d_out < 1 || r < 1) return 2;
+    for (int64_t n = 0; n < r * d_in; ++n) if (signsA[n] != 1 && signsA[n] != -1) return 3;
+    for (int64_t n = 0; n < d_out * r; ++n) if (signsB[n] != 1 && signsB[n] != -1) return 3;
+
+    double *alpha = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *beta = (double *)malloc(sizeof(double) * (size_t)r);
+    double *gamma = (double *)malloc(sizeof(double) * (size_t)d_out);
+    double *w = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *dw = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *v = (double *)malloc(sizeof(double) * (size_t)d_out);
+    double *dv = (double *)malloc(sizeof(double) * (size_t)d_out);
+    double *t = (double *)malloc(sizeof(double) * (size_t)r);
+    double *u = (double *)malloc(sizeof(double) * (size_t)r);
+    double *du = (double *)malloc(sizeof(double) * (size_t)r);
+    double *dt = (double *)malloc(sizeof(double) * (size_t)r);
+    int status = 0;
+    if (!alpha || !beta || !gamma || !w || !dw || !v || !dv || !t || !u || !du || !dt) { status = 9; goto done; }
+    lordba_oracle_f16_array_to_f64(s_in, alpha, d_in);
+    lordba_oracle_f16_array_to_f64(s_rank, beta, r);
+    lordba_oracle_f16_array_to_f64(s_out, gamma, d_out);
+
+    for (int64_t i = 0; i < d_in; ++i) d_s_in[i] = 0.0;
+    for (int64_t k = 0; k < r; ++k) d_s_rank[k] = 0.0;
+    for (int64_t j = 0; j < d_out; ++j) d_s_out[j] = 0.0;
+    for (int64_t n = 0; n < r * d_in; ++n) d_latA[n] = 0.0;      /* holds dB1 (as [r, d_in]) until the end */
+    for (int64_t n = 0; n < d_out * r; ++n) d_latB[n] = 0.0;     /* holds dB2 (as [d_out, r]) until the end */
+
+    for (int64_t row = 0; row < T; ++row) {
+        const uint16_t *xr = x + row * d_in, *gr = g + row * d_out;
+        /* forward intermediates of this row */
+        for (int64_t i = 0; i < d_in; ++i) w[i] = lordba_oracle_f16_to_f64(xr[i]) * alpha[i];
+        for (int64_t k = 0; k < r; ++k) {
+            double s = 0.0;
+            for (int64_t i = 0; i < d_in; ++i) s += w[i] * (double)signsA[k * d_in + i];
+            t[k] = s;
+            u[k] = s * beta[k];
+        }
+        for (int64_t j = 0; j < d_out; ++j) {
+            double s = 0.0;
+            for (int64_t k = 0; k < r; ++k) s += u[k] * (double)signsB[j * r + k];
+            v[j] = s;
+        }
+        /* reverse */
+        for (int64_t j = 0; j < d_out; ++j) {
+            double gj = lordba_oracle_f16_to_f64(gr[j]);
+            d_s_out[j] += gj * v[j];
+            dv[j] = gj * gamma[j];
+        }
+        for (int64_t k = 0; k < r; ++k) {
+            double s = 0.0;
+            for (int64_t j = 0; j < d_out; ++j) {
+                d_latB[j * r + k] += u[k] * dv[j];
+                s += dv[j] * (double)signsB[j * r + k];
+            }
+            du[k] = s;
+            d_s_rank[k] += s * t[k];
+            dt[k] = s * beta[k];
+        }
+        for (int64_t i = 0; i < d_in; ++i) {
+            double s = 0.0;
+            for (int64_t k = 0; k < r; ++k) {
+                d_latA[k * d_in + i] += w[i] * dt[k];
+                s += dt[k] * (double)signsA[k * d_in + i];
+            }
+            dw[i] = s;
+            d_s_in[i] += s * lordba_oracle_f16_to_f64(xr[i]);
+            double base = dx_base ? lordba_oracle_f16_to_f64(dx_base[row * d_in + i]) : 0.0;
+            dx[row * d_in + i] = base + s * alpha[i];
+        }
+    }
+    for (int64_t n = 0; n < r * d_in; ++n) d_latA[n] *= lordba_oracle_smooth_sign_grad((double)latA[n], kappa);
+    for (int64_t n = 0; n < d_out * r; ++n) d_latB[n] *= lordba_oracle_smooth_sign_grad((double)latB[n], kappa);
+done:
+    free(alpha); free(beta); free(gamma); free(w); free(dw); free(v); free(dv); free(t); free(u); free(du); free(dt);
     return status;
 }

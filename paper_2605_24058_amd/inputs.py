@@ -147,6 +147,23 @@ def make_inputs(seed: int, T: int, d_in: int, d_out: int, r: int) -> Dict[str, n
     return out
 
 
+def make_backward_inputs(seed: int, T: int, d_in: int, d_out: int, r: int, g_scale: float = 1.0) -> Dict[str, np.ndarray]:
+    """All tensors of one backward call of the branch in training: the forward tensors of make_inputs, the upstream
+    gradient g ~ g_scale * N(0,1) [T, d_out] and the base path's input gradient dx_base ~ g_scale * N(0,1) [T, d_in]
+    (fp16), and real-valued latent carriers in the carriers' layouts (float32): each latent entry is the carrier's
+    sign times a magnitude |N(0, 1/d)| with d the long side of its matrix, the size of the entries of the orthonormal
+    factors of a thin singular value decomposition from which training starts (magnitudes near 1/sqrt(d))."""
+    out = make_inputs(seed, T, d_in, d_out, r)
+    g = _rng(seed, 6)
+    out["g"] = (g_scale * g.standard_normal((T, d_out), dtype=np.float32)).astype(np.float16)
+    out["dx_base"] = (g_scale * g.standard_normal((T, d_in), dtype=np.float32)).astype(np.float16)
+    magA = np.abs(g.standard_normal((r, d_in), dtype=np.float32)) / np.float32(np.sqrt(d_in))
+    magB = np.abs(g.standard_normal((d_out, r), dtype=np.float32)) / np.float32(np.sqrt(d_out))
+    out["latA"] = (out["signsA"].astype(np.float32) * magA).astype(np.float32)
+    out["latB"] = (out["signsB"].astype(np.float32) * magB).astype(np.float32)
+    return out
+
+
 def make_inputs_for(shape: Shape, seed: int) -> Dict[str, np.ndarray]:
     return make_inputs(seed, shape.T, shape.d_in, shape.d_out, shape.r)
 
