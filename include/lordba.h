@@ -45,7 +45,8 @@ enum {
     LORDBA_ERR_ALIGN = 5,     /* a pointer is not aligned to its element size                 */
     LORDBA_ERR_NO_DEVICE = 6, /* no usable HIP device / not a gfx950 device                   */
     LORDBA_ERR_LAUNCH = 7,    /* the HIP runtime rejected the launch                          */
-    LORDBA_ERR_ALGO = 8       /* lordba_forward_algo: the requested kernel cannot run this shape */
+    LORDBA_ERR_ALGO = 8,      /* lordba_forward_algo: the requested kernel cannot run this shape */
+    LORDBA_ERR_WORKSPACE = 9  /* lordba_backward: the workspace is smaller than lordba_backward_workspace_bytes */
 };
 
 #define LORDBA_MAX_RANK 64
@@ -159,6 +160,44 @@ lordba_status lordba_forward_batched_algo(const void* x, const uint32_t* packedA
                                           const int32_t* adapter_of_row, const void* y_base, void* y_out,
                                           int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t n_adapters,
                                           void* stream, int algo);
+
+/* DEVICE function: the backward pass of the branch in training (Sec. 3.2, "Forward and backward pass"; Alg. QAT-LoRDBA;
+ * smooth-sign straight-through factor of Eq. (smoothsign)).  For Y = Y_base + X diag(s_in) S_A^T diag(s_rank) S_B^T diag(s_out)
+ * with S_A = sign(latentA), S_B = sign(latentB), and an upstream gradient g = dL/dY, it computes
+ *   dx        = dx_base + g DeltaW^T                                  fp16 [T, d_in]   (one rounding, as lordba_forward)
+ *   d_s_in, d_s_rank, d_s_out                                        fp32 [d_in], [r], [d_out]
+ *   d_latentA = dL/dS_A * kappa (1 - tanh^2(kappa latentA))           fp32 [r, d_in]
+ *   d_latentB = dL/dS_B * kappa (1 - tanh^2(kappa latentB))           fp32 [d_out, r]
+ * Inputs (device memory, row-major, contiguous, caller-owned):
+ *   x fp16 [T, d_in]; g fp16 [T, d_out]; s_in, s_rank, s_out fp16: the values the forward pass used (the optimiser's fp32
+ *   master copies are the caller's; Sec. 3.2 trains the scales in fp32); latentA fp32 [r, d_in], latentB fp32 [d_out, r];
+ *   kappa: the temperature of Eq. (smoothsign) (100 by default in the paper);
+ *   packedA : S_A   as [r, d_in]    (the forward pass's packedA)
+ *   packedAt: S_A^T as [d_in, r]    packedBt: S_B^T as [r, d_out]     (the same canonical format, transposed matrices;
+ *             the carriers are taken from these bits, which the caller keeps equal to the signs of the latents)
+ *   dx_base fp16 [T, d_in]: the input gradient of the base path, to which the branch's is added; dx may be the same
+ *   pointer.  dx == NULL and dx_base == NULL together: the input gradient is not computed.
+ *   workspace: at least lordba_backward_workspace_bytes(T, d_in, d_out, r) bytes of device memory, 16-byte aligned, owned
+ *   by the caller, contents irrelevant before and after; a smaller one -> LORDBA_ERR_WORKSPACE.  Calls that share a
+ *   workspace must not overlap in time.
+ * No output may overlap an input or another output (dx == dx_base excepted); this is not checked.
+ * Shapes: d_in and d_out multiples of 32, 1 <= r <= 64, x / g / s_in / s_out 16-byte aligned; else LORDBA_ERR_DIM /
+ * LORDBA_ERR_ALIGN.  T == 0: the parameter gradients are set to zero.
+ * The call only enqueues kernels on `stream`; it never synchronises, allocates or frees.  Results are deterministic
+ * (fixed summation order).  Arithmetic: fp16 inputs at their exact values, fp32 accumulation; every gradient array is
+ * within 1e-3 relative L2 (per token row for dx, per rank for the latents, whole vector for the scales) of the exact result. */
+lordba_status lordba_backward(const void* x, const void* g,
+                              const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
+                              const void* s_in, const void* s_rank, const void* s_out,
+                              const float* latentA, const float* latentB, float kappa,
+                              const void* dx_base, void* dx,
+                              float* d_s_in, float* d_s_rank, float* d_s_out,
+                              float* d_latentA, float* d_latentB,
+                              void* workspace, size_t workspace_bytes,
+                              int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream);
+
+/* Bytes of workspace lordba_backward needs for a shape (0 for a shape it does not support). */
+size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, int64_t r);
 
 /* Static, never-NULL description of a status code. */
 const char* lordba_status_string(lordba_status status);

@@ -18,7 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
 _LIB_PATH = os.path.join(_PKG, "liblordba.so")
-_SOURCES = ("lordba_forward.hip", "lordba_forward_multi.hip", "lordba_pack.cpp")
+_SOURCES = ("lordba_forward.hip", "lordba_forward_multi.hip", "lordba_backward.hip", "lordba_pack.cpp")
 _lib = None
 
 ALGO_AUTO, ALGO_GENERAL, ALGO_MFMA_T8, ALGO_MFMA_T16 = 0, 1, 2, 3
@@ -132,6 +132,10 @@ def load_library():
         f = getattr(lib, name)
         f.restype = ci
         f.argtypes = [vp] * 9 + [i64] * 5 + extra
+    lib.lordba_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.lordba_backward_workspace_bytes.argtypes = [i64] * 4
+    lib.lordba_backward.restype = ci
+    lib.lordba_backward.argtypes = [vp] * 10 + [ctypes.c_float] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 4 + [vp]
     lib.lordba_status_string.restype = ctypes.c_char_p
     lib.lordba_status_string.argtypes = [ci]
     _lib = lib
@@ -322,6 +326,77 @@ def lordba_forward_batched(x, packedA_pool, packedB_pool, s_in_pool, s_rank_pool
     if st != 0:
         raise LordbaError(st, "lordba_forward_batched")
     return y_out
+
+
+def lordba_backward_workspace_bytes(T: int, d_in: int, d_out: int, r: int) -> int:
+    return int(load_library().lordba_backward_workspace_bytes(T, d_in, d_out, r))
+
+
+def lordba_pack_transposed(signsA, signsB) -> Tuple[np.ndarray, np.ndarray]:
+    """The two extra packed carriers lordba_backward takes: S_A^T as [d_in, r] and S_B^T as [r, d_out], packed by the
+    library's host packer in the canonical format.  Returns (packedAt, packedBt)."""
+    A = np.ascontiguousarray(np.asarray(signsA).T)   # [d_in, r]
+    B = np.ascontiguousarray(np.asarray(signsB).T)   # [r, d_out]
+    # lordba_pack_signs(signsA [r', d_in'], signsB [d_out', r']) with r' = r, d_in' = d_out, d_out' = d_in
+    pBt, pAt = lordba_pack_signs(B, A)
+    return pAt, pBt
+
+
+def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa: float,
+                    dx_base=None, dx=None, workspace=None, stream=None, check: bool = True) -> dict:
+    """Gradients of the branch on the GPU (see include/lordba.h).  All tensors are torch CUDA tensors: x [T, d_in],
+    g [T, d_out], s_* float16; packed* int32; latentA [r, d_in], latentB [d_out, r] float32; dx_base [T, d_in] float16
+    or None (then no input gradient is computed).  workspace: a uint8 CUDA tensor of at least
+    lordba_backward_workspace_bytes(...) bytes (allocated here if None).  Returns a dict of new tensors dx (or None),
+    d_s_in, d_s_rank, d_s_out, d_latentA, d_latentB; enqueues on `stream` without synchronising."""
+    import torch
+
+    lib = load_library()
+    if check:
+        for name, t_ in (("x", x), ("g", g), ("s_in", s_in), ("s_rank", s_rank), ("s_out", s_out)):
+            if t_.dtype != torch.float16 or not t_.is_cuda or not t_.is_contiguous():
+                raise TypeError("%s must be a contiguous float16 CUDA tensor" % name)
+        for name, t_ in (("packedA", packedA), ("packedAt", packedAt), ("packedBt", packedBt)):
+            if t_.dtype != torch.int32 or not t_.is_cuda or not t_.is_contiguous():
+                raise TypeError("%s must be a contiguous int32 CUDA tensor holding the packed words" % name)
+        for name, t_ in (("latentA", latentA), ("latentB", latentB)):
+            if t_.dtype != torch.float32 or not t_.is_cuda or not t_.is_contiguous():
+                raise TypeError("%s must be a contiguous float32 CUDA tensor" % name)
+        if x.dim() != 2 or g.dim() != 2 or x.shape[0] != g.shape[0]:
+            raise ValueError("x must be [T, d_in] and g [T, d_out]")
+    T, d_in = x.shape
+    d_out = g.shape[1]
+    r = s_rank.numel()
+    if check:
+        if s_in.numel() != d_in or s_out.numel() != d_out or tuple(latentA.shape) != (r, d_in) or tuple(latentB.shape) != (d_out, r):
+            raise ValueError("scale / latent shapes do not match x / g")
+        words = ((r * d_in + 31) // 32, (r * d_out + 31) // 32)
+        if packedA.numel() != words[0] or packedAt.numel() != words[0] or packedBt.numel() != words[1]:
+            raise ValueError("packed carrier lengths do not match the shape")
+        if dx_base is not None and (dx_base.dtype != torch.float16 or not dx_base.is_cuda or not dx_base.is_contiguous()
+                                    or dx_base.shape != x.shape):
+            raise TypeError("dx_base must be a contiguous float16 CUDA tensor shaped like x")
+    need = lordba_backward_workspace_bytes(T, d_in, d_out, r)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    if dx_base is not None and dx is None:
+        dx = torch.empty_like(dx_base)
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=x.device)
+    out = {"dx": dx, "d_s_in": f32(d_in), "d_s_rank": f32(r), "d_s_out": f32(d_out),
+           "d_latentA": f32(r, d_in), "d_latentB": f32(d_out, r)}
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    ptr = lambda t_: None if t_ is None else t_.data_ptr()
+    st = lib.lordba_backward(x.data_ptr(), g.data_ptr(), packedA.data_ptr(), packedAt.data_ptr(), packedBt.data_ptr(),
+                             s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(), latentA.data_ptr(), latentB.data_ptr(),
+                             float(kappa), ptr(dx_base), ptr(dx), out["d_s_in"].data_ptr(), out["d_s_rank"].data_ptr(),
+                             out["d_s_out"].data_ptr(), out["d_latentA"].data_ptr(), out["d_latentB"].data_ptr(),
+                             workspace.data_ptr(), workspace.numel(), T, d_in, d_out, r, ctypes.c_void_p(stream))
+    if st != 0:
+        raise LordbaError(st, "lordba_backward")
+    return out
 
 
 def to_device(inputs: dict, device="cuda:0") -> dict:

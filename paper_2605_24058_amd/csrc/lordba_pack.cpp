@@ -98,6 +98,7 @@ extern "C" const char* lordba_status_string(lordba_status status) {
         case LORDBA_ERR_NO_DEVICE: return "no usable gfx950 HIP device";
         case LORDBA_ERR_LAUNCH: return "HIP runtime rejected the kernel launch";
         case LORDBA_ERR_ALGO: return "requested kernel cannot run this shape or alignment";
+        case LORDBA_ERR_WORKSPACE: return "workspace smaller than lordba_backward_workspace_bytes";
         default: return "unknown status";
     }
 }

@@ -1,0 +1,215 @@
+"""GPU parity of the branch's backward pass (lordba_backward, through the C ABI) against the fp64 CPU oracle on the
+same seeded inputs.  Bar (fp16 activations, fp32 accumulation): relative L2 error <= 1e-3
+  * per token row for dx (as configured, and with dx_base = 0 so that the branch's share cannot hide),
+  * over the whole vector for d_s_in, d_s_rank, d_s_out,
+  * per rank for the latent gradients (row k of d_latentA [r, d_in], column k of d_latentB [d_out, r]).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_24058_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-3
+KAPPA = 100.0
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load_library()
+    return torch
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+GUARD = 4096
+
+
+def new_workspace(torch, nbytes, fill=0xFF):
+    """nbytes of workspace followed by a guard band, all set to `fill`."""
+    return torch.full((nbytes + GUARD,), fill, dtype=torch.uint8, device="cuda:0")
+
+
+def gpu_backward(torch, d, kappa=KAPPA, with_dx=True, inplace=False, ws=None, ws_bytes=None):
+    """Runs the library on cuda:0.  ws: a buffer from new_workspace (its last GUARD bytes must stay untouched); by default
+    a fresh poisoned one of exactly the size the library asks for: the call must not depend on the workspace's contents
+    nor write past it.  ws_bytes: the size reported to the library (default: everything before the guard band)."""
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    pA, _ = binding.lordba_pack_signs(d["signsA"], d["signsB"])
+    pAt, pBt = binding.lordba_pack_transposed(d["signsA"], d["signsB"])
+    T, d_in = d["x"].shape
+    d_out, r = d["signsB"].shape
+    if ws is None:
+        ws = new_workspace(torch, binding.lordba_backward_workspace_bytes(T, d_in, d_out, r))
+    fill = int(ws[-1].item())
+    usable = ws.numel() - GUARD if ws_bytes is None else ws_bytes
+    dxb = cu(d["dx_base"]) if with_dx else None
+    out = binding.lordba_backward(cu(d["x"]), cu(d["g"]), cu(pA.view(np.int32)), cu(pAt.view(np.int32)), cu(pBt.view(np.int32)),
+                                  cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]), cu(d["latA"]), cu(d["latB"]), kappa,
+                                  dx_base=dxb, dx=dxb if inplace else None, workspace=ws[:usable])
+    torch.cuda.synchronize()
+    assert (ws[ws.numel() - GUARD:].cpu().numpy() == fill).all(), "write past the workspace"
+    return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}
+
+
+def oracle_backward(d, kappa=KAPPA, with_dx=True):
+    return oracle.backward(d["x"], d["g"], d["signsA"], d["signsB"], d["s_in"], d["s_rank"], d["s_out"], d["latA"], d["latB"],
+                           kappa, d["dx_base"] if with_dx else None)
+
+
+def compare(got, want, label, with_dx=True):
+    worst = {}
+    if with_dx:
+        e = oracle.row_rel_l2(got["dx"].astype(np.float64), want["dx"])
+        assert e.max() <= TOL, "%s dx: max row rel-L2 %.3e at row %d" % (label, e.max(), e.argmax())
+        worst["dx"] = e.max()
+    for k in ("d_s_in", "d_s_rank", "d_s_out"):
+        assert np.isfinite(got[k]).all(), "%s %s: non-finite" % (label, k)
+        e = oracle.rel_l2(got[k], want[k])
+        assert e <= TOL, "%s %s: rel-L2 %.3e" % (label, k, e)
+        worst[k] = e
+    eA = oracle.row_rel_l2(got["d_latentA"].astype(np.float64), want["d_latA"])
+    assert eA.max() <= TOL, "%s d_latentA: max rel-L2 %.3e at rank %d" % (label, eA.max(), eA.argmax())
+    eB = oracle.row_rel_l2(got["d_latentB"].astype(np.float64).T, want["d_latB"].T)
+    assert eB.max() <= TOL, "%s d_latentB: max rel-L2 %.3e at rank %d" % (label, eB.max(), eB.argmax())
+    worst["d_latentA"], worst["d_latentB"] = eA.max(), eB.max()
+    say("  %s: " % label + " ".join("%s %.2e" % kv for kv in worst.items()))
+    return worst
+
+
+def check(torch, d, label, kappa=KAPPA, dx_subnormal=False):
+    say("  case %s" % label)
+    got = gpu_backward(torch, d, kappa)
+    compare(got, oracle_backward(d, kappa), label)
+    # the branch's share of dx alone
+    dd = dict(d, dx_base=np.zeros_like(d["dx_base"]))
+    got0 = gpu_backward(torch, dd, kappa)
+    want0 = oracle_backward(dd, kappa)["dx"]
+    if dx_subnormal:
+        # the branch's share lies below the smallest normal fp16 (2^-14), where the output format itself has an absolute
+        # spacing of 2^-24: the bar is one such step
+        assert np.abs(want0).max() < 2.0 ** -14
+        assert np.abs(got0["dx"].astype(np.float64) - want0).max() <= 2.0 ** -24, label
+    else:
+        e = oracle.row_rel_l2(got0["dx"].astype(np.float64), want0)
+        assert e.max() <= TOL, "%s dx (branch alone): %.3e" % (label, e.max())
+    for k in ("d_s_in", "d_s_rank", "d_s_out", "d_latentA", "d_latentB"):
+        assert np.array_equal(got[k], got0[k]), "%s: %s depends on dx_base" % (label, k)
+
+
+# (T, d_in, d_out, r): several tiles of 8 rows and a ragged last one, 128-column blocks with a tail (d = 32 * odd),
+# every rank-block count, T below one tile and below one 32-row step
+SHAPES = [
+    (64, 512, 512, 4),        # the small benchmark configuration
+    (37, 1024, 1152, 16),
+    (1, 512, 384, 16),
+    (8, 256, 256, 8),
+    (203, 1056, 2080, 16),    # 33 and 65 words per carrier row: partial last column blocks
+    (70, 1024, 768, 32),
+    (45, 640, 1024, 48),
+    (33, 512, 1024, 64),
+    (130, 32, 96, 5),         # the smallest widths, a rank that is not a multiple of 8
+    (519, 2048, 1536, 16),    # several 32-row steps per wave
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "T%d_%dx%d_r%d" % s)
+def test_small_shapes_all_outputs(torch_cuda, shape):
+    T, d_in, d_out, r = shape
+    d = inputs.make_backward_inputs(21, T, d_in, d_out, r)
+    check(torch_cuda, d, "T%d_%dx%d_r%d" % shape)
+
+
+def test_sixteen_row_tiles(torch_cuda):
+    """T >= 4096 takes 16-row tiles in the rank kernel; ragged last tile."""
+    d = inputs.make_backward_inputs(22, 4100, 256, 384, 16)
+    check(torch_cuda, d, "T4100_256x384_r16")
+    d = inputs.make_backward_inputs(23, 4133, 512, 256, 32)
+    check(torch_cuda, d, "T4133_512x256_r32")
+
+
+@pytest.mark.parametrize("g_scale", [2.0 ** -14, 2.0 ** -7, 16.0])
+def test_gradient_magnitudes(torch_cuda, g_scale):
+    """Upstream gradients far from 1 (loss-scaled or tiny): the per-rank power-of-two scaling keeps the precision."""
+    d = inputs.make_backward_inputs(24, 100, 1024, 512, 16, g_scale=g_scale)
+    check(torch_cuda, d, "g_scale_%g" % g_scale, dx_subnormal=g_scale < 2.0 ** -10)
+
+
+def test_uneven_rank_scales(torch_cuda):
+    """Rank scales spread over many orders of magnitude, a zero (how extra envelopes start) and negative ones."""
+    d = inputs.make_backward_inputs(25, 96, 512, 768, 16)
+    s = d["s_rank"].astype(np.float32)
+    s *= np.array([1, -1, 2.0 ** -10, 2.0 ** 6, 0, 1, -2.0 ** -12, 1, 1, 64, 1, -1, 2.0 ** -8, 1, 1, 3], dtype=np.float32)
+    d["s_rank"] = s.astype(np.float16)
+    got = gpu_backward(torch_cuda, d)
+    want = oracle_backward(d)
+    compare(got, want, "uneven_rank_scales")
+    assert not got["d_latentA"][4].any() and not got["d_latentB"][:, 4].any()   # beta_4 = 0: exact zeros
+    assert got["d_s_rank"][4] != 0
+
+
+@pytest.mark.parametrize("kappa", [0.0, 1.0, 25.0, 400.0])
+def test_temperatures(torch_cuda, kappa):
+    d = inputs.make_backward_inputs(26, 50, 512, 512, 8)
+    got = gpu_backward(torch_cuda, d, kappa)
+    compare(got, oracle_backward(d, kappa), "kappa_%g" % kappa)
+    if kappa == 0.0:
+        assert not got["d_latentA"].any() and not got["d_latentB"].any()
+
+
+def test_without_input_gradient_and_in_place(torch_cuda):
+    d = inputs.make_backward_inputs(27, 77, 768, 512, 16)
+    want = oracle_backward(d)
+    got = gpu_backward(torch_cuda, d, with_dx=False)
+    assert got["dx"] is None
+    compare(got, want, "no_dx", with_dx=False)
+    got_ip = gpu_backward(torch_cuda, d, inplace=True)
+    compare(got_ip, want, "dx_in_place")
+
+
+def test_deterministic_and_workspace_reuse(torch_cuda):
+    """The result does not depend on what the workspace held; two calls in a row on one workspace, the second on a
+    smaller shape, give what fresh workspaces give, bit for bit."""
+    torch = torch_cuda
+    big = inputs.make_backward_inputs(28, 300, 1024, 1024, 32)
+    small = inputs.make_backward_inputs(29, 40, 512, 256, 8)
+    need = binding.lordba_backward_workspace_bytes(300, 1024, 1024, 32)
+    assert 0 < binding.lordba_backward_workspace_bytes(40, 512, 256, 8) <= need
+    a1 = gpu_backward(torch, big)
+    a2 = gpu_backward(torch, big, ws=new_workspace(torch, need, fill=0x00))
+    shared = new_workspace(torch, need, fill=0x7F)
+    a3 = gpu_backward(torch, big, ws=shared)
+    s2 = gpu_backward(torch, small, ws=shared)          # right after, on the same (now used) buffer
+    s1 = gpu_backward(torch, small)
+    for k in a1:
+        assert np.array_equal(a1[k], a2[k]) and np.array_equal(a1[k], a3[k]), k
+        assert np.array_equal(s1[k], s2[k]), k
+    compare(s2, oracle_backward(small), "small_after_big")
+
+
+def test_headline_shape(torch_cuda):
+    """d_in = d_out = 4096, r = 16, T = 2048 (the launch configuration bench.py times), every output against the oracle."""
+    d = inputs.make_backward_inputs(30, 2048, 4096, 4096, 16)
+    got = gpu_backward(torch_cuda, d)
+    compare(got, oracle_backward(d), "c2_backward")
+
+
+def test_argument_errors(torch_cuda):
+    torch = torch_cuda
+    d = inputs.make_backward_inputs(31, 16, 256, 256, 8)
+    need = binding.lordba_backward_workspace_bytes(16, 256, 256, 8)
+    assert need > 0
+    with pytest.raises(binding.LordbaError) as e:
+        gpu_backward(torch, d, ws=new_workspace(torch, need), ws_bytes=need - 16)
+    assert e.value.status == 9
+    assert binding.lordba_backward_workspace_bytes(16, 250, 256, 8) == 0      # d_in not a multiple of 32
+    assert binding.lordba_backward_workspace_bytes(16, 256, 256, 65) == 0
