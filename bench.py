@@ -213,6 +213,78 @@ def bench_c5_model(args):
     print(json.dumps(out))
 
 
+def backward_algorithmic_bytes(sh):
+    """What one backward call of the branch must move: x, g, dx_base read and dx written once (fp16); the three packed
+    carriers it takes; the fp16 scales; the fp32 latents read and the fp32 gradients of latents and scales written."""
+    act = 2 * sh.T * (3 * sh.d_in + sh.d_out)
+    carriers = (sh.r * (2 * sh.d_in + sh.d_out) + 7) // 8
+    scales = 2 * (sh.d_in + sh.r + sh.d_out)
+    latents = 4 * sh.r * (sh.d_in + sh.d_out)
+    grads = latents + 4 * (sh.d_in + sh.r + sh.d_out)
+    return act + carriers + scales + latents + grads
+
+
+def bench_backward(args):
+    """One step = one lordba_backward call (input gradient, scale gradients, latent-carrier gradients through the
+    smooth-sign factor) on HBM-resident inputs, cycling through enough buffer sets to defeat the Infinity Cache."""
+    import numpy as np
+    import torch
+    from paper_2605_24058_amd import binding, inputs
+    K, W = args.steps, args.warmup
+    use_graph = not args.no_graph
+    sh = _workloads()[args.workload]
+    per_set = 2 * sh.T * (3 * sh.d_in + sh.d_out)
+    sets = args.sets if args.sets > 0 else max(2, -(-2 * CACHE_BYTES // per_set) + 1)
+    host0 = inputs.make_backward_inputs(args.seed, sh.T, sh.d_in, sh.d_out, sh.r)
+    pA, _ = binding.lordba_pack_signs(host0["signsA"], host0["signsB"])
+    pAt, pBt = binding.lordba_pack_transposed(host0["signsA"], host0["signsB"])
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    dev = {k: cu(host0[k]) for k in ("s_in", "s_rank", "s_out", "latA", "latB")}
+    dev.update(pA=cu(pA.view(np.int32)), pAt=cu(pAt.view(np.int32)), pBt=cu(pBt.view(np.int32)))
+    xs, gs, dxbs, dxs = [], [], [], []
+    for s_ in range(sets):
+        h = host0 if s_ == 0 else inputs.make_backward_inputs(args.seed + 1000 * s_, sh.T, sh.d_in, sh.d_out, sh.r)
+        xs.append(cu(h["x"])); gs.append(cu(h["g"])); dxbs.append(cu(h["dx_base"])); dxs.append(torch.empty_like(dxbs[-1]))
+    ws = torch.empty(binding.lordba_backward_workspace_bytes(sh.T, sh.d_in, sh.d_out, sh.r), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    outs = {}
+
+    def step(i):
+        s_ = i % sets
+        outs[s_] = binding.lordba_backward(xs[s_], gs[s_], dev["pA"], dev["pAt"], dev["pBt"], dev["s_in"], dev["s_rank"],
+                                           dev["s_out"], dev["latA"], dev["latB"], args.kappa, dx_base=dxbs[s_], dx=dxs[s_],
+                                           workspace=ws, check=False)
+
+    reps_us, wall_s = timed(step, K, max(W, sets), use_graph, reps=3)
+    call_us = reps_us[0]
+    alg = backward_algorithmic_bytes(sh)
+    achieved = alg / (call_us * 1e-6) / 1e9
+    out = {"metric": "adapter-branch backward (dx, scale and latent-carrier gradients) tokens/s and achieved HBM GB/s",
+           "value": sh.T * K / wall_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": wall_s * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "io_dtype": "f16", "data": "synthetic",
+           "config": {"workload": sh.name, "pass": "backward", "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
+                      "kappa": args.kappa, "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
+           "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                        "traffic": None, "kernel_us": call_us, "kernel_us_repetitions": reps_us, "algorithmic_bytes": alg,
+                        "note": "all kernels of one call taken together (clear, dx, rank, wgrad, finish)"}}
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(sh.T, 256)
+        c0 = time.perf_counter()
+        want = oracle.backward(host0["x"][:rows], host0["g"][:rows], host0["signsA"], host0["signsB"], host0["s_in"],
+                               host0["s_rank"], host0["s_out"], host0["latA"], host0["latB"], args.kappa, host0["dx_base"][:rows])
+        c1 = time.perf_counter()
+        step(0)
+        torch.cuda.synchronize()
+        err = float(oracle.row_rel_l2(dxs[0][:rows].cpu().numpy().astype(np.float64), want["dx"]).max())
+        out["cpu_baseline"] = {"value": rows / (c1 - c0), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                               "sample": "the first %d of %d token rows of the same workload, one host thread" % (rows, sh.T)}
+        out["parity_max_row_rel_l2_dx"] = err
+        out["parity_ok"] = bool(err <= 1e-3)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -229,6 +301,9 @@ def main():
     ap.add_argument("--id-pattern", choices=["segments", "decode", "mixed"], default="segments",
                     help="adapter index per token row: sorted segments (prefill of several requests), independent draws "
                          "(decode, one token per request) or segments with rows that have no adapter")
+    ap.add_argument("--backward", action="store_true", help="time lordba_backward (the branch's backward pass in training) "
+                    "instead of the forward call; single-shape workloads only")
+    ap.add_argument("--kappa", type=float, default=100.0, help="temperature of the smooth-sign factor (--backward)")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to cycle through (0 = enough to defeat the cache)")
     ap.add_argument("--algo", type=int, default=0, help="kernel selector passed to lordba_forward_algo (0 = library default)")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
@@ -261,6 +336,9 @@ def main():
     args.warmup = 240 if args.warmup is None else args.warmup
     if args.workload == "c4_sweep":
         return bench_c4_sweep(args)
+    if args.backward:
+        args.steps = min(args.steps, 600)
+        return bench_backward(args)
     sh = _workloads()[args.workload]
 
     # ---- inputs: one adapter, `sets` activation sets, all resident in HBM before timing ------------------------

@@ -34,16 +34,17 @@
 namespace {
 
 constexpr int kWgradWaves = 4;        // waves per workgroup of the wgrad kernel, each with its own token range
-constexpr int kWgradTargetWgs = 512;  // workgroups the wgrad grid aims at (two per CU)
+constexpr int kWgradTargetWgs = 256;  // workgroups the wgrad grid aims at (one per CU; more only adds partial sums)
+constexpr int kWgradGroup = 4;        // 32-row steps a wave of the wgrad kernel keeps in flight (2 from three rank blocks on)
 
 struct BwdPlan {
     int rp;          // ranks padded to a multiple of 16
-    int t_pad;       // token rows padded to a multiple of 32
+    int t_pad;       // token rows padded to a multiple of 128 (a group of the wgrad kernel)
     int tmv;         // token rows per tile of the rank kernel
     int tiles;       // tiles of the rank kernel
     int nbx, nbg;    // 128-column blocks of d_in and of d_out
     int dcols;       // columns of one partial-sum plane: (nbx + nbg) * 128
-    int tw;          // token rows per wave of the wgrad kernel (multiple of 32)
+    int tw;          // token rows per wave of the wgrad kernel (multiple of 128)
     int splits;      // workgroups along the token axis of the wgrad kernel
     // workspace layout, in 4-byte words
     size_t off_max, off_u, off_dt, off_dbeta, off_part, words;
@@ -52,19 +53,19 @@ struct BwdPlan {
 BwdPlan make_plan(int64_t T, int64_t d_in, int64_t d_out, int64_t r) {
     BwdPlan p;
     p.rp = static_cast<int>((r + 15) / 16 * 16);
-    p.t_pad = static_cast<int>((T + 31) / 32 * 32);
+    p.t_pad = static_cast<int>((T + 127) / 128 * 128);
     p.tmv = T >= 4096 ? 16 : 8;
     p.tiles = static_cast<int>((T + p.tmv - 1) / p.tmv);
     p.nbx = static_cast<int>((d_in + 127) / 128);
     p.nbg = static_cast<int>((d_out + 127) / 128);
     p.dcols = (p.nbx + p.nbg) * 128;
-    const int steps = p.t_pad / 32;
+    const int steps = p.t_pad / (32 * kWgradGroup);  // groups of steps: a wave takes whole groups
     int splits = (kWgradTargetWgs + p.nbx + p.nbg - 1) / (p.nbx + p.nbg);
     const int max_splits = (steps + kWgradWaves - 1) / kWgradWaves;  // at least one step per wave
     splits = splits > max_splits ? max_splits : splits;
     splits = splits < 1 ? 1 : splits;
     const int steps_per_wave = (steps + splits * kWgradWaves - 1) / (splits * kWgradWaves);
-    p.tw = steps_per_wave * 32;
+    p.tw = steps_per_wave * 32 * kWgradGroup;
     p.splits = (steps + steps_per_wave * kWgradWaves - 1) / (steps_per_wave * kWgradWaves);
     p.off_max = 0;
     p.off_u = 128;
@@ -108,10 +109,10 @@ __global__ void bwd_zero_kernel(float* p, int64_t n) {
 }
 
 // ------------------------------------------------------------------------------------------ rank kernel ----
-// RB rank blocks of 16, TMV token rows per tile (8 or 16), NW waves.  The 128-column chunks of x (d_in) and of g (d_out)
-// form one list that is dealt round-robin to the waves; a chunk of x meets +-s_in built from S_A, a chunk of g meets
-// +-s_out built from S_B^T, and they accumulate into two separate tiles.
-template <int RB, int TMV, int NW>
+// RB rank blocks of 16, TMV token rows per tile (8 or 16), NW waves, DEPTH chunks in flight per wave.  The 128-column
+// chunks of x (d_in) and of g (d_out) form one list that is dealt round-robin to the waves; a chunk of x meets +-s_in
+// built from S_A, a chunk of g meets +-s_out built from S_B^T, and they accumulate into two separate tiles.
+template <int RB, int TMV, int NW, int DEPTH>
 __global__ __launch_bounds__(NW * 64) void lordba_bwd_rank_kernel(BwdArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int NI = TMV / 4;
@@ -129,9 +130,9 @@ __global__ __launch_bounds__(NW * 64) void lordba_bwd_rank_kernel(BwdArgs a) {
     const int nchunks = a.nbx + a.nbg;
     const int my_n = wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0;
 
-    u4 xbuf[2][NI];
-    uint32_t sbuf[2];
-    uint32_t bits[2][RB];
+    u4 xbuf[DEPTH][NI];
+    uint32_t sbuf[DEPTH];
+    uint32_t bits[DEPTH][RB];
     auto issue = [&](int slot, int n) {
         int c = wave + NW * n;
         c = c < nchunks ? c : nchunks - 1;  // past the end: re-read a valid chunk, the result is not used
@@ -143,8 +144,8 @@ __global__ __launch_bounds__(NW * 64) void lordba_bwd_rank_kernel(BwdArgs a) {
         const uint32_t* pk = is_x ? a.pA : a.pBt;
         const int words_per_row = d >> 5;  // d % 32 == 0 on this path
         const int pair = cc * 64 + lane;   // fp16 pair index of the scale slice
-        const uint32_t v = *reinterpret_cast<const uint32_t*>(sc + (pair * 2 < d ? pair * 2 : 0));
-        sbuf[slot] = pair * 2 < d ? v : 0u;  // columns past d get scale 0
+        // (columns past d get scale 0 when the chunk is consumed: nothing here may wait for a load)
+        sbuf[slot] = *reinterpret_cast<const uint32_t*>(sc + (pair * 2 < d ? pair * 2 : 0));
 #pragma unroll
         for (int m = 0; m < NI; ++m) {
             int row = m * 4 + q;
@@ -170,8 +171,10 @@ __global__ __launch_bounds__(NW * 64) void lordba_bwd_rank_kernel(BwdArgs a) {
         for (int rb = 0; rb < RB; ++rb) acc[s][rb] = f4{0.f, 0.f, 0.f, 0.f};
     }
     auto consume = [&](int slot, int n) {
-        const bool is_x = wave + NW * n < a.nbx;
-        reinterpret_cast<uint32_t*>(sw)[lane] = sbuf[slot];
+        const int c = wave + NW * n;
+        const bool is_x = c < a.nbx;
+        const bool in_range = ((is_x ? c : c - a.nbx) * 64 + lane) * 2 < (is_x ? a.d_in : a.d_out);
+        reinterpret_cast<uint32_t*>(sw)[lane] = in_range ? sbuf[slot] : 0u;
 #pragma unroll
         for (int m = 0; m < NI; ++m) store16(xs + (m * 4 + q) * kXRow + li * 8, xbuf[slot][m]);
         __builtin_amdgcn_wave_barrier();
@@ -190,16 +193,22 @@ __global__ __launch_bounds__(NW * 64) void lordba_bwd_rank_kernel(BwdArgs a) {
         __builtin_amdgcn_wave_barrier();
     };
 
-    if (my_n > 0) issue(0, 0);
-    if (my_n > 1) issue(1, 1);
-    for (int n = 0; n < my_n; n += 2) {
-        consume(0, n);
-        if (n + 2 < my_n) issue(0, n + 2);
-        if (n + 1 < my_n) {
-            consume(1, n + 1);
-            if (n + 3 < my_n) issue(1, n + 3);
+    // The first DEPTH chunks are requested without any condition (past the end a valid chunk is re-read and not used), and
+    // so is the next group's chunk after each consumed one: every wait then counts exactly the loads issued after the one
+    // it needs.  The last group is consumed without issuing anything.
+#pragma unroll
+    for (int slot = 0; slot < DEPTH; ++slot) issue(slot, slot);
+    int n0 = 0;
+    for (; n0 + DEPTH < my_n; n0 += DEPTH) {
+#pragma unroll
+        for (int slot = 0; slot < DEPTH; ++slot) {
+            consume(slot, n0 + slot);
+            issue(slot, n0 + DEPTH + slot);
         }
     }
+#pragma unroll
+    for (int slot = 0; slot < DEPTH; ++slot)
+        if (n0 + slot < my_n) consume(slot, n0 + slot);
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
 #pragma unroll
@@ -255,7 +264,7 @@ __global__ __launch_bounds__(NW * 64) void lordba_bwd_rank_kernel(BwdArgs a) {
             __hip_atomic_fetch_max(a.maxbits + 64 + rk, __float_as_uint(dmax), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    // The last tile also clears the padding rows up to t_pad, which the wgrad kernel reads as whole steps of 32 rows.
+    // The last tile also clears the padding rows up to t_pad, which the wgrad kernel reads as whole groups of steps.
     if (blockIdx.x == gridDim.x - 1) {
         const int from = static_cast<int>(t0) + TMV, n = a.t_pad - from;
         for (int e = lane; e < a.rp * n; e += 64) {
@@ -273,7 +282,10 @@ constexpr size_t rank_lds_bytes(int RB, int TMV, int NW) {
 // ----------------------------------------------------------------------------------------- wgrad kernel ----
 // Workgroup (cb, s): column block cb of x (cb < nbx: Q, with dt) or of g (P, with u), token rows [s * 4 tw, (s+1) * 4 tw),
 // a quarter per wave.  One step = 32 token rows x 128 columns.
-template <int RB>
+// G steps are in flight per wave: the loads of a group are issued without any condition (past the end of the wave's range
+// they re-read valid addresses and are not used), so that every wait counts exactly the loads issued after the one it
+// needs; the last group is consumed without issuing anything.
+template <int RB, int G>
 __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdArgs a) {
     __shared__ __align__(16) float red[kWgradWaves][8][64][4];
     // The wave index as a scalar: everything that depends on it (which chunks, how many steps) then branches on scalar
@@ -311,9 +323,10 @@ __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdA
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[rb][e] = f4{0.f, 0.f, 0.f, 0.f};
     }
-    u4 xb[2][8];
-    u4 sb[2][RB][2];
+    u4 xb[G][8];
+    u4 sb[G][RB][2];
     auto issue = [&](int slot, int tk) {
+        tk = tk < a.t_pad - 32 ? tk : a.t_pad - 32;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             int row = tk + 8 * q + e;
@@ -359,12 +372,20 @@ __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdA
             }
         }
     };
-    if (tk_begin < tk_end) issue(0, tk_begin);
-    for (int tk = tk_begin; tk < tk_end; tk += 64) {
-        if (tk + 32 < tk_end) issue(1, tk + 32);
-        consume(0);
-        if (tk + 64 < tk_end) issue(0, tk + 64);
-        if (tk + 32 < tk_end) consume(1);
+    // t_pad and tw are multiples of 32 G: a wave's range is a whole number of groups (possibly none)
+    if (tk_begin < tk_end) {
+#pragma unroll
+        for (int i = 0; i < G; ++i) issue(i, tk_begin + 32 * i);
+        int tk = tk_begin;
+        for (; tk + 32 * G < tk_end; tk += 32 * G) {
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                consume(i);
+                issue(i, tk + 32 * (G + i));
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < G; ++i) consume(i);
     }
 
     // Accumulator e, register i of lane (li, q): rank rb*16 + li, column 8 (4q + i) + e of the block.  The four waves'
@@ -398,46 +419,64 @@ __device__ __forceinline__ float smooth_sign_factor(float latent, float kappa) {
     return 4.f * kappa * e / (s * s);
 }
 
+// One workgroup per group of 32 columns of d_in (Q, d_s_in, d_latentA) or of d_out (P, d_s_out, d_latentB), plus one for
+// d_s_rank.  Thread (c, kq) takes column c of the group and ranks kq, kq + 8, ...; every sum has a fixed order.
 __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
-    const int ncol_blocks = (a.d_in + a.d_out + 255) / 256;
-    if (static_cast<int>(blockIdx.x) == ncol_blocks) {
-        // d_beta: the tiles' shares, summed in a fixed order (thread (k, c) takes tiles c, c + nc, ...; then the nc partial sums)
-        __shared__ float sh[256];
-        const int nc = 256 / a.rp, k = threadIdx.x % a.rp, c = threadIdx.x / a.rp;
+    __shared__ float sh[256];
+    __shared__ float lat[32 * LORDBA_MAX_RANK];
+    const int gx = a.d_in >> 5, gg = a.d_out >> 5;
+    const int tid = threadIdx.x;
+    if (static_cast<int>(blockIdx.x) == gx + gg) {
+        // d_beta: the tiles' shares (thread (k, c) takes tiles c, c + nc, ...; then the nc partial sums in order)
+        const int nc = 256 / a.rp, k = tid % a.rp, c = tid / a.rp;
         float s = 0.f;
         if (c < nc)
             for (int t = c; t < a.tiles; t += nc) s += a.dbeta_part[static_cast<size_t>(t) * a.rp + k];
-        sh[threadIdx.x] = s;
+        sh[tid] = s;
         __syncthreads();
-        if (static_cast<int>(threadIdx.x) < a.r) {
+        if (tid < a.r) {
             float tot = 0.f;
-            for (int cc = 0; cc < nc; ++cc) tot += sh[cc * a.rp + threadIdx.x];
-            a.d_s_rank[threadIdx.x] = tot;
+            for (int cc = 0; cc < nc; ++cc) tot += sh[cc * a.rp + tid];
+            a.d_s_rank[tid] = tot;
         }
         return;
     }
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= a.d_in + a.d_out) return;
-    const bool is_x = c < a.d_in;
-    const int col = is_x ? c : c - a.d_in;
+    const bool is_x = static_cast<int>(blockIdx.x) < gx;
+    const int grp = is_x ? blockIdx.x : blockIdx.x - gx;
     const int d = is_x ? a.d_in : a.d_out;
+    const int c = tid & 31, kq = tid >> 5;
+    const int col = grp * 32 + c;
     const float* plane = a.part + (is_x ? col : a.nbx * 128 + col);
-    const uint32_t* pk = is_x ? a.pA : a.pBt;
+    const uint32_t* pk = is_x ? a.pA : a.pBt;   // both [r, d]: the group's 32 bits of rank k are one word
     const float scale = static_cast<float>(is_x ? a.s_in[col] : a.s_out[col]);
+    const int r = a.r;
+    if (!is_x) {  // latentB [d_out, r]: the group's 32 rows are 32 r contiguous floats; through LDS for coalesced accesses
+        for (int e = tid; e < 32 * r; e += 256) lat[e] = a.latB[static_cast<size_t>(grp) * 32 * r + e];
+        __syncthreads();
+    }
     float dscale = 0.f;
-    for (int k = 0; k < a.r; ++k) {
+    for (int k = kq; k < r; k += 8) {
         float s = 0.f;
         for (int sp = 0; sp < a.splits; ++sp) s += plane[(static_cast<size_t>(sp) * a.rp + k) * a.dcols];
-        const int64_t n = static_cast<int64_t>(k) * d + col;
-        dscale += flip(s, (pk[n >> 5] >> (n & 31)) & 1u);
+        const uint32_t bit = (pk[k * (d >> 5) + grp] >> c) & 1u;
+        dscale += flip(s, bit);
         if (is_x) {
+            const size_t n = static_cast<size_t>(k) * d + col;
             a.d_latA[n] = scale * s * smooth_sign_factor(a.latA[n], a.kappa);
         } else {
-            const int64_t m = static_cast<int64_t>(col) * a.r + k;
-            a.d_latB[m] = scale * s * smooth_sign_factor(a.latB[m], a.kappa);
+            lat[c * r + k] = scale * s * smooth_sign_factor(lat[c * r + k], a.kappa);
         }
     }
-    (is_x ? a.d_s_in : a.d_s_out)[col] = dscale;
+    sh[tid] = dscale;
+    __syncthreads();
+    if (!is_x)
+        for (int e = tid; e < 32 * r; e += 256) a.d_latB[static_cast<size_t>(grp) * 32 * r + e] = lat[e];
+    if (kq == 0) {
+        float tot = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) tot += sh[j * 32 + c];
+        (is_x ? a.d_s_in : a.d_s_out)[col] = tot;
+    }
 }
 
 // ------------------------------------------------------------------------------------------ host side ----
@@ -445,7 +484,9 @@ bool aligned_to(const void* p, size_t n) { return (reinterpret_cast<uintptr_t>(p
 
 template <int RB, int TMV>
 lordba_status launch_rank(const BwdArgs& a, hipStream_t st) {
-    constexpr int NW = 8;
+    // 16 waves (128 registers per lane) where the accumulators leave room for four chunks in flight, else 8 waves
+    constexpr int NW = (TMV == 8 && RB <= 2) ? 16 : 8;
+    constexpr int DEPTH = 4;
     constexpr size_t lds = rank_lds_bytes(RB, TMV, NW);
     static_assert(lds <= 160 * 1024, "LDS of a gfx950 CU");
     if (lds > 64 * 1024) {
@@ -456,7 +497,7 @@ lordba_status launch_rank(const BwdArgs& a, hipStream_t st) {
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LORDBA_ERR_NO_DEVICE;
         std::lock_guard<std::mutex> lk(mu);
         if (!granted[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(lordba_bwd_rank_kernel<RB, TMV, NW>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(lordba_bwd_rank_kernel<RB, TMV, NW, DEPTH>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
                 (void)hipGetLastError();
                 return LORDBA_ERR_LAUNCH;
@@ -464,7 +505,7 @@ lordba_status launch_rank(const BwdArgs& a, hipStream_t st) {
             granted[dev] = true;
         }
     }
-    hipLaunchKernelGGL((lordba_bwd_rank_kernel<RB, TMV, NW>), dim3(a.tiles), dim3(NW * 64), lds, st, a);
+    hipLaunchKernelGGL((lordba_bwd_rank_kernel<RB, TMV, NW, DEPTH>), dim3(a.tiles), dim3(NW * 64), lds, st, a);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
 }
 
@@ -472,9 +513,11 @@ template <int RB>
 lordba_status launch_all(const BwdArgs& a, int tmv, hipStream_t st) {
     const lordba_status s = tmv == 16 ? launch_rank<RB, 16>(a, st) : launch_rank<RB, 8>(a, st);
     if (s != LORDBA_OK) return s;
-    hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB>), dim3(a.nbx + a.nbg, a.splits), dim3(kWgradWaves * 64), 0, st, a);
+    // kWgradGroup steps in flight where the registers allow two waves per SIMD or nearly so, else half of it
+    hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, (RB <= 2 ? kWgradGroup : kWgradGroup / 2)>), dim3(a.nbx + a.nbg, a.splits),
+                       dim3(kWgradWaves * 64), 0, st, a);
     if (hipGetLastError() != hipSuccess) return LORDBA_ERR_LAUNCH;
-    hipLaunchKernelGGL(lordba_bwd_finish_kernel, dim3((a.d_in + a.d_out + 255) / 256 + 1), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(lordba_bwd_finish_kernel, dim3((a.d_in >> 5) + (a.d_out >> 5) + 1), dim3(256), 0, st, a);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
 }
 
