@@ -161,6 +161,17 @@ lordba_status lordba_forward_batched_algo(const void* x, const uint32_t* packedA
                                           int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t n_adapters,
                                           void* stream, int algo);
 
+/* DEVICE function: the forward branch as training runs it (Sec. 3.2): lordba_forward, which also keeps the rank-r
+ * intermediate of Eq. (lordba-fwd) for the backward pass,
+ *   t_out[k * t_stride + t] = sum_i S_A[k, i] * s_in[i] * x[t, i]        fp32, rank-major, k < r, t < T, t_stride >= T
+ * (the value before the rank scaling; other entries of t_out are left untouched).  T * r * 4 bytes instead of recomputing
+ * a pass over x.  y_base == NULL and y_out == NULL together: only t_out is computed (x is read once, nothing else).
+ * Everything else as lordba_forward; t_out must not overlap x, y_base or y_out (LORDBA_ERR_ALIAS). */
+lordba_status lordba_forward_save_t(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                    const void* s_in, const void* s_rank, const void* s_out,
+                                    const void* y_base, void* y_out, float* t_out, int64_t t_stride,
+                                    int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream);
+
 /* DEVICE function: the backward pass of the branch in training (Sec. 3.2, "Forward and backward pass"; Alg. QAT-LoRDBA;
  * smooth-sign straight-through factor of Eq. (smoothsign)).  For Y = Y_base + X diag(s_in) S_A^T diag(s_rank) S_B^T diag(s_out)
  * with S_A = sign(latentA), S_B = sign(latentB), and an upstream gradient g = dL/dY, it computes
@@ -175,14 +186,17 @@ lordba_status lordba_forward_batched_algo(const void* x, const uint32_t* packedA
  *   packedA : S_A   as [r, d_in]    (the forward pass's packedA)
  *   packedAt: S_A^T as [d_in, r]    packedBt: S_B^T as [r, d_out]     (the same canonical format, transposed matrices;
  *             the carriers are taken from these bits, which the caller keeps equal to the signs of the latents)
+ *   t_saved : the rank-r intermediate that lordba_forward_save_t wrote for this x and adapter, with its t_stride, which
+ *             must be a multiple of 4 and at least T rounded up to a multiple of 128 (the rows are read in whole steps;
+ *             entries past T are ignored), 16-byte aligned; or NULL: it is recomputed from x (one more pass over x).
  *   dx_base fp16 [T, d_in]: the input gradient of the base path, to which the branch's is added; dx may be the same
  *   pointer.  dx == NULL and dx_base == NULL together: the input gradient is not computed.
  *   workspace: at least lordba_backward_workspace_bytes(T, d_in, d_out, r) bytes of device memory, 16-byte aligned, owned
  *   by the caller, contents irrelevant before and after; a smaller one -> LORDBA_ERR_WORKSPACE.  Calls that share a
  *   workspace must not overlap in time.
  * No output may overlap an input or another output (dx == dx_base excepted); this is not checked.
- * Shapes: d_in and d_out multiples of 32, 1 <= r <= 64, x / g / s_in / s_out 16-byte aligned; else LORDBA_ERR_DIM /
- * LORDBA_ERR_ALIGN.  T == 0: the parameter gradients are set to zero.
+ * Shapes: d_in and d_out multiples of 32, 1 <= r <= 64, activations, scales and packed carriers 16-byte aligned; else
+ * LORDBA_ERR_DIM / LORDBA_ERR_ALIGN.  T == 0: the parameter gradients are set to zero.
  * The call only enqueues kernels on `stream`; it never synchronises, allocates or frees.  Results are deterministic
  * (fixed summation order).  Arithmetic: fp16 inputs at their exact values, fp32 accumulation; every gradient array is
  * within 1e-3 relative L2 (per token row for dx, per rank for the latents, whole vector for the scales) of the exact result. */
@@ -190,6 +204,7 @@ lordba_status lordba_backward(const void* x, const void* g,
                               const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
                               const void* s_in, const void* s_rank, const void* s_out,
                               const float* latentA, const float* latentB, float kappa,
+                              const float* t_saved, int64_t t_stride,
                               const void* dx_base, void* dx,
                               float* d_s_in, float* d_s_rank, float* d_s_out,
                               float* d_latentA, float* d_latentB,

@@ -59,6 +59,8 @@ def _load():
         lib.lordba_oracle_forward_batched.argtypes = [vp] * 9 + [i64] * 5
         lib.lordba_oracle_forward_multi.restype = ci
         lib.lordba_oracle_forward_multi.argtypes = [vp] * 8 + [i64] * 5 + [ci]
+        lib.lordba_oracle_rank_intermediate.restype = ci
+        lib.lordba_oracle_rank_intermediate.argtypes = [vp] * 4 + [i64] * 3
         lib.lordba_oracle_smooth_sign_grad.restype = ctypes.c_double
         lib.lordba_oracle_smooth_sign_grad.argtypes = [ctypes.c_double, ctypes.c_double]
         lib.lordba_oracle_backward.restype = ci
@@ -234,6 +236,21 @@ def forward_packed(x, packedA, packedB, s_in, s_rank, s_out, y_base, r: int, nth
     if st != 0:
         raise ValueError("oracle forward failed with status %d" % st)
     return y
+
+
+def rank_intermediate(x, signsA, s_in) -> np.ndarray:
+    """fp64 t = (X diag(s_in)) S_A^T [T, r], the inner two factors of Eq. (lordba-fwd)."""
+    sA = _as(signsA, np.int8)
+    r, d_in = sA.shape
+    xb = _f16_bits(x)
+    T = xb.shape[0]
+    xb = _f16_bits(xb, (T, d_in))
+    si = _f16_bits(s_in, (d_in,))
+    t = np.empty((T, r), dtype=np.float64)
+    st = _load().lordba_oracle_rank_intermediate(_ptr(xb), _ptr(sA), _ptr(si), _ptr(t), T, d_in, r)
+    if st != 0:
+        raise ValueError("oracle rank_intermediate failed with status %d" % st)
+    return t
 
 
 def smooth_sign_grad(u: float, kappa: float) -> float:

@@ -38,7 +38,9 @@
  * derivative is the smooth-sign factor, by exact unit-step differences of the
  * loss on a dense numpy DeltaW, by the contraction of X^T G in exact rationals,
  * by the adjoint identity with the pinned forward, by Euler's relation for the
- * three scale vectors, and by closed forms of the smooth-sign factor.
+ * three scale vectors, and by closed forms of the smooth-sign factor.  The
+ * rank-r intermediate t is pinned by a numpy fp64 GEMM and by the forward
+ * oracle with an identity-like second carrier.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -381,6 +383,27 @@ int lordba_oracle_forward_batched(const uint16_t *x, const int8_t *signsA, const
 done:
     free(alpha); free(beta); free(gamma); free(w); free(u);
     return status;
+}
+
+/* ------------------------------------------------- rank-r intermediate ---- */
+
+/* t = (X D_alpha) B1, the inner two factors of Eq. (lordba-fwd): t[row, k] = sum_i S_A[k,i] * alpha_i * x[row, i].
+ * Training keeps it from the forward pass for the backward pass.  x[T,d_in], s_in[d_in]: fp16 bit patterns;
+ * signsA[r,d_in]: int8 +-1; t[T,r]: fp64 out (token-major).  Returns 0, 2 or 3 as the other functions. */
+int lordba_oracle_rank_intermediate(const uint16_t *x, const int8_t *signsA, const uint16_t *s_in, double *t,
+                                    int64_t T, int64_t d_in, int64_t r)
+{
+    if (T < 0 || d_in < 1 || r < 1) return 2;
+    for (int64_t n = 0; n < r * d_in; ++n) if (signsA[n] != 1 && signsA[n] != -1) return 3;
+    for (int64_t row = 0; row < T; ++row) {
+        for (int64_t k = 0; k < r; ++k) {
+            double s = 0.0;
+            for (int64_t i = 0; i < d_in; ++i)
+                s += lordba_oracle_f16_to_f64(x[row * d_in + i]) * lordba_oracle_f16_to_f64(s_in[i]) * (double)signsA[k * d_in + i];
+            t[row * r + k] = s;
+        }
+    }
+    return 0;
 }
 
 /* ------------------------------------------------- backward of the branch ---- */

@@ -135,7 +135,9 @@ def load_library():
     lib.lordba_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.lordba_backward_workspace_bytes.argtypes = [i64] * 4
     lib.lordba_backward.restype = ci
-    lib.lordba_backward.argtypes = [vp] * 10 + [ctypes.c_float] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 4 + [vp]
+    lib.lordba_backward.argtypes = [vp] * 10 + [ctypes.c_float, vp, i64] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 4 + [vp]
+    lib.lordba_forward_save_t.restype = ci
+    lib.lordba_forward_save_t.argtypes = [vp] * 9 + [i64] * 5 + [vp]
     lib.lordba_status_string.restype = ctypes.c_char_p
     lib.lordba_status_string.argtypes = [ci]
     _lib = lib
@@ -342,11 +344,45 @@ def lordba_pack_transposed(signsA, signsB) -> Tuple[np.ndarray, np.ndarray]:
     return pAt, pBt
 
 
+def saved_t_stride(T: int) -> int:
+    """Row stride (in floats) of a kept rank-r intermediate that lordba_backward accepts: T rounded up to a multiple of 128."""
+    return (int(T) + 127) // 128 * 128
+
+
+def lordba_forward_save_t(x, packedA, packedB, s_in, s_rank, s_out, y_base=None, y_out=None, t_out=None, stream=None):
+    """The training forward: lordba_forward that also writes the rank-r intermediate t = (x diag(s_in)) S_A^T, fp32,
+    rank-major [r, saved_t_stride(T)] (entries past T untouched).  y_base = None: only t is computed.
+    Returns (y_out or None, t_out)."""
+    import torch
+
+    lib = load_library()
+    T, d_in = x.shape
+    r = s_rank.numel()
+    d_out = s_out.numel()
+    stride = saved_t_stride(T) if t_out is None else t_out.shape[1]
+    if t_out is None:
+        t_out = torch.empty((r, stride), dtype=torch.float32, device=x.device)
+    if y_base is not None and y_out is None:
+        y_out = torch.empty_like(y_base)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    ptr = lambda t_: None if t_ is None else t_.data_ptr()
+    st = lib.lordba_forward_save_t(x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(), s_rank.data_ptr(),
+                                   s_out.data_ptr(), ptr(y_base), ptr(y_out), t_out.data_ptr(), stride, T, d_in, d_out, r,
+                                   ctypes.c_void_p(stream))
+    if st != 0:
+        raise LordbaError(st, "lordba_forward_save_t")
+    return y_out, t_out
+
+
 def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa: float,
-                    dx_base=None, dx=None, workspace=None, stream=None, check: bool = True) -> dict:
+                    dx_base=None, dx=None, workspace=None, stream=None, check: bool = True, t_saved=None) -> dict:
     """Gradients of the branch on the GPU (see include/lordba.h).  All tensors are torch CUDA tensors: x [T, d_in],
     g [T, d_out], s_* float16; packed* int32; latentA [r, d_in], latentB [d_out, r] float32; dx_base [T, d_in] float16
-    or None (then no input gradient is computed).  workspace: a uint8 CUDA tensor of at least
+    or None (then no input gradient is computed); t_saved: the float32 [r, stride] tensor lordba_forward_save_t returned
+    for this x, or None (recomputed).  workspace: a uint8 CUDA tensor of at least
     lordba_backward_workspace_bytes(...) bytes (allocated here if None).  Returns a dict of new tensors dx (or None),
     d_s_in, d_s_rank, d_s_out, d_latentA, d_latentB; enqueues on `stream` without synchronising."""
     import torch
@@ -391,7 +427,8 @@ def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, late
     ptr = lambda t_: None if t_ is None else t_.data_ptr()
     st = lib.lordba_backward(x.data_ptr(), g.data_ptr(), packedA.data_ptr(), packedAt.data_ptr(), packedBt.data_ptr(),
                              s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(), latentA.data_ptr(), latentB.data_ptr(),
-                             float(kappa), ptr(dx_base), ptr(dx), out["d_s_in"].data_ptr(), out["d_s_rank"].data_ptr(),
+                             float(kappa), ptr(t_saved), 0 if t_saved is None else t_saved.shape[1],
+                             ptr(dx_base), ptr(dx), out["d_s_in"].data_ptr(), out["d_s_rank"].data_ptr(),
                              out["d_s_out"].data_ptr(), out["d_latentA"].data_ptr(), out["d_latentB"].data_ptr(),
                              workspace.data_ptr(), workspace.numel(), T, d_in, d_out, r, ctypes.c_void_p(stream))
     if st != 0:

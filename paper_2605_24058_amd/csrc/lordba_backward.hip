@@ -11,22 +11,20 @@
 //   d_beta_k  = sum_t du[t,k] t[t,k]
 //   d_latent  = dS * kappa (1 - tanh^2(kappa latent))                                    (Eq. (smoothsign))
 //
-// Four kernels on the caller's stream, no host synchronisation, every buffer beyond inputs and outputs in the caller's
+// Kernels, all on the caller's stream, no host synchronisation, every buffer beyond inputs and outputs in the caller's
 // workspace:
-//   rank    one workgroup per tile of token rows: the two sign reductions t (over d_in, from x) and du (over d_out,
-//           from g) with the same MFMA scheme as stage 1 of the forward kernel; writes u and dt (fp32, rank-major),
-//           the tile's share of d_beta, and the largest |u|, |dt| per rank (atomic max: order-independent).
-//   dx      the forward kernel itself on the transposed adapter: DeltaW^T has the form of Eq. (lordba) with the
-//           carriers transposed and alpha, gamma exchanged.
+//   dx      The forward kernel itself on the transposed adapter: DeltaW^T has the form of Eq. (lordba) with the carriers
+//           transposed and alpha, gamma exchanged.  Its rank-r intermediate is du, which it also writes out.
+//   t       The forward kernel on x, stopped after its rank-r intermediate t (skipped when the caller kept t from the
+//           training forward pass, lordba_forward_save_t).
 //   wgrad   Q and P: MFMA with the token rows as contraction index.  A lane reads 8 token rows x 8 columns of x (or g)
-//           with row-contiguous 16-byte loads and transposes its 8 x 8 block in registers (v_perm_b32), MFMA e of a step
-//           takes column 8 m + e from lane group m; dt (or u) enters as fp16 hi + lo after a power-of-two scaling per
-//           rank.  Token ranges are split over waves and workgroups; partial sums are reduced in a fixed order.
+//           with row-contiguous 16-byte loads and transposes its 8 x 8 block in registers (v_perm_b32); MFMA e of a step
+//           takes column 8 m + e from lane group m.  dt = beta du (or u = beta t) enters as fp16 hi + lo after a
+//           power-of-two scaling per rank that follows the largest entry seen so far.  Token ranges are split over waves
+//           and workgroups; partial sums are reduced in a fixed order.  One extra workgroup column does d_beta.
 //   finish  sums the partials, applies the carrier signs, the scales and the smooth-sign factor.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-
-#include <mutex>
 
 #include "lordba.h"
 #include "lordba_dev_util.h"
@@ -40,38 +38,33 @@ constexpr int kWgradGroup = 4;        // 32-row steps a wave of the wgrad kernel
 struct BwdPlan {
     int rp;          // ranks padded to a multiple of 16
     int t_pad;       // token rows padded to a multiple of 128 (a group of the wgrad kernel)
-    int tmv;         // token rows per tile of the rank kernel
-    int tiles;       // tiles of the rank kernel
     int nbx, nbg;    // 128-column blocks of d_in and of d_out
     int dcols;       // columns of one partial-sum plane: (nbx + nbg) * 128
     int tw;          // token rows per wave of the wgrad kernel (multiple of 128)
     int splits;      // workgroups along the token axis of the wgrad kernel
     // workspace layout, in 4-byte words
-    size_t off_max, off_u, off_dt, off_dbeta, off_part, words;
+    size_t off_t, off_du, off_dbeta, off_part, words;
 };
 
 BwdPlan make_plan(int64_t T, int64_t d_in, int64_t d_out, int64_t r) {
     BwdPlan p;
     p.rp = static_cast<int>((r + 15) / 16 * 16);
     p.t_pad = static_cast<int>((T + 127) / 128 * 128);
-    p.tmv = T >= 4096 ? 16 : 8;
-    p.tiles = static_cast<int>((T + p.tmv - 1) / p.tmv);
     p.nbx = static_cast<int>((d_in + 127) / 128);
     p.nbg = static_cast<int>((d_out + 127) / 128);
     p.dcols = (p.nbx + p.nbg) * 128;
-    const int steps = p.t_pad / (32 * kWgradGroup);  // groups of steps: a wave takes whole groups
+    const int groups = p.t_pad / (32 * kWgradGroup);  // a wave takes whole groups of steps
     int splits = (kWgradTargetWgs + p.nbx + p.nbg - 1) / (p.nbx + p.nbg);
-    const int max_splits = (steps + kWgradWaves - 1) / kWgradWaves;  // at least one step per wave
+    const int max_splits = (groups + kWgradWaves - 1) / kWgradWaves;  // at least one group per wave
     splits = splits > max_splits ? max_splits : splits;
     splits = splits < 1 ? 1 : splits;
-    const int steps_per_wave = (steps + splits * kWgradWaves - 1) / (splits * kWgradWaves);
-    p.tw = steps_per_wave * 32 * kWgradGroup;
-    p.splits = (steps + steps_per_wave * kWgradWaves - 1) / (steps_per_wave * kWgradWaves);
-    p.off_max = 0;
-    p.off_u = 128;
-    p.off_dt = p.off_u + static_cast<size_t>(p.rp) * p.t_pad;
-    p.off_dbeta = p.off_dt + static_cast<size_t>(p.rp) * p.t_pad;
-    p.off_part = p.off_dbeta + static_cast<size_t>(p.tiles) * p.rp;
+    const int groups_per_wave = (groups + splits * kWgradWaves - 1) / (splits * kWgradWaves);
+    p.tw = groups_per_wave * 32 * kWgradGroup;
+    p.splits = (groups + groups_per_wave * kWgradWaves - 1) / (groups_per_wave * kWgradWaves);
+    p.off_t = 0;
+    p.off_du = p.off_t + static_cast<size_t>(p.rp) * p.t_pad;
+    p.off_dbeta = p.off_du + static_cast<size_t>(p.rp) * p.t_pad;
+    p.off_part = p.off_dbeta + static_cast<size_t>(p.splits) * p.rp;
     p.off_part = (p.off_part + 3) & ~static_cast<size_t>(3);
     p.words = p.off_part + static_cast<size_t>(p.splits) * p.rp * p.dcols;
     return p;
@@ -93,227 +86,86 @@ struct BwdArgs {
     float* d_s_out;
     float* d_latA;
     float* d_latB;
-    uint32_t* maxbits;     // [0..63] largest |u| per rank, [64..127] largest |dt| per rank (bit patterns)
-    float* uT;             // [rp, t_pad]
-    float* dtT;            // [rp, t_pad]
-    float* dbeta_part;     // [tiles, rp]
+    const float* tT;       // t,  rank-major: tT[k * t_stride + token], defined for k < r, token < T
+    const float* duT;      // du, rank-major: duT[k * du_stride + token]
+    float* dbeta_part;     // [splits, rp]
     float* part;           // [splits, rp, dcols]
     int T, d_in, d_out, r;
-    int rp, t_pad, tiles, nbx, nbg, dcols, tw, splits;
+    int rp, t_pad, t_stride, du_stride, nbx, nbg, dcols, tw, splits;
 };
 
-__global__ void bwd_clear_kernel(uint32_t* maxbits) { maxbits[threadIdx.x] = 0u; }
 __global__ void bwd_zero_kernel(float* p, int64_t n) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0.f;
 }
 
-// ------------------------------------------------------------------------------------------ rank kernel ----
-// RB rank blocks of 16, TMV token rows per tile (8 or 16), NW waves, DEPTH chunks in flight per wave.  The 128-column
-// chunks of x (d_in) and of g (d_out) form one list that is dealt round-robin to the waves; a chunk of x meets +-s_in
-// built from S_A, a chunk of g meets +-s_out built from S_B^T, and they accumulate into two separate tiles.
-template <int RB, int TMV, int NW, int DEPTH>
-__global__ __launch_bounds__(NW * 64) void lordba_bwd_rank_kernel(BwdArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int NI = TMV / 4;
-    // The wave index as a scalar: everything that depends on it (which chunks, how many steps) then branches on scalar
-    // conditions.  MFMA instructions ignore the EXEC mask, so they must never sit under a vector-predicated branch.
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int li = lane & 15, q = lane >> 4;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
-    const int last = static_cast<int>(a.T - 1 - t0 < TMV - 1 ? a.T - 1 - t0 : TMV - 1);  // last live row of the tile
-
-    _Float16* sw = reinterpret_cast<_Float16*>(smem) + wave * 128;                       // wave-private scale slice
-    _Float16* xs = reinterpret_cast<_Float16*>(smem + NW * 256) + wave * TMV * kXRow;    // wave-private transpose tile
-    float* red = reinterpret_cast<float*>(smem + NW * 256 + NW * TMV * kXRow * 2);       // [wave][set][rb][lane][4]
-
-    const int nchunks = a.nbx + a.nbg;
-    const int my_n = wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0;
-
-    u4 xbuf[DEPTH][NI];
-    uint32_t sbuf[DEPTH];
-    uint32_t bits[DEPTH][RB];
-    auto issue = [&](int slot, int n) {
-        int c = wave + NW * n;
-        c = c < nchunks ? c : nchunks - 1;  // past the end: re-read a valid chunk, the result is not used
-        const bool is_x = c < a.nbx;
-        const int cc = is_x ? c : c - a.nbx;
-        const int d = is_x ? a.d_in : a.d_out;
-        const _Float16* src = (is_x ? a.x : a.g) + t0 * d;
-        const _Float16* sc = is_x ? a.s_in : a.s_out;
-        const uint32_t* pk = is_x ? a.pA : a.pBt;
-        const int words_per_row = d >> 5;  // d % 32 == 0 on this path
-        const int pair = cc * 64 + lane;   // fp16 pair index of the scale slice
-        // (columns past d get scale 0 when the chunk is consumed: nothing here may wait for a load)
-        sbuf[slot] = *reinterpret_cast<const uint32_t*>(sc + (pair * 2 < d ? pair * 2 : 0));
-#pragma unroll
-        for (int m = 0; m < NI; ++m) {
-            int row = m * 4 + q;
-            row = row < last ? row : last;
-            int col = cc * 128 + li * 8;
-            col = col < d ? col : d - 8;
-            xbuf[slot][m] = load16_stream(at(src, static_cast<uint32_t>(row * d + col) * 2u));
-        }
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            int rk = rb * 16 + li;
-            rk = rk < a.r ? rk : a.r - 1;
-            int w = cc * 4 + q;
-            w = w < words_per_row ? w : words_per_row - 1;  // columns past d meet scale 0
-            bits[slot][rb] = pk[rk * words_per_row + w];
-        }
-    };
-
-    f4 acc[2][RB];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) acc[s][rb] = f4{0.f, 0.f, 0.f, 0.f};
-    }
-    auto consume = [&](int slot, int n) {
-        const int c = wave + NW * n;
-        const bool is_x = c < a.nbx;
-        const bool in_range = ((is_x ? c : c - a.nbx) * 64 + lane) * 2 < (is_x ? a.d_in : a.d_out);
-        reinterpret_cast<uint32_t*>(sw)[lane] = in_range ? sbuf[slot] : 0u;
-#pragma unroll
-        for (int m = 0; m < NI; ++m) store16(xs + (m * 4 + q) * kXRow + li * 8, xbuf[slot][m]);
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const h8 xf = as_h8(load16(xs + tile_row_of_mfma_row<TMV>(li) * kXRow + q * 32 + s * 8));
-            const u4 sv = load16(sw + q * 32 + s * 8);
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                const uint32_t both = __builtin_amdgcn_perm(bits[slot][rb], bits[slot][rb], 0x00010001u * s);
-                const h8 op = as_h8(flip_by_bits(sv, both));
-                if (is_x) acc[0][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf, op, acc[0][rb], 0, 0, 0);
-                else acc[1][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xf, op, acc[1][rb], 0, 0, 0);
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-    };
-
-    // The first DEPTH chunks are requested without any condition (past the end a valid chunk is re-read and not used), and
-    // so is the next group's chunk after each consumed one: every wait then counts exactly the loads issued after the one
-    // it needs.  The last group is consumed without issuing anything.
-#pragma unroll
-    for (int slot = 0; slot < DEPTH; ++slot) issue(slot, slot);
-    int n0 = 0;
-    for (; n0 + DEPTH < my_n; n0 += DEPTH) {
-#pragma unroll
-        for (int slot = 0; slot < DEPTH; ++slot) {
-            consume(slot, n0 + slot);
-            issue(slot, n0 + DEPTH + slot);
-        }
-    }
-#pragma unroll
-    for (int slot = 0; slot < DEPTH; ++slot)
-        if (n0 + slot < my_n) consume(slot, n0 + slot);
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) *reinterpret_cast<f4*>(red + (((wave * 2 + s) * RB + rb) * 64 + lane) * 4) = acc[s][rb];
-    }
-    __syncthreads();
-    if (wave != 0) return;
-
-    // Accumulator layout: lane (li, q) holds rank rb*16 + li for MFMA rows 4q .. 4q+3.
-    constexpr int LIVE = TMV == 16 ? 4 : 2;  // live rows per lane: token rows 4q + i, or 2q + i
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        f4 ts = f4{0.f, 0.f, 0.f, 0.f}, gs = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {  // fixed order: deterministic
-            ts += *reinterpret_cast<const f4*>(red + (((w * 2 + 0) * RB + rb) * 64 + lane) * 4);
-            gs += *reinterpret_cast<const f4*>(red + (((w * 2 + 1) * RB + rb) * 64 + lane) * 4);
-        }
-        const int rk = rb * 16 + li;
-        const float beta = rk < a.r ? static_cast<float>(a.s_rank[rk]) : 0.f;
-        float uv[LIVE], dv[LIVE];
-        float db = 0.f, umax = 0.f, dmax = 0.f;
-#pragma unroll
-        for (int i = 0; i < LIVE; ++i) {
-            const int row = (TMV == 16 ? 4 * q : 2 * q) + i;
-            const bool live = row <= last && rk < a.r;
-            uv[i] = live ? beta * ts[i] : 0.f;
-            dv[i] = live ? beta * gs[i] : 0.f;
-            db += live ? gs[i] * ts[i] : 0.f;
-            umax = fmaxf(umax, fabsf(uv[i]));
-            dmax = fmaxf(dmax, fabsf(dv[i]));
-        }
-        // over the four lane groups (token rows) of the same rank, fixed order
-        db += __shfl_xor(db, 16, 64);
-        db += __shfl_xor(db, 32, 64);
-        umax = fmaxf(umax, __shfl_xor(umax, 16, 64));
-        umax = fmaxf(umax, __shfl_xor(umax, 32, 64));
-        dmax = fmaxf(dmax, __shfl_xor(dmax, 16, 64));
-        dmax = fmaxf(dmax, __shfl_xor(dmax, 32, 64));
-        float* up = a.uT + static_cast<size_t>(rk) * a.t_pad + t0 + (TMV == 16 ? 4 * q : 2 * q);
-        float* dp = a.dtT + static_cast<size_t>(rk) * a.t_pad + t0 + (TMV == 16 ? 4 * q : 2 * q);
-        if (TMV == 16) {
-            *reinterpret_cast<f4*>(up) = f4{uv[0], uv[1], uv[LIVE - 2], uv[LIVE - 1]};
-            *reinterpret_cast<f4*>(dp) = f4{dv[0], dv[1], dv[LIVE - 2], dv[LIVE - 1]};
-        } else {
-            *reinterpret_cast<float2*>(up) = float2{uv[0], uv[1]};
-            *reinterpret_cast<float2*>(dp) = float2{dv[0], dv[1]};
-        }
-        if (q == 0) {
-            a.dbeta_part[static_cast<size_t>(blockIdx.x) * a.rp + rk] = db;
-            // bit patterns of non-negative floats order like unsigned integers
-            __hip_atomic_fetch_max(a.maxbits + rk, __float_as_uint(umax), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_fetch_max(a.maxbits + 64 + rk, __float_as_uint(dmax), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    // The last tile also clears the padding rows up to t_pad, which the wgrad kernel reads as whole groups of steps.
-    if (blockIdx.x == gridDim.x - 1) {
-        const int from = static_cast<int>(t0) + TMV, n = a.t_pad - from;
-        for (int e = lane; e < a.rp * n; e += 64) {
-            const int rk = e / n, t = from + e % n;
-            a.uT[static_cast<size_t>(rk) * a.t_pad + t] = 0.f;
-            a.dtT[static_cast<size_t>(rk) * a.t_pad + t] = 0.f;
-        }
-    }
-}
-
-constexpr size_t rank_lds_bytes(int RB, int TMV, int NW) {
-    return static_cast<size_t>(NW) * 256 + static_cast<size_t>(NW) * TMV * kXRow * 2 + static_cast<size_t>(NW) * 2 * RB * 1024;
-}
-
 // ----------------------------------------------------------------------------------------- wgrad kernel ----
 // Workgroup (cb, s): column block cb of x (cb < nbx: Q, with dt) or of g (P, with u), token rows [s * 4 tw, (s+1) * 4 tw),
-// a quarter per wave.  One step = 32 token rows x 128 columns.
+// a quarter per wave; cb == nbx + nbg: the share of d_beta of those token rows.  One step = 32 token rows x 128 columns.
 // G steps are in flight per wave: the loads of a group are issued without any condition (past the end of the wave's range
 // they re-read valid addresses and are not used), so that every wait counts exactly the loads issued after the one it
 // needs; the last group is consumed without issuing anything.
 template <int RB, int G>
 __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdArgs a) {
     __shared__ __align__(16) float red[kWgradWaves][8][64][4];
-    // The wave index as a scalar: everything that depends on it (which chunks, how many steps) then branches on scalar
-    // conditions.  MFMA instructions ignore the EXEC mask, so they must never sit under a vector-predicated branch.
+    // The wave index as a scalar: everything that depends on it (how many steps) then branches on scalar conditions.
+    // MFMA instructions ignore the EXEC mask, so they must never sit under a vector-predicated branch.
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, q = lane >> 4;
     const int cb = blockIdx.x;
+    const int tk_begin = (static_cast<int>(blockIdx.y) * kWgradWaves + wave) * a.tw;
+    int tk_end = tk_begin + a.tw;
+    tk_end = tk_end < a.t_pad ? tk_end : a.t_pad;
+
+    if (cb == a.nbx + a.nbg) {
+        // d_beta_k = sum_t du[t,k] t[t,k] over this workgroup's token rows: lane (li, q) takes rank li of each block and
+        // the tokens 8 q .. 8 q + 7 of every step; fixed order (lane, then lane groups, then waves)
+        float* sums = &red[0][0][0][0];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int rk = rb * 16 + li;
+            float s = 0.f;
+            const int row = rk < a.r ? rk : a.r - 1;  // a rank that exists; the result of a padded rank is dropped below
+            const float* dup = a.duT + static_cast<size_t>(row) * a.du_stride + 8 * q;
+            const float* tp = a.tT + static_cast<size_t>(row) * a.t_stride + 8 * q;
+            for (int tk = tk_begin; tk < tk_end; tk += 32) {  // 32 bytes of each array per lane and step, inside t_pad entries
+                const u4 d0 = load16(dup + tk), d1 = load16(dup + tk + 4), t0 = load16(tp + tk), t1 = load16(tp + tk + 4);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float dv = __uint_as_float(e < 4 ? d0[e & 3] : d1[e & 3]), tv = __uint_as_float(e < 4 ? t0[e & 3] : t1[e & 3]);
+                    s += (tk + 8 * q + e < a.T) ? dv * tv : 0.f;   // select: entries past T are undefined
+                }
+            }
+            if (rk >= a.r) s = 0.f;
+            s += __shfl_xor(s, 16, 64);
+            s += __shfl_xor(s, 32, 64);
+            if (q == 0) sums[(rb * 16 + li) * kWgradWaves + wave] = s;
+        }
+        __syncthreads();
+        if (tid < a.rp) {
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWgradWaves; ++w) tot += sums[tid * kWgradWaves + w];
+            a.dbeta_part[static_cast<size_t>(blockIdx.y) * a.rp + tid] = tot;
+        }
+        return;
+    }
+
     const bool is_x = cb < a.nbx;
     const int cc = is_x ? cb : cb - a.nbx;
     const int d = is_x ? a.d_in : a.d_out;
     const _Float16* src = is_x ? a.x : a.g;
-    const float* small = is_x ? a.dtT : a.uT;
-    const uint32_t* mb = a.maxbits + (is_x ? 64 : 0);
+    const float* small = is_x ? a.duT : a.tT;   // dt = beta du meets x, u = beta t meets g
+    const int sstride = is_x ? a.du_stride : a.t_stride;
 
-    // Power-of-two scaling per rank: the largest entry of the rank's column lands in [2^13, 2^14), so that hi + lo (two
-    // fp16) keep 22 bits of every entry that matters to the sum, whatever the magnitude of the gradients.
-    float mul[RB], inv[RB];
+    float beta[RB];
+    int row_of[RB];  // the lane's rank, clamped to a rank that exists (its values are then masked)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        int e = static_cast<int>((mb[rb * 16 + li] >> 23) & 0xffu);
-        e = e < 14 ? 14 : (e > 254 ? 254 : e);
-        mul[rb] = __uint_as_float(static_cast<uint32_t>(267 - e) << 23);
-        inv[rb] = __uint_as_float(static_cast<uint32_t>(e - 13) << 23);
+        const int rk = rb * 16 + li;
+        row_of[rb] = rk < a.r ? rk : a.r - 1;
+        beta[rb] = rk < a.r ? static_cast<float>(a.s_rank[row_of[rb]]) : 0.f;
     }
-
-    const int tk_begin = (static_cast<int>(blockIdx.y) * kWgradWaves + wave) * a.tw;
-    int tk_end = tk_begin + a.tw;
-    tk_end = tk_end < a.t_pad ? tk_end : a.t_pad;
     int col = cc * 128 + li * 8;
     col = col < d ? col : d - 8;  // past the end: a valid column group is re-read, its sums are never used
 
@@ -323,40 +175,83 @@ __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdA
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[rb][e] = f4{0.f, 0.f, 0.f, 0.f};
     }
-    u4 xb[G][8];
-    u4 sb[G][RB][2];
-    auto issue = [&](int slot, int tk) {
+    // Power-of-two scaling per rank: 2^(140 - cur_e) brings an entry with biased exponent cur_e to [2^13, 2^14), so that
+    // hi + lo (two fp16) keep 22 bits of it.  cur_e follows the largest entry of the rank seen so far, group by group; when
+    // it grows, what has been accumulated is rescaled.  Entries far below the largest lose bits that do not matter to the sum.
+    int cur_e[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) cur_e[rb] = 14;
+
+    u4 xb[G][8];         // x (or g): step i of the group, 8 token rows x 8 columns per lane
+    u4 sb[G][RB][2];     // du (or t): 8 tokens of the lane's rank per step, fp32
+    u4 hl[G][RB][2];     // the same as fp16 hi and lo operands, scaled
+    auto issue_x = [&](int i, int tk) {
         tk = tk < a.t_pad - 32 ? tk : a.t_pad - 32;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             int row = tk + 8 * q + e;
-            row = row < a.T ? row : a.T - 1;  // padding rows meet dt = u = 0
-            xb[slot][e] = load16_stream(src + static_cast<size_t>(row) * d + col);
-        }
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            const float* p = small + static_cast<size_t>(rb * 16 + li) * a.t_pad + tk + 8 * q;
-            sb[slot][rb][0] = load16(p);
-            sb[slot][rb][1] = load16(p + 4);
+            row = row < a.T ? row : a.T - 1;  // rows past T meet dt = u = 0
+            xb[i][e] = load16_stream(src + static_cast<size_t>(row) * d + col);
         }
     };
-    auto consume = [&](int slot) {
-        u4 hi[RB], lo[RB];
+    auto issue_small = [&](int tk0) {  // all G steps of the group that starts at token tk0
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
+        for (int i = 0; i < G; ++i) {
+            int tk = tk0 + 32 * i;
+            tk = tk < a.t_pad - 32 ? tk : a.t_pad - 32;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float v0 = __uint_as_float(sb[slot][rb][w >> 1][(w & 1) * 2]) * mul[rb];
-                const float v1 = __uint_as_float(sb[slot][rb][w >> 1][(w & 1) * 2 + 1]) * mul[rb];
-                h2 h, l;
-                h[0] = static_cast<_Float16>(v0);
-                h[1] = static_cast<_Float16>(v1);
-                l[0] = static_cast<_Float16>(v0 - static_cast<float>(h[0]));
-                l[1] = static_cast<_Float16>(v1 - static_cast<float>(h[1]));
-                hi[rb][w] = __builtin_bit_cast(uint32_t, h);
-                lo[rb][w] = __builtin_bit_cast(uint32_t, l);
+            for (int rb = 0; rb < RB; ++rb) {
+                // 32 bytes inside the row's t_pad entries; the array is defined for token < T only, the rest is masked
+                const float* p = small + static_cast<size_t>(row_of[rb]) * sstride + tk + 8 * q;
+                sb[i][rb][0] = load16(p);
+                sb[i][rb][1] = load16(p + 4);
             }
         }
+    };
+    auto convert = [&](int tk0) {  // scale of the group, then its hi / lo operands
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            float v[G][8];
+            float m = 0.f;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float raw = __uint_as_float(sb[i][rb][e >> 2][e & 3]);
+                    // select, not multiply: the padding rows and the ranks past r hold undefined values
+                    v[i][e] = (tk0 + 32 * i + 8 * q + e < a.T && beta[rb] != 0.f) ? raw * beta[rb] : 0.f;
+                    m = fmaxf(m, fabsf(v[i][e]));
+                }
+            }
+            m = fmaxf(m, __shfl_xor(m, 16, 64));
+            m = fmaxf(m, __shfl_xor(m, 32, 64));
+            int e_new = static_cast<int>((__float_as_uint(m) >> 23) & 0xffu);
+            e_new = e_new > 254 ? 254 : e_new;
+            if (__builtin_amdgcn_ballot_w64(e_new > cur_e[rb]) != 0ull) {   // scalar branch: rare after the first group
+                const int sh = cur_e[rb] - e_new;                           // < 0 where this lane's rank grows
+                const float f = sh >= 0 ? 1.f : (sh < -126 ? 0.f : __uint_as_float(static_cast<uint32_t>(127 + sh) << 23));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[rb][e] *= f;
+                cur_e[rb] = e_new > cur_e[rb] ? e_new : cur_e[rb];
+            }
+            const float mul = __uint_as_float(static_cast<uint32_t>(267 - cur_e[rb]) << 23);
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float v0 = v[i][2 * w] * mul, v1 = v[i][2 * w + 1] * mul;
+                    h2 h, l;
+                    h[0] = static_cast<_Float16>(v0);
+                    h[1] = static_cast<_Float16>(v1);
+                    l[0] = static_cast<_Float16>(v0 - static_cast<float>(h[0]));
+                    l[1] = static_cast<_Float16>(v1 - static_cast<float>(h[1]));
+                    hl[i][rb][0][w] = __builtin_bit_cast(uint32_t, h);
+                    hl[i][rb][1][w] = __builtin_bit_cast(uint32_t, l);
+                }
+            }
+        }
+    };
+    auto consume_x = [&](int i) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             // column e of the lane's 8 x 8 block: token pairs (0,1), (2,3), (4,5), (6,7)
@@ -364,38 +259,46 @@ __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdA
             u4 col8;
 #pragma unroll
             for (int pr = 0; pr < 4; ++pr)
-                col8[pr] = __builtin_amdgcn_perm(xb[slot][2 * pr + 1][e >> 1], xb[slot][2 * pr][e >> 1], sel);
+                col8[pr] = __builtin_amdgcn_perm(xb[i][2 * pr + 1][e >> 1], xb[i][2 * pr][e >> 1], sel);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                acc[rb][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(col8), as_h8(hi[rb]), acc[rb][e], 0, 0, 0);
-                acc[rb][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(col8), as_h8(lo[rb]), acc[rb][e], 0, 0, 0);
+                acc[rb][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(col8), as_h8(hl[i][rb][0]), acc[rb][e], 0, 0, 0);
+                acc[rb][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(col8), as_h8(hl[i][rb][1]), acc[rb][e], 0, 0, 0);
             }
         }
     };
-    // t_pad and tw are multiples of 32 G: a wave's range is a whole number of groups (possibly none)
+    // t_pad and tw are multiples of 32 G: a wave's range is a whole number of groups (possibly none).  The small loads of a
+    // group are requested before the x loads that are issued while the previous group is consumed, so the conversion (a
+    // dependent chain of vector-ALU work and two cross-lane exchanges) never waits for x.
     if (tk_begin < tk_end) {
+        issue_small(tk_begin);
 #pragma unroll
-        for (int i = 0; i < G; ++i) issue(i, tk_begin + 32 * i);
+        for (int i = 0; i < G; ++i) issue_x(i, tk_begin + 32 * i);
         int tk = tk_begin;
         for (; tk + 32 * G < tk_end; tk += 32 * G) {
+            convert(tk);
+            issue_small(tk + 32 * G);
 #pragma unroll
             for (int i = 0; i < G; ++i) {
-                consume(i);
-                issue(i, tk + 32 * (G + i));
+                consume_x(i);
+                issue_x(i, tk + 32 * (G + i));
             }
         }
+        convert(tk);
 #pragma unroll
-        for (int i = 0; i < G; ++i) consume(i);
+        for (int i = 0; i < G; ++i) consume_x(i);
     }
 
-    // Accumulator e, register i of lane (li, q): rank rb*16 + li, column 8 (4q + i) + e of the block.  The four waves'
-    // tiles are summed in wave order; wave w sums register i = w and so ends up with 8 consecutive columns.
+    // Accumulator e, register i of lane (li, q): rank rb*16 + li, column 8 (4q + i) + e of the block.  Each wave brings its
+    // tile back to true scale; the four tiles are summed in wave order; wave w sums register i = w and so ends up with 8
+    // consecutive columns.
     float* out = a.part + static_cast<size_t>(blockIdx.y) * a.rp * a.dcols + static_cast<size_t>(cb) * 128;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         if (rb > 0) __syncthreads();
+        const float inv = __uint_as_float(static_cast<uint32_t>(cur_e[rb] - 13) << 23);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) *reinterpret_cast<f4*>(&red[wave][e][lane][0]) = acc[rb][e];
+        for (int e = 0; e < 8; ++e) *reinterpret_cast<f4*>(&red[wave][e][lane][0]) = acc[rb][e] * inv;
         __syncthreads();
         float sum[8];
 #pragma unroll
@@ -403,7 +306,7 @@ __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdA
             float s = red[0][e][lane][wave];
 #pragma unroll
             for (int w = 1; w < kWgradWaves; ++w) s += red[w][e][lane][wave];
-            sum[e] = s * inv[rb];
+            sum[e] = s;
         }
         float* dst = out + static_cast<size_t>(rb * 16 + li) * a.dcols + 8 * (4 * q + wave);
         *reinterpret_cast<f4*>(dst) = f4{sum[0], sum[1], sum[2], sum[3]};
@@ -427,16 +330,9 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
     const int gx = a.d_in >> 5, gg = a.d_out >> 5;
     const int tid = threadIdx.x;
     if (static_cast<int>(blockIdx.x) == gx + gg) {
-        // d_beta: the tiles' shares (thread (k, c) takes tiles c, c + nc, ...; then the nc partial sums in order)
-        const int nc = 256 / a.rp, k = tid % a.rp, c = tid / a.rp;
-        float s = 0.f;
-        if (c < nc)
-            for (int t = c; t < a.tiles; t += nc) s += a.dbeta_part[static_cast<size_t>(t) * a.rp + k];
-        sh[tid] = s;
-        __syncthreads();
-        if (tid < a.r) {
+        if (tid < a.r) {  // d_beta: the shares of the token ranges, in their order
             float tot = 0.f;
-            for (int cc = 0; cc < nc; ++cc) tot += sh[cc * a.rp + tid];
+            for (int sp = 0; sp < a.splits; ++sp) tot += a.dbeta_part[static_cast<size_t>(sp) * a.rp + tid];
             a.d_s_rank[tid] = tot;
         }
         return;
@@ -482,39 +378,10 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
 // ------------------------------------------------------------------------------------------ host side ----
 bool aligned_to(const void* p, size_t n) { return (reinterpret_cast<uintptr_t>(p) & (n - 1)) == 0; }
 
-template <int RB, int TMV>
-lordba_status launch_rank(const BwdArgs& a, hipStream_t st) {
-    // 16 waves (128 registers per lane) where the accumulators leave room for four chunks in flight, else 8 waves
-    constexpr int NW = (TMV == 8 && RB <= 2) ? 16 : 8;
-    constexpr int DEPTH = 4;
-    constexpr size_t lds = rank_lds_bytes(RB, TMV, NW);
-    static_assert(lds <= 160 * 1024, "LDS of a gfx950 CU");
-    if (lds > 64 * 1024) {
-        // Opt in to more than 64 KiB of dynamic LDS once per device and kernel; raising the limit is idempotent.
-        static std::mutex mu;
-        static bool granted[64] = {false};
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LORDBA_ERR_NO_DEVICE;
-        std::lock_guard<std::mutex> lk(mu);
-        if (!granted[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(lordba_bwd_rank_kernel<RB, TMV, NW, DEPTH>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
-                (void)hipGetLastError();
-                return LORDBA_ERR_LAUNCH;
-            }
-            granted[dev] = true;
-        }
-    }
-    hipLaunchKernelGGL((lordba_bwd_rank_kernel<RB, TMV, NW, DEPTH>), dim3(a.tiles), dim3(NW * 64), lds, st, a);
-    return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
-}
-
 template <int RB>
-lordba_status launch_all(const BwdArgs& a, int tmv, hipStream_t st) {
-    const lordba_status s = tmv == 16 ? launch_rank<RB, 16>(a, st) : launch_rank<RB, 8>(a, st);
-    if (s != LORDBA_OK) return s;
+lordba_status launch_all(const BwdArgs& a, hipStream_t st) {
     // kWgradGroup steps in flight where the registers allow two waves per SIMD or nearly so, else half of it
-    hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, (RB <= 2 ? kWgradGroup : kWgradGroup / 2)>), dim3(a.nbx + a.nbg, a.splits),
+    hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, (RB <= 2 ? kWgradGroup : kWgradGroup / 2)>), dim3(a.nbx + a.nbg + 1, a.splits),
                        dim3(kWgradWaves * 64), 0, st, a);
     if (hipGetLastError() != hipSuccess) return LORDBA_ERR_LAUNCH;
     hipLaunchKernelGGL(lordba_bwd_finish_kernel, dim3((a.d_in >> 5) + (a.d_out >> 5) + 1), dim3(256), 0, st, a);
@@ -523,7 +390,7 @@ lordba_status launch_all(const BwdArgs& a, int tmv, hipStream_t st) {
 
 bool supported(int64_t T, int64_t d_in, int64_t d_out, int64_t r) {
     return T >= 0 && d_in >= 32 && d_out >= 32 && d_in % 32 == 0 && d_out % 32 == 0 && r >= 1 && r <= LORDBA_MAX_RANK &&
-           T <= INT32_MAX - 64 && d_in <= (1 << 24) && d_out <= (1 << 24);
+           T <= INT32_MAX - 128 && d_in <= (1 << 24) && d_out <= (1 << 24);
 }
 
 }  // namespace
@@ -537,6 +404,7 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
                                          const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
                                          const void* s_in, const void* s_rank, const void* s_out,
                                          const float* latentA, const float* latentB, float kappa,
+                                         const float* t_saved, int64_t t_stride,
                                          const void* dx_base, void* dx,
                                          float* d_s_in, float* d_s_rank, float* d_s_out,
                                          float* d_latentA, float* d_latentB,
@@ -548,10 +416,13 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
         return LORDBA_ERR_NULL;
     if (T > 0 && (!x || !g)) return LORDBA_ERR_NULL;
     if ((dx == nullptr) != (dx_base == nullptr)) return LORDBA_ERR_NULL;
+    // a kept t is read in whole 32-row steps: its rows must reach the padded token count
+    if (t_saved != nullptr && (t_stride < (T + 127) / 128 * 128 || t_stride % 4 != 0 || t_stride > INT32_MAX)) return LORDBA_ERR_DIM;
     if (!aligned_to(x, 16) || !aligned_to(g, 16) || !aligned_to(s_in, 16) || !aligned_to(s_out, 16) || !aligned_to(s_rank, 2) ||
-        !aligned_to(packedA, 4) || !aligned_to(packedBt, 4) || !aligned_to(latentA, 4) || !aligned_to(latentB, 4) ||
-        !aligned_to(d_s_in, 4) || !aligned_to(d_s_rank, 4) || !aligned_to(d_s_out, 4) || !aligned_to(d_latentA, 4) ||
-        !aligned_to(d_latentB, 4) || !aligned_to(workspace, 16))
+        !aligned_to(packedA, 16) || !aligned_to(packedAt, 16) || !aligned_to(packedBt, 4) || !aligned_to(latentA, 4) ||
+        !aligned_to(latentB, 4) || !aligned_to(d_s_in, 4) || !aligned_to(d_s_rank, 4) || !aligned_to(d_s_out, 4) ||
+        !aligned_to(d_latentA, 4) || !aligned_to(d_latentB, 4) || !aligned_to(workspace, 16) || !aligned_to(t_saved, 16) ||
+        !aligned_to(dx_base, 16) || !aligned_to(dx, 16))
         return LORDBA_ERR_ALIGN;
     const BwdPlan p = make_plan(T, d_in, d_out, r);
     if (workspace_bytes < p.words * 4) return LORDBA_ERR_WORKSPACE;
@@ -566,13 +437,23 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
         }
         return LORDBA_OK;
     }
-    if (dx != nullptr) {
-        // dx = dx_base + g DeltaW^T: the forward branch of the transposed adapter (validates its own arguments)
-        const lordba_status s = lordba_forward(g, packedBt, packedAt, s_out, s_rank, s_in, dx_base, dx, T, d_out, d_in, r, stream);
+
+    float* ws = static_cast<float*>(workspace);
+    float* duT = ws + p.off_du;
+    // du, and dx = dx_base + g DeltaW^T if wanted: the forward branch of the transposed adapter (it validates its own
+    // arguments); du is that call's rank-r intermediate
+    lordba_status s = lordba_forward_save_t(g, packedBt, packedAt, s_out, s_rank, s_in, dx_base, dx, duT, p.t_pad, T, d_out, d_in, r, stream);
+    if (s != LORDBA_OK) return s;
+    const float* tT = t_saved;
+    int64_t tT_stride = t_stride;
+    if (tT == nullptr) {
+        // t: the forward branch of the adapter itself, stopped after its rank-r intermediate (its second carrier is not
+        // read; packedAt stands in as a valid [d_in, r] carrier)
+        float* t_own = ws + p.off_t;
+        s = lordba_forward_save_t(x, packedA, packedAt, s_in, s_rank, s_in, nullptr, nullptr, t_own, p.t_pad, T, d_in, d_in, r, stream);
         if (s != LORDBA_OK) return s;
-    } else {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LORDBA_ERR_NO_DEVICE; }
+        tT = t_own;
+        tT_stride = p.t_pad;
     }
 
     BwdArgs a;
@@ -591,31 +472,28 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
     a.d_s_out = d_s_out;
     a.d_latA = d_latentA;
     a.d_latB = d_latentB;
-    uint32_t* ws = static_cast<uint32_t*>(workspace);
-    a.maxbits = ws + p.off_max;
-    a.uT = reinterpret_cast<float*>(ws + p.off_u);
-    a.dtT = reinterpret_cast<float*>(ws + p.off_dt);
-    a.dbeta_part = reinterpret_cast<float*>(ws + p.off_dbeta);
-    a.part = reinterpret_cast<float*>(ws + p.off_part);
+    a.tT = tT;
+    a.duT = duT;
+    a.dbeta_part = ws + p.off_dbeta;
+    a.part = ws + p.off_part;
     a.T = static_cast<int>(T);
     a.d_in = static_cast<int>(d_in);
     a.d_out = static_cast<int>(d_out);
     a.r = static_cast<int>(r);
     a.rp = p.rp;
     a.t_pad = p.t_pad;
-    a.tiles = p.tiles;
+    a.t_stride = static_cast<int>(tT_stride);
+    a.du_stride = p.t_pad;
     a.nbx = p.nbx;
     a.nbg = p.nbg;
     a.dcols = p.dcols;
     a.tw = p.tw;
     a.splits = p.splits;
 
-    hipLaunchKernelGGL(bwd_clear_kernel, dim3(1), dim3(128), 0, st, a.maxbits);
-    if (hipGetLastError() != hipSuccess) return LORDBA_ERR_LAUNCH;
     switch (p.rp / 16) {
-        case 1: return launch_all<1>(a, p.tmv, st);
-        case 2: return launch_all<2>(a, p.tmv, st);
-        case 3: return launch_all<3>(a, p.tmv, st);
-        default: return launch_all<4>(a, p.tmv, st);
+        case 1: return launch_all<1>(a, st);
+        case 2: return launch_all<2>(a, st);
+        case 3: return launch_all<3>(a, st);
+        default: return launch_all<4>(a, st);
     }
 }

@@ -59,6 +59,10 @@ struct FwdArgs {
     // after the other, and token row t uses adapter ids[t]; an id outside [0, n_adapters) means "no adapter".
     const int32_t* ids;
     int n_adapters;
+    // Training: if t_out != nullptr the rank-r intermediate t = (x D_alpha) B1 (before the rank scaling) is also written,
+    // fp32, rank-major: t_out[k * t_stride + token].  With y_out == nullptr nothing else is computed (no stage 3).
+    float* t_out;
+    int t_stride;
 };
 
 // The arguments of one adapter of a pool.
@@ -110,7 +114,7 @@ __host__ __device__ constexpr size_t mfma_lds_bytes(int RB, int TMV, int NW, int
 // fwd_tile: rows first..last (inclusive, relative to token row t0) of one tile through one adapter, by the whole
 // workgroup.  Rows of the tile outside that range are neither requested as such (loads are clamped into the range) nor
 // stored.  The function may be called several times in a row by a workgroup (its barriers order the reuse of LDS).
-template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L>
+template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L, bool TR>
 __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, const int64_t t0, const int first, const int last) {
     static_assert(NW >= 4, "stage 2 is spread over the first four waves");
     constexpr bool LP = GM == 1, SPLIT = GM == 2 || GM == 3, MASK = GM == 3;
@@ -310,8 +314,13 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
         for (int slot = 0; slot < D1; ++slot)
             if ((ngroups - 1) * D1 + slot < my_n) consume_x(slot);
     }
+    // TR (training instantiation): t is also written, and with y_out == nullptr nothing else is computed.  The inference
+    // instantiation carries none of this.
+    const bool with_y = !TR || a.y_out != nullptr;  // uniform: a kernel argument
+    if (with_y) {
 #pragma unroll
-    for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
+        for (int slot = 0; slot < D2; ++slot) issue_y(slot, slot);
+    }
 
     // ---------------------------------------------------------------- stage 2: reduce, scale, split -
 #pragma unroll
@@ -342,7 +351,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // The waves that run stage 2 build theirs while they wait for the slower waves to finish stage 1.  The others idle
     // during stage 2 anyway: with LP they build theirs there, which takes the work off the slowest wave's way to the
     // first barrier; without LP (a few workgroups, latency-bound) everything is built as early as possible.
-    if (PRE && (!LP || wave < 4)) build_pre();
+    if (PRE && (!LP || wave < 4) && with_y) build_pre();
     __syncthreads();
 
     if (wave < 4) {
@@ -362,6 +371,13 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
 #pragma unroll
                     for (int w = 0; w + st < NW; w += 2 * st) part[w] += part[w + st];
                 }
+                if constexpr (TR) {
+                    if (a.t_out != nullptr) {  // training: keep t for the backward pass
+                        const int row = TMV == 16 ? q * 4 + i : q * 2 + (i & 1);
+                        if ((TMV == 16 || i < 2) && row >= first && row <= last && rb * 16 + li < r)
+                            a.t_out[static_cast<int64_t>(rb * 16 + li) * a.t_stride + t0 + row] = part[0];
+                    }
+                }
                 u[rb] = part[0] * sr[rb][en];
                 amax = fmaxf(amax, fabsf(u[rb]));
             }
@@ -379,10 +395,11 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
                 us[((rb * L + en) * 16 + q * 4 + i) * kURow + 16 + li] = lo;
             }
         }
-    } else if (PRE && LP) {
+    } else if (PRE && LP && with_y) {
         build_pre();
     }
     __syncthreads();
+    if (!with_y) return;  // every wave has passed the last barrier
     // With 8 token rows, MFMA rows 4a+2 and 4a+3 only repeat rows 4a and 4a+1: in stage 3 they carry the SECOND envelope of
     // a pair instead, so that two envelopes cost the matrix-core work and the accumulator registers of one.
     constexpr int VS = TMV == 8 ? (L + 1) / 2 : L;  // accumulator sets per output column
@@ -487,14 +504,14 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     }
 }
 
-template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L>
+template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L, bool TR>
 __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
     if ((GM == 2 || GM == 3) && t0 >= a.T) return;  // padding workgroup (the whole workgroup leaves, before any barrier)
     const int last = static_cast<int>(a.T - 1 - t0 < TMV - 1 ? a.T - 1 - t0 : TMV - 1);  // last live row of the tile
     if constexpr (GM != 4) {
-        fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L>(a, smem, t0, 0, last);
+        fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L, TR>(a, smem, t0, 0, last);
     } else {
         // Multi-adapter batch: the rows of a tile are taken in runs of equal adapter index.  A tile of a sorted batch
         // has one run (two where requests meet), a decode batch has one per row.
@@ -518,7 +535,7 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
             const int id = __builtin_amdgcn_readlane(my_id, first);
             if (id >= 0) {
                 const FwdArgs b = select_adapter(a, id);
-                fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L>(b, smem, t0, first, end);
+                fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L, TR>(b, smem, t0, first, end);
             } else if (a.y_out != a.y_base) {  // no adapter: the rows pass through
                 for (int row = first; row <= end; ++row) {
                     const _Float16* src = a.y_base + (t0 + row) * a.d_out;
@@ -607,9 +624,11 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a0, int
         if (tid < RP) {
             const float tk = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
             u_s[en][tid] = tid < r ? static_cast<float>(a.s_rank[en * r + tid]) * tk : 0.f;
+            if (PLAIN && a.t_out != nullptr && tid < r) a.t_out[static_cast<int64_t>(tid) * a.t_stride + t] = tk;
         }
         __syncthreads();
     }
+    if (PLAIN && a.y_out == nullptr) return;  // only t was wanted
     const _Float16* ybr = a.y_base + t * d_out;
     _Float16* yor = a.y_out + t * d_out;
     for (int j = tid; j < d_out; j += 256) {
@@ -631,11 +650,14 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a0, int
 
 constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
 
-template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L>
+template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L, bool TR = false>
 lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
+    if constexpr (!TR && L == 1 && GM != 4) {  // training calls (t is kept) run their own instantiation
+        if (a.t_out != nullptr) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, GM, L, true>(a, stream);
+    }
     const size_t lds = mfma_lds_bytes(RB, TMV, NW, D1, L);
     if (lds > kMaxLds) return LORDBA_ERR_ALGO;
-    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, BM, GM, L>;
+    auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, BM, GM, L, TR>;
     if (lds > 64 * 1024) {
         // Opt in to more than 64 KiB of dynamic LDS once per device and kernel; raising the limit is idempotent.
         static std::mutex mu;
@@ -788,20 +810,24 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
                            const void* s_in, const void* s_rank, const void* s_out,
                            const void* y_base, void* y_out,
                            int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream, int algo,
-                           const int32_t* ids = nullptr, int64_t n_adapters = 1, bool batched = false) {
+                           const int32_t* ids = nullptr, int64_t n_adapters = 1, bool batched = false,
+                           float* t_out = nullptr, int64_t t_stride = 0) {
     if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || r > LORDBA_MAX_RANK) return LORDBA_ERR_DIM;
     if (batched && (n_adapters < 1 || n_adapters > (1 << 20))) return LORDBA_ERR_DIM;
     if (T > INT32_MAX - 64 || d_in > (1 << 24) || d_out > (1 << 24)) return LORDBA_ERR_DIM;
     if (algo < 0 || algo > (L == 1 ? 7 : 3)) return LORDBA_ERR_ALGO;
     // With no token rows the activation pointers may legitimately be NULL (empty allocations).
     if (T == 0) return (packedA && packedB && s_in && s_rank && s_out) ? LORDBA_OK : LORDBA_ERR_NULL;
-    if (!x || !packedA || !packedB || !s_in || !s_rank || !s_out || !y_base || !y_out) return LORDBA_ERR_NULL;
+    const bool t_only = t_out != nullptr && y_base == nullptr && y_out == nullptr;  // training: only the rank-r intermediate
+    if (!x || !packedA || !packedB || !s_in || !s_rank || !s_out) return LORDBA_ERR_NULL;
+    if (!t_only && (!y_base || !y_out)) return LORDBA_ERR_NULL;
+    if (t_out != nullptr && (L != 1 || batched || t_stride < T || t_stride > INT32_MAX || !aligned(t_out, 4))) return LORDBA_ERR_DIM;
     if (batched && !ids) return LORDBA_ERR_NULL;
     if (batched && !aligned(ids, 4)) return LORDBA_ERR_ALIGN;
     if (!aligned(x, 2) || !aligned(s_in, 2) || !aligned(s_rank, 2) || !aligned(s_out, 2) || !aligned(y_base, 2) ||
         !aligned(y_out, 2) || !aligned(packedA, 4) || !aligned(packedB, 4))
         return LORDBA_ERR_ALIGN;
-    const size_t ny = static_cast<size_t>(T) * d_out * 2, nx = static_cast<size_t>(T) * d_in * 2;
+    const size_t ny = t_only ? 0 : static_cast<size_t>(T) * d_out * 2, nx = static_cast<size_t>(T) * d_in * 2;
     const size_t np = static_cast<size_t>(batched ? n_adapters : 1);  // adapters behind the pool pointers
     const size_t nA = lordba_packed_words(r, d_in) * 4 * np, nB = lordba_packed_words(d_out, r) * 4 * np;
     if (overlaps(y_out, ny, x, nx) || overlaps(y_out, ny, packedA, nA) || overlaps(y_out, ny, packedB, nB) ||
@@ -809,6 +835,11 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
         overlaps(y_out, ny, s_out, np * L * d_out * 2) || (batched && overlaps(y_out, ny, ids, static_cast<size_t>(T) * 4)))
         return LORDBA_ERR_ALIAS;
     if (y_out != y_base && overlaps(y_out, ny, y_base, ny)) return LORDBA_ERR_ALIAS;
+    if (t_out != nullptr) {
+        const size_t nt = (static_cast<size_t>(r - 1) * t_stride + T) * 4;
+        if (overlaps(t_out, nt, x, nx) || overlaps(t_out, nt, y_out, ny) || overlaps(t_out, nt, y_base, ny))
+            return LORDBA_ERR_ALIAS;
+    }
     const lordba_status dev = check_device();
     if (dev != LORDBA_OK) return dev;
 
@@ -829,6 +860,8 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
     a.blocks_per_wg = 0;  // set per launch in grid mode 2
     a.ids = batched ? ids : nullptr;
     a.n_adapters = static_cast<int>(n_adapters);
+    a.t_out = t_out;
+    a.t_stride = static_cast<int>(t_stride);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     // Rows of the scale arrays start at multiples of d_in / d_out elements: the conditions below also align them.

@@ -39,7 +39,7 @@ def new_workspace(torch, nbytes, fill=0xFF):
     return torch.full((nbytes + GUARD,), fill, dtype=torch.uint8, device="cuda:0")
 
 
-def gpu_backward(torch, d, kappa=KAPPA, with_dx=True, inplace=False, ws=None, ws_bytes=None):
+def gpu_backward(torch, d, kappa=KAPPA, with_dx=True, inplace=False, ws=None, ws_bytes=None, keep_t=False):
     """Runs the library on cuda:0.  ws: a buffer from new_workspace (its last GUARD bytes must stay untouched); by default
     a fresh poisoned one of exactly the size the library asks for: the call must not depend on the workspace's contents
     nor write past it.  ws_bytes: the size reported to the library (default: everything before the guard band)."""
@@ -53,9 +53,16 @@ def gpu_backward(torch, d, kappa=KAPPA, with_dx=True, inplace=False, ws=None, ws
     fill = int(ws[-1].item())
     usable = ws.numel() - GUARD if ws_bytes is None else ws_bytes
     dxb = cu(d["dx_base"]) if with_dx else None
+    t_saved = None
+    if keep_t:  # the rank-r intermediate kept by the training forward pass instead of a second pass over x
+        _, pB = binding.lordba_pack_signs(d["signsA"], d["signsB"])
+        stride = binding.saved_t_stride(T)
+        t_saved = torch.full((r, stride), float("nan"), dtype=torch.float32, device="cuda:0")
+        binding.lordba_forward_save_t(cu(d["x"]), cu(pA.view(np.int32)), cu(pB.view(np.int32)), cu(d["s_in"]), cu(d["s_rank"]),
+                                      cu(d["s_out"]), cu(d["y_base"]), t_out=t_saved)
     out = binding.lordba_backward(cu(d["x"]), cu(d["g"]), cu(pA.view(np.int32)), cu(pAt.view(np.int32)), cu(pBt.view(np.int32)),
                                   cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]), cu(d["latA"]), cu(d["latB"]), kappa,
-                                  dx_base=dxb, dx=dxb if inplace else None, workspace=ws[:usable])
+                                  dx_base=dxb, dx=dxb if inplace else None, workspace=ws[:usable], t_saved=t_saved)
     torch.cuda.synchronize()
     assert (ws[ws.numel() - GUARD:].cpu().numpy() == fill).all(), "write past the workspace"
     return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}
@@ -194,6 +201,35 @@ def test_deterministic_and_workspace_reuse(torch_cuda):
         assert np.array_equal(a1[k], a2[k]) and np.array_equal(a1[k], a3[k]), k
         assert np.array_equal(s1[k], s2[k]), k
     compare(s2, oracle_backward(small), "small_after_big")
+
+
+@pytest.mark.parametrize("shape", [(37, 1024, 1152, 16), (203, 1056, 2080, 16), (130, 32, 96, 5), (4133, 512, 256, 32), (33, 512, 1024, 64)],
+                         ids=lambda s: "T%d_%dx%d_r%d" % s)
+def test_forward_that_keeps_t(torch_cuda, shape):
+    """lordba_forward_save_t: y_out bit-identical to lordba_forward, t against the oracle, entries past T untouched; the
+    t-only call gives the same t; lordba_backward fed with the kept t gives what it gives when it recomputes t."""
+    torch = torch_cuda
+    T, d_in, d_out, r = shape
+    d = inputs.make_backward_inputs(32, T, d_in, d_out, r)
+    dev = binding.to_device(d)
+    y_ref = binding.lordba_forward(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"], dev["y_base"])
+    stride = binding.saved_t_stride(T)
+    t_buf = torch.full((r, stride), float("nan"), dtype=torch.float32, device="cuda:0")
+    y, t = binding.lordba_forward_save_t(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                                         dev["y_base"], t_out=t_buf)
+    _, t_only = binding.lordba_forward_save_t(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"])
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_ref)
+    th = t.cpu().numpy()
+    assert np.isnan(th[:, T:]).all(), "t written past T"
+    assert np.array_equal(th[:, :T], t_only.cpu().numpy()[:, :T])
+    want = oracle.rank_intermediate(d["x"], d["signsA"], d["s_in"])
+    e = oracle.row_rel_l2(th[:, :T].T.astype(np.float64), want)
+    assert e.max() <= 1e-5, "t: max row rel-L2 %.3e" % e.max()
+    a = gpu_backward(torch, d)
+    b = gpu_backward(torch, d, keep_t=True)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
 
 
 def test_headline_shape(torch_cuda):

@@ -272,3 +272,21 @@ def test_planted_mistakes_are_caught():
     dS_A = (dt.T @ f["x"]) * f["s_in"][None, :]
     assert _rel(dS_A * kap * (1 - np.tanh(kap * f["latA"]) ** 2), want["d_latA"]) < 1e-12
     assert _rel(dS_A * kap * (1 - np.abs(np.tanh(kap * f["latA"]))), want["d_latA"]) > 1e-3
+
+
+def test_rank_intermediate():
+    """t = (X D_alpha) B1: against a numpy fp64 GEMM, and against the pinned forward oracle read through a second carrier
+    that copies rank k to output column k (r = d_out, S_B = 2 I - 1 needs the all-ones part removed; simpler: two calls)."""
+    d = _inputs(13, 6, 160, 32, 8)
+    f = _f64(d)
+    got = oracle.rank_intermediate(d["x"], d["signsA"], d["s_in"])
+    want = (f["x"] * f["s_in"]) @ f["signsA"].T
+    assert _rel(got, want) < 1e-13
+    # forward oracle with d_out = r, rank scales 1, out scales 1: y = t S_B^T; with S_B = +1 everywhere except -1 on the
+    # diagonal, y_j = sum_k t_k - 2 t_j, so t_j = (sum_k t_k - y_j) / 2 and sum_k t_k = sum_j y_j / (r - 2)
+    r = 8
+    sB = np.ones((r, r), dtype=np.int8) - 2 * np.eye(r, dtype=np.int8)
+    ones = np.ones(r, dtype=np.float16)
+    y = oracle.forward(d["x"], d["signsA"], sB, d["s_in"], ones, ones, np.zeros((6, r), dtype=np.float16))
+    tot = y.sum(axis=1, keepdims=True) / (r - 2)
+    assert _rel((tot - y) / 2, got) < 1e-12
