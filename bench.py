@@ -246,6 +246,12 @@ def bench_backward(args):
         h = host0 if s_ == 0 else inputs.make_backward_inputs(args.seed + 1000 * s_, sh.T, sh.d_in, sh.d_out, sh.r)
         xs.append(cu(h["x"])); gs.append(cu(h["g"])); dxbs.append(cu(h["dx_base"])); dxs.append(torch.empty_like(dxbs[-1]))
     ws = torch.empty(binding.lordba_backward_workspace_bytes(sh.T, sh.d_in, sh.d_out, sh.r), dtype=torch.uint8, device="cuda")
+    kept = [None] * sets
+    if args.keep_t:   # the rank-r intermediate of each set, kept by the training forward (outside the timed region)
+        _, pB = binding.lordba_pack_signs(host0["signsA"], host0["signsB"])
+        dev["pB"] = cu(pB.view(np.int32))
+        for s_ in range(sets):
+            _, kept[s_] = binding.lordba_forward_save_t(xs[s_], dev["pA"], dev["pB"], dev["s_in"], dev["s_rank"], dev["s_out"])
     torch.cuda.synchronize()
     outs = {}
 
@@ -253,7 +259,7 @@ def bench_backward(args):
         s_ = i % sets
         outs[s_] = binding.lordba_backward(xs[s_], gs[s_], dev["pA"], dev["pAt"], dev["pBt"], dev["s_in"], dev["s_rank"],
                                            dev["s_out"], dev["latA"], dev["latB"], args.kappa, dx_base=dxbs[s_], dx=dxs[s_],
-                                           workspace=ws, check=False)
+                                           workspace=ws, check=False, t_saved=kept[s_])
 
     reps_us, wall_s = timed(step, K, max(W, sets), use_graph, reps=3)
     call_us = reps_us[0]
@@ -264,10 +270,10 @@ def bench_backward(args):
            "ms_per_step": wall_s * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "io_dtype": "f16", "data": "synthetic",
            "config": {"workload": sh.name, "pass": "backward", "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
-                      "kappa": args.kappa, "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
+                      "kappa": args.kappa, "t": "kept by the forward pass" if args.keep_t else "recomputed from x", "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                         "traffic": None, "kernel_us": call_us, "kernel_us_repetitions": reps_us, "algorithmic_bytes": alg,
-                        "note": "all kernels of one call taken together (clear, dx, rank, wgrad, finish)"}}
+                        "note": "all kernels of one call taken together (dx + du, t unless kept, wgrad, finish)"}}
     if not args.no_cpu_baseline:
         import oracle
         rows = min(sh.T, 256)
@@ -303,6 +309,8 @@ def main():
                          "(decode, one token per request) or segments with rows that have no adapter")
     ap.add_argument("--backward", action="store_true", help="time lordba_backward (the branch's backward pass in training) "
                     "instead of the forward call; single-shape workloads only")
+    ap.add_argument("--keep-t", action="store_true", help="--backward: pass the rank-r intermediate kept by "
+                    "lordba_forward_save_t instead of letting lordba_backward recompute it from x")
     ap.add_argument("--kappa", type=float, default=100.0, help="temperature of the smooth-sign factor (--backward)")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to cycle through (0 = enough to defeat the cache)")
     ap.add_argument("--algo", type=int, default=0, help="kernel selector passed to lordba_forward_algo (0 = library default)")

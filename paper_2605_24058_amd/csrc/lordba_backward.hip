@@ -50,6 +50,7 @@ BwdPlan make_plan(int64_t T, int64_t d_in, int64_t d_out, int64_t r) {
     BwdPlan p;
     p.rp = static_cast<int>((r + 15) / 16 * 16);
     p.t_pad = static_cast<int>((T + 127) / 128 * 128);
+    p.t_pad = p.t_pad < 128 ? 128 : p.t_pad;  // T == 0 still yields a well-formed (unused) plan
     p.nbx = static_cast<int>((d_in + 127) / 128);
     p.nbg = static_cast<int>((d_out + 127) / 128);
     p.dcols = (p.nbx + p.nbg) * 128;

@@ -32,11 +32,11 @@ def test_exports_every_declared_symbol(lib):
 
 def test_status_strings(lib):
     seen = set()
-    for code in range(0, 9):
+    for code in range(0, 10):
         s = binding.lordba_status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 9
+    assert len(seen) == 10
     assert binding.lordba_status_string(1234) == "unknown status"
 
 
@@ -115,6 +115,46 @@ def test_forward_validation_needs_no_device(lib):
     assert f(x, pA, pB, si, sr, so, yb, yo, 0, d_in, d_out, r) == 0          # T == 0: nothing to do
     assert f(x, pA, pB, si, sr, so, yb, yb, 0, d_in, d_out, r) == 0          # in-place is legal
     assert lib.lordba_forward_algo(x, pA, pB, si, sr, so, yb, yo, T, d_in, d_out, r, None, 99) == 8
+
+
+def test_backward_validation_needs_no_device(lib):
+    """lordba_backward and lordba_forward_save_t reject bad arguments before any device work (fake addresses)."""
+    base = 0x10000000
+    names = ["x", "g", "pA", "pAt", "pBt", "si", "sr", "so", "lA", "lB", "dxb", "dx", "dsi", "dsr", "dso", "dlA", "dlB", "ws", "ts"]
+    p = {n: base + i * 0x1000000 for i, n in enumerate(names)}
+    T, d_in, d_out, r = 4, 64, 96, 8
+    need = lib.lordba_backward_workspace_bytes(T, d_in, d_out, r)
+    assert need > 0 and need % 4 == 0
+    assert lib.lordba_backward_workspace_bytes(T, 72, d_out, r) == 0          # widths must be multiples of 32
+    assert lib.lordba_backward_workspace_bytes(T, d_in, d_out, 0) == 0
+    assert lib.lordba_backward_workspace_bytes(0, d_in, d_out, r) > 0
+
+    def call(T=T, d_in=d_in, d_out=d_out, r=r, ws_bytes=need, ts=None, t_stride=0, kappa=100.0, **over):
+        q = dict(p); q.update(over)
+        return lib.lordba_backward(q["x"], q["g"], q["pA"], q["pAt"], q["pBt"], q["si"], q["sr"], q["so"], q["lA"], q["lB"],
+                                   ctypes.c_float(kappa), ts, t_stride, q["dxb"], q["dx"], q["dsi"], q["dsr"], q["dso"], q["dlA"],
+                                   q["dlB"], q["ws"], ws_bytes, T, d_in, d_out, r, None)
+
+    for n in ("pA", "pAt", "pBt", "si", "sr", "so", "lA", "lB", "dsi", "dsr", "dso", "dlA", "dlB", "ws", "x", "g"):
+        assert call(**{n: None}) == 1, n
+    assert call(dx=None) == 1 and call(dxb=None) == 1                           # dx and dx_base come or go together
+    assert call(d_in=72) == 2 and call(r=65) == 2 and call(T=-1) == 2
+    assert call(ws_bytes=need - 4) == 9
+    assert call(x=p["x"] + 2) == 5 and call(ws=p["ws"] + 4) == 5
+    assert call(ts=p["ts"], t_stride=4) == 2                                    # a kept t must reach the padded token count
+    assert call(ts=p["ts"] + 4, t_stride=128) == 5
+    # lordba_forward_save_t: t_out is required, must not overlap the activations, t_stride >= T
+    f = lambda *a: lib.lordba_forward_save_t(*a, None)
+    yb, yo = p["dxb"], p["dx"]
+    ok = [p["x"], p["pA"], p["pBt"], p["si"], p["sr"], p["so"], yb, yo, p["ts"], 128, T, d_in, d_out, r]
+    a = list(ok); a[8] = None
+    assert f(*a) == 1
+    a = list(ok); a[9] = T - 1
+    assert f(*a) == 2
+    a = list(ok); a[8] = p["x"]
+    assert f(*a) == 4
+    a = list(ok); a[6] = None                                                   # y_base without y_out
+    assert f(*a) == 1
 
 
 def test_forward_multi_validation_needs_no_device(lib):
