@@ -161,6 +161,18 @@ lordba_status lordba_forward_batched_algo(const void* x, const uint32_t* packedA
                                           int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t n_adapters,
                                           void* stream, int algo);
 
+/* DEVICE function: binarises and packs the latent carriers on the device, as every training step does before its
+ * forward pass (B1 = sign(U1), B2 = sign(U2), Sec. 3.2; Alg. QAT-LoRDBA), sign(0) = +1 (Sec. 2, Notation; -0.0 counts as
+ * zero).  latentA fp32 [r, d_in], latentB fp32 [d_out, r] (device memory).  Outputs, each in the canonical packed format
+ * and each optional (NULL = not wanted): packedA = S_A as [r, d_in], packedB = S_B as [d_out, r] (what lordba_forward
+ * takes), packedAt = S_A^T as [d_in, r], packedBt = S_B^T as [r, d_out] (what lordba_backward takes besides packedA).
+ * Bit-identical to lordba_pack_signs_f32 applied to the latents and to their transposes, except that a NaN, which the
+ * host function rejects, packs as +1 here (an enqueue-only call has no way to report it).  Enqueues one kernel on
+ * `stream`; never synchronises, allocates or frees. */
+lordba_status lordba_pack_latents(const float* latentA, const float* latentB,
+                                  uint32_t* packedA, uint32_t* packedB, uint32_t* packedAt, uint32_t* packedBt,
+                                  int64_t d_in, int64_t d_out, int64_t r, void* stream);
+
 /* DEVICE function: the forward branch as training runs it (Sec. 3.2): lordba_forward, which also keeps the rank-r
  * intermediate of Eq. (lordba-fwd) for the backward pass,
  *   t_out[k * t_stride + t] = sum_i S_A[k, i] * s_in[i] * x[t, i]        fp32, rank-major, k < r, t < T, t_stride >= T

@@ -18,7 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
 _LIB_PATH = os.path.join(_PKG, "liblordba.so")
-_SOURCES = ("lordba_forward.hip", "lordba_forward_multi.hip", "lordba_backward.hip", "lordba_pack.cpp")
+_SOURCES = ("lordba_forward.hip", "lordba_forward_multi.hip", "lordba_backward.hip", "lordba_pack_device.hip", "lordba_pack.cpp")
 _lib = None
 
 ALGO_AUTO, ALGO_GENERAL, ALGO_MFMA_T8, ALGO_MFMA_T16 = 0, 1, 2, 3
@@ -136,6 +136,8 @@ def load_library():
     lib.lordba_backward_workspace_bytes.argtypes = [i64] * 4
     lib.lordba_backward.restype = ci
     lib.lordba_backward.argtypes = [vp] * 10 + [ctypes.c_float, vp, i64] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 4 + [vp]
+    lib.lordba_pack_latents.restype = ci
+    lib.lordba_pack_latents.argtypes = [vp] * 6 + [i64] * 3 + [vp]
     lib.lordba_forward_save_t.restype = ci
     lib.lordba_forward_save_t.argtypes = [vp] * 9 + [i64] * 5 + [vp]
     lib.lordba_status_string.restype = ctypes.c_char_p
@@ -342,6 +344,33 @@ def lordba_pack_transposed(signsA, signsB) -> Tuple[np.ndarray, np.ndarray]:
     # lordba_pack_signs(signsA [r', d_in'], signsB [d_out', r']) with r' = r, d_in' = d_out, d_out' = d_in
     pBt, pAt = lordba_pack_signs(B, A)
     return pAt, pBt
+
+
+def lordba_pack_latents(latentA, latentB, stream=None, transposed: bool = True):
+    """Device-side binarisation and packing of the latent carriers (torch CUDA float32 tensors latentA [r, d_in],
+    latentB [d_out, r]).  Returns int32 CUDA tensors (packedA, packedB, packedAt, packedBt); the last two are None unless
+    `transposed`."""
+    import torch
+
+    lib = load_library()
+    r, d_in = latentA.shape
+    d_out = latentB.shape[0]
+    if tuple(latentB.shape) != (d_out, r) or latentA.dtype != torch.float32 or latentB.dtype != torch.float32:
+        raise ValueError("need float32 latentA [r, d_in] and latentB [d_out, r]")
+    wA, wB = (r * d_in + 31) // 32, (d_out * r + 31) // 32
+    new = lambda n: torch.empty(n, dtype=torch.int32, device=latentA.device)
+    pA, pB = new(wA), new(wB)
+    pAt, pBt = (new(wA), new(wB)) if transposed else (None, None)
+    if stream is None:
+        stream = torch.cuda.current_stream(latentA.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    ptr = lambda t_: None if t_ is None else t_.data_ptr()
+    st = lib.lordba_pack_latents(latentA.contiguous().data_ptr(), latentB.contiguous().data_ptr(), pA.data_ptr(), pB.data_ptr(),
+                                 ptr(pAt), ptr(pBt), d_in, d_out, r, ctypes.c_void_p(stream))
+    if st != 0:
+        raise LordbaError(st, "lordba_pack_latents")
+    return pA, pB, pAt, pBt
 
 
 def saved_t_stride(T: int) -> int:

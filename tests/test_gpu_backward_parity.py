@@ -249,3 +249,34 @@ def test_argument_errors(torch_cuda):
     assert e.value.status == 9
     assert binding.lordba_backward_workspace_bytes(16, 250, 256, 8) == 0      # d_in not a multiple of 32
     assert binding.lordba_backward_workspace_bytes(16, 256, 256, 65) == 0
+
+
+@pytest.mark.parametrize("shape", [(512, 512, 4), (4096, 4096, 16), (96, 40, 7), (33, 17, 1), (64, 64, 64), (4096, 11008, 16), (40, 3, 3)],
+                         ids=lambda s: "%dx%d_r%d" % s)
+def test_pack_latents_on_the_device_is_bit_exact(torch_cuda, shape):
+    """lordba_pack_latents against the oracle's own sign (sign(0) = +1) and packer, for the four packed carriers; zeros of
+    both signs and subnormals among the latents; pad bits 0."""
+    torch = torch_cuda
+    d_in, d_out, r = shape
+    g = np.random.default_rng(40)
+    latA = g.standard_normal((r, d_in)).astype(np.float32)
+    latB = g.standard_normal((d_out, r)).astype(np.float32)
+    for lat in (latA, latB):
+        flat = lat.reshape(-1)
+        idx = g.permutation(flat.size)[: max(4, flat.size // 8)]
+        flat[idx[0::4]] = 0.0
+        flat[idx[1::4]] = -0.0
+        flat[idx[2::4]] = 1e-42
+        flat[idx[3::4]] = -1e-42
+    pA, pB, pAt, pBt = binding.lordba_pack_latents(torch.from_numpy(latA).cuda(), torch.from_numpy(latB).cuda())
+    torch.cuda.synchronize()
+    sA, sB = oracle.sign(latA), oracle.sign(latB)
+    for got, want in ((pA, oracle.pack(sA)), (pB, oracle.pack(sB)), (pAt, oracle.pack(np.ascontiguousarray(sA.T))),
+                      (pBt, oracle.pack(np.ascontiguousarray(sB.T)))):
+        assert np.array_equal(got.cpu().numpy().view(np.uint32), want)
+    # the same words as the library's host packer, and a call that wants only two of the four
+    hA, hB = binding.lordba_pack_signs(latA, latB)
+    assert np.array_equal(pA.cpu().numpy().view(np.uint32), hA) and np.array_equal(pB.cpu().numpy().view(np.uint32), hB)
+    qA, qB, qAt, qBt = binding.lordba_pack_latents(torch.from_numpy(latA).cuda(), torch.from_numpy(latB).cuda(), transposed=False)
+    torch.cuda.synchronize()
+    assert qAt is None and qBt is None and torch.equal(qA, pA) and torch.equal(qB, pB)
