@@ -31,6 +31,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size
 # (profiles/lordba_fwd_mfma_c2_hbm_traffic.txt); bench.py cannot read hardware counters itself.
 MEASURED_TRAFFIC_BYTES = {"c2_llama7b_attn_4096x4096_r16_T2048": 49487 * 1024}
+# the same for lordba_backward (profiles/lordba_backward_c2_hbm_traffic.txt): t recomputed from x / t kept by the forward
+MEASURED_BACKWARD_TRAFFIC_BYTES = {"c2_llama7b_attn_4096x4096_r16_T2048": (106605 * 1024, 89900 * 1024)}
 CACHE_BYTES = 256 << 20        # Infinity Cache
 
 WORKLOADS = {}
@@ -272,7 +274,8 @@ def bench_backward(args):
            "config": {"workload": sh.name, "pass": "backward", "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
                       "kappa": args.kappa, "t": "kept by the forward pass" if args.keep_t else "recomputed from x", "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                        "traffic": None, "kernel_us": call_us, "kernel_us_repetitions": reps_us, "algorithmic_bytes": alg,
+                        "traffic": (MEASURED_BACKWARD_TRAFFIC_BYTES.get(sh.name) or (None, None))[1 if args.keep_t else 0],
+                        "kernel_us": call_us, "kernel_us_repetitions": reps_us, "algorithmic_bytes": alg,
                         "note": "all kernels of one call taken together (dx + du, t unless kept, wgrad, finish)"}}
     if not args.no_cpu_baseline:
         import oracle
