@@ -206,7 +206,7 @@ lordba_status lordba_forward_save_t(const void* x, const uint32_t* packedA, cons
  *   workspace: at least lordba_backward_workspace_bytes(T, d_in, d_out, r) bytes of device memory, 16-byte aligned, owned
  *   by the caller, contents irrelevant before and after; a smaller one -> LORDBA_ERR_WORKSPACE.  Calls that share a
  *   workspace must not overlap in time.
- * No output may overlap an input or another output (dx == dx_base excepted); this is not checked.
+ * No output, nor the workspace, may overlap an input or another output (dx == dx_base excepted): LORDBA_ERR_ALIAS.
  * Shapes: d_in and d_out multiples of 32, 1 <= r <= 64, activations, scales and packed carriers 16-byte aligned; else
  * LORDBA_ERR_DIM / LORDBA_ERR_ALIGN.  T == 0: the parameter gradients are set to zero.
  * The call only enqueues kernels on `stream`; it never synchronises, allocates or frees.  Results are deterministic

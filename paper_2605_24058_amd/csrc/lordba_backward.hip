@@ -462,6 +462,31 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
         return LORDBA_ERR_ALIGN;
     const BwdPlan p = make_plan(T, d_in, d_out, r);
     if (workspace_bytes < p.words * 4) return LORDBA_ERR_WORKSPACE;
+    {
+        // No output (and not the workspace) may overlap an input or another output; dx on top of dx_base is the one
+        // exception and is checked by the forward call below.
+        struct Span { const void* p; size_t n; };
+        const size_t nx = static_cast<size_t>(T) * d_in * 2, ng = static_cast<size_t>(T) * d_out * 2;
+        const size_t nA = static_cast<size_t>(r) * d_in, nB = static_cast<size_t>(d_out) * r;
+        const Span outs[] = {{d_s_in, static_cast<size_t>(d_in) * 4}, {d_s_rank, static_cast<size_t>(r) * 4},
+                             {d_s_out, static_cast<size_t>(d_out) * 4}, {d_latentA, nA * 4}, {d_latentB, nB * 4},
+                             {workspace, p.words * 4}, {dx, dx ? nx : 0}};
+        const Span ins[] = {{x, nx}, {g, ng}, {packedA, lordba_packed_words(r, d_in) * 4}, {packedAt, lordba_packed_words(d_in, r) * 4},
+                            {packedBt, lordba_packed_words(r, d_out) * 4}, {s_in, static_cast<size_t>(d_in) * 2},
+                            {s_rank, static_cast<size_t>(r) * 2}, {s_out, static_cast<size_t>(d_out) * 2}, {latentA, nA * 4},
+                            {latentB, nB * 4}, {t_saved, t_saved ? (static_cast<size_t>(r - 1) * t_stride + T) * 4 : 0}};
+        auto hit = [](const Span& a, const Span& b) {
+            const uintptr_t pa = reinterpret_cast<uintptr_t>(a.p), pb = reinterpret_cast<uintptr_t>(b.p);
+            return a.n != 0 && b.n != 0 && pa < pb + b.n && pb < pa + a.n;
+        };
+        constexpr int no = sizeof(outs) / sizeof(outs[0]), ni = sizeof(ins) / sizeof(ins[0]);
+        for (int i = 0; i < no; ++i) {
+            for (int j = 0; j < ni; ++j)
+                if (hit(outs[i], ins[j])) return LORDBA_ERR_ALIAS;
+            for (int j = i + 1; j < no; ++j)
+                if (hit(outs[i], outs[j])) return LORDBA_ERR_ALIAS;
+        }
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     if (T == 0) {  // no token rows: every parameter gradient is zero

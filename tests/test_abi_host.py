@@ -141,6 +141,8 @@ def test_backward_validation_needs_no_device(lib):
     assert call(d_in=72) == 2 and call(r=65) == 2 and call(T=-1) == 2
     assert call(ws_bytes=need - 4) == 9
     assert call(x=p["x"] + 2) == 5 and call(ws=p["ws"] + 4) == 5
+    assert call(dsi=p["x"]) == 4 and call(dlA=p["lA"]) == 4 and call(ws=p["g"]) == 4 and call(dso=p["dsi"]) == 4   # overlaps
+    assert call(dx=p["x"]) == 4
     assert call(ts=p["ts"], t_stride=4) == 2                                    # a kept t must reach the padded token count
     assert call(ts=p["ts"] + 4, t_stride=128) == 5
     # lordba_forward_save_t: t_out is required, must not overlap the activations, t_stride >= T

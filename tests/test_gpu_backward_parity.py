@@ -232,6 +232,41 @@ def test_forward_that_keeps_t(torch_cuda, shape):
         assert np.array_equal(a[k], b[k]), k
 
 
+def test_hip_graph_replays_match_eager(torch_cuda):
+    """bench.py replays a captured graph of backward calls: several replays, with eager work and synchronisations in
+    between, against the eager result (the call records kernel nodes only: no memset, no allocation)."""
+    torch = torch_cuda
+    T, d_in, d_out, r = 300, 1024, 768, 16
+    d = inputs.make_backward_inputs(33, T, d_in, d_out, r)
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    pA, _ = binding.lordba_pack_signs(d["signsA"], d["signsB"])
+    pAt, pBt = binding.lordba_pack_transposed(d["signsA"], d["signsB"])
+    w = lambda a: cu(a.view(np.int32))
+    args = (cu(d["x"]), cu(d["g"]), w(pA), w(pAt), w(pBt), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]), cu(d["latA"]), cu(d["latB"]), KAPPA)
+    dxb = cu(d["dx_base"])
+    ws = torch.empty(binding.lordba_backward_workspace_bytes(T, d_in, d_out, r), dtype=torch.uint8, device="cuda:0")
+    eager = binding.lordba_backward(*args, dx_base=dxb, workspace=ws)
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in eager.items()}
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rec = binding.lordba_backward(*args, dx_base=dxb, workspace=ws)
+    for rep in range(4):
+        for v in rec.values():
+            v.fill_(float("nan"))
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in eager:
+            assert torch.equal(rec[k], eager[k]), (rep, k)
+        again = binding.lordba_backward(*args, dx_base=dxb, workspace=ws)      # eager work between replays
+        torch.cuda.synchronize()
+        for k in eager:
+            assert torch.equal(again[k], eager[k]), (rep, k)
+    compare({k: v.cpu().numpy() for k, v in eager.items()}, oracle_backward(d), "graph_replay")
+
+
 def test_headline_shape(torch_cuda):
     """d_in = d_out = 4096, r = 16, T = 2048 (the launch configuration bench.py times), every output against the oracle."""
     d = inputs.make_backward_inputs(30, 2048, 4096, 4096, 16)
