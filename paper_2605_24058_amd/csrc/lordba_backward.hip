@@ -350,53 +350,21 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
     const uint32_t* pk = is_x ? a.pA : a.pBt;   // both [r, d]: the group's 32 bits of rank k are one word
     const float scale = static_cast<float>(is_x ? a.s_in[col] : a.s_out[col]);
     const int r = a.r;
-    // Every load of the workgroup is requested before the first wait: the latentB tile (d_out side: the group's 32 rows of
-    // latentB [d_out, r] are 32 r contiguous floats, staged through LDS for coalesced accesses), then the partial sums.
-    constexpr int KMAX = LORDBA_MAX_RANK / 8;
-    float lt[KMAX];
-#pragma unroll
-    for (int j = 0; j < KMAX; ++j) {
-        if (is_x) {   // latentA [r, d_in]: the thread's own entries (k, col)
-            const int k = kq + 8 * j;
-            lt[j] = k < r ? a.latA[static_cast<size_t>(k) * d + col] : 0.f;
-        } else {      // the tile of latentB, element tid + 256 j
-            const int e = tid + 256 * j;
-            lt[j] = e < 32 * r ? a.latB[static_cast<size_t>(grp) * 32 * r + e] : 0.f;
-        }
-    }
-    float sv[KMAX];
-    float dscale = 0.f;
-#pragma unroll
-    for (int j = 0; j < KMAX; ++j) {
-        const int k = kq + 8 * j;
-        float sum = 0.f;
-        if (k < r) {
-            for (int sp = 0; sp < a.splits; ++sp) sum += plane[(static_cast<size_t>(sp) * a.rp + k) * a.dcols];
-            const uint32_t bit = (pk[k * (d >> 5) + grp] >> c) & 1u;
-            dscale += flip(sum, bit);
-        }
-        sv[j] = sum;
-    }
-    if (is_x) {
-#pragma unroll
-        for (int j = 0; j < KMAX; ++j) {
-            const int k = kq + 8 * j;
-            if (k < r) {
-                const size_t n = static_cast<size_t>(k) * d + col;
-                a.d_latA[n] = scale * sv[j] * smooth_sign_factor(lt[j], a.kappa);
-            }
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < KMAX; ++j) {
-            const int e = tid + 256 * j;
-            if (e < 32 * r) lat[e] = lt[j];
-        }
+    if (!is_x) {  // latentB [d_out, r]: the group's 32 rows are 32 r contiguous floats; through LDS for coalesced accesses
+        for (int e = tid; e < 32 * r; e += 256) lat[e] = a.latB[static_cast<size_t>(grp) * 32 * r + e];
         __syncthreads();
-#pragma unroll
-        for (int j = 0; j < KMAX; ++j) {
-            const int k = kq + 8 * j;
-            if (k < r) lat[c * r + k] = scale * sv[j] * smooth_sign_factor(lat[c * r + k], a.kappa);
+    }
+    float dscale = 0.f;
+    for (int k = kq; k < r; k += 8) {
+        float s = 0.f;
+        for (int sp = 0; sp < a.splits; ++sp) s += plane[(static_cast<size_t>(sp) * a.rp + k) * a.dcols];
+        const uint32_t bit = (pk[k * (d >> 5) + grp] >> c) & 1u;
+        dscale += flip(s, bit);
+        if (is_x) {
+            const size_t n = static_cast<size_t>(k) * d + col;
+            a.d_latA[n] = scale * s * smooth_sign_factor(a.latA[n], a.kappa);
+        } else {
+            lat[c * r + k] = scale * s * smooth_sign_factor(lat[c * r + k], a.kappa);
         }
     }
     sh[tid] = dscale;

@@ -124,7 +124,10 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     static_assert(!R8 || RB == 1, "r = 8 is one rank block");
     constexpr bool PRE = (R16 || R8) && RB == 1;  // sign operands of the first block are built before u is known
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // The wave index is read into a scalar register: what depends on it (which chunks and blocks a wave owns, which waves
+    // run stage 2) then branches on scalar conditions.  MFMA instructions ignore the EXEC mask, so they must never end up
+    // under a vector-predicated branch, which is what a condition on a value derived from threadIdx may compile to.
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, q = lane >> 4;
     const int d_in = a.d_in, d_out = a.d_out, r = a.r;
     const int nchunks = (d_in + 127) >> 7;
@@ -354,6 +357,23 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     if (PRE && (!LP || wave < 4) && with_y) build_pre();
     __syncthreads();
 
+    // Training: the rank-r intermediate t (before the rank scaling) is kept for the backward pass.  The stores are issued
+    // after everything else: vector memory stores count in the same counter as the loads and may complete out of order
+    // with them, so that a wait for y_base issued after such a store could also have to wait for the store.
+    float tkeep[TR ? RB : 1];
+    auto export_t = [&]() {
+        if constexpr (TR) {
+            if (wave < 4 && a.t_out != nullptr) {
+                const int i = wave;
+                const int row = TMV == 16 ? q * 4 + i : q * 2 + (i & 1);
+                if ((TMV == 16 || i < 2) && row >= first && row <= last) {
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        if (rb * 16 + li < r) a.t_out[static_cast<int64_t>(rb * 16 + li) * a.t_stride + t0 + row] = tkeep[rb];
+                }
+            }
+        }
+    };
     if (wave < 4) {
         // Accumulator layout: lane (li, q) holds rank li of the block for MFMA rows 4q .. 4q+3; wave i takes row 4q+i.
         const int i = wave;
@@ -371,13 +391,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
 #pragma unroll
                     for (int w = 0; w + st < NW; w += 2 * st) part[w] += part[w + st];
                 }
-                if constexpr (TR) {
-                    if (a.t_out != nullptr) {  // training: keep t for the backward pass
-                        const int row = TMV == 16 ? q * 4 + i : q * 2 + (i & 1);
-                        if ((TMV == 16 || i < 2) && row >= first && row <= last && rb * 16 + li < r)
-                            a.t_out[static_cast<int64_t>(rb * 16 + li) * a.t_stride + t0 + row] = part[0];
-                    }
-                }
+                if constexpr (TR) tkeep[rb] = part[0];  // training: t is written out at the very end (see export_t)
                 u[rb] = part[0] * sr[rb][en];
                 amax = fmaxf(amax, fabsf(u[rb]));
             }
@@ -399,7 +413,10 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
         build_pre();
     }
     __syncthreads();
-    if (!with_y) return;  // every wave has passed the last barrier
+    if (!with_y) {  // every wave has passed the last barrier
+        export_t();
+        return;
+    }
     // With 8 token rows, MFMA rows 4a+2 and 4a+3 only repeat rows 4a and 4a+1: in stage 3 they carry the SECOND envelope of
     // a pair instead, so that two envelopes cost the matrix-core work and the accumulator registers of one.
     constexpr int VS = TMV == 8 ? (L + 1) / 2 : L;  // accumulator sets per output column
@@ -502,6 +519,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
             if (n + D2 < my_b) issue_y(slot, n + D2);
         }
     }
+    export_t();
 }
 
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L, bool TR>

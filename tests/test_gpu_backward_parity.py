@@ -274,6 +274,17 @@ def test_headline_shape(torch_cuda):
     compare(got, oracle_backward(d), "c2_backward")
 
 
+@pytest.mark.parametrize("shape", [(4096, 4096, 11008, 16), (4096, 5120, 5120, 16)], ids=lambda s: "T%d_%dx%d_r%d" % s)
+def test_large_shapes_in_their_launch_configuration(torch_cuda, shape):
+    """The MLP up-projection shape at its own T = 4096 (86 column blocks, the last one partial) and the 5120-wide
+    attention shape at T = 4096: 16-row tiles in the dx / t kernels, two wgrad workgroups per CU, as bench.py launches them.
+    Every output against the oracle (the oracle needs some ten seconds per shape)."""
+    T, d_in, d_out, r = shape
+    d = inputs.make_backward_inputs(34, T, d_in, d_out, r)
+    got = gpu_backward(torch_cuda, d, keep_t=True)
+    compare(got, oracle_backward(d), "T%d_%dx%d_r%d" % shape)
+
+
 def test_argument_errors(torch_cuda):
     torch = torch_cuda
     d = inputs.make_backward_inputs(31, 16, 256, 256, 8)
