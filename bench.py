@@ -257,7 +257,23 @@ def bench_backward(args):
     torch.cuda.synchronize()
     outs = {}
 
+    y_bases = [cu(host0["y_base"]) if s_ == 0 else torch.randn_like(gs[0]) for s_ in range(sets)] if args.train_step else None
+    y_outs = [torch.empty_like(y) for y in y_bases] if args.train_step else None
+    t_bufs = [torch.empty((sh.r, binding.saved_t_stride(sh.T)), dtype=torch.float32, device="cuda") for _ in range(sets)] if args.train_step else None
+
+    def train_step(i):
+        """One training step of the branch: sign and pack the latents, forward (keeping t), backward."""
+        s_ = i % sets
+        pA_, pB_, pAt_, pBt_ = binding.lordba_pack_latents(dev["latA"], dev["latB"])
+        binding.lordba_forward_save_t(xs[s_], pA_, pB_, dev["s_in"], dev["s_rank"], dev["s_out"], y_bases[s_], y_out=y_outs[s_],
+                                      t_out=t_bufs[s_])
+        outs[s_] = binding.lordba_backward(xs[s_], gs[s_], pA_, pAt_, pBt_, dev["s_in"], dev["s_rank"], dev["s_out"], dev["latA"],
+                                           dev["latB"], args.kappa, dx_base=dxbs[s_], dx=dxs[s_], workspace=ws, check=False,
+                                           t_saved=t_bufs[s_])
+
     def step(i):
+        if args.train_step:
+            return train_step(i)
         s_ = i % sets
         outs[s_] = binding.lordba_backward(xs[s_], gs[s_], dev["pA"], dev["pAt"], dev["pBt"], dev["s_in"], dev["s_rank"],
                                            dev["s_out"], dev["latA"], dev["latB"], args.kappa, dx_base=dxbs[s_], dx=dxs[s_],
@@ -266,15 +282,18 @@ def bench_backward(args):
     reps_us, wall_s = timed(step, K, max(W, sets), use_graph, reps=3)
     call_us = reps_us[0]
     alg = backward_algorithmic_bytes(sh)
+    if args.train_step:   # + the forward call + reading the latents and writing the four packed carriers
+        alg += sh.algorithmic_bytes() + 4 * sh.T * sh.r + 4 * sh.r * (sh.d_in + sh.d_out) + 4 * ((sh.r * (sh.d_in + sh.d_out) + 7) // 8)
     achieved = alg / (call_us * 1e-6) / 1e9
-    out = {"metric": "adapter-branch backward (dx, scale and latent-carrier gradients) tokens/s and achieved HBM GB/s",
+    out = {"metric": ("adapter-branch training step (pack latents, forward, backward) tokens/s and achieved HBM GB/s" if args.train_step else
+                      "adapter-branch backward (dx, scale and latent-carrier gradients) tokens/s and achieved HBM GB/s"),
            "value": sh.T * K / wall_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
            "ms_per_step": wall_s * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "io_dtype": "f16", "data": "synthetic",
-           "config": {"workload": sh.name, "pass": "backward", "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
+           "config": {"workload": sh.name, "pass": "train_step" if args.train_step else "backward", "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
                       "kappa": args.kappa, "t": "kept by the forward pass" if args.keep_t else "recomputed from x", "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                        "traffic": (MEASURED_BACKWARD_TRAFFIC_BYTES.get(sh.name) or (None, None))[1 if args.keep_t else 0],
+                        "traffic": None if args.train_step else (MEASURED_BACKWARD_TRAFFIC_BYTES.get(sh.name) or (None, None))[1 if args.keep_t else 0],
                         "kernel_us": call_us, "kernel_us_repetitions": reps_us, "algorithmic_bytes": alg,
                         "note": "all kernels of one call taken together (dx + du, t unless kept, wgrad, finish)"}}
     if not args.no_cpu_baseline:
@@ -286,6 +305,10 @@ def bench_backward(args):
         c1 = time.perf_counter()
         step(0)
         torch.cuda.synchronize()
+        if args.train_step:   # the forward output of the step, same rows
+            ywant = oracle.forward(host0["x"][:rows], host0["signsA"], host0["signsB"], host0["s_in"], host0["s_rank"], host0["s_out"],
+                                   host0["y_base"][:rows])
+            out["parity_max_row_rel_l2_y"] = float(oracle.row_rel_l2(y_outs[0][:rows].cpu().numpy().astype(np.float64), ywant).max())
         err = float(oracle.row_rel_l2(dxs[0][:rows].cpu().numpy().astype(np.float64), want["dx"]).max())
         out["cpu_baseline"] = {"value": rows / (c1 - c0), "unit": "tokens/s", "cores": 1, "kind": "oracle",
                                "sample": "the first %d of %d token rows of the same workload, one host thread" % (rows, sh.T)}
@@ -312,6 +335,8 @@ def main():
                          "(decode, one token per request) or segments with rows that have no adapter")
     ap.add_argument("--backward", action="store_true", help="time lordba_backward (the branch's backward pass in training) "
                     "instead of the forward call; single-shape workloads only")
+    ap.add_argument("--train-step", action="store_true", help="time one training step of the branch: lordba_pack_latents, "
+                    "lordba_forward_save_t, lordba_backward with the kept t (implies --backward)")
     ap.add_argument("--keep-t", action="store_true", help="--backward: pass the rank-r intermediate kept by "
                     "lordba_forward_save_t instead of letting lordba_backward recompute it from x")
     ap.add_argument("--kappa", type=float, default=100.0, help="temperature of the smooth-sign factor (--backward)")
@@ -347,7 +372,7 @@ def main():
     args.warmup = 240 if args.warmup is None else args.warmup
     if args.workload == "c4_sweep":
         return bench_c4_sweep(args)
-    if args.backward:
+    if args.backward or args.train_step:
         args.steps = min(args.steps, 600)
         return bench_backward(args)
     sh = _workloads()[args.workload]

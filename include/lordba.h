@@ -201,6 +201,8 @@ lordba_status lordba_forward_save_t(const void* x, const uint32_t* packedA, cons
  *   t_saved : the rank-r intermediate that lordba_forward_save_t wrote for this x and adapter, with its t_stride, which
  *             must be a multiple of 4 and at least T rounded up to a multiple of 128 (the rows are read in whole steps;
  *             entries past T are ignored), 16-byte aligned; or NULL: it is recomputed from x (one more pass over x).
+ *   d_latentA == NULL and d_latentB == NULL together: the carriers are frozen and only the scales are trained (the
+ *   "QAT Freeze" mode of Sec. 3.2): no latent gradients are computed; latentA, latentB and kappa are then ignored.
  *   dx_base fp16 [T, d_in]: the input gradient of the base path, to which the branch's is added; dx may be the same
  *   pointer.  dx == NULL and dx_base == NULL together: the input gradient is not computed.
  *   workspace: at least lordba_backward_workspace_bytes(T, d_in, d_out, r) bytes of device memory, 16-byte aligned, owned

@@ -424,8 +424,10 @@ def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, late
         for name, t_ in (("packedA", packedA), ("packedAt", packedAt), ("packedBt", packedBt)):
             if t_.dtype != torch.int32 or not t_.is_cuda or not t_.is_contiguous():
                 raise TypeError("%s must be a contiguous int32 CUDA tensor holding the packed words" % name)
+        if (latentA is None) != (latentB is None):
+            raise ValueError("latentA and latentB come or go together (both None: frozen carriers, no latent gradients)")
         for name, t_ in (("latentA", latentA), ("latentB", latentB)):
-            if t_.dtype != torch.float32 or not t_.is_cuda or not t_.is_contiguous():
+            if t_ is not None and (t_.dtype != torch.float32 or not t_.is_cuda or not t_.is_contiguous()):
                 raise TypeError("%s must be a contiguous float32 CUDA tensor" % name)
         if x.dim() != 2 or g.dim() != 2 or x.shape[0] != g.shape[0]:
             raise ValueError("x must be [T, d_in] and g [T, d_out]")
@@ -433,7 +435,8 @@ def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, late
     d_out = g.shape[1]
     r = s_rank.numel()
     if check:
-        if s_in.numel() != d_in or s_out.numel() != d_out or tuple(latentA.shape) != (r, d_in) or tuple(latentB.shape) != (d_out, r):
+        if s_in.numel() != d_in or s_out.numel() != d_out or (latentA is not None and (
+                tuple(latentA.shape) != (r, d_in) or tuple(latentB.shape) != (d_out, r))):
             raise ValueError("scale / latent shapes do not match x / g")
         words = ((r * d_in + 31) // 32, (r * d_out + 31) // 32)
         if packedA.numel() != words[0] or packedAt.numel() != words[0] or packedBt.numel() != words[1]:
@@ -448,17 +451,17 @@ def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, late
         dx = torch.empty_like(dx_base)
     f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=x.device)
     out = {"dx": dx, "d_s_in": f32(d_in), "d_s_rank": f32(r), "d_s_out": f32(d_out),
-           "d_latentA": f32(r, d_in), "d_latentB": f32(d_out, r)}
+           "d_latentA": None if latentA is None else f32(r, d_in), "d_latentB": None if latentB is None else f32(d_out, r)}
     if stream is None:
         stream = torch.cuda.current_stream(x.device).cuda_stream
     elif hasattr(stream, "cuda_stream"):
         stream = stream.cuda_stream
     ptr = lambda t_: None if t_ is None else t_.data_ptr()
     st = lib.lordba_backward(x.data_ptr(), g.data_ptr(), packedA.data_ptr(), packedAt.data_ptr(), packedBt.data_ptr(),
-                             s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(), latentA.data_ptr(), latentB.data_ptr(),
+                             s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(), ptr(latentA), ptr(latentB),
                              float(kappa), ptr(t_saved), 0 if t_saved is None else t_saved.shape[1],
                              ptr(dx_base), ptr(dx), out["d_s_in"].data_ptr(), out["d_s_rank"].data_ptr(),
-                             out["d_s_out"].data_ptr(), out["d_latentA"].data_ptr(), out["d_latentB"].data_ptr(),
+                             out["d_s_out"].data_ptr(), ptr(out["d_latentA"]), ptr(out["d_latentB"]),
                              workspace.data_ptr(), workspace.numel(), T, d_in, d_out, r, ctypes.c_void_p(stream))
     if st != 0:
         raise LordbaError(st, "lordba_backward")

@@ -350,7 +350,7 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
     const uint32_t* pk = is_x ? a.pA : a.pBt;   // both [r, d]: the group's 32 bits of rank k are one word
     const float scale = static_cast<float>(is_x ? a.s_in[col] : a.s_out[col]);
     const int r = a.r;
-    if (!is_x) {  // latentB [d_out, r]: the group's 32 rows are 32 r contiguous floats; through LDS for coalesced accesses
+    if (!is_x && a.d_latB != nullptr) {  // latentB [d_out, r]: the group's 32 rows are 32 r contiguous floats; through LDS for coalesced accesses
         for (int e = tid; e < 32 * r; e += 256) lat[e] = a.latB[static_cast<size_t>(grp) * 32 * r + e];
         __syncthreads();
     }
@@ -360,16 +360,18 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
         for (int sp = 0; sp < a.splits; ++sp) s += plane[(static_cast<size_t>(sp) * a.rp + k) * a.dcols];
         const uint32_t bit = (pk[k * (d >> 5) + grp] >> c) & 1u;
         dscale += flip(s, bit);
-        if (is_x) {
-            const size_t n = static_cast<size_t>(k) * d + col;
-            a.d_latA[n] = scale * s * smooth_sign_factor(a.latA[n], a.kappa);
-        } else {
-            lat[c * r + k] = scale * s * smooth_sign_factor(lat[c * r + k], a.kappa);
+        if (a.d_latA != nullptr) {  // (null: the carriers are frozen, only the scale gradients are wanted)
+            if (is_x) {
+                const size_t n = static_cast<size_t>(k) * d + col;
+                a.d_latA[n] = scale * s * smooth_sign_factor(a.latA[n], a.kappa);
+            } else {
+                lat[c * r + k] = scale * s * smooth_sign_factor(lat[c * r + k], a.kappa);
+            }
         }
     }
     sh[tid] = dscale;
     __syncthreads();
-    if (!is_x)
+    if (!is_x && a.d_latB != nullptr)
         for (int e = tid; e < 32 * r; e += 256) a.d_latB[static_cast<size_t>(grp) * 32 * r + e] = lat[e];
     if (kq == 0) {
         float tot = 0.f;
@@ -415,9 +417,11 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
                                          void* workspace, size_t workspace_bytes,
                                          int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream) {
     if (!supported(T, d_in, d_out, r)) return LORDBA_ERR_DIM;
-    if (!packedA || !packedAt || !packedBt || !s_in || !s_rank || !s_out || !latentA || !latentB || !d_s_in || !d_s_rank ||
-        !d_s_out || !d_latentA || !d_latentB || !workspace)
+    if (!packedA || !packedAt || !packedBt || !s_in || !s_rank || !s_out || !d_s_in || !d_s_rank || !d_s_out || !workspace)
         return LORDBA_ERR_NULL;
+    // frozen carriers (only the scales are trained): no latents, no latent gradients
+    const bool with_latents = d_latentA != nullptr || d_latentB != nullptr;
+    if (with_latents && (!latentA || !latentB || !d_latentA || !d_latentB)) return LORDBA_ERR_NULL;
     if (T > 0 && (!x || !g)) return LORDBA_ERR_NULL;
     if ((dx == nullptr) != (dx_base == nullptr)) return LORDBA_ERR_NULL;
     // a kept t is read in whole 32-row steps: its rows must reach the padded token count
@@ -445,7 +449,7 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
                             {latentB, nB * 4}, {t_saved, t_saved ? (static_cast<size_t>(r - 1) * t_stride + T) * 4 : 0}};
         auto hit = [](const Span& a, const Span& b) {
             const uintptr_t pa = reinterpret_cast<uintptr_t>(a.p), pb = reinterpret_cast<uintptr_t>(b.p);
-            return a.n != 0 && b.n != 0 && pa < pb + b.n && pb < pa + a.n;
+            return pa != 0 && pb != 0 && a.n != 0 && b.n != 0 && pa < pb + b.n && pb < pa + a.n;  // (optional arguments may be NULL)
         };
         constexpr int no = sizeof(outs) / sizeof(outs[0]), ni = sizeof(ins) / sizeof(ins[0]);
         for (int i = 0; i < no; ++i) {
@@ -460,7 +464,7 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
     if (T == 0) {  // no token rows: every parameter gradient is zero
         float* outs[5] = {d_s_in, d_s_rank, d_s_out, d_latentA, d_latentB};
         const int64_t ns[5] = {d_in, r, d_out, r * d_in, d_out * r};
-        for (int i = 0; i < 5; ++i) {
+        for (int i = 0; i < (with_latents ? 5 : 3); ++i) {
             hipLaunchKernelGGL(bwd_zero_kernel, dim3(static_cast<unsigned>((ns[i] + 255) / 256)), dim3(256), 0, st, outs[i], ns[i]);
             if (hipGetLastError() != hipSuccess) return LORDBA_ERR_LAUNCH;
         }

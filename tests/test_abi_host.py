@@ -136,7 +136,7 @@ def test_backward_validation_needs_no_device(lib):
                                    q["dlB"], q["ws"], ws_bytes, T, d_in, d_out, r, None)
 
     for n in ("pA", "pAt", "pBt", "si", "sr", "so", "lA", "lB", "dsi", "dsr", "dso", "dlA", "dlB", "ws", "x", "g"):
-        assert call(**{n: None}) == 1, n
+        assert call(**{n: None}) == 1, n           # (a single latent pointer missing is an error; all four: frozen carriers)
     assert call(dx=None) == 1 and call(dxb=None) == 1                           # dx and dx_base come or go together
     assert call(d_in=72) == 2 and call(r=65) == 2 and call(T=-1) == 2
     assert call(ws_bytes=need - 4) == 9

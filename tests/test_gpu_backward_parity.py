@@ -232,6 +232,25 @@ def test_forward_that_keeps_t(torch_cuda, shape):
         assert np.array_equal(a[k], b[k]), k
 
 
+def test_frozen_carriers_scale_gradients_only(torch_cuda):
+    """latentA = latentB = None (only the scales are trained): the scale gradients and dx are bit-identical to the full
+    call's, and no latent gradient is produced."""
+    torch = torch_cuda
+    T, d_in, d_out, r = 150, 768, 1024, 16
+    d = inputs.make_backward_inputs(35, T, d_in, d_out, r)
+    full = gpu_backward(torch, d)
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    pA, _ = binding.lordba_pack_signs(d["signsA"], d["signsB"])
+    pAt, pBt = binding.lordba_pack_transposed(d["signsA"], d["signsB"])
+    w = lambda a: cu(a.view(np.int32))
+    out = binding.lordba_backward(cu(d["x"]), cu(d["g"]), w(pA), w(pAt), w(pBt), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]),
+                                  None, None, 0.0, dx_base=cu(d["dx_base"]))
+    torch.cuda.synchronize()
+    assert out["d_latentA"] is None and out["d_latentB"] is None
+    for k in ("dx", "d_s_in", "d_s_rank", "d_s_out"):
+        assert np.array_equal(out[k].cpu().numpy(), full[k]), k
+
+
 def test_hip_graph_replays_match_eager(torch_cuda):
     """bench.py replays a captured graph of backward calls: several replays, with eager work and synchronisations in
     between, against the eager result (the call records kernel nodes only: no memset, no allocation)."""
