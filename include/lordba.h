@@ -225,6 +225,23 @@ lordba_status lordba_backward(const void* x, const void* g,
                               void* workspace, size_t workspace_bytes,
                               int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream);
 
+/* DEVICE function: lordba_backward for an adapter with `ell` scale envelopes over the same carriers (Def. 1 / Eq. (lordba),
+ * l = ell; the forward of lordba_forward_multi).  s_in fp16 [ell, d_in], s_rank fp16 [ell, r], s_out fp16 [ell, d_out];
+ * d_s_in fp32 [ell, d_in], d_s_rank fp32 [ell, r], d_s_out fp32 [ell, d_out]: every envelope has its own scale
+ * gradients; dx and the latent gradients are the sums over the envelopes (dx with one rounding).  1 <= ell <=
+ * LORDBA_MAX_ENVELOPES.  No kept t here: the rank-r intermediates are recomputed (one pass over x and one over g per
+ * envelope, besides the passes of the weight-gradient kernel).  Workspace: lordba_backward_workspace_bytes, whatever
+ * ell is.  Everything else as lordba_backward. */
+lordba_status lordba_backward_multi(const void* x, const void* g,
+                                    const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
+                                    const void* s_in, const void* s_rank, const void* s_out,
+                                    const float* latentA, const float* latentB, float kappa,
+                                    const void* dx_base, void* dx,
+                                    float* d_s_in, float* d_s_rank, float* d_s_out,
+                                    float* d_latentA, float* d_latentB,
+                                    void* workspace, size_t workspace_bytes,
+                                    int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream);
+
 /* Bytes of workspace lordba_backward needs for a shape (0 for a shape it does not support). */
 size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, int64_t r);
 

@@ -65,6 +65,8 @@ def _load():
         lib.lordba_oracle_smooth_sign_grad.argtypes = [ctypes.c_double, ctypes.c_double]
         lib.lordba_oracle_backward.restype = ci
         lib.lordba_oracle_backward.argtypes = [vp] * 9 + [ctypes.c_double] + [vp] * 7 + [i64] * 4
+        lib.lordba_oracle_backward_multi.restype = ci
+        lib.lordba_oracle_backward_multi.argtypes = [vp] * 9 + [ctypes.c_double] + [vp] * 7 + [i64] * 5
         _lib = lib
     return _lib
 
@@ -289,6 +291,38 @@ def backward(x, g, signsA, signsB, s_in, s_rank, s_out, latA, latB, kappa: float
         _ptr(out["d_s_out"]), _ptr(out["d_latA"]), _ptr(out["d_latB"]), T, d_in, d_out, r)
     if st != 0:
         raise ValueError("oracle backward failed with status %d" % st)
+    return out
+
+
+def backward_multi(x, g, signsA, signsB, s_in, s_rank, s_out, latA, latB, kappa: float, dx_base=None) -> dict:
+    """backward() for an adapter with ell envelopes: s_in[ell,d_in], s_rank[ell,r], s_out[ell,d_out] (float16); the scale
+    gradients come back with the same leading envelope index."""
+    sA = _as(signsA, np.int8)
+    sB = _as(signsB, np.int8)
+    r, d_in = sA.shape
+    d_out = sB.shape[0]
+    si = _f16_bits(s_in)
+    if si.ndim != 2:
+        raise ValueError("s_in must be [ell, d_in]")
+    ell = si.shape[0]
+    si = _f16_bits(si, (ell, d_in))
+    sr = _f16_bits(s_rank, (ell, r))
+    so = _f16_bits(s_out, (ell, d_out))
+    xb = _f16_bits(x)
+    T = xb.shape[0]
+    xb = _f16_bits(xb, (T, d_in))
+    gb = _f16_bits(g, (T, d_out))
+    lA = _as(latA, np.float32, (r, d_in))
+    lB = _as(latB, np.float32, (d_out, r))
+    db = None if dx_base is None else _f16_bits(dx_base, (T, d_in))
+    out = {"dx": np.empty((T, d_in)), "d_s_in": np.empty((ell, d_in)), "d_s_rank": np.empty((ell, r)),
+           "d_s_out": np.empty((ell, d_out)), "d_latA": np.empty((r, d_in)), "d_latB": np.empty((d_out, r))}
+    st = _load().lordba_oracle_backward_multi(
+        _ptr(xb), _ptr(gb), _ptr(sA), _ptr(sB), _ptr(si), _ptr(sr), _ptr(so), _ptr(lA), _ptr(lB), float(kappa),
+        None if db is None else _ptr(db), _ptr(out["dx"]), _ptr(out["d_s_in"]), _ptr(out["d_s_rank"]),
+        _ptr(out["d_s_out"]), _ptr(out["d_latA"]), _ptr(out["d_latB"]), T, d_in, d_out, r, ell)
+    if st != 0:
+        raise ValueError("oracle backward_multi failed with status %d" % st)
     return out
 
 

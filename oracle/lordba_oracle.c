@@ -38,7 +38,9 @@
  * derivative is the smooth-sign factor, by exact unit-step differences of the
  * loss on a dense numpy DeltaW, by the contraction of X^T G in exact rationals,
  * by the adjoint identity with the pinned forward, by Euler's relation for the
- * three scale vectors, and by closed forms of the smooth-sign factor.  The
+ * three scale vectors, and by closed forms of the smooth-sign factor; with
+ * several envelopes, by the sum of the pinned one-envelope results over the
+ * envelopes (DeltaW is their sum) and again by autograd.  The
  * rank-r intermediate t is pinned by a numpy fp64 GEMM and by the forward
  * oracle with an identity-like second carrier.
  * No function here is "parity unpinned".
@@ -516,5 +518,97 @@ int lordba_oracle_backward(const uint16_t *x, const uint16_t *g, const int8_t *s
     for (int64_t n = 0; n < d_out * r; ++n) d_latB[n] *= lordba_oracle_smooth_sign_grad((double)latB[n], kappa);
 done:
     free(alpha); free(beta); free(gamma); free(w); free(dw); free(v); free(dv); free(t); free(u); free(du); free(dt);
+    return status;
+}
+
+/* ------------------------------------- backward with several envelopes ---- */
+
+/* As lordba_oracle_backward for an adapter with ell scale envelopes over the same carriers (Def. 1 / Eq. (lordba),
+ * l >= 1): Y = Y_base + sum_e X diag(alpha_e) B1 diag(beta_e) B2 diag(gamma_e).  Each envelope is staged forward and
+ * reversed exactly as in the one-envelope function, one token row after the other; the input gradient and the carrier
+ * gradients add up over the envelopes (in envelope order), every envelope has its own scale gradients.
+ * s_in[ell,d_in], s_rank[ell,r], s_out[ell,d_out]: fp16 bit patterns; d_s_in[ell,d_in], d_s_rank[ell,r],
+ * d_s_out[ell,d_out]: fp64 out; everything else as lordba_oracle_backward. */
+int lordba_oracle_backward_multi(const uint16_t *x, const uint16_t *g, const int8_t *signsA, const int8_t *signsB,
+                                 const uint16_t *s_in, const uint16_t *s_rank, const uint16_t *s_out,
+                                 const float *latA, const float *latB, double kappa,
+                                 const uint16_t *dx_base, double *dx,
+                                 double *d_s_in, double *d_s_rank, double *d_s_out, double *d_latA, double *d_latB,
+                                 int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell)
+{
+    if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || ell < 1) return 2;
+    for (int64_t n = 0; n < r * d_in; ++n) if (signsA[n] != 1 && signsA[n] != -1) return 3;
+    for (int64_t n = 0; n < d_out * r; ++n) if (signsB[n] != 1 && signsB[n] != -1) return 3;
+
+    double *alpha = (double *)malloc(sizeof(double) * (size_t)(ell * d_in));
+    double *beta = (double *)malloc(sizeof(double) * (size_t)(ell * r));
+    double *gamma = (double *)malloc(sizeof(double) * (size_t)(ell * d_out));
+    double *w = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *v = (double *)malloc(sizeof(double) * (size_t)d_out);
+    double *dv = (double *)malloc(sizeof(double) * (size_t)d_out);
+    double *t = (double *)malloc(sizeof(double) * (size_t)r);
+    double *u = (double *)malloc(sizeof(double) * (size_t)r);
+    double *dt = (double *)malloc(sizeof(double) * (size_t)r);
+    int status = 0;
+    if (!alpha || !beta || !gamma || !w || !v || !dv || !t || !u || !dt) { status = 9; goto done; }
+    lordba_oracle_f16_array_to_f64(s_in, alpha, ell * d_in);
+    lordba_oracle_f16_array_to_f64(s_rank, beta, ell * r);
+    lordba_oracle_f16_array_to_f64(s_out, gamma, ell * d_out);
+
+    for (int64_t n = 0; n < ell * d_in; ++n) d_s_in[n] = 0.0;
+    for (int64_t n = 0; n < ell * r; ++n) d_s_rank[n] = 0.0;
+    for (int64_t n = 0; n < ell * d_out; ++n) d_s_out[n] = 0.0;
+    for (int64_t n = 0; n < r * d_in; ++n) d_latA[n] = 0.0;      /* dB1 (as [r, d_in]) until the end */
+    for (int64_t n = 0; n < d_out * r; ++n) d_latB[n] = 0.0;     /* dB2 (as [d_out, r]) until the end */
+
+    for (int64_t row = 0; row < T; ++row) {
+        const uint16_t *xr = x + row * d_in, *gr = g + row * d_out;
+        for (int64_t i = 0; i < d_in; ++i)
+            dx[row * d_in + i] = dx_base ? lordba_oracle_f16_to_f64(dx_base[row * d_in + i]) : 0.0;
+        for (int64_t e = 0; e < ell; ++e) {
+            const double *al = alpha + e * d_in, *be = beta + e * r, *ga = gamma + e * d_out;
+            /* forward intermediates of this row and envelope */
+            for (int64_t i = 0; i < d_in; ++i) w[i] = lordba_oracle_f16_to_f64(xr[i]) * al[i];
+            for (int64_t k = 0; k < r; ++k) {
+                double s = 0.0;
+                for (int64_t i = 0; i < d_in; ++i) s += w[i] * (double)signsA[k * d_in + i];
+                t[k] = s;
+                u[k] = s * be[k];
+            }
+            for (int64_t j = 0; j < d_out; ++j) {
+                double s = 0.0;
+                for (int64_t k = 0; k < r; ++k) s += u[k] * (double)signsB[j * r + k];
+                v[j] = s;
+            }
+            /* reverse */
+            for (int64_t j = 0; j < d_out; ++j) {
+                double gj = lordba_oracle_f16_to_f64(gr[j]);
+                d_s_out[e * d_out + j] += gj * v[j];
+                dv[j] = gj * ga[j];
+            }
+            for (int64_t k = 0; k < r; ++k) {
+                double s = 0.0;
+                for (int64_t j = 0; j < d_out; ++j) {
+                    d_latB[j * r + k] += u[k] * dv[j];
+                    s += dv[j] * (double)signsB[j * r + k];
+                }
+                d_s_rank[e * r + k] += s * t[k];
+                dt[k] = s * be[k];
+            }
+            for (int64_t i = 0; i < d_in; ++i) {
+                double s = 0.0;
+                for (int64_t k = 0; k < r; ++k) {
+                    d_latA[k * d_in + i] += w[i] * dt[k];
+                    s += dt[k] * (double)signsA[k * d_in + i];
+                }
+                d_s_in[e * d_in + i] += s * lordba_oracle_f16_to_f64(xr[i]);
+                dx[row * d_in + i] += s * al[i];
+            }
+        }
+    }
+    for (int64_t n = 0; n < r * d_in; ++n) d_latA[n] *= lordba_oracle_smooth_sign_grad((double)latA[n], kappa);
+    for (int64_t n = 0; n < d_out * r; ++n) d_latB[n] *= lordba_oracle_smooth_sign_grad((double)latB[n], kappa);
+done:
+    free(alpha); free(beta); free(gamma); free(w); free(v); free(dv); free(t); free(u); free(dt);
     return status;
 }

@@ -136,6 +136,8 @@ def load_library():
     lib.lordba_backward_workspace_bytes.argtypes = [i64] * 4
     lib.lordba_backward.restype = ci
     lib.lordba_backward.argtypes = [vp] * 10 + [ctypes.c_float, vp, i64] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 4 + [vp]
+    lib.lordba_backward_multi.restype = ci
+    lib.lordba_backward_multi.argtypes = [vp] * 10 + [ctypes.c_float] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 5 + [vp]
     lib.lordba_pack_latents.restype = ci
     lib.lordba_pack_latents.argtypes = [vp] * 6 + [i64] * 3 + [vp]
     lib.lordba_forward_save_t.restype = ci
@@ -465,6 +467,41 @@ def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, late
                              workspace.data_ptr(), workspace.numel(), T, d_in, d_out, r, ctypes.c_void_p(stream))
     if st != 0:
         raise LordbaError(st, "lordba_backward")
+    return out
+
+
+def lordba_backward_multi(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa: float,
+                          dx_base=None, dx=None, workspace=None, stream=None) -> dict:
+    """lordba_backward for ell envelopes: s_in [ell, d_in], s_rank [ell, r], s_out [ell, d_out] (float16 CUDA tensors); the
+    scale gradients come back with the same leading envelope index."""
+    import torch
+
+    lib = load_library()
+    T, d_in = x.shape
+    d_out = g.shape[1]
+    ell, r = s_rank.shape
+    if tuple(s_in.shape) != (ell, d_in) or tuple(s_out.shape) != (ell, d_out):
+        raise ValueError("scale arrays must be [ell, d_in], [ell, r], [ell, d_out]")
+    need = lordba_backward_workspace_bytes(T, d_in, d_out, r)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    if dx_base is not None and dx is None:
+        dx = torch.empty_like(dx_base)
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=x.device)
+    out = {"dx": dx, "d_s_in": f32(ell, d_in), "d_s_rank": f32(ell, r), "d_s_out": f32(ell, d_out),
+           "d_latentA": None if latentA is None else f32(r, d_in), "d_latentB": None if latentB is None else f32(d_out, r)}
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    ptr = lambda t_: None if t_ is None else t_.data_ptr()
+    st = lib.lordba_backward_multi(x.data_ptr(), g.data_ptr(), packedA.data_ptr(), packedAt.data_ptr(), packedBt.data_ptr(),
+                                   s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(), ptr(latentA), ptr(latentB), float(kappa),
+                                   ptr(dx_base), ptr(dx), out["d_s_in"].data_ptr(), out["d_s_rank"].data_ptr(),
+                                   out["d_s_out"].data_ptr(), ptr(out["d_latentA"]), ptr(out["d_latentB"]),
+                                   workspace.data_ptr(), workspace.numel(), T, d_in, d_out, r, ell, ctypes.c_void_p(stream))
+    if st != 0:
+        raise LordbaError(st, "lordba_backward_multi")
     return out
 
 

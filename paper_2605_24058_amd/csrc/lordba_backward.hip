@@ -96,6 +96,7 @@ struct BwdArgs {
     float* part;           // [splits, rp, dcols]
     int T, d_in, d_out, r;
     int rp, t_pad, t_stride, du_stride, nbx, nbg, dcols, tw, splits;
+    int accumulate;        // latent gradients are added to what the arrays hold (second and later envelopes)
 };
 
 __global__ void bwd_zero_kernel(float* p, int64_t n) {
@@ -363,7 +364,8 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
         if (a.d_latA != nullptr) {  // (null: the carriers are frozen, only the scale gradients are wanted)
             if (is_x) {
                 const size_t n = static_cast<size_t>(k) * d + col;
-                a.d_latA[n] = scale * s * smooth_sign_factor(a.latA[n], a.kappa);
+                const float val = scale * s * smooth_sign_factor(a.latA[n], a.kappa);
+                a.d_latA[n] = a.accumulate ? a.d_latA[n] + val : val;
             } else {
                 lat[c * r + k] = scale * s * smooth_sign_factor(lat[c * r + k], a.kappa);
             }
@@ -372,7 +374,10 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
     sh[tid] = dscale;
     __syncthreads();
     if (!is_x && a.d_latB != nullptr)
-        for (int e = tid; e < 32 * r; e += 256) a.d_latB[static_cast<size_t>(grp) * 32 * r + e] = lat[e];
+        for (int e = tid; e < 32 * r; e += 256) {
+            float* dst = a.d_latB + static_cast<size_t>(grp) * 32 * r + e;
+            *dst = a.accumulate ? *dst + lat[e] : lat[e];
+        }
     if (kq == 0) {
         float tot = 0.f;
 #pragma unroll
@@ -406,17 +411,22 @@ extern "C" size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64
     return make_plan(T, d_in, d_out, r).words * 4;
 }
 
-extern "C" lordba_status lordba_backward(const void* x, const void* g,
-                                         const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
-                                         const void* s_in, const void* s_rank, const void* s_out,
-                                         const float* latentA, const float* latentB, float kappa,
-                                         const float* t_saved, int64_t t_stride,
-                                         const void* dx_base, void* dx,
-                                         float* d_s_in, float* d_s_rank, float* d_s_out,
-                                         float* d_latentA, float* d_latentB,
-                                         void* workspace, size_t workspace_bytes,
-                                         int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream) {
-    if (!supported(T, d_in, d_out, r)) return LORDBA_ERR_DIM;
+namespace {
+
+// Shared by the entry points.  ell envelopes: s_in, s_rank, s_out and their gradients have ell rows; everything is additive
+// over the envelopes (DeltaW is their sum and g is fixed), so envelope e is one pass of the one-envelope machinery with its
+// own scales: its own scale gradients, and latent gradients added to those of the envelopes before it.
+lordba_status backward_impl(const void* x, const void* g,
+                            const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
+                            const void* s_in, const void* s_rank, const void* s_out,
+                            const float* latentA, const float* latentB, float kappa,
+                            const float* t_saved, int64_t t_stride,
+                            const void* dx_base, void* dx,
+                            float* d_s_in, float* d_s_rank, float* d_s_out,
+                            float* d_latentA, float* d_latentB,
+                            void* workspace, size_t workspace_bytes,
+                            int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream) {
+    if (!supported(T, d_in, d_out, r) || ell < 1 || ell > LORDBA_MAX_ENVELOPES) return LORDBA_ERR_DIM;
     if (!packedA || !packedAt || !packedBt || !s_in || !s_rank || !s_out || !d_s_in || !d_s_rank || !d_s_out || !workspace)
         return LORDBA_ERR_NULL;
     // frozen carriers (only the scales are trained): no latents, no latent gradients
@@ -440,12 +450,13 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
         struct Span { const void* p; size_t n; };
         const size_t nx = static_cast<size_t>(T) * d_in * 2, ng = static_cast<size_t>(T) * d_out * 2;
         const size_t nA = static_cast<size_t>(r) * d_in, nB = static_cast<size_t>(d_out) * r;
-        const Span outs[] = {{d_s_in, static_cast<size_t>(d_in) * 4}, {d_s_rank, static_cast<size_t>(r) * 4},
-                             {d_s_out, static_cast<size_t>(d_out) * 4}, {d_latentA, nA * 4}, {d_latentB, nB * 4},
+        const size_t L = static_cast<size_t>(ell);
+        const Span outs[] = {{d_s_in, L * d_in * 4}, {d_s_rank, L * r * 4},
+                             {d_s_out, L * d_out * 4}, {d_latentA, nA * 4}, {d_latentB, nB * 4},
                              {workspace, p.words * 4}, {dx, dx ? nx : 0}};
         const Span ins[] = {{x, nx}, {g, ng}, {packedA, lordba_packed_words(r, d_in) * 4}, {packedAt, lordba_packed_words(d_in, r) * 4},
-                            {packedBt, lordba_packed_words(r, d_out) * 4}, {s_in, static_cast<size_t>(d_in) * 2},
-                            {s_rank, static_cast<size_t>(r) * 2}, {s_out, static_cast<size_t>(d_out) * 2}, {latentA, nA * 4},
+                            {packedBt, lordba_packed_words(r, d_out) * 4}, {s_in, L * d_in * 2},
+                            {s_rank, L * r * 2}, {s_out, L * d_out * 2}, {latentA, nA * 4},
                             {latentB, nB * 4}, {t_saved, t_saved ? (static_cast<size_t>(r - 1) * t_stride + T) * 4 : 0}};
         auto hit = [](const Span& a, const Span& b) {
             const uintptr_t pa = reinterpret_cast<uintptr_t>(a.p), pb = reinterpret_cast<uintptr_t>(b.p);
@@ -463,7 +474,7 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
 
     if (T == 0) {  // no token rows: every parameter gradient is zero
         float* outs[5] = {d_s_in, d_s_rank, d_s_out, d_latentA, d_latentB};
-        const int64_t ns[5] = {d_in, r, d_out, r * d_in, d_out * r};
+        const int64_t ns[5] = {ell * d_in, ell * r, ell * d_out, r * d_in, d_out * r};
         for (int i = 0; i < (with_latents ? 5 : 3); ++i) {
             hipLaunchKernelGGL(bwd_zero_kernel, dim3(static_cast<unsigned>((ns[i] + 255) / 256)), dim3(256), 0, st, outs[i], ns[i]);
             if (hipGetLastError() != hipSuccess) return LORDBA_ERR_LAUNCH;
@@ -473,60 +484,106 @@ extern "C" lordba_status lordba_backward(const void* x, const void* g,
 
     float* ws = static_cast<float*>(workspace);
     float* duT = ws + p.off_du;
-    // du, and dx = dx_base + g DeltaW^T if wanted: the forward branch of the transposed adapter (it validates its own
-    // arguments); du is that call's rank-r intermediate
-    lordba_status s = lordba_forward_save_t(g, packedBt, packedAt, s_out, s_rank, s_in, dx_base, dx, duT, p.t_pad, T, d_out, d_in, r, stream);
-    if (s != LORDBA_OK) return s;
-    const float* tT = t_saved;
-    int64_t tT_stride = t_stride;
-    if (tT == nullptr) {
-        // t: the forward branch of the adapter itself, stopped after its rank-r intermediate (its second carrier is not
-        // read; packedAt stands in as a valid [d_in, r] carrier)
-        float* t_own = ws + p.off_t;
-        s = lordba_forward_save_t(x, packedA, packedAt, s_in, s_rank, s_in, nullptr, nullptr, t_own, p.t_pad, T, d_in, d_in, r, stream);
+    float* t_own = ws + p.off_t;
+    const _Float16* si = static_cast<const _Float16*>(s_in);
+    const _Float16* sr = static_cast<const _Float16*>(s_rank);
+    const _Float16* so = static_cast<const _Float16*>(s_out);
+    lordba_status s;
+    if (ell > 1 && dx != nullptr) {
+        // dx = dx_base + g DeltaW^T with all envelopes at once: the multi-envelope forward branch of the transposed adapter
+        // (one pass over g, dx_base and dx, one rounding)
+        s = lordba_forward_multi(g, packedBt, packedAt, s_out, s_rank, s_in, dx_base, dx, T, d_out, d_in, r, ell, stream);
         if (s != LORDBA_OK) return s;
-        tT = t_own;
-        tT_stride = p.t_pad;
     }
+    for (int64_t e = 0; e < ell; ++e) {
+        // du (and, with one envelope, dx = dx_base + g DeltaW^T): the forward branch of the transposed adapter (it validates
+        // its own arguments); du is that call's rank-r intermediate
+        const bool with_dx = ell == 1 && dx != nullptr;
+        s = lordba_forward_save_t(g, packedBt, packedAt, so + e * d_out, sr + e * r, si + e * d_in, with_dx ? dx_base : nullptr,
+                                  with_dx ? dx : nullptr, duT, p.t_pad, T, d_out, d_in, r, stream);
+        if (s != LORDBA_OK) return s;
+        const float* tT = t_saved;
+        int64_t tT_stride = t_stride;
+        if (tT == nullptr) {
+            // t: the forward branch of the adapter itself, stopped after its rank-r intermediate (its second carrier is
+            // not read; packedAt stands in as a valid [d_in, r] carrier)
+            s = lordba_forward_save_t(x, packedA, packedAt, si + e * d_in, sr + e * r, si + e * d_in, nullptr, nullptr, t_own, p.t_pad,
+                                      T, d_in, d_in, r, stream);
+            if (s != LORDBA_OK) return s;
+            tT = t_own;
+            tT_stride = p.t_pad;
+        }
 
-    BwdArgs a;
-    a.x = static_cast<const _Float16*>(x);
-    a.g = static_cast<const _Float16*>(g);
-    a.pA = packedA;
-    a.pBt = packedBt;
-    a.s_in = static_cast<const _Float16*>(s_in);
-    a.s_rank = static_cast<const _Float16*>(s_rank);
-    a.s_out = static_cast<const _Float16*>(s_out);
-    a.latA = latentA;
-    a.latB = latentB;
-    a.kappa = kappa;
-    a.d_s_in = d_s_in;
-    a.d_s_rank = d_s_rank;
-    a.d_s_out = d_s_out;
-    a.d_latA = d_latentA;
-    a.d_latB = d_latentB;
-    a.tT = tT;
-    a.duT = duT;
-    a.dbeta_part = ws + p.off_dbeta;
-    a.part = ws + p.off_part;
-    a.T = static_cast<int>(T);
-    a.d_in = static_cast<int>(d_in);
-    a.d_out = static_cast<int>(d_out);
-    a.r = static_cast<int>(r);
-    a.rp = p.rp;
-    a.t_pad = p.t_pad;
-    a.t_stride = static_cast<int>(tT_stride);
-    a.du_stride = p.t_pad;
-    a.nbx = p.nbx;
-    a.nbg = p.nbg;
-    a.dcols = p.dcols;
-    a.tw = p.tw;
-    a.splits = p.splits;
-
-    switch (p.rp / 16) {
-        case 1: return launch_all<1>(a, st);
-        case 2: return launch_all<2>(a, st);
-        case 3: return launch_all<3>(a, st);
-        default: return launch_all<4>(a, st);
+        BwdArgs a;
+        a.x = static_cast<const _Float16*>(x);
+        a.g = static_cast<const _Float16*>(g);
+        a.pA = packedA;
+        a.pBt = packedBt;
+        a.s_in = si + e * d_in;
+        a.s_rank = sr + e * r;
+        a.s_out = so + e * d_out;
+        a.latA = latentA;
+        a.latB = latentB;
+        a.kappa = kappa;
+        a.d_s_in = d_s_in + e * d_in;
+        a.d_s_rank = d_s_rank + e * r;
+        a.d_s_out = d_s_out + e * d_out;
+        a.d_latA = d_latentA;
+        a.d_latB = d_latentB;
+        a.tT = tT;
+        a.duT = duT;
+        a.dbeta_part = ws + p.off_dbeta;
+        a.part = ws + p.off_part;
+        a.T = static_cast<int>(T);
+        a.d_in = static_cast<int>(d_in);
+        a.d_out = static_cast<int>(d_out);
+        a.r = static_cast<int>(r);
+        a.rp = p.rp;
+        a.t_pad = p.t_pad;
+        a.t_stride = static_cast<int>(tT_stride);
+        a.du_stride = p.t_pad;
+        a.nbx = p.nbx;
+        a.nbg = p.nbg;
+        a.dcols = p.dcols;
+        a.tw = p.tw;
+        a.splits = p.splits;
+        a.accumulate = e > 0 ? 1 : 0;
+        switch (p.rp / 16) {
+            case 1: s = launch_all<1>(a, st); break;
+            case 2: s = launch_all<2>(a, st); break;
+            case 3: s = launch_all<3>(a, st); break;
+            default: s = launch_all<4>(a, st); break;
+        }
+        if (s != LORDBA_OK) return s;
     }
+    return LORDBA_OK;
+}
+
+}  // namespace
+
+extern "C" lordba_status lordba_backward(const void* x, const void* g,
+                                         const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
+                                         const void* s_in, const void* s_rank, const void* s_out,
+                                         const float* latentA, const float* latentB, float kappa,
+                                         const float* t_saved, int64_t t_stride,
+                                         const void* dx_base, void* dx,
+                                         float* d_s_in, float* d_s_rank, float* d_s_out,
+                                         float* d_latentA, float* d_latentB,
+                                         void* workspace, size_t workspace_bytes,
+                                         int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream) {
+    return backward_impl(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa, t_saved, t_stride, dx_base, dx,
+                         d_s_in, d_s_rank, d_s_out, d_latentA, d_latentB, workspace, workspace_bytes, T, d_in, d_out, r, 1, stream);
+}
+
+extern "C" lordba_status lordba_backward_multi(const void* x, const void* g,
+                                               const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
+                                               const void* s_in, const void* s_rank, const void* s_out,
+                                               const float* latentA, const float* latentB, float kappa,
+                                               const void* dx_base, void* dx,
+                                               float* d_s_in, float* d_s_rank, float* d_s_out,
+                                               float* d_latentA, float* d_latentB,
+                                               void* workspace, size_t workspace_bytes,
+                                               int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream) {
+    return backward_impl(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa, nullptr, 0, dx_base, dx,
+                         d_s_in, d_s_rank, d_s_out, d_latentA, d_latentB, workspace, workspace_bytes, T, d_in, d_out, r, ell, stream);
 }

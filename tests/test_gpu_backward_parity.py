@@ -251,6 +251,38 @@ def test_frozen_carriers_scale_gradients_only(torch_cuda):
         assert np.array_equal(out[k].cpu().numpy(), full[k]), k
 
 
+@pytest.mark.parametrize("case", [(2, 203, 1056, 2080, 16), (3, 70, 1024, 768, 32), (4, 45, 512, 640, 8), (2, 4100, 256, 384, 16),
+                                  (1, 37, 512, 512, 16)], ids=lambda c: "ell%d_T%d_%dx%d_r%d" % c)
+def test_several_envelopes(torch_cuda, case):
+    """lordba_backward_multi against the oracle: per-envelope scale gradients (whole vector each), dx per token row (as
+    configured and the branch alone), latent gradients per rank."""
+    torch = torch_cuda
+    ell, T, d_in, d_out, r = case
+    d = inputs.make_backward_inputs(36, T, d_in, d_out, r)
+    d.update(inputs.make_envelopes(36, d_in, d_out, r, ell))
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    pA, _ = binding.lordba_pack_signs(d["signsA"], d["signsB"])
+    pAt, pBt = binding.lordba_pack_transposed(d["signsA"], d["signsB"])
+    w = lambda a: cu(a.view(np.int32))
+    for tag, dxb in (("full", d["dx_base"]), ("branch", np.zeros_like(d["dx_base"]))):
+        ws = new_workspace(torch, binding.lordba_backward_workspace_bytes(T, d_in, d_out, r))
+        out = binding.lordba_backward_multi(cu(d["x"]), cu(d["g"]), w(pA), w(pAt), w(pBt), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]),
+                                            cu(d["latA"]), cu(d["latB"]), KAPPA, dx_base=cu(dxb), workspace=ws[:ws.numel() - GUARD])
+        torch.cuda.synchronize()
+        assert (ws[ws.numel() - GUARD:].cpu().numpy() == 0xFF).all(), "write past the workspace"
+        got = {k: v.cpu().numpy() for k, v in out.items()}
+        want = oracle.backward_multi(d["x"], d["g"], d["signsA"], d["signsB"], d["s_in"], d["s_rank"], d["s_out"], d["latA"], d["latB"],
+                                     KAPPA, dxb)
+        e = oracle.row_rel_l2(got["dx"].astype(np.float64), want["dx"])
+        assert e.max() <= TOL, "%s dx: %.3e" % (tag, e.max())
+        for k in ("d_s_in", "d_s_rank", "d_s_out"):
+            for en in range(ell):
+                err = oracle.rel_l2(got[k][en], want[k][en])
+                assert err <= TOL, "%s envelope %d: %.3e" % (k, en, err)
+        assert oracle.row_rel_l2(got["d_latentA"].astype(np.float64), want["d_latA"]).max() <= TOL
+        assert oracle.row_rel_l2(got["d_latentB"].astype(np.float64).T, want["d_latB"].T).max() <= TOL
+
+
 def test_hip_graph_replays_match_eager(torch_cuda):
     """bench.py replays a captured graph of backward calls: several replays, with eager work and synchronisations in
     between, against the eager result (the call records kernel nodes only: no memset, no allocation)."""

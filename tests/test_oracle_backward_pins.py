@@ -290,3 +290,54 @@ def test_rank_intermediate():
     y = oracle.forward(d["x"], d["signsA"], sB, d["s_in"], ones, ones, np.zeros((6, r), dtype=np.float16))
     tot = y.sum(axis=1, keepdims=True) / (r - 2)
     assert _rel((tot - y) / 2, got) < 1e-12
+
+
+def _multi_inputs(seed, T, d_in, d_out, r, ell):
+    d = _inputs(seed, T, d_in, d_out, r)
+    env = inputs.make_envelopes(seed, d_in, d_out, r, ell)
+    g = np.random.default_rng(seed + 1)
+    d["s_in"] = (env["s_in"].astype(np.float32) * 8).astype(np.float16)
+    d["s_out"] = (env["s_out"].astype(np.float32) * 8).astype(np.float16)
+    d["s_rank"] = (env["s_rank"].astype(np.float32) * g.choice([-4.0, -1.0, 2.0, 8.0], size=(ell, r))).astype(np.float16)
+    return d
+
+
+def _run_multi(d, kappa=KAPPA, with_base=True):
+    return oracle.backward_multi(d["x"], d["g"], d["signsA"], d["signsB"], d["s_in"], d["s_rank"], d["s_out"], d["latA"], d["latB"],
+                                 kappa, d["dx_base"] if with_base else None)
+
+
+@pytest.mark.parametrize("ell", [1, 2, 3])
+def test_multi_envelope_backward_is_the_sum_over_envelopes(ell):
+    """DeltaW is a sum over envelopes and the loss is linear in it, so with the pinned one-envelope function F_e run on
+    envelope e alone: the scale gradients of envelope e are F_e's, the carrier gradients and the branch's share of dx are
+    the sums over e."""
+    d = _multi_inputs(14, 6, 96, 64, 8, ell)
+    got = _run_multi(d)
+    base = d["dx_base"].astype(np.float64)
+    dx, dA, dB = base.copy(), 0.0, 0.0
+    for e in range(ell):
+        one = dict(d, s_in=d["s_in"][e], s_rank=d["s_rank"][e], s_out=d["s_out"][e])
+        f = _run(one)
+        for k in ("d_s_in", "d_s_rank", "d_s_out"):
+            assert _rel(got[k][e], f[k]) < 1e-13, (k, e)
+        dx += f["dx"] - base
+        dA, dB = dA + f["d_latA"], dB + f["d_latB"]
+    assert _rel(got["dx"], dx) < 1e-12 and _rel(got["d_latA"], dA) < 1e-12 and _rel(got["d_latB"], dB) < 1e-12
+
+
+def test_multi_envelope_backward_against_autograd():
+    d = _multi_inputs(15, 5, 64, 96, 4, 3)
+    f = _f64(d)
+    kap = 6.0
+    leaf = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    x, al, be, ga, uA, uB = leaf(f["x"]), leaf(f["s_in"]), leaf(f["s_rank"]), leaf(f["s_out"]), leaf(f["latA"]), leaf(f["latB"])
+    sA = _SmoothSign.apply(uA, torch.tensor(f["signsA"]), kap)
+    sB = _SmoothSign.apply(uB, torch.tensor(f["signsB"]), kap)
+    y = sum(((((x * al[e]) @ sA.T) * be[e]) @ sB.T) * ga[e] for e in range(3))     # Eq. (lordba) with l = 3
+    (y * torch.tensor(f["g"])).sum().backward()
+    got = _run_multi(d, kap)
+    want = {"dx": x.grad.numpy() + f["dx_base"], "d_s_in": al.grad.numpy(), "d_s_rank": be.grad.numpy(),
+            "d_s_out": ga.grad.numpy(), "d_latA": uA.grad.numpy(), "d_latB": uB.grad.numpy()}
+    for k in want:
+        assert _rel(got[k], want[k]) < 1e-12, k
