@@ -203,6 +203,28 @@ def test_deterministic_and_workspace_reuse(torch_cuda):
     compare(s2, oracle_backward(small), "small_after_big")
 
 
+@pytest.mark.parametrize("shape", [(9, 100, 36, 5), (3, 513, 77, 16), (3, 512, 384, 16), (20, 4096, 4096, 64)],
+                         ids=lambda s: "T%d_%dx%d_r%d" % s)
+def test_forward_that_keeps_t_other_kernels(torch_cuda, shape):
+    """The same export through the general kernel (unaligned widths) and through the small-T grid modes (a single partial
+    tile; a few tiles whose output blocks are split over workgroups, each of which writes the same t)."""
+    torch = torch_cuda
+    T, d_in, d_out, r = shape
+    d = inputs.make_inputs(37, T, d_in, d_out, r)
+    dev = binding.to_device(d)
+    y_ref = binding.lordba_forward(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"], dev["y_base"])
+    t_buf = torch.full((r, binding.saved_t_stride(T)), float("nan"), dtype=torch.float32, device="cuda:0")
+    y, t = binding.lordba_forward_save_t(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
+                                         dev["y_base"], t_out=t_buf)
+    _, t_only = binding.lordba_forward_save_t(dev["x"], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"])
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_ref)
+    th = t.cpu().numpy()
+    assert np.isnan(th[:, T:]).all() and np.array_equal(th[:, :T], t_only.cpu().numpy()[:, :T])
+    e = oracle.row_rel_l2(th[:, :T].T.astype(np.float64), oracle.rank_intermediate(d["x"], d["signsA"], d["s_in"]))
+    assert e.max() <= 1e-5, "t: max row rel-L2 %.3e" % e.max()
+
+
 @pytest.mark.parametrize("shape", [(37, 1024, 1152, 16), (203, 1056, 2080, 16), (130, 32, 96, 5), (4133, 512, 256, 32), (33, 512, 1024, 64)],
                          ids=lambda s: "T%d_%dx%d_r%d" % s)
 def test_forward_that_keeps_t(torch_cuda, shape):
