@@ -351,7 +351,7 @@ def main():
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (token rows shard with no exchange; see DESIGN.md). "
+        print("bench.py: this build runs on one GPU only (token rows shard over GPUs with no exchange). "
               "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 

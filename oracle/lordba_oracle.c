@@ -6,7 +6,7 @@
  * it shares no code, header, table or helper with the HIP library, and it has
  * its own fp16 decoder and its own bit packer.
  *
- * What it computes (paper notation; BASELINE name in brackets):
+ * What it computes (paper notation; the C ABI's name in brackets):
  *   host projection N x M  [d_in x d_out], carrier rank R [r], T token rows,
  *   B1 in {+-1}^{N x R}  [sign(A) = B1^T, stored as S_A[r, d_in]],
  *   B2 in {+-1}^{R x M}  [sign(B) = B2^T, stored as S_B[d_out, r]],
