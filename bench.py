@@ -271,10 +271,21 @@ def bench_backward(args):
                                            dev["latB"], args.kappa, dx_base=dxbs[s_], dx=dxs[s_], workspace=ws, check=False,
                                            t_saved=t_bufs[s_])
 
+    ell = args.ell
+    if ell > 1:   # several envelopes over the same carriers: lordba_backward_multi (t is always recomputed there)
+        assert not args.train_step and not args.keep_t, "--ell > 1 goes with the plain --backward mode"
+        env = inputs.make_envelopes(args.seed, sh.d_in, sh.d_out, sh.r, ell)
+        dev.update({k: cu(env[k]) for k in ("s_in", "s_rank", "s_out")})
+
     def step(i):
         if args.train_step:
             return train_step(i)
         s_ = i % sets
+        if ell > 1:
+            outs[s_] = binding.lordba_backward_multi(xs[s_], gs[s_], dev["pA"], dev["pAt"], dev["pBt"], dev["s_in"], dev["s_rank"],
+                                                     dev["s_out"], dev["latA"], dev["latB"], args.kappa, dx_base=dxbs[s_], dx=dxs[s_],
+                                                     workspace=ws)
+            return
         outs[s_] = binding.lordba_backward(xs[s_], gs[s_], dev["pA"], dev["pAt"], dev["pBt"], dev["s_in"], dev["s_rank"],
                                            dev["s_out"], dev["latA"], dev["latB"], args.kappa, dx_base=dxbs[s_], dx=dxs[s_],
                                            workspace=ws, check=False, t_saved=kept[s_])
@@ -282,6 +293,7 @@ def bench_backward(args):
     reps_us, wall_s = timed(step, K, max(W, sets), use_graph, reps=3)
     call_us = reps_us[0]
     alg = backward_algorithmic_bytes(sh)
+    alg += (ell - 1) * (2 + 4) * (sh.d_in + sh.r + sh.d_out)     # further envelopes: fp16 scales read, fp32 scale gradients written
     if args.train_step:   # + the forward call + reading the latents and writing the four packed carriers
         alg += sh.algorithmic_bytes() + 4 * sh.T * sh.r + 4 * sh.r * (sh.d_in + sh.d_out) + 4 * ((sh.r * (sh.d_in + sh.d_out) + 7) // 8)
     achieved = alg / (call_us * 1e-6) / 1e9
@@ -291,17 +303,21 @@ def bench_backward(args):
            "ms_per_step": wall_s * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "io_dtype": "f16", "data": "synthetic",
            "config": {"workload": sh.name, "pass": "train_step" if args.train_step else "backward", "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
-                      "kappa": args.kappa, "t": "kept by the forward pass" if args.keep_t else "recomputed from x", "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
+                      "ell": ell, "kappa": args.kappa, "t": "kept by the forward pass" if args.keep_t else "recomputed from x", "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                        "traffic": None if args.train_step else (MEASURED_BACKWARD_TRAFFIC_BYTES.get(sh.name) or (None, None))[1 if args.keep_t else 0],
+                        "traffic": None if (args.train_step or ell > 1) else (MEASURED_BACKWARD_TRAFFIC_BYTES.get(sh.name) or (None, None))[1 if args.keep_t else 0],
                         "kernel_us": call_us, "kernel_us_repetitions": reps_us, "algorithmic_bytes": alg,
                         "note": "all kernels of one call taken together (dx + du, t unless kept, wgrad, finish)"}}
     if not args.no_cpu_baseline:
         import oracle
         rows = min(sh.T, 256)
         c0 = time.perf_counter()
-        want = oracle.backward(host0["x"][:rows], host0["g"][:rows], host0["signsA"], host0["signsB"], host0["s_in"],
-                               host0["s_rank"], host0["s_out"], host0["latA"], host0["latB"], args.kappa, host0["dx_base"][:rows])
+        if ell > 1:
+            want = oracle.backward_multi(host0["x"][:rows], host0["g"][:rows], host0["signsA"], host0["signsB"], env["s_in"],
+                                         env["s_rank"], env["s_out"], host0["latA"], host0["latB"], args.kappa, host0["dx_base"][:rows])
+        else:
+            want = oracle.backward(host0["x"][:rows], host0["g"][:rows], host0["signsA"], host0["signsB"], host0["s_in"],
+                                   host0["s_rank"], host0["s_out"], host0["latA"], host0["latB"], args.kappa, host0["dx_base"][:rows])
         c1 = time.perf_counter()
         step(0)
         torch.cuda.synchronize()
