@@ -358,6 +358,17 @@ def test_large_shapes_in_their_launch_configuration(torch_cuda, shape):
     compare(got, oracle_backward(d), "T%d_%dx%d_r%d" % shape)
 
 
+@pytest.mark.parametrize("shape", [(5, 262144, 4096, 8), (12, 2048, 131072, 16), (40000, 256, 256, 16)],
+                         ids=lambda s: "T%d_%dx%d_r%d" % s)
+def test_extreme_aspect_ratios(torch_cuda, shape):
+    """Very wide inputs, very wide outputs (thousands of column blocks, the looped stage 1 of the forward kernel) and a
+    very long batch (thousands of token tiles): index arithmetic far from the benchmark shapes."""
+    T, d_in, d_out, r = shape
+    d = inputs.make_backward_inputs(38, T, d_in, d_out, r)
+    got = gpu_backward(torch_cuda, d)
+    compare(got, oracle_backward(d), "T%d_%dx%d_r%d" % shape)
+
+
 def test_argument_errors(torch_cuda):
     torch = torch_cuda
     d = inputs.make_backward_inputs(31, 16, 256, 256, 8)
