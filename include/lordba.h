@@ -184,6 +184,15 @@ lordba_status lordba_forward_save_t(const void* x, const uint32_t* packedA, cons
                                     const void* y_base, void* y_out, float* t_out, int64_t t_stride,
                                     int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream);
 
+/* DEVICE function: lordba_forward_save_t for an adapter with `ell` envelopes (the forward of lordba_forward_multi):
+ *   t_out[(e * r + k) * t_stride + t] = sum_i S_A[k, i] * s_in[e, i] * x[t, i]      fp32, one [r, t_stride] block per envelope
+ * y_base == NULL and y_out == NULL together: only t_out.  Runs the 8-row, 8-wave variant of the kernel (the only one
+ * with a training instantiation for ell >= 2), so y_out may differ from lordba_forward_multi's in the last bit. */
+lordba_status lordba_forward_multi_save_t(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                          const void* s_in, const void* s_rank, const void* s_out,
+                                          const void* y_base, void* y_out, float* t_out, int64_t t_stride,
+                                          int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream);
+
 /* DEVICE function: the backward pass of the branch in training (Sec. 3.2, "Forward and backward pass"; Alg. QAT-LoRDBA;
  * smooth-sign straight-through factor of Eq. (smoothsign)).  For Y = Y_base + X diag(s_in) S_A^T diag(s_rank) S_B^T diag(s_out)
  * with S_A = sign(latentA), S_B = sign(latentB), and an upstream gradient g = dL/dY, it computes
@@ -229,13 +238,13 @@ lordba_status lordba_backward(const void* x, const void* g,
  * l = ell; the forward of lordba_forward_multi).  s_in fp16 [ell, d_in], s_rank fp16 [ell, r], s_out fp16 [ell, d_out];
  * d_s_in fp32 [ell, d_in], d_s_rank fp32 [ell, r], d_s_out fp32 [ell, d_out]: every envelope has its own scale
  * gradients; dx and the latent gradients are the sums over the envelopes (dx with one rounding).  1 <= ell <=
- * LORDBA_MAX_ENVELOPES.  No kept t here: the rank-r intermediates are recomputed (one pass over x and one over g per
- * envelope, besides the passes of the weight-gradient kernel).  Workspace: lordba_backward_workspace_bytes, whatever
- * ell is.  Everything else as lordba_backward. */
+ * LORDBA_MAX_ENVELOPES.  t_saved: what lordba_forward_multi_save_t wrote ([ell, r, t_stride]), or NULL (recomputed: one
+ * more pass over x).  Workspace: lordba_backward_workspace_bytes, whatever ell is.  Everything else as lordba_backward. */
 lordba_status lordba_backward_multi(const void* x, const void* g,
                                     const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
                                     const void* s_in, const void* s_rank, const void* s_out,
                                     const float* latentA, const float* latentB, float kappa,
+                                    const float* t_saved, int64_t t_stride,
                                     const void* dx_base, void* dx,
                                     float* d_s_in, float* d_s_rank, float* d_s_out,
                                     float* d_latentA, float* d_latentB,

@@ -137,7 +137,9 @@ def load_library():
     lib.lordba_backward.restype = ci
     lib.lordba_backward.argtypes = [vp] * 10 + [ctypes.c_float, vp, i64] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 4 + [vp]
     lib.lordba_backward_multi.restype = ci
-    lib.lordba_backward_multi.argtypes = [vp] * 10 + [ctypes.c_float] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 5 + [vp]
+    lib.lordba_backward_multi.argtypes = [vp] * 10 + [ctypes.c_float, vp, i64] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 5 + [vp]
+    lib.lordba_forward_multi_save_t.restype = ci
+    lib.lordba_forward_multi_save_t.argtypes = [vp] * 9 + [i64] * 6 + [vp]
     lib.lordba_pack_latents.restype = ci
     lib.lordba_pack_latents.argtypes = [vp] * 6 + [i64] * 3 + [vp]
     lib.lordba_forward_save_t.restype = ci
@@ -470,8 +472,34 @@ def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, late
     return out
 
 
+def lordba_forward_multi_save_t(x, packedA, packedB, s_in, s_rank, s_out, y_base=None, y_out=None, t_out=None, stream=None):
+    """lordba_forward_save_t for ell envelopes (s_in [ell, d_in], s_rank [ell, r], s_out [ell, d_out]): t_out float32
+    [ell, r, saved_t_stride(T)].  Returns (y_out or None, t_out)."""
+    import torch
+
+    lib = load_library()
+    T, d_in = x.shape
+    ell, r = s_rank.shape
+    d_out = s_out.shape[1]
+    if t_out is None:
+        t_out = torch.empty((ell, r, saved_t_stride(T)), dtype=torch.float32, device=x.device)
+    if y_base is not None and y_out is None:
+        y_out = torch.empty_like(y_base)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    ptr = lambda t_: None if t_ is None else t_.data_ptr()
+    st = lib.lordba_forward_multi_save_t(x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(), s_rank.data_ptr(),
+                                         s_out.data_ptr(), ptr(y_base), ptr(y_out), t_out.data_ptr(), t_out.shape[2], T, d_in, d_out, r,
+                                         ell, ctypes.c_void_p(stream))
+    if st != 0:
+        raise LordbaError(st, "lordba_forward_multi_save_t")
+    return y_out, t_out
+
+
 def lordba_backward_multi(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa: float,
-                          dx_base=None, dx=None, workspace=None, stream=None) -> dict:
+                          dx_base=None, dx=None, workspace=None, stream=None, t_saved=None) -> dict:
     """lordba_backward for ell envelopes: s_in [ell, d_in], s_rank [ell, r], s_out [ell, d_out] (float16 CUDA tensors); the
     scale gradients come back with the same leading envelope index."""
     import torch
@@ -497,6 +525,7 @@ def lordba_backward_multi(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out
     ptr = lambda t_: None if t_ is None else t_.data_ptr()
     st = lib.lordba_backward_multi(x.data_ptr(), g.data_ptr(), packedA.data_ptr(), packedAt.data_ptr(), packedBt.data_ptr(),
                                    s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(), ptr(latentA), ptr(latentB), float(kappa),
+                                   ptr(t_saved), 0 if t_saved is None else t_saved.shape[2],
                                    ptr(dx_base), ptr(dx), out["d_s_in"].data_ptr(), out["d_s_rank"].data_ptr(),
                                    out["d_s_out"].data_ptr(), ptr(out["d_latentA"]), ptr(out["d_latentB"]),
                                    workspace.data_ptr(), workspace.numel(), T, d_in, d_out, r, ell, ctypes.c_void_p(stream))

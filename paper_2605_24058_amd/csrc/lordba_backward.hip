@@ -16,7 +16,8 @@
 //   dx      The forward kernel itself on the transposed adapter: DeltaW^T has the form of Eq. (lordba) with the carriers
 //           transposed and alpha, gamma exchanged.  Its rank-r intermediate is du, which it also writes out.
 //   t       The forward kernel on x, stopped after its rank-r intermediate t (skipped when the caller kept t from the
-//           training forward pass, lordba_forward_save_t).
+//           training forward pass, lordba_forward_save_t).  With several envelopes both calls produce the intermediates of
+//           all envelopes at once; wgrad and finish then run once per envelope.
 //   wgrad   Q and P: MFMA with the token rows as contraction index.  A lane reads 8 token rows x 8 columns of x (or g)
 //           with row-contiguous 16-byte loads and transposes its 8 x 8 block in registers (v_perm_b32); MFMA e of a step
 //           takes column 8 m + e from lane group m.  dt = beta du (or u = beta t) enters as fp16 hi + lo after a
@@ -65,9 +66,10 @@ BwdPlan make_plan(int64_t T, int64_t d_in, int64_t d_out, int64_t r) {
     const int groups_per_wave = (groups + splits * kWgradWaves - 1) / (splits * kWgradWaves);
     p.tw = groups_per_wave * 32 * kWgradGroup;
     p.splits = (groups + groups_per_wave * kWgradWaves - 1) / (groups_per_wave * kWgradWaves);
+    // t and du: one [r, t_pad] block per envelope, room for the largest envelope count
     p.off_t = 0;
-    p.off_du = p.off_t + static_cast<size_t>(p.rp) * p.t_pad;
-    p.off_dbeta = p.off_du + static_cast<size_t>(p.rp) * p.t_pad;
+    p.off_du = p.off_t + static_cast<size_t>(LORDBA_MAX_ENVELOPES) * p.rp * p.t_pad;
+    p.off_dbeta = p.off_du + static_cast<size_t>(LORDBA_MAX_ENVELOPES) * p.rp * p.t_pad;
     p.off_part = p.off_dbeta + static_cast<size_t>(p.splits) * p.rp;
     p.off_part = (p.off_part + 3) & ~static_cast<size_t>(3);
     p.words = p.off_part + static_cast<size_t>(p.splits) * p.rp * p.dcols;
@@ -457,7 +459,7 @@ lordba_status backward_impl(const void* x, const void* g,
         const Span ins[] = {{x, nx}, {g, ng}, {packedA, lordba_packed_words(r, d_in) * 4}, {packedAt, lordba_packed_words(d_in, r) * 4},
                             {packedBt, lordba_packed_words(r, d_out) * 4}, {s_in, L * d_in * 2},
                             {s_rank, L * r * 2}, {s_out, L * d_out * 2}, {latentA, nA * 4},
-                            {latentB, nB * 4}, {t_saved, t_saved ? (static_cast<size_t>(r - 1) * t_stride + T) * 4 : 0}};
+                            {latentB, nB * 4}, {t_saved, t_saved ? (static_cast<size_t>(ell * r - 1) * t_stride + T) * 4 : 0}};
         auto hit = [](const Span& a, const Span& b) {
             const uintptr_t pa = reinterpret_cast<uintptr_t>(a.p), pb = reinterpret_cast<uintptr_t>(b.p);
             return pa != 0 && pb != 0 && a.n != 0 && b.n != 0 && pa < pb + b.n && pb < pa + a.n;  // (optional arguments may be NULL)
@@ -489,30 +491,20 @@ lordba_status backward_impl(const void* x, const void* g,
     const _Float16* sr = static_cast<const _Float16*>(s_rank);
     const _Float16* so = static_cast<const _Float16*>(s_out);
     lordba_status s;
-    if (ell > 1 && dx != nullptr) {
-        // dx = dx_base + g DeltaW^T with all envelopes at once: the multi-envelope forward branch of the transposed adapter
-        // (one pass over g, dx_base and dx, one rounding)
-        s = lordba_forward_multi(g, packedBt, packedAt, s_out, s_rank, s_in, dx_base, dx, T, d_out, d_in, r, ell, stream);
+    // du of every envelope, and dx = dx_base + g DeltaW^T if wanted (all envelopes at once, one rounding): the forward branch
+    // of the transposed adapter (it validates its own arguments); du is that call's rank-r intermediate
+    s = lordba_forward_multi_save_t(g, packedBt, packedAt, s_out, s_rank, s_in, dx_base, dx, duT, p.t_pad, T, d_out, d_in, r, ell, stream);
+    if (s != LORDBA_OK) return s;
+    if (t_saved == nullptr) {
+        // t of every envelope: the forward branch of the adapter itself, stopped after its rank-r intermediate (its second
+        // carrier is not read; packedAt stands in as a valid [d_in, r] carrier)
+        s = lordba_forward_multi_save_t(x, packedA, packedAt, s_in, s_rank, s_in, nullptr, nullptr, t_own, p.t_pad, T, d_in, d_in, r, ell,
+                                        stream);
         if (s != LORDBA_OK) return s;
     }
     for (int64_t e = 0; e < ell; ++e) {
-        // du (and, with one envelope, dx = dx_base + g DeltaW^T): the forward branch of the transposed adapter (it validates
-        // its own arguments); du is that call's rank-r intermediate
-        const bool with_dx = ell == 1 && dx != nullptr;
-        s = lordba_forward_save_t(g, packedBt, packedAt, so + e * d_out, sr + e * r, si + e * d_in, with_dx ? dx_base : nullptr,
-                                  with_dx ? dx : nullptr, duT, p.t_pad, T, d_out, d_in, r, stream);
-        if (s != LORDBA_OK) return s;
-        const float* tT = t_saved;
-        int64_t tT_stride = t_stride;
-        if (tT == nullptr) {
-            // t: the forward branch of the adapter itself, stopped after its rank-r intermediate (its second carrier is
-            // not read; packedAt stands in as a valid [d_in, r] carrier)
-            s = lordba_forward_save_t(x, packedA, packedAt, si + e * d_in, sr + e * r, si + e * d_in, nullptr, nullptr, t_own, p.t_pad,
-                                      T, d_in, d_in, r, stream);
-            if (s != LORDBA_OK) return s;
-            tT = t_own;
-            tT_stride = p.t_pad;
-        }
+        const float* tT = t_saved ? t_saved + e * r * t_stride : t_own + e * r * p.t_pad;
+        const int64_t tT_stride = t_saved ? t_stride : p.t_pad;
 
         BwdArgs a;
         a.x = static_cast<const _Float16*>(x);
@@ -531,7 +523,7 @@ lordba_status backward_impl(const void* x, const void* g,
         a.d_latA = d_latentA;
         a.d_latB = d_latentB;
         a.tT = tT;
-        a.duT = duT;
+        a.duT = duT + e * r * p.t_pad;
         a.dbeta_part = ws + p.off_dbeta;
         a.part = ws + p.off_part;
         a.T = static_cast<int>(T);
@@ -579,11 +571,12 @@ extern "C" lordba_status lordba_backward_multi(const void* x, const void* g,
                                                const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
                                                const void* s_in, const void* s_rank, const void* s_out,
                                                const float* latentA, const float* latentB, float kappa,
+                                               const float* t_saved, int64_t t_stride,
                                                const void* dx_base, void* dx,
                                                float* d_s_in, float* d_s_rank, float* d_s_out,
                                                float* d_latentA, float* d_latentB,
                                                void* workspace, size_t workspace_bytes,
                                                int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream) {
-    return backward_impl(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa, nullptr, 0, dx_base, dx,
+    return backward_impl(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa, t_saved, t_stride, dx_base, dx,
                          d_s_in, d_s_rank, d_s_out, d_latentA, d_latentB, workspace, workspace_bytes, T, d_in, d_out, r, ell, stream);
 }

@@ -24,3 +24,18 @@ extern "C" lordba_status lordba_forward_multi(const void* x, const uint32_t* pac
     return lordba_forward_multi_algo(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, ell, stream,
                                      LORDBA_ALGO_AUTO);
 }
+
+extern "C" lordba_status lordba_forward_multi_save_t(const void* x, const uint32_t* packedA, const uint32_t* packedB,
+                                                     const void* s_in, const void* s_rank, const void* s_out,
+                                                     const void* y_base, void* y_out, float* t_out, int64_t t_stride,
+                                                     int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream) {
+    if (t_out == nullptr) return LORDBA_ERR_NULL;
+    const int algo = LORDBA_ALGO_AUTO;
+    switch (ell) {
+        case 1: return lordba_forward_save_t(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, t_out, t_stride, T, d_in, d_out, r, stream);
+        case 2: return forward_impl<2>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, nullptr, 1, false, t_out, t_stride);
+        case 3: return forward_impl<3>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, nullptr, 1, false, t_out, t_stride);
+        case 4: return forward_impl<4>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, nullptr, 1, false, t_out, t_stride);
+        default: return LORDBA_ERR_DIM;
+    }
+}

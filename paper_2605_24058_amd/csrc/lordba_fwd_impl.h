@@ -60,7 +60,8 @@ struct FwdArgs {
     const int32_t* ids;
     int n_adapters;
     // Training: if t_out != nullptr the rank-r intermediate t = (x D_alpha) B1 (before the rank scaling) is also written,
-    // fp32, rank-major: t_out[k * t_stride + token].  With y_out == nullptr nothing else is computed (no stage 3).
+    // fp32, rank-major, one [r, t_stride] block per envelope: t_out[(e * r + k) * t_stride + token].  With
+    // y_out == nullptr nothing else is computed (no stage 3).
     float* t_out;
     int t_stride;
 };
@@ -360,7 +361,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // Training: the rank-r intermediate t (before the rank scaling) is kept for the backward pass.  The stores are issued
     // after everything else: vector memory stores count in the same counter as the loads and may complete out of order
     // with them, so that a wait for y_base issued after such a store could also have to wait for the store.
-    float tkeep[TR ? RB : 1];
+    float tkeep[TR ? RB * L : 1];
     auto export_t = [&]() {
         if constexpr (TR) {
             if (wave < 4 && a.t_out != nullptr) {
@@ -368,8 +369,12 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
                 const int row = TMV == 16 ? q * 4 + i : q * 2 + (i & 1);
                 if ((TMV == 16 || i < 2) && row >= first && row <= last) {
 #pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-                        if (rb * 16 + li < r) a.t_out[static_cast<int64_t>(rb * 16 + li) * a.t_stride + t0 + row] = tkeep[rb];
+                    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+                        for (int en = 0; en < L; ++en)
+                            if (rb * 16 + li < r)
+                                a.t_out[(static_cast<int64_t>(en) * r + rb * 16 + li) * a.t_stride + t0 + row] = tkeep[rb * L + en];
+                    }
                 }
             }
         }
@@ -391,7 +396,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
 #pragma unroll
                     for (int w = 0; w + st < NW; w += 2 * st) part[w] += part[w + st];
                 }
-                if constexpr (TR) tkeep[rb] = part[0];  // training: t is written out at the very end (see export_t)
+                if constexpr (TR) tkeep[rb * L + en] = part[0];  // training: t is written out at the very end (see export_t)
                 u[rb] = part[0] * sr[rb][en];
                 amax = fmaxf(amax, fabsf(u[rb]));
             }
@@ -642,11 +647,11 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a0, int
         if (tid < RP) {
             const float tk = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
             u_s[en][tid] = tid < r ? static_cast<float>(a.s_rank[en * r + tid]) * tk : 0.f;
-            if (PLAIN && a.t_out != nullptr && tid < r) a.t_out[static_cast<int64_t>(tid) * a.t_stride + t] = tk;
+            if (a.t_out != nullptr && a0.ids == nullptr && tid < r) a.t_out[(static_cast<int64_t>(en) * r + tid) * a.t_stride + t] = tk;
         }
         __syncthreads();
     }
-    if (PLAIN && a.y_out == nullptr) return;  // only t was wanted
+    if (a.y_out == nullptr) return;  // only t was wanted
     const _Float16* ybr = a.y_base + t * d_out;
     _Float16* yor = a.y_out + t * d_out;
     for (int j = tid; j < d_out; j += 256) {
@@ -670,8 +675,13 @@ constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
 
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L, bool TR = false>
 lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
-    if constexpr (!TR && L == 1 && GM != 4) {  // training calls (t is kept) run their own instantiation
+    // Training calls (t is kept) run their own instantiation.  With several envelopes only the plain grid mode of the
+    // 8-row, 8-wave variants has one (the dispatch sends such calls there).
+    if constexpr (!TR && ((L == 1 && GM != 4) || (L > 1 && GM == 0 && TMV == 8 && NW == 8))) {
         if (a.t_out != nullptr) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, GM, L, true>(a, stream);
+    }
+    if constexpr (!TR) {
+        if (a.t_out != nullptr) return LORDBA_ERR_ALGO;
     }
     const size_t lds = mfma_lds_bytes(RB, TMV, NW, D1, L);
     if (lds > kMaxLds) return LORDBA_ERR_ALGO;
@@ -726,6 +736,9 @@ lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
             return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 4, L>(a, stream);
         }
         return LORDBA_ERR_ALGO;
+    }
+    if constexpr (L > 1) {
+        if (a.t_out != nullptr) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 0, L>(a, stream);  // see launch_mfma_gm
     }
     if constexpr (RB == 1 && BM != 0 && L == 1) {
         if (tiles >= 128) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 1, L>(a, stream);
@@ -839,7 +852,7 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
     const bool t_only = t_out != nullptr && y_base == nullptr && y_out == nullptr;  // training: only the rank-r intermediate
     if (!x || !packedA || !packedB || !s_in || !s_rank || !s_out) return LORDBA_ERR_NULL;
     if (!t_only && (!y_base || !y_out)) return LORDBA_ERR_NULL;
-    if (t_out != nullptr && (L != 1 || batched || t_stride < T || t_stride > INT32_MAX || !aligned(t_out, 4))) return LORDBA_ERR_DIM;
+    if (t_out != nullptr && (batched || t_stride < T || t_stride > INT32_MAX || !aligned(t_out, 4))) return LORDBA_ERR_DIM;
     if (batched && !ids) return LORDBA_ERR_NULL;
     if (batched && !aligned(ids, 4)) return LORDBA_ERR_ALIGN;
     if (!aligned(x, 2) || !aligned(s_in, 2) || !aligned(s_rank, 2) || !aligned(s_out, 2) || !aligned(y_base, 2) ||
@@ -854,7 +867,7 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
         return LORDBA_ERR_ALIAS;
     if (y_out != y_base && overlaps(y_out, ny, y_base, ny)) return LORDBA_ERR_ALIAS;
     if (t_out != nullptr) {
-        const size_t nt = (static_cast<size_t>(r - 1) * t_stride + T) * 4;
+        const size_t nt = (static_cast<size_t>(L * r - 1) * t_stride + T) * 4;
         if (overlaps(t_out, nt, x, nx) || overlaps(t_out, nt, y_out, ny) || overlaps(t_out, nt, y_base, ny))
             return LORDBA_ERR_ALIAS;
     }
@@ -917,7 +930,9 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
             s = rb <= 2 ? launch_mfma_rb<8, 16, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
         }
     } else {
-        if (tall) {
+        if (t_out != nullptr) {
+            s = launch_mfma_rb<8, 8, L>(a, st);  // the variant family that has a training instantiation
+        } else if (tall) {
             s = launch_mfma_rb<16, 8, L>(a, st);
             if (s == LORDBA_ERR_ALGO && algo == LORDBA_ALGO_AUTO) s = launch_mfma_rb<8, 8, L>(a, st);
         } else {

@@ -146,7 +146,7 @@ def test_backward_validation_needs_no_device(lib):
     assert call(ts=p["ts"], t_stride=4) == 2                                    # a kept t must reach the padded token count
     assert call(ts=p["ts"] + 4, t_stride=128) == 5
     multi = lambda ell: lib.lordba_backward_multi(p["x"], p["g"], p["pA"], p["pAt"], p["pBt"], p["si"], p["sr"], p["so"], p["lA"], p["lB"],
-                                                  ctypes.c_float(100.0), p["dxb"], p["dx"], p["dsi"], p["dsr"], p["dso"], p["dlA"], p["dlB"],
+                                                  ctypes.c_float(100.0), None, 0, p["dxb"], p["dx"], p["dsi"], p["dsr"], p["dso"], p["dlA"], p["dlB"],
                                                   p["ws"], need - 4, T, d_in, d_out, r, ell, None)
     assert multi(0) == 2 and multi(5) == 2 and multi(2) == 9                     # envelope count; then the workspace size
     # lordba_forward_save_t: t_out is required, must not overlap the activations, t_stride >= T

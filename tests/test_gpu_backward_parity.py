@@ -303,6 +303,24 @@ def test_several_envelopes(torch_cuda, case):
                 assert err <= TOL, "%s envelope %d: %.3e" % (k, en, err)
         assert oracle.row_rel_l2(got["d_latentA"].astype(np.float64), want["d_latA"]).max() <= TOL
         assert oracle.row_rel_l2(got["d_latentB"].astype(np.float64).T, want["d_latB"].T).max() <= TOL
+    # the training forward of the same adapter keeps t of every envelope: y against the oracle, t against the oracle,
+    # and the backward pass fed with it gives the same bits as the one that recomputes it
+    _, pB = binding.lordba_pack_signs(d["signsA"], d["signsB"])
+    t_buf = torch.full((ell, r, binding.saved_t_stride(T)), float("nan"), dtype=torch.float32, device="cuda:0")
+    y, t_kept = binding.lordba_forward_multi_save_t(cu(d["x"]), w(pA), w(pB), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]),
+                                                    cu(d["y_base"]), t_out=t_buf)
+    kept = binding.lordba_backward_multi(cu(d["x"]), cu(d["g"]), w(pA), w(pAt), w(pBt), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]),
+                                         cu(d["latA"]), cu(d["latB"]), KAPPA, dx_base=cu(np.zeros_like(d["dx_base"])), t_saved=t_kept)
+    torch.cuda.synchronize()
+    ywant = oracle.forward_multi(d["x"], d["signsA"], d["signsB"], d["s_in"], d["s_rank"], d["s_out"], d["y_base"])
+    assert oracle.row_rel_l2(y.cpu().numpy().astype(np.float64), ywant).max() <= TOL
+    th = t_kept.cpu().numpy()
+    assert np.isnan(th[:, :, T:]).all()
+    for en in range(ell):
+        twant = oracle.rank_intermediate(d["x"], d["signsA"], d["s_in"][en])
+        assert oracle.row_rel_l2(th[en, :, :T].T.astype(np.float64), twant).max() <= 1e-5
+    for k, v in kept.items():
+        assert np.array_equal(v.cpu().numpy(), got[k]), k
 
 
 def test_hip_graph_replays_match_eager(torch_cuda):
