@@ -18,7 +18,10 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
 _LIB_PATH = os.path.join(_PKG, "liblordba.so")
-_SOURCES = ("lordba_forward.hip", "lordba_forward_multi.hip", "lordba_backward.hip", "lordba_pack_device.hip", "lordba_pack.cpp")
+# one translation unit per kernel family and kind (inference / training): they compile side by side
+_SOURCES = ("lordba_forward.hip", "lordba_forward_train.hip", "lordba_forward_multi_l2.hip", "lordba_forward_multi_l3.hip",
+            "lordba_forward_multi_l4.hip", "lordba_forward_multi_train.hip", "lordba_forward_multi.hip", "lordba_backward.hip",
+            "lordba_pack_device.hip", "lordba_pack.cpp")
 _lib = None
 
 ALGO_AUTO, ALGO_GENERAL, ALGO_MFMA_T8, ALGO_MFMA_T16 = 0, 1, 2, 3

@@ -34,12 +34,3 @@ extern "C" lordba_status lordba_forward_batched(const void* x, const uint32_t* p
     return forward_impl<1>(x, packedA_pool, packedB_pool, s_in_pool, s_rank_pool, s_out_pool, y_base, y_out, T, d_in, d_out, r,
                            stream, LORDBA_ALGO_AUTO, adapter_of_row, n_adapters, true);
 }
-
-extern "C" lordba_status lordba_forward_save_t(const void* x, const uint32_t* packedA, const uint32_t* packedB,
-                                               const void* s_in, const void* s_rank, const void* s_out,
-                                               const void* y_base, void* y_out, float* t_out, int64_t t_stride,
-                                               int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream) {
-    if (t_out == nullptr) return LORDBA_ERR_NULL;
-    return forward_impl<1>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream,
-                           LORDBA_ALGO_AUTO, nullptr, 1, false, t_out, t_stride);
-}

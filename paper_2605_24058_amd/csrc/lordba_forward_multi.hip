@@ -1,6 +1,7 @@
-// C entry points of the multi-envelope adapter forward branch (Eq. (lordba) with envelope rank l >= 2; the kernels and
-// the dispatch live in lordba_fwd_impl.h and are instantiated here for 2, 3 and 4 envelopes).
-#include "lordba_fwd_impl.h"
+// C entry points of the multi-envelope adapter forward branch (Eq. (lordba) with envelope rank l >= 2).  The kernels are
+// instantiated in one translation unit per envelope count (lordba_forward_multi_l2/3/4.hip, and lordba_forward_multi_train.hip
+// for the calls that keep t); this file only dispatches on the envelope count.
+#include "lordba_forward_multi_units.h"
 
 extern "C" lordba_status lordba_forward_multi_algo(const void* x, const uint32_t* packedA, const uint32_t* packedB,
                                                    const void* s_in, const void* s_rank, const void* s_out,
@@ -9,9 +10,9 @@ extern "C" lordba_status lordba_forward_multi_algo(const void* x, const uint32_t
                                                    void* stream, int algo) {
     switch (ell) {
         case 1: return lordba_forward_algo(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo);
-        case 2: return forward_impl<2>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo);
-        case 3: return forward_impl<3>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo);
-        case 4: return forward_impl<4>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo);
+        case 2: return lordba_forward_multi_l2(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, nullptr, 0);
+        case 3: return lordba_forward_multi_l3(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, nullptr, 0);
+        case 4: return lordba_forward_multi_l4(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, nullptr, 0);
         default: return LORDBA_ERR_DIM;
     }
 }
@@ -33,9 +34,9 @@ extern "C" lordba_status lordba_forward_multi_save_t(const void* x, const uint32
     const int algo = LORDBA_ALGO_AUTO;
     switch (ell) {
         case 1: return lordba_forward_save_t(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, t_out, t_stride, T, d_in, d_out, r, stream);
-        case 2: return forward_impl<2>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, nullptr, 1, false, t_out, t_stride);
-        case 3: return forward_impl<3>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, nullptr, 1, false, t_out, t_stride);
-        case 4: return forward_impl<4>(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, nullptr, 1, false, t_out, t_stride);
+        case 2: return lordba_forward_multi_l2t(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, t_out, t_stride);
+        case 3: return lordba_forward_multi_l3t(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, t_out, t_stride);
+        case 4: return lordba_forward_multi_l4t(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, T, d_in, d_out, r, stream, algo, t_out, t_stride);
         default: return LORDBA_ERR_DIM;
     }
 }

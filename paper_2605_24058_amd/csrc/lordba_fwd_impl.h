@@ -673,16 +673,23 @@ __global__ __launch_bounds__(256) void lordba_fwd_general_kernel(FwdArgs a0, int
 
 constexpr size_t kMaxLds = 160 * 1024;  // LDS per CU on gfx950
 
-template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L, bool TR = false>
+// A translation unit holds either the inference instantiations of the matrix-core kernel (LORDBA_FWD_TRAINING 0, the
+// default) or the training ones, which also keep t (LORDBA_FWD_TRAINING 1); every entry point lives in a unit of the
+// matching kind, so that the units compile side by side and none carries both sets.
+#ifndef LORDBA_FWD_TRAINING
+#define LORDBA_FWD_TRAINING 0
+#endif
+constexpr bool kTraining = LORDBA_FWD_TRAINING != 0;
+
+template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L>
 lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
-    // Training calls (t is kept) run their own instantiation.  With several envelopes only the plain grid mode of the
-    // 8-row, 8-wave variants has one (the dispatch sends such calls there).
-    if constexpr (!TR && ((L == 1 && GM != 4) || (L > 1 && GM == 0 && TMV == 8 && NW == 8))) {
-        if (a.t_out != nullptr) return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, GM, L, true>(a, stream);
-    }
-    if constexpr (!TR) {
-        if (a.t_out != nullptr) return LORDBA_ERR_ALGO;
-    }
+    constexpr bool TR = kTraining;
+    if ((a.t_out != nullptr) != TR) return LORDBA_ERR_ALGO;  // (an entry point of the other kind of unit)
+    // With several envelopes only the plain grid mode of the 8-row, 8-wave variants has a training instantiation (the
+    // dispatch sends such calls there); the multi-adapter batch has none.
+    if constexpr (TR && !((L == 1 && GM != 4) || (L > 1 && GM == 0 && TMV == 8 && NW == 8))) {
+        return LORDBA_ERR_ALGO;
+    } else {
     const size_t lds = mfma_lds_bytes(RB, TMV, NW, D1, L);
     if (lds > kMaxLds) return LORDBA_ERR_ALGO;
     auto kern = lordba_fwd_mfma_kernel<RB, TMV, NW, D1, OS, BM, GM, L, TR>;
@@ -723,6 +730,7 @@ lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
     if constexpr (GM == 4) grid = dim3(tiles, TMV);  // one workgroup per possible run of a tile (see the kernel)
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, stream, b);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
+    }
 }
 
 // Grid mode 1 only exists where sign operands are built ahead (one rank block, byte-aligned carrier rows); it pays once
