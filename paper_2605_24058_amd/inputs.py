@@ -164,6 +164,17 @@ def make_backward_inputs(seed: int, T: int, d_in: int, d_out: int, r: int, g_sca
     return out
 
 
+def make_ptq_inputs(seed: int, N: int, M: int, r0: int, decay: float = 0.85) -> Dict[str, np.ndarray]:
+    """The fp16 LoRA factors that post-training quantisation starts from: A_star [N, r0] and B_star [M, r0] with
+    Delta W* = A_star B_star^T.  Entries are N(0, 0.05^2); column k of A_star is damped by decay^k, so that the update
+    has the decaying singular spectrum of a trained adapter and distinct singular values."""
+    g = _rng(seed, 7)
+    damp = (np.float32(decay) ** np.arange(r0, dtype=np.float32)).astype(np.float32)
+    a = (np.float32(0.05) * g.standard_normal((N, r0), dtype=np.float32) * damp[None, :]).astype(np.float16)
+    b = (np.float32(0.05) * g.standard_normal((M, r0), dtype=np.float32)).astype(np.float16)
+    return {"A_star": a, "B_star": b}
+
+
 def make_inputs_for(shape: Shape, seed: int) -> Dict[str, np.ndarray]:
     return make_inputs(seed, shape.T, shape.d_in, shape.d_out, shape.r)
 
