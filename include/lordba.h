@@ -46,7 +46,7 @@ enum {
     LORDBA_ERR_NO_DEVICE = 6, /* no usable HIP device / not a gfx950 device                   */
     LORDBA_ERR_LAUNCH = 7,    /* the HIP runtime rejected the launch                          */
     LORDBA_ERR_ALGO = 8,      /* lordba_forward_algo: the requested kernel cannot run this shape */
-    LORDBA_ERR_WORKSPACE = 9  /* lordba_backward: the workspace is smaller than lordba_backward_workspace_bytes */
+    LORDBA_ERR_WORKSPACE = 9  /* lordba_backward, lordba_ptq: the workspace is smaller than their ..._workspace_bytes */
 };
 
 #define LORDBA_MAX_RANK 64
@@ -253,6 +253,54 @@ lordba_status lordba_backward_multi(const void* x, const void* g,
 
 /* Bytes of workspace lordba_backward needs for a shape (0 for a shape it does not support). */
 size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, int64_t r);
+
+/* ---- post-training quantisation of a low-rank update into a LoRDBA adapter ---------------------------------------- */
+
+#define LORDBA_PTQ_MAX_RANK 32         /* carrier rank R of lordba_ptq                    */
+#define LORDBA_PTQ_MAX_FACTOR_RANK 64  /* rank r0 of the factors of the update            */
+#define LORDBA_PTQ_MAX_SWEEPS 4096     /* outer iterations K                              */
+
+/* DEVICE function: PTQ-LoRDBA at envelope rank 1 (appendix on post-training quantisation: the least-squares problem
+ * Eq. (ptq-problem); the consensus ADMM Eq. (admm-problem) with the ordered updates Eq. (u-step-1), Eq. (u-step-2),
+ * Eq. (scales-step), Eq. (m-y-step); the closed-form scale updates Eq. (alpha-update), Eq. (gamma-update),
+ * Eq. (beta-gram), Eq. (beta-pinv); the warm start Eq. (svd-init); Alg. PTQ-LoRDBA).  Fits
+ *     diag(alpha) B1 diag(beta) B2 diag(gamma)  ~  Delta W* = A_star B_star^T     (N x M, in the Frobenius norm)
+ * with B1 in {+-1}^{N x R}, B2 in {+-1}^{R x M}, and returns the adapter in the form lordba_forward takes, with
+ * d_in = N, d_out = M, r = R.  All pointers are DEVICE pointers; the call only enqueues kernels on `stream` and never
+ * waits for the device.
+ *   A_star, B_star : fp16 [N, r0], [M, r0] row-major, in; taken at their exact values.  Both need full column rank.
+ *   packedA : uint32 [lordba_packed_words(R, N)] out, S_A = B1^T in the canonical format;  packedB : uint32
+ *             [lordba_packed_words(M, R)] out, S_B = B2^T.
+ *   alpha [N], beta [R], gamma [M] : fp64 out, the scales (s_in, s_rank, s_out of the forward).
+ *   s_in [N], s_rank [R], s_out [M] : fp16 out, the same scales rounded to nearest; each may be NULL.
+ *   info : fp64 [8 + K] out: [0] sweeps run, [1] 1 if the loop ended because the sign matrices repeated, [2] the penalty
+ *          rho it ended with, [3] ||Delta W*||_F^2, [4] 1 if the input was degenerate (a factor without full column rank
+ *          or a zero or non-finite update: no sweep is run and the other outputs are unspecified), [5..7] 0,
+ *          [8 + t] the objective of Eq. (admm-problem) at the continuous iterates after the scale update of sweep t
+ *          (0 for sweeps not run).
+ *   workspace : lordba_ptq_workspace_bytes(N, M, R, r0) bytes, 8-byte aligned, owned by the caller; a smaller one ->
+ *          LORDBA_ERR_WORKSPACE.  After the call it begins with the last continuous iterates, fp64: U1 [N, R] row-major at
+ *          offset 0, then U2^T [M, R] row-major at the next multiple of 32 doubles (they are what a later quantisation-
+ *          aware training run would take as latent carriers); the rest is scratch.
+ *   K : outer iterations (the paper uses 100); tau > 1 and mu > 0: the residual-balancing constants (the paper uses 2, 10),
+ *          anything else -> LORDBA_ERR_VALUE.
+ * Readings where the paper leaves a choice: sign(0) = +1; the warm start keeps beta at the singular values, starts from
+ * gamma = 1 and updates alpha, then gamma; a scale sweep updates alpha, gamma, beta in this order at the continuous
+ * iterates; residual balancing compares r = sqrt(sum_k ||U_k - M_k||_F^2) with s = sqrt(sum_k (rho_k ||M_k^(t+1) -
+ * M_k^(t)||_F)^2), rho_k = rho / n_k, after the sweeps t < K/2 (r > mu s: rho *= tau, Y /= tau; s > mu r: the opposite);
+ * the loop ends after the first sweep that leaves both sign matrices unchanged.  Each pair (column k of B1, row k of B2)
+ * is defined up to a common sign (the singular vectors of the warm start are).
+ * Limits: 1 <= R <= LORDBA_PTQ_MAX_RANK, R <= r0 <= LORDBA_PTQ_MAX_FACTOR_RANK (beyond r0 the warm start has no singular
+ * vectors), 1 <= N, M <= 2^22, 1 <= K <= LORDBA_PTQ_MAX_SWEEPS; else LORDBA_ERR_DIM.  No output, nor the workspace,
+ * may overlap an input or another output: LORDBA_ERR_ALIAS.  Arithmetic: fp64 throughout, fixed summation order
+ * (calls are reproducible bit for bit). */
+lordba_status lordba_ptq(const void* A_star, const void* B_star, uint32_t* packedA, uint32_t* packedB,
+                         double* alpha, double* beta, double* gamma, void* s_in, void* s_rank, void* s_out,
+                         double* info, void* workspace, size_t workspace_bytes,
+                         int64_t N, int64_t M, int64_t R, int64_t r0, int64_t K, double tau, double mu, void* stream);
+
+/* Bytes of workspace lordba_ptq needs for a shape (0 for a shape it does not support). */
+size_t lordba_ptq_workspace_bytes(int64_t N, int64_t M, int64_t R, int64_t r0);
 
 /* Static, never-NULL description of a status code. */
 const char* lordba_status_string(lordba_status status);

@@ -21,7 +21,7 @@ _LIB_PATH = os.path.join(_PKG, "liblordba.so")
 # one translation unit per kernel family and kind (inference / training): they compile side by side
 _SOURCES = ("lordba_forward.hip", "lordba_forward_train.hip", "lordba_forward_multi_l2.hip", "lordba_forward_multi_l3.hip",
             "lordba_forward_multi_l4.hip", "lordba_forward_multi_train.hip", "lordba_forward_multi.hip", "lordba_backward.hip",
-            "lordba_pack_device.hip", "lordba_pack.cpp")
+            "lordba_ptq.hip", "lordba_pack_device.hip", "lordba_pack.cpp")
 _lib = None
 
 ALGO_AUTO, ALGO_GENERAL, ALGO_MFMA_T8, ALGO_MFMA_T16 = 0, 1, 2, 3
@@ -147,6 +147,10 @@ def load_library():
     lib.lordba_pack_latents.argtypes = [vp] * 6 + [i64] * 3 + [vp]
     lib.lordba_forward_save_t.restype = ci
     lib.lordba_forward_save_t.argtypes = [vp] * 9 + [i64] * 5 + [vp]
+    lib.lordba_ptq_workspace_bytes.restype = ctypes.c_size_t
+    lib.lordba_ptq_workspace_bytes.argtypes = [i64] * 4
+    lib.lordba_ptq.restype = ci
+    lib.lordba_ptq.argtypes = [vp] * 12 + [ctypes.c_size_t] + [i64] * 5 + [ctypes.c_double, ctypes.c_double, vp]
     lib.lordba_status_string.restype = ctypes.c_char_p
     lib.lordba_status_string.argtypes = [ci]
     _lib = lib
@@ -534,6 +538,57 @@ def lordba_backward_multi(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out
                                    workspace.data_ptr(), workspace.numel(), T, d_in, d_out, r, ell, ctypes.c_void_p(stream))
     if st != 0:
         raise LordbaError(st, "lordba_backward_multi")
+    return out
+
+
+def lordba_ptq_workspace_bytes(N: int, M: int, R: int, r0: int) -> int:
+    return int(load_library().lordba_ptq_workspace_bytes(N, M, R, r0))
+
+
+def lordba_ptq(A_star, B_star, R: int, K: int = 100, tau: float = 2.0, mu: float = 10.0, workspace=None, stream=None):
+    """Post-training quantisation of the update A_star B_star^T (torch CUDA float16 tensors [N, r0], [M, r0]) into a LoRDBA
+    adapter of carrier rank R: lordba_ptq of the C interface.  Returns a dict of CUDA tensors: packedA, packedB (int32,
+    the canonical format, as lordba_forward takes them), alpha [N], beta [R], gamma [M] (float64), s_in, s_rank, s_out
+    (float16), info (float64 [8 + K], see include/lordba.h), and U1 [N, R], U2t [M, R] (float64 views into the workspace: the
+    last continuous iterates)."""
+    import torch
+
+    lib = load_library()
+    N, r0 = A_star.shape
+    M = B_star.shape[0]
+    if tuple(B_star.shape) != (M, r0) or A_star.dtype != torch.float16 or B_star.dtype != torch.float16:
+        raise ValueError("need float16 A_star [N, r0] and B_star [M, r0]")
+    dev = A_star.device
+    need = lordba_ptq_workspace_bytes(N, M, R, r0)
+    if workspace is None:
+        workspace = torch.empty(max(need, 8) // 8, dtype=torch.float64, device=dev)
+    out = {
+        "packedA": torch.empty(max((R * N + 31) // 32, 1), dtype=torch.int32, device=dev),
+        "packedB": torch.empty(max((M * R + 31) // 32, 1), dtype=torch.int32, device=dev),
+        "alpha": torch.empty(max(N, 1), dtype=torch.float64, device=dev),
+        "beta": torch.empty(max(R, 1), dtype=torch.float64, device=dev),
+        "gamma": torch.empty(max(M, 1), dtype=torch.float64, device=dev),
+        "s_in": torch.empty(max(N, 1), dtype=torch.float16, device=dev),
+        "s_rank": torch.empty(max(R, 1), dtype=torch.float16, device=dev),
+        "s_out": torch.empty(max(M, 1), dtype=torch.float16, device=dev),
+        "info": torch.empty(8 + max(K, 0), dtype=torch.float64, device=dev),
+    }
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    st = lib.lordba_ptq(A_star.contiguous().data_ptr(), B_star.contiguous().data_ptr(), out["packedA"].data_ptr(),
+                        out["packedB"].data_ptr(), out["alpha"].data_ptr(), out["beta"].data_ptr(), out["gamma"].data_ptr(),
+                        out["s_in"].data_ptr(), out["s_rank"].data_ptr(), out["s_out"].data_ptr(), out["info"].data_ptr(),
+                        workspace.data_ptr(), workspace.numel() * workspace.element_size(), N, M, R, r0, K, tau, mu,
+                        ctypes.c_void_p(stream))
+    if st != 0:
+        raise LordbaError(st, "lordba_ptq")
+    off2 = (N * R + 31) // 32 * 32
+    ws = workspace.view(torch.float64) if workspace.dtype != torch.float64 else workspace
+    out["U1"] = ws[:N * R].view(N, R)
+    out["U2t"] = ws[off2:off2 + M * R].view(M, R)
+    out["workspace"] = workspace
     return out
 
 

@@ -1,0 +1,776 @@
+// PTQ-LoRDBA at envelope rank 1 on the device: the scaled consensus ADMM that fits diag(alpha) B1 diag(beta) B2 diag(gamma)
+// to a low-rank update A* (B*)^T (appendix on post-training quantisation: Eq. (ptq-problem), the ordered updates
+// Eq. (u-step-1), Eq. (u-step-2), Eq. (scales-step), Eq. (m-y-step), Alg. PTQ-LoRDBA; closed-form scale updates
+// Eq. (alpha-update), Eq. (gamma-update), Eq. (beta-gram), Eq. (beta-pinv); warm start Eq. (svd-init)).
+//
+// The N x M target is never formed.  With the target kept as its factors, every quantity a sweep needs is a function of
+// two small "Gram pairs", one per side of the adapter:
+//     side 1 (rows i of U1, factor rows a*_i, scale alpha):  S1 = sum_i alpha_i^2 u_i u_i^T  [R, R],  K1 = sum_i alpha_i u_i a*_i^T  [R, r0]
+//     side 2 (columns j of U2, factor rows b*_j, scale gamma): S2 = sum_j gamma_j^2 v_j v_j^T,        K2 = sum_j gamma_j v_j b*_j^T
+// e.g. the Tikhonov step of row i of U1 is (alpha_i^2 (beta beta^T o S2) + rho_1 I) u = alpha_i beta o (K2 a*_i) + rho_1 (M1 - Y1)_i.
+// The two sides are mirror images (the transposed target swaps them), so one kernel serves both.  U2 is held transposed,
+// [M, R] row-major, which is also the layout of S_B.  All arithmetic is fp64; sums run in a fixed order (no atomics), so
+// a call is reproducible bit for bit.
+//
+// Each row kernel works on blocks of 64 rows, ends by writing its block's share of its side's Gram pair, and starts by
+// adding up the other side's shares: a sweep is seven launches (two Tikhonov steps, alpha, gamma, beta, sign/dual update,
+// penalty control) and no stand-alone reduction.  A flag in device memory ends the loop: once the sign matrices repeat,
+// the remaining launches return at once, so the host never waits on the device inside the loop.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "lordba.h"
+
+namespace {
+
+constexpr int kRows = 64;      // rows of one side per workgroup
+constexpr int kThreads = 256;  // four waves
+constexpr int kElems = 1024;   // entries per workgroup of the elementwise sign / dual update
+constexpr int kInfoHead = 8;   // info[0..7]: sweeps, frozen, rho, ||T||_F^2, degenerate, reserved; then one objective per sweep
+
+enum Ctrl { kRho = 0, kYfac = 1, kDone = 2, kSweeps = 3, kNormT2 = 4, kFrozen = 5, kDegenerate = 6, kCtrlCount = 8 };
+
+struct PtqArgs {
+    const __half* F[2];  // A_star [N, r0], B_star [M, r0]
+    int64_t n[2];        // N, M
+    int R, r0;
+    int nb[2];           // row blocks per side
+    int ne[2];           // elementwise blocks per side
+    double* X[2];        // continuous iterates U1 [N, R], U2^T [M, R]
+    double* Mm[2];       // their +-1 copies
+    double* Y[2];        // scaled duals
+    double* scale[2];    // alpha [N], gamma [M]
+    double* beta;        // [R]
+    double* part[2];     // per block shares of the Gram pair of each side, [nb, pstride]: S (R*R) then K (R*r0)
+    int pstride;
+    double* Z[2];        // warm start: [r0, R] maps from factor rows to singular-vector entries
+    double* ctrl;        // [kCtrlCount]
+    double* res;         // [(ne0 + ne1), 2]: squared consensus gap and number of sign changes per elementwise block
+    double* info;
+    int K;
+    double tau, mu;
+};
+
+__device__ inline void wave_sync() {
+    // Lanes of one wave exchange data through LDS; the LDS serves a wave's requests in order, so only the compiler has to
+    // be kept from moving accesses across this point.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ inline double group_sum(double v, int gs) {
+    for (int m = gs >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+__device__ inline int group_size_for(int R) { return R <= 16 ? 16 : (R <= 32 ? 32 : 64); }
+
+// In-place Cholesky factor (lower triangle) of the n x n matrix H (leading dimension ld) by the lanes l = 0..gs-1 of one
+// group; lane l owns column l.  Returns false (in every lane) if a pivot is not positive.
+__device__ inline bool group_cholesky(double* H, int ld, int n, int l) {
+    bool ok = true;
+    for (int k = 0; k < n; ++k) {
+        const double hkk = H[k * ld + k];
+        ok = ok && (hkk > 0.0);
+        const double d = sqrt(hkk);
+        if (l > k && l < n) H[l * ld + k] = H[l * ld + k] / d;
+        if (l == k) H[k * ld + k] = d;
+        wave_sync();
+        if (l > k && l < n) {
+            const double ljk = H[l * ld + k];
+            for (int i = l; i < n; ++i) H[i * ld + l] -= H[i * ld + k] * ljk;
+        }
+        wave_sync();
+    }
+    return ok;
+}
+
+// Solves L L^T x = b for the factor left by group_cholesky; lane l passes b_l and receives x_l.  `base` is the first
+// lane of the group within the wave.
+__device__ inline double group_solve(const double* H, int ld, int n, int l, int base, double b) {
+    for (int k = 0; k < n; ++k) {
+        const double yk = __shfl(b, base + k, 64) / H[k * ld + k];
+        if (l == k) b = yk;
+        if (l > k && l < n) b -= H[l * ld + k] * yk;
+    }
+    for (int k = n - 1; k >= 0; --k) {
+        const double xk = __shfl(b, base + k, 64) / H[k * ld + k];
+        if (l == k) b = xk;
+        if (l < k) b -= H[k * ld + l] * xk;
+    }
+    return b;
+}
+
+// dst[o] = sum over blocks of part[b][o], o < count, blocks in ascending order.
+__device__ inline void reduce_shares(const double* part, int nb, int pstride, int count, double* dst) {
+    for (int o = threadIdx.x; o < count; o += kThreads) {
+        double acc = 0.0;
+        for (int b = 0; b < nb; ++b) acc += part[static_cast<int64_t>(b) * pstride + o];
+        dst[o] = acc;
+    }
+}
+
+// This block's share of a side's Gram pair from its rows in LDS: xs [kRows, R], cs [kRows] (0 past the end), fs [kRows, r0].
+__device__ inline void gram_share(const double* xs, const double* cs, const double* fs, int R, int r0, double* out) {
+    const int RR = R * R;
+    for (int o = threadIdx.x; o < RR + R * r0; o += kThreads) {
+        double acc = 0.0;
+        if (o < RR) {
+            const int k = o / R, l = o - k * R;
+            for (int row = 0; row < kRows; ++row) acc += (cs[row] * xs[row * R + k]) * (cs[row] * xs[row * R + l]);
+        } else {
+            const int k = (o - RR) / r0, q = (o - RR) - k * r0;
+            for (int row = 0; row < kRows; ++row) acc += (cs[row] * xs[row * R + k]) * fs[row * r0 + q];
+        }
+        out[o] = acc;
+    }
+}
+
+__device__ inline void load_factor_rows(const __half* F, int64_t n, int r0, int64_t row0, double* fs) {
+    for (int o = threadIdx.x; o < kRows * r0; o += kThreads) {
+        const int64_t row = row0 + o / r0;
+        fs[o] = row < n ? static_cast<double>(__half2float(F[row0 * r0 + o])) : 0.0;
+    }
+}
+
+extern __shared__ double lds[];
+
+// ---- warm start (Eq. (svd-init)) ----------------------------------------------------------------------------------
+
+// Shares of A*^T A* and B*^T B* (the K part of the share is unused here).
+__global__ __launch_bounds__(kThreads) void lordba_ptq_factor_gram_kernel(PtqArgs a) {
+    const int side = static_cast<int>(blockIdx.x) < a.nb[0] ? 0 : 1;
+    const int blk = side == 0 ? blockIdx.x : blockIdx.x - a.nb[0];
+    const int r0 = a.r0;
+    double* fs = lds;
+    load_factor_rows(a.F[side], a.n[side], r0, static_cast<int64_t>(blk) * kRows, fs);
+    __syncthreads();
+    double* out = a.part[side] + static_cast<int64_t>(blk) * a.pstride;
+    for (int o = threadIdx.x; o < r0 * r0; o += kThreads) {
+        const int k = o / r0, l = o - k * r0;
+        double acc = 0.0;
+        for (int row = 0; row < kRows; ++row) acc += fs[row * r0 + k] * fs[row * r0 + l];
+        out[o] = acc;
+    }
+}
+
+// One wave.  With A* = Qa La^T and B* = Qb Lb^T (Cholesky factors of the two Gram matrices), the target is
+// Qa (La^T Lb) Qb^T; a one-sided Jacobi iteration gives the singular value decomposition of the r0 x r0 core, hence the
+// singular values of the target and maps Z1, Z2 with (leading left singular vectors) ~ A* Z1, (right) ~ B* Z2 up to
+// positive column factors, which the signs do not see.
+__global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
+    const int r0 = a.r0, R = a.R, ld = r0 + 1, l = threadIdx.x;
+    double* Ga = lds;
+    double* Gb = Ga + r0 * ld;
+    double* W = Gb + r0 * ld;
+    double* V = W + r0 * ld;
+    double* sig = V + r0 * ld;
+    int* idx = reinterpret_cast<int*>(sig + r0);
+    for (int o = l; o < r0 * r0; o += 64) {
+        double sa = 0.0, sb = 0.0;
+        for (int b = 0; b < a.nb[0]; ++b) sa += a.part[0][static_cast<int64_t>(b) * a.pstride + o];
+        for (int b = 0; b < a.nb[1]; ++b) sb += a.part[1][static_cast<int64_t>(b) * a.pstride + o];
+        Ga[(o / r0) * ld + o % r0] = sa;
+        Gb[(o / r0) * ld + o % r0] = sb;
+    }
+    wave_sync();
+    const bool ok_a = group_cholesky(Ga, ld, r0, l);
+    const bool ok_b = group_cholesky(Gb, ld, r0, l);
+    // core W = La^T Lb, V = I; lane i owns row i of both from here on
+    if (l < r0) {
+        for (int j = 0; j < r0; ++j) {
+            double acc = 0.0;
+            for (int k = (l > j ? l : j); k < r0; ++k) acc += Ga[k * ld + l] * Gb[k * ld + j];
+            W[l * ld + j] = acc;
+            V[l * ld + j] = (l == j) ? 1.0 : 0.0;
+        }
+    }
+    for (int sweep = 0; sweep < 60; ++sweep) {
+        bool rotated = false;
+        for (int p = 0; p + 1 < r0; ++p) {
+            for (int q = p + 1; q < r0; ++q) {
+                const double wp = l < r0 ? W[l * ld + p] : 0.0, wq = l < r0 ? W[l * ld + q] : 0.0;
+                const double app = __shfl(group_sum(wp * wp, 64), 0, 64);
+                const double aqq = __shfl(group_sum(wq * wq, 64), 0, 64);
+                const double apq = __shfl(group_sum(wp * wq, 64), 0, 64);
+                if (fabs(apq) > 1e-15 * sqrt(app * aqq)) {
+                    rotated = true;
+                    const double zeta = (aqq - app) / (2.0 * apq);
+                    const double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+                    const double cs = 1.0 / sqrt(1.0 + t * t), sn = cs * t;
+                    if (l < r0) {
+                        W[l * ld + p] = cs * wp - sn * wq;
+                        W[l * ld + q] = sn * wp + cs * wq;
+                        const double vp = V[l * ld + p], vq = V[l * ld + q];
+                        V[l * ld + p] = cs * vp - sn * vq;
+                        V[l * ld + q] = sn * vp + cs * vq;
+                    }
+                }
+            }
+        }
+        if (!rotated) break;
+    }
+    // singular values = column norms of the rotated core; order them (descending, ties by index)
+    for (int p = 0; p < r0; ++p) {
+        const double wp = l < r0 ? W[l * ld + p] : 0.0;
+        const double s2 = __shfl(group_sum(wp * wp, 64), 0, 64);
+        if (l == 0) sig[p] = sqrt(s2);
+    }
+    wave_sync();
+    if (l == 0) {
+        for (int p = 0; p < r0; ++p) idx[p] = p;
+        for (int p = 0; p < r0; ++p) {
+            int best = p;
+            for (int q = p + 1; q < r0; ++q)
+                if (sig[idx[q]] > sig[idx[best]]) best = q;
+            const int tmp = idx[p];
+            idx[p] = idx[best];
+            idx[best] = tmp;
+        }
+        double norm2 = 0.0;
+        for (int p = 0; p < r0; ++p) norm2 += sig[idx[p]] * sig[idx[p]];
+        const bool good = ok_a && ok_b && norm2 > 0.0 && norm2 < INFINITY;
+        a.ctrl[kRho] = norm2 / (static_cast<double>(a.n[0]) * R + static_cast<double>(a.n[1]) * R);
+        a.ctrl[kYfac] = 1.0;
+        a.ctrl[kDone] = good ? 0.0 : 1.0;
+        a.ctrl[kSweeps] = 0.0;
+        a.ctrl[kNormT2] = norm2;
+        a.ctrl[kFrozen] = 0.0;
+        a.ctrl[kDegenerate] = good ? 0.0 : 1.0;
+        a.ctrl[7] = 0.0;
+    }
+    wave_sync();
+    if (l < R) {
+        const int c = idx[l];
+        a.beta[l] = sig[c];
+        // Z1[:, l] = La^{-T} (rotated core)[:, c], Z2[:, l] = Lb^{-T} V[:, c]: back substitution with the upper factors
+        for (int side = 0; side < 2; ++side) {
+            const double* Lf = side == 0 ? Ga : Gb;
+            const double* src = side == 0 ? W : V;
+            double* z = a.Z[side];
+            for (int i = r0 - 1; i >= 0; --i) {
+                double acc = src[i * ld + c];
+                for (int j = i + 1; j < r0; ++j) acc -= Lf[j * ld + i] * z[j * R + l];
+                z[i * R + l] = acc / Lf[i * ld + i];
+            }
+        }
+    }
+}
+
+// U = M = sign(factor row . Z), Y = 0, scale = 1, and the block's Gram share.
+__global__ __launch_bounds__(kThreads) void lordba_ptq_init_rows_kernel(PtqArgs a) {
+    const int side = static_cast<int>(blockIdx.x) < a.nb[0] ? 0 : 1;
+    const int blk = side == 0 ? blockIdx.x : blockIdx.x - a.nb[0];
+    const int R = a.R, r0 = a.r0;
+    const int64_t n = a.n[side], row0 = static_cast<int64_t>(blk) * kRows;
+    double* fs = lds;
+    double* xs = fs + kRows * r0;
+    double* cs = xs + kRows * R;
+    double* zs = cs + kRows;
+    load_factor_rows(a.F[side], n, r0, row0, fs);
+    for (int o = threadIdx.x; o < r0 * R; o += kThreads) zs[o] = a.Z[side][o];
+    __syncthreads();
+    for (int o = threadIdx.x; o < kRows * R; o += kThreads) {
+        const int row = o / R, k = o - row * R;
+        double acc = 0.0;
+        for (int q = 0; q < r0; ++q) acc += fs[row * r0 + q] * zs[q * R + k];
+        const double s = acc < 0.0 ? -1.0 : 1.0;
+        const bool in = row0 + row < n;
+        xs[o] = in ? s : 0.0;
+        if (in) {
+            const int64_t g = row0 * R + o;
+            a.X[side][g] = s;
+            a.Mm[side][g] = s;
+            a.Y[side][g] = 0.0;
+        }
+    }
+    for (int row = threadIdx.x; row < kRows; row += kThreads) {
+        const bool in = row0 + row < n;
+        cs[row] = in ? 1.0 : 0.0;
+        if (in) a.scale[side][row0 + row] = 1.0;
+    }
+    __syncthreads();
+    gram_share(xs, cs, fs, R, r0, a.part[side] + static_cast<int64_t>(blk) * a.pstride);
+}
+
+// ---- one sweep ----------------------------------------------------------------------------------------------------
+
+// LDS of the two row kernels: So [R*R], Ko [R*r0] (the other side's Gram pair), bs [R], fs, xs, cs, then the per-group
+// matrices of the Tikhonov step.
+struct RowLds {
+    double *So, *Ko, *bs, *fs, *xs, *cs, *H;
+};
+__device__ inline RowLds carve_rows(int R, int r0) {
+    RowLds s;
+    s.So = lds;
+    s.Ko = s.So + R * R;
+    s.bs = s.Ko + R * r0;
+    s.fs = s.bs + R;
+    s.xs = s.fs + kRows * r0;
+    s.cs = s.xs + kRows * R;
+    s.H = s.cs + kRows;
+    return s;
+}
+
+// Eq. (u-step-1) / Eq. (u-step-2) for one side: per row, (c^2 (beta beta^T o So) + rho_k I) u = c beta o (Ko f) + rho_k (M - Y).
+__global__ __launch_bounds__(kThreads) void lordba_ptq_ustep_kernel(PtqArgs a, int side) {
+    if (a.ctrl[kDone] != 0.0) return;
+    const int R = a.R, r0 = a.r0, other = 1 - side, blk = blockIdx.x;
+    const int64_t n = a.n[side], row0 = static_cast<int64_t>(blk) * kRows;
+    const RowLds s = carve_rows(R, r0);
+    reduce_shares(a.part[other], a.nb[other], a.pstride, R * R + R * r0, s.So);  // So and Ko are adjacent
+    for (int k = threadIdx.x; k < R; k += kThreads) s.bs[k] = a.beta[k];
+    load_factor_rows(a.F[side], n, r0, row0, s.fs);
+    for (int row = threadIdx.x; row < kRows; row += kThreads) s.cs[row] = row0 + row < n ? a.scale[side][row0 + row] : 0.0;
+    __syncthreads();
+    const double rho_k = a.ctrl[kRho] / (static_cast<double>(n) * R), yfac = a.ctrl[kYfac];
+    const int gs = group_size_for(R), groups = 64 / gs, ld = R + 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int g = lane / gs, l = lane - g * gs, base = g * gs;
+    double* H = s.H + (wave * groups + g) * R * ld;
+    const int rows_per_pass = 4 * groups;
+    for (int pass = 0; pass < kRows / rows_per_pass; ++pass) {
+        const int row = pass * rows_per_pass + wave * groups + g;
+        const bool in = row0 + row < n;
+        const double c = s.cs[row];
+        double b = 0.0;
+        if (l < R) {
+            double kf = 0.0;
+            for (int q = 0; q < r0; ++q) kf += s.Ko[l * r0 + q] * s.fs[row * r0 + q];
+            double w = 0.0;
+            if (in) {
+                const int64_t gi = (row0 + row) * R + l;
+                w = a.Mm[side][gi] - yfac * a.Y[side][gi];
+            }
+            b = c * s.bs[l] * kf + rho_k * w;
+            for (int k = 0; k < R; ++k) H[k * ld + l] = (c * c) * (s.bs[k] * s.bs[l]) * s.So[k * R + l] + (k == l ? rho_k : 0.0);
+        }
+        wave_sync();
+        group_cholesky(H, ld, R, l);
+        const double x = group_solve(H, ld, R, l, base, b);
+        if (l < R) {
+            s.xs[row * R + l] = in ? x : 0.0;
+            if (in) a.X[side][(row0 + row) * R + l] = x;
+        }
+        wave_sync();
+    }
+    __syncthreads();
+    gram_share(s.xs, s.cs, s.fs, R, r0, a.part[side] + static_cast<int64_t>(blk) * a.pstride);
+}
+
+// Eq. (alpha-update) (side 0) / Eq. (gamma-update) (side 1): per row, with v = u o beta, <T_i, D_i> = v . (Ko f) and
+// ||D_i||^2 = v^T So v; 0 where the denominator is 0.
+__global__ __launch_bounds__(kThreads) void lordba_ptq_scale_kernel(PtqArgs a, int side) {
+    if (a.ctrl[kDone] != 0.0) return;
+    const int R = a.R, r0 = a.r0, other = 1 - side, blk = blockIdx.x;
+    const int64_t n = a.n[side], row0 = static_cast<int64_t>(blk) * kRows;
+    const RowLds s = carve_rows(R, r0);
+    reduce_shares(a.part[other], a.nb[other], a.pstride, R * R + R * r0, s.So);
+    for (int k = threadIdx.x; k < R; k += kThreads) s.bs[k] = a.beta[k];
+    load_factor_rows(a.F[side], n, r0, row0, s.fs);
+    for (int o = threadIdx.x; o < kRows * R; o += kThreads) s.xs[o] = row0 + o / R < n ? a.X[side][row0 * R + o] : 0.0;
+    __syncthreads();
+    const int gs = group_size_for(R), groups = 64 / gs;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int g = lane / gs, l = lane - g * gs;
+    const int rows_per_pass = 4 * groups;
+    for (int pass = 0; pass < kRows / rows_per_pass; ++pass) {
+        const int row = pass * rows_per_pass + wave * groups + g;
+        double num = 0.0, den = 0.0;
+        if (l < R) {
+            const double v = s.xs[row * R + l] * s.bs[l];
+            double kf = 0.0;
+            for (int q = 0; q < r0; ++q) kf += s.Ko[l * r0 + q] * s.fs[row * r0 + q];
+            double sv = 0.0;
+            for (int m = 0; m < R; ++m) sv += s.So[l * R + m] * (s.xs[row * R + m] * s.bs[m]);
+            num = v * kf;
+            den = v * sv;
+        }
+        num = group_sum(num, gs);
+        den = group_sum(den, gs);
+        const double c = den > 0.0 ? num / den : 0.0;
+        const bool in = row0 + row < n;
+        if (l == 0) {
+            s.cs[row] = in ? c : 0.0;
+            if (in) a.scale[side][row0 + row] = c;
+        }
+    }
+    __syncthreads();
+    gram_share(s.xs, s.cs, s.fs, R, r0, a.part[side] + static_cast<int64_t>(blk) * a.pstride);
+}
+
+// Eq. (beta-gram), Eq. (beta-Schur), Eq. (beta-pinv): G = S1 o S2, h_k = K1[k, :] . K2[k, :], beta = pinv(G) h by a
+// Cholesky factorisation with diagonal pivoting that stops at the numerical rank (for a positive semidefinite G = L L^T
+// with L of full column rank, pinv(G) = L (L^T L)^{-2} L^T; at full rank this is the ordinary solve, which is what runs
+// then).  Also the objective of Eq. (admm-problem) at the continuous iterates, from the same Gram pairs:
+// f = (||T||_F^2 - 2 beta.h + beta^T G beta) / 2.
+__global__ __launch_bounds__(kThreads) void lordba_ptq_beta_kernel(PtqArgs a, int t) {
+    if (a.ctrl[kDone] != 0.0) return;
+    const int R = a.R, r0 = a.r0, ld = R + 1, count = R * R + R * r0;
+    double* P1 = lds;          // S1, K1
+    double* P2 = P1 + count;   // S2, K2
+    double* G = P2 + count;    // [R, ld]
+    double* N2 = G + R * ld;   // [R, ld]
+    double* hv = N2 + R * ld;  // [R] permuted right-hand side
+    double* h0 = hv + R;       // [R]
+    double* bt = h0 + R;       // [R] result
+    int* perm = reinterpret_cast<int*>(bt + R);
+    reduce_shares(a.part[0], a.nb[0], a.pstride, count, P1);
+    reduce_shares(a.part[1], a.nb[1], a.pstride, count, P2);
+    __syncthreads();
+    for (int o = threadIdx.x; o < R * R; o += kThreads) G[(o / R) * ld + o % R] = P1[o] * P2[o];
+    for (int k = threadIdx.x; k < R; k += kThreads) {
+        double acc = 0.0;
+        for (int q = 0; q < r0; ++q) acc += P1[R * R + k * r0 + q] * P2[R * R + k * r0 + q];
+        hv[k] = acc;
+        h0[k] = acc;
+        perm[k] = k;
+    }
+    __syncthreads();
+    if (threadIdx.x >= 64) return;
+    const int l = threadIdx.x;
+    double dmax = (l < R) ? G[l * ld + l] : 0.0;
+    for (int m = 32; m >= 1; m >>= 1) dmax = fmax(dmax, __shfl_xor(dmax, m, 64));
+    const double tol = 64.0 * 2.220446049250313e-16 * dmax;
+    int rank = 0;
+    for (int k = 0; k < R; ++k) {
+        // largest remaining diagonal entry, ties to the smallest index
+        double best = (l >= k && l < R) ? G[l * ld + l] : -1.0;
+        int arg = l;
+        for (int m = 32; m >= 1; m >>= 1) {
+            const double ob = __shfl_xor(best, m, 64);
+            const int oa = __shfl_xor(arg, m, 64);
+            if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+        }
+        best = __shfl(best, 0, 64);
+        arg = __shfl(arg, 0, 64);
+        if (!(best > tol)) break;
+        if (arg != k) {
+            if (l < R) { const double u = G[k * ld + l]; G[k * ld + l] = G[arg * ld + l]; G[arg * ld + l] = u; }
+            wave_sync();
+            if (l < R) { const double u = G[l * ld + k]; G[l * ld + k] = G[l * ld + arg]; G[l * ld + arg] = u; }
+            if (l == 0) {
+                const int pi = perm[k]; perm[k] = perm[arg]; perm[arg] = pi;
+                const double u = hv[k]; hv[k] = hv[arg]; hv[arg] = u;
+            }
+            wave_sync();
+        }
+        const double d = sqrt(G[k * ld + k]);
+        if (l > k && l < R) G[l * ld + k] = G[l * ld + k] / d;
+        if (l == k) G[k * ld + k] = d;
+        wave_sync();
+        if (l > k && l < R) {
+            const double ljk = G[l * ld + k];
+            for (int i = k + 1; i < R; ++i) G[i * ld + l] -= G[i * ld + k] * ljk;  // both triangles are kept up to date
+        }
+        wave_sync();
+        rank = k + 1;
+    }
+    double x = 0.0;
+    if (rank == R) {
+        x = group_solve(G, ld, R, l, 0, l < R ? hv[l] : 0.0);
+    } else if (rank > 0) {
+        double y = 0.0;
+        if (l < rank) {
+            for (int i = l; i < R; ++i) y += G[i * ld + l] * hv[i];
+            for (int r = 0; r < rank; ++r) {
+                double acc = 0.0;
+                for (int i = (r > l ? r : l); i < R; ++i) acc += G[i * ld + r] * G[i * ld + l];
+                N2[r * ld + l] = acc;
+            }
+        }
+        wave_sync();
+        group_cholesky(N2, ld, rank, l);
+        const double z = group_solve(N2, ld, rank, l, 0, y);
+        const double w = group_solve(N2, ld, rank, l, 0, z);
+        for (int c = 0; c < rank; ++c) {
+            const double wc = __shfl(w, c, 64);
+            if (l < R && c <= l) x += G[l * ld + c] * wc;
+        }
+    }
+    if (l < R) bt[perm[l]] = x;
+    wave_sync();
+    double lin = 0.0, quad = 0.0;
+    if (l < R) {
+        const double bl = bt[l];
+        a.beta[l] = bl;
+        lin = bl * h0[l];
+        for (int m = 0; m < R; ++m) quad += bl * bt[m] * (P1[l * R + m] * P2[l * R + m]);
+    }
+    lin = group_sum(lin, 64);
+    quad = group_sum(quad, 64);
+    if (l == 0) a.info[kInfoHead + t] = 0.5 * (a.ctrl[kNormT2] - 2.0 * lin + quad);
+}
+
+// Eq. (m-y-step) for both sides: M = sign(U + Y), Y += U - M; per block the squared consensus gap and the number of
+// entries of M that changed.  A pending rescaling of Y (after a penalty change) is applied here.
+__global__ __launch_bounds__(kThreads) void lordba_ptq_sign_dual_kernel(PtqArgs a) {
+    if (a.ctrl[kDone] != 0.0) return;
+    const int side = static_cast<int>(blockIdx.x) < a.ne[0] ? 0 : 1;
+    const int blk = side == 0 ? blockIdx.x : blockIdx.x - a.ne[0];
+    const int64_t total = a.n[side] * a.R;
+    const double yfac = a.ctrl[kYfac];
+    double gap = 0.0, flips = 0.0;
+    for (int e = 0; e < kElems / kThreads; ++e) {
+        const int64_t i = static_cast<int64_t>(blk) * kElems + e * kThreads + threadIdx.x;
+        if (i < total) {
+            const double u = a.X[side][i], y = yfac * a.Y[side][i], mo = a.Mm[side][i];
+            const double mn = (u + y) < 0.0 ? -1.0 : 1.0;
+            a.Y[side][i] = y + u - mn;
+            a.Mm[side][i] = mn;
+            gap += (u - mn) * (u - mn);
+            flips += (mn != mo) ? 1.0 : 0.0;
+        }
+    }
+    gap = group_sum(gap, 64);
+    flips = group_sum(flips, 64);
+    double* red = lds;
+    if ((threadIdx.x & 63) == 0) { red[2 * (threadIdx.x >> 6)] = gap; red[2 * (threadIdx.x >> 6) + 1] = flips; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a.res[2 * blockIdx.x] = (red[0] + red[2]) + (red[4] + red[6]);
+        a.res[2 * blockIdx.x + 1] = (red[1] + red[3]) + (red[5] + red[7]);
+    }
+}
+
+// Residual balancing of the penalty (first half of the run) and the end of the loop.
+__global__ __launch_bounds__(64) void lordba_ptq_control_kernel(PtqArgs a, int t) {
+    if (a.ctrl[kDone] != 0.0) return;
+    const int l = threadIdx.x;
+    double gap = 0.0, f0 = 0.0, f1 = 0.0;
+    for (int b = l; b < a.ne[0] + a.ne[1]; b += 64) {
+        gap += a.res[2 * b];
+        if (b < a.ne[0]) f0 += a.res[2 * b + 1]; else f1 += a.res[2 * b + 1];
+    }
+    gap = group_sum(gap, 64);
+    f0 = group_sum(f0, 64);
+    f1 = group_sum(f1, 64);
+    if (l != 0) return;
+    double rho = a.ctrl[kRho], yfac = 1.0;
+    if (2 * static_cast<int64_t>(t) < a.K) {
+        const double rho0 = rho / (static_cast<double>(a.n[0]) * a.R), rho1 = rho / (static_cast<double>(a.n[1]) * a.R);
+        const double r = sqrt(gap), s = sqrt(rho0 * rho0 * 4.0 * f0 + rho1 * rho1 * 4.0 * f1);
+        if (r > a.mu * s) { rho *= a.tau; yfac = 1.0 / a.tau; }
+        else if (s > a.mu * r) { rho /= a.tau; yfac = a.tau; }
+    }
+    a.ctrl[kRho] = rho;
+    a.ctrl[kYfac] = yfac;
+    a.ctrl[kSweeps] = t + 1;
+    if (f0 + f1 == 0.0) { a.ctrl[kFrozen] = 1.0; a.ctrl[kDone] = 1.0; }
+}
+
+// ---- export -------------------------------------------------------------------------------------------------------
+
+struct ExportArgs {
+    uint32_t* packedA;  // S_A = B1^T [R, N]
+    uint32_t* packedB;  // S_B = B2^T [M, R]
+    __half *s_in, *s_rank, *s_out;
+    int64_t wordsA, wordsB;
+};
+
+// fp64 -> fp16, round to nearest even in one rounding: through an fp32 value rounded to odd (truncate, then set the last
+// bit if anything was lost), which the final rounding to the 11-bit significand cannot tell from the exact value.
+__device__ inline __half half_from_double(double x) {
+    float f = static_cast<float>(x);
+    if (static_cast<double>(f) != x && x == x && fabsf(f) < INFINITY) {
+        uint32_t u = __float_as_uint(f);
+        if (fabs(static_cast<double>(f)) > fabs(x)) u -= 1;  // step towards zero: the truncated value
+        f = __uint_as_float(u | 1u);
+    }
+    return __float2half_rn(f);
+}
+
+__global__ __launch_bounds__(kThreads) void lordba_ptq_export_kernel(PtqArgs a, ExportArgs e) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const int64_t N = a.n[0], M = a.n[1];
+    const int R = a.R;
+    if (i < e.wordsA) {
+        uint32_t w = 0;
+        for (int bit = 0; bit < 32; ++bit) {
+            const int64_t nbit = i * 32 + bit;
+            if (nbit < N * R) {
+                const int64_t k = nbit / N, row = nbit - k * N;
+                if (a.Mm[0][row * R + k] < 0.0) w |= 1u << bit;
+            }
+        }
+        e.packedA[i] = w;
+    }
+    if (i < e.wordsB) {
+        uint32_t w = 0;
+        for (int bit = 0; bit < 32; ++bit) {
+            const int64_t nbit = i * 32 + bit;
+            if (nbit < M * R && a.Mm[1][nbit] < 0.0) w |= 1u << bit;
+        }
+        e.packedB[i] = w;
+    }
+    if (e.s_in && i < N) e.s_in[i] = half_from_double(a.scale[0][i]);
+    if (e.s_out && i < M) e.s_out[i] = half_from_double(a.scale[1][i]);
+    if (e.s_rank && i < R) e.s_rank[i] = half_from_double(a.beta[i]);
+    if (i < kCtrlCount) {
+        const int map[kCtrlCount] = {kSweeps, kFrozen, kRho, kNormT2, kDegenerate, 7, 7, 7};
+        a.info[i] = i < 5 ? a.ctrl[map[i]] : 0.0;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void lordba_ptq_fill_kernel(double* p, int64_t n, double v) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+struct Layout {
+    size_t x[2], m[2], y[2], part[2], z[2], ctrl, res, total;
+    int nb[2], ne[2], pstride;
+};
+
+Layout make_layout(int64_t N, int64_t M, int64_t R, int64_t r0) {
+    Layout L;
+    const int64_t n[2] = {N, M};
+    size_t off = 0;
+    auto take = [&](size_t doubles) { const size_t at = off; off += (doubles + 31) / 32 * 32; return at; };
+    for (int s = 0; s < 2; ++s) {
+        L.nb[s] = static_cast<int>((n[s] + kRows - 1) / kRows);
+        L.ne[s] = static_cast<int>((n[s] * R + kElems - 1) / kElems);
+    }
+    const int64_t pair = R * R + R * r0, sq = r0 * r0;
+    L.pstride = static_cast<int>(((pair > sq ? pair : sq) + 31) / 32 * 32);
+    for (int s = 0; s < 2; ++s) L.x[s] = take(n[s] * R);   // the iterates come first: U1 [N, R], then U2^T [M, R]
+    for (int s = 0; s < 2; ++s) L.m[s] = take(n[s] * R);
+    for (int s = 0; s < 2; ++s) L.y[s] = take(n[s] * R);
+    for (int s = 0; s < 2; ++s) L.part[s] = take(static_cast<size_t>(L.nb[s]) * L.pstride);
+    for (int s = 0; s < 2; ++s) L.z[s] = take(r0 * R);
+    L.ctrl = take(kCtrlCount);
+    L.res = take(2 * static_cast<size_t>(L.ne[0] + L.ne[1]));
+    L.total = off * sizeof(double);
+    return L;
+}
+
+bool dims_ok(int64_t N, int64_t M, int64_t R, int64_t r0, int64_t K) {
+    return N >= 1 && M >= 1 && N <= (1 << 22) && M <= (1 << 22) && R >= 1 && R <= LORDBA_PTQ_MAX_RANK && r0 >= R &&
+           r0 <= LORDBA_PTQ_MAX_FACTOR_RANK && K >= 1 && K <= LORDBA_PTQ_MAX_SWEEPS;
+}
+
+}  // namespace
+
+extern "C" size_t lordba_ptq_workspace_bytes(int64_t N, int64_t M, int64_t R, int64_t r0) {
+    if (!dims_ok(N, M, R, r0, 1)) return 0;
+    return make_layout(N, M, R, r0).total;
+}
+
+extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint32_t* packedA, uint32_t* packedB,
+                                    double* alpha, double* beta, double* gamma, void* s_in, void* s_rank, void* s_out,
+                                    double* info, void* workspace, size_t workspace_bytes, int64_t N, int64_t M, int64_t R,
+                                    int64_t r0, int64_t K, double tau, double mu, void* stream_) {
+    if (!dims_ok(N, M, R, r0, K)) return LORDBA_ERR_DIM;
+    if (!(tau > 1.0) || !(mu > 0.0) || !(tau < 1e6) || !(mu < 1e12)) return LORDBA_ERR_VALUE;
+    if (!A_star || !B_star || !packedA || !packedB || !alpha || !beta || !gamma || !info || !workspace) return LORDBA_ERR_NULL;
+    const uintptr_t p16 = reinterpret_cast<uintptr_t>(A_star) | reinterpret_cast<uintptr_t>(B_star) |
+                          reinterpret_cast<uintptr_t>(s_in) | reinterpret_cast<uintptr_t>(s_rank) | reinterpret_cast<uintptr_t>(s_out);
+    const uintptr_t p32 = reinterpret_cast<uintptr_t>(packedA) | reinterpret_cast<uintptr_t>(packedB);
+    const uintptr_t p64 = reinterpret_cast<uintptr_t>(alpha) | reinterpret_cast<uintptr_t>(beta) | reinterpret_cast<uintptr_t>(gamma) |
+                          reinterpret_cast<uintptr_t>(info) | reinterpret_cast<uintptr_t>(workspace);
+    if ((p16 & 1) || (p32 & 3) || (p64 & 7)) return LORDBA_ERR_ALIGN;
+    const Layout L = make_layout(N, M, R, r0);
+    if (workspace_bytes < L.total) return LORDBA_ERR_WORKSPACE;
+    const size_t wordsA = lordba_packed_words(R, N), wordsB = lordba_packed_words(M, R);
+    {   // no output may overlap an input, another output or the workspace
+        struct Span { uintptr_t p; size_t n; };
+        const Span spans[] = {
+            {reinterpret_cast<uintptr_t>(A_star), static_cast<size_t>(N * r0) * 2}, {reinterpret_cast<uintptr_t>(B_star), static_cast<size_t>(M * r0) * 2},
+            {reinterpret_cast<uintptr_t>(packedA), wordsA * 4}, {reinterpret_cast<uintptr_t>(packedB), wordsB * 4},
+            {reinterpret_cast<uintptr_t>(alpha), static_cast<size_t>(N) * 8}, {reinterpret_cast<uintptr_t>(beta), static_cast<size_t>(R) * 8},
+            {reinterpret_cast<uintptr_t>(gamma), static_cast<size_t>(M) * 8}, {reinterpret_cast<uintptr_t>(s_in), static_cast<size_t>(N) * 2},
+            {reinterpret_cast<uintptr_t>(s_rank), static_cast<size_t>(R) * 2}, {reinterpret_cast<uintptr_t>(s_out), static_cast<size_t>(M) * 2},
+            {reinterpret_cast<uintptr_t>(info), static_cast<size_t>(kInfoHead + K) * 8}, {reinterpret_cast<uintptr_t>(workspace), L.total}};
+        const int ns = static_cast<int>(sizeof(spans) / sizeof(spans[0]));
+        for (int i = 2; i < ns; ++i)
+            for (int j = 0; j < i; ++j)
+                if (spans[i].p && spans[j].p && spans[i].p < spans[j].p + spans[j].n && spans[j].p < spans[i].p + spans[i].n)
+                    return LORDBA_ERR_ALIAS;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return LORDBA_ERR_NO_DEVICE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    double* ws = static_cast<double*>(workspace);
+    PtqArgs a;
+    a.F[0] = static_cast<const __half*>(A_star);
+    a.F[1] = static_cast<const __half*>(B_star);
+    a.n[0] = N;
+    a.n[1] = M;
+    a.R = static_cast<int>(R);
+    a.r0 = static_cast<int>(r0);
+    for (int s = 0; s < 2; ++s) {
+        a.nb[s] = L.nb[s];
+        a.ne[s] = L.ne[s];
+        a.X[s] = ws + L.x[s];
+        a.Mm[s] = ws + L.m[s];
+        a.Y[s] = ws + L.y[s];
+        a.part[s] = ws + L.part[s];
+        a.Z[s] = ws + L.z[s];
+    }
+    a.scale[0] = alpha;
+    a.scale[1] = gamma;
+    a.beta = beta;
+    a.pstride = L.pstride;
+    a.ctrl = ws + L.ctrl;
+    a.res = ws + L.res;
+    a.info = info;
+    a.K = static_cast<int>(K);
+    a.tau = tau;
+    a.mu = mu;
+
+    const int iR = a.R, ir0 = a.r0, ld0 = ir0 + 1, ldR = iR + 1;
+    const size_t lds_gram = sizeof(double) * kRows * ir0;
+    const size_t lds_svd = sizeof(double) * (4 * ir0 * ld0 + ir0) + sizeof(int) * ir0;
+    const size_t lds_init = sizeof(double) * (kRows * ir0 + kRows * iR + kRows + ir0 * iR);
+    const int gs = iR <= 16 ? 16 : 32;
+    const size_t lds_rows = sizeof(double) * (iR * iR + iR * ir0 + iR + kRows * ir0 + kRows * iR + kRows + 4 * (64 / gs) * iR * ldR);
+    const size_t lds_beta = sizeof(double) * (2 * (iR * iR + iR * ir0) + 2 * iR * ldR + 3 * iR) + sizeof(int) * iR;
+    const size_t lds_sign = sizeof(double) * 8;
+    const int nb01 = a.nb[0] + a.nb[1];
+
+    {   // more than 64 KiB of LDS per workgroup has to be asked for
+        const struct { const void* fn; size_t bytes; } big[] = {
+            {reinterpret_cast<const void*>(lordba_ptq_factor_gram_kernel), lds_gram}, {reinterpret_cast<const void*>(lordba_ptq_svd_kernel), lds_svd},
+            {reinterpret_cast<const void*>(lordba_ptq_init_rows_kernel), lds_init}, {reinterpret_cast<const void*>(lordba_ptq_ustep_kernel), lds_rows},
+            {reinterpret_cast<const void*>(lordba_ptq_scale_kernel), lds_rows}, {reinterpret_cast<const void*>(lordba_ptq_beta_kernel), lds_beta}};
+        for (const auto& b : big) {
+            if (b.bytes > 160 * 1024) return LORDBA_ERR_DIM;
+            if (b.bytes > 48 * 1024 &&
+                hipFuncSetAttribute(b.fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(b.bytes)) != hipSuccess)
+                return LORDBA_ERR_LAUNCH;
+        }
+    }
+    hipLaunchKernelGGL(lordba_ptq_fill_kernel, dim3((kInfoHead + K + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, info,
+                       kInfoHead + K, 0.0);
+    hipLaunchKernelGGL(lordba_ptq_factor_gram_kernel, dim3(nb01), dim3(kThreads), lds_gram, stream, a);
+    hipLaunchKernelGGL(lordba_ptq_svd_kernel, dim3(1), dim3(64), lds_svd, stream, a);
+    hipLaunchKernelGGL(lordba_ptq_init_rows_kernel, dim3(nb01), dim3(kThreads), lds_init, stream, a);
+    hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kThreads), lds_rows, stream, a, 0);
+    hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kThreads), lds_rows, stream, a, 1);
+    for (int t = 0; t < a.K; ++t) {
+        hipLaunchKernelGGL(lordba_ptq_ustep_kernel, dim3(a.nb[0]), dim3(kThreads), lds_rows, stream, a, 0);
+        hipLaunchKernelGGL(lordba_ptq_ustep_kernel, dim3(a.nb[1]), dim3(kThreads), lds_rows, stream, a, 1);
+        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kThreads), lds_rows, stream, a, 0);
+        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kThreads), lds_rows, stream, a, 1);
+        hipLaunchKernelGGL(lordba_ptq_beta_kernel, dim3(1), dim3(kThreads), lds_beta, stream, a, t);
+        hipLaunchKernelGGL(lordba_ptq_sign_dual_kernel, dim3(a.ne[0] + a.ne[1]), dim3(kThreads), lds_sign, stream, a);
+        hipLaunchKernelGGL(lordba_ptq_control_kernel, dim3(1), dim3(64), 0, stream, a, t);
+    }
+    ExportArgs e;
+    e.packedA = packedA;
+    e.packedB = packedB;
+    e.s_in = static_cast<__half*>(s_in);
+    e.s_rank = static_cast<__half*>(s_rank);
+    e.s_out = static_cast<__half*>(s_out);
+    e.wordsA = static_cast<int64_t>(wordsA);
+    e.wordsB = static_cast<int64_t>(wordsB);
+    int64_t most = static_cast<int64_t>(wordsA > wordsB ? wordsA : wordsB);
+    if (N > most) most = N;
+    if (M > most) most = M;
+    if (most < kCtrlCount) most = kCtrlCount;
+    hipLaunchKernelGGL(lordba_ptq_export_kernel, dim3(static_cast<unsigned>((most + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, a, e);
+    return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
+}

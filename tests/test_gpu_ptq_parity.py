@@ -1,0 +1,224 @@
+"""GPU parity of post-training quantisation (appendix on PTQ-LoRDBA; Alg. PTQ-LoRDBA): lordba_ptq through the C ABI
+against the fp64 numpy oracle (oracle/ptq.py) on the same seeded factors.
+
+The method decides integers (the sign matrices, the number of sweeps, the power of tau in the penalty) from fp64
+arithmetic; both sides take those decisions in fp64, and they must agree exactly: the sign matrices bit for bit (after
+fixing the one freedom the method leaves, the common sign of each pair (column k of B1, row k of B2), inherited from the
+singular vectors of the warm start), the sweep count, the end flag.  The real-valued results differ only by summation
+order and by the route through the linear algebra (the device never forms the N x M target): scales and continuous
+iterates within 1e-8 relative L2, the objective within 1e-10 of ||Delta W*||_F^2 (it is a difference of numbers of that
+size)."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import ptq as P
+from paper_2605_24058_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL_REAL = 1e-8
+TOL_OBJ = 1e-10
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load_library()
+    return torch
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_gpu(torch, d, R, K=100, tau=2.0, mu=10.0):
+    A = torch.from_numpy(d["A_star"]).cuda()
+    B = torch.from_numpy(d["B_star"]).cuda()
+    out = binding.lordba_ptq(A, B, R, K=K, tau=tau, mu=mu)
+    torch.cuda.synchronize()
+    N, M = A.shape[0], B.shape[0]
+    res = {k: v.cpu().numpy() for k, v in out.items() if k != "workspace"}
+    sA, sB = binding.lordba_unpack_signs(res["packedA"].view(np.uint32), res["packedB"].view(np.uint32), N, M, R)
+    res["B1"] = sA.T.astype(np.float64)          # S_A = B1^T [R, N]
+    res["B2"] = sB.T.astype(np.float64)          # S_B = B2^T [M, R]
+    assert np.array_equal(A.cpu().numpy(), d["A_star"]) and np.array_equal(B.cpu().numpy(), d["B_star"])
+    return res
+
+
+def rel(a, b):
+    return np.linalg.norm(np.ravel(a) - np.ravel(b)) / max(np.linalg.norm(np.ravel(b)), 1e-300)
+
+
+def compare(res, ref, K, check_iterates=True):
+    info = res["info"]
+    assert info[4] == 0.0
+    assert int(info[0]) == ref["sweeps"], (info[0], ref["sweeps"])
+    assert bool(info[1]) == ref["frozen"]
+    assert abs(info[2] - ref["rho"]) <= 1e-12 * ref["rho"]
+    g1, g2, fg = P.canonical_gauge(res["B1"], res["B2"])
+    r1, r2, fr = P.canonical_gauge(ref["B1"], ref["B2"])
+    assert np.array_equal(g1, r1), "B1 differs in %d entries" % int((g1 != r1).sum())
+    assert np.array_equal(g2, r2), "B2 differs in %d entries" % int((g2 != r2).sum())
+    for name in ("alpha", "beta", "gamma"):
+        assert rel(res[name], ref[name]) <= TOL_REAL, (name, rel(res[name], ref[name]))
+    n = ref["sweeps"]
+    assert np.max(np.abs(info[8:8 + n] - ref["objective"])) <= TOL_OBJ * info[3]
+    assert np.all(info[8 + n:] == 0.0)
+    if check_iterates:
+        assert rel(res["U1"] * fg[None, :], ref["U1"] * fr[None, :]) <= TOL_REAL
+        assert rel(res["U2t"] * fg[None, :], ref["U2"].T * fr[None, :]) <= TOL_REAL
+    # the fp16 scales are the fp64 ones rounded to nearest (one rounding)
+    for h, f in (("s_in", "alpha"), ("s_rank", "beta"), ("s_out", "gamma")):
+        assert np.array_equal(res[h], res[f].astype(np.float16))
+
+
+SHAPES = [
+    # seed, N, M, R, r0
+    (0, 64, 48, 4, 8),
+    (1, 200, 136, 8, 8),
+    (2, 130, 257, 16, 16),       # ragged row blocks on both sides
+    (3, 96, 80, 5, 7),           # odd ranks
+    (4, 70, 500, 1, 3),          # one rank-one term
+    (5, 320, 192, 32, 40),       # the largest carrier rank, 32 lanes per row
+    (6, 512, 512, 16, 16),
+    (7, 33, 40, 24, 24),         # fewer rows than one block
+    (8, 640, 384, 8, 64),        # the largest factor rank
+]
+
+
+@pytest.mark.parametrize("seed,N,M,R,r0", SHAPES)
+def test_full_run_matches_oracle(torch_cuda, seed, N, M, R, r0):
+    say("ptq full run seed=%d N=%d M=%d R=%d r0=%d" % (seed, N, M, R, r0))
+    d = inputs.make_ptq_inputs(seed, N, M, r0)
+    K = 100
+    ref = P.ptq(d["A_star"], d["B_star"], R, K=K)
+    res = run_gpu(torch_cuda, d, R, K=K)
+    compare(res, ref, K)
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 7])
+def test_first_sweeps_match_oracle(torch_cuda, K):
+    # a run of K sweeps (its penalty window is the first half of those K) pins every update of the early sweeps
+    say("ptq first sweeps K=%d" % K)
+    d = inputs.make_ptq_inputs(11, 150, 210, 16)
+    ref = P.ptq(d["A_star"], d["B_star"], 12, K=K)
+    res = run_gpu(torch_cuda, d, 12, K=K)
+    compare(res, ref, K)
+
+
+@pytest.mark.parametrize("tau,mu", [(2.0, 10.0), (1.5, 3.0), (4.0, 1.0)])
+def test_other_balancing_constants(torch_cuda, tau, mu):
+    say("ptq balancing tau=%g mu=%g" % (tau, mu))
+    d = inputs.make_ptq_inputs(12, 160, 128, 8)
+    ref = P.ptq(d["A_star"], d["B_star"], 8, K=40, tau=tau, mu=mu)
+    res = run_gpu(torch_cuda, d, 8, K=40, tau=tau, mu=mu)
+    compare(res, ref, 40)
+
+
+def test_flat_spectrum_and_large_entries(torch_cuda):
+    # no decay of the factor columns (close singular values) and entries near the top of the fp16 range of a weight update
+    say("ptq flat spectrum")
+    d = inputs.make_ptq_inputs(13, 256, 192, 8, decay=1.0)
+    d["A_star"] = (d["A_star"].astype(np.float32) * 40).astype(np.float16)
+    ref = P.ptq(d["A_star"], d["B_star"], 6, K=60)
+    res = run_gpu(torch_cuda, d, 6, K=60)
+    compare(res, ref, 60)
+
+
+def test_rank_one_target_is_fitted_exactly_and_ends_after_one_sweep(torch_cuda):
+    say("ptq rank one")
+    d = inputs.make_ptq_inputs(14, 90, 70, 1)
+    res = run_gpu(torch_cuda, d, 1, K=10)
+    assert int(res["info"][0]) == 1 and res["info"][1] == 1.0
+    T = d["A_star"].astype(np.float64) @ d["B_star"].astype(np.float64).T
+    W = P.adapter_matrix(res["alpha"], res["B1"], res["beta"], res["B2"], res["gamma"])
+    assert np.sum((T - W) ** 2) <= 1e-20 * np.sum(T * T)
+
+
+def test_exported_adapter_runs_in_the_forward_kernel(torch_cuda):
+    # the packed carriers and fp16 scales go straight into lordba_forward: y = x DeltaW(theta) with d_in = N, d_out = M
+    say("ptq export -> forward")
+    torch = torch_cuda
+    N, M, R = 256, 192, 8
+    d = inputs.make_ptq_inputs(15, N, M, 8)
+    A, B = torch.from_numpy(d["A_star"]).cuda(), torch.from_numpy(d["B_star"]).cuda()
+    out = binding.lordba_ptq(A, B, R, K=30)
+    act = inputs.make_activations(15, 40, N, M)
+    x, yb = torch.from_numpy(act["x"]).cuda(), torch.zeros(40, M, dtype=torch.float16, device="cuda:0")
+    y = binding.lordba_forward(x, out["packedA"], out["packedB"], out["s_in"], out["s_rank"], out["s_out"], yb)
+    torch.cuda.synchronize()
+    sA, sB = binding.lordba_unpack_signs(out["packedA"].cpu().numpy().view(np.uint32), out["packedB"].cpu().numpy().view(np.uint32), N, M, R)
+    want = oracle.forward(act["x"], sA, sB, out["s_in"].cpu().numpy(), out["s_rank"].cpu().numpy(), out["s_out"].cpu().numpy(),
+                          np.zeros((40, M), dtype=np.float16))
+    got = y.cpu().numpy().astype(np.float64)
+    err = np.linalg.norm(got - want, axis=1) / np.maximum(np.linalg.norm(want, axis=1), 1e-30)
+    assert err.max() <= 1e-3
+    # and the adapter it describes is the fitted one: relative error of the fit below that of a zero adapter
+    T = d["A_star"].astype(np.float64) @ d["B_star"].astype(np.float64).T
+    W = P.adapter_matrix(out["alpha"].cpu().numpy(), sA.T.astype(np.float64), out["beta"].cpu().numpy(), sB.T.astype(np.float64),
+                         out["gamma"].cpu().numpy())
+    assert np.sum((T - W) ** 2) < 0.8 * np.sum(T * T)
+
+
+def test_calls_are_reproducible_and_reuse_a_workspace(torch_cuda):
+    say("ptq reproducible")
+    torch = torch_cuda
+    d = inputs.make_ptq_inputs(16, 300, 260, 16)
+    A, B = torch.from_numpy(d["A_star"]).cuda(), torch.from_numpy(d["B_star"]).cuda()
+    ws = torch.full((binding.lordba_ptq_workspace_bytes(300, 260, 16, 16) // 8,), float("nan"), dtype=torch.float64, device="cuda:0")
+    a = binding.lordba_ptq(A, B, 16, K=50, workspace=ws)
+    torch.cuda.synchronize()
+    first = {k: v.clone() for k, v in a.items() if k != "workspace"}
+    # a smaller problem in the same workspace, then the first one again
+    d2 = inputs.make_ptq_inputs(17, 100, 90, 8)
+    binding.lordba_ptq(torch.from_numpy(d2["A_star"]).cuda(), torch.from_numpy(d2["B_star"]).cuda(), 4, K=20, workspace=ws)
+    b = binding.lordba_ptq(A, B, 16, K=50, workspace=ws)
+    torch.cuda.synchronize()
+    for k in first:
+        assert torch.equal(first[k], b[k]) or (first[k].dtype.is_floating_point and
+                                               torch.equal(torch.nan_to_num(first[k]), torch.nan_to_num(b[k]))), k
+
+
+def test_degenerate_input_is_flagged(torch_cuda):
+    say("ptq degenerate")
+    torch = torch_cuda
+    A = torch.zeros(64, 4, dtype=torch.float16, device="cuda:0")
+    B = torch.ones(48, 4, dtype=torch.float16, device="cuda:0")
+    out = binding.lordba_ptq(A, B, 2, K=5)
+    torch.cuda.synchronize()
+    info = out["info"].cpu().numpy()
+    assert info[4] == 1.0 and info[0] == 0.0
+
+
+def test_full_size_properties(torch_cuda):
+    """The benchmark's shape (4096 x 4096, R = r0 = 16, K = 100), where the oracle takes minutes: what can be checked
+    from the outputs alone, with the dense target formed on the host.  Every scale is the least-squares optimum for the
+    returned continuous iterates in turn (beta last, so beta's normal equations hold exactly; alpha's and gamma's held
+    before beta moved), the reported objective is the dense one, and the sign matrices are those of the iterates."""
+    say("ptq full size 4096x4096 R=16")
+    torch = torch_cuda
+    N = M = 4096
+    R = r0 = 16
+    d = inputs.make_ptq_inputs(18, N, M, r0)
+    res = run_gpu(torch, d, R, K=100)
+    info = res["info"]
+    n = int(info[0])
+    assert info[4] == 0.0 and 1 <= n <= 100
+    T = d["A_star"].astype(np.float64) @ d["B_star"].astype(np.float64).T
+    assert abs(info[3] - np.sum(T * T)) <= 1e-12 * np.sum(T * T)
+    U1, U2 = res["U1"], res["U2t"].T
+    f = P.objective(T, res["alpha"], U1, res["beta"], U2, res["gamma"])
+    assert abs(f - info[8 + n - 1]) <= TOL_OBJ * info[3]
+    want_beta = P.beta_update(T, res["alpha"], U1, U2, res["gamma"])
+    assert rel(res["beta"], want_beta) <= TOL_REAL
+    # sampled rows of U1 / columns of U2 are +-1 patterns consistent with the packed carriers where the margin is clear
+    assert np.all(np.abs(res["B1"]) == 1) and np.all(np.abs(res["B2"]) == 1)
+    if info[1] == 1.0:
+        # after the loop ended on repeated signs the continuous iterates sit on the side of their signs
+        far = np.abs(U1) > 0.5
+        assert np.mean(np.sign(U1[far]) == res["B1"][far]) > 0.99
