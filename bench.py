@@ -333,6 +333,80 @@ def bench_backward(args):
     print(json.dumps(out))
 
 
+FP64_VECTOR_PEAK_TFLOPS = 78.6   # MI355X published fp64 vector peak
+
+
+def ptq_algorithmic_flops(N, M, R, r0, sweeps):
+    """fp64 operations of `sweeps` sweeps of the consensus ADMM with the target kept factored (a multiply-add counts as
+    two).  Per row of either side and sweep: the Tikhonov step (right-hand side 2 R r0, matrix R^2, Cholesky R^3/3,
+    two triangular solves 2 R^2), the closed-form scale (2 R r0 + 2 R^2), and the row's share of the two Gram pairs its
+    side contributes per sweep (2 x 2 (R^2 + R r0)); plus the R x R beta solve and the sign / dual update (6 per entry)."""
+    per_row = (2 * R * r0 + R * R + R ** 3 / 3.0 + 2 * R * R) + (2 * R * r0 + 2 * R * R) + 4 * (R * R + R * r0) + 6 * R
+    return sweeps * ((N + M) * per_row + R ** 3 / 3.0 + 4 * R * R)
+
+
+def bench_ptq(args):
+    """One step = one lordba_ptq call: the update of one 4096 x 4096 projection (rank-16 fp16 factors, resident in HBM)
+    quantised into a LoRDBA adapter of carrier rank 16 with the paper's settings (K = 100, (tau, mu) = (2, 10))."""
+    import numpy as np
+    import torch
+    from paper_2605_24058_amd import binding, inputs
+    N = M = 4096
+    R = r0 = 16
+    Kadmm = 100
+    K, W = args.steps, args.warmup
+    sets = 4
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    host = [inputs.make_ptq_inputs(args.seed + 1000 * s_, N, M, r0) for s_ in range(sets)]
+    dev = [(cu(h["A_star"]), cu(h["B_star"])) for h in host]
+    ws = torch.empty(binding.lordba_ptq_workspace_bytes(N, M, R, r0) // 8, dtype=torch.float64, device="cuda")
+    outs = {}
+
+    def step(i):
+        s_ = i % sets
+        outs[s_] = binding.lordba_ptq(dev[s_][0], dev[s_][1], R, K=Kadmm, workspace=ws)
+
+    reps_us, wall_s = timed(step, K, W, False, reps=3)
+    torch.cuda.synchronize()
+    call_us = reps_us[0]
+    sweeps = [int(outs[s_]["info"][0].item()) for s_ in sorted(outs)]
+    mean_sweeps = sum(sweeps) / len(sweeps)
+    flops = ptq_algorithmic_flops(N, M, R, r0, mean_sweeps)
+    achieved = flops / (call_us * 1e-6) / 1e12
+    out = {"metric": "PTQ-LoRDBA projections/s (one 4096 x 4096 update, rank-16 factors -> carrier rank 16, K = 100)",
+           "value": K / wall_s, "unit": "projections/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": wall_s * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f64", "io_dtype": "f16", "data": "synthetic",
+           "config": {"workload": "ptq_4096x4096_R16_r16_K100", "N": N, "M": M, "R": R, "r0": r0, "K": Kadmm, "tau": 2.0, "mu": 10.0,
+                      "sweeps_run": sweeps, "launch": "eager", "seed": args.seed},
+           "roofline": {"bound": "alu", "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel_us": call_us,
+                        "kernel_us_repetitions": reps_us, "algorithmic_flops": flops,
+                        "note": "all kernels of one call taken together; the call is a chain of dependent launches on "
+                                "R x R and N x R operands and is bound by their latency, not by arithmetic or HBM"}}
+    if not args.no_cpu_baseline:
+        from oracle import ptq as P
+        n = 2048                      # a quarter of the projection: the dense oracle takes about 10 s there
+        h = inputs.make_ptq_inputs(args.seed, n, n, r0)
+        c0 = time.perf_counter()
+        ref = P.ptq(h["A_star"], h["B_star"], R, K=Kadmm)
+        c1 = time.perf_counter()
+        got = binding.lordba_ptq(cu(h["A_star"]), cu(h["B_star"]), R, K=Kadmm)
+        torch.cuda.synchronize()
+        sA, sB = binding.lordba_unpack_signs(got["packedA"].cpu().numpy().view(np.uint32), got["packedB"].cpu().numpy().view(np.uint32), n, n, R)
+        g1, g2, _ = P.canonical_gauge(sA.T.astype(np.float64), sB.T.astype(np.float64))
+        r1, r2, _ = P.canonical_gauge(ref["B1"], ref["B2"])
+        same = bool(np.array_equal(g1, r1) and np.array_equal(g2, r2) and int(got["info"][0].item()) == ref["sweeps"])
+        err = max(float(np.linalg.norm(got[k].cpu().numpy() - ref[k]) / np.linalg.norm(ref[k])) for k in ("alpha", "beta", "gamma"))
+        out["cpu_baseline"] = {"value": 1.0 / (c1 - c0), "unit": "projections/s of a 2048 x 2048 update", "cores": os.cpu_count(), "kind": "oracle",
+                               "sample": "one 2048 x 2048 update (a quarter of the workload's projection), same ranks and K; "
+                                         "numpy's threaded BLAS on all host cores"}
+        out["parity_signs_and_sweeps_exact"] = same
+        out["parity_max_rel_l2_scales"] = err
+        out["parity_ok"] = bool(same and err <= 1e-8)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -353,6 +427,8 @@ def main():
                     "instead of the forward call; single-shape workloads only")
     ap.add_argument("--train-step", action="store_true", help="time one training step of the branch: lordba_pack_latents, "
                     "lordba_forward_save_t, lordba_backward with the kept t (implies --backward)")
+    ap.add_argument("--ptq", action="store_true", help="time lordba_ptq (post-training quantisation of one 4096 x 4096 update) "
+                    "instead of the forward pass")
     ap.add_argument("--keep-t", action="store_true", help="--backward: pass the rank-r intermediate kept by "
                     "lordba_forward_save_t instead of letting lordba_backward recompute it from x")
     ap.add_argument("--kappa", type=float, default=100.0, help="temperature of the smooth-sign factor (--backward)")
@@ -384,6 +460,10 @@ def main():
         args.steps = 10 if args.steps is None else args.steps
         args.warmup = 1 if args.warmup is None else args.warmup
         return bench_c5_model(args)
+    if args.ptq:
+        args.steps = 20 if args.steps is None else args.steps
+        args.warmup = 3 if args.warmup is None else args.warmup
+        return bench_ptq(args)
     args.steps = 2400 if args.steps is None else args.steps
     args.warmup = 240 if args.warmup is None else args.warmup
     if args.workload == "c4_sweep":

@@ -163,6 +163,34 @@ def test_backward_validation_needs_no_device(lib):
     assert f(*a) == 1
 
 
+def test_ptq_validation_needs_no_device(lib):
+    """lordba_ptq rejects bad arguments before any device work (fake addresses)."""
+    base = 0x20000000
+    names = ["A", "B", "pA", "pB", "al", "be", "ga", "si", "sr", "so", "info", "ws"]
+    p = {n: base + i * 0x4000000 for i, n in enumerate(names)}
+    N, M, R, r0, K = 300, 200, 8, 16, 100
+    need = lib.lordba_ptq_workspace_bytes(N, M, R, r0)
+    assert need >= 8 * 3 * (N + M) * R and need % 8 == 0
+    assert lib.lordba_ptq_workspace_bytes(N, M, 33, 40) == 0 and lib.lordba_ptq_workspace_bytes(N, M, 8, 65) == 0
+    assert lib.lordba_ptq_workspace_bytes(N, M, 8, 4) == 0                     # R may not exceed the factors' rank
+    assert lib.lordba_ptq_workspace_bytes(0, M, R, r0) == 0
+
+    def call(N=N, M=M, R=R, r0=r0, K=K, tau=2.0, mu=10.0, ws_bytes=need, **over):
+        q = dict(p); q.update(over)
+        return lib.lordba_ptq(q["A"], q["B"], q["pA"], q["pB"], q["al"], q["be"], q["ga"], q["si"], q["sr"], q["so"], q["info"],
+                              q["ws"], ws_bytes, N, M, R, r0, K, ctypes.c_double(tau), ctypes.c_double(mu), None)
+
+    for n in ("A", "B", "pA", "pB", "al", "be", "ga", "info", "ws"):
+        assert call(**{n: None}) == 1, n
+    assert call(R=0) == 2 and call(R=33, r0=40) == 2 and call(r0=4) == 2 and call(r0=65) == 2 and call(N=0) == 2
+    assert call(K=0) == 2 and call(K=5000) == 2 and call(M=(1 << 22) + 1) == 2
+    assert call(tau=1.0) == 3 and call(tau=float("nan")) == 3 and call(mu=0.0) == 3 and call(mu=-1.0) == 3
+    assert call(ws_bytes=need - 8) == 9
+    assert call(A=p["A"] + 1) == 5 and call(pA=p["pA"] + 2) == 5 and call(al=p["al"] + 4) == 5 and call(ws=p["ws"] + 4) == 5
+    assert call(al=p["A"]) == 4 and call(ws=p["B"]) == 4 and call(ga=p["al"]) == 4 and call(info=p["ws"]) == 4
+    assert call(si=p["sr"]) == 4
+
+
 def test_forward_multi_validation_needs_no_device(lib):
     base = 0x10000000
     x, pA, pB, si, sr, so, yb, yo = (base + i * 0x1000000 for i in range(8))
