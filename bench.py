@@ -398,7 +398,7 @@ def bench_ptq(args):
         r1, r2, _ = P.canonical_gauge(ref["B1"], ref["B2"])
         same = bool(np.array_equal(g1, r1) and np.array_equal(g2, r2) and int(got["info"][0].item()) == ref["sweeps"])
         err = max(float(np.linalg.norm(got[k].cpu().numpy() - ref[k]) / np.linalg.norm(ref[k])) for k in ("alpha", "beta", "gamma"))
-        out["cpu_baseline"] = {"value": 1.0 / (c1 - c0), "unit": "projections/s of a 2048 x 2048 update", "cores": os.cpu_count(), "kind": "oracle",
+        out["cpu_baseline"] = {"value": 1.0 / (c1 - c0), "unit": "projections/s of a 2048 x 2048 update", "cores": min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1)), "kind": "oracle",
                                "sample": "one 2048 x 2048 update (a quarter of the workload's projection), same ranks and K; "
                                          "numpy's threaded BLAS on all host cores"}
         out["parity_signs_and_sweeps_exact"] = same

@@ -12,10 +12,11 @@
 // [M, R] row-major, which is also the layout of S_B.  All arithmetic is fp64; sums run in a fixed order (no atomics), so
 // a call is reproducible bit for bit.
 //
-// Each row kernel works on blocks of 64 rows, ends by writing its block's share of its side's Gram pair, and starts by
-// adding up the other side's shares: a sweep is seven launches (two Tikhonov steps, alpha, gamma, beta, sign/dual update,
-// penalty control) and no stand-alone reduction.  A flag in device memory ends the loop: once the sign matrices repeat,
-// the remaining launches return at once, so the host never waits on the device inside the loop.
+// Each row kernel works on blocks of 32 rows, ends by writing its block's share of its side's Gram pair, and starts by
+// adding up the other side's shares: a sweep is five launches (two Tikhonov steps, each followed at once by the sign and
+// dual update of its rows, which needs nothing else; alpha; gamma; beta with the penalty control) and no stand-alone
+// reduction.  A flag in device memory ends the loop: once the sign matrices repeat, the remaining launches return at
+// once, so the host never waits on the device inside the loop.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <math.h>
@@ -25,9 +26,10 @@
 
 namespace {
 
-constexpr int kRows = 64;      // rows of one side per workgroup
-constexpr int kThreads = 256;  // four waves
-constexpr int kElems = 1024;   // entries per workgroup of the elementwise sign / dual update
+constexpr int kRows = 32;      // rows of one side per workgroup
+constexpr int kThreads = 256;  // four waves: the warm-start and export kernels
+constexpr int kRowThreads = 512;  // eight waves: the kernels of a sweep
+static_assert(LORDBA_PTQ_MAX_RANK == 32, "the Tikhonov kernel is instantiated for ranks up to 16 and up to 32");
 constexpr int kInfoHead = 8;   // info[0..7]: sweeps, frozen, rho, ||T||_F^2, degenerate, reserved; then one objective per sweep
 
 enum Ctrl { kRho = 0, kYfac = 1, kDone = 2, kSweeps = 3, kNormT2 = 4, kFrozen = 5, kDegenerate = 6, kCtrlCount = 8 };
@@ -37,17 +39,16 @@ struct PtqArgs {
     int64_t n[2];        // N, M
     int R, r0;
     int nb[2];           // row blocks per side
-    int ne[2];           // elementwise blocks per side
     double* X[2];        // continuous iterates U1 [N, R], U2^T [M, R]
     double* Mm[2];       // their +-1 copies
     double* Y[2];        // scaled duals
     double* scale[2];    // alpha [N], gamma [M]
     double* beta;        // [R]
-    double* part[2];     // per block shares of the Gram pair of each side, [nb, pstride]: S (R*R) then K (R*r0)
+    double* part[2];     // per block shares of each side, [nb, pstride]: S (R*R), K (R*r0), then the block's squared
+                         // consensus gap and its number of sign changes in the sweep (written by the Tikhonov kernel only)
     int pstride;
     double* Z[2];        // warm start: [r0, R] maps from factor rows to singular-vector entries
     double* ctrl;        // [kCtrlCount]
-    double* res;         // [(ne0 + ne1), 2]: squared consensus gap and number of sign changes per elementwise block
     double* info;
     int K;
     double tau, mu;
@@ -104,11 +105,22 @@ __device__ inline double group_solve(const double* H, int ld, int n, int l, int 
     return b;
 }
 
-// dst[o] = sum over blocks of part[b][o], o < count, blocks in ascending order.
+// dst[o] = sum over blocks of part[b][o], o < count, blocks in ascending order.  The loads of a batch of 32 shares are
+// issued together (unconditionally, from a clamped index), since each of them is a trip to memory another kernel wrote.
 __device__ inline void reduce_shares(const double* part, int nb, int pstride, int count, double* dst) {
-    for (int o = threadIdx.x; o < count; o += kThreads) {
+    constexpr int kBatch = 32;
+    for (int o = threadIdx.x; o < count; o += blockDim.x) {
         double acc = 0.0;
-        for (int b = 0; b < nb; ++b) acc += part[static_cast<int64_t>(b) * pstride + o];
+        for (int b0 = 0; b0 < nb; b0 += kBatch) {
+            double v[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const int b = b0 + j < nb ? b0 + j : nb - 1;
+                v[j] = part[static_cast<int64_t>(b) * pstride + o];
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) acc += (b0 + j < nb) ? v[j] : 0.0;
+        }
         dst[o] = acc;
     }
 }
@@ -116,7 +128,7 @@ __device__ inline void reduce_shares(const double* part, int nb, int pstride, in
 // This block's share of a side's Gram pair from its rows in LDS: xs [kRows, R], cs [kRows] (0 past the end), fs [kRows, r0].
 __device__ inline void gram_share(const double* xs, const double* cs, const double* fs, int R, int r0, double* out) {
     const int RR = R * R;
-    for (int o = threadIdx.x; o < RR + R * r0; o += kThreads) {
+    for (int o = threadIdx.x; o < RR + R * r0; o += blockDim.x) {
         double acc = 0.0;
         if (o < RR) {
             const int k = o / R, l = o - k * R;
@@ -130,7 +142,7 @@ __device__ inline void gram_share(const double* xs, const double* cs, const doub
 }
 
 __device__ inline void load_factor_rows(const __half* F, int64_t n, int r0, int64_t row0, double* fs) {
-    for (int o = threadIdx.x; o < kRows * r0; o += kThreads) {
+    for (int o = threadIdx.x; o < kRows * r0; o += blockDim.x) {
         const int64_t row = row0 + o / r0;
         fs[o] = row < n ? static_cast<double>(__half2float(F[row0 * r0 + o])) : 0.0;
     }
@@ -169,12 +181,12 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
     double* V = W + r0 * ld;
     double* sig = V + r0 * ld;
     int* idx = reinterpret_cast<int*>(sig + r0);
+    reduce_shares(a.part[0], a.nb[0], a.pstride, r0 * r0, W);  // (W and V serve as unpadded staging here)
+    reduce_shares(a.part[1], a.nb[1], a.pstride, r0 * r0, V);
+    wave_sync();
     for (int o = l; o < r0 * r0; o += 64) {
-        double sa = 0.0, sb = 0.0;
-        for (int b = 0; b < a.nb[0]; ++b) sa += a.part[0][static_cast<int64_t>(b) * a.pstride + o];
-        for (int b = 0; b < a.nb[1]; ++b) sb += a.part[1][static_cast<int64_t>(b) * a.pstride + o];
-        Ga[(o / r0) * ld + o % r0] = sa;
-        Gb[(o / r0) * ld + o % r0] = sb;
+        Ga[(o / r0) * ld + o % r0] = W[o];
+        Gb[(o / r0) * ld + o % r0] = V[o];
     }
     wave_sync();
     const bool ok_a = group_cholesky(Ga, ld, r0, l);
@@ -188,30 +200,46 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
             V[l * ld + j] = (l == j) ? 1.0 : 0.0;
         }
     }
-    for (int sweep = 0; sweep < 60; ++sweep) {
-        bool rotated = false;
-        for (int p = 0; p + 1 < r0; ++p) {
-            for (int q = p + 1; q < r0; ++q) {
-                const double wp = l < r0 ? W[l * ld + p] : 0.0, wq = l < r0 ? W[l * ld + q] : 0.0;
-                const double app = __shfl(group_sum(wp * wp, 64), 0, 64);
-                const double aqq = __shfl(group_sum(wq * wq, 64), 0, 64);
-                const double apq = __shfl(group_sum(wp * wq, 64), 0, 64);
-                if (fabs(apq) > 1e-15 * sqrt(app * aqq)) {
-                    rotated = true;
-                    const double zeta = (aqq - app) / (2.0 * apq);
-                    const double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                    const double cs = 1.0 / sqrt(1.0 + t * t), sn = cs * t;
-                    if (l < r0) {
-                        W[l * ld + p] = cs * wp - sn * wq;
-                        W[l * ld + q] = sn * wp + cs * wq;
-                        const double vp = V[l * ld + p], vq = V[l * ld + q];
-                        V[l * ld + p] = cs * vp - sn * vq;
-                        V[l * ld + q] = sn * vp + cs * vq;
+    // One-sided Jacobi in the round-robin order: the r0 / 2 column pairs of a round are disjoint, so groups of lanes
+    // rotate several pairs at once (lane i of a group owns row i of the core and of V for the group's pair).
+    {
+        const int gsz = r0 <= 16 ? 16 : (r0 <= 32 ? 32 : 64), ngroups = 64 / gsz;
+        const int g = l / gsz, i = l - g * gsz;
+        const int ne = r0 + (r0 & 1);  // an even number of players; with r0 odd, player r0 is a bye
+        for (int sweep = 0; sweep < 60; ++sweep) {
+            bool rotated = false;
+            for (int round = 0; round + 1 < ne; ++round) {
+                for (int m0 = 0; m0 < ne / 2; m0 += ngroups) {
+                    const int m = m0 + g;
+                    int p = 0, q = 0;
+                    bool valid = m < ne / 2;
+                    if (valid) {
+                        const int lo = (round + m) % (ne - 1);
+                        const int hi = m == 0 ? ne - 1 : (round + ne - 1 - m) % (ne - 1);
+                        p = lo < hi ? lo : hi;
+                        q = lo < hi ? hi : lo;
+                        valid = q < r0;
                     }
+                    const bool mine = valid && i < r0;
+                    const double wp = mine ? W[i * ld + p] : 0.0, wq = mine ? W[i * ld + q] : 0.0;
+                    const double app = group_sum(wp * wp, gsz), aqq = group_sum(wq * wq, gsz), apq = group_sum(wp * wq, gsz);
+                    const bool rot = valid && fabs(apq) > 1e-15 * sqrt(app * aqq);
+                    if (rot && mine) {
+                        const double zeta = (aqq - app) / (2.0 * apq);
+                        const double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+                        const double cs = 1.0 / sqrt(1.0 + t * t), sn = cs * t;
+                        W[i * ld + p] = cs * wp - sn * wq;
+                        W[i * ld + q] = sn * wp + cs * wq;
+                        const double vp = V[i * ld + p], vq = V[i * ld + q];
+                        V[i * ld + p] = cs * vp - sn * vq;
+                        V[i * ld + q] = sn * vp + cs * vq;
+                    }
+                    rotated = rotated || (__builtin_amdgcn_ballot_w64(rot) != 0);
+                    wave_sync();
                 }
             }
+            if (!rotated) break;
         }
-        if (!rotated) break;
     }
     // singular values = column norms of the rotated core; order them (descending, ties by index)
     for (int p = 0; p < r0; ++p) {
@@ -298,10 +326,10 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_init_rows_kernel(PtqArgs 
 
 // ---- one sweep ----------------------------------------------------------------------------------------------------
 
-// LDS of the two row kernels: So [R*R], Ko [R*r0] (the other side's Gram pair), bs [R], fs, xs, cs, then the per-group
-// matrices of the Tikhonov step.
+// LDS of the two row kernels: So [R*R], Ko [R*r0] (the other side's Gram pair), bs [R], fs, xs, cs, ys, then the per-group
+// matrices of the Tikhonov step (R x ld raw columns and R reciprocal pivots each).
 struct RowLds {
-    double *So, *Ko, *bs, *fs, *xs, *cs, *H;
+    double *So, *Ko, *bs, *fs, *xs, *cs, *ys, *H;
 };
 __device__ inline RowLds carve_rows(int R, int r0) {
     RowLds s;
@@ -311,72 +339,144 @@ __device__ inline RowLds carve_rows(int R, int r0) {
     s.fs = s.bs + R;
     s.xs = s.fs + kRows * r0;
     s.cs = s.xs + kRows * R;
-    s.H = s.cs + kRows;
+    s.ys = s.cs + kRows;
+    s.H = s.ys + kRows * R;
     return s;
 }
 
-// Eq. (u-step-1) / Eq. (u-step-2) for one side: per row, (c^2 (beta beta^T o So) + rho_k I) u = c beta o (Ko f) + rho_k (M - Y).
-__global__ __launch_bounds__(kThreads) void lordba_ptq_ustep_kernel(PtqArgs a, int side) {
+// Eq. (u-step-1) / Eq. (u-step-2) for one side: per row, (c^2 (beta beta^T o So) + rho_k I) u = c beta o (Ko f) + rho_k (M - Y),
+// then Eq. (m-y-step) for the same row: M = sign(u + Y), Y += u - M (a pending rescaling of Y after a penalty change is
+// applied on the way).  A group of lanes solves one row: lane l keeps column l of the matrix in registers through a
+// right-looking Cholesky factorisation; a finished column is published once, unscaled, to LDS together with the
+// reciprocal of its pivot's root, and the other lanes fold the scaling into their updates (no division but that one).
+// `solve_waves` of the block's waves take part (as many as the LDS holds matrices for).
+template <int RMAX>  // the carrier rank is at most RMAX (16 or 32): the length of the register-resident column
+__global__ __launch_bounds__(kRowThreads) void lordba_ptq_ustep_kernel(PtqArgs a, int side, int solve_waves) {
     if (a.ctrl[kDone] != 0.0) return;
     const int R = a.R, r0 = a.r0, other = 1 - side, blk = blockIdx.x;
     const int64_t n = a.n[side], row0 = static_cast<int64_t>(blk) * kRows;
     const RowLds s = carve_rows(R, r0);
-    reduce_shares(a.part[other], a.nb[other], a.pstride, R * R + R * r0, s.So);  // So and Ko are adjacent
-    for (int k = threadIdx.x; k < R; k += kThreads) s.bs[k] = a.beta[k];
+    const int count = R * R + R * r0;
+    reduce_shares(a.part[other], a.nb[other], a.pstride, count, s.So);  // So and Ko are adjacent
+    for (int k = threadIdx.x; k < R; k += kRowThreads) s.bs[k] = a.beta[k];
     load_factor_rows(a.F[side], n, r0, row0, s.fs);
-    for (int row = threadIdx.x; row < kRows; row += kThreads) s.cs[row] = row0 + row < n ? a.scale[side][row0 + row] : 0.0;
-    __syncthreads();
+    for (int row = threadIdx.x; row < kRows; row += kRowThreads) s.cs[row] = row0 + row < n ? a.scale[side][row0 + row] : 0.0;
     const double rho_k = a.ctrl[kRho] / (static_cast<double>(n) * R), yfac = a.ctrl[kYfac];
+    for (int o = threadIdx.x; o < kRows * R; o += kRowThreads) {   // xs holds M until the row is solved, ys the rescaled Y
+        const bool in = row0 + o / R < n;
+        s.xs[o] = in ? a.Mm[side][row0 * R + o] : 0.0;
+        s.ys[o] = in ? yfac * a.Y[side][row0 * R + o] : 0.0;
+    }
+    __syncthreads();
     const int gs = group_size_for(R), groups = 64 / gs, ld = R + 1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int g = lane / gs, l = lane - g * gs, base = g * gs;
-    double* H = s.H + (wave * groups + g) * R * ld;
-    const int rows_per_pass = 4 * groups;
-    for (int pass = 0; pass < kRows / rows_per_pass; ++pass) {
-        const int row = pass * rows_per_pass + wave * groups + g;
-        const bool in = row0 + row < n;
-        const double c = s.cs[row];
-        double b = 0.0;
-        if (l < R) {
+    double gap = 0.0, flips = 0.0;
+    if (wave < solve_waves) {
+        double* H = s.H + (wave * groups + g) * (R * ld + R);
+        double* rd = H + R * ld;
+        const int rows_per_pass = solve_waves * groups;
+        const bool act = l < R;
+        const int lc = act ? l : 0;   // a valid column for the idle lanes' reads
+        for (int pass = 0; pass < kRows / rows_per_pass; ++pass) {
+            const int row = pass * rows_per_pass + wave * groups + g;
+            const bool in = row0 + row < n;
+            const double c = s.cs[row], c2 = c * c, bl = s.bs[lc];
             double kf = 0.0;
-            for (int q = 0; q < r0; ++q) kf += s.Ko[l * r0 + q] * s.fs[row * r0 + q];
-            double w = 0.0;
-            if (in) {
-                const int64_t gi = (row0 + row) * R + l;
-                w = a.Mm[side][gi] - yfac * a.Y[side][gi];
+            for (int q = 0; q < r0; ++q) kf += s.Ko[lc * r0 + q] * s.fs[row * r0 + q];
+            const double m_old = s.xs[row * R + lc], y_old = s.ys[row * R + lc];
+            double b = c * bl * kf + rho_k * (m_old - y_old);
+            double col[RMAX];
+#pragma unroll
+            for (int i = 0; i < RMAX; ++i) {
+                col[i] = 0.0;
+                if (i < R) col[i] = c2 * (s.bs[i] * bl) * s.So[i * R + lc] + (i == l ? rho_k : 0.0);
             }
-            b = c * s.bs[l] * kf + rho_k * w;
-            for (int k = 0; k < R; ++k) H[k * ld + l] = (c * c) * (s.bs[k] * s.bs[l]) * s.So[k * R + l] + (k == l ? rho_k : 0.0);
+#pragma unroll
+            for (int k = 0; k < RMAX; ++k) {
+                if (k < R) {
+                    if (l == k) {
+#pragma unroll
+                        for (int i = k; i < RMAX; ++i)
+                            if (i < R) H[i * ld + k] = col[i];
+                    }
+                    wave_sync();
+                    const double rdk = 1.0 / sqrt(H[k * ld + k]);
+                    if (l == k) rd[k] = rdk;
+                    const double f = H[lc * ld + k] * (rdk * rdk);
+#pragma unroll
+                    for (int i = k + 1; i < RMAX; ++i)
+                        if (i < R) col[i] -= (l > k && i >= l) ? H[i * ld + k] * f : 0.0;
+                }
+            }
+            wave_sync();
+            // L[i][k] = H[i][k] rd[k].  Forward then backward substitution; lane l carries entry l of the right-hand side.
+#pragma unroll
+            for (int k = 0; k < RMAX; ++k) {
+                if (k < R) {
+                    const double rdk = rd[k];
+                    const double yk = __shfl(b, base + k, 64) * rdk;
+                    if (l == k) b = yk;
+                    if (l > k && act) b -= H[lc * ld + k] * (rdk * yk);
+                }
+            }
+            const double rdl = rd[lc];
+#pragma unroll
+            for (int k = RMAX - 1; k >= 0; --k) {
+                if (k < R) {
+                    const double xk = __shfl(b, base + k, 64) * rd[k];
+                    if (l == k) b = xk;
+                    if (l < k) b -= H[k * ld + lc] * (rdl * xk);
+                }
+            }
+            if (act) {
+                const double x = b;
+                const double mn = (x + y_old) < 0.0 ? -1.0 : 1.0;
+                s.xs[row * R + l] = in ? x : 0.0;
+                if (in) {
+                    const int64_t gi = (row0 + row) * R + l;
+                    a.X[side][gi] = x;
+                    a.Mm[side][gi] = mn;
+                    a.Y[side][gi] = y_old + x - mn;
+                    gap += (x - mn) * (x - mn);
+                    flips += (mn != m_old) ? 1.0 : 0.0;
+                }
+            }
+            wave_sync();
         }
-        wave_sync();
-        group_cholesky(H, ld, R, l);
-        const double x = group_solve(H, ld, R, l, base, b);
-        if (l < R) {
-            s.xs[row * R + l] = in ? x : 0.0;
-            if (in) a.X[side][(row0 + row) * R + l] = x;
-        }
-        wave_sync();
     }
+    gap = group_sum(gap, 64);
+    flips = group_sum(flips, 64);
+    double* red = s.ys;   // free once every row has taken its Y (the barrier below orders this after the last read)
     __syncthreads();
-    gram_share(s.xs, s.cs, s.fs, R, r0, a.part[side] + static_cast<int64_t>(blk) * a.pstride);
+    if (lane == 0) { red[2 * wave] = gap; red[2 * wave + 1] = flips; }
+    __syncthreads();
+    double* share = a.part[side] + static_cast<int64_t>(blk) * a.pstride;
+    gram_share(s.xs, s.cs, s.fs, R, r0, share);
+    if (threadIdx.x == 0) {
+        double gsum = 0.0, fsum = 0.0;
+        for (int w = 0; w < kRowThreads / 64; ++w) { gsum += red[2 * w]; fsum += red[2 * w + 1]; }
+        share[count] = gsum;
+        share[count + 1] = fsum;
+    }
 }
 
 // Eq. (alpha-update) (side 0) / Eq. (gamma-update) (side 1): per row, with v = u o beta, <T_i, D_i> = v . (Ko f) and
 // ||D_i||^2 = v^T So v; 0 where the denominator is 0.
-__global__ __launch_bounds__(kThreads) void lordba_ptq_scale_kernel(PtqArgs a, int side) {
+__global__ __launch_bounds__(kRowThreads) void lordba_ptq_scale_kernel(PtqArgs a, int side) {
     if (a.ctrl[kDone] != 0.0) return;
     const int R = a.R, r0 = a.r0, other = 1 - side, blk = blockIdx.x;
     const int64_t n = a.n[side], row0 = static_cast<int64_t>(blk) * kRows;
     const RowLds s = carve_rows(R, r0);
     reduce_shares(a.part[other], a.nb[other], a.pstride, R * R + R * r0, s.So);
-    for (int k = threadIdx.x; k < R; k += kThreads) s.bs[k] = a.beta[k];
+    for (int k = threadIdx.x; k < R; k += blockDim.x) s.bs[k] = a.beta[k];
     load_factor_rows(a.F[side], n, r0, row0, s.fs);
-    for (int o = threadIdx.x; o < kRows * R; o += kThreads) s.xs[o] = row0 + o / R < n ? a.X[side][row0 * R + o] : 0.0;
+    for (int o = threadIdx.x; o < kRows * R; o += blockDim.x) s.xs[o] = row0 + o / R < n ? a.X[side][row0 * R + o] : 0.0;
     __syncthreads();
-    const int gs = group_size_for(R), groups = 64 / gs;
+    const int gs = group_size_for(R), groups = 64 / gs, waves = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int g = lane / gs, l = lane - g * gs;
-    const int rows_per_pass = 4 * groups;
+    const int rows_per_pass = waves * groups;
     for (int pass = 0; pass < kRows / rows_per_pass; ++pass) {
         const int row = pass * rows_per_pass + wave * groups + g;
         double num = 0.0, den = 0.0;
@@ -406,23 +506,25 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_scale_kernel(PtqArgs a, i
 // Cholesky factorisation with diagonal pivoting that stops at the numerical rank (for a positive semidefinite G = L L^T
 // with L of full column rank, pinv(G) = L (L^T L)^{-2} L^T; at full rank this is the ordinary solve, which is what runs
 // then).  Also the objective of Eq. (admm-problem) at the continuous iterates, from the same Gram pairs:
-// f = (||T||_F^2 - 2 beta.h + beta^T G beta) / 2.
-__global__ __launch_bounds__(kThreads) void lordba_ptq_beta_kernel(PtqArgs a, int t) {
+// f = (||T||_F^2 - 2 beta.h + beta^T G beta) / 2.  Then the end of the sweep: residual balancing of the penalty (first
+// half of the run) from the consensus gaps and sign changes the Tikhonov kernels left in their shares, and the end of
+// the loop when no sign changed.
+__global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a, int t) {
     if (a.ctrl[kDone] != 0.0) return;
     const int R = a.R, r0 = a.r0, ld = R + 1, count = R * R + R * r0;
-    double* P1 = lds;          // S1, K1
-    double* P2 = P1 + count;   // S2, K2
-    double* G = P2 + count;    // [R, ld]
-    double* N2 = G + R * ld;   // [R, ld]
-    double* hv = N2 + R * ld;  // [R] permuted right-hand side
-    double* h0 = hv + R;       // [R]
-    double* bt = h0 + R;       // [R] result
+    double* P1 = lds;              // S1, K1, gap, sign changes of side 0
+    double* P2 = P1 + count + 2;   // the same of side 1
+    double* G = P2 + count + 2;    // [R, ld]
+    double* N2 = G + R * ld;       // [R, ld]
+    double* hv = N2 + R * ld;      // [R] permuted right-hand side
+    double* h0 = hv + R;           // [R]
+    double* bt = h0 + R;           // [R] result
     int* perm = reinterpret_cast<int*>(bt + R);
-    reduce_shares(a.part[0], a.nb[0], a.pstride, count, P1);
-    reduce_shares(a.part[1], a.nb[1], a.pstride, count, P2);
+    reduce_shares(a.part[0], a.nb[0], a.pstride, count + 2, P1);
+    reduce_shares(a.part[1], a.nb[1], a.pstride, count + 2, P2);
     __syncthreads();
-    for (int o = threadIdx.x; o < R * R; o += kThreads) G[(o / R) * ld + o % R] = P1[o] * P2[o];
-    for (int k = threadIdx.x; k < R; k += kThreads) {
+    for (int o = threadIdx.x; o < R * R; o += blockDim.x) G[(o / R) * ld + o % R] = P1[o] * P2[o];
+    for (int k = threadIdx.x; k < R; k += blockDim.x) {
         double acc = 0.0;
         for (int q = 0; q < r0; ++q) acc += P1[R * R + k * r0 + q] * P2[R * R + k * r0 + q];
         hv[k] = acc;
@@ -502,59 +604,15 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_beta_kernel(PtqArgs a, in
     }
     lin = group_sum(lin, 64);
     quad = group_sum(quad, 64);
-    if (l == 0) a.info[kInfoHead + t] = 0.5 * (a.ctrl[kNormT2] - 2.0 * lin + quad);
-}
-
-// Eq. (m-y-step) for both sides: M = sign(U + Y), Y += U - M; per block the squared consensus gap and the number of
-// entries of M that changed.  A pending rescaling of Y (after a penalty change) is applied here.
-__global__ __launch_bounds__(kThreads) void lordba_ptq_sign_dual_kernel(PtqArgs a) {
-    if (a.ctrl[kDone] != 0.0) return;
-    const int side = static_cast<int>(blockIdx.x) < a.ne[0] ? 0 : 1;
-    const int blk = side == 0 ? blockIdx.x : blockIdx.x - a.ne[0];
-    const int64_t total = a.n[side] * a.R;
-    const double yfac = a.ctrl[kYfac];
-    double gap = 0.0, flips = 0.0;
-    for (int e = 0; e < kElems / kThreads; ++e) {
-        const int64_t i = static_cast<int64_t>(blk) * kElems + e * kThreads + threadIdx.x;
-        if (i < total) {
-            const double u = a.X[side][i], y = yfac * a.Y[side][i], mo = a.Mm[side][i];
-            const double mn = (u + y) < 0.0 ? -1.0 : 1.0;
-            a.Y[side][i] = y + u - mn;
-            a.Mm[side][i] = mn;
-            gap += (u - mn) * (u - mn);
-            flips += (mn != mo) ? 1.0 : 0.0;
-        }
-    }
-    gap = group_sum(gap, 64);
-    flips = group_sum(flips, 64);
-    double* red = lds;
-    if ((threadIdx.x & 63) == 0) { red[2 * (threadIdx.x >> 6)] = gap; red[2 * (threadIdx.x >> 6) + 1] = flips; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        a.res[2 * blockIdx.x] = (red[0] + red[2]) + (red[4] + red[6]);
-        a.res[2 * blockIdx.x + 1] = (red[1] + red[3]) + (red[5] + red[7]);
-    }
-}
-
-// Residual balancing of the penalty (first half of the run) and the end of the loop.
-__global__ __launch_bounds__(64) void lordba_ptq_control_kernel(PtqArgs a, int t) {
-    if (a.ctrl[kDone] != 0.0) return;
-    const int l = threadIdx.x;
-    double gap = 0.0, f0 = 0.0, f1 = 0.0;
-    for (int b = l; b < a.ne[0] + a.ne[1]; b += 64) {
-        gap += a.res[2 * b];
-        if (b < a.ne[0]) f0 += a.res[2 * b + 1]; else f1 += a.res[2 * b + 1];
-    }
-    gap = group_sum(gap, 64);
-    f0 = group_sum(f0, 64);
-    f1 = group_sum(f1, 64);
     if (l != 0) return;
+    a.info[kInfoHead + t] = 0.5 * (a.ctrl[kNormT2] - 2.0 * lin + quad);
+    const double gap = P1[count] + P2[count], f0 = P1[count + 1], f1 = P2[count + 1];
     double rho = a.ctrl[kRho], yfac = 1.0;
     if (2 * static_cast<int64_t>(t) < a.K) {
-        const double rho0 = rho / (static_cast<double>(a.n[0]) * a.R), rho1 = rho / (static_cast<double>(a.n[1]) * a.R);
-        const double r = sqrt(gap), s = sqrt(rho0 * rho0 * 4.0 * f0 + rho1 * rho1 * 4.0 * f1);
-        if (r > a.mu * s) { rho *= a.tau; yfac = 1.0 / a.tau; }
-        else if (s > a.mu * r) { rho /= a.tau; yfac = a.tau; }
+        const double rho0 = rho / (static_cast<double>(a.n[0]) * R), rho1 = rho / (static_cast<double>(a.n[1]) * R);
+        const double r = sqrt(gap), sdual = sqrt(rho0 * rho0 * 4.0 * f0 + rho1 * rho1 * 4.0 * f1);
+        if (r > a.mu * sdual) { rho *= a.tau; yfac = 1.0 / a.tau; }
+        else if (sdual > a.mu * r) { rho /= a.tau; yfac = a.tau; }
     }
     a.ctrl[kRho] = rho;
     a.ctrl[kYfac] = yfac;
@@ -621,8 +679,8 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_fill_kernel(double* p, in
 }
 
 struct Layout {
-    size_t x[2], m[2], y[2], part[2], z[2], ctrl, res, total;
-    int nb[2], ne[2], pstride;
+    size_t x[2], m[2], y[2], part[2], z[2], ctrl, total;
+    int nb[2], pstride;
 };
 
 Layout make_layout(int64_t N, int64_t M, int64_t R, int64_t r0) {
@@ -630,11 +688,8 @@ Layout make_layout(int64_t N, int64_t M, int64_t R, int64_t r0) {
     const int64_t n[2] = {N, M};
     size_t off = 0;
     auto take = [&](size_t doubles) { const size_t at = off; off += (doubles + 31) / 32 * 32; return at; };
-    for (int s = 0; s < 2; ++s) {
-        L.nb[s] = static_cast<int>((n[s] + kRows - 1) / kRows);
-        L.ne[s] = static_cast<int>((n[s] * R + kElems - 1) / kElems);
-    }
-    const int64_t pair = R * R + R * r0, sq = r0 * r0;
+    for (int s = 0; s < 2; ++s) L.nb[s] = static_cast<int>((n[s] + kRows - 1) / kRows);
+    const int64_t pair = R * R + R * r0 + 2, sq = r0 * r0;
     L.pstride = static_cast<int>(((pair > sq ? pair : sq) + 31) / 32 * 32);
     for (int s = 0; s < 2; ++s) L.x[s] = take(n[s] * R);   // the iterates come first: U1 [N, R], then U2^T [M, R]
     for (int s = 0; s < 2; ++s) L.m[s] = take(n[s] * R);
@@ -642,7 +697,6 @@ Layout make_layout(int64_t N, int64_t M, int64_t R, int64_t r0) {
     for (int s = 0; s < 2; ++s) L.part[s] = take(static_cast<size_t>(L.nb[s]) * L.pstride);
     for (int s = 0; s < 2; ++s) L.z[s] = take(r0 * R);
     L.ctrl = take(kCtrlCount);
-    L.res = take(2 * static_cast<size_t>(L.ne[0] + L.ne[1]));
     L.total = off * sizeof(double);
     return L;
 }
@@ -703,7 +757,6 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
     a.r0 = static_cast<int>(r0);
     for (int s = 0; s < 2; ++s) {
         a.nb[s] = L.nb[s];
-        a.ne[s] = L.ne[s];
         a.X[s] = ws + L.x[s];
         a.Mm[s] = ws + L.m[s];
         a.Y[s] = ws + L.y[s];
@@ -715,7 +768,6 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
     a.beta = beta;
     a.pstride = L.pstride;
     a.ctrl = ws + L.ctrl;
-    a.res = ws + L.res;
     a.info = info;
     a.K = static_cast<int>(K);
     a.tau = tau;
@@ -726,15 +778,20 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
     const size_t lds_svd = sizeof(double) * (4 * ir0 * ld0 + ir0) + sizeof(int) * ir0;
     const size_t lds_init = sizeof(double) * (kRows * ir0 + kRows * iR + kRows + ir0 * iR);
     const int gs = iR <= 16 ? 16 : 32;
-    const size_t lds_rows = sizeof(double) * (iR * iR + iR * ir0 + iR + kRows * ir0 + kRows * iR + kRows + 4 * (64 / gs) * iR * ldR);
-    const size_t lds_beta = sizeof(double) * (2 * (iR * iR + iR * ir0) + 2 * iR * ldR + 3 * iR) + sizeof(int) * iR;
-    const size_t lds_sign = sizeof(double) * 8;
+    // the Tikhonov kernel: as many waves solve rows at once as the LDS has room for their matrices (8, 4, 2 or 1)
+    const size_t lds_fixed = sizeof(double) * (iR * iR + iR * ir0 + iR + kRows * ir0 + 2 * kRows * iR + kRows);
+    const size_t lds_wave = sizeof(double) * (64 / gs) * (iR * ldR + iR);
+    int solve_waves = kRowThreads / 64;
+    while (solve_waves > 1 && lds_fixed + solve_waves * lds_wave > 160 * 1024) solve_waves >>= 1;
+    const size_t lds_rows = lds_fixed + solve_waves * lds_wave;
+    const size_t lds_beta = sizeof(double) * (2 * (iR * iR + iR * ir0 + 2) + 2 * iR * ldR + 3 * iR) + sizeof(int) * iR;
     const int nb01 = a.nb[0] + a.nb[1];
 
     {   // more than 64 KiB of LDS per workgroup has to be asked for
         const struct { const void* fn; size_t bytes; } big[] = {
             {reinterpret_cast<const void*>(lordba_ptq_factor_gram_kernel), lds_gram}, {reinterpret_cast<const void*>(lordba_ptq_svd_kernel), lds_svd},
-            {reinterpret_cast<const void*>(lordba_ptq_init_rows_kernel), lds_init}, {reinterpret_cast<const void*>(lordba_ptq_ustep_kernel), lds_rows},
+            {reinterpret_cast<const void*>(lordba_ptq_init_rows_kernel), lds_init},
+            {reinterpret_cast<const void*>(iR <= 16 ? lordba_ptq_ustep_kernel<16> : lordba_ptq_ustep_kernel<32>), lds_rows},
             {reinterpret_cast<const void*>(lordba_ptq_scale_kernel), lds_rows}, {reinterpret_cast<const void*>(lordba_ptq_beta_kernel), lds_beta}};
         for (const auto& b : big) {
             if (b.bytes > 160 * 1024) return LORDBA_ERR_DIM;
@@ -748,16 +805,18 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
     hipLaunchKernelGGL(lordba_ptq_factor_gram_kernel, dim3(nb01), dim3(kThreads), lds_gram, stream, a);
     hipLaunchKernelGGL(lordba_ptq_svd_kernel, dim3(1), dim3(64), lds_svd, stream, a);
     hipLaunchKernelGGL(lordba_ptq_init_rows_kernel, dim3(nb01), dim3(kThreads), lds_init, stream, a);
-    hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kThreads), lds_rows, stream, a, 0);
-    hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kThreads), lds_rows, stream, a, 1);
+    hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_rows, stream, a, 0);
+    hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_rows, stream, a, 1);
     for (int t = 0; t < a.K; ++t) {
-        hipLaunchKernelGGL(lordba_ptq_ustep_kernel, dim3(a.nb[0]), dim3(kThreads), lds_rows, stream, a, 0);
-        hipLaunchKernelGGL(lordba_ptq_ustep_kernel, dim3(a.nb[1]), dim3(kThreads), lds_rows, stream, a, 1);
-        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kThreads), lds_rows, stream, a, 0);
-        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kThreads), lds_rows, stream, a, 1);
-        hipLaunchKernelGGL(lordba_ptq_beta_kernel, dim3(1), dim3(kThreads), lds_beta, stream, a, t);
-        hipLaunchKernelGGL(lordba_ptq_sign_dual_kernel, dim3(a.ne[0] + a.ne[1]), dim3(kThreads), lds_sign, stream, a);
-        hipLaunchKernelGGL(lordba_ptq_control_kernel, dim3(1), dim3(64), 0, stream, a, t);
+        for (int side = 0; side < 2; ++side) {
+            if (iR <= 16)
+                hipLaunchKernelGGL(lordba_ptq_ustep_kernel<16>, dim3(a.nb[side]), dim3(kRowThreads), lds_rows, stream, a, side, solve_waves);
+            else
+                hipLaunchKernelGGL(lordba_ptq_ustep_kernel<32>, dim3(a.nb[side]), dim3(kRowThreads), lds_rows, stream, a, side, solve_waves);
+        }
+        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_rows, stream, a, 0);
+        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_rows, stream, a, 1);
+        hipLaunchKernelGGL(lordba_ptq_beta_kernel, dim3(1), dim3(kRowThreads), lds_beta, stream, a, t);
     }
     ExportArgs e;
     e.packedA = packedA;
