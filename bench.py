@@ -366,7 +366,8 @@ def bench_ptq(args):
         s_ = i % sets
         outs[s_] = binding.lordba_ptq(dev[s_][0], dev[s_][1], R, K=Kadmm, workspace=ws)
 
-    reps_us, wall_s = timed(step, K, W, False, reps=3)
+    use_graph = not args.no_graph
+    reps_us, wall_s = timed(step, K, W, use_graph, reps=3)
     torch.cuda.synchronize()
     call_us = reps_us[0]
     sweeps = [int(outs[s_]["info"][0].item()) for s_ in sorted(outs)]
@@ -378,7 +379,7 @@ def bench_ptq(args):
            "ms_per_step": wall_s * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f64", "io_dtype": "f16", "data": "synthetic",
            "config": {"workload": "ptq_4096x4096_R16_r16_K100", "N": N, "M": M, "R": R, "r0": r0, "K": Kadmm, "tau": 2.0, "mu": 10.0,
-                      "sweeps_run": sweeps, "launch": "eager", "seed": args.seed},
+                      "sweeps_run": sweeps, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
            "roofline": {"bound": "alu", "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel_us": call_us,
                         "kernel_us_repetitions": reps_us, "algorithmic_flops": flops,

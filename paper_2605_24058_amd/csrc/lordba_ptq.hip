@@ -12,10 +12,11 @@
 // [M, R] row-major, which is also the layout of S_B.  All arithmetic is fp64; sums run in a fixed order (no atomics), so
 // a call is reproducible bit for bit.
 //
-// Each row kernel works on blocks of 32 rows, ends by writing its block's share of its side's Gram pair, and starts by
-// adding up the other side's shares: a sweep is five launches (two Tikhonov steps, each followed at once by the sign and
-// dual update of its rows, which needs nothing else; alpha; gamma; beta with the penalty control) and no stand-alone
-// reduction.  A flag in device memory ends the loop: once the sign matrices repeat, the remaining launches return at
+// Each row kernel works on blocks of 32 rows and ends by writing its block's share of its side's Gram pair; a small
+// kernel adds the shares up (each workgroup of a row kernel doing so itself would pull every share through its own
+// compute unit's 64 B/clk path to L2: measured 9 us per launch against 4.8 us for the extra launch).  A sweep is nine
+// launches: two Tikhonov steps (each followed at once by the sign and dual update of its rows, which needs nothing
+// else), alpha, gamma, each with its totals kernel, and beta with the penalty control.  A flag in device memory ends the loop: once the sign matrices repeat, the remaining launches return at
 // once, so the host never waits on the device inside the loop.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -47,6 +48,7 @@ struct PtqArgs {
     double* part[2];     // per block shares of each side, [nb, pstride]: S (R*R), K (R*r0), then the block's squared
                          // consensus gap and its number of sign changes in the sweep (written by the Tikhonov kernel only)
     int pstride;
+    double* tot[2];      // the shares of each side added up (same layout as one share), written by the totals kernel
     double* Z[2];        // warm start: [r0, R] maps from factor rows to singular-vector entries
     double* ctrl;        // [kCtrlCount]
     double* info;
@@ -105,26 +107,6 @@ __device__ inline double group_solve(const double* H, int ld, int n, int l, int 
     return b;
 }
 
-// dst[o] = sum over blocks of part[b][o], o < count, blocks in ascending order.  The loads of a batch of 32 shares are
-// issued together (unconditionally, from a clamped index), since each of them is a trip to memory another kernel wrote.
-__device__ inline void reduce_shares(const double* part, int nb, int pstride, int count, double* dst) {
-    constexpr int kBatch = 32;
-    for (int o = threadIdx.x; o < count; o += blockDim.x) {
-        double acc = 0.0;
-        for (int b0 = 0; b0 < nb; b0 += kBatch) {
-            double v[kBatch];
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) {
-                const int b = b0 + j < nb ? b0 + j : nb - 1;
-                v[j] = part[static_cast<int64_t>(b) * pstride + o];
-            }
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) acc += (b0 + j < nb) ? v[j] : 0.0;
-        }
-        dst[o] = acc;
-    }
-}
-
 // This block's share of a side's Gram pair from its rows in LDS: xs [kRows, R], cs [kRows] (0 past the end), fs [kRows, r0].
 __device__ inline void gram_share(const double* xs, const double* cs, const double* fs, int R, int r0, double* out) {
     const int RR = R * R;
@@ -149,6 +131,33 @@ __device__ inline void load_factor_rows(const __half* F, int64_t n, int r0, int6
 }
 
 extern __shared__ double lds[];
+
+// tot[side][o] = sum over the blocks of part[side][b][o], o < count: 64 outputs per workgroup, blocks in ascending order.
+__global__ __launch_bounds__(64) void lordba_ptq_totals_kernel(PtqArgs a, int side, int count, int always) {
+    if (!always && a.ctrl[kDone] != 0.0) return;
+    const int o = blockIdx.x * 64 + threadIdx.x;
+    if (o >= count) return;
+    constexpr int kBatch = 64;
+    const double* part = a.part[side] + o;
+    const int nb = a.nb[side];
+    double acc = 0.0;
+    for (int b0 = 0; b0 < nb; b0 += kBatch) {
+        double v[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const int b = b0 + j < nb ? b0 + j : nb - 1;
+            v[j] = part[static_cast<int64_t>(b) * a.pstride];
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) acc += (b0 + j < nb) ? v[j] : 0.0;
+    }
+    a.tot[side][o] = acc;
+}
+
+// The totals of a side into LDS.
+__device__ inline void load_totals(const double* tot, int count, double* dst) {
+    for (int o = threadIdx.x; o < count; o += blockDim.x) dst[o] = tot[o];
+}
 
 // ---- warm start (Eq. (svd-init)) ----------------------------------------------------------------------------------
 
@@ -181,12 +190,9 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
     double* V = W + r0 * ld;
     double* sig = V + r0 * ld;
     int* idx = reinterpret_cast<int*>(sig + r0);
-    reduce_shares(a.part[0], a.nb[0], a.pstride, r0 * r0, W);  // (W and V serve as unpadded staging here)
-    reduce_shares(a.part[1], a.nb[1], a.pstride, r0 * r0, V);
-    wave_sync();
     for (int o = l; o < r0 * r0; o += 64) {
-        Ga[(o / r0) * ld + o % r0] = W[o];
-        Gb[(o / r0) * ld + o % r0] = V[o];
+        Ga[(o / r0) * ld + o % r0] = a.tot[0][o];
+        Gb[(o / r0) * ld + o % r0] = a.tot[1][o];
     }
     wave_sync();
     const bool ok_a = group_cholesky(Ga, ld, r0, l);
@@ -327,7 +333,7 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_init_rows_kernel(PtqArgs 
 // ---- one sweep ----------------------------------------------------------------------------------------------------
 
 // LDS of the two row kernels: So [R*R], Ko [R*r0] (the other side's Gram pair), bs [R], fs, xs, cs, ys, then the per-group
-// matrices of the Tikhonov step (R x ld raw columns and R reciprocal pivots each).
+// matrices of the Tikhonov step (R x ld unscaled columns and R reciprocal pivots each).
 struct RowLds {
     double *So, *Ko, *bs, *fs, *xs, *cs, *ys, *H;
 };
@@ -344,11 +350,67 @@ __device__ inline RowLds carve_rows(int R, int r0) {
     return s;
 }
 
+// Solves H x = b for a symmetric positive definite R x R matrix by the lanes l = 0..R-1 of one group (the wave's lanes
+// base..base+gs-1).  Lane l passes column l of H in col[] (entries i >= l are used) and entry l of b, and receives entry
+// l of x.  Right-looking L D L^T factorisation with the columns in registers: a finished column is published once,
+// unscaled, to Hs (LDS, R x ld) together with the reciprocal of its pivot (rd, LDS, R), and the other lanes fold the
+// scaling into their rank-one updates; then forward substitution, the diagonal, backward substitution on lane
+// shuffles.  No square root and one reciprocal per column.  Returns the smallest pivot in *min_pivot.
+template <int RMAX>
+__device__ inline double group_ldlt_solve(double (&col)[RMAX], double b, double* Hs, double* rd, int ld, int R, int l, int base,
+                                          double* min_pivot) {
+    const bool act = l < R;
+    const int lc = act ? l : 0;  // a valid column for the idle lanes' reads
+    double* H = Hs;
+    double minp = INFINITY;
+#pragma unroll
+    for (int k = 0; k < RMAX; ++k) {
+        if (k < R) {
+            if (l == k) {
+#pragma unroll
+                for (int i = k; i < RMAX; ++i)
+                    if (i < R) H[i * ld + k] = col[i];
+            }
+            wave_sync();
+            const double pk = H[k * ld + k];
+            double ipk = __builtin_amdgcn_rcp(pk);       // 1 / pivot: hardware estimate and two Newton steps
+            ipk = fma(fma(-pk, ipk, 1.0), ipk, ipk);
+            ipk = fma(fma(-pk, ipk, 1.0), ipk, ipk);
+            if (l == k) rd[k] = ipk;
+            const double f = H[lc * ld + k] * ipk;
+#pragma unroll
+            for (int i = k + 1; i < RMAX; ++i)
+                if (i < R) col[i] -= (l > k && i >= l) ? H[i * ld + k] * f : 0.0;
+        }
+    }
+    wave_sync();
+    // H = L' D L'^T with D the pivots and L'[i][k] = H[i][k] / pivot_k (unit diagonal): no square root is needed.
+    // Forward substitution, the diagonal, then backward substitution; lane l carries entry l of the right-hand side.
+#pragma unroll
+    for (int k = 0; k < RMAX; ++k) {
+        if (k < R) {
+            const double zk = __shfl(b, base + k, 64) * rd[k];
+            if (l > k && act) b -= H[lc * ld + k] * zk;
+        }
+    }
+    const double ipl = rd[lc];
+    b *= ipl;
+#pragma unroll
+    for (int k = RMAX - 1; k >= 0; --k) {
+        if (k < R) {
+            const double xk = __shfl(b, base + k, 64);
+            if (l < k) b -= (H[k * ld + lc] * ipl) * xk;
+        }
+    }
+    *min_pivot = minp;
+    return b;
+}
+
 // Eq. (u-step-1) / Eq. (u-step-2) for one side: per row, (c^2 (beta beta^T o So) + rho_k I) u = c beta o (Ko f) + rho_k (M - Y),
 // then Eq. (m-y-step) for the same row: M = sign(u + Y), Y += u - M (a pending rescaling of Y after a penalty change is
 // applied on the way).  A group of lanes solves one row: lane l keeps column l of the matrix in registers through a
-// right-looking Cholesky factorisation; a finished column is published once, unscaled, to LDS together with the
-// reciprocal of its pivot's root, and the other lanes fold the scaling into their updates (no division but that one).
+// right-looking L D L^T factorisation; a finished column is published once, unscaled, to LDS together with the
+// reciprocal of its pivot, and the other lanes fold the scaling into their updates (no square root, one reciprocal).
 // `solve_waves` of the block's waves take part (as many as the LDS holds matrices for).
 template <int RMAX>  // the carrier rank is at most RMAX (16 or 32): the length of the register-resident column
 __global__ __launch_bounds__(kRowThreads) void lordba_ptq_ustep_kernel(PtqArgs a, int side, int solve_waves) {
@@ -357,7 +419,7 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_ustep_kernel(PtqArgs a
     const int64_t n = a.n[side], row0 = static_cast<int64_t>(blk) * kRows;
     const RowLds s = carve_rows(R, r0);
     const int count = R * R + R * r0;
-    reduce_shares(a.part[other], a.nb[other], a.pstride, count, s.So);  // So and Ko are adjacent
+    load_totals(a.tot[other], count, s.So);  // So and Ko are adjacent
     for (int k = threadIdx.x; k < R; k += kRowThreads) s.bs[k] = a.beta[k];
     load_factor_rows(a.F[side], n, r0, row0, s.fs);
     for (int row = threadIdx.x; row < kRows; row += kRowThreads) s.cs[row] = row0 + row < n ? a.scale[side][row0 + row] : 0.0;
@@ -392,43 +454,8 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_ustep_kernel(PtqArgs a
                 col[i] = 0.0;
                 if (i < R) col[i] = c2 * (s.bs[i] * bl) * s.So[i * R + lc] + (i == l ? rho_k : 0.0);
             }
-#pragma unroll
-            for (int k = 0; k < RMAX; ++k) {
-                if (k < R) {
-                    if (l == k) {
-#pragma unroll
-                        for (int i = k; i < RMAX; ++i)
-                            if (i < R) H[i * ld + k] = col[i];
-                    }
-                    wave_sync();
-                    const double rdk = 1.0 / sqrt(H[k * ld + k]);
-                    if (l == k) rd[k] = rdk;
-                    const double f = H[lc * ld + k] * (rdk * rdk);
-#pragma unroll
-                    for (int i = k + 1; i < RMAX; ++i)
-                        if (i < R) col[i] -= (l > k && i >= l) ? H[i * ld + k] * f : 0.0;
-                }
-            }
-            wave_sync();
-            // L[i][k] = H[i][k] rd[k].  Forward then backward substitution; lane l carries entry l of the right-hand side.
-#pragma unroll
-            for (int k = 0; k < RMAX; ++k) {
-                if (k < R) {
-                    const double rdk = rd[k];
-                    const double yk = __shfl(b, base + k, 64) * rdk;
-                    if (l == k) b = yk;
-                    if (l > k && act) b -= H[lc * ld + k] * (rdk * yk);
-                }
-            }
-            const double rdl = rd[lc];
-#pragma unroll
-            for (int k = RMAX - 1; k >= 0; --k) {
-                if (k < R) {
-                    const double xk = __shfl(b, base + k, 64) * rd[k];
-                    if (l == k) b = xk;
-                    if (l < k) b -= H[k * ld + lc] * (rdl * xk);
-                }
-            }
+            double min_pivot;   // positive: the matrix is a Gram matrix plus rho_k I
+            b = group_ldlt_solve<RMAX>(col, b, H, rd, ld, R, l, base, &min_pivot);
             if (act) {
                 const double x = b;
                 const double mn = (x + y_old) < 0.0 ? -1.0 : 1.0;
@@ -468,7 +495,7 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_scale_kernel(PtqArgs a
     const int R = a.R, r0 = a.r0, other = 1 - side, blk = blockIdx.x;
     const int64_t n = a.n[side], row0 = static_cast<int64_t>(blk) * kRows;
     const RowLds s = carve_rows(R, r0);
-    reduce_shares(a.part[other], a.nb[other], a.pstride, R * R + R * r0, s.So);
+    load_totals(a.tot[other], R * R + R * r0, s.So);
     for (int k = threadIdx.x; k < R; k += blockDim.x) s.bs[k] = a.beta[k];
     load_factor_rows(a.F[side], n, r0, row0, s.fs);
     for (int o = threadIdx.x; o < kRows * R; o += blockDim.x) s.xs[o] = row0 + o / R < n ? a.X[side][row0 * R + o] : 0.0;
@@ -520,8 +547,8 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a,
     double* h0 = hv + R;           // [R]
     double* bt = h0 + R;           // [R] result
     int* perm = reinterpret_cast<int*>(bt + R);
-    reduce_shares(a.part[0], a.nb[0], a.pstride, count + 2, P1);
-    reduce_shares(a.part[1], a.nb[1], a.pstride, count + 2, P2);
+    load_totals(a.tot[0], count + 2, P1);
+    load_totals(a.tot[1], count + 2, P2);
     __syncthreads();
     for (int o = threadIdx.x; o < R * R; o += blockDim.x) G[(o / R) * ld + o % R] = P1[o] * P2[o];
     for (int k = threadIdx.x; k < R; k += blockDim.x) {
@@ -537,8 +564,22 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a,
     double dmax = (l < R) ? G[l * ld + l] : 0.0;
     for (int m = 32; m >= 1; m >>= 1) dmax = fmax(dmax, __shfl_xor(dmax, m, 64));
     const double tol = 64.0 * 2.220446049250313e-16 * dmax;
+    // Fast path: G is positive definite whenever both sides' iterates have full column rank, so try the factorisation
+    // without pivoting first (columns in registers, N2 as its LDS area) and keep its result if every pivot clears the rank
+    // tolerance; G itself is left untouched for the pivoted factorisation below.
+    bool solved = false;
+    double x = 0.0;
+    if (R <= 16) {   // (the 32-entry column of the larger instantiation does not stay in registers here: those ranks pivot at once)
+        double col[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) col[i] = (i < R && l < R) ? G[i * ld + l] : 0.0;
+        double min_pivot;
+        const double xf = group_ldlt_solve<16>(col, l < R ? hv[l] : 0.0, N2, bt, ld, R, l, 0, &min_pivot);
+        wave_sync();
+        if (min_pivot > tol) { solved = true; x = xf; }
+    }
     int rank = 0;
-    for (int k = 0; k < R; ++k) {
+    for (int k = 0; k < R && !solved; ++k) {
         // largest remaining diagonal entry, ties to the smallest index
         double best = (l >= k && l < R) ? G[l * ld + l] : -1.0;
         int arg = l;
@@ -571,8 +612,8 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a,
         wave_sync();
         rank = k + 1;
     }
-    double x = 0.0;
-    if (rank == R) {
+    if (solved) {
+    } else if (rank == R) {
         x = group_solve(G, ld, R, l, 0, l < R ? hv[l] : 0.0);
     } else if (rank > 0) {
         double y = 0.0;
@@ -679,7 +720,7 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_fill_kernel(double* p, in
 }
 
 struct Layout {
-    size_t x[2], m[2], y[2], part[2], z[2], ctrl, total;
+    size_t x[2], m[2], y[2], part[2], tot[2], z[2], ctrl, total;
     int nb[2], pstride;
 };
 
@@ -695,6 +736,7 @@ Layout make_layout(int64_t N, int64_t M, int64_t R, int64_t r0) {
     for (int s = 0; s < 2; ++s) L.m[s] = take(n[s] * R);
     for (int s = 0; s < 2; ++s) L.y[s] = take(n[s] * R);
     for (int s = 0; s < 2; ++s) L.part[s] = take(static_cast<size_t>(L.nb[s]) * L.pstride);
+    for (int s = 0; s < 2; ++s) L.tot[s] = take(L.pstride);
     for (int s = 0; s < 2; ++s) L.z[s] = take(r0 * R);
     L.ctrl = take(kCtrlCount);
     L.total = off * sizeof(double);
@@ -761,6 +803,7 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
         a.Mm[s] = ws + L.m[s];
         a.Y[s] = ws + L.y[s];
         a.part[s] = ws + L.part[s];
+        a.tot[s] = ws + L.tot[s];
         a.Z[s] = ws + L.z[s];
     }
     a.scale[0] = alpha;
@@ -787,35 +830,53 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
     const size_t lds_beta = sizeof(double) * (2 * (iR * iR + iR * ir0 + 2) + 2 * iR * ldR + 3 * iR) + sizeof(int) * iR;
     const int nb01 = a.nb[0] + a.nb[1];
 
-    {   // more than 64 KiB of LDS per workgroup has to be asked for
-        const struct { const void* fn; size_t bytes; } big[] = {
-            {reinterpret_cast<const void*>(lordba_ptq_factor_gram_kernel), lds_gram}, {reinterpret_cast<const void*>(lordba_ptq_svd_kernel), lds_svd},
-            {reinterpret_cast<const void*>(lordba_ptq_init_rows_kernel), lds_init},
-            {reinterpret_cast<const void*>(iR <= 16 ? lordba_ptq_ustep_kernel<16> : lordba_ptq_ustep_kernel<32>), lds_rows},
-            {reinterpret_cast<const void*>(lordba_ptq_scale_kernel), lds_rows}, {reinterpret_cast<const void*>(lordba_ptq_beta_kernel), lds_beta}};
+    {   // More than 64 KiB of LDS per workgroup has to be asked for; the largest request so far is remembered per device and
+        // kernel, so that a call whose shapes the process has already seen makes no runtime call besides its launches
+        // (it can then be captured into a HIP graph).
+        static size_t granted[64][7];
+        const struct { const void* fn; size_t bytes; int slot; } big[] = {
+            {reinterpret_cast<const void*>(lordba_ptq_factor_gram_kernel), lds_gram, 0}, {reinterpret_cast<const void*>(lordba_ptq_svd_kernel), lds_svd, 1},
+            {reinterpret_cast<const void*>(lordba_ptq_init_rows_kernel), lds_init, 2},
+            {reinterpret_cast<const void*>(iR <= 16 ? lordba_ptq_ustep_kernel<16> : lordba_ptq_ustep_kernel<32>), lds_rows, iR <= 16 ? 3 : 4},
+            {reinterpret_cast<const void*>(lordba_ptq_scale_kernel), lds_rows, 5}, {reinterpret_cast<const void*>(lordba_ptq_beta_kernel), lds_beta, 6}};
         for (const auto& b : big) {
             if (b.bytes > 160 * 1024) return LORDBA_ERR_DIM;
-            if (b.bytes > 48 * 1024 &&
-                hipFuncSetAttribute(b.fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(b.bytes)) != hipSuccess)
-                return LORDBA_ERR_LAUNCH;
+            size_t& have = granted[dev & 63][b.slot];
+            if (b.bytes > 48 * 1024 && have < b.bytes) {
+                if (hipFuncSetAttribute(b.fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(b.bytes)) != hipSuccess)
+                    return LORDBA_ERR_LAUNCH;
+                have = b.bytes;
+            }
         }
     }
     hipLaunchKernelGGL(lordba_ptq_fill_kernel, dim3((kInfoHead + K + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, info,
                        kInfoHead + K, 0.0);
+    const int count = iR * iR + iR * ir0;
+    auto totals = [&](int side, int n, int always) {
+        hipLaunchKernelGGL(lordba_ptq_totals_kernel, dim3((n + 63) / 64), dim3(64), 0, stream, a, side, n, always);
+    };
     hipLaunchKernelGGL(lordba_ptq_factor_gram_kernel, dim3(nb01), dim3(kThreads), lds_gram, stream, a);
+    totals(0, ir0 * ir0, 1);
+    totals(1, ir0 * ir0, 1);
     hipLaunchKernelGGL(lordba_ptq_svd_kernel, dim3(1), dim3(64), lds_svd, stream, a);
     hipLaunchKernelGGL(lordba_ptq_init_rows_kernel, dim3(nb01), dim3(kThreads), lds_init, stream, a);
+    totals(1, count, 0);
     hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_rows, stream, a, 0);
+    totals(0, count, 0);
     hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_rows, stream, a, 1);
+    totals(1, count, 0);
     for (int t = 0; t < a.K; ++t) {
         for (int side = 0; side < 2; ++side) {
             if (iR <= 16)
                 hipLaunchKernelGGL(lordba_ptq_ustep_kernel<16>, dim3(a.nb[side]), dim3(kRowThreads), lds_rows, stream, a, side, solve_waves);
             else
                 hipLaunchKernelGGL(lordba_ptq_ustep_kernel<32>, dim3(a.nb[side]), dim3(kRowThreads), lds_rows, stream, a, side, solve_waves);
+            totals(side, count + 2, 0);
         }
         hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_rows, stream, a, 0);
+        totals(0, count, 0);
         hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_rows, stream, a, 1);
+        totals(1, count, 0);
         hipLaunchKernelGGL(lordba_ptq_beta_kernel, dim3(1), dim3(kRowThreads), lds_beta, stream, a, t);
     }
     ExportArgs e;

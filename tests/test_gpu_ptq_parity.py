@@ -184,6 +184,49 @@ def test_calls_are_reproducible_and_reuse_a_workspace(torch_cuda):
                                                torch.equal(torch.nan_to_num(first[k]), torch.nan_to_num(b[k]))), k
 
 
+def test_graph_replay_matches_eager(torch_cuda):
+    # a warmed-up call only launches kernels (no clearing by memset, no allocation, no wait): it can be captured; replays,
+    # with eager work of the same library in between, must give the eager result bit for bit
+    say("ptq graph replay")
+    torch = torch_cuda
+    d = inputs.make_ptq_inputs(19, 260, 200, 16)
+    A, B = torch.from_numpy(d["A_star"]).cuda(), torch.from_numpy(d["B_star"]).cuda()
+    ws = torch.empty(binding.lordba_ptq_workspace_bytes(260, 200, 12, 16) // 8, dtype=torch.float64, device="cuda:0")
+    eager = binding.lordba_ptq(A, B, 12, K=30, workspace=ws)
+    torch.cuda.synchronize()
+    want = {k: v.clone() for k, v in eager.items() if k != "workspace"}
+    import ctypes
+    lib = binding.load_library()
+    outs = ("packedA", "packedB", "alpha", "beta", "gamma", "s_in", "s_rank", "s_out", "info")
+
+    def scrub(held):
+        for k in outs:
+            held[k].fill_(float("nan")) if held[k].dtype.is_floating_point else held[k].fill_(-1)
+
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        held = binding.lordba_ptq(A, B, 12, K=30, workspace=ws, stream=side)     # allocates the outputs outside the capture
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            st = lib.lordba_ptq(A.data_ptr(), B.data_ptr(), held["packedA"].data_ptr(), held["packedB"].data_ptr(), held["alpha"].data_ptr(),
+                                held["beta"].data_ptr(), held["gamma"].data_ptr(), held["s_in"].data_ptr(), held["s_rank"].data_ptr(),
+                                held["s_out"].data_ptr(), held["info"].data_ptr(), ws.data_ptr(), ws.numel() * 8, 260, 200, 12, 16, 30, 2.0, 10.0,
+                                ctypes.c_void_p(side.cuda_stream))
+            assert st == 0
+    for rep in range(3):
+        scrub(held)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in outs:
+            assert torch.equal(held[k], want[k]), (rep, k)
+        # eager work between the replays: another problem in the same workspace
+        d2 = inputs.make_ptq_inputs(20 + rep, 100, 90, 8)
+        binding.lordba_ptq(torch.from_numpy(d2["A_star"]).cuda(), torch.from_numpy(d2["B_star"]).cuda(), 4, K=10, workspace=ws)
+        torch.cuda.synchronize()
+
+
 def test_degenerate_input_is_flagged(torch_cuda):
     say("ptq degenerate")
     torch = torch_cuda
