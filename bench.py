@@ -351,8 +351,7 @@ def bench_ptq(args):
     import numpy as np
     import torch
     from paper_2605_24058_amd import binding, inputs
-    N = M = 4096
-    R = r0 = 16
+    N, M, R, r0 = (int(v) for v in args.ptq_shape.split(","))
     Kadmm = 100
     K, W = args.steps, args.warmup
     sets = 4
@@ -374,11 +373,11 @@ def bench_ptq(args):
     mean_sweeps = sum(sweeps) / len(sweeps)
     flops = ptq_algorithmic_flops(N, M, R, r0, mean_sweeps)
     achieved = flops / (call_us * 1e-6) / 1e12
-    out = {"metric": "PTQ-LoRDBA projections/s (one 4096 x 4096 update, rank-16 factors -> carrier rank 16, K = 100)",
+    out = {"metric": "PTQ-LoRDBA projections/s (one %d x %d update, rank-%d factors -> carrier rank %d, K = 100)" % (N, M, r0, R),
            "value": K / wall_s, "unit": "projections/s", "n_gpus": 1, "steps": K, "warmup": W,
            "ms_per_step": wall_s * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f64", "io_dtype": "f16", "data": "synthetic",
-           "config": {"workload": "ptq_4096x4096_R16_r16_K100", "N": N, "M": M, "R": R, "r0": r0, "K": Kadmm, "tau": 2.0, "mu": 10.0,
+           "config": {"workload": "ptq_%dx%d_R%d_r%d_K100" % (N, M, R, r0), "N": N, "M": M, "R": R, "r0": r0, "K": Kadmm, "tau": 2.0, "mu": 10.0,
                       "sweeps_run": sweeps, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
            "roofline": {"bound": "alu", "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel_us": call_us,
@@ -387,7 +386,7 @@ def bench_ptq(args):
                                 "R x R and N x R operands and is bound by their latency, not by arithmetic or HBM"}}
     if not args.no_cpu_baseline:
         from oracle import ptq as P
-        n = 2048                      # a quarter of the projection: the dense oracle takes about 10 s there
+        n = min(2048, N, M)           # a quarter of the default projection: the dense oracle takes about 10 s there
         h = inputs.make_ptq_inputs(args.seed, n, n, r0)
         c0 = time.perf_counter()
         ref = P.ptq(h["A_star"], h["B_star"], R, K=Kadmm)
@@ -399,8 +398,8 @@ def bench_ptq(args):
         r1, r2, _ = P.canonical_gauge(ref["B1"], ref["B2"])
         same = bool(np.array_equal(g1, r1) and np.array_equal(g2, r2) and int(got["info"][0].item()) == ref["sweeps"])
         err = max(float(np.linalg.norm(got[k].cpu().numpy() - ref[k]) / np.linalg.norm(ref[k])) for k in ("alpha", "beta", "gamma"))
-        out["cpu_baseline"] = {"value": 1.0 / (c1 - c0), "unit": "projections/s of a 2048 x 2048 update", "cores": min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1)), "kind": "oracle",
-                               "sample": "one 2048 x 2048 update (a quarter of the workload's projection), same ranks and K; "
+        out["cpu_baseline"] = {"value": 1.0 / (c1 - c0), "unit": "projections/s of a %d x %d update" % (n, n), "cores": min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1)), "kind": "oracle",
+                               "sample": "one %d x %d update (a quarter of the default workload's projection), same ranks and K; " % (n, n) +
                                          "numpy's threaded BLAS on all host cores"}
         out["parity_signs_and_sweeps_exact"] = same
         out["parity_max_rel_l2_scales"] = err
@@ -430,6 +429,7 @@ def main():
                     "lordba_forward_save_t, lordba_backward with the kept t (implies --backward)")
     ap.add_argument("--ptq", action="store_true", help="time lordba_ptq (post-training quantisation of one 4096 x 4096 update) "
                     "instead of the forward pass")
+    ap.add_argument("--ptq-shape", default="4096,4096,16,16", help="--ptq: N,M,R,r0 (update N x M, carrier rank R, factor rank r0)")
     ap.add_argument("--keep-t", action="store_true", help="--backward: pass the rank-r intermediate kept by "
                     "lordba_forward_save_t instead of letting lordba_backward recompute it from x")
     ap.add_argument("--kappa", type=float, default=100.0, help="temperature of the smooth-sign factor (--backward)")

@@ -412,19 +412,20 @@ __device__ inline double group_ldlt_solve(double (&col)[RMAX], double b, double*
 // right-looking L D L^T factorisation; a finished column is published once, unscaled, to LDS together with the
 // reciprocal of its pivot, and the other lanes fold the scaling into their updates (no square root, one reciprocal).
 // `solve_waves` of the block's waves take part (as many as the LDS holds matrices for).
-template <int RMAX>  // the carrier rank is at most RMAX (16 or 32): the length of the register-resident column
-__global__ __launch_bounds__(kRowThreads) void lordba_ptq_ustep_kernel(PtqArgs a, int side, int solve_waves) {
+template <int RMAX>  // the carrier rank is at most RMAX (16 or 32): the length of the register-resident column; the larger one
+                     // runs with half the threads per block, so that a lane may hold twice the registers
+__global__ __launch_bounds__(RMAX <= 16 ? kRowThreads : kRowThreads / 2) void lordba_ptq_ustep_kernel(PtqArgs a, int side, int solve_waves) {
     if (a.ctrl[kDone] != 0.0) return;
     const int R = a.R, r0 = a.r0, other = 1 - side, blk = blockIdx.x;
     const int64_t n = a.n[side], row0 = static_cast<int64_t>(blk) * kRows;
     const RowLds s = carve_rows(R, r0);
     const int count = R * R + R * r0;
     load_totals(a.tot[other], count, s.So);  // So and Ko are adjacent
-    for (int k = threadIdx.x; k < R; k += kRowThreads) s.bs[k] = a.beta[k];
+    for (int k = threadIdx.x; k < R; k += blockDim.x) s.bs[k] = a.beta[k];
     load_factor_rows(a.F[side], n, r0, row0, s.fs);
-    for (int row = threadIdx.x; row < kRows; row += kRowThreads) s.cs[row] = row0 + row < n ? a.scale[side][row0 + row] : 0.0;
+    for (int row = threadIdx.x; row < kRows; row += blockDim.x) s.cs[row] = row0 + row < n ? a.scale[side][row0 + row] : 0.0;
     const double rho_k = a.ctrl[kRho] / (static_cast<double>(n) * R), yfac = a.ctrl[kYfac];
-    for (int o = threadIdx.x; o < kRows * R; o += kRowThreads) {   // xs holds M until the row is solved, ys the rescaled Y
+    for (int o = threadIdx.x; o < kRows * R; o += blockDim.x) {   // xs holds M until the row is solved, ys the rescaled Y
         const bool in = row0 + o / R < n;
         s.xs[o] = in ? a.Mm[side][row0 * R + o] : 0.0;
         s.ys[o] = in ? yfac * a.Y[side][row0 * R + o] : 0.0;
@@ -482,7 +483,7 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_ustep_kernel(PtqArgs a
     gram_share(s.xs, s.cs, s.fs, R, r0, share);
     if (threadIdx.x == 0) {
         double gsum = 0.0, fsum = 0.0;
-        for (int w = 0; w < kRowThreads / 64; ++w) { gsum += red[2 * w]; fsum += red[2 * w + 1]; }
+        for (int w = 0; w < static_cast<int>(blockDim.x >> 6); ++w) { gsum += red[2 * w]; fsum += red[2 * w + 1]; }
         share[count] = gsum;
         share[count + 1] = fsum;
     }
@@ -824,7 +825,8 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
     // the Tikhonov kernel: as many waves solve rows at once as the LDS has room for their matrices (8, 4, 2 or 1)
     const size_t lds_fixed = sizeof(double) * (iR * iR + iR * ir0 + iR + kRows * ir0 + 2 * kRows * iR + kRows);
     const size_t lds_wave = sizeof(double) * (64 / gs) * (iR * ldR + iR);
-    int solve_waves = kRowThreads / 64;
+    const int ustep_threads = iR <= 16 ? kRowThreads : kRowThreads / 2;
+    int solve_waves = ustep_threads / 64;
     while (solve_waves > 1 && lds_fixed + solve_waves * lds_wave > 160 * 1024) solve_waves >>= 1;
     const size_t lds_rows = lds_fixed + solve_waves * lds_wave;
     const size_t lds_beta = sizeof(double) * (2 * (iR * iR + iR * ir0 + 2) + 2 * iR * ldR + 3 * iR) + sizeof(int) * iR;
@@ -870,7 +872,7 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
             if (iR <= 16)
                 hipLaunchKernelGGL(lordba_ptq_ustep_kernel<16>, dim3(a.nb[side]), dim3(kRowThreads), lds_rows, stream, a, side, solve_waves);
             else
-                hipLaunchKernelGGL(lordba_ptq_ustep_kernel<32>, dim3(a.nb[side]), dim3(kRowThreads), lds_rows, stream, a, side, solve_waves);
+                hipLaunchKernelGGL(lordba_ptq_ustep_kernel<32>, dim3(a.nb[side]), dim3(ustep_threads), lds_rows, stream, a, side, solve_waves);
             totals(side, count + 2, 0);
         }
         hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_rows, stream, a, 0);
