@@ -165,6 +165,35 @@ def test_exported_adapter_runs_in_the_forward_kernel(torch_cuda):
     assert np.sum((T - W) ** 2) < 0.8 * np.sum(T * T)
 
 
+def test_quantised_adapter_trains_with_frozen_carriers(torch_cuda):
+    # the "freeze" training variant (Sec. 3.2, optional variants): carriers from post-training quantisation stay fixed, only
+    # the scales get gradients.  lordba_ptq -> lordba_forward_save_t -> lordba_backward without latents, against the
+    # backward oracle fed the same carriers and fp16 scales.
+    say("ptq -> forward -> backward with frozen carriers")
+    torch = torch_cuda
+    N, M, R, T = 256, 192, 8, 70
+    d = inputs.make_ptq_inputs(21, N, M, 8)
+    q = binding.lordba_ptq(torch.from_numpy(d["A_star"]).cuda(), torch.from_numpy(d["B_star"]).cuda(), R, K=30)
+    torch.cuda.synchronize()
+    sA, sB = binding.lordba_unpack_signs(q["packedA"].cpu().numpy().view(np.uint32), q["packedB"].cpu().numpy().view(np.uint32), N, M, R)
+    pAt, pBt = binding.lordba_pack_transposed(sA, sB)
+    cu = lambda a_: torch.from_numpy(np.ascontiguousarray(a_)).cuda()
+    b = inputs.make_backward_inputs(21, T, N, M, R)
+    x, g, yb, dxb = cu(b["x"]), cu(b["g"]), cu(b["y_base"]), cu(b["dx_base"])
+    y, t_kept = binding.lordba_forward_save_t(x, q["packedA"], q["packedB"], q["s_in"], q["s_rank"], q["s_out"], yb)
+    got = binding.lordba_backward(x, g, q["packedA"], cu(pAt.view(np.int32)), cu(pBt.view(np.int32)), q["s_in"], q["s_rank"], q["s_out"],
+                                  None, None, 100.0, dx_base=dxb, t_saved=t_kept)
+    torch.cuda.synchronize()
+    s_in, s_rank, s_out = (q[k].cpu().numpy() for k in ("s_in", "s_rank", "s_out"))
+    want_y = oracle.forward(b["x"], sA, sB, s_in, s_rank, s_out, b["y_base"])
+    assert oracle.row_rel_l2(y.cpu().numpy().astype(np.float64), want_y).max() <= 1e-3
+    want = oracle.backward(b["x"], b["g"], sA, sB, s_in, s_rank, s_out, b["latA"], b["latB"], 100.0, b["dx_base"])
+    assert oracle.row_rel_l2(got["dx"].cpu().numpy().astype(np.float64), want["dx"]).max() <= 1e-3
+    for k in ("d_s_in", "d_s_rank", "d_s_out"):
+        assert oracle.rel_l2(got[k].cpu().numpy(), want[k]) <= 1e-3, k
+    assert got["d_latentA"] is None and got["d_latentB"] is None
+
+
 def test_calls_are_reproducible_and_reuse_a_workspace(torch_cuda):
     say("ptq reproducible")
     torch = torch_cuda
