@@ -74,3 +74,70 @@ def test_pack_round_trip_and_bit_positions(rows, cols, seed):
     assert w.size == (rows * cols + 31) // 32
     if (rows * cols) % 32:
         assert int(w[-1]) >> ((rows * cols) % 32) == 0                               # pad bits are zero
+
+
+# ---- post-training quantisation (oracle/ptq.py): properties over random small problems ---------------------------------
+
+ptq_shape = st.tuples(st.integers(2, 14), st.integers(2, 14), st.integers(1, 4), st.integers(0, 10 ** 6))
+
+
+@settings(max_examples=30, deadline=None)
+@given(ptq_shape)
+def test_ptq_updates_are_coordinate_minimisers(s):
+    """Each closed-form update minimises the objective over its block: no random move of that block lowers it, and the
+    Tikhonov steps do the same for their augmented objectives."""
+    from oracle import ptq as P
+    N, M, R, seed = s
+    g = np.random.default_rng(seed)
+    T = g.standard_normal((N, M))
+    U1, U2 = g.standard_normal((N, R)), g.standard_normal((R, M))
+    a, b, c = g.standard_normal(N), g.standard_normal(R), g.standard_normal(M)
+    f = lambda a_, b_, c_, U1_=U1, U2_=U2: P.objective(T, a_, U1_, b_, U2_, c_)
+    a1 = P.alpha_update(T, U1, b, U2, c)
+    c1 = P.gamma_update(T, a1, U1, b, U2)
+    b1 = P.beta_update(T, a1, U1, U2, c1)
+    assert f(a, b, c) >= f(a1, b, c) * (1 - 1e-12) and f(a1, b, c) >= f(a1, b, c1) * (1 - 1e-12) >= 0
+    assert f(a1, b, c1) >= f(a1, b1, c1) * (1 - 1e-12)
+    slack = 1e-12 * max(np.sum(T * T), 1.0)   # (a flat direction leaves the objective unchanged up to rounding)
+    for _ in range(3):
+        assert f(a1 + 1e-3 * g.standard_normal(N), b, c) >= f(a1, b, c) - slack
+        assert f(a1, b, c1 + 1e-3 * g.standard_normal(M)) >= f(a1, b, c1) - slack
+        assert f(a1, b1 + 1e-3 * g.standard_normal(R), c1) >= f(a1, b1, c1) - slack
+    M1, Y1 = P.sgn(g.standard_normal((N, R))), 0.2 * g.standard_normal((N, R))
+    rho = float(g.uniform(0.05, 2.0))
+    X1 = P.u1_step(T, a, b, U2, c, rho, M1, Y1)
+    aug = lambda X: f(a, b, c, U1_=X) + 0.5 * rho * np.sum((X - M1 + Y1) ** 2)
+    for _ in range(3):
+        assert aug(X1 + 1e-3 * g.standard_normal((N, R))) > aug(X1)
+    M2, Y2 = P.sgn(g.standard_normal((R, M))), 0.2 * g.standard_normal((R, M))
+    X2 = P.u2_step(T, a, X1, b, c, rho, M2, Y2)
+    aug2 = lambda X: f(a, b, c, U1_=X1, U2_=X) + 0.5 * rho * np.sum((X - M2 + Y2) ** 2)
+    for _ in range(3):
+        assert aug2(X2 + 1e-3 * g.standard_normal((R, M))) > aug2(X2)
+
+
+@settings(max_examples=20, deadline=None)
+@given(st.integers(4, 24), st.integers(4, 24), st.integers(1, 4), st.integers(0, 10 ** 6))
+def test_ptq_run_invariants(N, M, R, seed):
+    """A whole run: +-1 outputs, the recorded objective, and dependence on the factors through their product only
+    (negating a column of both factors changes nothing)."""
+    from oracle import ptq as P
+    r0 = 4
+    d = inputs.make_ptq_inputs(seed, N, M, r0)
+    A, B = d["A_star"].astype(np.float64), d["B_star"].astype(np.float64)
+    tr = []
+    out = P.ptq(A, B, R, K=12, trace=tr)
+    assert np.all(np.abs(out["B1"]) == 1) and np.all(np.abs(out["B2"]) == 1)
+    assert out["sweeps"] == len(tr) == len(out["objective"]) <= 12
+    T = A @ B.T
+    last = tr[-1]
+    assert np.isclose(out["objective"][-1], P.objective(T, last["alpha"], last["U1"], last["beta"], last["U2"], last["gamma"]), rtol=1e-9,
+                      atol=1e-14 * np.sum(T * T))
+    # the target A B^T does not change when a column of A and the same column of B are both negated: same run
+    A2, B2 = A.copy(), B.copy()
+    A2[:, 0] *= -1
+    B2[:, 0] *= -1
+    out2 = P.ptq(A2, B2, R, K=12)
+    g1, g2, _ = P.canonical_gauge(out["B1"], out["B2"])
+    h1, h2, _ = P.canonical_gauge(out2["B1"], out2["B2"])
+    assert out2["sweeps"] == out["sweeps"] and np.array_equal(g1, h1) and np.array_equal(g2, h2)
