@@ -17,7 +17,9 @@ vectorised problem and against the vanishing gradient of its objective (torch au
 likewise; rank-one targets are fitted exactly by the warm start; the objective never rises in a scale sweep; the
 minimum-norm property of the beta update on a planted singular system; the result never beats the brute-force optimum
 over all sign patterns on tiny inputs and reaches it where the optimum is unique and known; the penalty is constant on
-the second half of the run and moves only by factors of tau; mistakes planted in each update are caught.
+the second half of the run and moves only by factors of tau; with the loop's break switched off the sign matrices stop
+changing within 50 sweeps, stay so, and the iterates converge on the fixed-penalty tail (the paper's statements on finite
+stabilisation); mistakes planted in each update are caught.
 
 Readings of the paper taken here (the product takes the same ones):
   * sign(0) = +1 (the packed format stores a sign bit).
@@ -126,11 +128,12 @@ def warm_start(T, R):
     return U1, U2, alpha, beta, gamma
 
 
-def ptq(A_star, B_star, R, K=100, tau=2.0, mu=10.0, trace=None):
+def ptq(A_star, B_star, R, K=100, tau=2.0, mu=10.0, trace=None, stop_on_freeze=True):
     """Alg. PTQ-LoRDBA.  A_star [N, r0], B_star [M, r0] (any float dtype, taken to fp64); returns a dict with the sign
     matrices B1 [N, R], B2 [R, M] (+-1 as fp64), alpha [N], beta [R], gamma [M], the number of sweeps run, whether the
     loop ended on equal sign matrices, the penalty it ended with, and the objective of Eq. (admm-problem) at the continuous
-    U after each sweep's scale update.  `trace`, if a list, receives a copy of the state after every sweep."""
+    U after each sweep's scale update.  `trace`, if a list, receives a copy of the state after every sweep.
+    stop_on_freeze=False runs all K sweeps (the algorithm's loop without its break), for looking at the tail."""
     A = np.asarray(A_star, dtype=np.float64)
     B = np.asarray(B_star, dtype=np.float64)
     N, r0 = A.shape
@@ -176,7 +179,8 @@ def ptq(A_star, B_star, R, K=100, tau=2.0, mu=10.0, trace=None):
                               alpha=alpha.copy(), beta=beta.copy(), gamma=gamma.copy(), rho=rho))
         if same:
             frozen = True
-            break
+            if stop_on_freeze:
+                break
     return dict(B1=M1, B2=M2, alpha=alpha, beta=beta, gamma=gamma, sweeps=sweeps, frozen=frozen, rho=rho,
                 objective=np.array(f_hist), U1=U1, U2=U2, Y1=Y1, Y2=Y2)
 

@@ -267,3 +267,25 @@ def test_rank_larger_than_the_factors_is_refused():
     d = inputs.make_ptq_inputs(0, 16, 16, 4)
     with pytest.raises(ValueError):
         P.ptq(d["A_star"], d["B_star"], 5)
+
+
+@pytest.mark.parametrize("seed,N,M,R,r0", [(0, 96, 80, 6, 8), (1, 200, 160, 8, 8), (2, 300, 300, 16, 16)])
+def test_signs_stabilise_within_fifty_sweeps_and_the_tail_converges(seed, N, M, R, r0):
+    """What the paper states about the run (paragraph on finite stabilisation on a fixed-penalty tail): the sign
+    matrices stop changing after finitely many sweeps, at most about 50 in its experiments, and stay so on the
+    fixed-penalty tail, where the iterates converge to a single limit.  Checked with the loop's break switched off."""
+    d = inputs.make_ptq_inputs(seed, N, M, r0)
+    K = 100
+    tr = []
+    out = P.ptq(d["A_star"], d["B_star"], R, K=K, trace=tr, stop_on_freeze=False)
+    assert len(tr) == K and out["frozen"]
+    changes = [int((tr[t]["M1"] != tr[t - 1]["M1"]).sum() + (tr[t]["M2"] != tr[t - 1]["M2"]).sum()) for t in range(1, K)]
+    first_still = next(t for t, c in enumerate(changes, start=1) if c == 0)
+    assert first_still <= 50
+    assert all(c == 0 for c in changes[first_still - 1:])                 # once still, still for the rest of the run
+    stopped = P.ptq(d["A_star"], d["B_star"], R, K=K)                     # the loop with its break ends exactly there
+    assert stopped["sweeps"] == first_still + 1 and np.array_equal(stopped["B1"], tr[first_still]["M1"])
+    assert all(tr[t]["rho"] == tr[K // 2]["rho"] for t in range(K // 2, K))
+    step = [np.linalg.norm(tr[t]["U1"] - tr[t - 1]["U1"]) + np.linalg.norm(tr[t]["U2"] - tr[t - 1]["U2"]) for t in range(K // 2, K)]
+    assert step[-1] <= 1e-10 * np.linalg.norm(tr[-1]["U1"])
+    assert abs(out["objective"][-1] - out["objective"][K // 2]) <= 1e-9 * out["objective"][-1]
