@@ -366,10 +366,73 @@ def bench_ptq(args):
         outs[s_] = binding.lordba_ptq(dev[s_][0], dev[s_][1], R, K=Kadmm, workspace=ws)
 
     use_graph = not args.no_graph
-    reps_us, wall_s = timed(step, K, W, use_graph, reps=3)
+    S = max(1, args.ptq_streams)
+    C = args.ptq_chunk
+    if S > 1 or C > 0:
+        # Several projections at once: one call is a chain of short dependent launches that leaves most of the chip idle,
+        # and it never waits for the device, so independent calls on separate streams (each with its own workspace and
+        # outputs, each captured into its own HIP graph) overlap.  K calls are dealt round-robin to the S streams.
+        # With --ptq-chunk C a run is enqueued in two pieces (lordba_ptq_sweeps): sweeps [0, C), then the host waits for
+        # that stream, reads the end flag, and enqueues [C, K) only if the loop has not ended yet.
+        streams = [torch.cuda.Stream() for _ in range(S)]
+        graphs, rest, held = [], [], []
+        first = (0, C) if C > 0 else (0, Kadmm)
+        for j in range(S):
+            A_, B_ = dev[j % sets]
+            with torch.cuda.stream(streams[j]):
+                o = binding.lordba_ptq(A_, B_, R, K=Kadmm, stream=streams[j])       # allocates outputs and workspace; warms up
+                streams[j].synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=streams[j]):
+                    binding.lordba_ptq(A_, B_, R, K=Kadmm, stream=streams[j], sweeps=first, out=o)
+                g2 = None
+                if C > 0:
+                    g2 = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g2, stream=streams[j]):
+                        binding.lordba_ptq(A_, B_, R, K=Kadmm, stream=streams[j], sweeps=(C, Kadmm), out=o)
+            graphs.append(g); rest.append(g2); held.append(o)
+            outs[j % sets] = o
+        torch.cuda.synchronize()
+        continued = 0
+
+        def finish(j):
+            nonlocal continued
+            if C > 0:
+                streams[j].synchronize()
+                if held[j]["info"][1].item() == 0.0:      # the loop has not ended within the first piece
+                    continued += 1
+                    with torch.cuda.stream(streams[j]):
+                        rest[j].replay()
+
+        reps_us = []
+        wall_s = None
+        for _ in range(3):
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            a0.record()
+            for j in range(S):
+                streams[j].wait_event(a0)
+            for i in range(K):
+                j = i % S
+                if i >= S:
+                    finish(j)                               # the call this stream was given a round ago
+                with torch.cuda.stream(streams[j]):
+                    graphs[j].replay()
+            for j in range(min(S, K)):
+                finish(j)
+            for j in range(S):
+                torch.cuda.current_stream().wait_stream(streams[j])
+            a1.record()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            reps_us.append(a0.elapsed_time(a1) * 1e3 / K)
+            wall_s = wall_s if wall_s is not None else t1 - t0
+    else:
+        reps_us, wall_s = timed(step, K, W, use_graph, reps=3)
     torch.cuda.synchronize()
     call_us = reps_us[0]
-    sweeps = [int(outs[s_]["info"][0].item()) for s_ in sorted(outs)]
+    sweeps = [int(outs[s_]["info"][0].item()) for s_ in outs if not isinstance(s_, tuple)]
     mean_sweeps = sum(sweeps) / len(sweeps)
     flops = ptq_algorithmic_flops(N, M, R, r0, mean_sweeps)
     achieved = flops / (call_us * 1e-6) / 1e12
@@ -378,7 +441,8 @@ def bench_ptq(args):
            "ms_per_step": wall_s * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f64", "io_dtype": "f16", "data": "synthetic",
            "config": {"workload": "ptq_%dx%d_R%d_r%d_K100" % (N, M, R, r0), "N": N, "M": M, "R": R, "r0": r0, "K": Kadmm, "tau": 2.0, "mu": 10.0,
-                      "sweeps_run": sweeps, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
+                      "sweeps_run": sweeps, "launch": "hip_graph" if (use_graph or S > 1) else "eager", "concurrent_streams": S,
+                      "pieces": ("[0, %d) then, after a look at the end flag, [%d, %d)" % (C, C, Kadmm)) if C > 0 else "one call", "seed": args.seed},
            "roofline": {"bound": "alu", "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel_us": call_us,
                         "kernel_us_repetitions": reps_us, "algorithmic_flops": flops,
@@ -429,6 +493,10 @@ def main():
                     "lordba_forward_save_t, lordba_backward with the kept t (implies --backward)")
     ap.add_argument("--ptq", action="store_true", help="time lordba_ptq (post-training quantisation of one 4096 x 4096 update) "
                     "instead of the forward pass")
+    ap.add_argument("--ptq-streams", type=int, default=1, help="--ptq: this many projections in flight at once, one stream and "
+                    "one HIP graph each")
+    ap.add_argument("--ptq-chunk", type=int, default=0, help="--ptq: enqueue the first this many sweeps, wait, and enqueue the rest "
+                    "only if the loop has not ended (lordba_ptq_sweeps); 0 = one call of all K sweeps that never waits")
     ap.add_argument("--ptq-shape", default="4096,4096,16,16", help="--ptq: N,M,R,r0 (update N x M, carrier rank R, factor rank r0)")
     ap.add_argument("--keep-t", action="store_true", help="--backward: pass the rank-r intermediate kept by "
                     "lordba_forward_save_t instead of letting lordba_backward recompute it from x")

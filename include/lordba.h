@@ -299,6 +299,21 @@ lordba_status lordba_ptq(const void* A_star, const void* B_star, uint32_t* packe
                          double* info, void* workspace, size_t workspace_bytes,
                          int64_t N, int64_t M, int64_t R, int64_t r0, int64_t K, double tau, double mu, void* stream);
 
+/* DEVICE function: lordba_ptq enqueued in pieces.  Enqueues the sweeps t_begin <= t < t_end of a run of K sweeps (the
+ * schedule of the penalty depends on K, not on the piece) and then the export; t_begin == 0 also enqueues the warm
+ * start.  A call with t_begin > 0 continues the run whose state the workspace and the output arrays hold: it takes the
+ * same arguments as the call before it (same pointers, shapes, K, tau, mu) and t_begin equal to that call's t_end, and
+ * nothing else may have written to them in between.  After every piece the outputs describe the run so far (info[0]
+ * sweeps, info[1] the end flag, ...), so a caller that is willing to wait can enqueue the typical number of sweeps,
+ * look at info[1], and enqueue the rest only if the loop has not ended: the result is bit for bit that of lordba_ptq
+ * (which is this function with t_begin = 0, t_end = K), without the launches that would return at once.
+ * 0 <= t_begin <= t_end <= K, else LORDBA_ERR_DIM; everything else as lordba_ptq. */
+lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_star, uint32_t* packedA, uint32_t* packedB,
+                                double* alpha, double* beta, double* gamma, void* s_in, void* s_rank, void* s_out,
+                                double* info, void* workspace, size_t workspace_bytes,
+                                int64_t N, int64_t M, int64_t R, int64_t r0, int64_t K, int64_t t_begin, int64_t t_end,
+                                double tau, double mu, void* stream);
+
 /* Bytes of workspace lordba_ptq needs for a shape (0 for a shape it does not support). */
 size_t lordba_ptq_workspace_bytes(int64_t N, int64_t M, int64_t R, int64_t r0);
 

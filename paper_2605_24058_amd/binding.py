@@ -151,6 +151,8 @@ def load_library():
     lib.lordba_ptq_workspace_bytes.argtypes = [i64] * 4
     lib.lordba_ptq.restype = ci
     lib.lordba_ptq.argtypes = [vp] * 12 + [ctypes.c_size_t] + [i64] * 5 + [ctypes.c_double, ctypes.c_double, vp]
+    lib.lordba_ptq_sweeps.restype = ci
+    lib.lordba_ptq_sweeps.argtypes = [vp] * 12 + [ctypes.c_size_t] + [i64] * 7 + [ctypes.c_double, ctypes.c_double, vp]
     lib.lordba_status_string.restype = ctypes.c_char_p
     lib.lordba_status_string.argtypes = [ci]
     _lib = lib
@@ -545,12 +547,14 @@ def lordba_ptq_workspace_bytes(N: int, M: int, R: int, r0: int) -> int:
     return int(load_library().lordba_ptq_workspace_bytes(N, M, R, r0))
 
 
-def lordba_ptq(A_star, B_star, R: int, K: int = 100, tau: float = 2.0, mu: float = 10.0, workspace=None, stream=None):
+def lordba_ptq(A_star, B_star, R: int, K: int = 100, tau: float = 2.0, mu: float = 10.0, workspace=None, stream=None,
+               sweeps=None, out=None):
     """Post-training quantisation of the update A_star B_star^T (torch CUDA float16 tensors [N, r0], [M, r0]) into a LoRDBA
     adapter of carrier rank R: lordba_ptq of the C interface.  Returns a dict of CUDA tensors: packedA, packedB (int32,
     the canonical format, as lordba_forward takes them), alpha [N], beta [R], gamma [M] (float64), s_in, s_rank, s_out
     (float16), info (float64 [8 + K], see include/lordba.h), and U1 [N, R], U2t [M, R] (float64 views into the workspace: the
-    last continuous iterates)."""
+    last continuous iterates).  sweeps = (t_begin, t_end) enqueues only that piece of the run (lordba_ptq_sweeps); a piece
+    with t_begin > 0 continues the run of the dict `out` a previous piece returned (its tensors and workspace are reused)."""
     import torch
 
     lib = load_library()
@@ -560,9 +564,14 @@ def lordba_ptq(A_star, B_star, R: int, K: int = 100, tau: float = 2.0, mu: float
         raise ValueError("need float16 A_star [N, r0] and B_star [M, r0]")
     dev = A_star.device
     need = lordba_ptq_workspace_bytes(N, M, R, r0)
+    t_begin, t_end = (0, K) if sweeps is None else sweeps
+    if out is not None:
+        workspace = out["workspace"]
+    elif t_begin != 0:
+        raise ValueError("a piece that continues a run needs the dict the previous piece returned (out=...)")
     if workspace is None:
         workspace = torch.empty(max(need, 8) // 8, dtype=torch.float64, device=dev)
-    out = {
+    out = out if out is not None else {
         "packedA": torch.empty(max((R * N + 31) // 32, 1), dtype=torch.int32, device=dev),
         "packedB": torch.empty(max((M * R + 31) // 32, 1), dtype=torch.int32, device=dev),
         "alpha": torch.empty(max(N, 1), dtype=torch.float64, device=dev),
@@ -577,13 +586,13 @@ def lordba_ptq(A_star, B_star, R: int, K: int = 100, tau: float = 2.0, mu: float
         stream = torch.cuda.current_stream(dev).cuda_stream
     elif hasattr(stream, "cuda_stream"):
         stream = stream.cuda_stream
-    st = lib.lordba_ptq(A_star.contiguous().data_ptr(), B_star.contiguous().data_ptr(), out["packedA"].data_ptr(),
-                        out["packedB"].data_ptr(), out["alpha"].data_ptr(), out["beta"].data_ptr(), out["gamma"].data_ptr(),
-                        out["s_in"].data_ptr(), out["s_rank"].data_ptr(), out["s_out"].data_ptr(), out["info"].data_ptr(),
-                        workspace.data_ptr(), workspace.numel() * workspace.element_size(), N, M, R, r0, K, tau, mu,
-                        ctypes.c_void_p(stream))
+    st = lib.lordba_ptq_sweeps(A_star.contiguous().data_ptr(), B_star.contiguous().data_ptr(), out["packedA"].data_ptr(),
+                               out["packedB"].data_ptr(), out["alpha"].data_ptr(), out["beta"].data_ptr(), out["gamma"].data_ptr(),
+                               out["s_in"].data_ptr(), out["s_rank"].data_ptr(), out["s_out"].data_ptr(), out["info"].data_ptr(),
+                               workspace.data_ptr(), workspace.numel() * workspace.element_size(), N, M, R, r0, K, t_begin, t_end,
+                               tau, mu, ctypes.c_void_p(stream))
     if st != 0:
-        raise LordbaError(st, "lordba_ptq")
+        raise LordbaError(st, "lordba_ptq_sweeps")
     off2 = (N * R + 31) // 32 * 32
     ws = workspace.view(torch.float64) if workspace.dtype != torch.float64 else workspace
     out["U1"] = ws[:N * R].view(N, R)

@@ -756,11 +756,12 @@ extern "C" size_t lordba_ptq_workspace_bytes(int64_t N, int64_t M, int64_t R, in
     return make_layout(N, M, R, r0).total;
 }
 
-extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint32_t* packedA, uint32_t* packedB,
-                                    double* alpha, double* beta, double* gamma, void* s_in, void* s_rank, void* s_out,
-                                    double* info, void* workspace, size_t workspace_bytes, int64_t N, int64_t M, int64_t R,
-                                    int64_t r0, int64_t K, double tau, double mu, void* stream_) {
-    if (!dims_ok(N, M, R, r0, K)) return LORDBA_ERR_DIM;
+extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_star, uint32_t* packedA, uint32_t* packedB,
+                                           double* alpha, double* beta, double* gamma, void* s_in, void* s_rank, void* s_out,
+                                           double* info, void* workspace, size_t workspace_bytes, int64_t N, int64_t M, int64_t R,
+                                           int64_t r0, int64_t K, int64_t t_begin, int64_t t_end, double tau, double mu,
+                                           void* stream_) {
+    if (!dims_ok(N, M, R, r0, K) || t_begin < 0 || t_end < t_begin || t_end > K) return LORDBA_ERR_DIM;
     if (!(tau > 1.0) || !(mu > 0.0) || !(tau < 1e6) || !(mu < 1e12)) return LORDBA_ERR_VALUE;
     if (!A_star || !B_star || !packedA || !packedB || !alpha || !beta || !gamma || !info || !workspace) return LORDBA_ERR_NULL;
     const uintptr_t p16 = reinterpret_cast<uintptr_t>(A_star) | reinterpret_cast<uintptr_t>(B_star) |
@@ -822,7 +823,8 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
     const size_t lds_svd = sizeof(double) * (4 * ir0 * ld0 + ir0) + sizeof(int) * ir0;
     const size_t lds_init = sizeof(double) * (kRows * ir0 + kRows * iR + kRows + ir0 * iR);
     const int gs = iR <= 16 ? 16 : 32;
-    // the Tikhonov kernel: as many waves solve rows at once as the LDS has room for their matrices (8, 4, 2 or 1)
+    // the Tikhonov kernel: as many waves solve rows at once as the LDS has room for their matrices (8, 4, 2 or 1); the scale
+    // kernel has the same layout without the matrices
     const size_t lds_fixed = sizeof(double) * (iR * iR + iR * ir0 + iR + kRows * ir0 + 2 * kRows * iR + kRows);
     const size_t lds_wave = sizeof(double) * (64 / gs) * (iR * ldR + iR);
     const int ustep_threads = iR <= 16 ? kRowThreads : kRowThreads / 2;
@@ -840,7 +842,7 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
             {reinterpret_cast<const void*>(lordba_ptq_factor_gram_kernel), lds_gram, 0}, {reinterpret_cast<const void*>(lordba_ptq_svd_kernel), lds_svd, 1},
             {reinterpret_cast<const void*>(lordba_ptq_init_rows_kernel), lds_init, 2},
             {reinterpret_cast<const void*>(iR <= 16 ? lordba_ptq_ustep_kernel<16> : lordba_ptq_ustep_kernel<32>), lds_rows, iR <= 16 ? 3 : 4},
-            {reinterpret_cast<const void*>(lordba_ptq_scale_kernel), lds_rows, 5}, {reinterpret_cast<const void*>(lordba_ptq_beta_kernel), lds_beta, 6}};
+            {reinterpret_cast<const void*>(lordba_ptq_scale_kernel), lds_fixed, 5}, {reinterpret_cast<const void*>(lordba_ptq_beta_kernel), lds_beta, 6}};
         for (const auto& b : big) {
             if (b.bytes > 160 * 1024) return LORDBA_ERR_DIM;
             size_t& have = granted[dev & 63][b.slot];
@@ -851,23 +853,25 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
             }
         }
     }
-    hipLaunchKernelGGL(lordba_ptq_fill_kernel, dim3((kInfoHead + K + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, info,
-                       kInfoHead + K, 0.0);
     const int count = iR * iR + iR * ir0;
     auto totals = [&](int side, int n, int always) {
         hipLaunchKernelGGL(lordba_ptq_totals_kernel, dim3((n + 63) / 64), dim3(64), 0, stream, a, side, n, always);
     };
-    hipLaunchKernelGGL(lordba_ptq_factor_gram_kernel, dim3(nb01), dim3(kThreads), lds_gram, stream, a);
-    totals(0, ir0 * ir0, 1);
-    totals(1, ir0 * ir0, 1);
-    hipLaunchKernelGGL(lordba_ptq_svd_kernel, dim3(1), dim3(64), lds_svd, stream, a);
-    hipLaunchKernelGGL(lordba_ptq_init_rows_kernel, dim3(nb01), dim3(kThreads), lds_init, stream, a);
-    totals(1, count, 0);
-    hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_rows, stream, a, 0);
-    totals(0, count, 0);
-    hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_rows, stream, a, 1);
-    totals(1, count, 0);
-    for (int t = 0; t < a.K; ++t) {
+    if (t_begin == 0) {   // the warm start; a later call continues from the state the workspace holds
+        hipLaunchKernelGGL(lordba_ptq_fill_kernel, dim3((kInfoHead + K + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, info,
+                           kInfoHead + K, 0.0);
+        hipLaunchKernelGGL(lordba_ptq_factor_gram_kernel, dim3(nb01), dim3(kThreads), lds_gram, stream, a);
+        totals(0, ir0 * ir0, 1);
+        totals(1, ir0 * ir0, 1);
+        hipLaunchKernelGGL(lordba_ptq_svd_kernel, dim3(1), dim3(64), lds_svd, stream, a);
+        hipLaunchKernelGGL(lordba_ptq_init_rows_kernel, dim3(nb01), dim3(kThreads), lds_init, stream, a);
+        totals(1, count, 0);
+        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_fixed, stream, a, 0);
+        totals(0, count, 0);
+        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_fixed, stream, a, 1);
+        totals(1, count, 0);
+    }
+    for (int t = static_cast<int>(t_begin); t < static_cast<int>(t_end); ++t) {
         for (int side = 0; side < 2; ++side) {
             if (iR <= 16)
                 hipLaunchKernelGGL(lordba_ptq_ustep_kernel<16>, dim3(a.nb[side]), dim3(kRowThreads), lds_rows, stream, a, side, solve_waves);
@@ -875,9 +879,9 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
                 hipLaunchKernelGGL(lordba_ptq_ustep_kernel<32>, dim3(a.nb[side]), dim3(ustep_threads), lds_rows, stream, a, side, solve_waves);
             totals(side, count + 2, 0);
         }
-        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_rows, stream, a, 0);
+        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_fixed, stream, a, 0);
         totals(0, count, 0);
-        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_rows, stream, a, 1);
+        hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_fixed, stream, a, 1);
         totals(1, count, 0);
         hipLaunchKernelGGL(lordba_ptq_beta_kernel, dim3(1), dim3(kRowThreads), lds_beta, stream, a, t);
     }
@@ -895,4 +899,12 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
     if (most < kCtrlCount) most = kCtrlCount;
     hipLaunchKernelGGL(lordba_ptq_export_kernel, dim3(static_cast<unsigned>((most + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, a, e);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
+}
+
+extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint32_t* packedA, uint32_t* packedB,
+                                    double* alpha, double* beta, double* gamma, void* s_in, void* s_rank, void* s_out,
+                                    double* info, void* workspace, size_t workspace_bytes, int64_t N, int64_t M, int64_t R,
+                                    int64_t r0, int64_t K, double tau, double mu, void* stream) {
+    return lordba_ptq_sweeps(A_star, B_star, packedA, packedB, alpha, beta, gamma, s_in, s_rank, s_out, info, workspace,
+                             workspace_bytes, N, M, R, r0, K, 0, K, tau, mu, stream);
 }

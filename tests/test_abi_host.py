@@ -189,6 +189,10 @@ def test_ptq_validation_needs_no_device(lib):
     assert call(A=p["A"] + 1) == 5 and call(pA=p["pA"] + 2) == 5 and call(al=p["al"] + 4) == 5 and call(ws=p["ws"] + 4) == 5
     assert call(al=p["A"]) == 4 and call(ws=p["B"]) == 4 and call(ga=p["al"]) == 4 and call(info=p["ws"]) == 4
     assert call(si=p["sr"]) == 4
+    piece = lambda t0, t1: lib.lordba_ptq_sweeps(p["A"], p["B"], p["pA"], p["pB"], p["al"], p["be"], p["ga"], p["si"], p["sr"], p["so"],
+                                                 p["info"], p["ws"], need - 8, N, M, R, r0, K, t0, t1, ctypes.c_double(2.0),
+                                                 ctypes.c_double(10.0), None)
+    assert piece(-1, 5) == 2 and piece(6, 5) == 2 and piece(0, K + 1) == 2 and piece(3, 7) == 9   # the range, then the workspace size
 
 
 def test_forward_multi_validation_needs_no_device(lib):

@@ -213,6 +213,28 @@ def test_calls_are_reproducible_and_reuse_a_workspace(torch_cuda):
                                                torch.equal(torch.nan_to_num(first[k]), torch.nan_to_num(b[k]))), k
 
 
+def test_a_run_enqueued_in_pieces_is_the_same_run(torch_cuda):
+    # lordba_ptq_sweeps: [0, 5) + [5, 6) + [6, 40) against one call of 40 sweeps, bit for bit; the outputs after the first
+    # piece are those of the run stopped there (same penalty schedule: K stays 40)
+    say("ptq in pieces")
+    torch = torch_cuda
+    d = inputs.make_ptq_inputs(22, 180, 150, 16)
+    A, B = torch.from_numpy(d["A_star"]).cuda(), torch.from_numpy(d["B_star"]).cuda()
+    whole = binding.lordba_ptq(A, B, 10, K=40)
+    part = binding.lordba_ptq(A, B, 10, K=40, sweeps=(0, 5))
+    torch.cuda.synchronize()
+    info5 = part["info"].cpu().numpy().copy()
+    assert info5[0] == 5.0 and info5[1] == 0.0 and np.all(info5[8:13] != 0.0) and np.all(info5[13:] == 0.0)
+    ref = P.ptq(d["A_star"], d["B_star"], 10, K=40, trace=(tr := []))
+    assert rel(part["alpha"].cpu().numpy(), tr[4]["alpha"]) <= TOL_REAL and abs(info5[2] - tr[4]["rho"]) <= 1e-12 * tr[4]["rho"]
+    binding.lordba_ptq(A, B, 10, K=40, sweeps=(5, 6), out=part)
+    binding.lordba_ptq(A, B, 10, K=40, sweeps=(6, 40), out=part)
+    torch.cuda.synchronize()
+    for k in ("packedA", "packedB", "alpha", "beta", "gamma", "s_in", "s_rank", "s_out", "info", "U1", "U2t"):
+        assert torch.equal(part[k], whole[k]), k
+    assert int(whole["info"][0].item()) == ref["sweeps"]
+
+
 def test_graph_replay_matches_eager(torch_cuda):
     # a warmed-up call only launches kernels (no clearing by memset, no allocation, no wait): it can be captured; replays,
     # with eager work of the same library in between, must give the eager result bit for bit
