@@ -16,8 +16,9 @@
 // kernel adds the shares up (each workgroup of a row kernel doing so itself would pull every share through its own
 // compute unit's 64 B/clk path to L2: measured 9 us per launch against 4.8 us for the extra launch).  A sweep is nine
 // launches: two Tikhonov steps (each followed at once by the sign and dual update of its rows, which needs nothing
-// else), alpha, gamma, each with its totals kernel, and beta with the penalty control.  A flag in device memory ends the loop: once the sign matrices repeat, the remaining launches return at
-// once, so the host never waits on the device inside the loop.
+// else), alpha, gamma, each with its totals kernel, and beta with the penalty control.  A flag in device memory ends the
+// loop: once the sign matrices repeat, the remaining launches return at once, so the host never waits on the device
+// inside the loop (lordba_ptq_sweeps lets a caller that is willing to wait enqueue the run in pieces instead).
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <math.h>

@@ -88,6 +88,9 @@ SHAPES = [
     (6, 512, 512, 16, 16),
     (7, 33, 40, 24, 24),         # fewer rows than one block
     (8, 640, 384, 8, 64),        # the largest factor rank
+    (9, 2048, 2048, 16, 16),     # a quarter of the benchmark's projection: the dense oracle takes about 10 s
+    (10, 1100, 4096, 16, 16),    # one side at the benchmark's width, ragged on the other
+    (11, 4096, 4096, 16, 16),    # the benchmark's projection (the dense oracle: about 10 s on the GPU machine's host, 40 s on 8 cores)
 ]
 
 
