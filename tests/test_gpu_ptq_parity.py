@@ -90,6 +90,8 @@ SHAPES = [
     (8, 640, 384, 8, 64),        # the largest factor rank
     (9, 2048, 2048, 16, 16),     # a quarter of the benchmark's projection: the dense oracle takes about 10 s
     (10, 1100, 4096, 16, 16),    # one side at the benchmark's width, ragged on the other
+    (12, 200, 150, 32, 64),      # both ranks at their limits
+    (13, 150, 70, 17, 33),       # just past the 16-lane / 16-entry instantiation
     (11, 4096, 4096, 16, 16),    # the benchmark's projection (the dense oracle: about 10 s on the GPU machine's host, 40 s on 8 cores)
 ]
 
