@@ -268,14 +268,15 @@ size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, i
  * with B1 in {+-1}^{N x R}, B2 in {+-1}^{R x M}, and returns the adapter in the form lordba_forward takes, with
  * d_in = N, d_out = M, r = R.  All pointers are DEVICE pointers; the call only enqueues kernels on `stream` and never
  * waits for the device.
- *   A_star, B_star : fp16 [N, r0], [M, r0] row-major, in; taken at their exact values.  Both need full column rank.
+ *   A_star, B_star : fp16 [N, r0], [M, r0] row-major, in; taken at their exact values.  They need not have full column
+ *          rank (dead or repeated columns, fewer rows than columns are fine), but the update must have rank >= R.
  *   packedA : uint32 [lordba_packed_words(R, N)] out, S_A = B1^T in the canonical format;  packedB : uint32
  *             [lordba_packed_words(M, R)] out, S_B = B2^T.
  *   alpha [N], beta [R], gamma [M] : fp64 out, the scales (s_in, s_rank, s_out of the forward).
  *   s_in [N], s_rank [R], s_out [M] : fp16 out, the same scales rounded to nearest; each may be NULL.
  *   info : fp64 [8 + K] out: [0] sweeps run, [1] 1 if the loop ended because the sign matrices repeated, [2] the penalty
- *          rho it ended with, [3] ||Delta W*||_F^2, [4] 1 if the input was degenerate (a factor without full column rank
- *          or a zero or non-finite update: no sweep is run and the other outputs are unspecified), [5..7] 0,
+ *          rho it ended with, [3] ||Delta W*||_F^2, [4] 1 if the input was degenerate (an update of rank below R,
+ *          zero or non-finite: no sweep is run and the other outputs are unspecified), [5..7] 0,
  *          [8 + t] the objective of Eq. (admm-problem) at the continuous iterates after the scale update of sweep t
  *          (0 for sweeps not run).
  *   workspace : lordba_ptq_workspace_bytes(N, M, R, r0) bytes, 8-byte aligned, owned by the caller; a smaller one ->

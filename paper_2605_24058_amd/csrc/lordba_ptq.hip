@@ -73,12 +73,12 @@ __device__ inline double group_sum(double v, int gs) {
 __device__ inline int group_size_for(int R) { return R <= 16 ? 16 : (R <= 32 ? 32 : 64); }
 
 // In-place Cholesky factor (lower triangle) of the n x n matrix H (leading dimension ld) by the lanes l = 0..gs-1 of one
-// group; lane l owns column l.  Returns false (in every lane) if a pivot is not positive.
-__device__ inline bool group_cholesky(double* H, int ld, int n, int l) {
+// group; lane l owns column l.  Returns false (in every lane) if a pivot is not above `floor`.
+__device__ inline bool group_cholesky(double* H, int ld, int n, int l, double floor = 0.0) {
     bool ok = true;
     for (int k = 0; k < n; ++k) {
         const double hkk = H[k * ld + k];
-        ok = ok && (hkk > 0.0);
+        ok = ok && (hkk > floor);
         const double d = sqrt(hkk);
         if (l > k && l < n) H[l * ld + k] = H[l * ld + k] / d;
         if (l == k) H[k * ld + k] = d;
@@ -179,10 +179,68 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_factor_gram_kernel(PtqArg
     }
 }
 
-// One wave.  With A* = Qa La^T and B* = Qb Lb^T (Cholesky factors of the two Gram matrices), the target is
-// Qa (La^T Lb) Qb^T; a one-sided Jacobi iteration gives the singular value decomposition of the r0 x r0 core, hence the
-// singular values of the target and maps Z1, Z2 with (leading left singular vectors) ~ A* Z1, (right) ~ B* Z2 up to
-// positive column factors, which the signs do not see.
+// One-sided Jacobi iteration on the n x n matrix W (n <= 64) by one wave: plane rotations of column pairs, accumulated
+// in V (which the caller sets to the identity), until all columns of W are orthogonal: W V_acc = (orthogonal columns).
+// Round-robin order: the n / 2 column pairs of a round are disjoint, so groups of lanes rotate several pairs at once
+// (lane i of a group owns row i of W and of V for the group's pair).
+__device__ inline void jacobi_onesided(double* W, double* V, int n, int ld, int l) {
+    const int gsz = n <= 16 ? 16 : (n <= 32 ? 32 : 64), ngroups = 64 / gsz;
+    const int g = l / gsz, i = l - g * gsz;
+    const int ne = n + (n & 1);  // an even number of players; with n odd, player n is a bye
+    for (int sweep = 0; sweep < 60; ++sweep) {
+        bool rotated = false;
+        for (int round = 0; round + 1 < ne; ++round) {
+            for (int m0 = 0; m0 < ne / 2; m0 += ngroups) {
+                const int m = m0 + g;
+                int p = 0, q = 0;
+                bool valid = m < ne / 2;
+                if (valid) {
+                    const int lo = (round + m) % (ne - 1);
+                    const int hi = m == 0 ? ne - 1 : (round + ne - 1 - m) % (ne - 1);
+                    p = lo < hi ? lo : hi;
+                    q = lo < hi ? hi : lo;
+                    valid = q < n;
+                }
+                const bool mine = valid && i < n;
+                const double wp = mine ? W[i * ld + p] : 0.0, wq = mine ? W[i * ld + q] : 0.0;
+                const double app = group_sum(wp * wp, gsz), aqq = group_sum(wq * wq, gsz), apq = group_sum(wp * wq, gsz);
+                const bool rot = valid && fabs(apq) > 1e-15 * sqrt(app * aqq);
+                if (rot && mine) {
+                    const double zeta = (aqq - app) / (2.0 * apq);
+                    const double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+                    const double cs = 1.0 / sqrt(1.0 + t * t), sn = cs * t;
+                    W[i * ld + p] = cs * wp - sn * wq;
+                    W[i * ld + q] = sn * wp + cs * wq;
+                    const double vp = V[i * ld + p], vq = V[i * ld + q];
+                    V[i * ld + p] = cs * vp - sn * vq;
+                    V[i * ld + q] = sn * vp + cs * vq;
+                }
+                rotated = rotated || (__builtin_amdgcn_ballot_w64(rot) != 0);
+                wave_sync();
+            }
+        }
+        if (!rotated) break;
+    }
+}
+
+// norms[p] = the 2-norm of column p of the n x n matrix W (one wave; every lane returns after the values are in LDS).
+__device__ inline void column_norms(const double* W, int n, int ld, int l, double* norms) {
+    for (int p = 0; p < n; ++p) {
+        const double wp = l < n ? W[l * ld + p] : 0.0;
+        const double s2 = __shfl(group_sum(wp * wp, 64), 0, 64);
+        if (l == 0) norms[p] = sqrt(s2);
+    }
+    wave_sync();
+}
+
+// One wave: the thin singular value decomposition of the target from the two r0 x r0 Gram matrices of its factors.
+// With A* = Qa Ra and B* = Qb Rb (Qa, Qb with orthonormal columns) the target is Qa (Ra Rb^T) Qb^T, and a one-sided
+// Jacobi iteration on the r0 x r0 core Ra Rb^T gives its singular values and vectors, hence the singular values of the
+// target and maps Z1, Z2 with (leading left singular vectors) ~ A* Z1, (right) ~ B* Z2 up to positive column factors,
+// which the signs do not see.  Ra, Rb are the transposed Cholesky factors of the Gram matrices when both factor
+// matrices have full column rank (every pivot above 1e-10 of the largest diagonal entry); otherwise (a dead or
+// dependent column, fewer rows than columns) they come from the eigen-decompositions G = E diag(lambda) E^T, taken with
+// the same Jacobi iteration: R = diag(sqrt(lambda)) E^T, inverted on the range of G only.
 __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
     const int r0 = a.r0, R = a.R, ld = r0 + 1, l = threadIdx.x;
     double* Ga = lds;
@@ -190,71 +248,63 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
     double* W = Gb + r0 * ld;
     double* V = W + r0 * ld;
     double* sig = V + r0 * ld;
-    int* idx = reinterpret_cast<int*>(sig + r0);
-    for (int o = l; o < r0 * r0; o += 64) {
-        Ga[(o / r0) * ld + o % r0] = a.tot[0][o];
-        Gb[(o / r0) * ld + o % r0] = a.tot[1][o];
-    }
-    wave_sync();
-    const bool ok_a = group_cholesky(Ga, ld, r0, l);
-    const bool ok_b = group_cholesky(Gb, ld, r0, l);
-    // core W = La^T Lb, V = I; lane i owns row i of both from here on
-    if (l < r0) {
-        for (int j = 0; j < r0; ++j) {
-            double acc = 0.0;
-            for (int k = (l > j ? l : j); k < r0; ++k) acc += Ga[k * ld + l] * Gb[k * ld + j];
-            W[l * ld + j] = acc;
-            V[l * ld + j] = (l == j) ? 1.0 : 0.0;
+    double* lam = sig + r0;   // [2, r0] eigenvalues of the two Gram matrices (second route only)
+    int* idx = reinterpret_cast<int*>(lam + 2 * r0);
+    auto load_gram = [&]() {
+        for (int o = l; o < r0 * r0; o += 64) {
+            Ga[(o / r0) * ld + o % r0] = a.tot[0][o];
+            Gb[(o / r0) * ld + o % r0] = a.tot[1][o];
         }
-    }
-    // One-sided Jacobi in the round-robin order: the r0 / 2 column pairs of a round are disjoint, so groups of lanes
-    // rotate several pairs at once (lane i of a group owns row i of the core and of V for the group's pair).
-    {
-        const int gsz = r0 <= 16 ? 16 : (r0 <= 32 ? 32 : 64), ngroups = 64 / gsz;
-        const int g = l / gsz, i = l - g * gsz;
-        const int ne = r0 + (r0 & 1);  // an even number of players; with r0 odd, player r0 is a bye
-        for (int sweep = 0; sweep < 60; ++sweep) {
-            bool rotated = false;
-            for (int round = 0; round + 1 < ne; ++round) {
-                for (int m0 = 0; m0 < ne / 2; m0 += ngroups) {
-                    const int m = m0 + g;
-                    int p = 0, q = 0;
-                    bool valid = m < ne / 2;
-                    if (valid) {
-                        const int lo = (round + m) % (ne - 1);
-                        const int hi = m == 0 ? ne - 1 : (round + ne - 1 - m) % (ne - 1);
-                        p = lo < hi ? lo : hi;
-                        q = lo < hi ? hi : lo;
-                        valid = q < r0;
-                    }
-                    const bool mine = valid && i < r0;
-                    const double wp = mine ? W[i * ld + p] : 0.0, wq = mine ? W[i * ld + q] : 0.0;
-                    const double app = group_sum(wp * wp, gsz), aqq = group_sum(wq * wq, gsz), apq = group_sum(wp * wq, gsz);
-                    const bool rot = valid && fabs(apq) > 1e-15 * sqrt(app * aqq);
-                    if (rot && mine) {
-                        const double zeta = (aqq - app) / (2.0 * apq);
-                        const double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                        const double cs = 1.0 / sqrt(1.0 + t * t), sn = cs * t;
-                        W[i * ld + p] = cs * wp - sn * wq;
-                        W[i * ld + q] = sn * wp + cs * wq;
-                        const double vp = V[i * ld + p], vq = V[i * ld + q];
-                        V[i * ld + p] = cs * vp - sn * vq;
-                        V[i * ld + q] = sn * vp + cs * vq;
-                    }
-                    rotated = rotated || (__builtin_amdgcn_ballot_w64(rot) != 0);
-                    wave_sync();
-                }
+        wave_sync();
+    };
+    auto identity = [&](double* X) {
+        if (l < r0)
+            for (int j = 0; j < r0; ++j) X[l * ld + j] = (l == j) ? 1.0 : 0.0;
+    };
+    load_gram();
+    double da = l < r0 ? Ga[l * ld + l] : 0.0, db = l < r0 ? Gb[l * ld + l] : 0.0;
+    for (int m = 32; m >= 1; m >>= 1) { da = fmax(da, __shfl_xor(da, m, 64)); db = fmax(db, __shfl_xor(db, m, 64)); }
+    const bool ok_a = group_cholesky(Ga, ld, r0, l, 1e-10 * da);
+    const bool ok_b = group_cholesky(Gb, ld, r0, l, 1e-10 * db);
+    const bool full_rank = ok_a && ok_b;
+    if (full_rank) {
+        // core W = La^T Lb, V = I; lane i owns row i of both from here on
+        if (l < r0) {
+            for (int j = 0; j < r0; ++j) {
+                double acc = 0.0;
+                for (int k = (l > j ? l : j); k < r0; ++k) acc += Ga[k * ld + l] * Gb[k * ld + j];
+                W[l * ld + j] = acc;
             }
-            if (!rotated) break;
         }
+        identity(V);
+        wave_sync();
+    } else {
+        load_gram();   // (the factorisation overwrote them)
+        for (int side = 0; side < 2; ++side) {
+            double* G = side == 0 ? Ga : Gb;
+            // eigen-decomposition of the positive semidefinite G: rotate its columns orthogonal; G V = V diag(lambda)
+            identity(V);
+            wave_sync();
+            jacobi_onesided(G, V, r0, ld, l);
+            column_norms(G, r0, ld, l, lam + side * r0);
+            if (l < r0)
+                for (int j = 0; j < r0; ++j) G[l * ld + j] = V[l * ld + j];   // keep the eigenvectors in G's place
+            wave_sync();
+        }
+        // core W[i][j] = sqrt(lambda_a,i lambda_b,j) (Ea^T Eb)[i][j]
+        if (l < r0) {
+            for (int j = 0; j < r0; ++j) {
+                double acc = 0.0;
+                for (int k = 0; k < r0; ++k) acc += Ga[k * ld + l] * Gb[k * ld + j];
+                W[l * ld + j] = sqrt(lam[l] * lam[r0 + j]) * acc;
+            }
+        }
+        identity(V);
+        wave_sync();
     }
+    jacobi_onesided(W, V, r0, ld, l);
     // singular values = column norms of the rotated core; order them (descending, ties by index)
-    for (int p = 0; p < r0; ++p) {
-        const double wp = l < r0 ? W[l * ld + p] : 0.0;
-        const double s2 = __shfl(group_sum(wp * wp, 64), 0, 64);
-        if (l == 0) sig[p] = sqrt(s2);
-    }
-    wave_sync();
+    column_norms(W, r0, ld, l, sig);
     if (l == 0) {
         for (int p = 0; p < r0; ++p) idx[p] = p;
         for (int p = 0; p < r0; ++p) {
@@ -267,7 +317,9 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
         }
         double norm2 = 0.0;
         for (int p = 0; p < r0; ++p) norm2 += sig[idx[p]] * sig[idx[p]];
-        const bool good = ok_a && ok_b && norm2 > 0.0 && norm2 < INFINITY;
+        // beyond the rank of the target the singular vectors are not defined (the second route can meet such a target;
+        // through squared quantities a singular value below 1e-7 of the largest is noise)
+        const bool good = norm2 > 0.0 && norm2 < INFINITY && (full_rank || sig[idx[R - 1]] > 1e-7 * sig[idx[0]]);
         a.ctrl[kRho] = norm2 / (static_cast<double>(a.n[0]) * R + static_cast<double>(a.n[1]) * R);
         a.ctrl[kYfac] = 1.0;
         a.ctrl[kDone] = good ? 0.0 : 1.0;
@@ -281,15 +333,28 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
     if (l < R) {
         const int c = idx[l];
         a.beta[l] = sig[c];
-        // Z1[:, l] = La^{-T} (rotated core)[:, c], Z2[:, l] = Lb^{-T} V[:, c]: back substitution with the upper factors
         for (int side = 0; side < 2; ++side) {
             const double* Lf = side == 0 ? Ga : Gb;
             const double* src = side == 0 ? W : V;
             double* z = a.Z[side];
-            for (int i = r0 - 1; i >= 0; --i) {
-                double acc = src[i * ld + c];
-                for (int j = i + 1; j < r0; ++j) acc -= Lf[j * ld + i] * z[j * R + l];
-                z[i * R + l] = acc / Lf[i * ld + i];
+            if (full_rank) {
+                // Z1[:, l] = La^{-T} (rotated core)[:, c], Z2[:, l] = Lb^{-T} V[:, c]: back substitution with the upper factors
+                for (int i = r0 - 1; i >= 0; --i) {
+                    double acc = src[i * ld + c];
+                    for (int j = i + 1; j < r0; ++j) acc -= Lf[j * ld + i] * z[j * R + l];
+                    z[i * R + l] = acc / Lf[i * ld + i];
+                }
+            } else {
+                // Z[:, l] = E diag(lambda^{-1/2} on the range, 0 off it) src[:, c]
+                const double* lm = lam + side * r0;
+                double top = 0.0;
+                for (int p = 0; p < r0; ++p) top = fmax(top, lm[p]);
+                for (int i = 0; i < r0; ++i) {
+                    double acc = 0.0;
+                    for (int p = 0; p < r0; ++p)
+                        if (lm[p] > 1e-13 * top) acc += Lf[i * ld + p] * (src[p * ld + c] / sqrt(lm[p]));
+                    z[i * R + l] = acc;
+                }
             }
         }
     }
@@ -821,7 +886,7 @@ extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_sta
 
     const int iR = a.R, ir0 = a.r0, ld0 = ir0 + 1, ldR = iR + 1;
     const size_t lds_gram = sizeof(double) * kRows * ir0;
-    const size_t lds_svd = sizeof(double) * (4 * ir0 * ld0 + ir0) + sizeof(int) * ir0;
+    const size_t lds_svd = sizeof(double) * (4 * ir0 * ld0 + 3 * ir0) + sizeof(int) * ir0;
     const size_t lds_init = sizeof(double) * (kRows * ir0 + kRows * iR + kRows + ir0 * iR);
     const int gs = iR <= 16 ? 16 : 32;
     // the Tikhonov kernel: as many waves solve rows at once as the LDS has room for their matrices (8, 4, 2 or 1); the scale

@@ -135,6 +135,46 @@ def test_flat_spectrum_and_large_entries(torch_cuda):
     compare(res, ref, 60)
 
 
+@pytest.mark.parametrize("case", ["padded", "dependent", "few_rows", "both_sides"])
+def test_rank_deficient_factors(torch_cuda, case):
+    # factors without full column rank (an adapter padded with dead columns, a repeated column, fewer rows than
+    # columns): the warm start takes its second route; the update still has rank >= R
+    say("ptq rank-deficient factors: " + case)
+    if case == "padded":
+        d = inputs.make_ptq_inputs(30, 180, 140, 12)
+        d["A_star"][:, 9:] = 0
+        R = 8
+    elif case == "dependent":
+        d = inputs.make_ptq_inputs(31, 150, 200, 10)
+        d["B_star"][:, 7] = d["B_star"][:, 2]
+        R = 6
+    elif case == "few_rows":
+        d = inputs.make_ptq_inputs(32, 5, 90, 8)
+        R = 4
+    else:
+        d = inputs.make_ptq_inputs(33, 120, 130, 16)
+        d["A_star"][:, 12:] = 0
+        d["B_star"][:, :2] = 0
+        R = 10
+    ref = P.ptq(d["A_star"], d["B_star"], R, K=50)
+    res = run_gpu(torch_cuda, d, R, K=50)
+    compare(res, ref, 50)
+
+
+def test_carrier_rank_beyond_the_rank_of_the_update_is_flagged(torch_cuda):
+    say("ptq R beyond the rank of the update")
+    torch = torch_cuda
+    d = inputs.make_ptq_inputs(34, 100, 80, 8)
+    d["A_star"][:, 3:] = 0                       # the update has rank 3
+    out = binding.lordba_ptq(torch.from_numpy(d["A_star"]).cuda(), torch.from_numpy(d["B_star"]).cuda(), 5, K=5)
+    torch.cuda.synchronize()
+    info = out["info"].cpu().numpy()
+    assert info[4] == 1.0 and info[0] == 0.0
+    ok = binding.lordba_ptq(torch.from_numpy(d["A_star"]).cuda(), torch.from_numpy(d["B_star"]).cuda(), 3, K=5)
+    torch.cuda.synchronize()
+    assert ok["info"][4].item() == 0.0
+
+
 def test_rank_one_target_is_fitted_exactly_and_ends_after_one_sweep(torch_cuda):
     say("ptq rank one")
     d = inputs.make_ptq_inputs(14, 90, 70, 1)
