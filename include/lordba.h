@@ -178,7 +178,8 @@ lordba_status lordba_pack_latents(const float* latentA, const float* latentB,
  *   t_out[k * t_stride + t] = sum_i S_A[k, i] * s_in[i] * x[t, i]        fp32, rank-major, k < r, t < T, t_stride >= T
  * (the value before the rank scaling; other entries of t_out are left untouched).  T * r * 4 bytes instead of recomputing
  * a pass over x.  y_base == NULL and y_out == NULL together: only t_out is computed (x is read once, nothing else).
- * Everything else as lordba_forward; t_out must not overlap x, y_base or y_out (LORDBA_ERR_ALIAS). */
+ * Everything else as lordba_forward (T == 0: no work, t_out may then be NULL too); t_out must not overlap x, y_base or
+ * y_out (LORDBA_ERR_ALIAS). */
 lordba_status lordba_forward_save_t(const void* x, const uint32_t* packedA, const uint32_t* packedB,
                                     const void* s_in, const void* s_rank, const void* s_out,
                                     const void* y_base, void* y_out, float* t_out, int64_t t_stride,

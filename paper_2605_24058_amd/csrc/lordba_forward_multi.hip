@@ -30,7 +30,7 @@ extern "C" lordba_status lordba_forward_multi_save_t(const void* x, const uint32
                                                      const void* s_in, const void* s_rank, const void* s_out,
                                                      const void* y_base, void* y_out, float* t_out, int64_t t_stride,
                                                      int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream) {
-    if (t_out == nullptr) return LORDBA_ERR_NULL;
+    if (t_out == nullptr && T != 0) return LORDBA_ERR_NULL;   // (an empty batch has nothing to keep)
     const int algo = LORDBA_ALGO_AUTO;
     switch (ell) {
         case 1: return lordba_forward_save_t(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out, t_out, t_stride, T, d_in, d_out, r, stream);

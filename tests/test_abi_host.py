@@ -155,6 +155,8 @@ def test_backward_validation_needs_no_device(lib):
     ok = [p["x"], p["pA"], p["pBt"], p["si"], p["sr"], p["so"], yb, yo, p["ts"], 128, T, d_in, d_out, r]
     a = list(ok); a[8] = None
     assert f(*a) == 1
+    a = list(ok); a[8] = None; a[10] = 0                                        # an empty batch needs no t_out
+    assert f(*a) == 0
     a = list(ok); a[9] = T - 1
     assert f(*a) == 2
     a = list(ok); a[8] = p["x"]
