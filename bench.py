@@ -495,7 +495,7 @@ def main():
                     "instead of the forward pass")
     ap.add_argument("--ptq-streams", type=int, default=1, help="--ptq: this many projections in flight at once, one stream and "
                     "one HIP graph each")
-    ap.add_argument("--ptq-chunk", type=int, default=0, help="--ptq: enqueue the first this many sweeps, wait, and enqueue the rest "
+    ap.add_argument("--ptq-chunk", type=int, default=32, help="--ptq: enqueue the first this many sweeps, wait, and enqueue the rest "
                     "only if the loop has not ended (lordba_ptq_sweeps); 0 = one call of all K sweeps that never waits")
     ap.add_argument("--ptq-shape", default="4096,4096,16,16", help="--ptq: N,M,R,r0 (update N x M, carrier rank R, factor rank r0)")
     ap.add_argument("--keep-t", action="store_true", help="--backward: pass the rank-r intermediate kept by "
