@@ -249,7 +249,8 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
     double* V = W + r0 * ld;
     double* sig = V + r0 * ld;
     double* lam = sig + r0;   // [2, r0] eigenvalues of the two Gram matrices (second route only)
-    int* idx = reinterpret_cast<int*>(lam + 2 * r0);
+    double* zs = lam + 2 * r0;   // [r0, R] one side's map before it goes to memory
+    int* idx = reinterpret_cast<int*>(zs + r0 * R);
     auto load_gram = [&]() {
         for (int o = l; o < r0 * r0; o += 64) {
             Ga[(o / r0) * ld + o % r0] = a.tot[0][o];
@@ -305,16 +306,19 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
     jacobi_onesided(W, V, r0, ld, l);
     // singular values = column norms of the rotated core; order them (descending, ties by index)
     column_norms(W, r0, ld, l, sig);
-    if (l == 0) {
-        for (int p = 0; p < r0; ++p) idx[p] = p;
-        for (int p = 0; p < r0; ++p) {
-            int best = p;
-            for (int q = p + 1; q < r0; ++q)
-                if (sig[idx[q]] > sig[idx[best]]) best = q;
-            const int tmp = idx[p];
-            idx[p] = idx[best];
-            idx[best] = tmp;
+    if (l < r0) idx[l] = l;   // (stays a valid index wherever non-finite values make the ranking below collide)
+    wave_sync();
+    if (l < r0) {   // position of column l in the descending order (ties by index)
+        const double mine = sig[l];
+        int before = 0;
+        for (int q = 0; q < r0; ++q) {
+            const double other = sig[q];
+            before += (other > mine || (other == mine && q < l)) ? 1 : 0;
         }
+        idx[before] = l;
+    }
+    wave_sync();
+    if (l == 0) {
         double norm2 = 0.0;
         for (int p = 0; p < r0; ++p) norm2 += sig[idx[p]] * sig[idx[p]];
         // beyond the rank of the target the singular vectors are not defined (the second route can meet such a target;
@@ -330,19 +334,18 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
         a.ctrl[7] = 0.0;
     }
     wave_sync();
-    if (l < R) {
-        const int c = idx[l];
-        a.beta[l] = sig[c];
-        for (int side = 0; side < 2; ++side) {
-            const double* Lf = side == 0 ? Ga : Gb;
-            const double* src = side == 0 ? W : V;
-            double* z = a.Z[side];
+    if (l < R) a.beta[l] = sig[idx[l]];
+    for (int side = 0; side < 2; ++side) {
+        const double* Lf = side == 0 ? Ga : Gb;
+        const double* src = side == 0 ? W : V;
+        if (l < R) {   // lane l: column l of the side's map, built in LDS (zs, [r0, R])
+            const int c = idx[l];
             if (full_rank) {
                 // Z1[:, l] = La^{-T} (rotated core)[:, c], Z2[:, l] = Lb^{-T} V[:, c]: back substitution with the upper factors
                 for (int i = r0 - 1; i >= 0; --i) {
                     double acc = src[i * ld + c];
-                    for (int j = i + 1; j < r0; ++j) acc -= Lf[j * ld + i] * z[j * R + l];
-                    z[i * R + l] = acc / Lf[i * ld + i];
+                    for (int j = i + 1; j < r0; ++j) acc -= Lf[j * ld + i] * zs[j * R + l];
+                    zs[i * R + l] = acc / Lf[i * ld + i];
                 }
             } else {
                 // Z[:, l] = E diag(lambda^{-1/2} on the range, 0 off it) src[:, c]
@@ -353,10 +356,13 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
                     double acc = 0.0;
                     for (int p = 0; p < r0; ++p)
                         if (lm[p] > 1e-13 * top) acc += Lf[i * ld + p] * (src[p * ld + c] / sqrt(lm[p]));
-                    z[i * R + l] = acc;
+                    zs[i * R + l] = acc;
                 }
             }
         }
+        wave_sync();
+        for (int o = l; o < r0 * R; o += 64) a.Z[side][o] = zs[o];
+        wave_sync();
     }
 }
 
@@ -886,7 +892,7 @@ extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_sta
 
     const int iR = a.R, ir0 = a.r0, ld0 = ir0 + 1, ldR = iR + 1;
     const size_t lds_gram = sizeof(double) * kRows * ir0;
-    const size_t lds_svd = sizeof(double) * (4 * ir0 * ld0 + 3 * ir0) + sizeof(int) * ir0;
+    const size_t lds_svd = sizeof(double) * (4 * ir0 * ld0 + 3 * ir0 + ir0 * iR) + sizeof(int) * ir0;
     const size_t lds_init = sizeof(double) * (kRows * ir0 + kRows * iR + kRows + ir0 * iR);
     const int gs = iR <= 16 ? 16 : 32;
     // the Tikhonov kernel: as many waves solve rows at once as the LDS has room for their matrices (8, 4, 2 or 1); the scale
