@@ -295,7 +295,10 @@ size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, i
  * Limits: 1 <= R <= LORDBA_PTQ_MAX_RANK, R <= r0 <= LORDBA_PTQ_MAX_FACTOR_RANK (beyond r0 the warm start has no singular
  * vectors), 1 <= N, M <= 2^22, 1 <= K <= LORDBA_PTQ_MAX_SWEEPS; else LORDBA_ERR_DIM.  No output, nor the workspace,
  * may overlap an input or another output: LORDBA_ERR_ALIAS.  Arithmetic: fp64 throughout, fixed summation order
- * (calls are reproducible bit for bit). */
+ * (calls are reproducible bit for bit).  The warm start works from the r0 x r0 Gram matrices of the factors, which
+ * resolves singular triplet k of the update to a relative error of about eps (sigma_1 / sigma_k)^2: with sigma_R / sigma_1
+ * below about 1e-5 a few near-zero entries of the trailing carriers may start from the other sign than a dense singular
+ * value decomposition would give them. */
 lordba_status lordba_ptq(const void* A_star, const void* B_star, uint32_t* packedA, uint32_t* packedB,
                          double* alpha, double* beta, double* gamma, void* s_in, void* s_rank, void* s_out,
                          double* info, void* workspace, size_t workspace_bytes,
