@@ -108,8 +108,9 @@ __device__ inline double group_solve(const double* H, int ld, int n, int l, int 
     return b;
 }
 
-// This block's share of a side's Gram pair from its rows in LDS: xs [kRows, R], cs [kRows] (0 past the end), fs [kRows, r0].
-__device__ inline void gram_share(const double* xs, const double* cs, const double* fs, int R, int r0, double* out) {
+// This block's share of a side's Gram pair from its rows in LDS: xs [kRows, R], cs [kRows] (0 past the end), fs [kRows, r0]
+// with row stride fstride.
+__device__ inline void gram_share(const double* xs, const double* cs, const double* fs, int fstride, int R, int r0, double* out) {
     const int RR = R * R;
     for (int o = threadIdx.x; o < RR + R * r0; o += blockDim.x) {
         double acc = 0.0;
@@ -118,16 +119,17 @@ __device__ inline void gram_share(const double* xs, const double* cs, const doub
             for (int row = 0; row < kRows; ++row) acc += (cs[row] * xs[row * R + k]) * (cs[row] * xs[row * R + l]);
         } else {
             const int k = (o - RR) / r0, q = (o - RR) - k * r0;
-            for (int row = 0; row < kRows; ++row) acc += (cs[row] * xs[row * R + k]) * fs[row * r0 + q];
+            for (int row = 0; row < kRows; ++row) acc += (cs[row] * xs[row * R + k]) * fs[row * fstride + q];
         }
         out[o] = acc;
     }
 }
 
-__device__ inline void load_factor_rows(const __half* F, int64_t n, int r0, int64_t row0, double* fs) {
+// Rows row0 .. row0 + kRows - 1 of a factor into LDS as doubles, row stride fstride (zeros past the end of the factor).
+__device__ inline void load_factor_rows(const __half* F, int64_t n, int r0, int64_t row0, double* fs, int fstride) {
     for (int o = threadIdx.x; o < kRows * r0; o += blockDim.x) {
-        const int64_t row = row0 + o / r0;
-        fs[o] = row < n ? static_cast<double>(__half2float(F[row0 * r0 + o])) : 0.0;
+        const int row = o / r0, q = o - row * r0;
+        fs[row * fstride + q] = row0 + row < n ? static_cast<double>(__half2float(F[row0 * r0 + o])) : 0.0;
     }
 }
 
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_factor_gram_kernel(PtqArg
     const int blk = side == 0 ? blockIdx.x : blockIdx.x - a.nb[0];
     const int r0 = a.r0;
     double* fs = lds;
-    load_factor_rows(a.F[side], a.n[side], r0, static_cast<int64_t>(blk) * kRows, fs);
+    load_factor_rows(a.F[side], a.n[side], r0, static_cast<int64_t>(blk) * kRows, fs, r0);
     __syncthreads();
     double* out = a.part[side] + static_cast<int64_t>(blk) * a.pstride;
     for (int o = threadIdx.x; o < r0 * r0; o += kThreads) {
@@ -376,7 +378,7 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_init_rows_kernel(PtqArgs 
     double* xs = fs + kRows * r0;
     double* cs = xs + kRows * R;
     double* zs = cs + kRows;
-    load_factor_rows(a.F[side], n, r0, row0, fs);
+    load_factor_rows(a.F[side], n, r0, row0, fs, r0);
     for (int o = threadIdx.x; o < r0 * R; o += kThreads) zs[o] = a.Z[side][o];
     __syncthreads();
     for (int o = threadIdx.x; o < kRows * R; o += kThreads) {
@@ -399,80 +401,86 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_init_rows_kernel(PtqArgs 
         if (in) a.scale[side][row0 + row] = 1.0;
     }
     __syncthreads();
-    gram_share(xs, cs, fs, R, r0, a.part[side] + static_cast<int64_t>(blk) * a.pstride);
+    gram_share(xs, cs, fs, r0, R, r0, a.part[side] + static_cast<int64_t>(blk) * a.pstride);
 }
 
 // ---- one sweep ----------------------------------------------------------------------------------------------------
 
-// LDS of the two row kernels: So [R*R], Ko [R*r0] (the other side's Gram pair), bs [R], fs, xs, cs, ys, then the per-group
-// matrices of the Tikhonov step (R x ld unscaled columns and R reciprocal pivots each).
+// LDS of the two row kernels: So [R*R], Ko [R*r0] (the other side's Gram pair), bs [R], fs [kRows, r0] with row stride
+// r0 + 1, xs, cs, ys, kfs [kRows, R] (Ko f of every row), then the per-group areas of the Tikhonov step.
 struct RowLds {
-    double *So, *Ko, *bs, *fs, *xs, *cs, *ys, *H;
+    double *So, *Ko, *bs, *fs, *xs, *cs, *ys, *kfs, *H;
+    int fstride;
 };
 __device__ inline RowLds carve_rows(int R, int r0) {
     RowLds s;
+    s.fstride = r0 + 1;
     s.So = lds;
     s.Ko = s.So + R * R;
     s.bs = s.Ko + R * r0;
     s.fs = s.bs + R;
-    s.xs = s.fs + kRows * r0;
+    s.xs = s.fs + kRows * s.fstride;
     s.cs = s.xs + kRows * R;
     s.ys = s.cs + kRows;
-    s.H = s.ys + kRows * R;
+    s.kfs = s.ys + kRows * R;
+    s.H = s.kfs + kRows * R;
     return s;
 }
 
-// Solves H x = b for a symmetric positive definite R x R matrix by the lanes l = 0..R-1 of one group (the wave's lanes
-// base..base+gs-1).  Lane l passes column l of H in col[] (entries i >= l are used) and entry l of b, and receives entry
-// l of x.  Right-looking L D L^T factorisation with the columns in registers: a finished column is published once,
-// unscaled, to Hs (LDS, R x ld) together with the reciprocal of its pivot (rd, LDS, R), and the other lanes fold the
-// scaling into their rank-one updates; then forward substitution, the diagonal, backward substitution on lane
-// shuffles.  No square root and one reciprocal per column.  Returns the smallest pivot in *min_pivot.
+// kfs[row][k] = Ko[k, :] . f_row for the block's rows (thread o: k = o / kRows, row = o % kRows, so that a wave reads one
+// row of Ko and consecutive, padded rows of fs).  Call between two barriers.
+__device__ inline void factor_products(const RowLds& s, int R, int r0) {
+    for (int o = threadIdx.x; o < kRows * R; o += blockDim.x) {
+        const int k = o / kRows, row = o - k * kRows;
+        double acc = 0.0;
+        for (int q = 0; q < r0; ++q) acc += s.Ko[k * r0 + q] * s.fs[row * s.fstride + q];
+        s.kfs[row * R + k] = acc;
+    }
+}
+
+// Solves H x = b for a symmetric positive definite RMAX x RMAX matrix by the RMAX lanes of one group (the wave's lanes
+// base .. base + RMAX - 1; a smaller system is passed padded with an identity block, and R says how many pivots are its
+// own).  Lane l passes column l of H in col[] (entries i >= l are used) and entry l of b, and receives entry l of x.
+// Right-looking L D L^T factorisation with the columns in registers: a finished column is published once, unscaled, to
+// Hs (LDS, RMAX x (RMAX + 1)), and the other lanes fold the scaling by its pivot into their rank-one updates.  The
+// right-hand side rides along as one more row of the matrix (zrow, LDS, RMAX), which makes the forward substitution
+// part of the factorisation; the backward substitution runs on lane shuffles with each lane's own column still in its
+// registers.  Every loop has a fixed trip count and every LDS read is unconditional, so that the reads of a step are
+// issued together.  No square root, one reciprocal per column (hardware estimate and two Newton steps).  Returns the
+// smallest of the first R pivots in *min_pivot.
 template <int RMAX>
-__device__ inline double group_ldlt_solve(double (&col)[RMAX], double b, double* Hs, double* rd, int ld, int R, int l, int base,
+__device__ inline double group_ldlt_solve(double (&col)[RMAX], double b, double* H, double* zrow, int R, int l, int base,
                                           double* min_pivot) {
-    const bool act = l < R;
-    const int lc = act ? l : 0;  // a valid column for the idle lanes' reads
-    double* H = Hs;
-    double minp = INFINITY;
+    constexpr int ld = RMAX + 1;
+    double minp = INFINITY, ipl = 0.0;
 #pragma unroll
     for (int k = 0; k < RMAX; ++k) {
-        if (k < R) {
-            if (l == k) {
+        if (l == k) {
 #pragma unroll
-                for (int i = k; i < RMAX; ++i)
-                    if (i < R) H[i * ld + k] = col[i];
-            }
-            wave_sync();
-            const double pk = H[k * ld + k];
-            double ipk = __builtin_amdgcn_rcp(pk);       // 1 / pivot: hardware estimate and two Newton steps
-            ipk = fma(fma(-pk, ipk, 1.0), ipk, ipk);
-            ipk = fma(fma(-pk, ipk, 1.0), ipk, ipk);
-            if (l == k) rd[k] = ipk;
-            const double f = H[lc * ld + k] * ipk;
-#pragma unroll
-            for (int i = k + 1; i < RMAX; ++i)
-                if (i < R) col[i] -= (l > k && i >= l) ? H[i * ld + k] * f : 0.0;
+            for (int i = k; i < RMAX; ++i) H[i * ld + k] = col[i];
+            zrow[k] = b;
         }
-    }
-    wave_sync();
-    // H = L' D L'^T with D the pivots and L'[i][k] = H[i][k] / pivot_k (unit diagonal): no square root is needed.
-    // Forward substitution, the diagonal, then backward substitution; lane l carries entry l of the right-hand side.
+        wave_sync();
+        const double pk = H[k * ld + k], hl = H[l * ld + k], zk = zrow[k];
+        double hk[RMAX];
 #pragma unroll
-    for (int k = 0; k < RMAX; ++k) {
-        if (k < R) {
-            const double zk = __shfl(b, base + k, 64) * rd[k];
-            if (l > k && act) b -= H[lc * ld + k] * zk;
-        }
+        for (int i = k + 1; i < RMAX; ++i) hk[i] = H[i * ld + k];
+        minp = fmin(minp, k < R ? pk : INFINITY);
+        double ipk = __builtin_amdgcn_rcp(pk);
+        ipk = fma(fma(-pk, ipk, 1.0), ipk, ipk);
+        ipk = fma(fma(-pk, ipk, 1.0), ipk, ipk);
+        ipl = (l == k) ? ipk : ipl;
+        const double f = (l > k) ? hl * ipk : 0.0;   // L'[l][k] = H[l][k] / pivot_k for the lanes below the diagonal
+#pragma unroll
+        for (int i = k + 1; i < RMAX; ++i) col[i] = fma(-hk[i], f, col[i]);   // (entries i < l are updated too; they are never used)
+        b = fma(-zk, f, b);                                                   // forward substitution: b as row RMAX of the matrix
     }
-    const double ipl = rd[lc];
+    // H = L' D L'^T with D the pivots and L' unit lower triangular; b now holds entry l of L'^{-1} b.
     b *= ipl;
 #pragma unroll
-    for (int k = RMAX - 1; k >= 0; --k) {
-        if (k < R) {
-            const double xk = __shfl(b, base + k, 64);
-            if (l < k) b -= (H[k * ld + lc] * ipl) * xk;
-        }
+    for (int k = RMAX - 1; k >= 1; --k) {
+        const double xk = __shfl(b, base + k, 64);
+        b = fma(-((l < k) ? col[k] * ipl : 0.0), xk, b);   // L'[k][l] = (lane l's own column, entry k) / pivot_l
     }
     *min_pivot = minp;
     return b;
@@ -484,8 +492,8 @@ __device__ inline double group_ldlt_solve(double (&col)[RMAX], double b, double*
 // right-looking L D L^T factorisation; a finished column is published once, unscaled, to LDS together with the
 // reciprocal of its pivot, and the other lanes fold the scaling into their updates (no square root, one reciprocal).
 // `solve_waves` of the block's waves take part (as many as the LDS holds matrices for).
-template <int RMAX>  // the carrier rank is at most RMAX (16 or 32): the length of the register-resident column; the larger one
-                     // runs with half the threads per block, so that a lane may hold twice the registers
+template <int RMAX>  // the carrier rank is at most RMAX (16 or 32): lanes per row and length of the register-resident column; the
+                     // larger one runs with half the threads per block, so that a lane may hold twice the registers
 __global__ __launch_bounds__(RMAX <= 16 ? kRowThreads : kRowThreads / 2) void lordba_ptq_ustep_kernel(PtqArgs a, int side, int solve_waves) {
     if (a.ctrl[kDone] != 0.0) return;
     const int R = a.R, r0 = a.r0, other = 1 - side, blk = blockIdx.x;
@@ -494,7 +502,7 @@ __global__ __launch_bounds__(RMAX <= 16 ? kRowThreads : kRowThreads / 2) void lo
     const int count = R * R + R * r0;
     load_totals(a.tot[other], count, s.So);  // So and Ko are adjacent
     for (int k = threadIdx.x; k < R; k += blockDim.x) s.bs[k] = a.beta[k];
-    load_factor_rows(a.F[side], n, r0, row0, s.fs);
+    load_factor_rows(a.F[side], n, r0, row0, s.fs, s.fstride);
     for (int row = threadIdx.x; row < kRows; row += blockDim.x) s.cs[row] = row0 + row < n ? a.scale[side][row0 + row] : 0.0;
     const double rho_k = a.ctrl[kRho] / (static_cast<double>(n) * R), yfac = a.ctrl[kYfac];
     for (int o = threadIdx.x; o < kRows * R; o += blockDim.x) {   // xs holds M until the row is solved, ys the rescaled Y
@@ -503,32 +511,33 @@ __global__ __launch_bounds__(RMAX <= 16 ? kRowThreads : kRowThreads / 2) void lo
         s.ys[o] = in ? yfac * a.Y[side][row0 * R + o] : 0.0;
     }
     __syncthreads();
-    const int gs = group_size_for(R), groups = 64 / gs, ld = R + 1;
+    factor_products(s, R, r0);
+    __syncthreads();
+    constexpr int gs = RMAX, groups = 64 / gs, ld = RMAX + 1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int g = lane / gs, l = lane - g * gs, base = g * gs;
     double gap = 0.0, flips = 0.0;
     if (wave < solve_waves) {
-        double* H = s.H + (wave * groups + g) * (R * ld + R);
-        double* rd = H + R * ld;
+        double* H = s.H + (wave * groups + g) * (RMAX * ld + RMAX);
+        double* zrow = H + RMAX * ld;
         const int rows_per_pass = solve_waves * groups;
-        const bool act = l < R;
-        const int lc = act ? l : 0;   // a valid column for the idle lanes' reads
+        const bool act = l < R;       // the other lanes of the group carry the identity block that pads the system
+        const int lc = act ? l : 0;   // a valid column for their reads
         for (int pass = 0; pass < kRows / rows_per_pass; ++pass) {
             const int row = pass * rows_per_pass + wave * groups + g;
             const bool in = row0 + row < n;
             const double c = s.cs[row], c2 = c * c, bl = s.bs[lc];
-            double kf = 0.0;
-            for (int q = 0; q < r0; ++q) kf += s.Ko[lc * r0 + q] * s.fs[row * r0 + q];
             const double m_old = s.xs[row * R + lc], y_old = s.ys[row * R + lc];
-            double b = c * bl * kf + rho_k * (m_old - y_old);
+            double b = act ? c * bl * s.kfs[row * R + lc] + rho_k * (m_old - y_old) : 0.0;
             double col[RMAX];
 #pragma unroll
             for (int i = 0; i < RMAX; ++i) {
-                col[i] = 0.0;
-                if (i < R) col[i] = c2 * (s.bs[i] * bl) * s.So[i * R + lc] + (i == l ? rho_k : 0.0);
+                const int ic = i < R ? i : 0;
+                const double own = c2 * (s.bs[ic] * bl) * s.So[ic * R + lc] + (i == l ? rho_k : 0.0);
+                col[i] = (act && i < R) ? own : (i == l ? 1.0 : 0.0);
             }
             double min_pivot;   // positive: the matrix is a Gram matrix plus rho_k I
-            b = group_ldlt_solve<RMAX>(col, b, H, rd, ld, R, l, base, &min_pivot);
+            b = group_ldlt_solve<RMAX>(col, b, H, zrow, R, l, base, &min_pivot);
             if (act) {
                 const double x = b;
                 const double mn = (x + y_old) < 0.0 ? -1.0 : 1.0;
@@ -552,7 +561,7 @@ __global__ __launch_bounds__(RMAX <= 16 ? kRowThreads : kRowThreads / 2) void lo
     if (lane == 0) { red[2 * wave] = gap; red[2 * wave + 1] = flips; }
     __syncthreads();
     double* share = a.part[side] + static_cast<int64_t>(blk) * a.pstride;
-    gram_share(s.xs, s.cs, s.fs, R, r0, share);
+    gram_share(s.xs, s.cs, s.fs, s.fstride, R, r0, share);
     if (threadIdx.x == 0) {
         double gsum = 0.0, fsum = 0.0;
         for (int w = 0; w < static_cast<int>(blockDim.x >> 6); ++w) { gsum += red[2 * w]; fsum += red[2 * w + 1]; }
@@ -570,8 +579,10 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_scale_kernel(PtqArgs a
     const RowLds s = carve_rows(R, r0);
     load_totals(a.tot[other], R * R + R * r0, s.So);
     for (int k = threadIdx.x; k < R; k += blockDim.x) s.bs[k] = a.beta[k];
-    load_factor_rows(a.F[side], n, r0, row0, s.fs);
+    load_factor_rows(a.F[side], n, r0, row0, s.fs, s.fstride);
     for (int o = threadIdx.x; o < kRows * R; o += blockDim.x) s.xs[o] = row0 + o / R < n ? a.X[side][row0 * R + o] : 0.0;
+    __syncthreads();
+    factor_products(s, R, r0);
     __syncthreads();
     const int gs = group_size_for(R), groups = 64 / gs, waves = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -582,8 +593,7 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_scale_kernel(PtqArgs a
         double num = 0.0, den = 0.0;
         if (l < R) {
             const double v = s.xs[row * R + l] * s.bs[l];
-            double kf = 0.0;
-            for (int q = 0; q < r0; ++q) kf += s.Ko[l * r0 + q] * s.fs[row * r0 + q];
+            const double kf = s.kfs[row * R + l];
             double sv = 0.0;
             for (int m = 0; m < R; ++m) sv += s.So[l * R + m] * (s.xs[row * R + m] * s.bs[m]);
             num = v * kf;
@@ -599,7 +609,7 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_scale_kernel(PtqArgs a
         }
     }
     __syncthreads();
-    gram_share(s.xs, s.cs, s.fs, R, r0, a.part[side] + static_cast<int64_t>(blk) * a.pstride);
+    gram_share(s.xs, s.cs, s.fs, s.fstride, R, r0, a.part[side] + static_cast<int64_t>(blk) * a.pstride);
 }
 
 // Eq. (beta-gram), Eq. (beta-Schur), Eq. (beta-pinv): G = S1 o S2, h_k = K1[k, :] . K2[k, :], beta = pinv(G) h by a
@@ -615,8 +625,9 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a,
     double* P1 = lds;              // S1, K1, gap, sign changes of side 0
     double* P2 = P1 + count + 2;   // the same of side 1
     double* G = P2 + count + 2;    // [R, ld]
-    double* N2 = G + R * ld;       // [R, ld]
-    double* hv = N2 + R * ld;      // [R] permuted right-hand side
+    double* N2 = G + R * ld;       // [R, ld]; the unpivoted attempt uses it as its 16 x 17 area plus the 16-entry extra row
+    const int n2 = R * ld > 16 * 17 + 16 ? R * ld : 16 * 17 + 16;
+    double* hv = N2 + n2;          // [R] permuted right-hand side
     double* h0 = hv + R;           // [R]
     double* bt = h0 + R;           // [R] result
     int* perm = reinterpret_cast<int*>(bt + R);
@@ -642,12 +653,18 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a,
     // tolerance; G itself is left untouched for the pivoted factorisation below.
     bool solved = false;
     double x = 0.0;
-    if (R <= 16) {   // (the 32-entry column of the larger instantiation does not stay in registers here: those ranks pivot at once)
+    if (R <= 16) {   // (a 32-entry column does not stay in registers beside the rest of this kernel: those ranks pivot at once)
+        const int lg = l & 15;   // the wave's four groups of 16 lanes solve the same system; the first one's result is kept
+        const int lc = lg < R ? lg : 0;
         double col[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) col[i] = (i < R && l < R) ? G[i * ld + l] : 0.0;
+        for (int i = 0; i < 16; ++i) {
+            const int ic = i < R ? i : 0;
+            const double own = G[ic * ld + lc];
+            col[i] = (i < R && lg < R) ? own : (i == lg ? 1.0 : 0.0);
+        }
         double min_pivot;
-        const double xf = group_ldlt_solve<16>(col, l < R ? hv[l] : 0.0, N2, bt, ld, R, l, 0, &min_pivot);
+        const double xf = group_ldlt_solve<16>(col, lg < R ? hv[lc] : 0.0, N2, N2 + 16 * 17, R, lg, l & ~15, &min_pivot);
         wave_sync();
         if (min_pivot > tol) { solved = true; x = xf; }
     }
@@ -897,13 +914,13 @@ extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_sta
     const int gs = iR <= 16 ? 16 : 32;
     // the Tikhonov kernel: as many waves solve rows at once as the LDS has room for their matrices (8, 4, 2 or 1); the scale
     // kernel has the same layout without the matrices
-    const size_t lds_fixed = sizeof(double) * (iR * iR + iR * ir0 + iR + kRows * ir0 + 2 * kRows * iR + kRows);
-    const size_t lds_wave = sizeof(double) * (64 / gs) * (iR * ldR + iR);
+    const size_t lds_fixed = sizeof(double) * (iR * iR + iR * ir0 + iR + kRows * (ir0 + 1) + 3 * kRows * iR + kRows);
+    const size_t lds_wave = sizeof(double) * (64 / gs) * (gs * (gs + 1) + gs);   // (systems are padded to the group's 16 or 32 lanes)
     const int ustep_threads = iR <= 16 ? kRowThreads : kRowThreads / 2;
     int solve_waves = ustep_threads / 64;
     while (solve_waves > 1 && lds_fixed + solve_waves * lds_wave > 160 * 1024) solve_waves >>= 1;
     const size_t lds_rows = lds_fixed + solve_waves * lds_wave;
-    const size_t lds_beta = sizeof(double) * (2 * (iR * iR + iR * ir0 + 2) + 2 * iR * ldR + 3 * iR) + sizeof(int) * iR;
+    const size_t lds_beta = sizeof(double) * (2 * (iR * iR + iR * ir0 + 2) + iR * ldR + (iR * ldR > 288 ? iR * ldR : 288) + 3 * iR) + sizeof(int) * iR;
     const int nb01 = a.nb[0] + a.nb[1];
 
     {   // More than 64 KiB of LDS per workgroup has to be asked for; the largest request so far is remembered per device and
