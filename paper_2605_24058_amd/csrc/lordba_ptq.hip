@@ -109,17 +109,28 @@ __device__ inline double group_solve(const double* H, int ld, int n, int l, int 
 }
 
 // This block's share of a side's Gram pair from its rows in LDS: xs [kRows, R], cs [kRows] (0 past the end), fs [kRows, r0]
-// with row stride fstride.
-__device__ inline void gram_share(const double* xs, const double* cs, const double* fs, int fstride, int R, int r0, double* out) {
+// with row stride fstride.  The rows are first scaled in place (xs <- cs o xs; the callers are done with xs), then every
+// thread sums its output over the rows, eight rows' operands requested at a time.
+__device__ inline void gram_share(double* xs, const double* cs, const double* fs, int fstride, int R, int r0, double* out) {
+    for (int o = threadIdx.x; o < kRows * R; o += blockDim.x) xs[o] *= cs[o / R];
+    __syncthreads();
     const int RR = R * R;
     for (int o = threadIdx.x; o < RR + R * r0; o += blockDim.x) {
+        const bool gram = o < RR;
+        const int k = gram ? o / R : (o - RR) / r0;
+        const int j = gram ? o - k * R : (o - RR) - k * r0;
+        const double* right = gram ? xs + j : fs + j;
+        const int rstride = gram ? R : fstride;
         double acc = 0.0;
-        if (o < RR) {
-            const int k = o / R, l = o - k * R;
-            for (int row = 0; row < kRows; ++row) acc += (cs[row] * xs[row * R + k]) * (cs[row] * xs[row * R + l]);
-        } else {
-            const int k = (o - RR) / r0, q = (o - RR) - k * r0;
-            for (int row = 0; row < kRows; ++row) acc += (cs[row] * xs[row * R + k]) * fs[row * fstride + q];
+        for (int row0 = 0; row0 < kRows; row0 += 8) {
+            double u[8], v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                u[e] = xs[(row0 + e) * R + k];
+                v[e] = right[(row0 + e) * rstride];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = fma(u[e], v[e], acc);
         }
         out[o] = acc;
     }
@@ -135,26 +146,32 @@ __device__ inline void load_factor_rows(const __half* F, int64_t n, int r0, int6
 
 extern __shared__ double lds[];
 
-// tot[side][o] = sum over the blocks of part[side][b][o], o < count: 64 outputs per workgroup, blocks in ascending order.
-__global__ __launch_bounds__(64) void lordba_ptq_totals_kernel(PtqArgs a, int side, int count, int always) {
+// tot[side][o] = sum over the blocks of part[side][b][o], o < count: 64 outputs per workgroup of 256 threads.  Wave w adds
+// up the shares b = w, w + 4, w + 8, ... (32 loads in flight per thread), and the four partial sums are added in the
+// order of w: a fixed order, whatever the timing.
+__global__ __launch_bounds__(256) void lordba_ptq_totals_kernel(PtqArgs a, int side, int count, int always) {
     if (!always && a.ctrl[kDone] != 0.0) return;
-    const int o = blockIdx.x * 64 + threadIdx.x;
-    if (o >= count) return;
-    constexpr int kBatch = 64;
-    const double* part = a.part[side] + o;
+    __shared__ double partial[4][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int o = blockIdx.x * 64 + lane;
+    const int oc = o < count ? o : count - 1;
+    constexpr int kBatch = 32;
+    const double* part = a.part[side] + oc;
     const int nb = a.nb[side];
     double acc = 0.0;
-    for (int b0 = 0; b0 < nb; b0 += kBatch) {
+    for (int b0 = w; b0 < nb; b0 += 4 * kBatch) {
         double v[kBatch];
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
-            const int b = b0 + j < nb ? b0 + j : nb - 1;
+            const int b = b0 + 4 * j < nb ? b0 + 4 * j : nb - 1;
             v[j] = part[static_cast<int64_t>(b) * a.pstride];
         }
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j) acc += (b0 + j < nb) ? v[j] : 0.0;
+        for (int j = 0; j < kBatch; ++j) acc += (b0 + 4 * j < nb) ? v[j] : 0.0;
     }
-    a.tot[side][o] = acc;
+    partial[w][lane] = acc;
+    __syncthreads();
+    if (w == 0 && o < count) a.tot[side][o] = (partial[0][lane] + partial[1][lane]) + (partial[2][lane] + partial[3][lane]);
 }
 
 // The totals of a side into LDS.
@@ -944,7 +961,7 @@ extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_sta
     }
     const int count = iR * iR + iR * ir0;
     auto totals = [&](int side, int n, int always) {
-        hipLaunchKernelGGL(lordba_ptq_totals_kernel, dim3((n + 63) / 64), dim3(64), 0, stream, a, side, n, always);
+        hipLaunchKernelGGL(lordba_ptq_totals_kernel, dim3((n + 63) / 64), dim3(256), 0, stream, a, side, n, always);
     };
     if (t_begin == 0) {   // the warm start; a later call continues from the state the workspace holds
         hipLaunchKernelGGL(lordba_ptq_fill_kernel, dim3((kInfoHead + K + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, info,
