@@ -65,8 +65,23 @@ __device__ inline void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// v rotated by N lanes within each row of 16 lanes (data-parallel primitive: no LDS traffic).
+template <int N>
+__device__ inline double row_rotate16(double v) {
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    constexpr int ctrl = 0x120 + N;   // row_ror:N
+    return __hiloint2double(__builtin_amdgcn_update_dpp(0, hi, ctrl, 0xf, 0xf, false),
+                            __builtin_amdgcn_update_dpp(0, lo, ctrl, 0xf, 0xf, false));
+}
+
+// Sum over each group of gs consecutive lanes (gs = 16, 32 or 64), returned in every lane of the group.  Within rows of 16
+// lanes the partial sums travel by rotation, across rows by lane exchange.
 __device__ inline double group_sum(double v, int gs) {
-    for (int m = gs >> 1; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    for (int m = gs >> 1; m >= 16; m >>= 1) v += __shfl_xor(v, m, 64);
+    v += row_rotate16<8>(v);
+    v += row_rotate16<4>(v);
+    v += row_rotate16<2>(v);
+    v += row_rotate16<1>(v);
     return v;
 }
 
