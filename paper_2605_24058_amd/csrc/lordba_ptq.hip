@@ -537,10 +537,10 @@ __global__ __launch_bounds__(RMAX <= 16 ? kRowThreads : kRowThreads / 2) void lo
     load_factor_rows(a.F[side], n, r0, row0, s.fs, s.fstride);
     for (int row = threadIdx.x; row < kRows; row += blockDim.x) s.cs[row] = row0 + row < n ? a.scale[side][row0 + row] : 0.0;
     const double rho_k = a.ctrl[kRho] / (static_cast<double>(n) * R), yfac = a.ctrl[kYfac];
-    for (int o = threadIdx.x; o < kRows * R; o += blockDim.x) {   // xs holds M until the row is solved, ys the rescaled Y
-        const bool in = row0 + o / R < n;
-        s.xs[o] = in ? a.Mm[side][row0 * R + o] : 0.0;
-        s.ys[o] = in ? yfac * a.Y[side][row0 * R + o] : 0.0;
+    for (int o = threadIdx.x; o < kRows * R; o += blockDim.x) {   // xs holds M until the row is solved, ys holds Y (its pending
+        const bool in = row0 + o / R < n;                         // rescaling is applied where it is read, so that these loads
+        s.xs[o] = in ? a.Mm[side][row0 * R + o] : 0.0;            // do not wait for the control words)
+        s.ys[o] = in ? a.Y[side][row0 * R + o] : 0.0;
     }
     __syncthreads();
     factor_products(s, R, r0);
@@ -559,7 +559,7 @@ __global__ __launch_bounds__(RMAX <= 16 ? kRowThreads : kRowThreads / 2) void lo
             const int row = pass * rows_per_pass + wave * groups + g;
             const bool in = row0 + row < n;
             const double c = s.cs[row], c2 = c * c, bl = s.bs[lc];
-            const double m_old = s.xs[row * R + lc], y_old = s.ys[row * R + lc];
+            const double m_old = s.xs[row * R + lc], y_old = yfac * s.ys[row * R + lc];
             double b = act ? c * bl * s.kfs[row * R + lc] + rho_k * (m_old - y_old) : 0.0;
             double col[RMAX];
 #pragma unroll
@@ -626,8 +626,19 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_scale_kernel(PtqArgs a
         if (l < R) {
             const double v = s.xs[row * R + l] * s.bs[l];
             const double kf = s.kfs[row * R + l];
-            double sv = 0.0;
-            for (int m = 0; m < R; ++m) sv += s.So[l * R + m] * (s.xs[row * R + m] * s.bs[m]);
+            double sv = 0.0;   // (So v)_l: So is symmetric, so lane l walks column l (consecutive lanes, consecutive words)
+            for (int m0 = 0; m0 < R; m0 += 8) {
+                double so[8], xv[8], bv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int m = m0 + e < R ? m0 + e : R - 1;
+                    so[e] = s.So[m * R + l];
+                    xv[e] = s.xs[row * R + m];
+                    bv[e] = s.bs[m];
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sv += (m0 + e < R) ? so[e] * (xv[e] * bv[e]) : 0.0;
+            }
             num = v * kf;
             den = v * sv;
         }
