@@ -358,19 +358,34 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
         __syncthreads();
     }
     float dscale = 0.f;
+    const bool with_lat = a.d_latA != nullptr;   // (null: the carriers are frozen, only the scale gradients are wanted)
+    const bool lat_x = with_lat && is_x, add_x = lat_x && a.accumulate;
     for (int k = kq; k < r; k += 8) {
+        // Everything this rank needs is requested before anything is used: the shares of the token ranges (eight at a
+        // time, from a clamped index), the carrier word, the latent and, when accumulating, the gradient so far.  The
+        // last two come from a harmless address when they are not wanted, so that no request hides behind a branch.
+        const size_t n = static_cast<size_t>(k) * d + col;
+        const uint32_t word = pk[k * (d >> 5) + grp];
+        const float latent = *(lat_x ? a.latA + n : plane);
+        const float so_far = *(add_x ? a.d_latA + n : plane);
         float s = 0.f;
-        for (int sp = 0; sp < a.splits; ++sp) s += plane[(static_cast<size_t>(sp) * a.rp + k) * a.dcols];
-        const uint32_t bit = (pk[k * (d >> 5) + grp] >> c) & 1u;
-        dscale += flip(s, bit);
-        if (a.d_latA != nullptr) {  // (null: the carriers are frozen, only the scale gradients are wanted)
-            if (is_x) {
-                const size_t n = static_cast<size_t>(k) * d + col;
-                const float val = scale * s * smooth_sign_factor(a.latA[n], a.kappa);
-                a.d_latA[n] = a.accumulate ? a.d_latA[n] + val : val;
-            } else {
-                lat[c * r + k] = scale * s * smooth_sign_factor(lat[c * r + k], a.kappa);
+        for (int sp0 = 0; sp0 < a.splits; sp0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int sp = sp0 + j < a.splits ? sp0 + j : a.splits - 1;
+                v[j] = plane[(static_cast<size_t>(sp) * a.rp + k) * a.dcols];
             }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += (sp0 + j < a.splits) ? v[j] : 0.f;
+        }
+        const uint32_t bit = (word >> c) & 1u;
+        dscale += flip(s, bit);
+        if (lat_x) {
+            const float val = scale * s * smooth_sign_factor(latent, a.kappa);
+            a.d_latA[n] = add_x ? so_far + val : val;
+        } else if (with_lat) {
+            lat[c * r + k] = scale * s * smooth_sign_factor(lat[c * r + k], a.kappa);
         }
     }
     sh[tid] = dscale;
