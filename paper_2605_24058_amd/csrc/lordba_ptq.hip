@@ -238,11 +238,13 @@ __device__ inline void jacobi_onesided(double* W, double* V, int n, int ld, int 
                 const bool mine = valid && i < n;
                 const double wp = mine ? W[i * ld + p] : 0.0, wq = mine ? W[i * ld + q] : 0.0;
                 const double app = group_sum(wp * wp, gsz), aqq = group_sum(wq * wq, gsz), apq = group_sum(wp * wq, gsz);
-                const bool rot = valid && fabs(apq) > 1e-15 * sqrt(app * aqq);
+                const bool rot = valid && apq * apq > 1e-30 * (app * aqq);   // |apq| > 1e-15 sqrt(app aqq)
                 if (rot && mine) {
-                    const double zeta = (aqq - app) / (2.0 * apq);
-                    const double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                    const double cs = 1.0 / sqrt(1.0 + t * t), sn = cs * t;
+                    // tangent of the rotation angle: with zeta = (aqq - app) / (2 apq), t = sign(zeta) / (|zeta| + sqrt(1 + zeta^2)),
+                    // written with one square root and one division: t = sign(d) h / (|d| + sqrt(d^2 + h^2)), d = aqq - app, h = 2 apq
+                    const double d = aqq - app, h = 2.0 * apq;
+                    const double t = (signbit(d) ? -h : h) / (fabs(d) + sqrt(d * d + h * h));
+                    const double cs = rsqrt(1.0 + t * t), sn = cs * t;
                     W[i * ld + p] = cs * wp - sn * wq;
                     W[i * ld + q] = sn * wp + cs * wq;
                     const double vp = V[i * ld + p], vq = V[i * ld + q];
@@ -819,23 +821,29 @@ __global__ __launch_bounds__(kThreads) void lordba_ptq_export_kernel(PtqArgs a, 
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
     const int64_t N = a.n[0], M = a.n[1];
     const int R = a.R;
+    // a word's 32 entries are requested together (from a clamped position), then tested
     if (i < e.wordsA) {
-        uint32_t w = 0;
+        double v[32];
+#pragma unroll
         for (int bit = 0; bit < 32; ++bit) {
-            const int64_t nbit = i * 32 + bit;
-            if (nbit < N * R) {
-                const int64_t k = nbit / N, row = nbit - k * N;
-                if (a.Mm[0][row * R + k] < 0.0) w |= 1u << bit;
-            }
+            const int nbit = static_cast<int>(i * 32 + bit < N * R ? i * 32 + bit : N * R - 1);   // (N R <= 2^27)
+            const int k = nbit / static_cast<int>(N), row = nbit - k * static_cast<int>(N);
+            v[bit] = a.Mm[0][row * R + k];
         }
+        uint32_t w = 0;
+#pragma unroll
+        for (int bit = 0; bit < 32; ++bit)
+            if (i * 32 + bit < N * R && v[bit] < 0.0) w |= 1u << bit;
         e.packedA[i] = w;
     }
     if (i < e.wordsB) {
+        double v[32];
+#pragma unroll
+        for (int bit = 0; bit < 32; ++bit) v[bit] = a.Mm[1][i * 32 + bit < M * R ? i * 32 + bit : M * R - 1];
         uint32_t w = 0;
-        for (int bit = 0; bit < 32; ++bit) {
-            const int64_t nbit = i * 32 + bit;
-            if (nbit < M * R && a.Mm[1][nbit] < 0.0) w |= 1u << bit;
-        }
+#pragma unroll
+        for (int bit = 0; bit < 32; ++bit)
+            if (i * 32 + bit < M * R && v[bit] < 0.0) w |= 1u << bit;
         e.packedB[i] = w;
     }
     if (e.s_in && i < N) e.s_in[i] = half_from_double(a.scale[0][i]);
