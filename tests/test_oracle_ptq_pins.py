@@ -289,3 +289,28 @@ def test_signs_stabilise_within_fifty_sweeps_and_the_tail_converges(seed, N, M, 
     step = [np.linalg.norm(tr[t]["U1"] - tr[t - 1]["U1"]) + np.linalg.norm(tr[t]["U2"] - tr[t - 1]["U2"]) for t in range(K // 2, K)]
     assert step[-1] <= 1e-10 * np.linalg.norm(tr[-1]["U1"])
     assert abs(out["objective"][-1] - out["objective"][K // 2]) <= 1e-9 * out["objective"][-1]
+
+
+def test_defaults_are_the_settings_the_paper_prints():
+    """K, (tau, mu), the truncation of the penalty schedule and the warm penalty against tests/golden/ptq_settings.txt."""
+    import inspect
+    import os
+    gold = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "ptq_settings.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            gold[k] = float(v)
+    sig = inspect.signature(P.ptq).parameters
+    assert sig["K"].default == gold["K"] and sig["tau"].default == gold["tau"] and sig["mu"].default == gold["mu"]
+    from paper_2605_24058_amd import binding
+    bsig = inspect.signature(binding.lordba_ptq).parameters
+    assert bsig["K"].default == gold["K"] and bsig["tau"].default == gold["tau"] and bsig["mu"].default == gold["mu"]
+    d = inputs.make_ptq_inputs(3, 60, 50, 6)
+    T = d["A_star"].astype(np.float64) @ d["B_star"].astype(np.float64).T
+    K = 20
+    tr = []
+    P.ptq(d["A_star"], d["B_star"], 4, K=K, trace=tr, stop_on_freeze=False)
+    rho0 = np.sum(T * T) / (60 * 4 + 4 * 50)                                  # the printed warm penalty
+    assert tr[0]["rho"] / rho0 in (0.5, 1.0, 2.0)
+    last_change = max(t for t in range(1, K) if tr[t]["rho"] != tr[t - 1]["rho"])
+    assert last_change < gold["balancing_until_fraction_of_K"] * K             # no change from sweep K / 2 on
