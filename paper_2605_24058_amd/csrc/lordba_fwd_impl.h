@@ -130,6 +130,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // under a vector-predicated branch, which is what a condition on a value derived from threadIdx may compile to.
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, q = lane >> 4;
+    const int li_ = li, q_ = q;  // (issue_x shadows li and q, see there)
     const int d_in = a.d_in, d_out = a.d_out, r = a.r;
     const int nchunks = (d_in + 127) >> 7;
 
@@ -167,6 +168,14 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     auto issue_x = [&](int slot, int n) {
         int c = wave + NW * n;
         c = c < nchunks ? c : nchunks - 1;  // past the end: re-read a valid chunk, the result is not used
+        // 16 waves leave 128 registers per lane.  In the looped pipeline the compiler would keep every lane's row and rank
+        // offsets in registers across the loop (the chunk index is scalar, so they are loop invariants) and spill; hiding
+        // the lane coordinates behind an empty asm makes it recompute them per chunk, a few vector-ALU instructions.
+        int q = q_, li = li_;
+        if constexpr (NW == 16 && !OS) {
+            asm volatile("" : "+v"(q));
+            asm volatile("" : "+v"(li));
+        }
 #pragma unroll
         for (int en = 0; en < L; ++en) {
             const int pair = c * 64 + lane;  // fp16 pair index; d_in is even, so a pair is inside or outside as a whole
@@ -931,7 +940,11 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
         } else if (algo == 6 || algo == 7) {   // tuning variants: 8 waves
             s = tall ? launch_mfma_rb<16, 8, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
         } else if (tall) {
-            s = rb == 1 ? launch_mfma_rb<16, 16, 1>(a, st) : launch_mfma_rb<16, 8, 1>(a, st);
+            // With more 16-row tiles than the 256 compute units, 8-wave workgroups win: two of them share a compute
+            // unit, and one streams its y rows while the other is in its sign stages (0.5 to 9 % on nine shapes with
+            // 384 to 1024 tiles).  With one tile per compute unit the 16 waves hide more latency.
+            const bool two_per_cu = algo == LORDBA_ALGO_AUTO && (T + 15) / 16 > 256;
+            s = rb == 1 && !two_per_cu ? launch_mfma_rb<16, 16, 1>(a, st) : launch_mfma_rb<16, 8, 1>(a, st);
         } else if (batched && (T + 7) / 8 > 32) {
             s = launch_mfma_rb<8, 8, 1>(a, st);  // two workgroups per CU: see the batch mode of the kernel
         } else {
