@@ -121,6 +121,27 @@ def test_small_shapes_all_kernels(torch_cuda, sh):
             assert e.status == 8 and algo in A_VARIANTS, (algo, e.status)
 
 
+# Batches around the point where the library changes the workgroup shape of its 16-row kernel (more tiles than compute
+# units), with a partial last tile, with the looped x pipeline (d_in > 8192), and with the kernels chosen by hand.
+TALL = [
+    inputs.Shape("tall_T4096_256x384_r16", 4096, 256, 384, 16),      # one tile per compute unit
+    inputs.Shape("tall_T4097_256x384_r16", 4097, 256, 384, 16),      # one more tile, holding a single row
+    inputs.Shape("tall_T4111_8320x128_r16", 4111, 8320, 128, 16),    # looped x pipeline, ragged last tile
+    inputs.Shape("tall_T4099_384x264_r8", 4099, 384, 264, 8),        # r = 8, tail output block
+    inputs.Shape("tall_T4101_512x256_r32", 4101, 512, 256, 32),      # two rank blocks
+]
+
+
+@pytest.mark.parametrize("sh", TALL, ids=lambda s: s.name)
+def test_tall_batches_every_workgroup_shape(torch_cuda, sh):
+    d = inputs.make_inputs_for(sh, 300 + sh.T)
+    for algo in [A_AUTO, A_T16, A_T8] + list(A_VARIANTS):
+        try:
+            check(torch_cuda, d, algo, sh.name)
+        except binding.LordbaError as e:
+            assert e.status == 8 and algo in A_VARIANTS, (algo, e.status)
+
+
 GENERAL_ONLY = [
     inputs.Shape("odd_T5_33x17_r3", 5, 33, 17, 3),         # nothing aligned: general kernel, scalar path
     inputs.Shape("odd_T7_100x60_r5", 7, 100, 60, 5),
