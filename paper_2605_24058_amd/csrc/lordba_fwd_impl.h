@@ -939,6 +939,11 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
             s = tall ? launch_mfma_rb<16, 4, 1>(a, st) : launch_mfma_rb<8, 4, 1>(a, st);
         } else if (algo == 6 || algo == 7) {   // tuning variants: 8 waves
             s = tall ? launch_mfma_rb<16, 8, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
+        } else if (algo == LORDBA_ALGO_AUTO && !batched && T >= 4096 && d_out >= 8192 && d_out % 4096 == 0) {
+            // Rows of y that lie a multiple of 8 KiB apart: the rows of a tile then meet in the same memory channels, and
+            // 8-row tiles on 8 waves stream y faster than 16-row tiles do (1.6 to 14 % on ten shapes with d_out = 8192,
+            // 16384, 20480, 28672; no such gain at 11008, 13824, 14336).
+            s = launch_mfma_rb<8, 8, 1>(a, st);
         } else if (tall) {
             // With more 16-row tiles than the 256 compute units, 8-wave workgroups win: two of them share a compute
             // unit, and one streams its y rows while the other is in its sign stages (0.5 to 9 % on nine shapes with
