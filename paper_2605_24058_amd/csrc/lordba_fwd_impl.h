@@ -933,16 +933,18 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
     const bool tall = batched ? false
                               : algo == LORDBA_ALGO_AUTO ? T >= 4096 : (algo == LORDBA_ALGO_MFMA_T16 || algo == 5 || algo == 7);
     if (batched && algo != LORDBA_ALGO_AUTO && algo != LORDBA_ALGO_MFMA_T8) return LORDBA_ERR_ALGO;
+    auto far_apart = [](int64_t d) { return d >= 8192 && d % 4096 == 0; };
     lordba_status s;
     if constexpr (L == 1) {
         if (algo == 4 || algo == 5) {          // tuning variants: 4 waves
             s = tall ? launch_mfma_rb<16, 4, 1>(a, st) : launch_mfma_rb<8, 4, 1>(a, st);
         } else if (algo == 6 || algo == 7) {   // tuning variants: 8 waves
             s = tall ? launch_mfma_rb<16, 8, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
-        } else if (algo == LORDBA_ALGO_AUTO && !batched && T >= 4096 && d_out >= 8192 && d_out % 4096 == 0) {
-            // Rows of y that lie a multiple of 8 KiB apart: the rows of a tile then meet in the same memory channels, and
-            // 8-row tiles on 8 waves stream y faster than 16-row tiles do (1.6 to 14 % on ten shapes with d_out = 8192,
-            // 16384, 20480, 28672; no such gain at 11008, 13824, 14336).
+        } else if (algo == LORDBA_ALGO_AUTO && !batched && T >= 4096 && (far_apart(d_in) || far_apart(d_out))) {
+            // Rows of x or of y that lie a multiple of 8 KiB apart (16 KiB or more): the rows of a tile then meet in the
+            // same memory channels, and 8-row tiles on 8 waves stream them faster than 16-row tiles do (up to 14 % on
+            // eighteen shapes with d_in or d_out = 8192, 16384, 20480, 28672, never slower; no such gain at 11008, 13824,
+            // 14336).
             s = launch_mfma_rb<8, 8, 1>(a, st);
         } else if (tall) {
             // With more 16-row tiles than the 256 compute units, 8-wave workgroups win: two of them share a compute

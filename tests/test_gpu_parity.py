@@ -130,6 +130,7 @@ TALL = [
     inputs.Shape("tall_T4099_384x264_r8", 4099, 384, 264, 8),        # r = 8, tail output block
     inputs.Shape("tall_T4101_512x256_r32", 4101, 512, 256, 32),      # two rank blocks
     inputs.Shape("tall_T4097_256x8192_r16", 4097, 256, 8192, 16),    # y rows a multiple of 8 KiB apart: 8-row tiles again
+    inputs.Shape("tall_T4098_8192x136_r16", 4098, 8192, 136, 16),    # the same for the rows of x
 ]
 
 
