@@ -955,7 +955,10 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
         } else if (batched && (T + 7) / 8 > 32) {
             s = launch_mfma_rb<8, 8, 1>(a, st);  // two workgroups per CU: see the batch mode of the kernel
         } else {
-            s = rb <= 2 ? launch_mfma_rb<8, 16, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
+            // More 8-row tiles than compute units (2048 < T < 4096): 8 waves again, for the same reason (1 to 10 % on
+            // twelve of thirteen shapes at T = 2304 ... 3584, 1 % slower on one).
+            const bool two_per_cu = algo == LORDBA_ALGO_AUTO && (T + 7) / 8 > 256;
+            s = rb <= 2 && !two_per_cu ? launch_mfma_rb<8, 16, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
         }
     } else {
         if (t_out != nullptr) {

@@ -131,6 +131,8 @@ TALL = [
     inputs.Shape("tall_T4101_512x256_r32", 4101, 512, 256, 32),      # two rank blocks
     inputs.Shape("tall_T4097_256x8192_r16", 4097, 256, 8192, 16),    # y rows a multiple of 8 KiB apart: 8-row tiles again
     inputs.Shape("tall_T4098_8192x136_r16", 4098, 8192, 136, 16),    # the same for the rows of x
+    inputs.Shape("mid_T2049_256x384_r16", 2049, 256, 384, 16),       # one 8-row tile more than compute units
+    inputs.Shape("mid_T3001_640x264_r24", 3001, 640, 264, 24),
 ]
 
 
