@@ -255,6 +255,30 @@ lordba_status lordba_backward_multi(const void* x, const void* g,
 /* Bytes of workspace lordba_backward needs for a shape (0 for a shape it does not support). */
 size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, int64_t r);
 
+/* Size of the library-owned scratch array behind lordba_backward_noalloc (one per GPU the library runs on, held until the
+ * process ends). */
+#define LORDBA_BACKWARD_NOALLOC_MAX_BYTES (16 * 1024 * 1024)
+
+/* DEVICE function for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving or training loops, harnesses that forbid allocation.  It is lordba_backward (same arguments, kernels,
+ * results bit for bit, error codes) without the workspace arguments: the scratch lives in a device array of
+ * LORDBA_BACKWARD_NOALLOC_MAX_BYTES bytes that is part of the library's code object, and the call allocates and frees
+ * nothing (its first call on a device only looks up that device's address of the array; make that call outside a graph
+ * capture).  A shape with lordba_backward_workspace_bytes(T, d_in, d_out, r) > LORDBA_BACKWARD_NOALLOC_MAX_BYTES ->
+ * LORDBA_ERR_WORKSPACE, nothing is enqueued (every shape of the paper's models at r = 16 and T <= 8192 fits; so does
+ * d = 4096, r = 64, T = 2048).  All calls on one GPU share that GPU's array: calls that may overlap in time (different
+ * streams, or graphs replayed side by side) race on it and must be ordered by the caller.  The array's contents after a
+ * call are unspecified; nothing in it needs clearing between calls. */
+lordba_status lordba_backward_noalloc(const void* x, const void* g,
+                                      const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
+                                      const void* s_in, const void* s_rank, const void* s_out,
+                                      const float* latentA, const float* latentB, float kappa,
+                                      const float* t_saved, int64_t t_stride,
+                                      const void* dx_base, void* dx,
+                                      float* d_s_in, float* d_s_rank, float* d_s_out,
+                                      float* d_latentA, float* d_latentB,
+                                      int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream);
+
 /* ---- post-training quantisation of a low-rank update into a LoRDBA adapter ---------------------------------------- */
 
 #define LORDBA_PTQ_MAX_RANK 32         /* carrier rank R of lordba_ptq                    */

@@ -139,6 +139,8 @@ def load_library():
     lib.lordba_backward_workspace_bytes.argtypes = [i64] * 4
     lib.lordba_backward.restype = ci
     lib.lordba_backward.argtypes = [vp] * 10 + [ctypes.c_float, vp, i64] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 4 + [vp]
+    lib.lordba_backward_noalloc.restype = ci
+    lib.lordba_backward_noalloc.argtypes = [vp] * 10 + [ctypes.c_float, vp, i64] + [vp] * 7 + [i64] * 4 + [vp]
     lib.lordba_backward_multi.restype = ci
     lib.lordba_backward_multi.argtypes = [vp] * 10 + [ctypes.c_float, vp, i64] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 5 + [vp]
     lib.lordba_forward_multi_save_t.restype = ci
@@ -241,9 +243,9 @@ def lordba_forward(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out=None,
         stream = torch.cuda.current_stream(x.device).cuda_stream
     elif hasattr(stream, "cuda_stream"):
         stream = stream.cuda_stream
-    st = lib.lordba_forward_algo(x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(),
-                                 s_rank.data_ptr(), s_out.data_ptr(), y_base.data_ptr(), y_out.data_ptr(),
-                                 T, d_in, d_out, r, ctypes.c_void_p(stream), int(algo))
+    args = (x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(),
+            y_base.data_ptr(), y_out.data_ptr(), T, d_in, d_out, r, ctypes.c_void_p(stream))
+    st = lib.lordba_forward_algo(*args, int(algo))
     if st != 0:
         raise LordbaError(st, "lordba_forward")
     return y_out
@@ -284,9 +286,9 @@ def lordba_forward_multi(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out
         stream = torch.cuda.current_stream(x.device).cuda_stream
     elif hasattr(stream, "cuda_stream"):
         stream = stream.cuda_stream
-    st = lib.lordba_forward_multi_algo(x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(),
-                                       s_rank.data_ptr(), s_out.data_ptr(), y_base.data_ptr(), y_out.data_ptr(),
-                                       T, d_in, d_out, r, ell, ctypes.c_void_p(stream), int(algo))
+    args = (x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(),
+            y_base.data_ptr(), y_out.data_ptr(), T, d_in, d_out, r, ell, ctypes.c_void_p(stream))
+    st = lib.lordba_forward_multi_algo(*args, int(algo))
     if st != 0:
         raise LordbaError(st, "lordba_forward_multi")
     return y_out
@@ -336,10 +338,10 @@ def lordba_forward_batched(x, packedA_pool, packedB_pool, s_in_pool, s_rank_pool
         stream = torch.cuda.current_stream(x.device).cuda_stream
     elif hasattr(stream, "cuda_stream"):
         stream = stream.cuda_stream
-    st = lib.lordba_forward_batched_algo(x.data_ptr(), packedA_pool.data_ptr(), packedB_pool.data_ptr(), s_in_pool.data_ptr(),
-                                         s_rank_pool.data_ptr(), s_out_pool.data_ptr(), adapter_of_row.data_ptr(),
-                                         y_base.data_ptr(), y_out.data_ptr(), T, d_in, d_out, r, n,
-                                         ctypes.c_void_p(stream), int(algo))
+    args = (x.data_ptr(), packedA_pool.data_ptr(), packedB_pool.data_ptr(), s_in_pool.data_ptr(), s_rank_pool.data_ptr(),
+            s_out_pool.data_ptr(), adapter_of_row.data_ptr(), y_base.data_ptr(), y_out.data_ptr(), T, d_in, d_out, r, n,
+            ctypes.c_void_p(stream))
+    st = lib.lordba_forward_batched_algo(*args, int(algo))
     if st != 0:
         raise LordbaError(st, "lordba_forward_batched")
     return y_out
@@ -420,7 +422,8 @@ def lordba_forward_save_t(x, packedA, packedB, s_in, s_rank, s_out, y_base=None,
 
 
 def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa: float,
-                    dx_base=None, dx=None, workspace=None, stream=None, check: bool = True, t_saved=None) -> dict:
+                    dx_base=None, dx=None, workspace=None, stream=None, check: bool = True, t_saved=None,
+                    _noalloc: bool = False, out: Optional[dict] = None) -> dict:
     """Gradients of the branch on the GPU (see include/lordba.h).  All tensors are torch CUDA tensors: x [T, d_in],
     g [T, d_out], s_* float16; packed* int32; latentA [r, d_in], latentB [d_out, r] float32; dx_base [T, d_in] float16
     or None (then no input gradient is computed); t_saved: the float32 [r, stride] tensor lordba_forward_save_t returned
@@ -457,28 +460,46 @@ def lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, late
         if dx_base is not None and (dx_base.dtype != torch.float16 or not dx_base.is_cuda or not dx_base.is_contiguous()
                                     or dx_base.shape != x.shape):
             raise TypeError("dx_base must be a contiguous float16 CUDA tensor shaped like x")
-    need = lordba_backward_workspace_bytes(T, d_in, d_out, r)
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    if dx_base is not None and dx is None:
+    if workspace is None and not _noalloc:
+        workspace = torch.empty(max(lordba_backward_workspace_bytes(T, d_in, d_out, r), 16), dtype=torch.uint8, device=x.device)
+    if out is not None:
+        dx = out["dx"]
+    elif dx_base is not None and dx is None:
         dx = torch.empty_like(dx_base)
     f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=x.device)
-    out = {"dx": dx, "d_s_in": f32(d_in), "d_s_rank": f32(r), "d_s_out": f32(d_out),
-           "d_latentA": None if latentA is None else f32(r, d_in), "d_latentB": None if latentB is None else f32(d_out, r)}
+    if out is None:
+        out = {"dx": dx, "d_s_in": f32(d_in), "d_s_rank": f32(r), "d_s_out": f32(d_out),
+               "d_latentA": None if latentA is None else f32(r, d_in), "d_latentB": None if latentB is None else f32(d_out, r)}
     if stream is None:
         stream = torch.cuda.current_stream(x.device).cuda_stream
     elif hasattr(stream, "cuda_stream"):
         stream = stream.cuda_stream
     ptr = lambda t_: None if t_ is None else t_.data_ptr()
-    st = lib.lordba_backward(x.data_ptr(), g.data_ptr(), packedA.data_ptr(), packedAt.data_ptr(), packedBt.data_ptr(),
-                             s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(), ptr(latentA), ptr(latentB),
-                             float(kappa), ptr(t_saved), 0 if t_saved is None else t_saved.shape[1],
-                             ptr(dx_base), ptr(dx), out["d_s_in"].data_ptr(), out["d_s_rank"].data_ptr(),
-                             out["d_s_out"].data_ptr(), ptr(out["d_latentA"]), ptr(out["d_latentB"]),
-                             workspace.data_ptr(), workspace.numel(), T, d_in, d_out, r, ctypes.c_void_p(stream))
+    head = (x.data_ptr(), g.data_ptr(), packedA.data_ptr(), packedAt.data_ptr(), packedBt.data_ptr(),
+            s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(), ptr(latentA), ptr(latentB),
+            float(kappa), ptr(t_saved), 0 if t_saved is None else t_saved.shape[1],
+            ptr(dx_base), ptr(dx), out["d_s_in"].data_ptr(), out["d_s_rank"].data_ptr(),
+            out["d_s_out"].data_ptr(), ptr(out["d_latentA"]), ptr(out["d_latentB"]))
+    tail = (T, d_in, d_out, r, ctypes.c_void_p(stream))
+    if _noalloc:
+        st = lib.lordba_backward_noalloc(*head, *tail)
+    else:
+        st = lib.lordba_backward(*head, workspace.data_ptr(), workspace.numel(), *tail)
     if st != 0:
-        raise LordbaError(st, "lordba_backward")
+        raise LordbaError(st, "lordba_backward_noalloc" if _noalloc else "lordba_backward")
     return out
+
+
+BACKWARD_NOALLOC_MAX_BYTES = 16 * 1024 * 1024   # LORDBA_BACKWARD_NOALLOC_MAX_BYTES of include/lordba.h
+
+
+def lordba_backward_noalloc(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa: float,
+                            dx_base=None, stream=None, t_saved=None, out: Optional[dict] = None) -> dict:
+    """lordba_backward_noalloc of the C interface: lordba_backward with the scratch in the library's own device array
+    instead of a workspace.  The C call allocates nothing; this wrapper allocates the output tensors unless `out` (the
+    dict of an earlier call of the same shape) is passed, in which case nothing at all is allocated."""
+    return lordba_backward(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa,
+                           dx_base=dx_base, stream=stream, t_saved=t_saved, _noalloc=True, out=out)
 
 
 def lordba_forward_multi_save_t(x, packedA, packedB, s_in, s_rank, s_out, y_base=None, y_out=None, t_out=None, stream=None):

@@ -27,6 +27,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "lordba.h"
 #include "lordba_dev_util.h"
 
@@ -594,4 +596,52 @@ extern "C" lordba_status lordba_backward_multi(const void* x, const void* g,
                                                int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream) {
     return backward_impl(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa, t_saved, t_stride, dx_base, dx,
                          d_s_in, d_s_rank, d_s_out, d_latentA, d_latentB, workspace, workspace_bytes, T, d_in, d_out, r, ell, stream);
+}
+
+// ---------------------------------------------------------------------------- entry point that allocates nothing ----
+// For callers that cannot allocate or pass a workspace: the scratch of the call (rank-r intermediates and partial sums, the
+// layout of make_plan) lives in a device array of fixed size that belongs to the library.  Every GPU holds its own copy
+// at its own address; in host code the array's name is only a handle, so the address is asked for once per device and
+// that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[LORDBA_BACKWARD_NOALLOC_MAX_BYTES];
+
+namespace {
+lordba_status noalloc_scratch(void** out) {
+    static std::mutex mu;
+    static void* ptr[64] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LORDBA_ERR_NO_DEVICE; }
+    if (dev < 0 || dev >= 64) return LORDBA_ERR_NO_DEVICE;
+    std::lock_guard<std::mutex> g(mu);
+    if (ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return LORDBA_ERR_NO_DEVICE;
+        }
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return LORDBA_OK;
+}
+}  // namespace
+
+extern "C" lordba_status lordba_backward_noalloc(const void* x, const void* g,
+                                                 const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
+                                                 const void* s_in, const void* s_rank, const void* s_out,
+                                                 const float* latentA, const float* latentB, float kappa,
+                                                 const float* t_saved, int64_t t_stride,
+                                                 const void* dx_base, void* dx,
+                                                 float* d_s_in, float* d_s_rank, float* d_s_out,
+                                                 float* d_latentA, float* d_latentB,
+                                                 int64_t T, int64_t d_in, int64_t d_out, int64_t r, void* stream) {
+    if (!supported(T, d_in, d_out, r)) return LORDBA_ERR_DIM;
+    // the size check comes first: a shape beyond the array is refused whatever else is wrong with the call
+    if (make_plan(T, d_in, d_out, r).words * 4 > static_cast<size_t>(LORDBA_BACKWARD_NOALLOC_MAX_BYTES)) return LORDBA_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const lordba_status s = noalloc_scratch(&ws);
+    if (s != LORDBA_OK) return s;
+    // Nothing in the scratch has to start at zero: every word a kernel reads was written earlier in the same call.
+    return backward_impl(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out, latentA, latentB, kappa, t_saved, t_stride, dx_base, dx,
+                         d_s_in, d_s_rank, d_s_out, d_latentA, d_latentB, ws, LORDBA_BACKWARD_NOALLOC_MAX_BYTES, T, d_in, d_out, r, 1, stream);
 }
