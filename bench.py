@@ -28,12 +28,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
-# HBM bytes per launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size
-# (profiles/lordba_fwd_mfma_c2_hbm_traffic.txt); bench.py cannot read hardware counters itself.
-MEASURED_TRAFFIC_BYTES = {"c2_llama7b_attn_4096x4096_r16_T2048": 49487 * 1024}
-# the same for lordba_backward (profiles/lordba_backward_c2_hbm_traffic.txt): t recomputed from x / t kept by the forward
-MEASURED_BACKWARD_TRAFFIC_BYTES = {"c2_llama7b_attn_4096x4096_r16_T2048": (106605 * 1024, 89900 * 1024)}
+# bench.py cannot read hardware counters itself: `traffic` (HBM bytes per call from rocprofv3 FETCH_SIZE + WRITE_SIZE) is
+# looked up in profiles/hbm_traffic.json, which paper_2605_24058_amd/traffic_profile.py writes from the counter files and
+# stamps with a hash of the kernel sources; it is null, with the reason, once those sources have changed.
 CACHE_BYTES = 256 << 20        # Infinity Cache
+REPS = 7                       # repetitions of the timed region; the median one is reported
 
 WORKLOADS = {}
 
@@ -48,14 +47,19 @@ def _workloads():
     return WORKLOADS
 
 
-def timed(fn, K, W, graph, reps=1):
+WARM_SECONDS = 0.06            # untimed replays of the timed region before the first timed one: the clocks ramp up
+
+
+def timed(fn, K, W, graph, reps=1, warm_s=WARM_SECONDS):
     """Runs fn(0..K-1) as the timed region `reps` times.  Returns (microseconds per step of each repetition from HIP
-    events on the launch stream, wall-clock seconds of the first repetition)."""
+    events on the launch stream, wall-clock seconds of each repetition).  Before the first timed repetition the region is
+    run untimed for at least `warm_s` seconds, whatever W and K are: on a box that has been idle the first ~50 ms of work
+    run at lower clocks, and a region of a few dozen 10-microsecond launches would otherwise be measured inside that ramp."""
     import torch
     for i in range(W):
         fn(i)
     torch.cuda.synchronize()
-    us, wall = [], None
+    us, walls = [], []
     if graph:
         # The K launches of the timed region are captured once and replayed: same kernels, same buffers, no host
         # launch cost between them.  Only kernel launches are captured (no memset nodes).
@@ -69,6 +73,11 @@ def timed(fn, K, W, graph, reps=1):
         def run():
             for i in range(K):
                 fn(i)
+    torch.cuda.synchronize()
+    t_warm = time.perf_counter()
+    while time.perf_counter() - t_warm < warm_s:
+        run()
+        torch.cuda.synchronize()
     for _ in range(reps):
         a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
@@ -79,8 +88,14 @@ def timed(fn, K, W, graph, reps=1):
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         us.append(a0.elapsed_time(a1) * 1e3 / K)
-        wall = wall if wall is not None else t1 - t0
-    return us, wall
+        walls.append(t1 - t0)
+    return us, walls
+
+
+def _median_index(v):
+    """Index of the median repetition (the lower of the two middle ones for an even count): a figure that was measured."""
+    order = sorted(range(len(v)), key=lambda i: v[i])
+    return order[(len(v) - 1) // 2]
 
 
 def _median(v):
@@ -118,8 +133,8 @@ def bench_c4_sweep(args):
             binding.lordba_forward(xs[s], dev["packedA"], dev["packedB"], dev["s_in"], dev["s_rank"], dev["s_out"],
                                    ybs[s], y_out=youts[s], algo=args.algo, check=False)
 
-        us, wall = timed(step, K, W, use_graph, reps=5)
-        total_wall += wall
+        us, walls = timed(step, K, W, use_graph, reps=5)
+        total_wall += walls[_median_index(us)]
         total_tok += sh.T * K
         rows.append({"r": sh.r, "T": sh.T, "us_per_call": _median(us), "tokens_per_s": sh.T / (_median(us) * 1e-6),
                      "algorithmic_bytes": sh.algorithmic_bytes()})
@@ -177,8 +192,8 @@ def bench_c5_model(args):
         for c in range(ncalls):
             call(c)
 
-    us, wall = timed(model_pass, K, W, use_graph, reps=1)
-    pass_us = us[0]
+    us, walls = timed(model_pass, K, W, use_graph, reps=3)
+    pass_us, wall = us[_median_index(us)], walls[_median_index(us)]
     alg_bytes = sum(sh.algorithmic_bytes() for *_, sh, _, _ in adapters)
     achieved = alg_bytes / (pass_us * 1e-6) / 1e9
     out = {"metric": "model-level adapter-branch tokens/s over the 280 adapter calls of LLaMA-2-13B at T=8192",
@@ -191,7 +206,8 @@ def bench_c5_model(args):
            "achieved_hbm_gbs": achieved, "hbm_peak_gbs": HBM_PEAK_GBS,
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel_us": pass_us / ncalls,
-                        "algorithmic_bytes": alg_bytes, "note": "all 280 launches of a pass taken together"}}
+                        "kernel_us_repetitions": [u / ncalls for u in us],
+                        "algorithmic_bytes": alg_bytes, "note": "all 280 launches of a pass taken together; median of 3 repetitions"}}
     if not args.no_cpu_baseline:
         # The oracle on every 64th token row of all 280 projections; the same rows are the parity check.
         import oracle
@@ -231,7 +247,7 @@ def bench_backward(args):
     smooth-sign factor) on HBM-resident inputs, cycling through enough buffer sets to defeat the Infinity Cache."""
     import numpy as np
     import torch
-    from paper_2605_24058_amd import binding, inputs
+    from paper_2605_24058_amd import binding, inputs, traffic_profile
     K, W = args.steps, args.warmup
     use_graph = not args.no_graph
     sh = _workloads()[args.workload]
@@ -290,13 +306,15 @@ def bench_backward(args):
                                            dev["s_out"], dev["latA"], dev["latB"], args.kappa, dx_base=dxbs[s_], dx=dxs[s_],
                                            workspace=ws, check=False, t_saved=kept[s_])
 
-    reps_us, wall_s = timed(step, K, max(W, sets), use_graph, reps=3)
-    call_us = reps_us[0]
+    reps_us, walls = timed(step, K, max(W, sets), use_graph, reps=5)
+    call_us, wall_s = reps_us[_median_index(reps_us)], walls[_median_index(reps_us)]   # the median repetition
     alg = backward_algorithmic_bytes(sh)
     alg += (ell - 1) * (2 + 4) * (sh.d_in + sh.r + sh.d_out)     # further envelopes: fp16 scales read, fp32 scale gradients written
     if args.train_step:   # + the forward call + reading the latents and writing the four packed carriers
         alg += sh.algorithmic_bytes() + 4 * sh.T * sh.r + 4 * sh.r * (sh.d_in + sh.d_out) + 4 * ((sh.r * (sh.d_in + sh.d_out) + 7) // 8)
     achieved = alg / (call_us * 1e-6) / 1e9
+    traffic, traffic_note = (None, "not measured for this mode") if (args.train_step or ell > 1) else \
+        traffic_profile.lookup("lordba_backward", sh.name, "t kept" if args.keep_t else "t recomputed")
     out = {"metric": ("adapter-branch training step (pack latents, forward, backward) tokens/s and achieved HBM GB/s" if args.train_step else
                       "adapter-branch backward (dx, scale and latent-carrier gradients) tokens/s and achieved HBM GB/s"),
            "value": sh.T * K / wall_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -305,7 +323,7 @@ def bench_backward(args):
            "config": {"workload": sh.name, "pass": "train_step" if args.train_step else "backward", "T": sh.T, "d_in": sh.d_in, "d_out": sh.d_out, "r": sh.r,
                       "ell": ell, "kappa": args.kappa, "t": "kept by the forward pass" if args.keep_t else "recomputed from x", "buffer_sets": sets, "launch": "hip_graph" if use_graph else "eager", "seed": args.seed},
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                        "traffic": None if (args.train_step or ell > 1) else (MEASURED_BACKWARD_TRAFFIC_BYTES.get(sh.name) or (None, None))[1 if args.keep_t else 0],
+                        "traffic": traffic, "traffic_source": traffic_note,
                         "kernel_us": call_us, "kernel_us_repetitions": reps_us, "algorithmic_bytes": alg,
                         "note": "all kernels of one call taken together (dx + du, t unless kept, wgrad, finish)"}}
     if not args.no_cpu_baseline:
@@ -404,8 +422,7 @@ def bench_ptq(args):
                     with torch.cuda.stream(streams[j]):
                         rest[j].replay()
 
-        reps_us = []
-        wall_s = None
+        reps_us, walls = [], []
         for _ in range(3):
             a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
@@ -427,11 +444,11 @@ def bench_ptq(args):
             torch.cuda.synchronize()
             t1 = time.perf_counter()
             reps_us.append(a0.elapsed_time(a1) * 1e3 / K)
-            wall_s = wall_s if wall_s is not None else t1 - t0
+            walls.append(t1 - t0)
     else:
-        reps_us, wall_s = timed(step, K, W, use_graph, reps=3)
+        reps_us, walls = timed(step, K, W, use_graph, reps=3)
     torch.cuda.synchronize()
-    call_us = reps_us[0]
+    call_us, wall_s = reps_us[_median_index(reps_us)], walls[_median_index(reps_us)]
     sweeps = [int(outs[s_]["info"][0].item()) for s_ in outs if not isinstance(s_, tuple)]
     mean_sweeps = sum(sweeps) / len(sweeps)
     flops = ptq_algorithmic_flops(N, M, R, r0, mean_sweeps)
@@ -606,15 +623,21 @@ def main():
     K, W = args.steps, args.warmup
     use_graph = not args.no_graph
     full = args.mode == "forward" and not args.no_ceiling
-    # The first repetition is the timed region (value, ms_per_step, roofline); the others only show the spread.
-    reps_us, wall_s = timed(step, K, max(W, sets), use_graph, reps=5 if full else 1)
-    kern_us = reps_us[0]     # average launch-to-launch duration on the stream over the timed region
+    # The timed region of K steps is run REPS times after a warm-up of at least max(W, sets) steps and WARM_SECONDS of
+    # untimed replays; the headline (value, ms_per_step, roofline) is the median repetition, all of them are listed.
+    reps_us, walls = timed(step, K, max(W, sets), use_graph, reps=REPS)
+    mid = _median_index(reps_us)
+    kern_us = reps_us[mid]   # average launch-to-launch duration on the stream over that repetition's K steps
+    wall_s = walls[mid]
     ms_per_step = wall_s * 1e3 / K
     alg_bytes = sh.algorithmic_bytes_multi(ell)
     if nad:                  # every adapter that some row uses is read once, plus the index array
         used = len(set(int(a) for a in host0["ids"] if 0 <= a < nad))
         alg_bytes = sh.activation_bytes() + used * sh.adapter_bytes() + 4 * sh.T
     achieved = alg_bytes / (kern_us * 1e-6) / 1e9
+    from paper_2605_24058_amd import traffic_profile
+    traffic, traffic_note = traffic_profile.lookup("lordba_forward", sh.name) \
+        if args.mode == "forward" and args.algo == 0 and ell == 1 and not nad else (None, "not measured for this mode")
 
     out = {
         "metric": "multi-adapter batch: adapter-branch tokens/s and achieved HBM GB/s" if nad else
@@ -629,13 +652,12 @@ def main():
         "achieved_hbm_gbs": achieved, "hbm_peak_gbs": HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(sh.name) if args.mode == "forward" and args.algo == 0 and ell == 1 and not nad else None,
-                     "kernel_us": kern_us, "algorithmic_bytes": alg_bytes},
+                     "traffic": traffic, "traffic_source": traffic_note,
+                     "kernel_us": kern_us, "algorithmic_bytes": alg_bytes,
+                     "kernel_us_repetitions": reps_us, "statistic": "median of %d repetitions of the %d-step region" % (REPS, K)},
     }
 
     if full:
-        out["roofline"]["kernel_us_repetitions"] = reps_us
-        out["roofline"]["kernel_us_median"] = _median(reps_us)
         c_us, _ = timed(stream_step, max(200, K // 4), 20, use_graph, reps=3)
         c_us = _median(c_us)
         h_us, _ = timed(hot_step, max(200, K // 4), 20, use_graph, reps=3)

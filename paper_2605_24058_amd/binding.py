@@ -245,7 +245,8 @@ def lordba_forward(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out=None,
         stream = stream.cuda_stream
     args = (x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(),
             y_base.data_ptr(), y_out.data_ptr(), T, d_in, d_out, r, ctypes.c_void_p(stream))
-    st = lib.lordba_forward_algo(*args, int(algo))
+    # the library's own choice of kernel goes through the entry point of that name; a selector through its _algo twin
+    st = lib.lordba_forward(*args) if int(algo) == ALGO_AUTO else lib.lordba_forward_algo(*args, int(algo))
     if st != 0:
         raise LordbaError(st, "lordba_forward")
     return y_out
@@ -288,7 +289,7 @@ def lordba_forward_multi(x, packedA, packedB, s_in, s_rank, s_out, y_base, y_out
         stream = stream.cuda_stream
     args = (x.data_ptr(), packedA.data_ptr(), packedB.data_ptr(), s_in.data_ptr(), s_rank.data_ptr(), s_out.data_ptr(),
             y_base.data_ptr(), y_out.data_ptr(), T, d_in, d_out, r, ell, ctypes.c_void_p(stream))
-    st = lib.lordba_forward_multi_algo(*args, int(algo))
+    st = lib.lordba_forward_multi(*args) if int(algo) == ALGO_AUTO else lib.lordba_forward_multi_algo(*args, int(algo))
     if st != 0:
         raise LordbaError(st, "lordba_forward_multi")
     return y_out
@@ -341,7 +342,7 @@ def lordba_forward_batched(x, packedA_pool, packedB_pool, s_in_pool, s_rank_pool
     args = (x.data_ptr(), packedA_pool.data_ptr(), packedB_pool.data_ptr(), s_in_pool.data_ptr(), s_rank_pool.data_ptr(),
             s_out_pool.data_ptr(), adapter_of_row.data_ptr(), y_base.data_ptr(), y_out.data_ptr(), T, d_in, d_out, r, n,
             ctypes.c_void_p(stream))
-    st = lib.lordba_forward_batched_algo(*args, int(algo))
+    st = lib.lordba_forward_batched(*args) if int(algo) == ALGO_AUTO else lib.lordba_forward_batched_algo(*args, int(algo))
     if st != 0:
         raise LordbaError(st, "lordba_forward_batched")
     return y_out
