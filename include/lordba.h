@@ -319,10 +319,10 @@ lordba_status lordba_backward_noalloc(const void* x, const void* g,
  * Limits: 1 <= R <= LORDBA_PTQ_MAX_RANK, R <= r0 <= LORDBA_PTQ_MAX_FACTOR_RANK (beyond r0 the warm start has no singular
  * vectors), 1 <= N, M <= 2^22, 1 <= K <= LORDBA_PTQ_MAX_SWEEPS; else LORDBA_ERR_DIM.  No output, nor the workspace,
  * may overlap an input or another output: LORDBA_ERR_ALIAS.  Arithmetic: fp64 throughout, fixed summation order
- * (calls are reproducible bit for bit).  The warm start works from the r0 x r0 Gram matrices of the factors, which
- * resolves singular triplet k of the update to a relative error of about eps (sigma_1 / sigma_k)^2: with sigma_R / sigma_1
- * below about 1e-5 a few near-zero entries of the trailing carriers may start from the other sign than a dense singular
- * value decomposition would give them. */
+ * (calls are reproducible bit for bit).  The warm start (Eq. (svd-init)) takes the singular triplets of the update from
+ * the triangular factors of Householder QR factorisations of A_star and B_star: triplet k carries a relative error of
+ * about eps sigma_1 / sigma_k, as a dense singular value decomposition's would; an update whose R-th singular value is
+ * below 1e-12 of its largest counts as rank deficient (info[4]). */
 lordba_status lordba_ptq(const void* A_star, const void* B_star, uint32_t* packedA, uint32_t* packedB,
                          double* alpha, double* beta, double* gamma, void* s_in, void* s_rank, void* s_out,
                          double* info, void* workspace, size_t workspace_bytes,
@@ -345,6 +345,17 @@ lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_star, uint32_t
 
 /* Bytes of workspace lordba_ptq needs for a shape (0 for a shape it does not support). */
 size_t lordba_ptq_workspace_bytes(int64_t N, int64_t M, int64_t R, int64_t r0);
+
+/* DEVICE function: the closed-form update of the rank scales on its own (Eq. (beta-gram), Eq. (beta-pinv)): beta = pinv(G) h
+ * for a symmetric positive semidefinite G, the minimum-norm least-squares solution when G is singular (two carrier
+ * columns that coincide, a zero scale vector).  It is the routine a sweep of lordba_ptq runs after it has formed
+ * G = (P^T P) o (Q Q^T) and h; exported so that it can be used, and checked, by itself.
+ *   G : fp64 [R, R] row-major, in (only its symmetric content matters: both triangles are read);  h : fp64 [R], in;
+ *   beta : fp64 [R], out.  Device pointers, 8-byte aligned; beta may not overlap G or h (LORDBA_ERR_ALIAS).
+ * 1 <= R <= LORDBA_PTQ_MAX_RANK, else LORDBA_ERR_DIM.  One small kernel on `stream`; never waits, allocates or frees.
+ * Rank decision: a pivot of the diagonally pivoted Cholesky factorisation that does not exceed 64 eps max_k G_kk ends
+ * the factorisation; G = 0 gives beta = 0. */
+lordba_status lordba_ptq_beta_solve(const double* G, const double* h, double* beta, int64_t R, void* stream);
 
 /* Static, never-NULL description of a status code. */
 const char* lordba_status_string(lordba_status status);

@@ -155,6 +155,8 @@ def load_library():
     lib.lordba_ptq.argtypes = [vp] * 12 + [ctypes.c_size_t] + [i64] * 5 + [ctypes.c_double, ctypes.c_double, vp]
     lib.lordba_ptq_sweeps.restype = ci
     lib.lordba_ptq_sweeps.argtypes = [vp] * 12 + [ctypes.c_size_t] + [i64] * 7 + [ctypes.c_double, ctypes.c_double, vp]
+    lib.lordba_ptq_beta_solve.restype = ci
+    lib.lordba_ptq_beta_solve.argtypes = [vp, vp, vp, i64, vp]
     lib.lordba_status_string.restype = ctypes.c_char_p
     lib.lordba_status_string.argtypes = [ci]
     _lib = lib
@@ -621,6 +623,25 @@ def lordba_ptq(A_star, B_star, R: int, K: int = 100, tau: float = 2.0, mu: float
     out["U2t"] = ws[off2:off2 + M * R].view(M, R)
     out["workspace"] = workspace
     return out
+
+
+def lordba_ptq_beta_solve(G, h, stream=None):
+    """beta = pinv(G) h on the GPU (lordba_ptq_beta_solve of the C interface): G [R, R], h [R] float64 CUDA tensors."""
+    import torch
+
+    lib = load_library()
+    R = h.numel()
+    if tuple(G.shape) != (R, R) or G.dtype != torch.float64 or h.dtype != torch.float64 or not G.is_contiguous() or not h.is_contiguous():
+        raise ValueError("need contiguous float64 G [R, R] and h [R]")
+    beta = torch.empty(R, dtype=torch.float64, device=G.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(G.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    st = lib.lordba_ptq_beta_solve(G.data_ptr(), h.data_ptr(), beta.data_ptr(), R, ctypes.c_void_p(stream))
+    if st != 0:
+        raise LordbaError(st, "lordba_ptq_beta_solve")
+    return beta
 
 
 def to_device(inputs: dict, device="cuda:0") -> dict:

@@ -24,7 +24,10 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "lordba.h"
+#include "lordba_host_util.h"
 
 namespace {
 
@@ -32,6 +35,7 @@ constexpr int kRows = 32;      // rows of one side per workgroup
 constexpr int kThreads = 256;  // four waves: the warm-start and export kernels
 constexpr int kRowThreads = 512;  // eight waves: the kernels of a sweep
 static_assert(LORDBA_PTQ_MAX_RANK == 32, "the Tikhonov kernel is instantiated for ranks up to 16 and up to 32");
+constexpr double kRankFloor = 1e-12;  // a singular value of the update below this fraction of the largest counts as zero
 constexpr int kInfoHead = 8;   // info[0..7]: sweeps, frozen, rho, ||T||_F^2, degenerate, reserved; then one objective per sweep
 
 enum Ctrl { kRho = 0, kYfac = 1, kDone = 2, kSweeps = 3, kNormT2 = 4, kFrozen = 5, kDegenerate = 6, kCtrlCount = 8 };
@@ -196,20 +200,90 @@ __device__ inline void load_totals(const double* tot, int count, double* dst) {
 
 // ---- warm start (Eq. (svd-init)) ----------------------------------------------------------------------------------
 
-// Shares of A*^T A* and B*^T B* (the K part of the share is unused here).
-__global__ __launch_bounds__(kThreads) void lordba_ptq_factor_gram_kernel(PtqArgs a) {
-    const int side = static_cast<int>(blockIdx.x) < a.nb[0] ? 0 : 1;
-    const int blk = side == 0 ? blockIdx.x : blockIdx.x - a.nb[0];
-    const int r0 = a.r0;
-    double* fs = lds;
-    load_factor_rows(a.F[side], a.n[side], r0, static_cast<int64_t>(blk) * kRows, fs, r0);
+// Tall-skinny QR of the two factors: only the triangular factors are wanted (A* = Qa Ra, B* = Qb Rb with orthonormal Qa, Qb
+// that are never formed).  One workgroup factors a panel of up to kQrRows rows by Householder reflections and writes the
+// panel's r0 x r0 upper-triangular factor; the panels of level 0 are rows of the fp16 factor (taken at their exact
+// values), those of a higher level the stacked factors of `group` panels of the level below, until one is left.  The
+// triangular factor of a Householder QR is backward stable column by column, so the singular triplets of the update
+// that the warm start takes from Ra Rb^T carry an error of eps sigma_1 / sigma_k, as a dense decomposition's would
+// (through the Gram matrices A*^T A*, B*^T B* it would be the square of that ratio).
+constexpr int kQrRows = 256;
+
+struct QrLevel {
+    const double* src[2];   // level >= 1: the factors of the level below, [count_in, r0, r0]
+    double* dst[2];         // [count_out, r0, r0]
+    int count_in[2];        // level 0: unused
+    int count_out[2];       // 0: this side is finished (or has nothing at this level)
+    int level, group;
+};
+
+
+__global__ __launch_bounds__(256) void lordba_ptq_qr_kernel(PtqArgs a, QrLevel lv) {
+    const int side = static_cast<int>(blockIdx.x) < lv.count_out[0] ? 0 : 1;
+    const int blk = side == 0 ? blockIdx.x : blockIdx.x - lv.count_out[0];
+    const int n = a.r0, tid = threadIdx.x;
+    const int m = lv.level == 0 ? kQrRows : lv.group * n;   // rows of the panel (zero rows where the input ends)
+    double* P = lds;                    // [m, n] row-major
+    double* partial = P + kQrRows * n;  // [slices, n]
+    double* diag = partial + 256;       // [n]
+    if (lv.level == 0) {
+        const int64_t row0 = static_cast<int64_t>(blk) * kQrRows, rows = a.n[side];
+        const __half* F = a.F[side];
+        for (int o = tid; o < kQrRows * n; o += 256) {
+            const int64_t row = row0 + o / n;
+            P[o] = row < rows ? static_cast<double>(__half2float(F[row0 * n + o])) : 0.0;
+        }
+    } else {
+        const int64_t first = static_cast<int64_t>(blk) * lv.group;
+        const double* src = lv.src[side] + first * n * n;
+        const int64_t have = (lv.count_in[side] - first < lv.group ? lv.count_in[side] - first : lv.group) * n;  // rows that exist
+        for (int o = tid; o < m * n; o += 256) P[o] = o / n < have ? src[o] : 0.0;
+    }
+    // thread (j, s): column j, row slice s
+    const int slices = 256 / n, rps = (m + slices - 1) / slices;
+    const int j = tid % n, sl = tid / n;
+    const bool active = sl < slices;
+    const int i_lo = sl * rps, i_hi = (sl + 1) * rps < m ? (sl + 1) * rps : m;
     __syncthreads();
-    double* out = a.part[side] + static_cast<int64_t>(blk) * a.pstride;
-    for (int o = threadIdx.x; o < r0 * r0; o += kThreads) {
-        const int k = o / r0, l = o - k * r0;
-        double acc = 0.0;
-        for (int row = 0; row < kRows; ++row) acc += fs[row * r0 + k] * fs[row * r0 + l];
-        out[o] = acc;
+    for (int k = 0; k < n; ++k) {
+        // the sums over the rows below the diagonal of (column k) x (column j), j >= k, slice by slice; row k's entries are
+        // read here, before the barrier, because the update below rewrites them
+        double alpha = 0.0, pkj = 0.0;
+        if (active && j >= k) {
+            alpha = P[k * n + k];
+            pkj = P[k * n + j];
+            double acc = 0.0;
+            for (int i = (i_lo > k + 1 ? i_lo : k + 1); i < i_hi; ++i) acc = fma(P[i * n + k], P[i * n + j], acc);
+            partial[sl * n + j] = acc;
+        }
+        __syncthreads();
+        // Every thread forms the reflector's scalars itself (same values everywhere): x = column k from the diagonal down,
+        // alpha its first entry; H = I - tau v v^T with v = (1, x_below / (alpha - beta)), beta = -sign(alpha) ||x||,
+        // tau = (beta - alpha) / beta; H x = beta e_1.  A column that is zero below the diagonal is left as it is.
+        if (active && j >= k) {
+            double below2 = 0.0, dot = 0.0;
+            for (int q = 0; q < slices; ++q) { below2 += partial[q * n + k]; dot += partial[q * n + j]; }
+            if (below2 > 0.0) {
+                const double beta = alpha < 0.0 ? sqrt(fma(alpha, alpha, below2)) : -sqrt(fma(alpha, alpha, below2));
+                const double inv = 1.0 / (alpha - beta), tau = (beta - alpha) / beta;
+                if (j == k) {
+                    if (sl == 0) diag[k] = beta;
+                } else {
+                    const double w = fma(dot, inv, pkj);        // v^T (column j)
+                    const double tw = tau * w, c = tw * inv;
+                    for (int i = (i_lo > k + 1 ? i_lo : k + 1); i < i_hi; ++i) P[i * n + j] = fma(-c, P[i * n + k], P[i * n + j]);
+                    if (sl == 0) P[k * n + j] = pkj - tw;
+                }
+            } else if (j == k && sl == 0) {
+                diag[k] = alpha;
+            }
+        }
+        __syncthreads();
+    }
+    double* dst = lv.dst[side] + static_cast<int64_t>(blk) * n * n;
+    for (int o = tid; o < n * n; o += 256) {
+        const int row = o / n, col = o - row * n;
+        dst[o] = col > row ? P[o] : (col == row ? diag[row] : 0.0);
     }
 }
 
@@ -269,76 +343,38 @@ __device__ inline void column_norms(const double* W, int n, int ld, int l, doubl
     wave_sync();
 }
 
-// One wave: the thin singular value decomposition of the target from the two r0 x r0 Gram matrices of its factors.
-// With A* = Qa Ra and B* = Qb Rb (Qa, Qb with orthonormal columns) the target is Qa (Ra Rb^T) Qb^T, and a one-sided
-// Jacobi iteration on the r0 x r0 core Ra Rb^T gives its singular values and vectors, hence the singular values of the
-// target and maps Z1, Z2 with (leading left singular vectors) ~ A* Z1, (right) ~ B* Z2 up to positive column factors,
-// which the signs do not see.  Ra, Rb are the transposed Cholesky factors of the Gram matrices when both factor
-// matrices have full column rank (every pivot above 1e-10 of the largest diagonal entry); otherwise (a dead or
-// dependent column, fewer rows than columns) they come from the eigen-decompositions G = E diag(lambda) E^T, taken with
-// the same Jacobi iteration: R = diag(sqrt(lambda)) E^T, inverted on the range of G only.
-__global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
+// One wave: the thin singular value decomposition of the target from the triangular factors of its two factors.
+// With A* = Qa Ra and B* = Qb Rb (Qa, Qb with orthonormal columns, never formed) the target is Qa (Ra Rb^T) Qb^T, and a
+// one-sided Jacobi iteration on the r0 x r0 core W = Ra Rb^T, W V = (orthogonal columns sigma_c u_c), gives the singular
+// values of the target and its singular vectors Qb v_c, Qa u_c.  The warm start wants only their signs, and
+//     (target) (Qb v_c) = A* (Rb^T v_c) = sigma_c (left vector c),     (target)^T (Qa u_c) = B* (Ra^T u_c) = sigma_c (right vector c),
+// so the maps from factor rows to singular-vector entries are Z1 = Rb^T V and Z2 = Ra^T (rotated core), up to positive
+// column factors that the signs do not see: no triangular system is solved, and factors without full column rank (a dead
+// or repeated column, fewer rows than columns) need no other route.
+__global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a, const double* RaG, const double* RbG) {
     const int r0 = a.r0, R = a.R, ld = r0 + 1, l = threadIdx.x;
-    double* Ga = lds;
-    double* Gb = Ga + r0 * ld;
-    double* W = Gb + r0 * ld;
+    double* Ra = lds;
+    double* Rb = Ra + r0 * ld;
+    double* W = Rb + r0 * ld;
     double* V = W + r0 * ld;
     double* sig = V + r0 * ld;
-    double* lam = sig + r0;   // [2, r0] eigenvalues of the two Gram matrices (second route only)
-    double* zs = lam + 2 * r0;   // [r0, R] one side's map before it goes to memory
+    double* zs = sig + r0;   // [r0, R] one side's map before it goes to memory
     int* idx = reinterpret_cast<int*>(zs + r0 * R);
-    auto load_gram = [&]() {
-        for (int o = l; o < r0 * r0; o += 64) {
-            Ga[(o / r0) * ld + o % r0] = a.tot[0][o];
-            Gb[(o / r0) * ld + o % r0] = a.tot[1][o];
-        }
-        wave_sync();
-    };
-    auto identity = [&](double* X) {
-        if (l < r0)
-            for (int j = 0; j < r0; ++j) X[l * ld + j] = (l == j) ? 1.0 : 0.0;
-    };
-    load_gram();
-    double da = l < r0 ? Ga[l * ld + l] : 0.0, db = l < r0 ? Gb[l * ld + l] : 0.0;
-    for (int m = 32; m >= 1; m >>= 1) { da = fmax(da, __shfl_xor(da, m, 64)); db = fmax(db, __shfl_xor(db, m, 64)); }
-    const bool ok_a = group_cholesky(Ga, ld, r0, l, 1e-10 * da);
-    const bool ok_b = group_cholesky(Gb, ld, r0, l, 1e-10 * db);
-    const bool full_rank = ok_a && ok_b;
-    if (full_rank) {
-        // core W = La^T Lb, V = I; lane i owns row i of both from here on
-        if (l < r0) {
-            for (int j = 0; j < r0; ++j) {
-                double acc = 0.0;
-                for (int k = (l > j ? l : j); k < r0; ++k) acc += Ga[k * ld + l] * Gb[k * ld + j];
-                W[l * ld + j] = acc;
-            }
-        }
-        identity(V);
-        wave_sync();
-    } else {
-        load_gram();   // (the factorisation overwrote them)
-        for (int side = 0; side < 2; ++side) {
-            double* G = side == 0 ? Ga : Gb;
-            // eigen-decomposition of the positive semidefinite G: rotate its columns orthogonal; G V = V diag(lambda)
-            identity(V);
-            wave_sync();
-            jacobi_onesided(G, V, r0, ld, l);
-            column_norms(G, r0, ld, l, lam + side * r0);
-            if (l < r0)
-                for (int j = 0; j < r0; ++j) G[l * ld + j] = V[l * ld + j];   // keep the eigenvectors in G's place
-            wave_sync();
-        }
-        // core W[i][j] = sqrt(lambda_a,i lambda_b,j) (Ea^T Eb)[i][j]
-        if (l < r0) {
-            for (int j = 0; j < r0; ++j) {
-                double acc = 0.0;
-                for (int k = 0; k < r0; ++k) acc += Ga[k * ld + l] * Gb[k * ld + j];
-                W[l * ld + j] = sqrt(lam[l] * lam[r0 + j]) * acc;
-            }
-        }
-        identity(V);
-        wave_sync();
+    for (int o = l; o < r0 * r0; o += 64) {
+        Ra[(o / r0) * ld + o % r0] = RaG[o];
+        Rb[(o / r0) * ld + o % r0] = RbG[o];
     }
+    wave_sync();
+    // core W = Ra Rb^T (both upper triangular), V = I; lane i owns row i of both from here on
+    if (l < r0) {
+        for (int j = 0; j < r0; ++j) {
+            double acc = 0.0;
+            for (int k = (l > j ? l : j); k < r0; ++k) acc = fma(Ra[l * ld + k], Rb[j * ld + k], acc);
+            W[l * ld + j] = acc;
+            V[l * ld + j] = (l == j) ? 1.0 : 0.0;
+        }
+    }
+    wave_sync();
     jacobi_onesided(W, V, r0, ld, l);
     // singular values = column norms of the rotated core; order them (descending, ties by index)
     column_norms(W, r0, ld, l, sig);
@@ -357,9 +393,9 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
     if (l == 0) {
         double norm2 = 0.0;
         for (int p = 0; p < r0; ++p) norm2 += sig[idx[p]] * sig[idx[p]];
-        // beyond the rank of the target the singular vectors are not defined (the second route can meet such a target;
-        // through squared quantities a singular value below 1e-7 of the largest is noise)
-        const bool good = norm2 > 0.0 && norm2 < INFINITY && (full_rank || sig[idx[R - 1]] > 1e-7 * sig[idx[0]]);
+        // beyond the rank of the target the singular vectors are not defined: a singular value at the rounding level of the
+        // largest one (a few eps sigma_1) is noise
+        const bool good = norm2 > 0.0 && norm2 < INFINITY && sig[idx[R - 1]] > kRankFloor * sig[idx[0]];
         a.ctrl[kRho] = norm2 / (static_cast<double>(a.n[0]) * R + static_cast<double>(a.n[1]) * R);
         a.ctrl[kYfac] = 1.0;
         a.ctrl[kDone] = good ? 0.0 : 1.0;
@@ -372,28 +408,14 @@ __global__ __launch_bounds__(64) void lordba_ptq_svd_kernel(PtqArgs a) {
     wave_sync();
     if (l < R) a.beta[l] = sig[idx[l]];
     for (int side = 0; side < 2; ++side) {
-        const double* Lf = side == 0 ? Ga : Gb;
-        const double* src = side == 0 ? W : V;
+        const double* Rt = side == 0 ? Rb : Ra;   // the OTHER factor's triangle, transposed: Z[i, l] = sum_{j <= i} Rt[j, i] src[j, c]
+        const double* src = side == 0 ? V : W;
         if (l < R) {   // lane l: column l of the side's map, built in LDS (zs, [r0, R])
             const int c = idx[l];
-            if (full_rank) {
-                // Z1[:, l] = La^{-T} (rotated core)[:, c], Z2[:, l] = Lb^{-T} V[:, c]: back substitution with the upper factors
-                for (int i = r0 - 1; i >= 0; --i) {
-                    double acc = src[i * ld + c];
-                    for (int j = i + 1; j < r0; ++j) acc -= Lf[j * ld + i] * zs[j * R + l];
-                    zs[i * R + l] = acc / Lf[i * ld + i];
-                }
-            } else {
-                // Z[:, l] = E diag(lambda^{-1/2} on the range, 0 off it) src[:, c]
-                const double* lm = lam + side * r0;
-                double top = 0.0;
-                for (int p = 0; p < r0; ++p) top = fmax(top, lm[p]);
-                for (int i = 0; i < r0; ++i) {
-                    double acc = 0.0;
-                    for (int p = 0; p < r0; ++p)
-                        if (lm[p] > 1e-13 * top) acc += Lf[i * ld + p] * (src[p * ld + c] / sqrt(lm[p]));
-                    zs[i * R + l] = acc;
-                }
+            for (int i = 0; i < r0; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j <= i; ++j) acc = fma(Rt[j * ld + i], src[j * ld + c], acc);
+                zs[i * R + l] = acc;
             }
         }
         wave_sync();
@@ -657,39 +679,13 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_scale_kernel(PtqArgs a
     gram_share(s.xs, s.cs, s.fs, s.fstride, R, r0, a.part[side] + static_cast<int64_t>(blk) * a.pstride);
 }
 
-// Eq. (beta-gram), Eq. (beta-Schur), Eq. (beta-pinv): G = S1 o S2, h_k = K1[k, :] . K2[k, :], beta = pinv(G) h by a
-// Cholesky factorisation with diagonal pivoting that stops at the numerical rank (for a positive semidefinite G = L L^T
-// with L of full column rank, pinv(G) = L (L^T L)^{-2} L^T; at full rank this is the ordinary solve, which is what runs
-// then).  Also the objective of Eq. (admm-problem) at the continuous iterates, from the same Gram pairs:
-// f = (||T||_F^2 - 2 beta.h + beta^T G beta) / 2.  Then the end of the sweep: residual balancing of the penalty (first
-// half of the run) from the consensus gaps and sign changes the Tikhonov kernels left in their shares, and the end of
-// the loop when no sign changed.
-__global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a, int t) {
-    if (a.ctrl[kDone] != 0.0) return;
-    const int R = a.R, r0 = a.r0, ld = R + 1, count = R * R + R * r0;
-    double* P1 = lds;              // S1, K1, gap, sign changes of side 0
-    double* P2 = P1 + count + 2;   // the same of side 1
-    double* G = P2 + count + 2;    // [R, ld]
-    double* N2 = G + R * ld;       // [R, ld]; the unpivoted attempt uses it as its 16 x 17 area plus the 16-entry extra row
-    const int n2 = R * ld > 16 * 17 + 16 ? R * ld : 16 * 17 + 16;
-    double* hv = N2 + n2;          // [R] permuted right-hand side
-    double* h0 = hv + R;           // [R]
-    double* bt = h0 + R;           // [R] result
-    int* perm = reinterpret_cast<int*>(bt + R);
-    load_totals(a.tot[0], count + 2, P1);
-    load_totals(a.tot[1], count + 2, P2);
-    __syncthreads();
-    for (int o = threadIdx.x; o < R * R; o += blockDim.x) G[(o / R) * ld + o % R] = P1[o] * P2[o];
-    for (int k = threadIdx.x; k < R; k += blockDim.x) {
-        double acc = 0.0;
-        for (int q = 0; q < r0; ++q) acc += P1[R * R + k * r0 + q] * P2[R * R + k * r0 + q];
-        hv[k] = acc;
-        h0[k] = acc;
-        perm[k] = k;
-    }
-    __syncthreads();
-    if (threadIdx.x >= 64) return;
-    const int l = threadIdx.x;
+// beta = pinv(G) h for a symmetric positive semidefinite R x R matrix G, by one wave (Eq. (beta-pinv)).  G [R, ld] and hv [R]
+// are in LDS and are overwritten; N2 is an LDS area of max(R ld, 16 * 17 + 16) doubles; perm [R] must hold the identity.
+// The result goes to bt [R].  A factorisation without pivoting is tried first (ranks up to 16: its columns stay in
+// registers) and kept if every pivot clears the rank tolerance 64 eps max_k G_kk; otherwise a Cholesky factorisation with
+// diagonal pivoting stops at the numerical rank: with G = L L^T, L of full column rank, pinv(G) = L (L^T L)^{-2} L^T (at
+// full rank the ordinary solve).
+__device__ inline void beta_pinv_solve(double* G, int ld, double* hv, double* N2, int* perm, double* bt, int R, int l) {
     double dmax = (l < R) ? G[l * ld + l] : 0.0;
     for (int m = 32; m >= 1; m >>= 1) dmax = fmax(dmax, __shfl_xor(dmax, m, 64));
     const double tol = 64.0 * 2.220446049250313e-16 * dmax;
@@ -771,6 +767,42 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a,
     }
     if (l < R) bt[perm[l]] = x;
     wave_sync();
+}
+
+// Eq. (beta-gram), Eq. (beta-Schur), Eq. (beta-pinv): G = S1 o S2, h_k = K1[k, :] . K2[k, :], beta = pinv(G) h by a
+// Cholesky factorisation with diagonal pivoting that stops at the numerical rank (for a positive semidefinite G = L L^T
+// with L of full column rank, pinv(G) = L (L^T L)^{-2} L^T; at full rank this is the ordinary solve, which is what runs
+// then).  Also the objective of Eq. (admm-problem) at the continuous iterates, from the same Gram pairs:
+// f = (||T||_F^2 - 2 beta.h + beta^T G beta) / 2.  Then the end of the sweep: residual balancing of the penalty (first
+// half of the run) from the consensus gaps and sign changes the Tikhonov kernels left in their shares, and the end of
+// the loop when no sign changed.
+__global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a, int t) {
+    if (a.ctrl[kDone] != 0.0) return;
+    const int R = a.R, r0 = a.r0, ld = R + 1, count = R * R + R * r0;
+    double* P1 = lds;              // S1, K1, gap, sign changes of side 0
+    double* P2 = P1 + count + 2;   // the same of side 1
+    double* G = P2 + count + 2;    // [R, ld]
+    double* N2 = G + R * ld;       // [R, ld]; the unpivoted attempt uses it as its 16 x 17 area plus the 16-entry extra row
+    const int n2 = R * ld > 16 * 17 + 16 ? R * ld : 16 * 17 + 16;
+    double* hv = N2 + n2;          // [R] permuted right-hand side
+    double* h0 = hv + R;           // [R]
+    double* bt = h0 + R;           // [R] result
+    int* perm = reinterpret_cast<int*>(bt + R);
+    load_totals(a.tot[0], count + 2, P1);
+    load_totals(a.tot[1], count + 2, P2);
+    __syncthreads();
+    for (int o = threadIdx.x; o < R * R; o += blockDim.x) G[(o / R) * ld + o % R] = P1[o] * P2[o];
+    for (int k = threadIdx.x; k < R; k += blockDim.x) {
+        double acc = 0.0;
+        for (int q = 0; q < r0; ++q) acc += P1[R * R + k * r0 + q] * P2[R * R + k * r0 + q];
+        hv[k] = acc;
+        h0[k] = acc;
+        perm[k] = k;
+    }
+    __syncthreads();
+    if (threadIdx.x >= 64) return;
+    const int l = threadIdx.x;
+    beta_pinv_solve(G, ld, hv, N2, perm, bt, R, l);
     double lin = 0.0, quad = 0.0;
     if (l < R) {
         const double bl = bt[l];
@@ -794,6 +826,22 @@ __global__ __launch_bounds__(kRowThreads) void lordba_ptq_beta_kernel(PtqArgs a,
     a.ctrl[kYfac] = yfac;
     a.ctrl[kSweeps] = t + 1;
     if (f0 + f1 == 0.0) { a.ctrl[kFrozen] = 1.0; a.ctrl[kDone] = 1.0; }
+}
+
+// The beta update on its own (lordba_ptq_beta_solve): G [R, R] row-major and h [R] from memory, beta [R] to memory.
+__global__ __launch_bounds__(64) void lordba_ptq_beta_solve_kernel(const double* Gin, const double* hin, double* out, int R) {
+    const int ld = R + 1, l = threadIdx.x;
+    double* G = lds;
+    const int n2 = R * ld > 16 * 17 + 16 ? R * ld : 16 * 17 + 16;
+    double* N2 = G + R * ld;
+    double* hv = N2 + n2;
+    double* bt = hv + R;
+    int* perm = reinterpret_cast<int*>(bt + R);
+    for (int o = l; o < R * R; o += 64) G[(o / R) * ld + o % R] = Gin[o];
+    if (l < R) { hv[l] = hin[l]; perm[l] = l; }
+    wave_sync();
+    beta_pinv_solve(G, ld, hv, N2, perm, bt, R, l);
+    if (l < R) out[l] = bt[l];
 }
 
 // ---- export -------------------------------------------------------------------------------------------------------
@@ -928,8 +976,12 @@ extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_sta
                 if (spans[i].p && spans[j].p && spans[i].p < spans[j].p + spans[j].n && spans[j].p < spans[i].p + spans[i].n)
                     return LORDBA_ERR_ALIAS;
     }
+    {
+        const lordba_status ds = check_device();   // the kernels are built for gfx950 only
+        if (ds != LORDBA_OK) return ds;
+    }
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return LORDBA_ERR_NO_DEVICE;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LORDBA_ERR_NO_DEVICE; }
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     double* ws = static_cast<double*>(workspace);
     PtqArgs a;
@@ -959,8 +1011,8 @@ extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_sta
     a.mu = mu;
 
     const int iR = a.R, ir0 = a.r0, ld0 = ir0 + 1, ldR = iR + 1;
-    const size_t lds_gram = sizeof(double) * kRows * ir0;
-    const size_t lds_svd = sizeof(double) * (4 * ir0 * ld0 + 3 * ir0 + ir0 * iR) + sizeof(int) * ir0;
+    const size_t lds_qr = sizeof(double) * (kQrRows * ir0 + 256 + ir0);
+    const size_t lds_svd = sizeof(double) * (4 * ir0 * ld0 + ir0 + ir0 * iR) + sizeof(int) * ir0;
     const size_t lds_init = sizeof(double) * (kRows * ir0 + kRows * iR + kRows + ir0 * iR);
     const int gs = iR <= 16 ? 16 : 32;
     // the Tikhonov kernel: as many waves solve rows at once as the LDS has room for their matrices (8, 4, 2 or 1); the scale
@@ -977,22 +1029,29 @@ extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_sta
     {   // More than 64 KiB of LDS per workgroup has to be asked for; the largest request so far is remembered per device and
         // kernel, so that a call whose shapes the process has already seen makes no runtime call besides its launches
         // (it can then be captured into a HIP graph).
+        static std::mutex mu;
         static size_t granted[64][7];
         const struct { const void* fn; size_t bytes; int slot; } big[] = {
-            {reinterpret_cast<const void*>(lordba_ptq_factor_gram_kernel), lds_gram, 0}, {reinterpret_cast<const void*>(lordba_ptq_svd_kernel), lds_svd, 1},
+            {reinterpret_cast<const void*>(lordba_ptq_qr_kernel), lds_qr, 0}, {reinterpret_cast<const void*>(lordba_ptq_svd_kernel), lds_svd, 1},
             {reinterpret_cast<const void*>(lordba_ptq_init_rows_kernel), lds_init, 2},
             {reinterpret_cast<const void*>(iR <= 16 ? lordba_ptq_ustep_kernel<16> : lordba_ptq_ustep_kernel<32>), lds_rows, iR <= 16 ? 3 : 4},
             {reinterpret_cast<const void*>(lordba_ptq_scale_kernel), lds_fixed, 5}, {reinterpret_cast<const void*>(lordba_ptq_beta_kernel), lds_beta, 6}};
+        std::lock_guard<std::mutex> guard(mu);
         for (const auto& b : big) {
             if (b.bytes > 160 * 1024) return LORDBA_ERR_DIM;
             size_t& have = granted[dev & 63][b.slot];
             if (b.bytes > 48 * 1024 && have < b.bytes) {
-                if (hipFuncSetAttribute(b.fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(b.bytes)) != hipSuccess)
+                if (hipFuncSetAttribute(b.fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(b.bytes)) != hipSuccess) {
+                    (void)hipGetLastError();
                     return LORDBA_ERR_LAUNCH;
+                }
                 have = b.bytes;
             }
         }
     }
+    // A launch the runtime refuses (say, an LDS request it does not grant) is reported at once, not only after the last one.
+    bool launch_failed = false;
+    auto launched = [&]() { if (hipGetLastError() != hipSuccess) launch_failed = true; };
     const int count = iR * iR + iR * ir0;
     auto totals = [&](int side, int n, int always) {
         hipLaunchKernelGGL(lordba_ptq_totals_kernel, dim3((n + 63) / 64), dim3(256), 0, stream, a, side, n, always);
@@ -1000,16 +1059,46 @@ extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_sta
     if (t_begin == 0) {   // the warm start; a later call continues from the state the workspace holds
         hipLaunchKernelGGL(lordba_ptq_fill_kernel, dim3((kInfoHead + K + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, info,
                            kInfoHead + K, 0.0);
-        hipLaunchKernelGGL(lordba_ptq_factor_gram_kernel, dim3(nb01), dim3(kThreads), lds_gram, stream, a);
-        totals(0, ir0 * ir0, 1);
-        totals(1, ir0 * ir0, 1);
-        hipLaunchKernelGGL(lordba_ptq_svd_kernel, dim3(1), dim3(64), lds_svd, stream, a);
+        // The triangular factors of A* and B*: panels of kQrRows rows, then groups of panel factors, level by level until one
+        // factor per side is left.  The factors of a level live in the area of the Gram shares (not in use yet): even
+        // levels at its start, odd levels behind the level-0 factors.
+        const double* Rfinal[2] = {nullptr, nullptr};
+        {
+            const int group = kQrRows / ir0;
+            int count[2];
+            const double* src[2] = {nullptr, nullptr};
+            for (int s = 0; s < 2; ++s) count[s] = static_cast<int>((a.n[s] + kQrRows - 1) / kQrRows);
+            const size_t c0[2] = {static_cast<size_t>(count[0]), static_cast<size_t>(count[1])};
+            for (int level = 0; Rfinal[0] == nullptr || Rfinal[1] == nullptr; ++level) {
+                QrLevel lv;
+                lv.level = level;
+                lv.group = group;
+                for (int s = 0; s < 2; ++s) {
+                    lv.src[s] = src[s];
+                    lv.count_in[s] = count[s];
+                    lv.count_out[s] = Rfinal[s] != nullptr ? 0 : (level == 0 ? count[s] : (count[s] + group - 1) / group);
+                    lv.dst[s] = a.part[s] + ((level & 1) ? c0[s] * ir0 * ir0 : 0);
+                }
+                hipLaunchKernelGGL(lordba_ptq_qr_kernel, dim3(lv.count_out[0] + lv.count_out[1]), dim3(256), lds_qr, stream, a, lv);
+                launched();
+                for (int s = 0; s < 2; ++s) {
+                    if (lv.count_out[s] == 0) continue;
+                    src[s] = lv.dst[s];
+                    count[s] = lv.count_out[s];
+                    if (count[s] == 1) Rfinal[s] = lv.dst[s];
+                }
+            }
+        }
+        hipLaunchKernelGGL(lordba_ptq_svd_kernel, dim3(1), dim3(64), lds_svd, stream, a, Rfinal[0], Rfinal[1]);
         hipLaunchKernelGGL(lordba_ptq_init_rows_kernel, dim3(nb01), dim3(kThreads), lds_init, stream, a);
+        launched();
         totals(1, count, 0);
         hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[0]), dim3(kRowThreads), lds_fixed, stream, a, 0);
         totals(0, count, 0);
         hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_fixed, stream, a, 1);
         totals(1, count, 0);
+        launched();
+        if (launch_failed) return LORDBA_ERR_LAUNCH;
     }
     for (int t = static_cast<int>(t_begin); t < static_cast<int>(t_end); ++t) {
         for (int side = 0; side < 2; ++side) {
@@ -1024,6 +1113,8 @@ extern "C" lordba_status lordba_ptq_sweeps(const void* A_star, const void* B_sta
         hipLaunchKernelGGL(lordba_ptq_scale_kernel, dim3(a.nb[1]), dim3(kRowThreads), lds_fixed, stream, a, 1);
         totals(1, count, 0);
         hipLaunchKernelGGL(lordba_ptq_beta_kernel, dim3(1), dim3(kRowThreads), lds_beta, stream, a, t);
+        launched();
+        if (launch_failed) return LORDBA_ERR_LAUNCH;
     }
     ExportArgs e;
     e.packedA = packedA;
@@ -1047,4 +1138,19 @@ extern "C" lordba_status lordba_ptq(const void* A_star, const void* B_star, uint
                                     int64_t r0, int64_t K, double tau, double mu, void* stream) {
     return lordba_ptq_sweeps(A_star, B_star, packedA, packedB, alpha, beta, gamma, s_in, s_rank, s_out, info, workspace,
                              workspace_bytes, N, M, R, r0, K, 0, K, tau, mu, stream);
+}
+
+extern "C" lordba_status lordba_ptq_beta_solve(const double* G, const double* h, double* beta, int64_t R, void* stream) {
+    if (R < 1 || R > LORDBA_PTQ_MAX_RANK) return LORDBA_ERR_DIM;
+    if (!G || !h || !beta) return LORDBA_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(h) | reinterpret_cast<uintptr_t>(beta)) & 7) return LORDBA_ERR_ALIGN;
+    const uintptr_t pb = reinterpret_cast<uintptr_t>(beta), pg = reinterpret_cast<uintptr_t>(G), ph = reinterpret_cast<uintptr_t>(h);
+    const size_t nb = static_cast<size_t>(R) * 8, ng = static_cast<size_t>(R) * R * 8;
+    if ((pb < pg + ng && pg < pb + nb) || (pb < ph + nb && ph < pb + nb)) return LORDBA_ERR_ALIAS;
+    const lordba_status ds = check_device();
+    if (ds != LORDBA_OK) return ds;
+    const int iR = static_cast<int>(R), ld = iR + 1;
+    const size_t lds_bytes = sizeof(double) * (iR * ld + (iR * ld > 288 ? iR * ld : 288) + 2 * iR) + sizeof(int) * iR;
+    hipLaunchKernelGGL(lordba_ptq_beta_solve_kernel, dim3(1), dim3(64), lds_bytes, static_cast<hipStream_t>(stream), G, h, beta, iR);
+    return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
 }

@@ -138,7 +138,7 @@ def test_flat_spectrum_and_large_entries(torch_cuda):
 @pytest.mark.parametrize("case", ["padded", "dependent", "few_rows", "both_sides"])
 def test_rank_deficient_factors(torch_cuda, case):
     # factors without full column rank (an adapter padded with dead columns, a repeated column, fewer rows than
-    # columns): the warm start takes its second route; the update still has rank >= R
+    # columns): their triangular factors are singular, which the warm start must not mind; the update still has rank >= R
     say("ptq rank-deficient factors: " + case)
     if case == "padded":
         d = inputs.make_ptq_inputs(30, 180, 140, 12)
@@ -159,6 +159,96 @@ def test_rank_deficient_factors(torch_cuda, case):
     ref = P.ptq(d["A_star"], d["B_star"], R, K=50)
     res = run_gpu(torch_cuda, d, R, K=50)
     compare(res, ref, 50)
+
+
+# Spectra that fall by many orders of magnitude within the first R singular values (column k of A_star damped by 0.6^k or
+# 0.55^k; the last columns underflow to zero in fp16).  The trailing singular vectors of the warm start (Eq. (svd-init)) are
+# then resolved to about eps sigma_1 / sigma_R by a dense decomposition, and the device must do as well: a route through the
+# Gram matrices of the factors would square that ratio and give a few near-zero entries of the trailing carriers the
+# other sign (the first case once differed in 9 of its 16 037 signs that way).
+ILL_CONDITIONED = [
+    # seed, N, M, R, r0, K, decay     sigma_R / sigma_1
+    (1056, 259, 294, 29, 36, 100, 0.6),    # 5e-7
+    (1057, 250, 221, 27, 40, 30, 0.6),     # 1e-6
+    (1076, 141, 215, 24, 35, 2, 0.6),      # 7e-6
+    (1090, 300, 280, 24, 40, 100, 0.55),
+    (1091, 700, 520, 32, 64, 40, 0.7),     # several QR panels per side, both ranks at their limits
+]
+
+
+@pytest.mark.parametrize("seed,N,M,R,r0,K,decay", ILL_CONDITIONED)
+def test_ill_conditioned_spectrum_matches_dense_svd(torch_cuda, seed, N, M, R, r0, K, decay):
+    say("ptq steep spectrum seed=%d N=%d M=%d R=%d r0=%d K=%d decay=%g" % (seed, N, M, R, r0, K, decay))
+    d = inputs.make_ptq_inputs(seed, N, M, r0, decay=decay)
+    T = d["A_star"].astype(np.float64) @ d["B_star"].astype(np.float64).T
+    sv = np.linalg.svd(T, compute_uv=False)
+    say("  sigma_R / sigma_1 = %.1e" % (sv[R - 1] / sv[0]))
+    assert 1e-9 < sv[R - 1] / sv[0] < 1e-3
+    ref = P.ptq(d["A_star"], d["B_star"], R, K=K)
+    res = run_gpu(torch_cuda, d, R, K=K)
+    compare(res, ref, K)
+
+
+def test_warm_start_alone_on_tall_factors(torch_cuda):
+    """K = 1 on tall factors (thousands of rows: several levels of QR panels): after one sweep every sign still agrees."""
+    say("ptq warm start, tall factors")
+    for seed, N, M, R, r0, decay in ((40, 3000, 1300, 12, 20, 0.7), (41, 5000, 700, 20, 48, 0.8)):
+        d = inputs.make_ptq_inputs(seed, N, M, r0, decay=decay)
+        ref = P.ptq(d["A_star"], d["B_star"], R, K=1)
+        res = run_gpu(torch_cuda, d, R, K=1)
+        compare(res, ref, 1)
+
+
+# ---- the rank-scale update on its own (Eq. (beta-gram), Eq. (beta-pinv)): lordba_ptq_beta_solve against the oracle ----
+
+def _beta_system(T, alpha, B1, B2, gamma):
+    """G and h of Eq. (beta-gram) written out with numpy (test input for the device routine)."""
+    Pm, Q = alpha[:, None] * B1, B2 * gamma[None, :]
+    return (Pm.T @ Pm) * (Q @ Q.T), np.sum((Pm.T @ T) * Q, axis=1)
+
+
+def _planted(seed, N, M, R, kind):
+    rng = np.random.default_rng(seed)
+    T = rng.standard_normal((N, M))
+    alpha, gamma = np.exp(0.3 * rng.standard_normal(N)), np.exp(0.3 * rng.standard_normal(M))
+    B1, B2 = P.sgn(rng.standard_normal((N, R))), P.sgn(rng.standard_normal((R, M)))
+    if kind == "duplicate pair":          # carrier pair 1 repeats pair 0: G has two equal rows, rank R - 1
+        B1[:, 1], B2[1, :] = B1[:, 0], B2[0, :]
+    elif kind == "negated pair":          # pair 2 = minus pair 0 on both sides: the same rank-one term again
+        B1[:, 2], B2[2, :] = -B1[:, 0], -B2[0, :]
+    elif kind == "three copies":          # rank R - 2
+        B1[:, 1], B2[1, :] = B1[:, 0], B2[0, :]
+        B1[:, R - 1], B2[R - 1, :] = B1[:, 0], B2[0, :]
+    elif kind == "dead rows":             # alpha = 0 on most rows: P^T P (a Gram matrix of 3 rows) has rank 3 and
+        alpha[3:] = 0.0                   # Q Q^T is made rank 2, so G has rank <= 6 whatever R is
+        B2[2:, :] = B2[:2, :][np.arange(R - 2) % 2]
+    elif kind == "zero":
+        alpha[:] = 0.0
+    return T, alpha, B1, B2, gamma
+
+
+@pytest.mark.parametrize("R", [1, 2, 5, 16, 17, 29, 32])
+@pytest.mark.parametrize("kind", ["full rank", "duplicate pair", "negated pair", "three copies", "dead rows", "zero"])
+def test_beta_solve_matches_the_oracle_pseudo_inverse(torch_cuda, R, kind):
+    torch = torch_cuda
+    if R < 3 and kind in ("negated pair", "three copies", "dead rows") or (R == 1 and kind == "duplicate pair"):
+        pytest.skip("needs more carrier pairs")
+    say("ptq beta solve R=%d %s" % (R, kind))
+    T, alpha, B1, B2, gamma = _planted(100 * R + len(kind), 60, 50, R, kind)
+    want = P.beta_update(T, alpha, B1, B2, gamma)
+    G, h = _beta_system(T, alpha, B1, B2, gamma)
+    rank = np.linalg.matrix_rank(G, hermitian=True)
+    assert (rank == R) == (kind == "full rank"), (kind, rank)
+    got = binding.lordba_ptq_beta_solve(torch.from_numpy(G).cuda(), torch.from_numpy(h).cuda())
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    say("  rank %d of %d, |beta| %.3e, rel err %.1e" % (rank, R, np.linalg.norm(want), rel(got, want) if np.linalg.norm(want) else 0.0))
+    if kind == "zero":
+        assert np.all(got == 0.0) and np.all(want == 0.0)
+    else:
+        assert rel(got, want) <= TOL_REAL
+        # the solution of least norm among the least-squares solutions: G beta reproduces G pinv(G) h, and beta is in G's range
+        assert np.linalg.norm(G @ got - G @ want) <= 1e-8 * np.linalg.norm(G @ want)
 
 
 def test_carrier_rank_beyond_the_rank_of_the_update_is_flagged(torch_cuda):
