@@ -129,8 +129,8 @@ lordba_status lordba_forward_multi(const void* x, const uint32_t* packedA, const
                                    const void* y_base, void* y_out,
                                    int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream);
 
-/* Same with the kernel chosen by the caller: LORDBA_ALGO_AUTO, _GENERAL, _MFMA_T8 or _MFMA_T16 (for ell >= 2 the
- * matrix-core kernel always runs 8 waves per workgroup; the tuning values 4..7 exist for ell == 1 only). */
+/* Same with the kernel chosen by the caller: LORDBA_ALGO_AUTO, _GENERAL, _MFMA_T8 or _MFMA_T16; for ell >= 2 the tuning
+ * values 6 and 7 select the 8-row / 16-row matrix-core kernel on 8 waves per workgroup (4 and 5 exist for ell == 1 only). */
 lordba_status lordba_forward_multi_algo(const void* x, const uint32_t* packedA, const uint32_t* packedB,
                                         const void* s_in, const void* s_rank, const void* s_out,
                                         const void* y_base, void* y_out,

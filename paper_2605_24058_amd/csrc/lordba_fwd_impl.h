@@ -121,10 +121,16 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     static_assert(NW >= 4, "stage 2 is spread over the first four waves");
     constexpr bool LP = GM == 1, SPLIT = GM == 2 || GM == 3, MASK = GM == 3;
     constexpr int NI = TMV / 4;           // 16-byte row accesses per lane per 128-column block of a tile
-    constexpr int D2 = 2;                 // y_base column blocks in flight per wave
+    // y_base column blocks in flight per wave.  Three and four envelopes run on 8 waves (their registers do not fit 16
+    // waves): on 8-row tiles four blocks in flight per wave keep as many bytes of y_base under way per compute unit as 16
+    // waves with two.  Four envelopes on 16-row tiles (grids of at least 256 tiles, two workgroups per compute unit) hold one.
+    constexpr int D2 = (TMV == 16 && L == 4) ? 1 : (NW == 8 && TMV == 8 && ((L >= 3 && RB == 1) || (L == 3 && RB == 2))) ? 4 : 2;
     constexpr bool R16 = BM == 1, R8 = BM == 2;
     static_assert(!R8 || RB == 1, "r = 8 is one rank block");
-    constexpr bool PRE = (R16 || R8) && RB == 1;  // sign operands of the first block are built before u is known
+    // Four envelopes on 16-row tiles: to stay inside the registers, no sign operands are built ahead and the row scalings
+    // are read from LDS where they are used.
+    constexpr bool LEAN = TMV == 16 && L == 4;
+    constexpr bool PRE = (R16 || R8) && RB == 1 && !LEAN;  // sign operands of the first block are built before u is known
 
     // The wave index is read into a scalar register: what depends on it (which chunks and blocks a wave owns, which waves
     // run stage 2) then branches on scalar conditions.  MFMA instructions ignore the EXEC mask, so they must never end up
@@ -371,29 +377,32 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // Training: the rank-r intermediate t (before the rank scaling) is kept for the backward pass.  The stores are issued
     // after everything else: vector memory stores count in the same counter as the loads and may complete out of order
     // with them, so that a wait for y_base issued after such a store could also have to wait for the store.
+    constexpr int SG = (L >= 3 && NW >= 8) ? 2 : 1;  // groups of four waves that share the envelopes of stage 2
     float tkeep[TR ? RB * L : 1];
     auto export_t = [&]() {
         if constexpr (TR) {
-            if (wave < 4 && a.t_out != nullptr) {
-                const int i = wave;
+            if (wave < 4 * SG && a.t_out != nullptr) {
+                const int i = wave & 3, grp = wave >> 2;
                 const int row = TMV == 16 ? q * 4 + i : q * 2 + (i & 1);
                 if ((TMV == 16 || i < 2) && row >= first && row <= last) {
 #pragma unroll
                     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
                         for (int en = 0; en < L; ++en)
-                            if (rb * 16 + li < r)
+                            if (en % SG == grp && rb * 16 + li < r)
                                 a.t_out[(static_cast<int64_t>(en) * r + rb * 16 + li) * a.t_stride + t0 + row] = tkeep[rb * L + en];
                     }
                 }
             }
         }
     };
-    if (wave < 4) {
+    if (wave < 4 * SG) {
         // Accumulator layout: lane (li, q) holds rank li of the block for MFMA rows 4q .. 4q+3; wave i takes row 4q+i.
-        const int i = wave;
+        // With several envelopes and at least 8 waves, waves 0..3 take the even envelopes and waves 4..7 the odd ones.
+        const int i = wave & 3, grp = wave >> 2;
 #pragma unroll
         for (int en = 0; en < L; ++en) {
+            if (SG > 1 && en % SG != grp) continue;
             float u[RB];
             float amax = 0.f;
 #pragma unroll
@@ -436,7 +445,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // a pair instead, so that two envelopes cost the matrix-core work and the accumulator registers of one.
     constexpr int VS = TMV == 8 ? (L + 1) / 2 : L;  // accumulator sets per output column
     h8 ufrag[RB][VS];
-    float inv[NI][L];
+    float inv[LEAN ? 1 : NI][LEAN ? 1 : L];
 #pragma unroll
     for (int vs = 0; vs < VS; ++vs) {
         int en = vs;
@@ -447,10 +456,12 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) ufrag[rb][vs] = as_h8(load16(us + ((rb * L + en) * 16 + li) * kURow + q * 8));
     }
+    if constexpr (!LEAN) {
 #pragma unroll
-    for (int en = 0; en < L; ++en) {
+        for (int en = 0; en < L; ++en) {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) inv[i][en] = invs[en * 16 + q * 4 + i];
+            for (int i = 0; i < NI; ++i) inv[i][en] = invs[en * 16 + q * 4 + i];
+        }
     }
 
     // ---------------------------------------------------------------- stage 3: expand + epilogue ----
@@ -480,44 +491,97 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
                 }
             }
         }
-        f4 v[VS][8];
+        // The sign operand of (column e, rank block rb): built ahead for the first block; otherwise from the table (measured
+        // faster than building it here with the vector ALU, which stage 3 needs for the epilogue).
+        auto sign_operand = [&](int e, int rb) -> u4 {
+            return (PRE && use_pre) ? pre[e] : *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutp) + off[e][rb]);
+        };
+        if constexpr (L == 1) {
+            f4 v[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
+            for (int e = 0; e < 8; ++e) {
+                v[e] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int vs = 0; vs < VS; ++vs) v[vs][e] = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                // Built ahead for the first block; otherwise from the table (measured faster than building them here
-                // with the vector ALU, which stage 3 needs for the epilogue).  All envelopes share the operand.
-                const u4 sg = (PRE && use_pre) ? pre[e]
-                                               : *reinterpret_cast<const u4*>(reinterpret_cast<const unsigned char*>(lutp) + off[e][rb]);
-#pragma unroll
-                for (int vs = 0; vs < VS; ++vs)
-                    v[vs][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb][vs], as_h8(sg), v[vs][e], 0, 0, 0);
+                for (int rb = 0; rb < RB; ++rb)
+                    v[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb][0], as_h8(sign_operand(e, rb)), v[e], 0, 0, 0);
             }
-        }
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int row = TMV == 16 ? q * 4 + i : q * 2 + i;
-            u4 out;
+            for (int i = 0; i < NI; ++i) {
+                const int row = TMV == 16 ? q * 4 + i : q * 2 + i;
+                u4 out;
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const h2 b = as_h2(ybuf[slot][i][d]);
-                float o0 = static_cast<float>(b[0]), o1 = static_cast<float>(b[1]);
-#pragma unroll
-                for (int en = 0; en < L; ++en) {  // envelopes are added in their order, in fp32; one rounding at the end
-                    const h2 so = as_h2(sobuf[slot][en][d]);
-                    const int vs = TMV == 8 ? en >> 1 : en;           // accumulator set of this envelope
-                    const int vi = TMV == 8 ? i + 2 * (en & 1) : i;   // and its register inside the set
-                    o0 = __builtin_fmaf(v[vs][2 * d][vi] * inv[i][en], static_cast<float>(so[0]), o0);
-                    o1 = __builtin_fmaf(v[vs][2 * d + 1][vi] * inv[i][en], static_cast<float>(so[1]), o1);
+                for (int d = 0; d < 4; ++d) {
+                    const h2 b = as_h2(ybuf[slot][i][d]);
+                    const h2 so = as_h2(sobuf[slot][0][d]);
+                    h2 o;
+                    o[0] = static_cast<_Float16>(__builtin_fmaf(v[2 * d][i] * inv[i][0], static_cast<float>(so[0]), static_cast<float>(b[0])));
+                    o[1] = static_cast<_Float16>(__builtin_fmaf(v[2 * d + 1][i] * inv[i][0], static_cast<float>(so[1]), static_cast<float>(b[1])));
+                    out[d] = __builtin_bit_cast(uint32_t, o);
                 }
-                h2 o;
-                o[0] = static_cast<_Float16>(o0);
-                o[1] = static_cast<_Float16>(o1);
-                out[d] = __builtin_bit_cast(uint32_t, o);
+                if (j_ok && row >= first && row <= last) store16_stream(at(yot, static_cast<uint32_t>(row * d_out + j0) * 2u), out);
             }
-            if (j_ok && row >= first && row <= last) store16_stream(at(yot, static_cast<uint32_t>(row * d_out + j0) * 2u), out);
+        } else {
+            // Several envelopes: the accumulator sets are run one after the other into the same registers, and each set is
+            // folded at once into the fp32 outputs of the lane's 8 columns (which start from y_base), so the register cost
+            // is one accumulator set plus 8 NI floats whatever L is.  The sign operands are read again per set (LDS).
+            // Envelopes are added in their order, in fp32; one rounding at the end.
+            float o[NI][8];
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const h2 b = as_h2(ybuf[slot][i][d]);
+                    o[i][2 * d] = static_cast<float>(b[0]);
+                    o[i][2 * d + 1] = static_cast<float>(b[1]);
+                }
+            }
+            constexpr int EH = (D2 > 2 || (TMV == 16 && L >= 3)) ? 4 : 8;   // columns per pass: half a set at a time where more blocks are in flight
+#pragma unroll
+            for (int vs = 0; vs < VS; ++vs) {
+#pragma unroll
+                for (int e0 = 0; e0 < 8; e0 += EH) {
+                    f4 v[EH];
+#pragma unroll
+                    for (int e = 0; e < EH; ++e) {
+                        v[e] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb)
+                            v[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ufrag[rb][vs], as_h8(sign_operand(e0 + e, rb)), v[e], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int sub = 0; sub < (TMV == 8 ? 2 : 1); ++sub) {
+                        const int en = TMV == 8 ? 2 * vs + sub : vs;   // 8-row tiles: the set carries a pair of envelopes
+                        if (en < L) {
+#pragma unroll
+                            for (int i = 0; i < NI; ++i) {
+                                const int vi = TMV == 8 ? i + 2 * sub : i;   // the envelope's register inside the set
+                                float iv;
+                                if constexpr (LEAN) iv = invs[en * 16 + q * 4 + i];
+                                else iv = inv[i][en];
+#pragma unroll
+                                for (int d = e0 / 2; d < (e0 + EH) / 2; ++d) {
+                                    const h2 so = as_h2(sobuf[slot][en][d]);
+                                    o[i][2 * d] = __builtin_fmaf(v[2 * d - e0][vi] * iv, static_cast<float>(so[0]), o[i][2 * d]);
+                                    o[i][2 * d + 1] = __builtin_fmaf(v[2 * d + 1 - e0][vi] * iv, static_cast<float>(so[1]), o[i][2 * d + 1]);
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int row = TMV == 16 ? q * 4 + i : q * 2 + i;
+                u4 out;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    h2 oh;
+                    oh[0] = static_cast<_Float16>(o[i][2 * d]);
+                    oh[1] = static_cast<_Float16>(o[i][2 * d + 1]);
+                    out[d] = __builtin_bit_cast(uint32_t, oh);
+                }
+                if (j_ok && row >= first && row <= last) store16_stream(at(yot, static_cast<uint32_t>(row * d_out + j0) * 2u), out);
+            }
         }
     };
 
@@ -787,7 +851,7 @@ lordba_status launch_mfma_rb(const FwdArgs& a, hipStream_t stream) {
     // keep L accumulator sets per block: 16-row tiles then only fit two envelopes of at most two rank blocks.
     constexpr int kMaxRb = NW == 16 ? (L == 1 ? (TMV == 8 ? 2 : 1) : (L == 2 && TMV == 8 ? 1 : 0))
                            : L == 1 ? 4
-                           : TMV == 16 ? (L == 2 ? 2 : 0)
+                           : TMV == 16 ? (L == 2 ? 2 : 1)
                            : (L == 4 ? 3 : 4);
     const int rb = (a.r + 15) / 16;
     if (rb > kMaxRb) return LORDBA_ERR_ALGO;
@@ -842,7 +906,7 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
     if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || r > LORDBA_MAX_RANK) return LORDBA_ERR_DIM;
     if (batched && (n_adapters < 1 || n_adapters > (1 << 20))) return LORDBA_ERR_DIM;
     if (T > INT32_MAX - 64 || d_in > (1 << 24) || d_out > (1 << 24)) return LORDBA_ERR_DIM;
-    if (algo < 0 || algo > (L == 1 ? 7 : 3)) return LORDBA_ERR_ALGO;
+    if (algo < 0 || algo > 7 || (L > 1 && (algo == 4 || algo == 5))) return LORDBA_ERR_ALGO;
     // With no token rows the activation pointers may legitimately be NULL (empty allocations).
     if (T == 0) return (packedA && packedB && s_in && s_rank && s_out) ? LORDBA_OK : LORDBA_ERR_NULL;
     const bool t_only = t_out != nullptr && y_base == nullptr && y_out == nullptr;  // training: only the rank-r intermediate
@@ -946,8 +1010,9 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
             s = launch_mfma_rb<16, 8, L>(a, st);
             if (s == LORDBA_ERR_ALGO && algo == LORDBA_ALGO_AUTO) s = launch_mfma_rb<8, 8, L>(a, st);
         } else {
-            s = LORDBA_ERR_ALGO;
-            if constexpr (L == 2) s = launch_mfma_rb<8, 16, L>(a, st);  // a pair of envelopes fits the registers of 16 waves
+            // a pair of envelopes with one rank block fits the registers of 16 waves (the pair shares an accumulator set);
+            // anything more, or the tuning value 6, runs 8 waves
+            s = algo == 6 ? LORDBA_ERR_ALGO : launch_mfma_rb<8, 16, L>(a, st);
             if (s == LORDBA_ERR_ALGO) s = launch_mfma_rb<8, 8, L>(a, st);
         }
     }

@@ -80,7 +80,7 @@ def algos_for(sh, ell):
     does not fit its registers or LDS; AUTO and GENERAL must always run."""
     al = [(A_AUTO, False), (A_GEN, False)]
     if sh.d_in % 32 == 0 and sh.d_out % 8 == 0:
-        al += [(A_T8, True), (A_T16, True)]
+        al += [(A_T8, True), (A_T16, True), (6, True), (7, True)]   # 6, 7: the same tile heights on 8 waves
     return al
 
 
@@ -128,11 +128,35 @@ def test_headline_shape_all_rows(torch_cuda, ell):
     check(torch_cuda, d, A_AUTO, "c2")
 
 
-def test_tall_shape_sampled_rows(torch_cuda):
-    sh = inputs.C3_UP                     # T = 4096: 16-row tiles
-    d = inputs.make_inputs_multi(1, sh.T, sh.d_in, sh.d_out, sh.r, 2)
+@pytest.mark.parametrize("ell", [2, 3, 4])
+def test_tall_shape_sampled_rows(torch_cuda, ell):
+    sh = inputs.C3_UP                     # T = 4096: 16-row tiles (four envelopes: the variant with one y block in flight)
+    d = inputs.make_inputs_multi(1, sh.T, sh.d_in, sh.d_out, sh.r, ell)
     rows = np.unique(np.concatenate([np.arange(0, sh.T, 97), [0, 15, 16, sh.T - 17, sh.T - 1]]))
     check(torch_cuda, d, A_AUTO, "c3_up", rows=rows)
+
+
+@pytest.mark.parametrize("sh,ell", [(inputs.Shape("T4100_1024x1152_r16", 4100, 1024, 1152, 16), 3),
+                                    (inputs.Shape("T4107_640x896_r16", 4107, 640, 896, 16), 4),
+                                    (inputs.Shape("T4099_512x640_r12", 4099, 512, 640, 12), 4),
+                                    (inputs.Shape("T4112_384x512_r32", 4112, 384, 512, 32), 3),
+                                    (inputs.Shape("T2100_1024x1152_r16", 2100, 1024, 1152, 16), 4),
+                                    (inputs.Shape("T300_4096x4096_r16", 300, 4096, 4096, 16), 3)],
+                         ids=lambda v: v.name if hasattr(v, "name") else "l%d" % v)
+def test_sixteen_row_tiles_and_deep_y_pipeline_every_row(torch_cuda, sh, ell):
+    """Three and four envelopes on 16-row tiles (T >= 4096, ragged last tile, a general rank, two rank blocks falling
+    back to 8-row tiles) and on 8-row tiles with four y blocks in flight per wave (more blocks than four per wave at
+    4096 columns, fewer at 1152), every row against the oracle, every matrix-core selector."""
+    d = inputs.make_inputs_multi(13, sh.T, sh.d_in, sh.d_out, sh.r, ell)
+    ran = 0
+    for algo in (A_AUTO, A_T8, A_T16, 6, 7):
+        try:
+            check(torch_cuda, d, algo, sh.name)
+            ran += 1
+        except binding.LordbaError as e:
+            assert algo != A_AUTO and e.status == 8, (algo, e.status)
+            say("  algo %d declines %s with ell=%d" % (algo, sh.name, ell))
+    assert ran >= 2
 
 
 def test_one_envelope_through_the_multi_entry_point_is_the_single_call(torch_cuda):
