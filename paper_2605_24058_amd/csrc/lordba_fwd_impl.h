@@ -109,7 +109,8 @@ __host__ __device__ constexpr size_t mfma_lds_bytes(int RB, int TMV, int NW, int
 //      operands during stage 2 instead of before it.  2 (a handful of tiles): gridDim.y workgroups share a token tile
 //      and split its output blocks; the x extent of the grid is padded to a multiple of 8 and padding workgroups exit.
 //      3 (fewer token rows than a tile): as 2, and rows past T are not requested at all.  4: multi-adapter batch,
-//      workgroup (tile, k) processes the k-th run of rows of its tile that use the same adapter.  0: none of these.
+//      the gridDim.y workgroups of a tile share its runs of rows that use the same adapter (rows outside a run are not
+//      requested).  0: none of these.
 // L    scale envelopes over the same carriers (Eq. (lordba)): s_in, s_rank, s_out hold L rows; everything that depends
 //      on a scale is done L times, everything that depends only on x or on the carrier bits once
 //
@@ -119,18 +120,21 @@ __host__ __device__ constexpr size_t mfma_lds_bytes(int RB, int TMV, int NW, int
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L, bool TR>
 __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, const int64_t t0, const int first, const int last) {
     static_assert(NW >= 4, "stage 2 is spread over the first four waves");
-    constexpr bool LP = GM == 1, SPLIT = GM == 2 || GM == 3, MASK = GM == 3;
+    constexpr bool LP = GM == 1, SPLIT = GM == 2 || GM == 3, MASK = GM == 3 || GM == 4;
     constexpr int NI = TMV / 4;           // 16-byte row accesses per lane per 128-column block of a tile
     // y_base column blocks in flight per wave.  Three and four envelopes run on 8 waves (their registers do not fit 16
     // waves): on 8-row tiles four blocks in flight per wave keep as many bytes of y_base under way per compute unit as 16
-    // waves with two.  Four envelopes on 16-row tiles (grids of at least 256 tiles, two workgroups per compute unit) hold one.
-    constexpr int D2 = (TMV == 16 && L == 4) ? 1 : (NW == 8 && TMV == 8 && ((L >= 3 && RB == 1) || (L == 3 && RB == 2))) ? 4 : 2;
+    // waves with two.  The multi-adapter batch on 8 waves holds three (two of its workgroups share a compute unit, so a
+    // lane has 128 registers).  Four envelopes on 16-row tiles (grids of at least 256 tiles, two workgroups per compute
+    // unit) hold one.
+    constexpr int D2 = (TMV == 16 && L == 4) ? 1 : (GM == 4 && NW == 8 && RB == 1) ? 3 : (NW == 8 && TMV == 8 && ((L >= 3 && RB == 1) || (L == 3 && RB == 2))) ? 4 : 2;
     constexpr bool R16 = BM == 1, R8 = BM == 2;
     static_assert(!R8 || RB == 1, "r = 8 is one rank block");
     // Four envelopes on 16-row tiles: to stay inside the registers, no sign operands are built ahead and the row scalings
     // are read from LDS where they are used.
     constexpr bool LEAN = TMV == 16 && L == 4;
-    constexpr bool PRE = (R16 || R8) && RB == 1 && !LEAN;  // sign operands of the first block are built before u is known
+    // (not in the multi-adapter batch on 8 waves either: two of its workgroups must fit a compute unit, 128 registers per lane)
+    constexpr bool PRE = (R16 || R8) && RB == 1 && !LEAN && !(GM == 4 && NW == 8);  // sign operands of the first block are built before u is known
 
     // The wave index is read into a scalar register: what depends on it (which chunks and blocks a wave owns, which waves
     // run stage 2) then branches on scalar conditions.  MFMA instructions ignore the EXEC mask, so they must never end up
@@ -601,23 +605,37 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     export_t();
 }
 
+// The second launch bound is the number of waves per SIMD the registers must leave room for: what the workgroup size
+// implies, except in the multi-adapter batch on 8 waves (one rank block, or two with whole-word carrier rows), where two
+// workgroups have to share a compute unit.
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L, bool TR>
-__global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
+__global__ __launch_bounds__(NW * 64, (GM == 4 && NW == 8 && (RB == 1 || (RB == 2 && BM == 1))) ? 4 : NW / 4) void lordba_fwd_mfma_kernel(FwdArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
-    if ((GM == 2 || GM == 3) && t0 >= a.T) return;  // padding workgroup (the whole workgroup leaves, before any barrier)
-    const int last = static_cast<int>(a.T - 1 - t0 < TMV - 1 ? a.T - 1 - t0 : TMV - 1);  // last live row of the tile
     if constexpr (GM != 4) {
+        const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
+        if ((GM == 2 || GM == 3) && t0 >= a.T) return;  // padding workgroup (the whole workgroup leaves, before any barrier)
+        const int last = static_cast<int>(a.T - 1 - t0 < TMV - 1 ? a.T - 1 - t0 : TMV - 1);  // last live row of the tile
         fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L, TR>(a, smem, t0, 0, last);
     } else {
-        // Multi-adapter batch: the rows of a tile are taken in runs of equal adapter index.  A tile of a sorted batch
-        // has one run (two where requests meet), a decode batch has one per row.
-        // Workgroup (tile, k) handles the k-th run of its tile and leaves if there is none, so the runs of a tile proceed
-        // in parallel.  A workgroup that only finds out that it has nothing to do still holds a CU slot for most of a
-        // microsecond: on grids that fill the chip the host picks 8-wave workgroups, two of which fit a CU, so that
-        // these pass through the second slot while the first works.  (One workgroup per tile looping over its runs
-        // was tried: inlined into a loop, and also behind a real call, the tile code compiles to twice the time.)
+        // Multi-adapter batch: the rows of a tile are taken in runs of equal adapter index.  A tile of a sorted batch has
+        // one run (two where requests meet), a decode batch has one per row.  The gridDim.y workgroups of a tile share its
+        // runs: workgroup y takes runs y, y + gridDim.y, ... and leaves if it has none.  The host launches 8 per tile while
+        // the tiles are few (every run of a decode batch in parallel; the compute units would idle otherwise) and 2 on
+        // grids that fill the chip: there the first workgroup of a tile of a sorted batch does all the work and the second
+        // only finds out that it has none, which still holds a slot of a compute unit for most of a microsecond - the
+        // workgroups have 8 waves, two fit a compute unit, so these pass through the second slot while the first works.
+        // A workgroup's first run is straight-line code; further runs of the same workgroup go through a loop around a
+        // second copy of the tile code, which compiles to about twice the time per run (spills, conservative waits) but
+        // is only met by tiles with more runs than workgroups.
+        // Consecutive tiles go to the same XCD (workgroups are dealt to the 8 XCDs round-robin in launch order): the tiles
+        // of one request then read their adapter through one L2 instead of pulling it into several.
         static_assert(TMV == 8, "runs are found among 8 rows");
+        const int64_t tiles = (static_cast<int64_t>(a.T) + TMV - 1) / TMV, per_xcd = (tiles + 7) >> 3;
+        const bool by_xcd = a.blocks_per_wg != 0;  // (set by the host on grids that fill the chip; the x extent is then padded)
+        const int64_t tile = by_xcd ? static_cast<int64_t>(blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3) : static_cast<int64_t>(blockIdx.x);
+        if (tile >= tiles) return;  // padding workgroup
+        const int64_t t0 = tile * TMV;
+        const int last = static_cast<int>(a.T - 1 - t0 < TMV - 1 ? a.T - 1 - t0 : TMV - 1);
         const int lane = threadIdx.x & 63;
         int my_id = -1;
         if ((lane & 7) <= last) my_id = a.ids[t0 + (lane & 7)];
@@ -628,25 +646,35 @@ __global__ __launch_bounds__(NW * 64) void lordba_fwd_mfma_kernel(FwdArgs a) {
             while (end < last && __builtin_amdgcn_readlane(my_id, end + 1) == id) ++end;
             return end;
         };
-        auto one_run = [&](int first, int end) {
-            const int id = __builtin_amdgcn_readlane(my_id, first);
-            if (id >= 0) {
-                const FwdArgs b = select_adapter(a, id);
-                fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L, TR>(b, smem, t0, first, end);
-            } else if (a.y_out != a.y_base) {  // no adapter: the rows pass through
-                for (int row = first; row <= end; ++row) {
-                    const _Float16* src = a.y_base + (t0 + row) * a.d_out;
-                    _Float16* dst = a.y_out + (t0 + row) * a.d_out;
-                    for (int c = static_cast<int>(threadIdx.x) * 8; c < a.d_out; c += NW * 64 * 8)
-                        store16_stream(dst + c, load16_stream(src + c));
-                }
+        auto pass_through = [&](int first, int end) {  // no adapter: the rows pass through
+            if (a.y_out == a.y_base) return;
+            for (int row = first; row <= end; ++row) {
+                const _Float16* src = a.y_base + (t0 + row) * a.d_out;
+                _Float16* dst = a.y_out + (t0 + row) * a.d_out;
+                for (int c = static_cast<int>(threadIdx.x) * 8; c < a.d_out; c += NW * 64 * 8)
+                    store16_stream(dst + c, load16_stream(src + c));
             }
         };
-        const int want = static_cast<int>(blockIdx.y);
-        int first = 0;
-        for (int run = 0; run < want && first <= last; ++run) first = run_end(first) + 1;
-        if (first > last) return;  // no such run: the whole workgroup leaves, before any barrier
-        one_run(first, run_end(first));
+        auto skip_runs = [&](int first, int n) {  // start of the run n runs after the one that starts at `first` (> last: none)
+            for (int k = 0; k < n && first <= last; ++k) first = run_end(first) + 1;
+            return first;
+        };
+        const int stride = static_cast<int>(gridDim.y);
+        int first = skip_runs(0, static_cast<int>(blockIdx.y));
+        if (first > last) return;  // no run for this workgroup: it leaves, before any barrier
+        {
+            const int end = run_end(first), id = __builtin_amdgcn_readlane(my_id, first);
+            if (id >= 0) fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L, TR>(select_adapter(a, id), smem, t0, first, end);
+            else pass_through(first, end);
+            first = skip_runs(end + 1, stride - 1);
+        }
+        while (first <= last) {
+            const int end = run_end(first), id = __builtin_amdgcn_readlane(my_id, first);
+            __syncthreads();  // the previous run's last LDS reads are over
+            if (id >= 0) fwd_tile<RB, TMV, NW, D1, OS, BM, GM, L, TR>(select_adapter(a, id), smem, t0, first, end);
+            else pass_through(first, end);
+            first = skip_runs(end + 1, stride - 1);
+        }
     }
 }
 
@@ -801,7 +829,11 @@ lordba_status launch_mfma_gm(const FwdArgs& a, hipStream_t stream) {
         // through one L2 instead of fetching them into eight; the padding workgroups exit at once.
         grid = dim3((tiles + 7u) & ~7u, split);
     }
-    if constexpr (GM == 4) grid = dim3(tiles, TMV);  // one workgroup per possible run of a tile (see the kernel)
+    if constexpr (GM == 4) {  // see the kernel
+        const bool big = tiles > 32;
+        b.blocks_per_wg = big ? 1 : 0;  // (read by the kernel as "tiles are dealt to the XCDs in contiguous ranges")
+        grid = big ? dim3((tiles + 7u) & ~7u, 2) : dim3(tiles, TMV);
+    }
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, stream, b);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
     }
@@ -814,7 +846,8 @@ template <int RB, int TMV, int NW, int D1, bool OS, int BM, int L>
 lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
     const int64_t tiles = (static_cast<int64_t>(a.T) + TMV - 1) / TMV;
     if (a.ids != nullptr) {
-        if constexpr (TMV == 8 && L == 1 && NW >= 8) {
+        // (two rank blocks on 16 waves would spill a few registers in the batch mode's second copy of the tile code: 8 waves)
+        if constexpr (TMV == 8 && L == 1 && D1 <= 4 && (NW == 8 || (NW == 16 && RB == 1))) {
             return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 4, L>(a, stream);
         }
         return LORDBA_ERR_ALGO;
@@ -841,7 +874,7 @@ lordba_status launch_mfma_depth(const FwdArgs& a, hipStream_t stream) {
     const int per_wave = (nchunks + NW - 1) / NW;
     if (per_wave <= 2) return launch_mfma<RB, TMV, NW, 2, true, BM, L>(a, stream);
     if (per_wave <= 4) return launch_mfma<RB, TMV, NW, 4, true, BM, L>(a, stream);
-    if (kDeep && per_wave <= 8) return launch_mfma<RB, TMV, NW, (kDeep ? 8 : 4), true, BM, L>(a, stream);
+    if (kDeep && per_wave <= 8 && a.ids == nullptr) return launch_mfma<RB, TMV, NW, (kDeep ? 8 : 4), true, BM, L>(a, stream);  // (the batch mode has 128 registers)
     return launch_mfma<RB, TMV, NW, (TMV == 8 ? 4 : 2), false, BM, L>(a, stream);
 }
 
@@ -1002,6 +1035,7 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
             // twelve of thirteen shapes at T = 2304 ... 3584, 1 % slower on one).
             const bool two_per_cu = algo == LORDBA_ALGO_AUTO && (T + 7) / 8 > 256;
             s = rb <= 2 && !two_per_cu ? launch_mfma_rb<8, 16, 1>(a, st) : launch_mfma_rb<8, 8, 1>(a, st);
+            if (batched && s == LORDBA_ERR_ALGO) s = launch_mfma_rb<8, 8, 1>(a, st);
         }
     } else {
         if (t_out != nullptr) {

@@ -87,6 +87,15 @@ CASES = [
     (9, 33, 17, 3, 2, "decode"),                # nothing aligned: general kernel
     (1, 4096, 4096, 16, 2, "segments"),
     (8, 2048, 1024, 16, 8, "decode"),
+    # more than 32 tiles: two 8-wave workgroups per tile share its runs (the second and later runs of a workgroup go through
+    # the looped copy of the tile code), tiles dealt to the XCDs in contiguous ranges, tile counts that are no multiple of 8
+    (301, 512, 640, 16, 9, "decode"),           # 38 tiles, up to 8 runs each, ragged last tile
+    (333, 384, 512, 16, 6, "mixed"),            # runs without an adapter inside the loops
+    (290, 640, 384, 8, 5, "decode"),
+    (275, 256, 384, 32, 7, "decode"),           # two rank blocks
+    (270, 256, 256, 64, 3, "mixed"),            # four rank blocks (one workgroup per compute unit)
+    (280, 512, 384, 12, 4, "decode"),           # generic carrier fetch
+    (520, 8192, 512, 16, 3, "segments"),        # 64 chunks of x: the looped x pipeline (the batch mode has no 8-deep one)
 ]
 
 
