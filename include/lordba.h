@@ -208,9 +208,10 @@ lordba_status lordba_forward_multi_save_t(const void* x, const uint32_t* packedA
  *   packedA : S_A   as [r, d_in]    (the forward pass's packedA)
  *   packedAt: S_A^T as [d_in, r]    packedBt: S_B^T as [r, d_out]     (the same canonical format, transposed matrices;
  *             the carriers are taken from these bits, which the caller keeps equal to the signs of the latents)
- *   t_saved : the rank-r intermediate that lordba_forward_save_t wrote for this x and adapter, with its t_stride, which
- *             must be a multiple of 4 and at least T rounded up to a multiple of 128 (the rows are read in whole steps;
- *             entries past T are ignored), 16-byte aligned; or NULL: it is recomputed from x (one more pass over x).
+ *   t_saved : the rank-r intermediate that lordba_forward_save_t wrote for this x and adapter, with its t_stride >= T
+ *             (entries past T are ignored); or NULL: it is recomputed from x (one more pass over x).  The matrix-core
+ *             kernels take it only with a t_stride that is a multiple of 4 and at least T rounded up to a multiple of
+ *             128 (they read the rows in whole steps), 16-byte aligned.
  *   d_latentA == NULL and d_latentB == NULL together: the carriers are frozen and only the scales are trained (the
  *   "QAT Freeze" mode of Sec. 3.2): no latent gradients are computed; latentA, latentB and kappa are then ignored.
  *   dx_base fp16 [T, d_in]: the input gradient of the base path, to which the branch's is added; dx may be the same
@@ -219,8 +220,10 @@ lordba_status lordba_forward_multi_save_t(const void* x, const uint32_t* packedA
  *   by the caller, contents irrelevant before and after; a smaller one -> LORDBA_ERR_WORKSPACE.  Calls that share a
  *   workspace must not overlap in time.
  * No output, nor the workspace, may overlap an input or another output (dx == dx_base excepted): LORDBA_ERR_ALIAS.
- * Shapes: d_in and d_out multiples of 32, 1 <= r <= 64, activations, scales and packed carriers 16-byte aligned; else
- * LORDBA_ERR_DIM / LORDBA_ERR_ALIGN.  T == 0: the parameter gradients are set to zero.
+ * Shapes: any d_in, d_out >= 1 and 1 <= r <= 64, every pointer aligned to its element (the workspace to 16 bytes), as
+ * lordba_forward and lordba_forward_save_t; else LORDBA_ERR_DIM / LORDBA_ERR_ALIGN.  With d_in and d_out multiples of 32
+ * and 16-byte aligned activations, scales and packed carriers the matrix-core kernels run; anything else takes a slower
+ * general kernel with the same results (one thread per column).  T == 0: the parameter gradients are set to zero.
  * The call only enqueues kernels on `stream`; it never synchronises, allocates or frees.  Results are deterministic
  * (fixed summation order).  Arithmetic: fp16 inputs at their exact values, fp32 accumulation; every gradient array is
  * within 1e-3 relative L2 (per token row for dx, per rank for the latents, whole vector for the scales) of the exact result. */
@@ -252,7 +255,8 @@ lordba_status lordba_backward_multi(const void* x, const void* g,
                                     void* workspace, size_t workspace_bytes,
                                     int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, void* stream);
 
-/* Bytes of workspace lordba_backward needs for a shape (0 for a shape it does not support). */
+/* Bytes of workspace lordba_backward needs for a shape (0 for sizes outside its range: T < 0, a width below 1 or above
+ * 2^24, r outside 1..64). */
 size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, int64_t r);
 
 /* Size of the library-owned scratch array behind lordba_backward_noalloc (one per GPU the library runs on, held until the

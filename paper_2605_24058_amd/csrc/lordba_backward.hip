@@ -405,6 +405,72 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
     }
 }
 
+// --------------------------------------------------------------------------------------- general kernel ----
+// Q, P and everything that follows from them for any shape and alignment, on the vector ALU: one thread per column of x
+// (Q[:, i], then d_s_in[i] and d_latentA[:, i]) or of g (P[:, j], d_s_out[j], d_latentB[j, :]) walks all token rows with
+// its r sums in registers; r more threads take d_s_rank.  No partial sums, fixed order.  Slow (a column's T x r
+// multiply-adds in one thread) but it is what a shape outside the matrix-core path gets, as in the forward pass.
+template <int RP>
+__global__ __launch_bounds__(256) void lordba_bwd_general_kernel(BwdArgs a) {
+    __shared__ float beta_s[RP];
+    const int r = a.r, tid = threadIdx.x;
+    if (tid < RP) beta_s[tid] = tid < r ? static_cast<float>(a.s_rank[tid]) : 0.f;
+    __syncthreads();
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + tid;
+    const int64_t ncols = static_cast<int64_t>(a.d_in) + a.d_out;
+    if (c >= ncols + r) return;
+    if (c >= ncols) {  // d_beta_k = sum_t du[t, k] t[t, k]
+        const int k = static_cast<int>(c - ncols);
+        const float* dup = a.duT + static_cast<size_t>(k) * a.du_stride;
+        const float* tp = a.tT + static_cast<size_t>(k) * a.t_stride;
+        float s = 0.f;
+        for (int t = 0; t < a.T; ++t) s = fmaf(dup[t], tp[t], s);
+        a.d_s_rank[k] = s;
+        return;
+    }
+    const bool is_x = c < a.d_in;
+    const int col = static_cast<int>(is_x ? c : c - a.d_in);
+    const int d = is_x ? a.d_in : a.d_out;
+    const _Float16* src = (is_x ? a.x : a.g) + col;
+    const float* small = is_x ? a.duT : a.tT;   // dt = beta du meets x, u = beta t meets g
+    const int sstride = is_x ? a.du_stride : a.t_stride;
+    float acc[RP];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) acc[k] = 0.f;
+    for (int t = 0; t < a.T; ++t) {
+        const float v = static_cast<float>(src[static_cast<size_t>(t) * d]);
+#pragma unroll
+        for (int k = 0; k < RP; ++k)
+            if (k < r) acc[k] = fmaf(small[static_cast<size_t>(k) * sstride + t] * beta_s[k], v, acc[k]);
+    }
+    const uint32_t* pk = is_x ? a.pA : a.pBt;   // both [r, d] bit streams
+    const float scale = static_cast<float>(is_x ? a.s_in[col] : a.s_out[col]);
+    const bool with_lat = a.d_latA != nullptr;
+    float dscale = 0.f;
+#pragma unroll
+    for (int k = 0; k < RP; ++k) {
+        if (k < r) {
+            const int64_t n = static_cast<int64_t>(k) * d + col;
+            dscale += flip(acc[k], (pk[n >> 5] >> (n & 31)) & 1u);
+            if (with_lat) {
+                const size_t at = is_x ? static_cast<size_t>(n) : static_cast<size_t>(col) * r + k;   // latentA [r, d_in], latentB [d_out, r]
+                const float* lat = is_x ? a.latA : a.latB;
+                float* out = is_x ? a.d_latA : a.d_latB;
+                const float val = scale * acc[k] * smooth_sign_factor(lat[at], a.kappa);
+                out[at] = a.accumulate ? out[at] + val : val;
+            }
+        }
+    }
+    (is_x ? a.d_s_in : a.d_s_out)[col] = dscale;
+}
+
+template <int RP>
+lordba_status launch_general(const BwdArgs& a, hipStream_t st) {
+    const int64_t n = static_cast<int64_t>(a.d_in) + a.d_out + a.r;
+    hipLaunchKernelGGL((lordba_bwd_general_kernel<RP>), dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st, a);
+    return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
+}
+
 // ------------------------------------------------------------------------------------------ host side ----
 bool aligned_to(const void* p, size_t n) { return (reinterpret_cast<uintptr_t>(p) & (n - 1)) == 0; }
 
@@ -419,9 +485,11 @@ lordba_status launch_all(const BwdArgs& a, hipStream_t st) {
 }
 
 bool supported(int64_t T, int64_t d_in, int64_t d_out, int64_t r) {
-    return T >= 0 && d_in >= 32 && d_out >= 32 && d_in % 32 == 0 && d_out % 32 == 0 && r >= 1 && r <= LORDBA_MAX_RANK &&
-           T <= INT32_MAX - 128 && d_in <= (1 << 24) && d_out <= (1 << 24);
+    return T >= 0 && d_in >= 1 && d_out >= 1 && r >= 1 && r <= LORDBA_MAX_RANK && T <= INT32_MAX - 128 && d_in <= (1 << 24) &&
+           d_out <= (1 << 24);
 }
+// The matrix-core wgrad and the finish kernel read whole 128-column blocks and 32-column words.
+bool fast_shape(int64_t d_in, int64_t d_out) { return d_in % 32 == 0 && d_out % 32 == 0; }
 
 }  // namespace
 
@@ -453,14 +521,20 @@ lordba_status backward_impl(const void* x, const void* g,
     if (with_latents && (!latentA || !latentB || !d_latentA || !d_latentB)) return LORDBA_ERR_NULL;
     if (T > 0 && (!x || !g)) return LORDBA_ERR_NULL;
     if ((dx == nullptr) != (dx_base == nullptr)) return LORDBA_ERR_NULL;
-    // a kept t is read in whole 32-row steps: its rows must reach the padded token count
-    if (t_saved != nullptr && (t_stride < (T + 127) / 128 * 128 || t_stride % 4 != 0 || t_stride > INT32_MAX)) return LORDBA_ERR_DIM;
-    if (!aligned_to(x, 16) || !aligned_to(g, 16) || !aligned_to(s_in, 16) || !aligned_to(s_out, 16) || !aligned_to(s_rank, 2) ||
-        !aligned_to(packedA, 16) || !aligned_to(packedAt, 16) || !aligned_to(packedBt, 4) || !aligned_to(latentA, 4) ||
+    if (t_saved != nullptr && (t_stride < T || t_stride > INT32_MAX)) return LORDBA_ERR_DIM;
+    // every pointer aligned to its element; the workspace to 16 bytes (its layout is this library's)
+    if (!aligned_to(x, 2) || !aligned_to(g, 2) || !aligned_to(s_in, 2) || !aligned_to(s_out, 2) || !aligned_to(s_rank, 2) ||
+        !aligned_to(packedA, 4) || !aligned_to(packedAt, 4) || !aligned_to(packedBt, 4) || !aligned_to(latentA, 4) ||
         !aligned_to(latentB, 4) || !aligned_to(d_s_in, 4) || !aligned_to(d_s_rank, 4) || !aligned_to(d_s_out, 4) ||
-        !aligned_to(d_latentA, 4) || !aligned_to(d_latentB, 4) || !aligned_to(workspace, 16) || !aligned_to(t_saved, 16) ||
-        !aligned_to(dx_base, 16) || !aligned_to(dx, 16))
+        !aligned_to(d_latentA, 4) || !aligned_to(d_latentB, 4) || !aligned_to(workspace, 16) || !aligned_to(t_saved, 4) ||
+        !aligned_to(dx_base, 2) || !aligned_to(dx, 2))
         return LORDBA_ERR_ALIGN;
+    // The matrix-core wgrad and the finish kernel need widths that are multiples of 32, 16-byte aligned activations and
+    // carriers, and a kept t whose rows reach the padded token count (it is read in whole 32-row steps); anything else
+    // takes the general kernel.
+    const bool fast = fast_shape(d_in, d_out) && aligned_to(x, 16) && aligned_to(g, 16) && aligned_to(s_in, 16) && aligned_to(s_out, 16) &&
+                      aligned_to(packedA, 16) && aligned_to(packedAt, 16) && aligned_to(dx_base, 16) && aligned_to(dx, 16) &&
+                      (t_saved == nullptr || (aligned_to(t_saved, 16) && t_stride % 4 == 0 && t_stride >= (T + 127) / 128 * 128));
     const BwdPlan p = make_plan(T, d_in, d_out, r);
     if (workspace_bytes < p.words * 4) return LORDBA_ERR_WORKSPACE;
     {
@@ -557,11 +631,15 @@ lordba_status backward_impl(const void* x, const void* g,
         a.tw = p.tw;
         a.splits = p.splits;
         a.accumulate = e > 0 ? 1 : 0;
-        switch (p.rp / 16) {
-            case 1: s = launch_all<1>(a, st); break;
-            case 2: s = launch_all<2>(a, st); break;
-            case 3: s = launch_all<3>(a, st); break;
-            default: s = launch_all<4>(a, st); break;
+        if (!fast) {
+            s = r <= 8 ? launch_general<8>(a, st) : r <= 16 ? launch_general<16>(a, st) : r <= 32 ? launch_general<32>(a, st) : launch_general<64>(a, st);
+        } else {
+            switch (p.rp / 16) {
+                case 1: s = launch_all<1>(a, st); break;
+                case 2: s = launch_all<2>(a, st); break;
+                case 3: s = launch_all<3>(a, st); break;
+                default: s = launch_all<4>(a, st); break;
+            }
         }
         if (s != LORDBA_OK) return s;
     }

@@ -125,7 +125,8 @@ def test_backward_validation_needs_no_device(lib):
     T, d_in, d_out, r = 4, 64, 96, 8
     need = lib.lordba_backward_workspace_bytes(T, d_in, d_out, r)
     assert need > 0 and need % 4 == 0
-    assert lib.lordba_backward_workspace_bytes(T, 72, d_out, r) == 0          # widths must be multiples of 32
+    assert lib.lordba_backward_workspace_bytes(T, 72, d_out, r) > 0           # any width (the general kernel takes odd ones)
+    assert lib.lordba_backward_workspace_bytes(T, 0, d_out, r) == 0 and lib.lordba_backward_workspace_bytes(T, d_in, (1 << 24) + 1, r) == 0
     assert lib.lordba_backward_workspace_bytes(T, d_in, d_out, 0) == 0
     assert lib.lordba_backward_workspace_bytes(0, d_in, d_out, r) > 0
 
@@ -138,13 +139,13 @@ def test_backward_validation_needs_no_device(lib):
     for n in ("pA", "pAt", "pBt", "si", "sr", "so", "lA", "lB", "dsi", "dsr", "dso", "dlA", "dlB", "ws", "x", "g"):
         assert call(**{n: None}) == 1, n           # (a single latent pointer missing is an error; all four: frozen carriers)
     assert call(dx=None) == 1 and call(dxb=None) == 1                           # dx and dx_base come or go together
-    assert call(d_in=72) == 2 and call(r=65) == 2 and call(T=-1) == 2
+    assert call(d_in=0) == 2 and call(r=65) == 2 and call(T=-1) == 2
     assert call(ws_bytes=need - 4) == 9
-    assert call(x=p["x"] + 2) == 5 and call(ws=p["ws"] + 4) == 5
+    assert call(x=p["x"] + 1) == 5 and call(ws=p["ws"] + 4) == 5 and call(dsi=p["dsi"] + 2) == 5
     assert call(dsi=p["x"]) == 4 and call(dlA=p["lA"]) == 4 and call(ws=p["g"]) == 4 and call(dso=p["dsi"]) == 4   # overlaps
     assert call(dx=p["x"]) == 4
-    assert call(ts=p["ts"], t_stride=4) == 2                                    # a kept t must reach the padded token count
-    assert call(ts=p["ts"] + 4, t_stride=128) == 5
+    assert call(ts=p["ts"], t_stride=3) == 2                                    # a kept t must hold T entries per rank
+    assert call(ts=p["ts"] + 2, t_stride=128) == 5
     multi = lambda ell: lib.lordba_backward_multi(p["x"], p["g"], p["pA"], p["pAt"], p["pBt"], p["si"], p["sr"], p["so"], p["lA"], p["lB"],
                                                   ctypes.c_float(100.0), None, 0, p["dxb"], p["dx"], p["dsi"], p["dsr"], p["dso"], p["dlA"], p["dlB"],
                                                   p["ws"], need - 4, T, d_in, d_out, r, ell, None)

@@ -126,6 +126,16 @@ SHAPES = [
     (33, 512, 1024, 64),
     (130, 32, 96, 5),         # the smallest widths, a rank that is not a multiple of 8
     (519, 2048, 1536, 16),    # several 32-row steps per wave
+    # widths that are no multiples of 32: the general (vector ALU) kernel, as in the forward pass
+    (7, 100, 60, 5),
+    (9, 100, 36, 5),
+    (50, 33, 17, 3),
+    (130, 96, 40, 17),        # only d_out is odd
+    (64, 72, 64, 8),          # only d_in is odd
+    (21, 200, 136, 33),
+    (12, 80, 48, 64),
+    (1, 40, 24, 16),
+    (300, 1000, 520, 16),
 ]
 
 
@@ -254,6 +264,33 @@ def test_forward_that_keeps_t(torch_cuda, shape):
         assert np.array_equal(a[k], b[k]), k
 
 
+def test_unaligned_tensors_and_any_kept_t_take_the_general_kernel(torch_cuda):
+    """Widths that would fit the matrix-core kernels, but x starts 2 bytes past a 16-byte boundary, or the kept t has a row
+    stride of exactly T (no multiple of 4): the call is accepted (as lordba_forward accepts such tensors) and takes the
+    general kernel; same bar against the oracle."""
+    torch = torch_cuda
+    T, d_in, d_out, r = 37, 256, 384, 16
+    d = inputs.make_backward_inputs(38, T, d_in, d_out, r)
+    want = oracle_backward(d)
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    pA, pB = binding.lordba_pack_signs(d["signsA"], d["signsB"])
+    pAt, pBt = binding.lordba_pack_transposed(d["signsA"], d["signsB"])
+    w = lambda a: cu(a.view(np.int32))
+    holder = torch.zeros(T * d_in + 8, dtype=torch.float16, device="cuda:0")
+    x_off = holder[1:1 + T * d_in].view(T, d_in)
+    x_off.copy_(cu(d["x"]))
+    assert x_off.data_ptr() % 16 == 2 and x_off.is_contiguous()
+    head = (w(pA), w(pAt), w(pBt), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]), cu(d["latA"]), cu(d["latB"]), KAPPA)
+    out = binding.lordba_backward(x_off, cu(d["g"]), *head, dx_base=cu(d["dx_base"]))
+    torch.cuda.synchronize()
+    compare({k: v.cpu().numpy() for k, v in out.items()}, want, "x two bytes off a 16-byte boundary")
+    t_odd = torch.full((r, T), float("nan"), dtype=torch.float32, device="cuda:0")       # row stride 37
+    binding.lordba_forward_save_t(cu(d["x"]), w(pA), w(pB), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]), t_out=t_odd)
+    out = binding.lordba_backward(cu(d["x"]), cu(d["g"]), *head, dx_base=cu(d["dx_base"]), t_saved=t_odd)
+    torch.cuda.synchronize()
+    compare({k: v.cpu().numpy() for k, v in out.items()}, want, "kept t with row stride T")
+
+
 def test_frozen_carriers_scale_gradients_only(torch_cuda):
     """latentA = latentB = None (only the scales are trained): the scale gradients and dx are bit-identical to the full
     call's, and no latent gradient is produced."""
@@ -274,7 +311,8 @@ def test_frozen_carriers_scale_gradients_only(torch_cuda):
 
 
 @pytest.mark.parametrize("case", [(2, 203, 1056, 2080, 16), (3, 70, 1024, 768, 32), (4, 45, 512, 640, 8), (2, 4100, 256, 384, 16),
-                                  (1, 37, 512, 512, 16)], ids=lambda c: "ell%d_T%d_%dx%d_r%d" % c)
+                                  (1, 37, 512, 512, 16), (3, 21, 100, 60, 5), (4, 33, 72, 200, 16)],   # the last two: general kernel
+                         ids=lambda c: "ell%d_T%d_%dx%d_r%d" % c)
 def test_several_envelopes(torch_cuda, case):
     """lordba_backward_multi against the oracle: per-envelope scale gradients (whole vector each), dx per token row (as
     configured and the branch alone), latent gradients per rank."""
@@ -395,7 +433,8 @@ def test_argument_errors(torch_cuda):
     with pytest.raises(binding.LordbaError) as e:
         gpu_backward(torch, d, ws=new_workspace(torch, need), ws_bytes=need - 16)
     assert e.value.status == 9
-    assert binding.lordba_backward_workspace_bytes(16, 250, 256, 8) == 0      # d_in not a multiple of 32
+    assert binding.lordba_backward_workspace_bytes(16, 250, 256, 8) > 0       # any width (general kernel)
+    assert binding.lordba_backward_workspace_bytes(16, 0, 256, 8) == 0
     assert binding.lordba_backward_workspace_bytes(16, 256, 256, 65) == 0
 
 
