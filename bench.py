@@ -37,6 +37,16 @@ REPS = 7                       # repetitions of the timed region; the median one
 WORKLOADS = {}
 
 
+def _shape(name):
+    """A workload by name, or any shape written T,d_in,d_out,r (for sweeps and counter runs)."""
+    from paper_2605_24058_amd import inputs
+    parts = name.split(",")
+    if len(parts) == 4 and all(p.isdigit() for p in parts):
+        T, d_in, d_out, r = (int(p) for p in parts)
+        return inputs.Shape("shape_%dx%d_r%d_T%d" % (d_in, d_out, r, T), T, d_in, d_out, r)
+    return _workloads()[name]
+
+
 def _workloads():
     from paper_2605_24058_amd import inputs
     if not WORKLOADS:
@@ -250,7 +260,7 @@ def bench_backward(args):
     from paper_2605_24058_amd import binding, inputs, traffic_profile
     K, W = args.steps, args.warmup
     use_graph = not args.no_graph
-    sh = _workloads()[args.workload]
+    sh = _shape(args.workload)
     per_set = 2 * sh.T * (3 * sh.d_in + sh.d_out)
     sets = args.sets if args.sets > 0 else max(2, -(-2 * CACHE_BYTES // per_set) + 1)
     host0 = inputs.make_backward_inputs(args.seed, sh.T, sh.d_in, sh.d_out, sh.r)
@@ -494,7 +504,7 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="c2",
-                    help="c1, c2 (default), c3_up, c3_down, c5_q, c5_up, c5_down or a full shape name; c5_model (the 280 adapter "
+                    help="c1, c2 (default), c3_up, c3_down, c5_q, c5_up, c5_down, a full shape name, or T,d_in,d_out,r; c5_model (the 280 adapter "
                          "calls of a LLaMA-2-13B pass); c4_sweep (decode sizes, microseconds per call)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--ell", type=int, default=1, help="scale envelopes over the same carriers (1 = lordba_forward; "
@@ -557,7 +567,7 @@ def main():
     if args.backward or args.train_step:
         args.steps = min(args.steps, 600)
         return bench_backward(args)
-    sh = _workloads()[args.workload]
+    sh = _shape(args.workload)
 
     # ---- inputs: one adapter, `sets` activation sets, all resident in HBM before timing ------------------------
     per_set = sh.activation_bytes()

@@ -1020,7 +1020,8 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
             // Rows of x or of y that lie a multiple of 8 KiB apart (16 KiB or more): the rows of a tile then meet in the
             // same memory channels, and 8-row tiles on 8 waves stream them faster than 16-row tiles do (up to 14 % on
             // eighteen shapes with d_in or d_out = 8192, 16384, 20480, 28672, never slower; no such gain at 11008, 13824,
-            // 14336).
+            // 14336).  L2 counters at d_out = 8192: with 16-row tiles the requests to DRAM wait for credits 1.5 to 3 times
+            // as often and the mean read latency at the L2 is 20 % longer (6 % at d_out = 11008).
             s = launch_mfma_rb<8, 8, 1>(a, st);
         } else if (tall) {
             // With more 16-row tiles than the 256 compute units, 8-wave workgroups win: two of them share a compute
