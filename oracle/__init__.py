@@ -57,6 +57,8 @@ def _load():
         lib.lordba_oracle_forward_packed.argtypes = [vp] * 8 + [i64] * 4 + [ci]
         lib.lordba_oracle_forward_batched.restype = ci
         lib.lordba_oracle_forward_batched.argtypes = [vp] * 9 + [i64] * 5
+        lib.lordba_oracle_forward_batched_multi.restype = ci
+        lib.lordba_oracle_forward_batched_multi.argtypes = [vp] * 9 + [i64] * 6
         lib.lordba_oracle_forward_multi.restype = ci
         lib.lordba_oracle_forward_multi.argtypes = [vp] * 8 + [i64] * 5 + [ci]
         lib.lordba_oracle_rank_intermediate.restype = ci
@@ -217,6 +219,40 @@ def forward_batched(x, signsA, signsB, s_in, s_rank, s_out, adapter_of_row, y_ba
                                                _ptr(yb), _ptr(y), T, d_in, d_out, r, n)
     if st != 0:
         raise ValueError("oracle forward_batched failed with status %d" % st)
+    return y
+
+
+def forward_batched_multi(x, signsA, signsB, s_in, s_rank, s_out, adapter_of_row, y_base) -> np.ndarray:
+    """fp64 Y[t] = Y_base[t] + X[t] DeltaW(adapter adapter_of_row[t]) where every adapter of the pool has ell scale envelopes
+    over its own carriers (Def. 1 / Eq. (lordba) with l = ell per adapter); rows with an id outside [0, n) pass through.
+
+    signsA[n,r,d_in], signsB[n,d_out,r]: int8 +-1; s_in[n,ell,d_in], s_rank[n,ell,r], s_out[n,ell,d_out]: float16;
+    adapter_of_row[T]: int32."""
+    sA = _as(signsA, np.int8)
+    sB = _as(signsB, np.int8)
+    if sA.ndim != 3 or sB.ndim != 3:
+        raise ValueError("pools must be [n, r, d_in] and [n, d_out, r]")
+    n, r, d_in = sA.shape
+    d_out = sB.shape[1]
+    if sB.shape != (n, d_out, r):
+        raise ValueError("signsB must be [n, d_out, r]")
+    sr0 = np.asarray(s_rank)
+    if sr0.ndim != 3:
+        raise ValueError("s_rank must be [n, ell, r]")
+    ell = sr0.shape[1]
+    si = _f16_bits(s_in, (n, ell, d_in))
+    sr = _f16_bits(s_rank, (n, ell, r))
+    so = _f16_bits(s_out, (n, ell, d_out))
+    xb = _f16_bits(x)
+    T = xb.shape[0]
+    xb = _f16_bits(xb, (T, d_in))
+    yb = _f16_bits(y_base, (T, d_out))
+    ids = _as(adapter_of_row, np.int32, (T,))
+    y = np.empty((T, d_out), dtype=np.float64)
+    st = _load().lordba_oracle_forward_batched_multi(_ptr(xb), _ptr(sA), _ptr(sB), _ptr(si), _ptr(sr), _ptr(so), _ptr(ids),
+                                                     _ptr(yb), _ptr(y), T, d_in, d_out, r, ell, n)
+    if st != 0:
+        raise ValueError("oracle forward_batched_multi failed with status %d" % st)
     return y
 
 

@@ -387,6 +387,43 @@ done:
     return status;
 }
 
+/* The same batch when every adapter of the pool has `ell` scale envelopes over its own carriers (Def. 1 / Eq. (lordba)
+ * with envelope rank l = ell for each adapter; Sec. 3.3):
+ *   y[t] = y_base[t] + x[t] sum_e diag(alpha_{a,e}) B1_a diag(beta_{a,e}) B2_a diag(gamma_{a,e}),   a = id[t],
+ * pools s_in[n, ell, d_in], s_rank[n, ell, r], s_out[n, ell, d_out].  Plain loop over rows; each row is the
+ * multi-envelope row function with its adapter's carriers and envelopes. */
+int lordba_oracle_forward_batched_multi(const uint16_t *x, const int8_t *signsA, const int8_t *signsB,
+                                        const uint16_t *s_in, const uint16_t *s_rank, const uint16_t *s_out,
+                                        const int32_t *id, const uint16_t *y_base, double *y,
+                                        int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, int64_t n_adapters)
+{
+    if (T < 0 || d_in < 1 || d_out < 1 || r < 1 || ell < 1 || n_adapters < 0) return 2;
+    for (int64_t n = 0; n < n_adapters * r * d_in; ++n) if (signsA[n] != 1 && signsA[n] != -1) return 3;
+    for (int64_t n = 0; n < n_adapters * d_out * r; ++n) if (signsB[n] != 1 && signsB[n] != -1) return 3;
+    double *alpha = (double *)malloc(sizeof(double) * (size_t)(ell * d_in));
+    double *beta = (double *)malloc(sizeof(double) * (size_t)(ell * r));
+    double *gamma = (double *)malloc(sizeof(double) * (size_t)(ell * d_out));
+    double *w = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *u = (double *)malloc(sizeof(double) * (size_t)r);
+    int status = 0;
+    if (!alpha || !beta || !gamma || !w || !u) { status = 9; goto done; }
+    for (int64_t t = 0; t < T; ++t) {
+        const int64_t a = id[t];
+        if (a < 0 || a >= n_adapters) {
+            for (int64_t j = 0; j < d_out; ++j) y[t * d_out + j] = lordba_oracle_f16_to_f64(y_base[t * d_out + j]);
+            continue;
+        }
+        lordba_oracle_f16_array_to_f64(s_in + a * ell * d_in, alpha, ell * d_in);
+        lordba_oracle_f16_array_to_f64(s_rank + a * ell * r, beta, ell * r);
+        lordba_oracle_f16_array_to_f64(s_out + a * ell * d_out, gamma, ell * d_out);
+        forward_row_multi(x + t * d_in, signsA + a * r * d_in, signsB + a * d_out * r, alpha, beta, gamma,
+                          y_base + t * d_out, y + t * d_out, d_in, d_out, r, ell, w, u);
+    }
+done:
+    free(alpha); free(beta); free(gamma); free(w); free(u);
+    return status;
+}
+
 /* ------------------------------------------------- rank-r intermediate ---- */
 
 /* t = (X D_alpha) B1, the inner two factors of Eq. (lordba-fwd): t[row, k] = sum_i S_A[k,i] * alpha_i * x[row, i].

@@ -113,6 +113,18 @@ def make_adapter_pool(seed: int, d_in: int, d_out: int, r: int, n: int) -> Dict[
     return {k: np.stack([ad[k] for ad in ads]) for k in ("signsA", "signsB", "s_in", "s_rank", "s_out")}
 
 
+def make_adapter_pool_multi(seed: int, d_in: int, d_out: int, r: int, n: int, ell: int) -> Dict[str, np.ndarray]:
+    """The pool of make_adapter_pool when every adapter has ell scale envelopes over its carriers (make_envelopes with the
+    adapter's derived seed): signsA [n, r, d_in], signsB [n, d_out, r], s_in [n, ell, d_in], s_rank [n, ell, r],
+    s_out [n, ell, d_out].  With ell = 1 the scales are those of make_adapter_pool with a unit envelope axis."""
+    seeds = [int(np.random.SeedSequence([int(seed), 4, a]).generate_state(1)[0]) for a in range(n)]
+    ads = [make_adapter(sd, d_in, d_out, r) for sd in seeds]
+    env = [make_envelopes(sd, d_in, d_out, r, ell) for sd in seeds]
+    out = {k: np.stack([ad[k] for ad in ads]) for k in ("signsA", "signsB")}
+    out.update({k: np.stack([e[k] for e in env]) for k in ("s_in", "s_rank", "s_out")})
+    return out
+
+
 def make_adapter_ids(seed: int, T: int, n: int, pattern: str) -> np.ndarray:
     """int32[T] adapter index per token row.
     "segments": rows sorted by adapter, n contiguous segments of random lengths (prefill of n requests);
