@@ -510,7 +510,7 @@ def main():
     ap.add_argument("--ell", type=int, default=1, help="scale envelopes over the same carriers (1 = lordba_forward; "
                     "2..4 = lordba_forward_multi); single-shape workloads only")
     ap.add_argument("--adapters", type=int, default=0, help="serve the batch with a pool of this many adapters through "
-                    "lordba_forward_batched (0 = one adapter, lordba_forward); single-shape workloads, --ell 1 only")
+                    "lordba_forward_batched (0 = one adapter, lordba_forward; with --ell 2..4: lordba_forward_batched_multi); single-shape workloads")
     ap.add_argument("--id-pattern", choices=["segments", "decode", "mixed"], default="segments",
                     help="adapter index per token row: sorted segments (prefill of several requests), independent draws "
                          "(decode, one token per request) or segments with rows that have no adapter")
@@ -575,12 +575,12 @@ def main():
     sets = min(sets, max(1, int(200e9 // per_set)))
     ell = args.ell
     nad = args.adapters
-    assert not (nad and ell > 1), "--adapters goes with one envelope"
     host0 = inputs.make_inputs_for(sh, args.seed)
     if ell > 1:
         host0.update(inputs.make_envelopes(args.seed, sh.d_in, sh.d_out, sh.r, ell))
     if nad:
-        host0.update(inputs.make_adapter_pool(args.seed, sh.d_in, sh.d_out, sh.r, nad))
+        host0.update(inputs.make_adapter_pool(args.seed, sh.d_in, sh.d_out, sh.r, nad) if ell == 1 else
+                     inputs.make_adapter_pool_multi(args.seed, sh.d_in, sh.d_out, sh.r, nad, ell))
         host0["ids"] = inputs.make_adapter_ids(args.seed, sh.T, nad, args.id_pattern)
         pA, pB = binding.lordba_pack_pool(host0["signsA"], host0["signsB"])
     else:
@@ -602,8 +602,10 @@ def main():
     cur = lambda: torch.cuda.current_stream().cuda_stream
 
     if nad:
-        def fwd(x, pa, pb, si, sr, so, yb, **kw):
-            return binding.lordba_forward_batched(x, pa, pb, si, sr, so, dev["ids"], yb, **kw)
+        def fwd(x, pa, pb, si, sr, so, yb, check=False, **kw):
+            if ell > 1:
+                return binding.lordba_forward_batched_multi(x, pa, pb, si, sr, so, dev["ids"], yb, **kw)
+            return binding.lordba_forward_batched(x, pa, pb, si, sr, so, dev["ids"], yb, check=check, **kw)
     else:
         fwd = binding.lordba_forward if ell == 1 else binding.lordba_forward_multi
 
@@ -643,7 +645,7 @@ def main():
     alg_bytes = sh.algorithmic_bytes_multi(ell)
     if nad:                  # every adapter that some row uses is read once, plus the index array
         used = len(set(int(a) for a in host0["ids"] if 0 <= a < nad))
-        alg_bytes = sh.activation_bytes() + used * sh.adapter_bytes() + 4 * sh.T
+        alg_bytes = sh.activation_bytes() + used * (sh.adapter_bytes() + 2 * (ell - 1) * (sh.d_in + sh.r + sh.d_out)) + 4 * sh.T
     achieved = alg_bytes / (kern_us * 1e-6) / 1e9
     from paper_2605_24058_amd import traffic_profile
     traffic, traffic_note = traffic_profile.lookup("lordba_forward", sh.name) \
@@ -692,7 +694,8 @@ def main():
         ofwd = oracle.forward if ell == 1 else oracle.forward_multi
         if nad:              # the batched oracle is single-threaded: the thread count is ignored
             ids_h = host0["ids"][idx]
-            ofwd = lambda x, sa, sb, si, sr, so, yb, nthreads=1: oracle.forward_batched(
+            obatched = oracle.forward_batched if ell == 1 else oracle.forward_batched_multi
+            ofwd = lambda x, sa, sb, si, sr, so, yb, nthreads=1: obatched(
                 x, sa, sb, si, sr, so, ids_h[:x.shape[0]], yb)
             cores = 1
         run = lambda nt: ofwd(xh, host0["signsA"], host0["signsB"], host0["s_in"], host0["s_rank"],

@@ -161,6 +161,27 @@ lordba_status lordba_forward_batched_algo(const void* x, const uint32_t* packedA
                                           int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t n_adapters,
                                           void* stream, int algo);
 
+/* DEVICE function: lordba_forward_batched for a pool whose adapters have `ell` scale envelopes each over their own
+ * carriers (Def. 1 / Eq. (lordba) with envelope rank l = ell per adapter; Sec. 3.3: such adapters are hot-swapped and served
+ * concurrently like any other):
+ *   y_out[t] = y_base[t] + sum_{e < ell} (branch of envelope e of adapter adapter_of_row[t]) applied to x[t]
+ *   s_in_pool: fp16 [n_adapters, ell, d_in]    s_rank_pool: fp16 [n_adapters, ell, r]    s_out_pool: fp16 [n_adapters, ell, d_out]
+ * 1 <= ell <= LORDBA_MAX_ENVELOPES (else LORDBA_ERR_DIM); ell == 1 is lordba_forward_batched.  Everything else (the packed
+ * pools, the index array, pass-through rows, arithmetic as lordba_forward_multi, error bound, aliasing, stream semantics:
+ * enqueue only, no allocation, no workspace) as lordba_forward_batched. */
+lordba_status lordba_forward_batched_multi(const void* x, const uint32_t* packedA_pool, const uint32_t* packedB_pool,
+                                           const void* s_in_pool, const void* s_rank_pool, const void* s_out_pool,
+                                           const int32_t* adapter_of_row, const void* y_base, void* y_out,
+                                           int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell, int64_t n_adapters,
+                                           void* stream);
+
+/* Same with the kernel chosen by the caller: LORDBA_ALGO_AUTO, LORDBA_ALGO_GENERAL or LORDBA_ALGO_MFMA_T8. */
+lordba_status lordba_forward_batched_multi_algo(const void* x, const uint32_t* packedA_pool, const uint32_t* packedB_pool,
+                                                const void* s_in_pool, const void* s_rank_pool, const void* s_out_pool,
+                                                const int32_t* adapter_of_row, const void* y_base, void* y_out,
+                                                int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell,
+                                                int64_t n_adapters, void* stream, int algo);
+
 /* DEVICE function: binarises and packs the latent carriers on the device, as every training step does before its
  * forward pass (B1 = sign(U1), B2 = sign(U2), Sec. 3.2; Alg. QAT-LoRDBA), sign(0) = +1 (Sec. 2, Notation; -0.0 counts as
  * zero).  latentA fp32 [r, d_in], latentB fp32 [d_out, r] (device memory).  Outputs, each in the canonical packed format

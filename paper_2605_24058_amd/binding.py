@@ -135,6 +135,10 @@ def load_library():
         f = getattr(lib, name)
         f.restype = ci
         f.argtypes = [vp] * 9 + [i64] * 5 + extra
+    for name, extra in (("lordba_forward_batched_multi", [vp]), ("lordba_forward_batched_multi_algo", [vp, ci])):
+        f = getattr(lib, name)
+        f.restype = ci
+        f.argtypes = [vp] * 9 + [i64] * 6 + extra
     lib.lordba_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.lordba_backward_workspace_bytes.argtypes = [i64] * 4
     lib.lordba_backward.restype = ci
@@ -347,6 +351,45 @@ def lordba_forward_batched(x, packedA_pool, packedB_pool, s_in_pool, s_rank_pool
     st = lib.lordba_forward_batched(*args) if int(algo) == ALGO_AUTO else lib.lordba_forward_batched_algo(*args, int(algo))
     if st != 0:
         raise LordbaError(st, "lordba_forward_batched")
+    return y_out
+
+
+def lordba_forward_batched_multi(x, packedA_pool, packedB_pool, s_in_pool, s_rank_pool, s_out_pool, adapter_of_row, y_base,
+                                 y_out=None, stream=None, algo: int = ALGO_AUTO):
+    """lordba_forward_batched for a pool whose adapters have ell scale envelopes each: s_in_pool [n, ell, d_in],
+    s_rank_pool [n, ell, r], s_out_pool [n, ell, d_out] (float16 CUDA tensors); everything else as lordba_forward_batched."""
+    import torch
+
+    lib = load_library()
+    for name, t_ in (("x", x), ("s_in_pool", s_in_pool), ("s_rank_pool", s_rank_pool), ("s_out_pool", s_out_pool), ("y_base", y_base)):
+        if t_.dtype != torch.float16 or not t_.is_cuda or not t_.is_contiguous():
+            raise TypeError("%s must be a contiguous float16 CUDA tensor" % name)
+    for name, t_ in (("packedA_pool", packedA_pool), ("packedB_pool", packedB_pool), ("adapter_of_row", adapter_of_row)):
+        if t_.dtype != torch.int32 or not t_.is_cuda or not t_.is_contiguous():
+            raise TypeError("%s must be a contiguous int32 CUDA tensor" % name)
+    if x.dim() != 2 or y_base.dim() != 2 or x.shape[0] != y_base.shape[0] or adapter_of_row.numel() != x.shape[0]:
+        raise ValueError("x must be [T, d_in], y_base [T, d_out], adapter_of_row [T]")
+    if s_rank_pool.dim() != 3:
+        raise ValueError("scale pools must be [n, ell, .]")
+    T, d_in = x.shape
+    d_out = y_base.shape[1]
+    n, ell, r = s_rank_pool.shape
+    if tuple(s_in_pool.shape) != (n, ell, d_in) or tuple(s_out_pool.shape) != (n, ell, d_out):
+        raise ValueError("scale pool shapes do not match")
+    if tuple(packedA_pool.shape) != (n, (r * d_in + 31) // 32) or tuple(packedB_pool.shape) != (n, (d_out * r + 31) // 32):
+        raise ValueError("packed pool shapes do not match")
+    if y_out is None:
+        y_out = torch.empty_like(y_base)
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    args = (x.data_ptr(), packedA_pool.data_ptr(), packedB_pool.data_ptr(), s_in_pool.data_ptr(), s_rank_pool.data_ptr(),
+            s_out_pool.data_ptr(), adapter_of_row.data_ptr(), y_base.data_ptr(), y_out.data_ptr(), T, d_in, d_out, r, ell, n,
+            ctypes.c_void_p(stream))
+    st = lib.lordba_forward_batched_multi(*args) if int(algo) == ALGO_AUTO else lib.lordba_forward_batched_multi_algo(*args, int(algo))
+    if st != 0:
+        raise LordbaError(st, "lordba_forward_batched_multi")
     return y_out
 
 

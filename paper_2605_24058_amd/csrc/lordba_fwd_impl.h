@@ -72,9 +72,9 @@ __device__ __forceinline__ FwdArgs select_adapter(const FwdArgs& a, int id) {
     FwdArgs b = a;
     b.pA += static_cast<int64_t>(id) * ((static_cast<int64_t>(a.r) * a.d_in + 31) >> 5);
     b.pB += static_cast<int64_t>(id) * ((static_cast<int64_t>(a.d_out) * a.r + 31) >> 5);
-    b.s_in += static_cast<int64_t>(id) * a.d_in;
-    b.s_rank += static_cast<int64_t>(id) * a.r;
-    b.s_out += static_cast<int64_t>(id) * a.d_out;
+    b.s_in += static_cast<int64_t>(id) * a.ell * a.d_in;   // each adapter of the pool has its ell rows of scales
+    b.s_rank += static_cast<int64_t>(id) * a.ell * a.r;
+    b.s_out += static_cast<int64_t>(id) * a.ell * a.d_out;
     return b;
 }
 
@@ -127,7 +127,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // waves with two.  The multi-adapter batch on 8 waves holds three (two of its workgroups share a compute unit, so a
     // lane has 128 registers).  Four envelopes on 16-row tiles (grids of at least 256 tiles, two workgroups per compute
     // unit) hold one.
-    constexpr int D2 = (TMV == 16 && L == 4) ? 1 : (GM == 4 && NW == 8 && RB == 1) ? 3 : (NW == 8 && TMV == 8 && ((L >= 3 && RB == 1) || (L == 3 && RB == 2))) ? 4 : 2;
+    constexpr int D2 = (TMV == 16 && L == 4) ? 1 : (GM == 4 && NW == 8 && RB == 1 && L == 1) ? 3 : (NW == 8 && TMV == 8 && GM != 4 && ((L >= 3 && RB == 1) || (L == 3 && RB == 2))) ? 4 : 2;
     constexpr bool R16 = BM == 1, R8 = BM == 2;
     static_assert(!R8 || RB == 1, "r = 8 is one rank block");
     // Four envelopes on 16-row tiles: to stay inside the registers, no sign operands are built ahead and the row scalings
@@ -542,6 +542,9 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
             constexpr int EH = (D2 > 2 || (TMV == 16 && L >= 3)) ? 4 : 8;   // columns per pass: half a set at a time where more blocks are in flight
 #pragma unroll
             for (int vs = 0; vs < VS; ++vs) {
+                // With three or four rank blocks the compiler would keep the 8 RB sign operands of the first set in
+                // registers for the next one (same LDS addresses) and spill; this makes it read them again.
+                if constexpr (RB >= 3) asm volatile("" ::: "memory");
 #pragma unroll
                 for (int e0 = 0; e0 < 8; e0 += EH) {
                     f4 v[EH];
@@ -606,10 +609,10 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
 }
 
 // The second launch bound is the number of waves per SIMD the registers must leave room for: what the workgroup size
-// implies, except in the multi-adapter batch on 8 waves (one rank block, or two with whole-word carrier rows), where two
-// workgroups have to share a compute unit.
+// implies, except in the multi-adapter batch on 8 waves (one envelope; one rank block, or two with whole-word carrier rows),
+// where two workgroups have to share a compute unit.
 template <int RB, int TMV, int NW, int D1, bool OS, int BM, int GM, int L, bool TR>
-__global__ __launch_bounds__(NW * 64, (GM == 4 && NW == 8 && (RB == 1 || (RB == 2 && BM == 1))) ? 4 : NW / 4) void lordba_fwd_mfma_kernel(FwdArgs a) {
+__global__ __launch_bounds__(NW * 64, (GM == 4 && NW == 8 && L == 1 && (RB == 1 || (RB == 2 && BM == 1))) ? 4 : NW / 4) void lordba_fwd_mfma_kernel(FwdArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     if constexpr (GM != 4) {
         const int64_t t0 = static_cast<int64_t>(blockIdx.x) * TMV;
@@ -847,7 +850,9 @@ lordba_status launch_mfma(const FwdArgs& a, hipStream_t stream) {
     const int64_t tiles = (static_cast<int64_t>(a.T) + TMV - 1) / TMV;
     if (a.ids != nullptr) {
         // (two rank blocks on 16 waves would spill a few registers in the batch mode's second copy of the tile code: 8 waves)
-        if constexpr (TMV == 8 && L == 1 && D1 <= 4 && (NW == 8 || (NW == 16 && RB == 1))) {
+        // Pools of adapters with several envelopes run the 8-wave variants (one workgroup per compute unit) up to r = 32 (r = 16 with four envelopes); beyond
+        // that the registers do not hold the batch mode's two copies of the tile code, and the general kernel runs.
+        if constexpr (TMV == 8 && D1 <= 4 && ((L == 1 && (NW == 8 || (NW == 16 && RB == 1))) || (L > 1 && NW == 8 && (RB == 1 || (RB == 2 && L <= 3))))) {
             return launch_mfma_gm<RB, TMV, NW, D1, OS, BM, 4, L>(a, stream);
         }
         return LORDBA_ERR_ALGO;
