@@ -273,7 +273,7 @@ def bench_backward(args):
     for s_ in range(sets):
         h = host0 if s_ == 0 else inputs.make_backward_inputs(args.seed + 1000 * s_, sh.T, sh.d_in, sh.d_out, sh.r)
         xs.append(cu(h["x"])); gs.append(cu(h["g"])); dxbs.append(cu(h["dx_base"])); dxs.append(torch.empty_like(dxbs[-1]))
-    ws = torch.empty(binding.lordba_backward_workspace_bytes(sh.T, sh.d_in, sh.d_out, sh.r), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(binding.lordba_backward_multi_workspace_bytes(sh.T, sh.d_in, sh.d_out, sh.r, args.ell), dtype=torch.uint8, device="cuda")
     kept = [None] * sets
     if args.keep_t:   # the rank-r intermediate of each set, kept by the training forward (outside the timed region)
         _, pB = binding.lordba_pack_signs(host0["signsA"], host0["signsB"])

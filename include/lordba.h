@@ -264,7 +264,10 @@ lordba_status lordba_backward(const void* x, const void* g,
  * d_s_in fp32 [ell, d_in], d_s_rank fp32 [ell, r], d_s_out fp32 [ell, d_out]: every envelope has its own scale
  * gradients; dx and the latent gradients are the sums over the envelopes (dx with one rounding).  1 <= ell <=
  * LORDBA_MAX_ENVELOPES.  t_saved: what lordba_forward_multi_save_t wrote ([ell, r, t_stride]), or NULL (recomputed: one
- * more pass over x).  Workspace: lordba_backward_workspace_bytes, whatever ell is.  Everything else as lordba_backward. */
+ * more pass over x).  Workspace: lordba_backward_workspace_bytes is enough whatever ell is (the activations are then
+ * contracted once per envelope); with lordba_backward_multi_workspace_bytes(..., ell) bytes, and at most four rank blocks of
+ * 16 in all envelopes together (ell * ceil(r / 16) <= 4), one pass over x and g serves every envelope (the carriers are
+ * shared, only the rank-r operand differs; same results up to the order of fp32 sums).  Everything else as lordba_backward. */
 lordba_status lordba_backward_multi(const void* x, const void* g,
                                     const uint32_t* packedA, const uint32_t* packedAt, const uint32_t* packedBt,
                                     const void* s_in, const void* s_rank, const void* s_out,
@@ -279,6 +282,10 @@ lordba_status lordba_backward_multi(const void* x, const void* g,
 /* Bytes of workspace lordba_backward needs for a shape (0 for sizes outside its range: T < 0, a width below 1 or above
  * 2^24, r outside 1..64). */
 size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, int64_t r);
+
+/* Bytes of workspace with which lordba_backward_multi reads x and g once for all `ell` envelopes (never less than
+ * lordba_backward_workspace_bytes; equal to it where the one-pass form does not apply; 0 for sizes out of range). */
+size_t lordba_backward_multi_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell);
 
 /* Size of the library-owned scratch array behind lordba_backward_noalloc (one per GPU the library runs on, held until the
  * process ends). */

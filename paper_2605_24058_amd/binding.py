@@ -141,6 +141,8 @@ def load_library():
         f.argtypes = [vp] * 9 + [i64] * 6 + extra
     lib.lordba_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.lordba_backward_workspace_bytes.argtypes = [i64] * 4
+    lib.lordba_backward_multi_workspace_bytes.restype = ctypes.c_size_t
+    lib.lordba_backward_multi_workspace_bytes.argtypes = [i64] * 5
     lib.lordba_backward.restype = ci
     lib.lordba_backward.argtypes = [vp] * 10 + [ctypes.c_float, vp, i64] + [vp] * 8 + [ctypes.c_size_t] + [i64] * 4 + [vp]
     lib.lordba_backward_noalloc.restype = ci
@@ -397,6 +399,10 @@ def lordba_backward_workspace_bytes(T: int, d_in: int, d_out: int, r: int) -> in
     return int(load_library().lordba_backward_workspace_bytes(T, d_in, d_out, r))
 
 
+def lordba_backward_multi_workspace_bytes(T: int, d_in: int, d_out: int, r: int, ell: int) -> int:
+    return int(load_library().lordba_backward_multi_workspace_bytes(T, d_in, d_out, r, ell))
+
+
 def lordba_pack_transposed(signsA, signsB) -> Tuple[np.ndarray, np.ndarray]:
     """The two extra packed carriers lordba_backward takes: S_A^T as [d_in, r] and S_B^T as [r, d_out], packed by the
     library's host packer in the canonical format.  Returns (packedAt, packedBt)."""
@@ -586,7 +592,7 @@ def lordba_backward_multi(x, g, packedA, packedAt, packedBt, s_in, s_rank, s_out
     ell, r = s_rank.shape
     if tuple(s_in.shape) != (ell, d_in) or tuple(s_out.shape) != (ell, d_out):
         raise ValueError("scale arrays must be [ell, d_in], [ell, r], [ell, d_out]")
-    need = lordba_backward_workspace_bytes(T, d_in, d_out, r)
+    need = lordba_backward_multi_workspace_bytes(T, d_in, d_out, r, ell)   # room for the one-pass form where it applies
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
     if dx_base is not None and dx is None:

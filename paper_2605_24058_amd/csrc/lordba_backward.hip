@@ -34,7 +34,7 @@
 
 namespace {
 
-constexpr int kWgradWaves = 4;        // waves per workgroup of the wgrad kernel, each with its own token range
+constexpr int kWgradWaves = 4;        // waves per workgroup of the wgrad kernel, each with its own token range (8 on short batches)
 // Workgroups the wgrad grid aims at: two per CU once the token ranges are long (measured 3-4 % faster from T = 4096 on),
 // one per CU below that, where a second one only doubles the partial sums the finish kernel has to read.
 constexpr int kWgradTargetWgsLong = 512, kWgradTargetWgsShort = 256;
@@ -47,11 +47,13 @@ struct BwdPlan {
     int dcols;       // columns of one partial-sum plane: (nbx + nbg) * 128
     int tw;          // token rows per wave of the wgrad kernel (multiple of 128)
     int splits;      // workgroups along the token axis of the wgrad kernel
+    int waves;       // waves per workgroup of the wgrad kernel: 4, or 8 on short batches (see make_plan)
     // workspace layout, in 4-byte words
     size_t off_t, off_du, off_dbeta, off_part, words;
 };
 
-BwdPlan make_plan(int64_t T, int64_t d_in, int64_t d_out, int64_t r) {
+// ell_fused: envelopes whose partial sums the wgrad kernel holds at once (1: one envelope per wgrad / finish pass).
+BwdPlan make_plan(int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell_fused = 1) {
     BwdPlan p;
     p.rp = static_cast<int>((r + 15) / 16 * 16);
     p.t_pad = static_cast<int>((T + 127) / 128 * 128);
@@ -59,22 +61,27 @@ BwdPlan make_plan(int64_t T, int64_t d_in, int64_t d_out, int64_t r) {
     p.nbx = static_cast<int>((d_in + 127) / 128);
     p.nbg = static_cast<int>((d_out + 127) / 128);
     p.dcols = (p.nbx + p.nbg) * 128;
-    const int groups = p.t_pad / (32 * kWgradGroup);  // a wave takes whole groups of steps
+    // Below 4096 token rows a wave of a 4-wave workgroup would have a single group of four steps and nothing to overlap
+    // with: such batches run 8 waves (two per SIMD, each with groups of two steps), up to two rank blocks (registers).
+    const bool short_batch = T < 4096 && p.rp * ell_fused <= 32;
+    p.waves = short_batch ? 2 * kWgradWaves : kWgradWaves;
+    const int group_rows = 32 * (short_batch ? kWgradGroup / 2 : kWgradGroup);
+    const int groups = p.t_pad / group_rows;  // a wave takes whole groups of steps (t_pad is a multiple of 128)
     const int target = T >= 4096 ? kWgradTargetWgsLong : kWgradTargetWgsShort;
-    int splits = (target + p.nbx + p.nbg - 1) / (p.nbx + p.nbg);
-    const int max_splits = (groups + kWgradWaves - 1) / kWgradWaves;  // at least one group per wave
+    int splits = target / (p.nbx + p.nbg);   // rounded down: a grid just above the target would start another round
+    const int max_splits = (groups + p.waves - 1) / p.waves;  // at least one group per wave
     splits = splits > max_splits ? max_splits : splits;
     splits = splits < 1 ? 1 : splits;
-    const int groups_per_wave = (groups + splits * kWgradWaves - 1) / (splits * kWgradWaves);
-    p.tw = groups_per_wave * 32 * kWgradGroup;
-    p.splits = (groups + groups_per_wave * kWgradWaves - 1) / (groups_per_wave * kWgradWaves);
+    const int groups_per_wave = (groups + splits * p.waves - 1) / (splits * p.waves);
+    p.tw = groups_per_wave * group_rows;
+    p.splits = (groups + groups_per_wave * p.waves - 1) / (groups_per_wave * p.waves);
     // t and du: one [r, t_pad] block per envelope, room for the largest envelope count
     p.off_t = 0;
     p.off_du = p.off_t + static_cast<size_t>(LORDBA_MAX_ENVELOPES) * p.rp * p.t_pad;
     p.off_dbeta = p.off_du + static_cast<size_t>(LORDBA_MAX_ENVELOPES) * p.rp * p.t_pad;
-    p.off_part = p.off_dbeta + static_cast<size_t>(p.splits) * p.rp;
+    p.off_part = p.off_dbeta + static_cast<size_t>(p.splits) * p.rp * ell_fused;
     p.off_part = (p.off_part + 3) & ~static_cast<size_t>(3);
-    p.words = p.off_part + static_cast<size_t>(p.splits) * p.rp * p.dcols;
+    p.words = p.off_part + static_cast<size_t>(p.splits) * p.rp * ell_fused * p.dcols;
     return p;
 }
 
@@ -96,11 +103,15 @@ struct BwdArgs {
     float* d_latB;
     const float* tT;       // t,  rank-major: tT[k * t_stride + token], defined for k < r, token < T
     const float* duT;      // du, rank-major: duT[k * du_stride + token]
-    float* dbeta_part;     // [splits, rp]
-    float* part;           // [splits, rp, dcols]
+    float* dbeta_part;     // [splits, ell, rp]
+    float* part;           // [splits, ell, rp, dcols]
     int T, d_in, d_out, r;
-    int rp, t_pad, t_stride, du_stride, nbx, nbg, dcols, tw, splits;
-    int accumulate;        // latent gradients are added to what the arrays hold (second and later envelopes)
+    int rp, t_pad, t_stride, du_stride, nbx, nbg, dcols, tw, splits, waves;
+    int accumulate;        // latent gradients are added to what the arrays hold (second and later envelopes, one pass each)
+    // Envelopes held at once (Eq. (lordba): the carriers are shared, so Q and P of all envelopes contract the same x and g
+    // with different small operands).  s_in, s_rank, s_out and the scale gradients then have ell rows, tT and duT one
+    // [r, stride] block per envelope, and the wgrad kernel's rank blocks are the ell * rp / 16 blocks of all envelopes.
+    int ell;
 };
 
 __global__ void bwd_zero_kernel(float* p, int64_t n) {
@@ -109,56 +120,23 @@ __global__ void bwd_zero_kernel(float* p, int64_t n) {
 }
 
 // ----------------------------------------------------------------------------------------- wgrad kernel ----
-// Workgroup (cb, s): column block cb of x (cb < nbx: Q, with dt) or of g (P, with u), token rows [s * 4 tw, (s+1) * 4 tw),
-// a quarter per wave; cb == nbx + nbg: the share of d_beta of those token rows.  One step = 32 token rows x 128 columns.
+// Workgroup (cb, s): column block cb of x (cb < nbx: Q, with dt) or of g (P, with u), token rows [s * W tw, (s+1) * W tw),
+// one range of tw rows per wave; the workgroups with cb == 0 also take the share of d_beta of those token rows.  One step = 32 token rows x 128 columns.
 // G steps are in flight per wave: the loads of a group are issued without any condition (past the end of the wave's range
 // they re-read valid addresses and are not used), so that every wait counts exactly the loads issued after the one it
 // needs; the last group is consumed without issuing anything.
-template <int RB, int G>
-__global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdArgs a) {
-    __shared__ __align__(16) float red[kWgradWaves][8][64][4];
+template <int RB, int G, int W>
+__global__ __launch_bounds__(W * 64) void lordba_bwd_wgrad_kernel(BwdArgs a) {
+    static_assert(W == 4 || W == 8, "the final sums are dealt to 4 or 8 waves");
+    __shared__ __align__(16) float red[W][8][64][4];
     // The wave index as a scalar: everything that depends on it (how many steps) then branches on scalar conditions.
     // MFMA instructions ignore the EXEC mask, so they must never sit under a vector-predicated branch.
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, q = lane >> 4;
     const int cb = blockIdx.x;
-    const int tk_begin = (static_cast<int>(blockIdx.y) * kWgradWaves + wave) * a.tw;
+    const int tk_begin = (static_cast<int>(blockIdx.y) * W + wave) * a.tw;
     int tk_end = tk_begin + a.tw;
     tk_end = tk_end < a.t_pad ? tk_end : a.t_pad;
-
-    if (cb == a.nbx + a.nbg) {
-        // d_beta_k = sum_t du[t,k] t[t,k] over this workgroup's token rows: lane (li, q) takes rank li of each block and
-        // the tokens 8 q .. 8 q + 7 of every step; fixed order (lane, then lane groups, then waves)
-        float* sums = &red[0][0][0][0];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            const int rk = rb * 16 + li;
-            float s = 0.f;
-            const int row = rk < a.r ? rk : a.r - 1;  // a rank that exists; the result of a padded rank is dropped below
-            const float* dup = a.duT + static_cast<size_t>(row) * a.du_stride + 8 * q;
-            const float* tp = a.tT + static_cast<size_t>(row) * a.t_stride + 8 * q;
-            for (int tk = tk_begin; tk < tk_end; tk += 32) {  // 32 bytes of each array per lane and step, inside t_pad entries
-                const u4 d0 = load16(dup + tk), d1 = load16(dup + tk + 4), t0 = load16(tp + tk), t1 = load16(tp + tk + 4);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float dv = __uint_as_float(e < 4 ? d0[e & 3] : d1[e & 3]), tv = __uint_as_float(e < 4 ? t0[e & 3] : t1[e & 3]);
-                    s += (tk + 8 * q + e < a.T) ? dv * tv : 0.f;   // select: entries past T are undefined
-                }
-            }
-            if (rk >= a.r) s = 0.f;
-            s += __shfl_xor(s, 16, 64);
-            s += __shfl_xor(s, 32, 64);
-            if (q == 0) sums[(rb * 16 + li) * kWgradWaves + wave] = s;
-        }
-        __syncthreads();
-        if (tid < a.rp) {
-            float tot = 0.f;
-#pragma unroll
-            for (int w = 0; w < kWgradWaves; ++w) tot += sums[tid * kWgradWaves + w];
-            a.dbeta_part[static_cast<size_t>(blockIdx.y) * a.rp + tid] = tot;
-        }
-        return;
-    }
 
     const bool is_x = cb < a.nbx;
     const int cc = is_x ? cb : cb - a.nbx;
@@ -167,12 +145,13 @@ __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdA
     const float* small = is_x ? a.duT : a.tT;   // dt = beta du meets x, u = beta t meets g
     const int sstride = is_x ? a.du_stride : a.t_stride;
 
+    const int rbe = a.rp >> 4;  // rank blocks per envelope
     float beta[RB];
-    int row_of[RB];  // the lane's rank, clamped to a rank that exists (its values are then masked)
+    int row_of[RB];  // the lane's row in the small arrays: envelope * r + rank, clamped to a rank that exists (its values are then masked)
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int rk = rb * 16 + li;
-        row_of[rb] = rk < a.r ? rk : a.r - 1;
+    for (int rb = 0; rb < RB; ++rb) {   // block rb: envelope rb / (rp / 16), ranks 16 (rb % (rp / 16)) ..
+        const int en = rb / rbe, rk = (rb - en * rbe) * 16 + li;
+        row_of[rb] = en * a.r + (rk < a.r ? rk : a.r - 1);
         beta[rb] = rk < a.r ? static_cast<float>(a.s_rank[row_of[rb]]) : 0.f;
     }
     int col = cc * 128 + li * 8;
@@ -299,9 +278,12 @@ __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdA
     }
 
     // Accumulator e, register i of lane (li, q): rank rb*16 + li, column 8 (4q + i) + e of the block.  Each wave brings its
-    // tile back to true scale; the four tiles are summed in wave order; wave w sums register i = w and so ends up with 8
-    // consecutive columns.
-    float* out = a.part + static_cast<size_t>(blockIdx.y) * a.rp * a.dcols + static_cast<size_t>(cb) * 128;
+    // tile back to true scale; the tiles are summed in wave order; with 4 waves wave w sums register i = w of all 8
+    // accumulators and so ends up with 8 consecutive columns, with 8 waves it sums register i = w mod 4 of accumulators
+    // 4 (w / 4) .. 4 (w / 4) + 3: 4 consecutive columns.
+    float* out = a.part + static_cast<size_t>(blockIdx.y) * (RB * 16) * a.dcols + static_cast<size_t>(cb) * 128;
+    constexpr int NE = W == 4 ? 8 : 4;
+    const int ri = wave & 3, e0 = W == 4 ? 0 : 4 * (wave >> 2);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         if (rb > 0) __syncthreads();
@@ -309,17 +291,53 @@ __global__ __launch_bounds__(kWgradWaves * 64) void lordba_bwd_wgrad_kernel(BwdA
 #pragma unroll
         for (int e = 0; e < 8; ++e) *reinterpret_cast<f4*>(&red[wave][e][lane][0]) = acc[rb][e] * inv;
         __syncthreads();
-        float sum[8];
+        float sum[NE];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float s = red[0][e][lane][wave];
+        for (int e = 0; e < NE; ++e) {
+            float s = red[0][e0 + e][lane][ri];
 #pragma unroll
-            for (int w = 1; w < kWgradWaves; ++w) s += red[w][e][lane][wave];
+            for (int w = 1; w < W; ++w) s += red[w][e0 + e][lane][ri];
             sum[e] = s;
         }
-        float* dst = out + static_cast<size_t>(rb * 16 + li) * a.dcols + 8 * (4 * q + wave);
+        float* dst = out + static_cast<size_t>(rb * 16 + li) * a.dcols + 8 * (4 * q + ri) + e0;
         *reinterpret_cast<f4*>(dst) = f4{sum[0], sum[1], sum[2], sum[3]};
-        *reinterpret_cast<f4*>(dst + 4) = f4{sum[4], sum[5], sum[6], sum[7]};
+        if constexpr (NE == 8) *reinterpret_cast<f4*>(dst + 4) = f4{sum[4], sum[5], sum[6], sum[7]};
+    }
+    if (cb != 0) return;
+    // The workgroups of the first column block also take the share of d_beta_k = sum_t du[t,k] t[t,k] of their token rows
+    // (a column of workgroups of its own would push the grid past one workgroup per compute unit, i.e. into a second
+    // round): lane (li, q) takes rank li of each block and the tokens 8 q .. 8 q + 7 of every step; fixed order (lane, then
+    // lane groups, then waves).
+    __syncthreads();  // the sums below reuse the reduction area
+    {
+        float* sums = &red[0][0][0][0];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int en = rb / rbe, rk = (rb - en * rbe) * 16 + li;
+            float s = 0.f;
+            const int row = en * a.r + (rk < a.r ? rk : a.r - 1);  // a rank that exists; the result of a padded rank is dropped below
+            const float* dup = a.duT + static_cast<size_t>(row) * a.du_stride + 8 * q;
+            const float* tp = a.tT + static_cast<size_t>(row) * a.t_stride + 8 * q;
+            for (int tk = tk_begin; tk < tk_end; tk += 32) {  // 32 bytes of each array per lane and step, inside t_pad entries
+                const u4 d0 = load16(dup + tk), d1 = load16(dup + tk + 4), t0 = load16(tp + tk), t1 = load16(tp + tk + 4);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float dv = __uint_as_float(e < 4 ? d0[e & 3] : d1[e & 3]), tv = __uint_as_float(e < 4 ? t0[e & 3] : t1[e & 3]);
+                    s += (tk + 8 * q + e < a.T) ? dv * tv : 0.f;   // select: entries past T are undefined
+                }
+            }
+            if (rk >= a.r) s = 0.f;
+            s += __shfl_xor(s, 16, 64);
+            s += __shfl_xor(s, 32, 64);
+            if (q == 0) sums[(rb * 16 + li) * W + wave] = s;
+        }
+        __syncthreads();
+        if (tid < RB * 16) {
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < W; ++w) tot += sums[tid * W + w];
+            a.dbeta_part[static_cast<size_t>(blockIdx.y) * (RB * 16) + tid] = tot;
+        }
     }
 }
 
@@ -334,15 +352,17 @@ __device__ __forceinline__ float smooth_sign_factor(float latent, float kappa) {
 // One workgroup per group of 32 columns of d_in (Q, d_s_in, d_latentA) or of d_out (P, d_s_out, d_latentB), plus one for
 // d_s_rank.  Thread (c, kq) takes column c of the group and ranks kq, kq + 8, ...; every sum has a fixed order.
 __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
-    __shared__ float sh[256];
+    __shared__ float sh[LORDBA_MAX_ENVELOPES][256];
     __shared__ float lat[32 * LORDBA_MAX_RANK];
     const int gx = a.d_in >> 5, gg = a.d_out >> 5;
     const int tid = threadIdx.x;
+    const int r = a.r, ell = a.ell, rows = ell * a.rp;   // rows of one token range's plane of partial sums: all envelopes' rank blocks
     if (static_cast<int>(blockIdx.x) == gx + gg) {
-        if (tid < a.r) {  // d_beta: the shares of the token ranges, in their order
+        for (int o = tid; o < ell * r; o += 256) {  // d_beta of every envelope: the shares of the token ranges, in their order
+            const int en = o / r, k = o - en * r;
             float tot = 0.f;
-            for (int sp = 0; sp < a.splits; ++sp) tot += a.dbeta_part[static_cast<size_t>(sp) * a.rp + tid];
-            a.d_s_rank[tid] = tot;
+            for (int sp = 0; sp < a.splits; ++sp) tot += a.dbeta_part[static_cast<size_t>(sp) * rows + en * a.rp + k];
+            a.d_s_rank[en * r + k] = tot;
         }
         return;
     }
@@ -353,13 +373,17 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
     const int col = grp * 32 + c;
     const float* plane = a.part + (is_x ? col : a.nbx * 128 + col);
     const uint32_t* pk = is_x ? a.pA : a.pBt;   // both [r, d]: the group's 32 bits of rank k are one word
-    const float scale = static_cast<float>(is_x ? a.s_in[col] : a.s_out[col]);
-    const int r = a.r;
+    float scale[LORDBA_MAX_ENVELOPES], dscale[LORDBA_MAX_ENVELOPES];
+#pragma unroll
+    for (int en = 0; en < LORDBA_MAX_ENVELOPES; ++en) {
+        const int ec = en < ell ? en : 0;
+        scale[en] = static_cast<float>(is_x ? a.s_in[static_cast<size_t>(ec) * d + col] : a.s_out[static_cast<size_t>(ec) * d + col]);
+        dscale[en] = 0.f;
+    }
     if (!is_x && a.d_latB != nullptr) {  // latentB [d_out, r]: the group's 32 rows are 32 r contiguous floats; through LDS for coalesced accesses
         for (int e = tid; e < 32 * r; e += 256) lat[e] = a.latB[static_cast<size_t>(grp) * 32 * r + e];
         __syncthreads();
     }
-    float dscale = 0.f;
     const bool with_lat = a.d_latA != nullptr;   // (null: the carriers are frozen, only the scale gradients are wanted)
     const bool lat_x = with_lat && is_x, add_x = lat_x && a.accumulate;
     for (int k = kq; k < r; k += 8) {
@@ -370,38 +394,46 @@ __global__ __launch_bounds__(256) void lordba_bwd_finish_kernel(BwdArgs a) {
         const uint32_t word = pk[k * (d >> 5) + grp];
         const float latent = *(lat_x ? a.latA + n : plane);
         const float so_far = *(add_x ? a.d_latA + n : plane);
-        float s = 0.f;
-        for (int sp0 = 0; sp0 < a.splits; sp0 += 8) {
-            float v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int sp = sp0 + j < a.splits ? sp0 + j : a.splits - 1;
-                v[j] = plane[(static_cast<size_t>(sp) * a.rp + k) * a.dcols];
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) s += (sp0 + j < a.splits) ? v[j] : 0.f;
-        }
         const uint32_t bit = (word >> c) & 1u;
-        dscale += flip(s, bit);
+        float weighted = 0.f;   // sum over the envelopes of scale_e * (Q_e or P_e)[k, col]: dL/dS[k, col]
+#pragma unroll
+        for (int en = 0; en < LORDBA_MAX_ENVELOPES; ++en) {
+            if (en < ell) {
+                float s = 0.f;
+                for (int sp0 = 0; sp0 < a.splits; sp0 += 8) {
+                    float v[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int sp = sp0 + j < a.splits ? sp0 + j : a.splits - 1;
+                        v[j] = plane[(static_cast<size_t>(sp) * rows + en * a.rp + k) * a.dcols];
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) s += (sp0 + j < a.splits) ? v[j] : 0.f;
+                }
+                dscale[en] += flip(s, bit);
+                weighted = ell == 1 ? scale[0] * s : fmaf(scale[en], s, weighted);
+            }
+        }
         if (lat_x) {
-            const float val = scale * s * smooth_sign_factor(latent, a.kappa);
+            const float val = weighted * smooth_sign_factor(latent, a.kappa);
             a.d_latA[n] = add_x ? so_far + val : val;
         } else if (with_lat) {
-            lat[c * r + k] = scale * s * smooth_sign_factor(lat[c * r + k], a.kappa);
+            lat[c * r + k] = weighted * smooth_sign_factor(lat[c * r + k], a.kappa);
         }
     }
-    sh[tid] = dscale;
+#pragma unroll
+    for (int en = 0; en < LORDBA_MAX_ENVELOPES; ++en) sh[en][tid] = dscale[en];
     __syncthreads();
     if (!is_x && a.d_latB != nullptr)
         for (int e = tid; e < 32 * r; e += 256) {
             float* dst = a.d_latB + static_cast<size_t>(grp) * 32 * r + e;
             *dst = a.accumulate ? *dst + lat[e] : lat[e];
         }
-    if (kq == 0) {
+    if (kq < ell) {   // wave pair kq sums envelope kq's eight partial sums of every column
         float tot = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) tot += sh[j * 32 + c];
-        (is_x ? a.d_s_in : a.d_s_out)[col] = tot;
+        for (int j = 0; j < 8; ++j) tot += sh[kq][j * 32 + c];
+        (is_x ? a.d_s_in : a.d_s_out)[static_cast<size_t>(kq) * d + col] = tot;
     }
 }
 
@@ -476,9 +508,16 @@ bool aligned_to(const void* p, size_t n) { return (reinterpret_cast<uintptr_t>(p
 
 template <int RB>
 lordba_status launch_all(const BwdArgs& a, hipStream_t st) {
-    // kWgradGroup steps in flight where the registers allow two waves per SIMD or nearly so, else half of it
-    hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, (RB <= 2 ? kWgradGroup : kWgradGroup / 2)>), dim3(a.nbx + a.nbg + 1, a.splits),
-                       dim3(kWgradWaves * 64), 0, st, a);
+    // kWgradGroup steps in flight where the registers allow it, else half of it; short batches: 8 waves with half of it
+    const dim3 grid(a.nbx + a.nbg, a.splits);
+    if constexpr (RB <= 2) {
+        if (a.waves == 2 * kWgradWaves)
+            hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, kWgradGroup / 2, 2 * kWgradWaves>), grid, dim3(2 * kWgradWaves * 64), 0, st, a);
+        else
+            hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, kWgradGroup, kWgradWaves>), grid, dim3(kWgradWaves * 64), 0, st, a);
+    } else {
+        hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, kWgradGroup / 2, kWgradWaves>), grid, dim3(kWgradWaves * 64), 0, st, a);
+    }
     if (hipGetLastError() != hipSuccess) return LORDBA_ERR_LAUNCH;
     hipLaunchKernelGGL(lordba_bwd_finish_kernel, dim3((a.d_in >> 5) + (a.d_out >> 5) + 1), dim3(256), 0, st, a);
     return hipGetLastError() == hipSuccess ? LORDBA_OK : LORDBA_ERR_LAUNCH;
@@ -496,6 +535,12 @@ bool fast_shape(int64_t d_in, int64_t d_out) { return d_in % 32 == 0 && d_out % 
 extern "C" size_t lordba_backward_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, int64_t r) {
     if (!supported(T, d_in, d_out, r)) return 0;
     return make_plan(T, d_in, d_out, r).words * 4;
+}
+
+extern "C" size_t lordba_backward_multi_workspace_bytes(int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell) {
+    if (!supported(T, d_in, d_out, r) || ell < 1 || ell > LORDBA_MAX_ENVELOPES) return 0;
+    const bool one_pass = ell > 1 && fast_shape(d_in, d_out) && ell * ((r + 15) / 16) <= 4;
+    return make_plan(T, d_in, d_out, r, one_pass ? ell : 1).words * 4;
 }
 
 namespace {
@@ -535,7 +580,12 @@ lordba_status backward_impl(const void* x, const void* g,
     const bool fast = fast_shape(d_in, d_out) && aligned_to(x, 16) && aligned_to(g, 16) && aligned_to(s_in, 16) && aligned_to(s_out, 16) &&
                       aligned_to(packedA, 16) && aligned_to(packedAt, 16) && aligned_to(dx_base, 16) && aligned_to(dx, 16) &&
                       (t_saved == nullptr || (aligned_to(t_saved, 16) && t_stride % 4 == 0 && t_stride >= (T + 127) / 128 * 128));
-    const BwdPlan p = make_plan(T, d_in, d_out, r);
+    // Several envelopes: with room for the partial sums of all of them (lordba_backward_multi_workspace_bytes) and at most
+    // four rank blocks in all, one wgrad and one finish pass serve every envelope (x and g are read once); otherwise one
+    // pass per envelope.
+    const int64_t rbe = (r + 15) / 16;
+    const bool fused = fast && ell > 1 && ell * rbe <= 4 && workspace_bytes >= make_plan(T, d_in, d_out, r, ell).words * 4;
+    const BwdPlan p = make_plan(T, d_in, d_out, r, fused ? ell : 1);
     if (workspace_bytes < p.words * 4) return LORDBA_ERR_WORKSPACE;
     {
         // No output (and not the workspace) may overlap an input or another output; dx on top of dx_base is the one
@@ -593,7 +643,7 @@ lordba_status backward_impl(const void* x, const void* g,
                                         stream);
         if (s != LORDBA_OK) return s;
     }
-    for (int64_t e = 0; e < ell; ++e) {
+    for (int64_t e = 0; e < (fused ? 1 : ell); ++e) {
         const float* tT = t_saved ? t_saved + e * r * t_stride : t_own + e * r * p.t_pad;
         const int64_t tT_stride = t_saved ? t_stride : p.t_pad;
 
@@ -630,11 +680,13 @@ lordba_status backward_impl(const void* x, const void* g,
         a.dcols = p.dcols;
         a.tw = p.tw;
         a.splits = p.splits;
+        a.waves = p.waves;
         a.accumulate = e > 0 ? 1 : 0;
+        a.ell = fused ? static_cast<int>(ell) : 1;
         if (!fast) {
             s = r <= 8 ? launch_general<8>(a, st) : r <= 16 ? launch_general<16>(a, st) : r <= 32 ? launch_general<32>(a, st) : launch_general<64>(a, st);
         } else {
-            switch (p.rp / 16) {
+            switch (a.ell * (p.rp / 16)) {   // rank blocks held at once
                 case 1: s = launch_all<1>(a, st); break;
                 case 2: s = launch_all<2>(a, st); break;
                 case 3: s = launch_all<3>(a, st); break;

@@ -291,6 +291,51 @@ def test_unaligned_tensors_and_any_kept_t_take_the_general_kernel(torch_cuda):
     compare({k: v.cpu().numpy() for k, v in out.items()}, want, "kept t with row stride T")
 
 
+@pytest.mark.parametrize("case", [(2, 203, 1056, 2080, 16), (4, 45, 512, 640, 8), (3, 70, 1024, 768, 16), (2, 4100, 256, 384, 32),
+                                  (4, 37, 512, 512, 16), (4, 4133, 512, 256, 16), (3, 70, 1024, 768, 32)],
+                         ids=lambda c: "ell%d_T%d_%dx%d_r%d" % c)
+def test_several_envelopes_in_one_pass(torch_cuda, case):
+    """lordba_backward_multi with the workspace of lordba_backward_multi_workspace_bytes: one wgrad and one finish pass hold
+    the partial sums of all envelopes (up to four rank blocks in all; the last case has six and goes envelope by envelope
+    whatever the workspace).  Every output against the oracle, and against the envelope-by-envelope result of the same
+    library (same sums in another order: 1e-5), with recomputed and with kept t."""
+    torch = torch_cuda
+    ell, T, d_in, d_out, r = case
+    d = inputs.make_backward_inputs(39, T, d_in, d_out, r)
+    d.update(inputs.make_envelopes(39, d_in, d_out, r, ell))
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    pA, pB = binding.lordba_pack_signs(d["signsA"], d["signsB"])
+    pAt, pBt = binding.lordba_pack_transposed(d["signsA"], d["signsB"])
+    w = lambda a: cu(a.view(np.int32))
+    small, big = binding.lordba_backward_workspace_bytes(T, d_in, d_out, r), binding.lordba_backward_multi_workspace_bytes(T, d_in, d_out, r, ell)
+    one_pass = ell * ((r + 15) // 16) <= 4
+    assert big >= small and (big > small) == one_pass
+    head = (cu(d["x"]), cu(d["g"]), w(pA), w(pAt), w(pBt), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]), cu(d["latA"]), cu(d["latB"]), KAPPA)
+    want = oracle.backward_multi(d["x"], d["g"], d["signsA"], d["signsB"], d["s_in"], d["s_rank"], d["s_out"], d["latA"], d["latB"],
+                                 KAPPA, d["dx_base"])
+    _, t_kept = binding.lordba_forward_multi_save_t(cu(d["x"]), w(pA), w(pB), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]))
+    results = {}
+    for tag, nbytes, t_saved in (("by_envelope", small, None), ("one_pass", big, None), ("one_pass_kept_t", big, t_kept)):
+        ws = new_workspace(torch, nbytes)
+        out = binding.lordba_backward_multi(*head, dx_base=cu(d["dx_base"]), workspace=ws[:nbytes], t_saved=t_saved)
+        torch.cuda.synchronize()
+        assert (ws[nbytes:].cpu().numpy() == 0xFF).all(), "write past the workspace (%s)" % tag
+        got = {k: v.cpu().numpy() for k, v in out.items()}
+        results[tag] = got
+        e = oracle.row_rel_l2(got["dx"].astype(np.float64), want["dx"])
+        assert e.max() <= TOL, "%s dx: %.3e" % (tag, e.max())
+        for k in ("d_s_in", "d_s_rank", "d_s_out"):
+            for en in range(ell):
+                assert oracle.rel_l2(got[k][en], want[k][en]) <= TOL, (tag, k, en)
+        assert oracle.row_rel_l2(got["d_latentA"].astype(np.float64), want["d_latA"]).max() <= TOL, tag
+        assert oracle.row_rel_l2(got["d_latentB"].astype(np.float64).T, want["d_latB"].T).max() <= TOL, tag
+    for k in ("d_s_in", "d_s_rank", "d_s_out", "d_latentA", "d_latentB"):
+        a, b = results["by_envelope"][k].astype(np.float64), results["one_pass"][k].astype(np.float64)
+        assert np.linalg.norm(a - b) <= 1e-5 * np.linalg.norm(a), k
+        assert np.array_equal(results["one_pass"][k], results["one_pass_kept_t"][k]), k   # a kept t is the recomputed one, bit for bit
+    assert np.array_equal(results["by_envelope"]["dx"], results["one_pass"]["dx"])
+
+
 def test_frozen_carriers_scale_gradients_only(torch_cuda):
     """latentA = latentB = None (only the scales are trained): the scale gradients and dx are bit-identical to the full
     call's, and no latent gradient is produced."""
@@ -348,7 +393,8 @@ def test_several_envelopes(torch_cuda, case):
     y, t_kept = binding.lordba_forward_multi_save_t(cu(d["x"]), w(pA), w(pB), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]),
                                                     cu(d["y_base"]), t_out=t_buf)
     kept = binding.lordba_backward_multi(cu(d["x"]), cu(d["g"]), w(pA), w(pAt), w(pBt), cu(d["s_in"]), cu(d["s_rank"]), cu(d["s_out"]),
-                                         cu(d["latA"]), cu(d["latB"]), KAPPA, dx_base=cu(np.zeros_like(d["dx_base"])), t_saved=t_kept)
+                                         cu(d["latA"]), cu(d["latB"]), KAPPA, dx_base=cu(np.zeros_like(d["dx_base"])), t_saved=t_kept,
+                                         workspace=ws[:ws.numel() - GUARD])   # (the same envelope-by-envelope mode as above)
     torch.cuda.synchronize()
     ywant = oracle.forward_multi(d["x"], d["signsA"], d["signsB"], d["s_in"], d["s_rank"], d["s_out"], d["y_base"])
     assert oracle.row_rel_l2(y.cpu().numpy().astype(np.float64), ywant).max() <= TOL

@@ -110,10 +110,11 @@ def test_allocates_nothing_and_reuses_outputs(torch_cuda):
     for k in KEYS:
         out[k].fill_(float("nan"))
     torch.cuda.synchronize()
-    before = (torch.cuda.memory_allocated(), torch.cuda.memory_stats()["allocation.all.allocated"])
+    # the allocator's running count of allocations (bytes in use may fall meanwhile: tensors of earlier tests being collected)
+    before = torch.cuda.memory_stats()["allocation.all.allocated"]
     again = binding.lordba_backward_noalloc(*head, dx_base=a["dx_base"], out=out)
     torch.cuda.synchronize()
-    assert (torch.cuda.memory_allocated(), torch.cuda.memory_stats()["allocation.all.allocated"]) == before
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
     for k in KEYS:
         assert again[k] is out[k] and torch.equal(out[k], first[k]), k
 
