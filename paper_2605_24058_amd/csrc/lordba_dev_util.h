@@ -76,6 +76,18 @@ __device__ __forceinline__ u4 flip_by_bits(u4 v, uint32_t both) {
 // fp16).  Deliberately not inline assembly: the compiler reuses dead accumulator registers of an MFMA that is still in
 // flight, and it inserts the wait states such a write needs only for instructions it can see.
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+// The four lane groups of 16 (lanes 16 g .. 16 g + 15) each hold four dwords v[0..3]; afterwards group g holds in v[n] what
+// group n held in v[g] (a 4 x 4 transpose between the groups, lane by lane).  Two rounds of the row swaps of gfx950:
+// v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its second, v_permlane16_swap lanes
+// 16..31 and 48..63 of the first with lanes 0..15 and 32..47 of the second.
+__device__ __forceinline__ void transpose_lane_groups(u4& v) {
+    const auto a = __builtin_amdgcn_permlane32_swap(v[0], v[2], false, false);
+    const auto b = __builtin_amdgcn_permlane32_swap(v[1], v[3], false, false);
+    const auto c = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
+    const auto d = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
+    v = u4{c[0], c[1], d[0], d[1]};
+}
+
 __device__ __forceinline__ h2 as_h2(uint32_t v) { return __builtin_bit_cast(h2, v); }
 
 }  // namespace

@@ -170,14 +170,24 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // -> 256 contiguous bytes per row and quarter-wave.  s_in: the chunk's 256 bytes, one dword per lane.  Carrier
     // bits: lane (rank li, dword q of the chunk) holds the 32 bits of its rank for columns 32q..32q+31 of the chunk;
     // byte s of that dword belongs to MFMA step s.
-    const int my_n = wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0;
+    // When a few workgroups run alone on their compute units (grid modes 2 and 3), what a workgroup spends on issuing its
+    // loads is latency of the call: there a wave owns CONSECUTIVE chunks, so that the carrier bits of its chunks are 16
+    // contiguous bytes per rank and slot group; one 16-byte load per lane (lane group q fetches the four words of the wave's
+    // q-th chunk) and a transpose between the lane groups replace four gathering dword loads, each of which has the
+    // memory pipeline look up 16 cache lines for 256 bytes.
+    constexpr bool CA = OS && (GM == 2 || GM == 3);
     const int words_per_row = d_in >> 5;  // d_in % 32 == 0 on this path
+    const int per_wave = (nchunks + NW - 1) / NW;  // (<= D1 where OS)
+    const int my_n = CA ? (nchunks - wave * per_wave < 0 ? 0 : (nchunks - wave * per_wave < per_wave ? nchunks - wave * per_wave : per_wave))
+                        : (wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0);
+    // (16-byte loads need whole chunks and rows that start on 16-byte boundaries)
+    const bool wide_a = CA && (d_in & 127) == 0 && (reinterpret_cast<uintptr_t>(a.pA) & 15) == 0;
     u4 xbuf[D1][NI];
     uint32_t sinbuf[D1][L];
     uint32_t abits[D1][RB];
 
     auto issue_x = [&](int slot, int n) {
-        int c = wave + NW * n;
+        int c = CA ? wave * per_wave + n : wave + NW * n;
         c = c < nchunks ? c : nchunks - 1;  // past the end: re-read a valid chunk, the result is not used
         // 16 waves leave 128 registers per lane.  In the looped pipeline the compiler would keep every lane's row and rank
         // offsets in registers across the loop (the chunk index is scalar, so they are loop invariants) and spill; hiding
@@ -210,15 +220,34 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
                 xbuf[slot][m] = load16_stream(at(xt, static_cast<uint32_t>(row * d_in + col) * 2u));
             }
         }
+        if (!wide_a) {
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            int rk = rb * 16 + li;
-            rk = rk < r ? rk : r - 1;
-            int w = c * 4 + q;
-            w = w < words_per_row ? w : words_per_row - 1;  // columns past d_in meet s_in = 0
-            abits[slot][rb] = *static_cast<const uint32_t*>(at(a.pA, static_cast<uint32_t>(rk * words_per_row + w) * 4u));
+            for (int rb = 0; rb < RB; ++rb) {
+                int rk = rb * 16 + li;
+                rk = rk < r ? rk : r - 1;
+                int w = c * 4 + q;
+                w = w < words_per_row ? w : words_per_row - 1;  // columns past d_in meet s_in = 0
+                abits[slot][rb] = *static_cast<const uint32_t*>(at(a.pA, static_cast<uint32_t>(rk * words_per_row + w) * 4u));
+            }
         }
     };
+    constexpr int AG = CA ? (D1 + 3) / 4 : 1;  // groups of four chunk slots
+    u4 awide[AG][CA ? RB : 1];
+    if constexpr (CA) {
+        if (wide_a) {  // needed first, so requested first
+#pragma unroll
+            for (int g = 0; g < AG; ++g) {
+                int c = wave * per_wave + g * 4 + q;
+                c = c < nchunks ? c : nchunks - 1;
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    int rk = rb * 16 + li;
+                    rk = rk < r ? rk : r - 1;
+                    awide[g][rb] = load16(at(a.pA, static_cast<uint32_t>(rk * words_per_row + c * 4) * 4u));
+                }
+            }
+        }
+    }
 #pragma unroll
     for (int slot = 0; slot < D1; ++slot) issue_x(slot, slot);
     __builtin_amdgcn_sched_barrier(0);  // keep the issue order: nothing below may be hoisted above these requests
@@ -321,6 +350,20 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
         __builtin_amdgcn_wave_barrier();
     };
 
+    if constexpr (CA) {
+        if (wide_a) {  // lane group q now gets word q of every slot's chunk
+#pragma unroll
+            for (int g = 0; g < AG; ++g) {
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    transpose_lane_groups(awide[g][rb]);
+#pragma unroll
+                    for (int n = 0; n < 4; ++n)
+                        if (g * 4 + n < D1) abits[g * 4 + n][rb] = awide[g][rb][n];
+                }
+            }
+        }
+    }
     if (OS) {
 #pragma unroll
         for (int slot = 0; slot < D1; ++slot)
