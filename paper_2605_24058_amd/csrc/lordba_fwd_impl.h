@@ -170,12 +170,13 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // -> 256 contiguous bytes per row and quarter-wave.  s_in: the chunk's 256 bytes, one dword per lane.  Carrier
     // bits: lane (rank li, dword q of the chunk) holds the 32 bits of its rank for columns 32q..32q+31 of the chunk;
     // byte s of that dword belongs to MFMA step s.
-    // When a few workgroups run alone on their compute units (grid modes 2 and 3), what a workgroup spends on issuing its
-    // loads is latency of the call: there a wave owns CONSECUTIVE chunks, so that the carrier bits of its chunks are 16
-    // contiguous bytes per rank and slot group; one 16-byte load per lane (lane group q fetches the four words of the wave's
-    // q-th chunk) and a transpose between the lane groups replace four gathering dword loads, each of which has the
-    // memory pipeline look up 16 cache lines for 256 bytes.
-    constexpr bool CA = OS && (GM == 2 || GM == 3);
+    // One-shot variants (every chunk of a wave in flight at once): a wave owns CONSECUTIVE chunks, so that the carrier bits
+    // of its chunks are 16 contiguous bytes per rank and group of four slots; one 16-byte load per lane (lane group q
+    // fetches the four words of the wave's q-th chunk) and a transpose between the lane groups replace four gathering
+    // dword loads, each of which has the memory pipeline look up 16 cache lines for 256 bytes.  At decode sizes, where a
+    // few workgroups run alone and the time to issue the loads is latency of the call, that is 2.4 us of 9.6 at r = 64;
+    // grids that fill the chip gain 1 to 5 %.  (The multi-adapter batch keeps the round-robin deal: 128 registers.)
+    constexpr bool CA = OS && GM != 4;
     const int words_per_row = d_in >> 5;  // d_in % 32 == 0 on this path
     const int per_wave = (nchunks + NW - 1) / NW;  // (<= D1 where OS)
     const int my_n = CA ? (nchunks - wave * per_wave < 0 ? 0 : (nchunks - wave * per_wave < per_wave ? nchunks - wave * per_wave : per_wave))
