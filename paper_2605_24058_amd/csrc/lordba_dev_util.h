@@ -76,6 +76,23 @@ __device__ __forceinline__ u4 flip_by_bits(u4 v, uint32_t both) {
 // fp16).  Deliberately not inline assembly: the compiler reuses dead accumulator registers of an MFMA that is still in
 // flight, and it inserts the wait states such a write needs only for instructions it can see.
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+// Raw buffer access (stride 0) to `bytes` bytes behind p, with the range check of the buffer instructions: a load whose
+// offset is not below `bytes` returns zeros and a store there is dropped, without a memory request.  An access that is to
+// be left out is given the offset kBufferSkip instead of being put under a branch: the number of outstanding vector
+// memory operations at any point of the code then does not depend on the data, and the compiler's wait counts can be exact
+// (bytes <= 2^30 here).
+constexpr uint32_t kBufferSkip = 0x80000000u;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_over(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, static_cast<int>(bytes), 0x00020000);
+}
+__device__ __forceinline__ u4 buffer_load16_stream(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off) {
+    return __builtin_bit_cast(u4, __builtin_amdgcn_raw_buffer_load_b128(rs, static_cast<int>(byte_off), 0, 2));  // 2: nontemporal
+}
+__device__ __forceinline__ void buffer_store16_stream(__amdgpu_buffer_rsrc_t rs, uint32_t byte_off, u4 v) {
+    typedef unsigned raw4 __attribute__((vector_size(16)));
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(raw4, v), rs, static_cast<int>(byte_off), 0, 2);
+}
+
 // The four lane groups of 16 (lanes 16 g .. 16 g + 15) each hold four dwords v[0..3]; afterwards group g holds in v[n] what
 // group n held in v[g] (a 4 x 4 transpose between the groups, lane by lane).  Two rounds of the row swaps of gfx950:
 // v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its second, v_permlane16_swap lanes

@@ -164,6 +164,11 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     const _Float16* xt = a.x + t0 * d_in;
     const _Float16* ybt = a.y_base + t0 * d_out;
     _Float16* yot = a.y_out + t0 * d_out;
+    // Multi-adapter batch: y_base and y_out of the tile as buffers of rows 0..last; rows of stage 3 that are not live get an
+    // offset outside instead of a branch around the access (the runs of a tile make most accesses partial there).
+    constexpr bool BUFY = GM == 4 || (L == 1 && (GM == 0 || GM == 1) && TMV == 8 && NW == 8);
+    const uint32_t ytile_bytes = static_cast<uint32_t>(last + 1) * static_cast<uint32_t>(d_out) * 2u;
+    const __amdgpu_buffer_rsrc_t yb_rs = buffer_over(ybt, BUFY ? ytile_bytes : 0u), yo_rs = buffer_over(yot, BUFY ? ytile_bytes : 0u);
 
     // ---------------------------------------------------------------- stage 1 loads -----------------
     // Chunk c = 128 columns of d_in; wave w owns chunks w, w + NW, ...  x: lane (row q + 4m, 16-byte column group li)
@@ -281,6 +286,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
 
     auto issue_y = [&](int slot, int n) {
         int b = b_first + wave + NW * n;
+        const bool mine = wave + NW * n < nblk;  // (past the wave's share: with buffer accesses the rows of y_base are not requested)
         b = b < nblk_all ? b : nblk_all - 1;  // past the end: re-read a valid block, the result is not used
         int j0 = b * 128 + li * 8;
         j0 = j0 < d_out ? j0 : d_out - 8;
@@ -300,7 +306,9 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
             const bool live = row >= first && row <= last;
             row = row < last ? row : last;
             row = row > first ? row : first;
-            if (MASK) {
+            if (BUFY) {
+                ybuf[slot][i] = buffer_load16_stream(yb_rs, (mine && (!MASK || live)) ? static_cast<uint32_t>(row * d_out + j0) * 2u : kBufferSkip);
+            } else if (MASK) {
                 ybuf[slot][i] = u4{0u, 0u, 0u, 0u};
                 if (live) ybuf[slot][i] = load16_stream(at(ybt, static_cast<uint32_t>(row * d_out + j0) * 2u));
             } else {
@@ -515,11 +523,23 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // ---------------------------------------------------------------- stage 3: expand + epilogue ----
     // MFMA e of a block produces column 8 li + e of the block for lane group li, so after the 8 MFMAs a lane holds 8
     // consecutive columns of its token rows.
-    auto consume_y = [&](int slot, int n, bool use_pre) {
+    auto store_y = [&](int row, int j0, bool j_ok, u4 out) {
+        const bool wanted = j_ok && row >= first && row <= last;
+        const uint32_t off = static_cast<uint32_t>(row * d_out + j0) * 2u;
+        if (BUFY) buffer_store16_stream(yo_rs, wanted ? off : kBufferSkip, out);
+        else if (wanted) store16_stream(at(yot, off), out);
+    };
+    // (`run` false, only with buffer accesses: nothing is computed or stored, but the same vector memory instructions are issued)
+    auto consume_y = [&](int slot, int n, bool use_pre, bool run) {
         const int b = b_first + wave + NW * n;
         const int j0 = b * 128 + li * 8;
         const bool j_ok = j0 < d_out;
         const int jc = j_ok ? j0 : d_out - 8;
+        if (!run) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i) store_y(0, 0, false, u4{0u, 0u, 0u, 0u});
+            return;
+        }
         // Table offsets of all 8 * RB sign operands first (for a general r these are global loads: one wait for all).
         uint32_t off[8][RB];
         if (!(PRE && use_pre)) {
@@ -561,12 +581,18 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
                 for (int d = 0; d < 4; ++d) {
                     const h2 b = as_h2(ybuf[slot][i][d]);
                     const h2 so = as_h2(sobuf[slot][0][d]);
+                    // y_out = fp16(fp32 fma): the fp32 result is made opaque so that every variant rounds twice (to fp32, then
+                    // to fp16); left alone, the compiler fuses some of these pairs into one instruction that rounds once.
+                    float f0 = __builtin_fmaf(v[2 * d][i] * inv[i][0], static_cast<float>(so[0]), static_cast<float>(b[0]));
+                    float f1 = __builtin_fmaf(v[2 * d + 1][i] * inv[i][0], static_cast<float>(so[1]), static_cast<float>(b[1]));
+                    asm("" : "+v"(f0));
+                    asm("" : "+v"(f1));
                     h2 o;
-                    o[0] = static_cast<_Float16>(__builtin_fmaf(v[2 * d][i] * inv[i][0], static_cast<float>(so[0]), static_cast<float>(b[0])));
-                    o[1] = static_cast<_Float16>(__builtin_fmaf(v[2 * d + 1][i] * inv[i][0], static_cast<float>(so[1]), static_cast<float>(b[1])));
+                    o[0] = static_cast<_Float16>(f0);
+                    o[1] = static_cast<_Float16>(f1);
                     out[d] = __builtin_bit_cast(uint32_t, o);
                 }
-                if (j_ok && row >= first && row <= last) store16_stream(at(yot, static_cast<uint32_t>(row * d_out + j0) * 2u), out);
+                store_y(row, j0, j_ok, out);
             }
         } else {
             // Several envelopes: the accumulator sets are run one after the other into the same registers, and each set is
@@ -627,26 +653,42 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
                     h2 oh;
+                    asm("" : "+v"(o[i][2 * d]));      // (round to fp32, then to fp16, in every variant: see the one-envelope epilogue)
+                    asm("" : "+v"(o[i][2 * d + 1]));
                     oh[0] = static_cast<_Float16>(o[i][2 * d]);
                     oh[1] = static_cast<_Float16>(o[i][2 * d + 1]);
                     out[d] = __builtin_bit_cast(uint32_t, oh);
                 }
-                if (j_ok && row >= first && row <= last) store16_stream(at(yot, static_cast<uint32_t>(row * d_out + j0) * 2u), out);
+                store_y(row, j0, j_ok, out);
             }
         }
     };
 
-    if (my_b > 0) {
-        consume_y(0, 0, true);
-        if (D2 < my_b) issue_y(0, D2);
-    }
-    for (int n0 = 0; n0 < my_b; n0 += D2) {
+    if (my_b > 0) consume_y(0, 0, true, true);
+    // 8-row tiles on 8 waves with more blocks than the waves hold in flight: every pass of the loop issues the same vector
+    // memory instructions whatever the wave's number of blocks is (what is not wanted is skipped by its offset), so that
+    // the wait for a slot's y_base leaves the later requests and the stores in flight; with requests under branches the
+    // compiler has to wait for all of them.
+    constexpr bool kSteadyLoop = BUFY && GM != 4;
+    if (kSteadyLoop && nblk > NW * D2) {
+        for (int n0 = 0; n0 < my_b; n0 += D2) {
 #pragma unroll
-        for (int slot = 0; slot < D2; ++slot) {
-            const int n = n0 + slot;
-            if (n == 0) continue;
-            if (n < my_b) consume_y(slot, n, false);
-            if (n + D2 < my_b) issue_y(slot, n + D2);
+            for (int slot = 0; slot < D2; ++slot) {
+                const int n = n0 + slot;
+                consume_y(slot, n, false, n != 0 && n < my_b);
+                issue_y(slot, n + D2);
+            }
+        }
+    } else {
+        if (my_b > D2) issue_y(0, D2);
+        for (int n0 = 0; n0 < my_b; n0 += D2) {
+#pragma unroll
+            for (int slot = 0; slot < D2; ++slot) {
+                const int n = n0 + slot;
+                if (n == 0) continue;
+                if (n < my_b) consume_y(slot, n, false, true);
+                if (n + D2 < my_b) issue_y(slot, n + D2);
+            }
         }
     }
     export_t();
@@ -1077,7 +1119,12 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
             // unit, and one streams its y rows while the other is in its sign stages (0.5 to 9 % on nine shapes with
             // 384 to 1024 tiles).  With one tile per compute unit the 16 waves hide more latency.
             const bool two_per_cu = algo == LORDBA_ALGO_AUTO && (T + 15) / 16 > 256;
-            s = rb == 1 && !two_per_cu ? launch_mfma_rb<16, 16, 1>(a, st) : launch_mfma_rb<16, 8, 1>(a, st);
+            // One 16-row tile per compute unit and at least three output blocks per wave of the 16: the call is mostly stage
+            // 3, and 8-row tiles on 8 waves, two workgroups per compute unit that overlap each other's stages, stream it
+            // faster (4096 -> 11008: 41.8 against 42.7 us, 4096 -> 6144: 24.6 against 24.9, 5120 -> 13824: 51.2 against 51.7;
+            // at 4096 -> 5120 the 16-row tiles still win, 19.4 against 21.2).
+            if (algo == LORDBA_ALGO_AUTO && rb == 1 && !two_per_cu && d_out >= 6144) s = launch_mfma_rb<8, 8, 1>(a, st);
+            else s = rb == 1 && !two_per_cu ? launch_mfma_rb<16, 16, 1>(a, st) : launch_mfma_rb<16, 8, 1>(a, st);
         } else if (batched && (T + 7) / 8 > 32) {
             s = launch_mfma_rb<8, 8, 1>(a, st);  // two workgroups per CU: see the batch mode of the kernel
         } else {
