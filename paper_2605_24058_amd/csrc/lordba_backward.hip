@@ -38,11 +38,16 @@ constexpr int kWgradWaves = 4;        // waves per workgroup of the wgrad kernel
 // Workgroups the wgrad grid aims at: two per CU once the token ranges are long (measured 3-4 % faster from T = 4096 on),
 // one per CU below that, where a second one only doubles the partial sums the finish kernel has to read.
 constexpr int kWgradTargetWgsLong = 512, kWgradTargetWgsShort = 256;
-constexpr int kWgradGroup = 4;        // 32-row steps a wave of the wgrad kernel keeps in flight (2 from three rank blocks on)
+// 32-row steps a wave of the wgrad kernel keeps in flight: one (two from three rank blocks on).  Deeper requests per wave
+// were slower wherever they were tried (four steps against one: 4 to 5 % of the whole call at T = 8192, 1 to 6 % below 4096);
+// a kernel that only reads the same column stripes shows the same (5120 columns, 8192 rows, 240 workgroups: 4.4 TB/s with
+// four steps in flight per wave, 5.9 with one or two): a wave that requests 128 rows at a time spreads its requests over
+// more DRAM pages than one that walks 32 rows at a time.
+constexpr int kWgradGroup = 1, kWgradGroupWide = 2;
 
 struct BwdPlan {
     int rp;          // ranks padded to a multiple of 16
-    int t_pad;       // token rows padded to a multiple of 128 (a group of the wgrad kernel)
+    int t_pad;       // token rows padded to a multiple of 128 (whole groups of steps of the wgrad kernel, whole 16-byte pieces of t and du)
     int nbx, nbg;    // 128-column blocks of d_in and of d_out
     int dcols;       // columns of one partial-sum plane: (nbx + nbg) * 128
     int tw;          // token rows per wave of the wgrad kernel (multiple of 128)
@@ -61,11 +66,12 @@ BwdPlan make_plan(int64_t T, int64_t d_in, int64_t d_out, int64_t r, int64_t ell
     p.nbx = static_cast<int>((d_in + 127) / 128);
     p.nbg = static_cast<int>((d_out + 127) / 128);
     p.dcols = (p.nbx + p.nbg) * 128;
-    // Below 4096 token rows a wave of a 4-wave workgroup would have a single group of four steps and nothing to overlap
-    // with: such batches run 8 waves (two per SIMD, each with groups of two steps), up to two rank blocks (registers).
-    const bool short_batch = T < 4096 && p.rp * ell_fused <= 32;
+    // Below 4096 token rows a wave of a 4-wave workgroup would have little to overlap with: such batches run 8 waves (two
+    // per SIMD), up to two rank blocks (registers).
+    const bool narrow = p.rp * ell_fused <= 32;
+    const bool short_batch = T < 4096 && narrow;
     p.waves = short_batch ? 2 * kWgradWaves : kWgradWaves;
-    const int group_rows = 32 * (short_batch ? kWgradGroup / 2 : kWgradGroup);
+    const int group_rows = 32 * (narrow ? kWgradGroup : kWgradGroupWide);
     const int groups = p.t_pad / group_rows;  // a wave takes whole groups of steps (t_pad is a multiple of 128)
     const int target = T >= 4096 ? kWgradTargetWgsLong : kWgradTargetWgsShort;
     int splits = target / (p.nbx + p.nbg);   // rounded down: a grid just above the target would start another round
@@ -508,15 +514,15 @@ bool aligned_to(const void* p, size_t n) { return (reinterpret_cast<uintptr_t>(p
 
 template <int RB>
 lordba_status launch_all(const BwdArgs& a, hipStream_t st) {
-    // kWgradGroup steps in flight where the registers allow it, else half of it; short batches: 8 waves with half of it
+    // (steps in flight and waves as make_plan laid the token ranges out)
     const dim3 grid(a.nbx + a.nbg, a.splits);
     if constexpr (RB <= 2) {
         if (a.waves == 2 * kWgradWaves)
-            hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, kWgradGroup / 2, 2 * kWgradWaves>), grid, dim3(2 * kWgradWaves * 64), 0, st, a);
+            hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, kWgradGroup, 2 * kWgradWaves>), grid, dim3(2 * kWgradWaves * 64), 0, st, a);
         else
             hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, kWgradGroup, kWgradWaves>), grid, dim3(kWgradWaves * 64), 0, st, a);
     } else {
-        hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, kWgradGroup / 2, kWgradWaves>), grid, dim3(kWgradWaves * 64), 0, st, a);
+        hipLaunchKernelGGL((lordba_bwd_wgrad_kernel<RB, kWgradGroupWide, kWgradWaves>), grid, dim3(kWgradWaves * 64), 0, st, a);
     }
     if (hipGetLastError() != hipSuccess) return LORDBA_ERR_LAUNCH;
     hipLaunchKernelGGL(lordba_bwd_finish_kernel, dim3((a.d_in >> 5) + (a.d_out >> 5) + 1), dim3(256), 0, st, a);
