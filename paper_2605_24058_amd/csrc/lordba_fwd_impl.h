@@ -664,23 +664,41 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
         }
     };
 
-    if (my_b > 0) consume_y(0, 0, true, true);
     // 8-row tiles on 8 waves with more blocks than the waves hold in flight: every pass of the loop issues the same vector
     // memory instructions whatever the wave's number of blocks is (what is not wanted is skipped by its offset), so that
     // the wait for a slot's y_base leaves the later requests and the stores in flight; with requests under branches the
     // compiler has to wait for all of them.
     constexpr bool kSteadyLoop = BUFY && GM != 4;
-    if (kSteadyLoop && nblk > NW * D2) {
-        for (int n0 = 0; n0 < my_b; n0 += D2) {
+    if constexpr (kSteadyLoop) {
+        if (my_b > 0) consume_y(0, 0, true, true);
+        if (nblk > NW * D2) {
+            for (int n0 = 0; n0 < my_b; n0 += D2) {
 #pragma unroll
-            for (int slot = 0; slot < D2; ++slot) {
-                const int n = n0 + slot;
-                consume_y(slot, n, false, n != 0 && n < my_b);
-                issue_y(slot, n + D2);
+                for (int slot = 0; slot < D2; ++slot) {
+                    const int n = n0 + slot;
+                    consume_y(slot, n, false, n != 0 && n < my_b);
+                    issue_y(slot, n + D2);
+                }
+            }
+        } else {
+            if (my_b > D2) issue_y(0, D2);
+            for (int n0 = 0; n0 < my_b; n0 += D2) {
+#pragma unroll
+                for (int slot = 0; slot < D2; ++slot) {
+                    const int n = n0 + slot;
+                    if (n == 0) continue;
+                    if (n < my_b) consume_y(slot, n, false, true);
+                    if (n + D2 < my_b) issue_y(slot, n + D2);
+                }
             }
         }
     } else {
-        if (my_b > D2) issue_y(0, D2);
+        // (kept in exactly this shape: with the first block's request for its successor outside the branch, the
+        // three-envelope variants with four rank blocks spill)
+        if (my_b > 0) {
+            consume_y(0, 0, true, true);
+            if (D2 < my_b) issue_y(0, D2);
+        }
         for (int n0 = 0; n0 < my_b; n0 += D2) {
 #pragma unroll
             for (int slot = 0; slot < D2; ++slot) {
