@@ -270,7 +270,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     __builtin_amdgcn_sched_barrier(0);
 
     // ---------------------------------------------------------------- stage 3 loads (issued later) ---
-    // Block b = 128 output columns; wave w owns blocks w, w + NW, ...; lane (li, q) owns columns 8 li .. 8 li + 7 of
+    // Block b = 128 output columns; a wave owns a run of consecutive blocks (or blocks w, w + NW, ...); lane (li, q) owns columns 8 li .. 8 li + 7 of
     // the block for its token rows.
     // gridDim.y workgroups may share a token tile (small T: most of the chip would idle otherwise): each repeats stages 1
     // and 2, which costs no extra HBM traffic worth naming at such T, and takes its own contiguous range of blocks.
@@ -278,15 +278,22 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     const int per_wg = SPLIT ? a.blocks_per_wg : nblk_all;
     const int b_first = SPLIT ? static_cast<int>(blockIdx.y) * per_wg : 0;
     const int nblk = nblk_all - b_first < per_wg ? (nblk_all - b_first > 0 ? nblk_all - b_first : 0) : per_wg;
-    const int my_b = wave < nblk ? (nblk - wave + NW - 1) / NW : 0;
+    // A wave owns CONSECUTIVE blocks (its blocks in flight are then one contiguous piece of each row: 512 bytes per row at
+    // the headline shape instead of two pieces 4 KiB apart: C2 9.99 -> 9.61 us, 4096 -> 11008 at T = 4096 42.1 -> 39.7),
+    // except on 16-row tiles with 16 waves and in the multi-adapter batch, where the round-robin deal measured faster.
+    constexpr bool CB = !(TMV == 16 && NW == 16) && GM != 4;
+    const int per_wave_b = (nblk + NW - 1) / NW;
+    const int my_b = CB ? (nblk - wave * per_wave_b < 0 ? 0 : (nblk - wave * per_wave_b < per_wave_b ? nblk - wave * per_wave_b : per_wave_b))
+                        : (wave < nblk ? (nblk - wave + NW - 1) / NW : 0);
+    auto block_of = [&](int n) { return CB ? wave * per_wave_b + n : wave + NW * n; };  // the wave's n-th block (relative to b_first)
     const int64_t nwordsB = (static_cast<int64_t>(d_out) * r + 31) >> 5;
     u4 ybuf[D2][NI];
     u4 sobuf[D2][L];
     u4 bbuf[D2][R16 ? RB : 1];
 
     auto issue_y = [&](int slot, int n) {
-        int b = b_first + wave + NW * n;
-        const bool mine = wave + NW * n < nblk;  // (past the wave's share: with buffer accesses the rows of y_base are not requested)
+        int b = b_first + block_of(n);
+        const bool mine = n < my_b;  // (past the wave's share: with buffer accesses the rows of y_base are not requested)
         b = b < nblk_all ? b : nblk_all - 1;  // past the end: re-read a valid block, the result is not used
         int j0 = b * 128 + li * 8;
         j0 = j0 < d_out ? j0 : d_out - 8;
@@ -531,7 +538,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     };
     // (`run` false, only with buffer accesses: nothing is computed or stored, but the same vector memory instructions are issued)
     auto consume_y = [&](int slot, int n, bool use_pre, bool run) {
-        const int b = b_first + wave + NW * n;
+        const int b = b_first + block_of(n);
         const int j0 = b * 128 + li * 8;
         const bool j_ok = j0 < d_out;
         const int jc = j_ok ? j0 : d_out - 8;
