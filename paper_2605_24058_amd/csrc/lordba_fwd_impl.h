@@ -1146,9 +1146,16 @@ lordba_status forward_impl(const void* x, const uint32_t* packedA, const uint32_
             const bool two_per_cu = algo == LORDBA_ALGO_AUTO && (T + 15) / 16 > 256;
             // One 16-row tile per compute unit and at least three output blocks per wave of the 16: the call is mostly stage
             // 3, and 8-row tiles on 8 waves, two workgroups per compute unit that overlap each other's stages, stream it
-            // faster (4096 -> 11008: 41.8 against 42.7 us, 4096 -> 6144: 24.6 against 24.9, 5120 -> 13824: 51.2 against 51.7;
-            // at 4096 -> 5120 the 16-row tiles still win, 19.4 against 21.2).
-            if (algo == LORDBA_ALGO_AUTO && rb == 1 && !two_per_cu && d_out >= 6144) s = launch_mfma_rb<8, 8, 1>(a, st);
+            // faster (4096 -> 11008: 39.9 against 42.6 us; at 4096 -> 5120 the 16-row tiles still win, 19.4 against 21.2).
+            // Beyond one tile per compute unit the same holds while the x pipeline of the 8 waves is one-shot (d_in <= 4096):
+            // 4096 -> 11008 at T = 8192 77.3 against 85.9 us, at T = 16384 150.7 against 167.9; 4096 -> 14336 3 to 4 %.
+            const bool mostly_stage3 = d_out >= 6144 && (!two_per_cu || d_in <= 4096);
+            // Tiles are dealt to 256 compute units: 16-row tiles that leave the last round of a compute unit half empty
+            // (T = 6144: 384 tiles, two on half of the units and one on the others) lose more than 8-row tiles cost
+            // (768 tiles, three per unit): nine shapes at T = 6144, 8-row tiles 2.6 to 11 % faster on every one.
+            auto fill = [](int64_t tiles) { return static_cast<double>(tiles) / static_cast<double>((tiles + 255) / 256 * 256); };
+            const bool ragged_rounds = two_per_cu && fill((T + 7) / 8) >= 1.15 * fill((T + 15) / 16);
+            if (algo == LORDBA_ALGO_AUTO && rb == 1 && (mostly_stage3 || ragged_rounds)) s = launch_mfma_rb<8, 8, 1>(a, st);
             else s = rb == 1 && !two_per_cu ? launch_mfma_rb<16, 16, 1>(a, st) : launch_mfma_rb<16, 8, 1>(a, st);
         } else if (batched && (T + 7) / 8 > 32) {
             s = launch_mfma_rb<8, 8, 1>(a, st);  // two workgroups per CU: see the batch mode of the kernel
