@@ -183,9 +183,10 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     // grids that fill the chip gain 1 to 5 %.  (The multi-adapter batch keeps the round-robin deal: 128 registers.)
     constexpr bool CA = OS && GM != 4;
     const int words_per_row = d_in >> 5;  // d_in % 32 == 0 on this path
-    const int per_wave = (nchunks + NW - 1) / NW;  // (<= D1 where OS)
-    const int my_n = CA ? (nchunks - wave * per_wave < 0 ? 0 : (nchunks - wave * per_wave < per_wave ? nchunks - wave * per_wave : per_wave))
-                        : (wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0);
+    // (the first nchunks mod NW waves own one chunk more than the others: at most ceil(nchunks / NW), <= D1 where OS)
+    const int c_each = nchunks / NW, c_more = nchunks - c_each * NW;
+    const int c_first = wave * c_each + (wave < c_more ? wave : c_more);   // first chunk of the wave's run
+    const int my_n = CA ? c_each + (wave < c_more ? 1 : 0) : (wave < nchunks ? (nchunks - wave + NW - 1) / NW : 0);
     // (16-byte loads need whole chunks and rows that start on 16-byte boundaries)
     const bool wide_a = CA && (d_in & 127) == 0 && (reinterpret_cast<uintptr_t>(a.pA) & 15) == 0;
     u4 xbuf[D1][NI];
@@ -193,7 +194,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     uint32_t abits[D1][RB];
 
     auto issue_x = [&](int slot, int n) {
-        int c = CA ? wave * per_wave + n : wave + NW * n;
+        int c = CA ? c_first + n : wave + NW * n;
         c = c < nchunks ? c : nchunks - 1;  // past the end: re-read a valid chunk, the result is not used
         // 16 waves leave 128 registers per lane.  In the looped pipeline the compiler would keep every lane's row and rank
         // offsets in registers across the loop (the chunk index is scalar, so they are loop invariants) and spill; hiding
@@ -243,7 +244,7 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
         if (wide_a) {  // needed first, so requested first
 #pragma unroll
             for (int g = 0; g < AG; ++g) {
-                int c = wave * per_wave + g * 4 + q;
+                int c = c_first + g * 4 + q;
                 c = c < nchunks ? c : nchunks - 1;
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) {
@@ -280,12 +281,18 @@ __device__ __forceinline__ void fwd_tile(const FwdArgs& a, unsigned char* smem, 
     const int nblk = nblk_all - b_first < per_wg ? (nblk_all - b_first > 0 ? nblk_all - b_first : 0) : per_wg;
     // A wave owns CONSECUTIVE blocks (its blocks in flight are then one contiguous piece of each row: 512 bytes per row at
     // the headline shape instead of two pieces 4 KiB apart: C2 9.99 -> 9.61 us, 4096 -> 11008 at T = 4096 42.1 -> 39.7),
-    // except on 16-row tiles with 16 waves and in the multi-adapter batch, where the round-robin deal measured faster.
-    constexpr bool CB = !(TMV == 16 && NW == 16) && GM != 4;
-    const int per_wave_b = (nblk + NW - 1) / NW;
-    const int my_b = CB ? (nblk - wave * per_wave_b < 0 ? 0 : (nblk - wave * per_wave_b < per_wave_b ? nblk - wave * per_wave_b : per_wave_b))
-                        : (wave < nblk ? (nblk - wave + NW - 1) / NW : 0);
-    auto block_of = [&](int n) { return CB ? wave * per_wave_b + n : wave + NW * n; };  // the wave's n-th block (relative to b_first)
+    // The multi-adapter batch keeps the round-robin deal, which measured faster there.
+    constexpr bool CB = GM != 4;
+    // Runs of ceil(nblk / NW) blocks while that leaves the last wave at least half a run (108 blocks over 8 waves: 14 .. 14 10,
+    // measured 1.5 % faster than 14 14 14 14 13 13 13 13); otherwise the first nblk mod NW waves own one block more than
+    // the others (40 blocks over 16 waves: 3 .. 3 2 .. 2; runs of 3 would leave two waves without a block and cost 8 %).
+    const int b_run = (nblk + NW - 1) / NW;
+    const bool even_runs = 2 * (nblk - (NW - 1) * b_run) >= b_run;
+    const int b_each = nblk / NW, b_more = nblk - b_each * NW;
+    const int b_start = even_runs ? wave * b_run : wave * b_each + (wave < b_more ? wave : b_more);
+    const int b_mine = even_runs ? (nblk - wave * b_run < b_run ? nblk - wave * b_run : b_run) : b_each + (wave < b_more ? 1 : 0);
+    const int my_b = CB ? (b_mine > 0 ? b_mine : 0) : (wave < nblk ? (nblk - wave + NW - 1) / NW : 0);
+    auto block_of = [&](int n) { return CB ? b_start + n : wave + NW * n; };  // the wave's n-th block (relative to b_first)
     const int64_t nwordsB = (static_cast<int64_t>(d_out) * r + 31) >> 5;
     u4 ybuf[D2][NI];
     u4 sobuf[D2][L];
