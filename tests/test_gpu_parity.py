@@ -133,6 +133,12 @@ TALL = [
     inputs.Shape("tall_T4098_8192x136_r16", 4098, 8192, 136, 16),    # the same for the rows of x
     inputs.Shape("mid_T2049_256x384_r16", 2049, 256, 384, 16),       # one 8-row tile more than compute units
     inputs.Shape("mid_T3001_640x264_r24", 3001, 640, 264, 24),
+    # chunks and output blocks that do not divide by the wave count (20 chunks and 40 blocks over 16 or 8 waves; 65 chunks,
+    # a looped pipeline on 16 waves, and 22 blocks): waves with one chunk / block more than others, or with none
+    inputs.Shape("deal_T300_2560x5120_r16", 300, 2560, 5120, 16),
+    inputs.Shape("deal_T300_8320x2816_r32", 300, 8320, 2816, 32),
+    inputs.Shape("deal_T4100_2560x1152_r16", 4100, 2560, 1152, 16),  # 9 blocks: runs of 2 on 8 waves, one wave without
+    inputs.Shape("deal_T6144_640x1408_r16", 6144, 640, 1408, 16),    # 384 16-row tiles would half fill the last round: 8-row tiles
 ]
 
 
